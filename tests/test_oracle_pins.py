@@ -1,0 +1,398 @@
+"""Pins for the CPU oracle: every block is checked against something other than itself
+(published vectors, closed forms, brute force in scalar loops, library routines, invariants)."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import sapo_oracle as O
+from paper_2509_08721_amd import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def tiny_model(seed=7, gains=True, **kw):
+    shape = W.scaled(W.WORKLOADS["tiny"], ).shape
+    if kw:
+        from dataclasses import replace
+        shape = replace(shape, **kw)
+    w = W.make_weights(shape, seed)
+    if gains:
+        w = W.perturb_norm_gains(w, seed)
+    return shape, w, O.Model(shape, w)
+
+
+# ----------------------------------------------------------------------------- RNG
+def test_philox_known_answer_vectors():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")) if not l.startswith("#")]
+    assert len(rows) == 3
+    for r in rows:
+        w = [int(x, 16) for x in r]
+        out = O.philox4x32_10(np.array(w[:4], dtype=np.uint32), np.array(w[4:6], dtype=np.uint32))
+        assert [int(x) for x in out] == w[6:]
+
+
+def test_philox_vectorised_equals_scalar_calls():
+    rng = np.random.default_rng(0)
+    ctr = rng.integers(0, 2**32, size=(50, 4), dtype=np.uint64).astype(np.uint32)
+    key = rng.integers(0, 2**32, size=(2,), dtype=np.uint64).astype(np.uint32)
+    batch = O.philox4x32_10(ctr, key)
+    for i in range(50):
+        assert np.array_equal(batch[i], O.philox4x32_10(ctr[i], key))
+
+
+def test_sampling_stream_keying():
+    """Noise is a pure function of (seed, seq, step, v): word v%4 of block v//4, counter
+    (v//4, step, seq, 0), key = (seed low, seed high)."""
+    seed, seq, step, V = 0x123456789ABCDEF, 5, 9, 37
+    bits = O.sampling_uniform_bits(seed, seq, step, V)
+    for v in (0, 1, 3, 4, 18, 36):
+        blk = O.philox4x32_10(np.array([v // 4, step, seq, 0], dtype=np.uint32),
+                              np.array([0x89ABCDEF, 0x01234567], dtype=np.uint32))
+        assert bits[v] == blk[v % 4]
+    # different seq / step / seed give different streams; longer vocab extends the same stream
+    assert not np.array_equal(bits, O.sampling_uniform_bits(seed, seq + 1, step, V))
+    assert not np.array_equal(bits, O.sampling_uniform_bits(seed, seq, step + 1, V))
+    assert not np.array_equal(bits, O.sampling_uniform_bits(seed + 1, seq, step, V))
+    assert np.array_equal(bits, O.sampling_uniform_bits(seed, seq, step, V + 11)[:V])
+
+
+def test_uniform_open_interval_and_fp32_exact():
+    x = np.array([0, 1, 511, 512, 2**32 - 1, 2**31], dtype=np.uint32)
+    u = O.uniform_from_bits(x)
+    assert u.min() == 2.0 ** -24 and u.max() == 1.0 - 2.0 ** -24
+    assert np.array_equal(u.astype(np.float32).astype(np.float64), u)
+
+
+def test_gumbel_moments():
+    g = np.concatenate([O.gumbel_noise(42, s, 0, 50000) for s in range(8)]).astype(np.float64)
+    n = g.size
+    assert abs(g.mean() - 0.5772156649) < 4 * math.sqrt((math.pi ** 2 / 6) / n)
+    assert abs(g.var() - math.pi ** 2 / 6) < 0.03
+    assert g.min() > -2.82 and g.max() < 16.64
+
+
+def test_gumbel_max_histogram_matches_softmax():
+    """Chi-square of sampled-token counts against softmax(z/T) on a small vocab."""
+    rng = np.random.default_rng(3)
+    V, T = 12, 0.7
+    z = rng.normal(0, 1.5, V)
+    p = np.exp(z / T - np.max(z / T))
+    p /= p.sum()
+    n = 20000
+    counts = np.zeros(V)
+    for i in range(n):
+        counts[O.sample_token(z, T, seed=99, seq=i % 64, step=i // 64)] += 1
+    chi2 = np.sum((counts - n * p) ** 2 / (n * p))
+    assert chi2 < 36.0          # 11 dof: P(chi2 > 36) ~ 1.6e-4
+    # greedy limit
+    assert O.sample_token(z, 0.0, 99, 0, 0) == int(np.argmax(z))
+
+
+def test_argmax_ties_go_to_lowest_id():
+    z = np.zeros(8)
+    assert O.sample_token(z, 0.0, 1, 0, 0) == 0
+
+
+# ----------------------------------------------------------------------------- RoPE
+def test_rope_closed_forms():
+    hd, theta = 16, 1e4
+    # position 0 is the identity
+    x = np.random.default_rng(0).normal(size=(3, 2, hd))
+    assert np.allclose(O.rope_rotate(x, np.zeros(3, dtype=np.int64), theta), x, atol=0)
+    # one-hot in slot i rotates into (cos m f_i, sin m f_i) in slots (i, i + hd/2); f_0 = 1
+    for i in (0, 3, 7):
+        e = np.zeros((1, 1, hd))
+        e[0, 0, i] = 1.0
+        m = 5
+        f = theta ** (-2.0 * i / hd)
+        r = O.rope_rotate(e, np.array([m]), theta)[0, 0]
+        expect = np.zeros(hd)
+        expect[i], expect[i + hd // 2] = math.cos(m * f), math.sin(m * f)
+        assert np.allclose(r, expect, atol=1e-15)
+    e = np.zeros((1, 1, hd)); e[0, 0, 0] = 1.0
+    r = O.rope_rotate(e, np.array([2]), theta)[0, 0]
+    assert abs(r[0] - math.cos(2.0)) < 1e-15 and abs(r[8] - math.sin(2.0)) < 1e-15
+    # one-hot in the upper half slot rotates the other way round: (-sin, cos)
+    e = np.zeros((1, 1, hd)); e[0, 0, 8 + 2] = 1.0
+    f = theta ** (-4.0 / hd)
+    r = O.rope_rotate(e, np.array([3]), theta)[0, 0]
+    assert abs(r[2] + math.sin(3 * f)) < 1e-15 and abs(r[10] - math.cos(3 * f)) < 1e-15
+    # norms preserved, inner product depends on m - n only
+    q = np.random.default_rng(1).normal(size=(1, 1, hd))
+    k = np.random.default_rng(2).normal(size=(1, 1, hd))
+    def ip(m, n):
+        return float(np.sum(O.rope_rotate(q, np.array([m]), theta) * O.rope_rotate(k, np.array([n]), theta)))
+    assert abs(np.linalg.norm(O.rope_rotate(q, np.array([77]), theta)) - np.linalg.norm(q)) < 1e-12
+    assert abs(ip(9, 4) - ip(1009, 1004)) < 1e-9
+    assert abs(ip(9, 4) - ip(4, 9)) > 1e-3       # sign of the relative offset matters
+
+
+# ----------------------------------------------------------------------------- attention
+def brute_attention(q, k, v, q_pos0):
+    """Scalar-loop softmax attention with an explicit probability row."""
+    nq, hq, hd = q.shape
+    nk, hkv, _ = k.shape
+    rep = hq // hkv
+    out = np.zeros((nq, hq, hd))
+    for i in range(nq):
+        for h in range(hq):
+            kvh = h // rep
+            sc = []
+            for n in range(nk):
+                if n <= q_pos0 + i:
+                    sc.append(sum(q[i, h, e] * k[n, kvh, e] for e in range(hd)) / math.sqrt(hd))
+            mx = max(sc)
+            w = [math.exp(x - mx) for x in sc]
+            tot = sum(w)
+            for n, wn in enumerate(w):
+                for e in range(hd):
+                    out[i, h, e] += wn / tot * v[n, kvh, e]
+    return out
+
+
+def test_attention_vs_brute_force_gqa():
+    rng = np.random.default_rng(5)
+    q = rng.normal(size=(6, 4, 8))
+    k = rng.normal(size=(9, 2, 8))
+    v = rng.normal(size=(9, 2, 8))
+    v[:, 1, :] += 100.0                    # KV heads differ wildly: a wrong head mapping shows
+    got = O.attention(q, k, v, q_pos0=3)
+    assert np.allclose(got, brute_attention(q, k, v, 3), atol=1e-12)
+    assert np.all(got[:, :2, :] < 50) and np.all(got[:, 2:, :] > 50)   # heads 0,1 -> KV0; 2,3 -> KV1
+
+
+def test_attention_vs_torch_sdpa():
+    rng = np.random.default_rng(6)
+    T, hq, hkv, hd = 10, 6, 2, 16
+    q, k, v = rng.normal(size=(T, hq, hd)), rng.normal(size=(T, hkv, hd)), rng.normal(size=(T, hkv, hd))
+    got = O.attention(q, k, v, 0)
+    tq, tk, tv = (torch.from_numpy(a).permute(1, 0, 2)[None] for a in (q, k, v))
+    tk = tk.repeat_interleave(hq // hkv, dim=1)
+    tv = tv.repeat_interleave(hq // hkv, dim=1)
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True)[0].permute(1, 0, 2).numpy()
+    assert np.allclose(got, ref, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------- small blocks vs library
+def test_rmsnorm_silu_logsoftmax_vs_torch():
+    rng = np.random.default_rng(8)
+    h, g = rng.normal(size=(5, 64)), rng.normal(size=64)
+    ref = torch.nn.functional.rms_norm(torch.from_numpy(h), (64,), torch.from_numpy(g), eps=1e-6).numpy()
+    assert np.allclose(O.rmsnorm(h, g, 1e-6), ref, atol=1e-13)
+    x = rng.normal(size=100) * 5
+    assert np.allclose(O.silu(x), torch.nn.functional.silu(torch.from_numpy(x)).numpy(), atol=1e-14)
+    z = rng.normal(size=(3, 50)) * 30
+    lp = O.log_softmax(z)
+    assert np.allclose(lp, torch.log_softmax(torch.from_numpy(z), -1).numpy(), atol=1e-12)
+    assert np.allclose(np.exp(lp).sum(-1), 1.0, atol=1e-12)
+    zz = np.array([[1000.0, -1000.0, 0.0]])          # extreme logits stay finite
+    assert np.isfinite(O.log_softmax(zz)).all()
+
+
+def test_round_bf16():
+    x = np.array([1.0, 1.00390625, 1.005859375, 1.001953125, -3.14159, 1e-30, 65504.0])
+    r = O.round_bf16(x)
+    ref = torch.from_numpy(x).float().bfloat16().double().numpy()
+    assert np.array_equal(r, ref)
+    # ties to even: 1 + 2^-8 is halfway between 1 and 1 + 2^-7 -> 1 ; 1 + 3*2^-8 -> 1 + 2^-6
+    assert O.round_bf16(np.array([1.0 + 2.0 ** -8]))[0] == 1.0
+    assert O.round_bf16(np.array([1.0 + 3 * 2.0 ** -8]))[0] == 1.0 + 2.0 ** -6
+
+
+# ----------------------------------------------------------------------------- whole forward
+def scalar_forward(shape, wf, tokens):
+    """Independent scalar-loop forward of the decoder (brute force on tiny inputs)."""
+    d, hq, hkv, hd, F = shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ff
+    T = len(tokens)
+
+    def norm(vec, g):
+        ms = sum(x * x for x in vec) / len(vec)
+        return [x / math.sqrt(ms + shape.rms_eps) * float(gi) for x, gi in zip(vec, g)]
+
+    def matvec(Wm, x):
+        return [sum(float(Wm[o][i]) * x[i] for i in range(len(x))) for o in range(len(Wm))]
+
+    def rot(vec, pos):
+        out = list(vec)
+        for i in range(hd // 2):
+            ang = pos * shape.rope_theta ** (-2.0 * i / hd)
+            a, b = vec[i], vec[i + hd // 2]
+            out[i] = a * math.cos(ang) - b * math.sin(ang)
+            out[i + hd // 2] = b * math.cos(ang) + a * math.sin(ang)
+        return out
+
+    hs = [[float(x) for x in wf["embed"][t]] for t in tokens]
+    for lw in wf["layers"]:
+        qs, ks, vs = [], [], []
+        for t in range(T):
+            a = norm(hs[t], lw["attn_norm"])
+            q, k, v = matvec(lw["wq"], a), matvec(lw["wk"], a), matvec(lw["wv"], a)
+            qs.append([rot(q[h * hd:(h + 1) * hd], t) for h in range(hq)])
+            ks.append([rot(k[h * hd:(h + 1) * hd], t) for h in range(hkv)])
+            vs.append([v[h * hd:(h + 1) * hd] for h in range(hkv)])
+        for t in range(T):
+            o = []
+            for h in range(hq):
+                kh = h // (hq // hkv)
+                sc = [sum(qs[t][h][e] * ks[n][kh][e] for e in range(hd)) / math.sqrt(hd) for n in range(t + 1)]
+                mx = max(sc)
+                ws = [math.exp(x - mx) for x in sc]
+                tot = sum(ws)
+                o += [sum(ws[n] / tot * vs[n][kh][e] for n in range(t + 1)) for e in range(hd)]
+            proj = matvec(lw["wo"], o)
+            hs[t] = [x + y for x, y in zip(hs[t], proj)]
+        for t in range(T):
+            b = norm(hs[t], lw["ffn_norm"])
+            gt, up = matvec(lw["w_gate"], b), matvec(lw["w_up"], b)
+            act = [g / (1.0 + math.exp(-g)) * u for g, u in zip(gt, up)]
+            dn = matvec(lw["w_down"], act)
+            hs[t] = [x + y for x, y in zip(hs[t], dn)]
+    lm = wf["embed"] if wf["lm_head"] is None else wf["lm_head"]
+    return np.array([matvec(lm, norm(hs[t], wf["final_norm"])) for t in range(T)])
+
+
+def test_forward_vs_scalar_loops():
+    from dataclasses import replace
+    shape = replace(W.TINY, n_layers=2, d_model=16, n_q_heads=4, n_kv_heads=2, head_dim=4, d_ff=12, vocab=20)
+    w = W.perturb_norm_gains(W.make_weights(shape, 11, std=0.3), 11)
+    m = O.Model(shape, w)
+    tokens = np.array([3, 19, 0, 7, 7, 12])
+    got = O.forward_logits(m, tokens)
+    ref = scalar_forward(shape, W.weights_as_f32(shape, w), tokens)
+    assert np.allclose(got, ref, atol=1e-12)
+
+
+def test_zero_layer_model_is_norm_times_embedding():
+    from dataclasses import replace
+    shape = replace(W.TINY, n_layers=0)
+    w = W.perturb_norm_gains(W.make_weights(shape, 13), 13)
+    m = O.Model(shape, w)
+    tokens = np.array([5, 400, 5])
+    z = O.forward_logits(m, tokens)
+    E = w["embed"].astype(np.float64)
+    for i, t in enumerate(tokens):
+        e = E[t]
+        x = e / math.sqrt(np.mean(e * e) + 1e-6) * w["final_norm"]
+        assert np.allclose(z[i], E @ x, atol=1e-13)
+    assert np.allclose(z[0], z[2])      # no layers: no position dependence
+
+
+def test_causality_and_batch_invariance():
+    shape, w, m = tiny_model()
+    rng = np.random.default_rng(17)
+    toks = rng.integers(0, shape.vocab, size=12)
+    z = O.forward_logits(m, toks)
+    toks2 = toks.copy(); toks2[8:] = (toks2[8:] + 1) % shape.vocab
+    z2 = O.forward_logits(m, toks2)
+    assert np.array_equal(z[:8], z2[:8]) and not np.allclose(z[8:], z2[8:])
+    # a sequence scored alone equals its row in a batch
+    batch = rng.integers(0, shape.vocab, size=(3, 12)).astype(np.int32)
+    mask = W.make_completion_mask(3, 12, 6)
+    full = O.score_logprobs(m, batch, mask)
+    alone = O.score_logprobs(m, batch[1:2], mask[1:2])
+    assert np.array_equal(full[1], alone[0])
+
+
+def test_kv_cache_decode_equals_full_recompute():
+    wl = W.WORKLOADS["tiny"]
+    shape, w, m = tiny_model(seed=wl.weight_seed)
+    prompts = W.make_prompts(wl)
+    toks, lps, zs = O.rollout_generate(m, prompts, wl.group, wl.n_new, 1.0, wl.rollout_seed, return_logits=True)
+    assert toks.shape == (8, 16) and toks.min() >= 0 and toks.max() < shape.vocab
+    for s in range(wl.n_seqs):
+        seq = np.concatenate([prompts[s // wl.group], toks[s]])
+        zfull = O.forward_logits(m, seq, at=range(wl.prompt_len - 1, wl.prompt_len + wl.n_new - 1))
+        assert np.allclose(zfull, zs[s], atol=1e-10)
+        for t in range(wl.n_new):          # tokens re-derived from the recomputed logits are identical
+            assert O.sample_token(zfull[t], 1.0, wl.rollout_seed, s, t) == toks[s, t]
+    # rollout log-probs are what the scoring pass gives on the same sequences
+    seqs = np.concatenate([np.repeat(prompts, wl.group, axis=0), toks], axis=1)
+    mask = W.make_completion_mask(wl.n_seqs, wl.prompt_len + wl.n_new, wl.n_new)
+    sc = O.score_logprobs(m, seqs, mask)
+    assert np.allclose(sc[:, wl.prompt_len:], lps, atol=1e-6)
+    assert np.all(sc[:, :wl.prompt_len] == 0.0)
+    # siblings share the step-0 logits but draw different noise
+    assert np.allclose(zs[0, 0], zs[1, 0], atol=0) and len({tuple(t) for t in toks}) > 1
+
+
+def test_score_logprobs_properties():
+    shape, w, m = tiny_model()
+    rng = np.random.default_rng(21)
+    toks = rng.integers(0, shape.vocab, size=(2, 10)).astype(np.int32)
+    mask = np.ones((2, 10), dtype=np.uint8)
+    lp = O.score_logprobs(m, toks, mask)
+    assert np.all(lp[:, 0] == 0.0)                  # t = 0 is never scorable
+    assert np.all(lp[:, 1:] < 0.0) and np.isfinite(lp).all()
+    # each entry equals the log-softmax of the definition; probabilities over the vocab sum to 1
+    for s in range(2):
+        z = O.forward_logits(m, toks[s])
+        full = O.log_softmax(z)
+        assert np.allclose(np.exp(full).sum(-1), 1.0, atol=1e-12)
+        for t in range(1, 10):
+            assert abs(lp[s, t] - full[t - 1, toks[s, t]]) < 1e-6
+    # an unlikely continuation (argmin of the logits) is scored finite and very negative
+    z = O.forward_logits(m, toks[0, :5])
+    worst = toks[0].copy(); worst[5] = int(np.argmin(z[4]))
+    lpw = O.score_logprobs(m, worst[None], mask[:1])
+    assert np.isfinite(lpw).all() and lpw[0, 5] <= lp[0, 5]
+    # mask selects entries, does not change them
+    mask2 = mask.copy(); mask2[:, ::2] = 0
+    lp2 = O.score_logprobs(m, toks, mask2)
+    assert np.array_equal(lp2[:, 1::2], lp[:, 1::2]) and np.all(lp2[:, ::2] == 0.0)
+
+
+def test_temperature_changes_sampling_not_logprob_definition():
+    shape, w, m = tiny_model()
+    prompts = np.random.default_rng(2).integers(0, shape.vocab, size=(1, 6)).astype(np.int32)
+    t0, l0 = O.rollout_generate(m, prompts, 2, 5, 0.0, seed=1)
+    assert np.array_equal(t0[0], t0[1])             # greedy: siblings identical
+    z = O.forward_logits(m, prompts[0])[-1]
+    assert t0[0, 0] == int(np.argmax(z))
+    assert abs(l0[0, 0] - O.log_softmax(z)[t0[0, 0]]) < 1e-6
+    t7, l7 = O.rollout_generate(m, prompts, 2, 5, 0.7, seed=1)
+    assert abs(l7[0, 0] - O.log_softmax(z)[t7[0, 0]]) < 1e-6   # log-prob is at T = 1
+
+
+def test_mode_b_rounding_is_small_perturbation():
+    shape, w, _ = tiny_model()
+    ma, mb = O.Model(shape, w), O.Model(shape, w, act_round="bf16")
+    toks = np.random.default_rng(4).integers(0, shape.vocab, size=20)
+    za, zb = O.forward_logits(ma, toks), O.forward_logits(mb, toks)
+    err = np.abs(za - zb).max()
+    assert 0 < err < 5e-2
+
+
+# ----------------------------------------------------------------------------- advantages
+def test_group_advantages_closed_forms():
+    G = 8
+    r = np.array([1, 1, 0, 0, 0, 0, 0, 0], dtype=np.float32)        # k = 2 of 8
+    a = O.group_advantages(r, G)
+    assert np.allclose(a[:2], 1.7320508, atol=1e-5) and np.allclose(a[2:], -0.5773503, atol=1e-5)
+    for k in range(1, G):
+        r = np.array([1.0] * k + [0.0] * (G - k), dtype=np.float32)
+        a = O.group_advantages(np.random.default_rng(k).permutation(r), G).astype(np.float64)
+        p = k / G
+        sd = math.sqrt(p * (1 - p))
+        assert abs(a.sum()) < 1e-5
+        assert abs(np.sum(a * a) - G * (sd / (sd + 1e-6)) ** 2) < 1e-4
+        assert np.allclose(sorted(set(np.round(a, 5))), sorted({round((0 - p) / (sd + 1e-6), 5), round((1 - p) / (sd + 1e-6), 5)}))
+    # equal rewards -> exactly zero (also for values whose mean is not exact in binary)
+    for val in (0.0, 1.0, 0.3):
+        a = O.group_advantages(np.full(8, val, dtype=np.float32), 8)
+        assert np.all(a == 0.0)
+    assert np.all(O.group_advantages(np.array([0.7, 0.1], dtype=np.float32), 1) == 0.0)   # G = 1
+    # groups are independent runs of G consecutive sequences
+    r = np.array([1, 0, 0, 0, 1, 1, 1, 0], dtype=np.float32)
+    a = O.group_advantages(r, 4)
+    assert np.allclose(a[:4], O.group_advantages(r[:4], 4)) and np.allclose(a[4:], O.group_advantages(r[4:], 4))
+    # vs library: (r - mean) / (std + eps), population std
+    r = np.random.default_rng(0).random(16).astype(np.float32)
+    t = torch.from_numpy(r).double().reshape(2, 8)
+    ref = ((t - t.mean(1, keepdim=True)) / (t.std(1, unbiased=False, keepdim=True) + 1e-6)).reshape(-1).numpy()
+    assert np.allclose(O.group_advantages(r, 8), ref, atol=1e-6)
+    # partial credit rewards are accepted (floats, not booleans)
+    a = O.group_advantages(np.array([0.5, 1.0, 0.0, 0.5], dtype=np.float32), 4)
+    assert abs(a[0]) < 1e-7 and a[1] > 0 > a[2]
