@@ -1,0 +1,150 @@
+/*
+ * sapo.h - C ABI of the MI355X (gfx950) implementation of the per-node hot path of
+ * Swarm sAmpling Policy Optimization (SAPO).
+ *
+ * One node-round of Algorithm 1 spends its accelerator time in two places:
+ *   - "Generate rollouts": for each question q of the batch, the policy pi^n produces a
+ *     rollout R^n(q) = {a_1 .. a_L} of L sampled answers (Sec. 3.1, Algorithm 1)
+ *                                                        -> sapo_rollout_generate
+ *   - re-encoding every rollout of the training set T^n (own and swarm-shared) and
+ *     computing its token-level values under the node's own policy, however unlikely the
+ *     rollout is under it (Sec. 3.2), plus the group-relative advantages GRPO consumes
+ *     (Sec. 4.2; zero-advantage groups, Sec. 3.2 and Sec. 5)
+ *                                                        -> sapo_score_logprobs
+ *
+ * The policy is a decoder-only LM with RMSNorm, rotary positions (rotate-half pairing),
+ * grouped-query attention, a SwiGLU FFN and an (optionally tied) LM head.
+ *
+ * Conventions
+ *   - Every pointer marked "dev" is device (HBM) memory of the current HIP device, owned by
+ *     the caller; the library never frees or reallocates caller memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work: they return before the GPU has finished.  Outputs are valid after the
+ *     stream has been synchronised.
+ *   - The only allocations the library makes are the packed weight copy owned by a
+ *     sapo_weights handle; rollout and scoring calls run entirely inside the caller's
+ *     workspace.
+ *   - Every function returning int returns SAPO_OK or a negative error code and writes
+ *     nothing to its outputs when it rejects its arguments.  sapo_last_error() gives a
+ *     human-readable message for the calling thread's last failure.
+ *   - Token ids in inputs must lie in [0, vocab); this is not checked on the device.
+ *   - Sequences of a rollout are ordered s = p * G + g (prompt-major); group of s is s / G.
+ */
+#ifndef SAPO_H
+#define SAPO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  SAPO_OK = 0,
+  SAPO_EINVAL = -1,     /* null pointer, non-positive size, negative temperature, S % G != 0, ... */
+  SAPO_ESHAPE = -2,     /* model config the kernels cannot run (Hq % Hkv != 0, odd head_dim, ...) */
+  SAPO_EWORKSPACE = -3, /* workspace smaller than the matching *_workspace_bytes() */
+  SAPO_EHIP = -4        /* HIP runtime error (allocation, launch); see sapo_last_error() */
+};
+
+enum { SAPO_DTYPE_F32 = 0, SAPO_DTYPE_BF16 = 1 };
+
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab;
+  float rms_eps, rope_theta;
+  int32_t tied_embeddings; /* 1: the LM head is the embedding matrix */
+  int32_t dtype;           /* SAPO_DTYPE_*: storage type of weights, activations and KV cache */
+  int32_t kv_page_tokens;  /* tokens per KV-cache page; must be 16 */
+  int32_t max_seq;         /* longest sequence (prompt + generated) any call will use */
+} sapo_model_config;
+
+typedef struct sapo_weights sapo_weights; /* opaque, library-owned */
+
+/*
+ * Build the library's packed copy of the model weights.
+ * tensors: host array of dev pointers in this order, matrices row-major
+ *   [out_features, in_features] (y = x W^T), element type per cfg->dtype (fp32 or bf16),
+ *   RMSNorm gains always fp32:
+ *     embed[vocab, d];
+ *     per layer: attn_norm[d], wq[Hq*hd, d], wk[Hkv*hd, d], wv[Hkv*hd, d], wo[d, Hq*hd],
+ *                ffn_norm[d], w_gate[F, d], w_up[F, d], w_down[d, F];
+ *     final_norm[d];
+ *     lm_head[vocab, d]  (ignored, may be NULL, when tied_embeddings = 1).
+ *   n_tensors must be 1 + 9 * n_layers + 2.
+ * The copy is complete once `stream` has been synchronised; after that the caller may free
+ * the originals.  Allocates device memory (about the size of the model, twice the embedding).
+ */
+int sapo_weights_create(const sapo_model_config* cfg, const void* const* tensors, int n_tensors,
+                        void* stream, sapo_weights** out);
+void sapo_weights_destroy(sapo_weights* w);
+
+/* Workspace sizes in bytes (0 on invalid arguments). */
+size_t sapo_rollout_workspace_bytes(const sapo_weights* w, int P, int Lp, int G, int max_new);
+size_t sapo_score_workspace_bytes(const sapo_weights* w, int S, int T);
+size_t sapo_debug_logits_workspace_bytes(const sapo_weights* w, int S, int T, int n);
+
+/*
+ * Rollout generation (Sec. 3.1; Algorithm 1 "Generate rollouts").
+ * For each of the P prompts, G completions of exactly max_new tokens are sampled
+ * autoregressively from the policy at the given temperature.  Token t of sequence s is
+ *   argmax_v ( z_v / temperature + g_v ),  g_v = -ln(-ln u_v)
+ * (an exact sample of softmax(z / temperature)), with u_v from Philox4x32-10 keyed on
+ * (seed, s, t, v); temperature == 0 is greedy argmax of z; ties go to the lowest id.
+ *   prompts       dev int32 [P, Lp]
+ *   out_tokens    dev int32 [P*G, max_new]   generated tokens only
+ *   out_logprobs  dev fp32  [P*G, max_new]   log softmax(z)[token] at temperature 1
+ *   workspace     dev, >= sapo_rollout_workspace_bytes(w, P, Lp, G, max_new), 256-byte aligned
+ * Requires Lp >= 1, Lp + max_new <= cfg.max_seq.
+ */
+int sapo_rollout_generate(const sapo_weights* w, const int32_t* prompts, int P, int Lp, int G,
+                          int max_new, float temperature, uint64_t seed, int32_t* out_tokens,
+                          float* out_logprobs, void* workspace, size_t workspace_bytes,
+                          void* stream);
+
+/*
+ * Scoring pass (Sec. 3.2: token-level values of any rollout under the node's own policy;
+ * Sec. 4.2: GRPO's group-relative advantage).
+ *   tokens           dev int32 [S, T]   prompt + completion of every training-set sequence
+ *   completion_mask  dev uint8 [S, T]   non-zero where a log-prob is wanted
+ *   rewards          dev fp32  [S]
+ *   out_logprobs     dev fp32  [S, T]   log softmax(z_{t-1})[tokens[s, t]] where the mask is
+ *                                       set and t >= 1; 0.0 elsewhere
+ *   out_advantages   dev fp32  [S]      per group of G consecutive sequences:
+ *                                       (r - mean) / (population std + 1e-6); exactly 0 for a
+ *                                       group whose rewards are all equal
+ * Requires S % G == 0, T <= cfg.max_seq.
+ */
+int sapo_score_logprobs(const sapo_weights* w, const int32_t* tokens,
+                        const uint8_t* completion_mask, const float* rewards, int S, int T, int G,
+                        float* out_logprobs, float* out_advantages, void* workspace,
+                        size_t workspace_bytes, void* stream);
+
+/*
+ * Test hook: teacher-forced logits z (Sec. 3.2's re-encoding, before the log-softmax) at n
+ * chosen (sequence, position) pairs: out_logits[i, :] are the logits after consuming
+ * tokens[s_i, 0 .. t_i].
+ *   tokens dev int32 [S, T]; positions dev int32 [n, 2] = (s, t); out_logits dev fp32 [n, vocab]
+ */
+int sapo_debug_logits(const sapo_weights* w, const int32_t* tokens, int S, int T,
+                      const int32_t* positions, int n, float* out_logits, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
+/*
+ * Test hook: the sampler's noise.  out[i] = g for (seed, seq, step, v = v0 + i), i < n.
+ * out dev fp32 [n].
+ */
+int sapo_debug_gumbel(uint64_t seed, uint32_t seq, uint32_t step, uint32_t v0, int n, float* out,
+                      void* stream);
+
+/* Message for the calling thread's last failed call ("" if none). */
+const char* sapo_last_error(void);
+
+/* 1 if this weights handle runs on the MFMA (bf16, tile-aligned) kernels, 0 if on the
+ * shape-generic kernels. */
+int sapo_weights_uses_mfma(const sapo_weights* w);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAPO_H */

@@ -1,0 +1,505 @@
+// C ABI of libsapo and the host-side orchestration of rollout generation and scoring.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "common.h"
+
+using namespace sapo;
+
+// ---------------------------------------------------------------------------------------
+// error reporting
+// ---------------------------------------------------------------------------------------
+static thread_local std::string g_err;
+
+static int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof(buf), fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+#define HIP_CK(expr)                                                                           \
+  do {                                                                                         \
+    hipError_t e__ = (expr);                                                                   \
+    if (e__ != hipSuccess)                                                                     \
+      return fail(SAPO_EHIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__), __FILE__, __LINE__); \
+  } while (0)
+
+extern "C" const char* sapo_last_error(void) { return g_err.c_str(); }
+
+// ---------------------------------------------------------------------------------------
+// weights
+// ---------------------------------------------------------------------------------------
+struct LayerWeights {
+  float* attn_norm;
+  float* ffn_norm;
+  void* wqkv;   // [q + 2 kv, d]
+  void* wo;     // [d, q]
+  void* wgu;    // [2 F, d]: gate rows then up rows
+  void* wdown;  // [d, F]
+};
+
+struct sapo_weights {
+  sapo_model_config cfg;
+  int elt;                       // bytes per weight element
+  bool mfma;
+  void* embed;                   // row-major [V, d]
+  void* lm_head;                 // row-major [V, d] (== embed when tied)
+  float* final_norm;
+  float2* rope;                  // [max_seq][hd / 2] (cos, sin)
+  std::vector<LayerWeights> layers;
+  std::vector<void*> allocs;
+};
+
+static int validate_config(const sapo_model_config* c) {
+  if (!c) return fail(SAPO_EINVAL, "config is NULL");
+  if (c->n_layers < 0 || c->d_model <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 ||
+      c->d_ff <= 0 || c->vocab <= 0 || c->max_seq <= 0)
+    return fail(SAPO_EINVAL, "non-positive model dimension");
+  if (c->dtype != SAPO_DTYPE_F32 && c->dtype != SAPO_DTYPE_BF16) return fail(SAPO_EINVAL, "unknown dtype %d", c->dtype);
+  if (c->n_q_heads % c->n_kv_heads != 0) return fail(SAPO_ESHAPE, "n_q_heads %% n_kv_heads != 0");
+  if (c->head_dim % 2 != 0) return fail(SAPO_ESHAPE, "head_dim must be even");
+  if (c->kv_page_tokens != kPageTokens) return fail(SAPO_ESHAPE, "kv_page_tokens must be %d", kPageTokens);
+  if (c->max_seq > 3584) return fail(SAPO_ESHAPE, "max_seq > 3584 not supported");
+  if (!(c->rms_eps > 0.f) || !(c->rope_theta > 0.f)) return fail(SAPO_EINVAL, "rms_eps and rope_theta must be > 0");
+  return SAPO_OK;
+}
+
+extern "C" void sapo_weights_destroy(sapo_weights* w) {
+  if (!w) return;
+  for (void* p : w->allocs) (void)hipFree(p);
+  delete w;
+}
+
+extern "C" int sapo_weights_uses_mfma(const sapo_weights* w) { return (w && w->mfma) ? 1 : 0; }
+
+static int dev_alloc(sapo_weights* w, size_t bytes, void** out) {
+  void* p = nullptr;
+  hipError_t e = hipMalloc(&p, bytes ? bytes : 256);
+  if (e != hipSuccess) return fail(SAPO_EHIP, "hipMalloc(%zu) failed: %s", bytes, hipGetErrorString(e));
+  w->allocs.push_back(p);
+  *out = p;
+  return SAPO_OK;
+}
+
+static int create_impl(sapo_weights* w, const void* const* t, hipStream_t st) {
+  const sapo_model_config& c = w->cfg;
+  const size_t e = (size_t)w->elt;
+  const size_t d = c.d_model, q = (size_t)c.n_q_heads * c.head_dim, kv = (size_t)c.n_kv_heads * c.head_dim;
+  const size_t F = c.d_ff, V = c.vocab;
+  int rc;
+  auto copy = [&](void* dst, const void* src, size_t bytes) -> hipError_t {
+    return hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, st);
+  };
+  if ((rc = dev_alloc(w, V * d * e, &w->embed))) return rc;
+  HIP_CK(copy(w->embed, t[0], V * d * e));
+  w->layers.resize(c.n_layers);
+  for (int l = 0; l < c.n_layers; ++l) {
+    const void* const* lt = t + 1 + 9 * l;
+    LayerWeights& lw = w->layers[l];
+    if ((rc = dev_alloc(w, d * 4, (void**)&lw.attn_norm))) return rc;
+    if ((rc = dev_alloc(w, d * 4, (void**)&lw.ffn_norm))) return rc;
+    if ((rc = dev_alloc(w, (q + 2 * kv) * d * e, &lw.wqkv))) return rc;
+    if ((rc = dev_alloc(w, d * q * e, &lw.wo))) return rc;
+    if ((rc = dev_alloc(w, 2 * F * d * e, &lw.wgu))) return rc;
+    if ((rc = dev_alloc(w, d * F * e, &lw.wdown))) return rc;
+    HIP_CK(copy(lw.attn_norm, lt[0], d * 4));
+    HIP_CK(copy(lw.wqkv, lt[1], q * d * e));
+    HIP_CK(copy((char*)lw.wqkv + q * d * e, lt[2], kv * d * e));
+    HIP_CK(copy((char*)lw.wqkv + (q + kv) * d * e, lt[3], kv * d * e));
+    HIP_CK(copy(lw.wo, lt[4], d * q * e));
+    HIP_CK(copy(lw.ffn_norm, lt[5], d * 4));
+    HIP_CK(copy(lw.wgu, lt[6], F * d * e));
+    HIP_CK(copy((char*)lw.wgu + F * d * e, lt[7], F * d * e));
+    HIP_CK(copy(lw.wdown, lt[8], d * F * e));
+  }
+  const void* const* tail = t + 1 + 9 * c.n_layers;
+  if ((rc = dev_alloc(w, d * 4, (void**)&w->final_norm))) return rc;
+  HIP_CK(copy(w->final_norm, tail[0], d * 4));
+  if (c.tied_embeddings) {
+    w->lm_head = w->embed;
+  } else {
+    if ((rc = dev_alloc(w, V * d * e, &w->lm_head))) return rc;
+    HIP_CK(copy(w->lm_head, tail[1], V * d * e));
+  }
+  // rotary table in double on the host: angle(pos, i) = pos * theta^(-2 i / hd)
+  const int half = c.head_dim / 2;
+  std::vector<float2> tab((size_t)c.max_seq * half);
+  for (int i = 0; i < half; ++i) {
+    const double f = pow((double)c.rope_theta, -2.0 * i / c.head_dim);
+    for (int p = 0; p < c.max_seq; ++p) {
+      const double a = p * f;
+      tab[(size_t)p * half + i] = make_float2((float)cos(a), (float)sin(a));
+    }
+  }
+  if ((rc = dev_alloc(w, tab.size() * sizeof(float2), (void**)&w->rope))) return rc;
+  HIP_CK(hipMemcpy(w->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice));
+  return SAPO_OK;
+}
+
+extern "C" int sapo_weights_create(const sapo_model_config* cfg, const void* const* tensors, int n_tensors,
+                                   void* stream, sapo_weights** out) {
+  int rc = validate_config(cfg);
+  if (rc) return rc;
+  if (!tensors || !out) return fail(SAPO_EINVAL, "tensors/out is NULL");
+  const int expect = 1 + 9 * cfg->n_layers + 2;
+  if (n_tensors != expect) return fail(SAPO_EINVAL, "n_tensors = %d, expected %d", n_tensors, expect);
+  for (int i = 0; i < expect; ++i)
+    if (!tensors[i] && !(i == expect - 1 && cfg->tied_embeddings)) return fail(SAPO_EINVAL, "tensor %d is NULL", i);
+  sapo_weights* w = new sapo_weights();
+  w->cfg = *cfg;
+  w->elt = cfg->dtype == SAPO_DTYPE_F32 ? 4 : 2;
+  w->mfma = false;
+  rc = create_impl(w, tensors, (hipStream_t)stream);
+  if (rc) {
+    sapo_weights_destroy(w);
+    return rc;
+  }
+  *out = w;
+  return SAPO_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// workspace carving: the same walk computes the size (base == NULL) and the pointers
+// ---------------------------------------------------------------------------------------
+struct Arena {
+  char* base;
+  size_t off;
+  template <typename T> T* take(size_t n) {
+    off = (off + 255) & ~(size_t)255;
+    T* p = base ? (T*)(base + off) : nullptr;
+    off += n * sizeof(T);
+    return p;
+  }
+  void* take_bytes(size_t n) { return take<char>(n); }
+};
+
+struct FwdBufs {      // activations for M rows
+  float* h;           // [M, d] residual stream
+  void* a;            // [M, d] norm output (T)
+  float* qkv;         // [M, q + 2 kv]
+  void* q;            // [M, q] rotated queries (T)
+  void* attn;         // [M, q] attention output (T)
+  float* gu;          // [M, 2 F]
+  void* act;          // [M, F] (T)
+};
+
+static void carve_fwd(Arena& A, const sapo_weights* w, size_t M, FwdBufs& b) {
+  const sapo_model_config& c = w->cfg;
+  const size_t d = c.d_model, q = (size_t)c.n_q_heads * c.head_dim, kv = (size_t)c.n_kv_heads * c.head_dim, F = c.d_ff;
+  b.h = A.take<float>(M * d);
+  b.a = A.take_bytes(M * d * w->elt);
+  b.qkv = A.take<float>(M * (q + 2 * kv));
+  b.q = A.take_bytes(M * q * w->elt);
+  b.attn = A.take_bytes(M * q * w->elt);
+  b.gu = A.take<float>(M * 2 * F);
+  b.act = A.take_bytes(M * F * w->elt);
+}
+
+struct CacheBufs {
+  int* page_table;
+  int pages_per_seq;
+  size_t n_pages;
+  std::vector<void*> k, v;   // per layer
+};
+
+static void carve_cache(Arena& A, const sapo_weights* w, int n_seq, int pages_per_seq, size_t n_pages, CacheBufs& cb) {
+  const sapo_model_config& c = w->cfg;
+  cb.pages_per_seq = pages_per_seq;
+  cb.n_pages = n_pages;
+  cb.page_table = A.take<int>((size_t)n_seq * pages_per_seq);
+  const size_t page_bytes = (size_t)c.n_kv_heads * kPageTokens * c.head_dim * w->elt;
+  cb.k.resize(c.n_layers);
+  cb.v.resize(c.n_layers);
+  for (int l = 0; l < c.n_layers; ++l) {
+    cb.k[l] = A.take_bytes(n_pages * page_bytes);
+    cb.v[l] = A.take_bytes(n_pages * page_bytes);
+  }
+}
+
+static KVCache layer_cache(const sapo_weights* w, const CacheBufs& cb, int l) {
+  KVCache kv;
+  kv.k = cb.k[l];
+  kv.v = cb.v[l];
+  kv.page_table = cb.page_table;
+  kv.pages_per_seq = cb.pages_per_seq;
+  kv.n_kv_heads = w->cfg.n_kv_heads;
+  kv.head_dim = w->cfg.head_dim;
+  return kv;
+}
+
+// ---------------------------------------------------------------------------------------
+// the decoder layers on M rows whose residual stream is already in b.h
+// ---------------------------------------------------------------------------------------
+static int run_layers(const sapo_weights* w, const FwdBufs& b, int M, RowMap rm, const CacheBufs& cb, int max_ctx,
+                      hipStream_t st) {
+  const sapo_model_config& c = w->cfg;
+  const int dt = c.dtype;
+  const int d = c.d_model, q = c.n_q_heads * c.head_dim, kv = c.n_kv_heads * c.head_dim, F = c.d_ff;
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerWeights& lw = w->layers[l];
+    const KVCache kvc = layer_cache(w, cb, l);
+    HIP_CK(g_rmsnorm(dt, b.h, lw.attn_norm, c.rms_eps, b.a, M, d, nullptr, st));
+    HIP_CK(g_gemm(dt, b.a, lw.wqkv, b.qkv, M, q + 2 * kv, d, q + 2 * kv, EPI_STORE_F32, st));
+    HIP_CK(g_rope_append(dt, b.qkv, w->rope, rm, kvc, b.q, M, c.n_q_heads, st));
+    HIP_CK(g_attention(dt, b.q, rm, kvc, b.attn, M, c.n_q_heads, max_ctx, st));
+    HIP_CK(g_gemm(dt, b.attn, lw.wo, b.h, M, d, q, d, EPI_ADD_F32, st));
+    HIP_CK(g_rmsnorm(dt, b.h, lw.ffn_norm, c.rms_eps, b.a, M, d, nullptr, st));
+    HIP_CK(g_gemm(dt, b.a, lw.wgu, b.gu, M, 2 * F, d, 2 * F, EPI_STORE_F32, st));
+    HIP_CK(g_swiglu(dt, b.gu, b.act, M, F, st));
+    HIP_CK(g_gemm(dt, b.act, lw.wdown, b.h, M, d, F, d, EPI_ADD_F32, st));
+  }
+  return SAPO_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// rollout generation
+// ---------------------------------------------------------------------------------------
+struct RolloutPlan {
+  int P, Lp, G, N, S;
+  int full_prompt_pages, pages_per_seq;
+  size_t n_pages, M_max;
+  CacheBufs cache;
+  FwdBufs fwd;
+  int* step;        // device step counter
+  int* last_rows;   // [P]
+  void* x_last;     // [max(P, S), d] final-norm output (T)
+  float* logits;    // [max(P, S), V]
+  size_t bytes;
+};
+
+static void plan_rollout(const sapo_weights* w, int P, int Lp, int G, int N, char* base, RolloutPlan& pl) {
+  const sapo_model_config& c = w->cfg;
+  pl.P = P; pl.Lp = Lp; pl.G = G; pl.N = N; pl.S = P * G;
+  pl.full_prompt_pages = Lp / kPageTokens;
+  pl.pages_per_seq = (Lp + N + kPageTokens - 1) / kPageTokens;
+  const int own = pl.pages_per_seq - pl.full_prompt_pages;
+  pl.n_pages = (size_t)P * pl.full_prompt_pages + (size_t)pl.S * own;
+  pl.M_max = (size_t)P * Lp > (size_t)pl.S ? (size_t)P * Lp : (size_t)pl.S;
+  Arena A{base, 0};
+  pl.step = A.take<int>(64);
+  pl.last_rows = A.take<int>(P);
+  carve_cache(A, w, pl.S, pl.pages_per_seq, pl.n_pages, pl.cache);
+  carve_fwd(A, w, pl.M_max, pl.fwd);
+  const size_t R = (size_t)(P > pl.S ? P : pl.S);
+  pl.x_last = A.take_bytes(R * c.d_model * w->elt);
+  pl.logits = A.take<float>(R * c.vocab);
+  pl.bytes = (A.off + 255) & ~(size_t)255;
+}
+
+static int check_rollout_args(const sapo_weights* w, int P, int Lp, int G, int N) {
+  if (!w) return fail(SAPO_EINVAL, "weights is NULL");
+  if (P <= 0 || Lp <= 0 || G <= 0 || N <= 0) return fail(SAPO_EINVAL, "P, Lp, G, max_new must be positive");
+  if ((long)Lp + N > w->cfg.max_seq) return fail(SAPO_EINVAL, "Lp + max_new = %d exceeds max_seq = %d", Lp + N, w->cfg.max_seq);
+  if ((long)P * G > (1 << 20) || (long)P * Lp > (1 << 24)) return fail(SAPO_EINVAL, "batch too large");
+  return SAPO_OK;
+}
+
+extern "C" size_t sapo_rollout_workspace_bytes(const sapo_weights* w, int P, int Lp, int G, int max_new) {
+  if (check_rollout_args(w, P, Lp, G, max_new)) return 0;
+  RolloutPlan pl;
+  plan_rollout(w, P, Lp, G, max_new, nullptr, pl);
+  return pl.bytes;
+}
+
+extern "C" int sapo_rollout_generate(const sapo_weights* w, const int32_t* prompts, int P, int Lp, int G, int max_new,
+                                     float temperature, uint64_t seed, int32_t* out_tokens, float* out_logprobs,
+                                     void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_rollout_args(w, P, Lp, G, max_new);
+  if (rc) return rc;
+  if (!prompts || !out_tokens || !out_logprobs || !workspace) return fail(SAPO_EINVAL, "NULL buffer");
+  if (!(temperature >= 0.f)) return fail(SAPO_EINVAL, "temperature must be >= 0");
+  if (((uintptr_t)workspace & 255) != 0) return fail(SAPO_EINVAL, "workspace must be 256-byte aligned");
+  RolloutPlan pl;
+  plan_rollout(w, P, Lp, G, max_new, (char*)workspace, pl);
+  if (workspace_bytes < pl.bytes) return fail(SAPO_EWORKSPACE, "workspace %zu < required %zu", workspace_bytes, pl.bytes);
+  hipStream_t st = (hipStream_t)stream;
+  const sapo_model_config& c = w->cfg;
+  const int dt = c.dtype, d = c.d_model, V = c.vocab, S = pl.S;
+
+  SampleParams sp;
+  sp.temperature = temperature;
+  sp.seed_lo = (uint32_t)(seed & 0xffffffffu);
+  sp.seed_hi = (uint32_t)(seed >> 32);
+  sp.max_new = max_new;
+  sp.step = pl.step;
+  sp.out_tokens = out_tokens;
+  sp.out_logprobs = out_logprobs;
+
+  HIP_CK(g_fill_i32(pl.step, 0, 1, st));
+  HIP_CK(g_page_table(pl.cache.page_table, S, pl.pages_per_seq, G, pl.full_prompt_pages, P, st));
+  HIP_CK(g_last_rows(pl.last_rows, P, Lp, st));
+
+  // prefill: the P unique prompts, written through the page table of each prompt's first sibling
+  {
+    const int M = P * Lp;
+    RowMap rm{0, Lp, G, 0, nullptr};
+    HIP_CK(g_embed(dt, prompts, 1, nullptr, w->embed, pl.fwd.h, M, d, st));
+    if ((rc = run_layers(w, pl.fwd, M, rm, pl.cache, Lp, st))) return rc;
+    if (Lp % kPageTokens != 0)
+      for (int l = 0; l < c.n_layers; ++l)
+        HIP_CK(g_copy_partial_page(dt, layer_cache(w, pl.cache, l), P, G, pl.full_prompt_pages, st));
+    HIP_CK(g_rmsnorm(dt, pl.fwd.h, w->final_norm, c.rms_eps, pl.x_last, P, d, pl.last_rows, st));
+    HIP_CK(g_gemm(dt, pl.x_last, w->lm_head, pl.logits, P, V, d, V, EPI_STORE_F32, st));
+    HIP_CK(g_sample_rows(pl.logits, P, G, V, sp, st));   // step 0: G siblings per prompt row
+  }
+  // decode: token t-1 of every sequence goes through the layers, token t is sampled
+  RowMap rm{1, 0, 1, Lp, pl.step};
+  for (int t = 1; t < max_new; ++t) {
+    HIP_CK(g_incr(pl.step, st));
+    HIP_CK(g_embed(dt, out_tokens, max_new, pl.step, w->embed, pl.fwd.h, S, d, st));
+    if ((rc = run_layers(w, pl.fwd, S, rm, pl.cache, Lp + max_new, st))) return rc;
+    HIP_CK(g_rmsnorm(dt, pl.fwd.h, w->final_norm, c.rms_eps, pl.x_last, S, d, nullptr, st));
+    HIP_CK(g_gemm(dt, pl.x_last, w->lm_head, pl.logits, S, V, d, V, EPI_STORE_F32, st));
+    HIP_CK(g_sample_rows(pl.logits, S, 1, V, sp, st));
+  }
+  return SAPO_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// scoring
+// ---------------------------------------------------------------------------------------
+struct ScorePlan {
+  int S, T, chunk_seqs, row_chunk;
+  int pages_per_seq;
+  CacheBufs cache;
+  FwdBufs fwd;
+  int* count;       // device: number of rows to score in the current chunk
+  int* rows;        // [chunk_seqs * T, 2] (s, t)
+  int* src_rows;    // [chunk_seqs * T]
+  void* x;          // [chunk_seqs * T, d] final-norm output of the gathered rows (T)
+  float* logits;    // [row_chunk, V]
+  size_t bytes;
+};
+
+static void plan_score(const sapo_weights* w, int S, int T, int chunk_seqs, size_t extra_rows, char* base, ScorePlan& pl) {
+  const sapo_model_config& c = w->cfg;
+  pl.S = S; pl.T = T;
+  pl.chunk_seqs = chunk_seqs;
+  pl.pages_per_seq = (T + kPageTokens - 1) / kPageTokens;
+  const size_t M = (size_t)chunk_seqs * T;
+  const size_t R = M > extra_rows ? M : extra_rows;
+  size_t rc = ((size_t)256 << 20) / ((size_t)c.vocab * 4);   // logits chunk of about 256 MiB
+  if (rc < 1) rc = 1;
+  if (rc > R) rc = R;
+  pl.row_chunk = (int)rc;
+  Arena A{base, 0};
+  pl.count = A.take<int>(64);
+  pl.rows = A.take<int>(2 * R);
+  pl.src_rows = A.take<int>(R);
+  carve_cache(A, w, chunk_seqs, pl.pages_per_seq, (size_t)chunk_seqs * pl.pages_per_seq, pl.cache);
+  carve_fwd(A, w, M, pl.fwd);
+  pl.x = A.take_bytes(R * c.d_model * w->elt);
+  pl.logits = A.take<float>((size_t)pl.row_chunk * c.vocab);
+  pl.bytes = (A.off + 255) & ~(size_t)255;
+}
+
+static int score_chunk_seqs(int S, int T) {
+  int cs = 8192 / T;
+  if (cs < 1) cs = 1;
+  if (cs > S) cs = S;
+  return cs;
+}
+
+static int check_score_args(const sapo_weights* w, int S, int T) {
+  if (!w) return fail(SAPO_EINVAL, "weights is NULL");
+  if (S <= 0 || T <= 0) return fail(SAPO_EINVAL, "S and T must be positive");
+  if (T > w->cfg.max_seq) return fail(SAPO_EINVAL, "T = %d exceeds max_seq = %d", T, w->cfg.max_seq);
+  if ((long)S * T > (1L << 28)) return fail(SAPO_EINVAL, "batch too large");
+  return SAPO_OK;
+}
+
+extern "C" size_t sapo_score_workspace_bytes(const sapo_weights* w, int S, int T) {
+  if (check_score_args(w, S, T)) return 0;
+  ScorePlan pl;
+  plan_score(w, S, T, score_chunk_seqs(S, T), 0, nullptr, pl);
+  return pl.bytes;
+}
+
+// forward of sequences [s0, s0 + ns) into pl.fwd.h (rows (s - s0) * T + t)
+static int forward_chunk(const sapo_weights* w, const ScorePlan& pl, const int32_t* tokens, int s0, int ns, hipStream_t st) {
+  const sapo_model_config& c = w->cfg;
+  const int M = ns * pl.T;
+  RowMap rm{0, pl.T, 1, 0, nullptr};
+  HIP_CK(g_embed(c.dtype, tokens + (size_t)s0 * pl.T, 1, nullptr, w->embed, pl.fwd.h, M, c.d_model, st));
+  return run_layers(w, pl.fwd, M, rm, pl.cache, pl.T, st);
+}
+
+extern "C" int sapo_score_logprobs(const sapo_weights* w, const int32_t* tokens, const uint8_t* completion_mask,
+                                   const float* rewards, int S, int T, int G, float* out_logprobs,
+                                   float* out_advantages, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_score_args(w, S, T);
+  if (rc) return rc;
+  if (G <= 0 || S % G != 0) return fail(SAPO_EINVAL, "S = %d is not a multiple of G = %d", S, G);
+  if (!tokens || !completion_mask || !rewards || !out_logprobs || !out_advantages || !workspace)
+    return fail(SAPO_EINVAL, "NULL buffer");
+  if (((uintptr_t)workspace & 255) != 0) return fail(SAPO_EINVAL, "workspace must be 256-byte aligned");
+  ScorePlan pl;
+  plan_score(w, S, T, score_chunk_seqs(S, T), 0, (char*)workspace, pl);
+  if (workspace_bytes < pl.bytes) return fail(SAPO_EWORKSPACE, "workspace %zu < required %zu", workspace_bytes, pl.bytes);
+  hipStream_t st = (hipStream_t)stream;
+  const sapo_model_config& c = w->cfg;
+
+  HIP_CK(g_advantages(rewards, S, G, out_advantages, st));
+  HIP_CK(g_fill_f32(out_logprobs, 0.f, (size_t)S * T, st));
+  HIP_CK(g_page_table(pl.cache.page_table, pl.chunk_seqs, pl.pages_per_seq, 1, 0, pl.chunk_seqs, st));
+  for (int s0 = 0; s0 < S; s0 += pl.chunk_seqs) {
+    const int ns = (S - s0 < pl.chunk_seqs) ? S - s0 : pl.chunk_seqs;
+    const int M = ns * T;
+    if ((rc = forward_chunk(w, pl, tokens, s0, ns, st))) return rc;
+    HIP_CK(g_masked_rows(completion_mask, T, s0, ns, pl.rows, pl.src_rows, pl.count, st));
+    HIP_CK(g_rmsnorm(c.dtype, pl.fwd.h, w->final_norm, c.rms_eps, pl.x, M, c.d_model, pl.src_rows, st));
+    for (int r0 = 0; r0 < M; r0 += pl.row_chunk) {
+      const int nr = (M - r0 < pl.row_chunk) ? M - r0 : pl.row_chunk;
+      HIP_CK(g_gemm(c.dtype, (char*)pl.x + (size_t)r0 * c.d_model * w->elt, w->lm_head, pl.logits, nr, c.vocab,
+                    c.d_model, c.vocab, EPI_STORE_F32, st));
+      HIP_CK(g_score_rows(pl.logits, nr, r0, c.vocab, pl.rows, pl.count, tokens, T, out_logprobs, st));
+    }
+  }
+  return SAPO_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// test hooks
+// ---------------------------------------------------------------------------------------
+extern "C" size_t sapo_debug_logits_workspace_bytes(const sapo_weights* w, int S, int T, int n) {
+  if (check_score_args(w, S, T) || n <= 0) return 0;
+  ScorePlan pl;
+  plan_score(w, S, T, S, (size_t)n, nullptr, pl);
+  return pl.bytes;
+}
+
+extern "C" int sapo_debug_logits(const sapo_weights* w, const int32_t* tokens, int S, int T, const int32_t* positions,
+                                 int n, float* out_logits, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_score_args(w, S, T);
+  if (rc) return rc;
+  if (n <= 0) return fail(SAPO_EINVAL, "n must be positive");
+  if (!tokens || !positions || !out_logits || !workspace) return fail(SAPO_EINVAL, "NULL buffer");
+  if (((uintptr_t)workspace & 255) != 0) return fail(SAPO_EINVAL, "workspace must be 256-byte aligned");
+  ScorePlan pl;
+  plan_score(w, S, T, S, (size_t)n, (char*)workspace, pl);
+  if (workspace_bytes < pl.bytes) return fail(SAPO_EWORKSPACE, "workspace %zu < required %zu", workspace_bytes, pl.bytes);
+  hipStream_t st = (hipStream_t)stream;
+  const sapo_model_config& c = w->cfg;
+  HIP_CK(g_page_table(pl.cache.page_table, S, pl.pages_per_seq, 1, 0, S, st));
+  if ((rc = forward_chunk(w, pl, tokens, 0, S, st))) return rc;
+  HIP_CK(g_rows_from_positions(positions, n, T, pl.src_rows, st));
+  HIP_CK(g_rmsnorm(c.dtype, pl.fwd.h, w->final_norm, c.rms_eps, pl.x, n, c.d_model, pl.src_rows, st));
+  HIP_CK(g_gemm(c.dtype, pl.x, w->lm_head, out_logits, n, c.vocab, c.d_model, c.vocab, EPI_STORE_F32, st));
+  return SAPO_OK;
+}
+
+extern "C" int sapo_debug_gumbel(uint64_t seed, uint32_t seq, uint32_t step, uint32_t v0, int n, float* out,
+                                 void* stream) {
+  if (n < 0 || !out) return fail(SAPO_EINVAL, "bad arguments");
+  HIP_CK(g_gumbel((uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32), seq, step, v0, n, out, (hipStream_t)stream));
+  return SAPO_OK;
+}

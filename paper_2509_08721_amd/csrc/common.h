@@ -1,0 +1,168 @@
+// Internal declarations shared by the translation units of libsapo (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/sapo.h"
+
+namespace sapo {
+
+typedef __bf16 bf16;
+
+constexpr int kPageTokens = 16;
+constexpr int kWave = 64;
+
+// ---------------------------------------------------------------------------------------
+// Row -> (sequence, position) maps.  A "row" is one token being pushed through the layers.
+//   block mode : rows are laid out [n_seq, T]; row m is position m % T of cache sequence
+//                (m / T) * seq_stride (prefill of prompt p writes through the page table of
+//                the first sibling, seq_stride = G; scoring uses seq_stride = 1).
+//   decode mode: row m is sequence m at position Lp + *step - 1 (the token sampled at the
+//                previous step); *step lives in device memory so that one captured graph
+//                can be replayed for every step.
+// ---------------------------------------------------------------------------------------
+struct RowMap {
+  int decode;       // 0 block, 1 decode
+  int T;            // block mode: positions per sequence
+  int seq_stride;   // block mode: cache-sequence stride
+  int Lp;           // decode mode: prompt length
+  const int* step;  // decode mode: device pointer to the current step index (>= 1)
+  __device__ __forceinline__ void get(int m, int& seq, int& pos) const {
+    if (decode) {
+      seq = m;
+      pos = Lp + *step - 1;
+    } else {
+      seq = (m / T) * seq_stride;
+      pos = m % T;
+    }
+  }
+};
+
+// Paged KV cache of one layer.  K page: [Hkv][16 tokens][hd]; V page: [Hkv][hd][16 tokens]
+// (V is kept token-minor so that a fixed feature's 16 tokens are contiguous).
+struct KVCache {
+  void* k;                // [n_pages][Hkv][16][hd]
+  void* v;                // [n_pages][Hkv][hd][16]
+  const int* page_table;  // [n_cache_seq][pages_per_seq]
+  int pages_per_seq;
+  int n_kv_heads;
+  int head_dim;
+};
+
+// ---------------------------------------------------------------------------------------
+// Device helpers
+// ---------------------------------------------------------------------------------------
+template <typename T> __device__ __forceinline__ float to_f32(T x) { return static_cast<float>(x); }
+template <typename T> __device__ __forceinline__ T from_f32(float x) { return static_cast<T>(x); }
+
+__device__ __forceinline__ float wave_reduce_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_reduce_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// Philox4x32-10 (Salmon et al., SC'11): ten rounds on a 4-word counter with a 2-word key.
+struct Philox4 { uint32_t x, y, z, w; };
+__device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                 uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+    k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+  }
+  return Philox4{c0, c1, c2, c3};
+}
+
+// Standard Gumbel noise from one 32-bit random word: u = (2 (x >> 9) + 1) 2^-24 is strictly
+// inside (0, 1) and exact in fp32; g = -ln(-ln u).
+__device__ __forceinline__ float gumbel_from_bits(uint32_t x) {
+  const float u = (float)(2u * (x >> 9) + 1u) * 5.9604644775390625e-08f;
+  return -logf(-logf(u));
+}
+
+// Noise for vocab entries 4*blk .. 4*blk+3 of (seed, seq, step): counter (blk, step, seq, 0),
+// key = (seed low, seed high); entry v uses output word v % 4.
+__device__ __forceinline__ void gumbel4(uint32_t seed_lo, uint32_t seed_hi, uint32_t seq, uint32_t step,
+                                        uint32_t blk, float g[4]) {
+  const Philox4 r = philox4x32_10(blk, step, seq, 0u, seed_lo, seed_hi);
+  g[0] = gumbel_from_bits(r.x); g[1] = gumbel_from_bits(r.y);
+  g[2] = gumbel_from_bits(r.z); g[3] = gumbel_from_bits(r.w);
+}
+
+// Running (max, sum of exp) pair of an online log-sum-exp.
+struct LseAcc {
+  float m, l;
+  __device__ __forceinline__ void init() { m = -INFINITY; l = 0.f; }
+  __device__ __forceinline__ void add(float z) {
+    if (z > m) { l = l * __expf(m - z) + 1.f; m = z; } else { l += __expf(z - m); }
+  }
+  __device__ __forceinline__ void merge(float m2, float l2) {
+    const float mn = fmaxf(m, m2);
+    if (mn == -INFINITY) return;
+    l = l * __expf(m - mn) + l2 * __expf(m2 - mn);
+    m = mn;
+  }
+};
+
+// Best perturbed score so far: larger y wins, equal y goes to the lower id.
+struct BestAcc {
+  float y, z; int id;
+  __device__ __forceinline__ void init() { y = -INFINITY; z = 0.f; id = 0x7fffffff; }
+  __device__ __forceinline__ void add(float y2, float z2, int id2) {
+    if (y2 > y || (y2 == y && id2 < id)) { y = y2; z = z2; id = id2; }
+  }
+};
+
+// ---------------------------------------------------------------------------------------
+// Host-side launchers.  Every launcher enqueues on `st` and returns the launch's hipError_t.
+// dtype: SAPO_DTYPE_F32 / SAPO_DTYPE_BF16 selects the element type T of weights/activations.
+// ---------------------------------------------------------------------------------------
+struct SampleParams {
+  float temperature;
+  uint32_t seed_lo, seed_hi;
+  int max_new;            // row stride of out_tokens / out_logprobs
+  const int* step;        // device: index of the token being sampled (0-based)
+  int32_t* out_tokens;    // [S, max_new]
+  float* out_logprobs;    // [S, max_new]
+};
+
+// generic (shape-agnostic) kernels --------------------------------------------------------
+hipError_t g_embed(int dtype, const int32_t* tokens, int tok_stride, const int* step, const void* embed,
+                   float* h, int M, int d, hipStream_t st);
+hipError_t g_rmsnorm(int dtype, const float* h, const float* gain, float eps, void* out, int M, int d,
+                     const int* row_index, hipStream_t st);
+enum GemmEpi { EPI_STORE_F32 = 0, EPI_ADD_F32 = 1 };
+hipError_t g_gemm(int dtype, const void* A, const void* W, float* C, int M, int N, int K, int ldc, GemmEpi epi,
+                  hipStream_t st);
+hipError_t g_rope_append(int dtype, const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* q_out,
+                         int M, int n_q_heads, hipStream_t st);
+hipError_t g_attention(int dtype, const void* q, RowMap rm, KVCache kv, void* out, int M, int n_q_heads,
+                       int max_ctx, hipStream_t st);
+hipError_t g_swiglu(int dtype, const float* gu, void* act, int M, int F, hipStream_t st);
+hipError_t g_sample_rows(const float* logits, int n_prompt_rows, int G, int V, SampleParams sp, hipStream_t st);
+hipError_t g_score_rows(const float* logits, int n_rows, int row_offset, int V, const int* row_seq_pos,
+                        const int* n_rows_dev, const int32_t* tokens, int T, float* out_logprobs, hipStream_t st);
+hipError_t g_advantages(const float* rewards, int S, int G, float* out, hipStream_t st);
+hipError_t g_page_table(int* pt, int n_seq, int pages_per_seq, int G, int full_prompt_pages, int n_prompts,
+                        hipStream_t st);
+hipError_t g_copy_partial_page(int dtype, KVCache kv, int n_prompts, int G, int page_idx, hipStream_t st);
+hipError_t g_fill_i32(int* p, int v, size_t n, hipStream_t st);
+hipError_t g_fill_f32(float* p, float v, size_t n, hipStream_t st);
+hipError_t g_incr(int* p, hipStream_t st);
+hipError_t g_masked_rows(const uint8_t* mask, int T, int s0, int ns, int* rows /*[ns*T,2]*/, int* src_rows /*[ns*T]*/,
+                         int* count, hipStream_t st);
+hipError_t g_rows_from_positions(const int* positions, int n, int T, int* src_rows, hipStream_t st);
+hipError_t g_last_rows(int* rows, int P, int Lp, hipStream_t st);
+hipError_t g_gumbel(uint32_t seed_lo, uint32_t seed_hi, uint32_t seq, uint32_t step, uint32_t v0, int n, float* out,
+                    hipStream_t st);
+
+}  // namespace sapo

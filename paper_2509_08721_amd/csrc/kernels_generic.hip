@@ -1,0 +1,492 @@
+// Shape-generic kernels: any model shape, fp32 or bf16 storage, plain ALU arithmetic.
+// They run the fp32 configuration and every step that has no tile-aligned MFMA kernel.
+#include "common.h"
+
+namespace sapo {
+
+#define SAPO_DISPATCH_T(dtype, ...)                                   \
+  do {                                                                \
+    if ((dtype) == SAPO_DTYPE_F32) { typedef float T; __VA_ARGS__; }  \
+    else { typedef bf16 T; __VA_ARGS__; }                             \
+  } while (0)
+
+// ---------------------------------------------------------------------------------------
+// small utilities
+// ---------------------------------------------------------------------------------------
+__global__ void k_fill_i32(int* p, int v, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+__global__ void k_fill_f32(float* p, float v, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+__global__ void k_incr(int* p) { if (threadIdx.x == 0) *p += 1; }
+
+hipError_t g_fill_i32(int* p, int v, size_t n, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  k_fill_i32<<<dim3((unsigned)((n + 255) / 256)), 256, 0, st>>>(p, v, n);
+  return hipGetLastError();
+}
+hipError_t g_fill_f32(float* p, float v, size_t n, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  k_fill_f32<<<dim3((unsigned)((n + 255) / 256)), 256, 0, st>>>(p, v, n);
+  return hipGetLastError();
+}
+hipError_t g_incr(int* p, hipStream_t st) {
+  k_incr<<<1, 64, 0, st>>>(p);
+  return hipGetLastError();
+}
+
+// Page table: the first `full_prompt_pages` pages of a sequence are its prompt's shared pages,
+// the rest are the sequence's own.
+__global__ void k_page_table(int* pt, int n_seq, int pages_per_seq, int G, int fp, int n_prompts) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_seq * pages_per_seq) return;
+  int s = i / pages_per_seq, j = i % pages_per_seq;
+  int own = pages_per_seq - fp;
+  pt[i] = (j < fp) ? (s / G) * fp + j : n_prompts * fp + s * own + (j - fp);
+}
+hipError_t g_page_table(int* pt, int n_seq, int pages_per_seq, int G, int fp, int n_prompts, hipStream_t st) {
+  int n = n_seq * pages_per_seq;
+  k_page_table<<<(n + 255) / 256, 256, 0, st>>>(pt, n_seq, pages_per_seq, G, fp, n_prompts);
+  return hipGetLastError();
+}
+
+// Copy the (partially filled) page `page_idx` of each prompt's first sibling to the other
+// siblings, both K and V.
+template <typename T>
+__global__ void k_copy_partial_page(KVCache kv, int G, int page_idx) {
+  const int p = blockIdx.x, g = blockIdx.y + 1;
+  const int src = kv.page_table[(size_t)(p * G) * kv.pages_per_seq + page_idx];
+  const int dst = kv.page_table[(size_t)(p * G + g) * kv.pages_per_seq + page_idx];
+  const size_t n = (size_t)kv.n_kv_heads * kPageTokens * kv.head_dim;
+  T* k = (T*)kv.k; T* v = (T*)kv.v;
+  for (size_t i = threadIdx.x; i < n; i += blockDim.x) {
+    k[dst * n + i] = k[src * n + i];
+    v[dst * n + i] = v[src * n + i];
+  }
+}
+hipError_t g_copy_partial_page(int dtype, KVCache kv, int n_prompts, int G, int page_idx, hipStream_t st) {
+  if (G <= 1) return hipSuccess;
+  SAPO_DISPATCH_T(dtype, (k_copy_partial_page<T><<<dim3(n_prompts, G - 1), 256, 0, st>>>(kv, G, page_idx)));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// embedding gather: h[m, :] = embed[token(m), :]
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ void k_embed(const int32_t* tokens, int tok_stride, const int* step, const T* embed, float* h, int d) {
+  const int m = blockIdx.x;
+  const int tok = step ? tokens[(size_t)m * tok_stride + (*step - 1)] : tokens[(size_t)m * tok_stride];
+  const T* e = embed + (size_t)tok * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) h[(size_t)m * d + i] = to_f32(e[i]);
+}
+hipError_t g_embed(int dtype, const int32_t* tokens, int tok_stride, const int* step, const void* embed, float* h,
+                   int M, int d, hipStream_t st) {
+  SAPO_DISPATCH_T(dtype, (k_embed<T><<<M, 256, 0, st>>>(tokens, tok_stride, step, (const T*)embed, h, d)));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// RMSNorm: out[i, :] = T( h[r, :] * rsqrt(mean(h[r, :]^2) + eps) * gain ),  r = row_index ? row_index[i] : i
+// row_index < 0 entries (padding) produce zeros.
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ void k_rmsnorm(const float* h, const float* gain, float eps, T* out, int d, const int* row_index) {
+  const int i = blockIdx.x;
+  const int r = row_index ? row_index[i] : i;
+  T* o = out + (size_t)i * d;
+  if (r < 0) {
+    for (int j = threadIdx.x; j < d; j += blockDim.x) o[j] = from_f32<T>(0.f);
+    return;
+  }
+  const float* x = h + (size_t)r * d;
+  float ss = 0.f;
+  for (int j = threadIdx.x; j < d; j += blockDim.x) ss += x[j] * x[j];
+  __shared__ float red[4];
+  ss = wave_reduce_sum(ss);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float tot = red[0] + red[1] + red[2] + red[3];
+  const float scale = 1.0f / sqrtf(tot / (float)d + eps);
+  for (int j = threadIdx.x; j < d; j += blockDim.x) o[j] = from_f32<T>(x[j] * scale * gain[j]);
+}
+hipError_t g_rmsnorm(int dtype, const float* h, const float* gain, float eps, void* out, int M, int d,
+                     const int* row_index, hipStream_t st) {
+  if (M == 0) return hipSuccess;
+  SAPO_DISPATCH_T(dtype, (k_rmsnorm<T><<<M, 256, 0, st>>>(h, gain, eps, (T*)out, d, row_index)));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// GEMM  C[m, n] (+)= sum_k A[m, k] W[n, k]   (A: T [M, K], W: T [N, K], C fp32 with row stride ldc)
+// 64x64 tile per 256 threads, 4x4 outputs per thread, fp32 accumulation in k order.
+// ---------------------------------------------------------------------------------------
+template <typename T, int EPI>
+__global__ void __launch_bounds__(256) k_gemm(const T* __restrict__ A, const T* __restrict__ W, float* __restrict__ C,
+                                              int M, int N, int K, int ldc) {
+  constexpr int BM = 64, BN = 64, BK = 16;
+  __shared__ float sa[BK][BM + 4];
+  __shared__ float sw[BK][BN + 4];
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < K; k0 += BK) {
+    for (int i = threadIdx.x; i < BM * BK; i += 256) {
+      const int r = i / BK, c = i % BK;
+      const int gm = m0 + r, gn = n0 + r, gk = k0 + c;
+      sa[c][r] = (gm < M && gk < K) ? to_f32(A[(size_t)gm * K + gk]) : 0.f;
+      sw[c][r] = (gn < N && gk < K) ? to_f32(W[(size_t)gn * K + gk]) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < BK; ++kk) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = sa[kk][ty * 4 + i]; b[i] = sw[kk][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int gm = m0 + ty * 4 + i;
+    if (gm >= M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int gn = n0 + tx * 4 + j;
+      if (gn >= N) continue;
+      float* c = C + (size_t)gm * ldc + gn;
+      if (EPI == EPI_ADD_F32) *c += acc[i][j]; else *c = acc[i][j];
+    }
+  }
+}
+hipError_t g_gemm(int dtype, const void* A, const void* W, float* C, int M, int N, int K, int ldc, GemmEpi epi,
+                  hipStream_t st) {
+  if (M == 0 || N == 0) return hipSuccess;
+  dim3 grid((N + 63) / 64, (M + 63) / 64);
+  SAPO_DISPATCH_T(dtype, {
+    if (epi == EPI_ADD_F32) k_gemm<T, EPI_ADD_F32><<<grid, 256, 0, st>>>((const T*)A, (const T*)W, C, M, N, K, ldc);
+    else k_gemm<T, EPI_STORE_F32><<<grid, 256, 0, st>>>((const T*)A, (const T*)W, C, M, N, K, ldc);
+  });
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Rotary positions + KV append.  qkv fp32 [M, (Hq + 2 Hkv) hd].  For head-dim pair (i, i + hd/2):
+//   (x_i, x_{i+hd/2}) <- (x_i c - x_{i+hd/2} s, x_{i+hd/2} c + x_i s),  (c, s) = rope[pos][i].
+// q heads go to q_out T [M, Hq hd]; k heads (rotated) and v heads go to the row's cache page.
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ void k_rope_append(const float* __restrict__ qkv, const float2* __restrict__ rope, RowMap rm, KVCache kv,
+                              T* __restrict__ q_out, int n_q_heads) {
+  const int m = blockIdx.x;
+  const int hd = kv.head_dim, half = hd / 2, hkv = kv.n_kv_heads;
+  const int n_heads = n_q_heads + 2 * hkv;
+  int seq, pos;
+  rm.get(m, seq, pos);
+  const int page = kv.page_table[(size_t)seq * kv.pages_per_seq + pos / kPageTokens];
+  const int slot = pos % kPageTokens;
+  const float* row = qkv + (size_t)m * n_heads * hd;
+  for (int idx = threadIdx.x; idx < n_heads * half; idx += blockDim.x) {
+    const int head = idx / half, i = idx % half;
+    const float x1 = row[head * hd + i], x2 = row[head * hd + i + half];
+    if (head < n_q_heads + hkv) {
+      const float2 cs = rope[(size_t)pos * half + i];
+      const float r1 = x1 * cs.x - x2 * cs.y, r2 = x2 * cs.x + x1 * cs.y;
+      if (head < n_q_heads) {
+        q_out[((size_t)m * n_q_heads + head) * hd + i] = from_f32<T>(r1);
+        q_out[((size_t)m * n_q_heads + head) * hd + i + half] = from_f32<T>(r2);
+      } else {
+        const int kh = head - n_q_heads;
+        T* kp = (T*)kv.k + (((size_t)page * hkv + kh) * kPageTokens + slot) * hd;
+        kp[i] = from_f32<T>(r1);
+        kp[i + half] = from_f32<T>(r2);
+      }
+    } else {
+      const int vh = head - n_q_heads - hkv;
+      T* vp = (T*)kv.v + ((size_t)page * hkv + vh) * hd * kPageTokens;
+      vp[(size_t)i * kPageTokens + slot] = from_f32<T>(x1);
+      vp[(size_t)(i + half) * kPageTokens + slot] = from_f32<T>(x2);
+    }
+  }
+}
+hipError_t g_rope_append(int dtype, const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* q_out, int M,
+                         int n_q_heads, hipStream_t st) {
+  if (M == 0) return hipSuccess;
+  SAPO_DISPATCH_T(dtype, (k_rope_append<T><<<M, 256, 0, st>>>(qkv, rope, rm, kv, (T*)q_out, n_q_heads)));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Causal grouped-query attention over the paged cache, one wave per (row, query head).
+// Scores of the row's context are kept in LDS: pass 1 scores + max, pass 2 exp + sum, pass 3 PV.
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) k_attention(const T* __restrict__ q, RowMap rm, KVCache kv, T* __restrict__ out,
+                                                   int M, int n_q_heads, int max_ctx) {
+  extern __shared__ float smem[];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int hd = kv.head_dim, hkv = kv.n_kv_heads;
+  const long item = (long)blockIdx.x * 4 + wave;
+  if (item >= (long)M * n_q_heads) return;           // whole wave exits together; no block barriers below
+  const int m = (int)(item / n_q_heads), h = (int)(item % n_q_heads);
+  const int kvh = h / (n_q_heads / hkv);
+  int seq, pos;
+  rm.get(m, seq, pos);
+  const int ctx = pos + 1;
+  float* sc = smem + (size_t)wave * (max_ctx + hd);
+  float* qs = sc + max_ctx;
+  const T* qrow = q + ((size_t)m * n_q_heads + h) * hd;
+  for (int i = lane; i < hd; i += 64) qs[i] = to_f32(qrow[i]);
+  __builtin_amdgcn_wave_barrier();
+  const int* pt = kv.page_table + (size_t)seq * kv.pages_per_seq;
+  const float scale = 1.0f / sqrtf((float)hd);
+  float mx = -INFINITY;
+  for (int n = lane; n < ctx; n += 64) {
+    const T* kp = (const T*)kv.k + (((size_t)pt[n / kPageTokens] * hkv + kvh) * kPageTokens + n % kPageTokens) * hd;
+    float acc = 0.f;
+    for (int i = 0; i < hd; ++i) acc = fmaf(qs[i], to_f32(kp[i]), acc);
+    acc *= scale;
+    sc[n] = acc;
+    mx = fmaxf(mx, acc);
+  }
+  mx = wave_reduce_max(mx);
+  float sum = 0.f;
+  for (int n = lane; n < ctx; n += 64) {
+    const float p = expf(sc[n] - mx);
+    sc[n] = p;
+    sum += p;
+  }
+  sum = wave_reduce_sum(sum);
+  __builtin_amdgcn_wave_barrier();
+  const float inv = 1.0f / sum;
+  for (int i = lane; i < hd; i += 64) {
+    float acc = 0.f;
+    for (int n = 0; n < ctx; ++n) {
+      const T* vp = (const T*)kv.v + ((size_t)pt[n / kPageTokens] * hkv + kvh) * hd * kPageTokens;
+      acc = fmaf(sc[n], to_f32(vp[(size_t)i * kPageTokens + n % kPageTokens]), acc);
+    }
+    out[((size_t)m * n_q_heads + h) * hd + i] = from_f32<T>(acc * inv);
+  }
+}
+hipError_t g_attention(int dtype, const void* q, RowMap rm, KVCache kv, void* out, int M, int n_q_heads, int max_ctx,
+                       hipStream_t st) {
+  if (M == 0) return hipSuccess;
+  const long items = (long)M * n_q_heads;
+  const size_t smem = (size_t)4 * (max_ctx + kv.head_dim) * sizeof(float);
+  SAPO_DISPATCH_T(dtype, (k_attention<T><<<(unsigned)((items + 3) / 4), 256, smem, st>>>((const T*)q, rm, kv, (T*)out,
+                                                                                           M, n_q_heads, max_ctx)));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// SwiGLU: act[m, j] = T( silu(gu[m, j]) * gu[m, F + j] ),  silu(x) = x / (1 + exp(-x))
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ void k_swiglu(const float* __restrict__ gu, T* __restrict__ act, int M, int F) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)M * F) return;
+  const size_t m = i / F, j = i % F;
+  const float g = gu[m * 2 * F + j], u = gu[m * 2 * F + F + j];
+  act[i] = from_f32<T>(g / (1.0f + expf(-g)) * u);
+}
+hipError_t g_swiglu(int dtype, const float* gu, void* act, int M, int F, hipStream_t st) {
+  const size_t n = (size_t)M * F;
+  if (n == 0) return hipSuccess;
+  SAPO_DISPATCH_T(dtype, (k_swiglu<T><<<(unsigned)((n + 255) / 256), 256, 0, st>>>(gu, (T*)act, M, F)));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Row-wise LM-head reductions on materialised fp32 logits.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void block_merge_lse(LseAcc& a, float* sm_m, float* sm_l) {
+  // all 256 threads: reduce (m, l) pairs; result valid in every thread
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) a.merge(__shfl_xor(a.m, o, 64), __shfl_xor(a.l, o, 64));
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) { sm_m[wave] = a.m; sm_l[wave] = a.l; }
+  __syncthreads();
+  LseAcc r; r.m = sm_m[0]; r.l = sm_l[0];
+  for (int w = 1; w < 4; ++w) r.merge(sm_m[w], sm_l[w]);
+  a = r;
+}
+
+// Sample one token for sequence s = row * G + sibling from logits[row, :].
+__global__ void __launch_bounds__(256) k_sample_rows(const float* __restrict__ logits, int G, int V, SampleParams sp) {
+  const int row = blockIdx.x / G, s = blockIdx.x;   // s = row * G + sibling
+  const float* z = logits + (size_t)row * V;
+  const int step = *sp.step;
+  LseAcc lse; lse.init();
+  BestAcc best; best.init();
+  const int nblk = (V + 3) / 4;
+  for (int b = threadIdx.x; b < nblk; b += 256) {
+    float g[4] = {0.f, 0.f, 0.f, 0.f};
+    if (sp.temperature != 0.f) gumbel4(sp.seed_lo, sp.seed_hi, (uint32_t)s, (uint32_t)step, (uint32_t)b, g);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int v = 4 * b + j;
+      if (v >= V) break;
+      const float zv = z[v];
+      lse.add(zv);
+      const float y = (sp.temperature != 0.f) ? zv / sp.temperature + g[j] : zv;
+      best.add(y, zv, v);
+    }
+  }
+  __shared__ float sm_m[4], sm_l[4], sm_y[4], sm_z[4];
+  __shared__ int sm_id[4];
+  block_merge_lse(lse, sm_m, sm_l);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) best.add(__shfl_xor(best.y, o, 64), __shfl_xor(best.z, o, 64), __shfl_xor(best.id, o, 64));
+  if ((threadIdx.x & 63) == 0) { sm_y[threadIdx.x >> 6] = best.y; sm_z[threadIdx.x >> 6] = best.z; sm_id[threadIdx.x >> 6] = best.id; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w) best.add(sm_y[w], sm_z[w], sm_id[w]);
+    sp.out_tokens[(size_t)s * sp.max_new + step] = best.id;
+    sp.out_logprobs[(size_t)s * sp.max_new + step] = best.z - (lse.m + logf(lse.l));
+  }
+}
+hipError_t g_sample_rows(const float* logits, int n_rows, int G, int V, SampleParams sp, hipStream_t st) {
+  k_sample_rows<<<n_rows * G, 256, 0, st>>>(logits, G, V, sp);
+  return hipGetLastError();
+}
+
+// log-prob of the teacher-forced token: row i holds the logits after position (s, t-1) where
+// (s, t) = row_seq_pos[i]; writes out[s, t] = z[tokens[s, t]] - logsumexp(z).
+__global__ void __launch_bounds__(256) k_score_rows(const float* __restrict__ logits, int row_offset, int V,
+                                                    const int* row_seq_pos, const int* n_rows_dev,
+                                                    const int32_t* tokens, int T, float* out_logprobs) {
+  const int i = row_offset + blockIdx.x;
+  if (i >= *n_rows_dev) return;
+  const float* z = logits + (size_t)blockIdx.x * V;
+  LseAcc lse; lse.init();
+  for (int v = threadIdx.x; v < V; v += 256) lse.add(z[v]);
+  __shared__ float sm_m[4], sm_l[4];
+  block_merge_lse(lse, sm_m, sm_l);
+  if (threadIdx.x == 0) {
+    const int s = row_seq_pos[2 * i], t = row_seq_pos[2 * i + 1];
+    const int tok = tokens[(size_t)s * T + t];
+    out_logprobs[(size_t)s * T + t] = z[tok] - (lse.m + logf(lse.l));
+  }
+}
+hipError_t g_score_rows(const float* logits, int n_rows, int row_offset, int V, const int* row_seq_pos,
+                        const int* n_rows_dev, const int32_t* tokens, int T, float* out_logprobs, hipStream_t st) {
+  if (n_rows == 0) return hipSuccess;
+  k_score_rows<<<n_rows, 256, 0, st>>>(logits, row_offset, V, row_seq_pos, n_rows_dev, tokens, T, out_logprobs);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Group-relative advantages, one thread per group, fp64.
+// ---------------------------------------------------------------------------------------
+__global__ void k_advantages(const float* __restrict__ r, int n_groups, int G, float* __restrict__ out) {
+  const int g = blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= n_groups) return;
+  const float* rg = r + (size_t)g * G;
+  bool all_equal = true;
+  double sum = 0.0;
+  for (int i = 0; i < G; ++i) { sum += (double)rg[i]; all_equal = all_equal && (rg[i] == rg[0]); }
+  if (all_equal) {
+    for (int i = 0; i < G; ++i) out[(size_t)g * G + i] = 0.f;
+    return;
+  }
+  const double mu = sum / G;
+  double var = 0.0;
+  for (int i = 0; i < G; ++i) { const double dlt = (double)rg[i] - mu; var += dlt * dlt; }
+  const double sd = sqrt(var / G);
+  for (int i = 0; i < G; ++i) out[(size_t)g * G + i] = (float)(((double)rg[i] - mu) / (sd + 1e-6));
+}
+hipError_t g_advantages(const float* rewards, int S, int G, float* out, hipStream_t st) {
+  const int ng = S / G;
+  k_advantages<<<(ng + 63) / 64, 64, 0, st>>>(rewards, ng, G, out);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Ordered compaction of the positions to score in sequences [s0, s0 + ns): entry i of `rows`
+// is (s, t) with mask[s, t] != 0 and t >= 1, in (s, t) order; *count = number of entries.
+// `src_rows[i]` = local row (s - s0) * T + t - 1 whose hidden state predicts token (s, t).
+// Entries past the count are filled with (-1) in src_rows so that gathers read padding.
+// ---------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024) k_masked_rows(const uint8_t* __restrict__ mask, int T, int s0, int ns,
+                                                      int* __restrict__ rows, int* __restrict__ src_rows,
+                                                      int* __restrict__ count) {
+  __shared__ int wave_tot[16];
+  __shared__ int base;
+  if (threadIdx.x == 0) base = 0;
+  __syncthreads();
+  const int total = ns * T;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int i0 = 0; i0 < total; i0 += 1024) {
+    const int i = i0 + threadIdx.x;
+    int flag = 0, s = 0, t = 0;
+    if (i < total) {
+      s = s0 + i / T; t = i % T;
+      flag = (t >= 1 && mask[(size_t)s * T + t] != 0) ? 1 : 0;
+    }
+    const unsigned long long bal = __ballot(flag);
+    const int before = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) wave_tot[wave] = __popcll(bal);
+    __syncthreads();
+    int off = base;
+    for (int w = 0; w < wave; ++w) off += wave_tot[w];
+    if (flag) {
+      const int o = off + before;
+      rows[2 * o] = s; rows[2 * o + 1] = t;
+      src_rows[o] = (s - s0) * T + t - 1;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) { int tot = 0; for (int w = 0; w < 16; ++w) tot += wave_tot[w]; base += tot; }
+    __syncthreads();
+  }
+  for (int i = base + threadIdx.x; i < total; i += 1024) src_rows[i] = -1;
+  if (threadIdx.x == 0) *count = base;
+}
+hipError_t g_masked_rows(const uint8_t* mask, int T, int s0, int ns, int* rows, int* src_rows, int* count,
+                         hipStream_t st) {
+  k_masked_rows<<<1, 1024, 0, st>>>(mask, T, s0, ns, rows, src_rows, count);
+  return hipGetLastError();
+}
+
+// src_rows for a list of (s, t) positions: row s * T + t (debug logits).
+__global__ void k_rows_from_positions(const int* positions, int n, int T, int* src_rows) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) src_rows[i] = positions[2 * i] * T + positions[2 * i + 1];
+}
+hipError_t g_rows_from_positions(const int* positions, int n, int T, int* src_rows, hipStream_t st) {
+  k_rows_from_positions<<<(n + 255) / 256, 256, 0, st>>>(positions, n, T, src_rows);
+  return hipGetLastError();
+}
+
+// rows[p] = index of the last prompt position of prompt p in a [P, Lp] block.
+__global__ void k_last_rows(int* rows, int P, int Lp) {
+  const int p = blockIdx.x * blockDim.x + threadIdx.x;
+  if (p < P) rows[p] = p * Lp + Lp - 1;
+}
+hipError_t g_last_rows(int* rows, int P, int Lp, hipStream_t st) {
+  k_last_rows<<<(P + 255) / 256, 256, 0, st>>>(rows, P, Lp);
+  return hipGetLastError();
+}
+
+__global__ void k_gumbel(uint32_t seed_lo, uint32_t seed_hi, uint32_t seq, uint32_t step, uint32_t v0, int n, float* out) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const uint32_t v = v0 + (uint32_t)i;
+  float g[4];
+  gumbel4(seed_lo, seed_hi, seq, step, v >> 2, g);
+  out[i] = g[v & 3];
+}
+hipError_t g_gumbel(uint32_t seed_lo, uint32_t seed_hi, uint32_t seq, uint32_t step, uint32_t v0, int n, float* out,
+                    hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  k_gumbel<<<(n + 255) / 256, 256, 0, st>>>(seed_lo, seed_hi, seq, step, v0, n, out);
+  return hipGetLastError();
+}
+
+}  // namespace sapo

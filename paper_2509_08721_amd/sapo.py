@@ -1,0 +1,248 @@
+"""Thin ctypes binding over libsapo.so (the C ABI declared in include/sapo.h).
+
+Argument marshalling only: every step of rollout generation and scoring runs in
+the HIP kernels of the library.  torch is used for device memory and streams.
+There is no CPU fallback: if the library has not been built, or there is no
+GPU, the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsapo.so")
+
+SAPO_OK, SAPO_EINVAL, SAPO_ESHAPE, SAPO_EWORKSPACE, SAPO_EHIP = 0, -1, -2, -3, -4
+SAPO_DTYPE_F32, SAPO_DTYPE_BF16 = 0, 1
+
+
+class SapoError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__("libsapo error %d: %s" % (code, msg))
+        self.code = code
+
+
+class sapo_model_config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ff", C.c_int32),
+                ("vocab", C.c_int32), ("rms_eps", C.c_float), ("rope_theta", C.c_float),
+                ("tied_embeddings", C.c_int32), ("dtype", C.c_int32), ("kv_page_tokens", C.c_int32),
+                ("max_seq", C.c_int32)]
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Load libsapo.so built in-tree; raise if it is missing (no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libsapo.so is not built: run `python -m paper_2509_08721_amd.build` "
+                           "(expected at %s)" % LIB_PATH)
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, u64, u32, sz, f32 = C.c_void_p, C.c_int, C.c_uint64, C.c_uint32, C.c_size_t, C.c_float
+    lib.sapo_weights_create.argtypes = [C.POINTER(sapo_model_config), C.POINTER(vp), i32, vp, C.POINTER(vp)]
+    lib.sapo_weights_create.restype = i32
+    lib.sapo_weights_destroy.argtypes = [vp]
+    lib.sapo_weights_destroy.restype = None
+    lib.sapo_weights_uses_mfma.argtypes = [vp]
+    lib.sapo_weights_uses_mfma.restype = i32
+    lib.sapo_rollout_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
+    lib.sapo_rollout_workspace_bytes.restype = sz
+    lib.sapo_score_workspace_bytes.argtypes = [vp, i32, i32]
+    lib.sapo_score_workspace_bytes.restype = sz
+    lib.sapo_debug_logits_workspace_bytes.argtypes = [vp, i32, i32, i32]
+    lib.sapo_debug_logits_workspace_bytes.restype = sz
+    lib.sapo_rollout_generate.argtypes = [vp, vp, i32, i32, i32, i32, f32, u64, vp, vp, vp, sz, vp]
+    lib.sapo_rollout_generate.restype = i32
+    lib.sapo_score_logprobs.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+    lib.sapo_score_logprobs.restype = i32
+    lib.sapo_debug_logits.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, sz, vp]
+    lib.sapo_debug_logits.restype = i32
+    lib.sapo_debug_gumbel.argtypes = [u64, u32, u32, u32, i32, vp, vp]
+    lib.sapo_debug_gumbel.restype = i32
+    lib.sapo_last_error.argtypes = []
+    lib.sapo_last_error.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+EXPORTED = ["sapo_weights_create", "sapo_weights_destroy", "sapo_weights_uses_mfma",
+            "sapo_rollout_workspace_bytes", "sapo_score_workspace_bytes",
+            "sapo_debug_logits_workspace_bytes", "sapo_rollout_generate", "sapo_score_logprobs",
+            "sapo_debug_logits", "sapo_debug_gumbel", "sapo_last_error"]
+
+
+def _check(rc: int):
+    if rc != SAPO_OK:
+        raise SapoError(rc, load_library().sapo_last_error().decode())
+
+
+def _torch():
+    import torch
+    if not torch.cuda.is_available():
+        raise RuntimeError("no GPU visible: libsapo has no CPU path")
+    return torch
+
+
+def _stream_ptr(stream=None) -> int:
+    torch = _torch()
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def make_config(shape) -> sapo_model_config:
+    """workloads.ModelShape -> sapo_model_config."""
+    return sapo_model_config(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                             shape.d_ff, shape.vocab, shape.rms_eps, shape.rope_theta,
+                             1 if shape.tied_embeddings else 0,
+                             SAPO_DTYPE_F32 if shape.dtype == "f32" else SAPO_DTYPE_BF16,
+                             shape.kv_page_tokens, shape.max_seq)
+
+
+class Weights:
+    """Owner of a sapo_weights handle."""
+
+    def __init__(self, handle: int, cfg: sapo_model_config):
+        self.handle = handle
+        self.cfg = cfg
+
+    @property
+    def uses_mfma(self) -> bool:
+        return bool(load_library().sapo_weights_uses_mfma(self.handle))
+
+    def close(self):
+        if self.handle:
+            load_library().sapo_weights_destroy(self.handle)
+            self.handle = 0
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def _to_device(a: np.ndarray):
+    """numpy array (float32, or uint16 holding bf16 bits) -> device tensor with the same bytes."""
+    torch = _torch()
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if a.dtype == np.uint16:
+        t = t.view(torch.bfloat16)
+    return t.cuda()
+
+
+def sapo_weights_create(shape, weights: dict, stream=None) -> Weights:
+    """Upload the tensors of workloads.make_weights() and build the library's packed copy."""
+    torch = _torch()
+    lib = load_library()
+    cfg = make_config(shape)
+    order: List[Optional[np.ndarray]] = [weights["embed"]]
+    for lw in weights["layers"]:
+        order += [lw[k] for k in ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")]
+    order += [weights["final_norm"], weights.get("lm_head")]
+    dev = [None if a is None else _to_device(a) for a in order]
+    ptrs = (C.c_void_p * len(dev))(*[None if t is None else t.data_ptr() for t in dev])
+    out = C.c_void_p()
+    _check(lib.sapo_weights_create(C.byref(cfg), ptrs, len(dev), _stream_ptr(stream), C.byref(out)))
+    torch.cuda.synchronize()          # the originals in `dev` may be freed after this
+    return Weights(out.value, cfg)
+
+
+def sapo_weights_destroy(w: Weights):
+    w.close()
+
+
+def _workspace(nbytes: int):
+    torch = _torch()
+    if nbytes == 0:
+        raise SapoError(SAPO_EINVAL, load_library().sapo_last_error().decode())
+    return torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+
+
+def _aligned_ptr(t) -> int:
+    return (t.data_ptr() + 255) & ~255
+
+
+def sapo_rollout_workspace_bytes(w: Weights, P: int, Lp: int, G: int, max_new: int) -> int:
+    return int(load_library().sapo_rollout_workspace_bytes(w.handle, P, Lp, G, max_new))
+
+
+def sapo_score_workspace_bytes(w: Weights, S: int, T: int) -> int:
+    return int(load_library().sapo_score_workspace_bytes(w.handle, S, T))
+
+
+def sapo_rollout_generate(w: Weights, prompts, G: int, max_new: int, temperature: float, seed: int,
+                          workspace=None, stream=None, out_tokens=None, out_logprobs=None):
+    """prompts: int32 device tensor [P, Lp].  Returns (tokens int32 [P*G, max_new],
+    logprobs float32 [P*G, max_new]) device tensors; work is enqueued on the stream."""
+    torch = _torch()
+    lib = load_library()
+    P, Lp = int(prompts.shape[0]), int(prompts.shape[1])
+    assert prompts.dtype == torch.int32 and prompts.is_cuda and prompts.is_contiguous()
+    if out_tokens is None:
+        out_tokens = torch.empty((P * G, max_new), dtype=torch.int32, device="cuda")
+    if out_logprobs is None:
+        out_logprobs = torch.empty((P * G, max_new), dtype=torch.float32, device="cuda")
+    nbytes = sapo_rollout_workspace_bytes(w, P, Lp, G, max_new)
+    if workspace is None:
+        workspace = _workspace(nbytes)
+    _check(lib.sapo_rollout_generate(w.handle, prompts.data_ptr(), P, Lp, G, max_new, float(temperature),
+                                     int(seed), out_tokens.data_ptr(), out_logprobs.data_ptr(),
+                                     _aligned_ptr(workspace), nbytes, _stream_ptr(stream)))
+    return out_tokens, out_logprobs
+
+
+def sapo_score_logprobs(w: Weights, tokens, completion_mask, rewards, G: int, workspace=None, stream=None,
+                        out_logprobs=None, out_advantages=None):
+    """tokens int32 [S, T], completion_mask uint8 [S, T], rewards float32 [S] (device tensors).
+    Returns (logprobs float32 [S, T], advantages float32 [S])."""
+    torch = _torch()
+    lib = load_library()
+    S, T = int(tokens.shape[0]), int(tokens.shape[1])
+    assert tokens.dtype == torch.int32 and tokens.is_cuda and tokens.is_contiguous()
+    assert completion_mask.dtype == torch.uint8 and completion_mask.is_cuda and completion_mask.is_contiguous()
+    assert rewards.dtype == torch.float32 and rewards.is_cuda and rewards.is_contiguous()
+    if out_logprobs is None:
+        out_logprobs = torch.empty((S, T), dtype=torch.float32, device="cuda")
+    if out_advantages is None:
+        out_advantages = torch.empty((S,), dtype=torch.float32, device="cuda")
+    nbytes = sapo_score_workspace_bytes(w, S, T)
+    if workspace is None:
+        workspace = _workspace(nbytes)
+    _check(lib.sapo_score_logprobs(w.handle, tokens.data_ptr(), completion_mask.data_ptr(), rewards.data_ptr(),
+                                   S, T, G, out_logprobs.data_ptr(), out_advantages.data_ptr(),
+                                   _aligned_ptr(workspace), nbytes, _stream_ptr(stream)))
+    return out_logprobs, out_advantages
+
+
+def sapo_debug_logits(w: Weights, tokens, positions: Sequence[Sequence[int]], stream=None):
+    """Teacher-forced logits after consuming tokens[s, 0..t] for each (s, t) in positions.
+    Returns float32 [n, vocab] device tensor."""
+    torch = _torch()
+    lib = load_library()
+    S, T = int(tokens.shape[0]), int(tokens.shape[1])
+    pos = torch.tensor(np.asarray(positions, dtype=np.int32).reshape(-1, 2), dtype=torch.int32, device="cuda")
+    n = int(pos.shape[0])
+    assert int(pos[:, 0].min()) >= 0 and int(pos[:, 0].max()) < S and int(pos[:, 1].min()) >= 0 and int(pos[:, 1].max()) < T
+    out = torch.empty((n, w.cfg.vocab), dtype=torch.float32, device="cuda")
+    nbytes = int(lib.sapo_debug_logits_workspace_bytes(w.handle, S, T, n))
+    ws = _workspace(nbytes)
+    _check(lib.sapo_debug_logits(w.handle, tokens.data_ptr(), S, T, pos.data_ptr(), n, out.data_ptr(),
+                                 _aligned_ptr(ws), nbytes, _stream_ptr(stream)))
+    torch.cuda.synchronize()
+    return out
+
+
+def sapo_debug_gumbel(seed: int, seq: int, step: int, v0: int, n: int, stream=None):
+    """The sampler's noise g for vocab entries v0 .. v0+n-1 of (seed, seq, step): float32 [n]."""
+    torch = _torch()
+    out = torch.empty((n,), dtype=torch.float32, device="cuda")
+    _check(load_library().sapo_debug_gumbel(int(seed), seq, step, v0, n, out.data_ptr(), _stream_ptr(stream)))
+    return out

@@ -1,0 +1,61 @@
+"""CPU-side checks of the C ABI: the library loads and exports every function the header declares."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2509_08721_amd import sapo
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sapo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sapo_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_two_calls():
+    names = declared_functions()
+    assert "sapo_rollout_generate" in names and "sapo_score_logprobs" in names
+
+
+def test_library_exports_every_declared_symbol():
+    if not os.path.exists(sapo.LIB_PATH):
+        from paper_2509_08721_amd import build
+        build.build_library(verbose=False)
+    lib = ctypes.CDLL(sapo.LIB_PATH)
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+    assert sorted(sapo.EXPORTED) == declared_functions()
+
+
+def test_binding_has_same_names():
+    for name in declared_functions():
+        if name in ("sapo_last_error", "sapo_weights_uses_mfma", "sapo_debug_logits_workspace_bytes"):
+            continue
+        assert hasattr(sapo, name), name
+
+
+def test_config_struct_layout():
+    assert ctypes.sizeof(sapo.sapo_model_config) == 13 * 4
+
+
+def test_host_side_argument_validation_needs_no_gpu():
+    """Calls that are rejected before any HIP call return error codes and a message."""
+    lib = sapo.load_library()
+    assert lib.sapo_rollout_workspace_bytes(None, 1, 1, 1, 1) == 0
+    assert b"NULL" in lib.sapo_last_error()
+    cfg = sapo.sapo_model_config(2, 64, 4, 3, 16, 172, 512, 1e-6, 1e4, 1, 0, 16, 256)
+    out = ctypes.c_void_p()
+    ptrs = (ctypes.c_void_p * 21)()
+    rc = lib.sapo_weights_create(ctypes.byref(cfg), ptrs, 21, None, ctypes.byref(out))
+    assert rc == sapo.SAPO_ESHAPE and b"n_kv_heads" in lib.sapo_last_error()
+    cfg.n_kv_heads = 2
+    rc = lib.sapo_weights_create(ctypes.byref(cfg), ptrs, 20, None, ctypes.byref(out))
+    assert rc == sapo.SAPO_EINVAL
+    rc = lib.sapo_weights_create(ctypes.byref(cfg), ptrs, 21, None, ctypes.byref(out))
+    assert rc == sapo.SAPO_EINVAL and b"tensor 0" in lib.sapo_last_error()
+    cfg.kv_page_tokens = 32
+    assert lib.sapo_weights_create(ctypes.byref(cfg), ptrs, 21, None, ctypes.byref(out)) == sapo.SAPO_ESHAPE
