@@ -2,6 +2,7 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <string>
@@ -38,12 +39,13 @@ extern "C" const char* sapo_last_error(void) { return g_err.c_str(); }
 // ---------------------------------------------------------------------------------------
 // weights
 // ---------------------------------------------------------------------------------------
+// Row-major (shape-generic kernels) or fragment order (MFMA kernels); see common.h.
 struct LayerWeights {
   float* attn_norm;
   float* ffn_norm;
   void* wqkv;   // [q + 2 kv, d]
   void* wo;     // [d, q]
-  void* wgu;    // [2 F, d]: gate rows then up rows
+  void* wgu;    // [2 F, d]: generic: gate rows then up rows; MFMA: 32-row gate/up tiles interleaved
   void* wdown;  // [d, F]
 };
 
@@ -52,7 +54,7 @@ struct sapo_weights {
   int elt;                       // bytes per weight element
   bool mfma;
   void* embed;                   // row-major [V, d]
-  void* lm_head;                 // row-major [V, d] (== embed when tied)
+  void* lm_head;                 // generic: row-major [V, d] (== embed when tied); MFMA: fragment order
   float* final_norm;
   float2* rope;                  // [max_seq][hd / 2] (cos, sin)
   std::vector<LayerWeights> layers;
@@ -71,6 +73,17 @@ static int validate_config(const sapo_model_config* c) {
   if (c->max_seq > 3584) return fail(SAPO_ESHAPE, "max_seq > 3584 not supported");
   if (!(c->rms_eps > 0.f) || !(c->rope_theta > 0.f)) return fail(SAPO_EINVAL, "rms_eps and rope_theta must be > 0");
   return SAPO_OK;
+}
+
+// The MFMA kernels need bf16 storage and tile-aligned shapes; everything else runs on the
+// shape-generic kernels.  SAPO_FORCE_GENERIC=1 in the environment forces the generic kernels.
+static bool mfma_eligible(const sapo_model_config* c) {
+  const char* f = getenv("SAPO_FORCE_GENERIC");
+  if (f && f[0] == '1') return false;
+  const int q = c->n_q_heads * c->head_dim, kv = c->n_kv_heads * c->head_dim;
+  return c->dtype == SAPO_DTYPE_BF16 && (c->head_dim == 64 || c->head_dim == 128) && c->d_model % 128 == 0 &&
+         q % 128 == 0 && (q + 2 * kv) % 128 == 0 && kv % 32 == 0 && c->d_ff % 64 == 0 && c->vocab % 128 == 0 &&
+         c->n_q_heads / c->n_kv_heads <= 16;
 }
 
 extern "C" void sapo_weights_destroy(sapo_weights* w) {
@@ -112,19 +125,32 @@ static int create_impl(sapo_weights* w, const void* const* t, hipStream_t st) {
     if ((rc = dev_alloc(w, 2 * F * d * e, &lw.wgu))) return rc;
     if ((rc = dev_alloc(w, d * F * e, &lw.wdown))) return rc;
     HIP_CK(copy(lw.attn_norm, lt[0], d * 4));
-    HIP_CK(copy(lw.wqkv, lt[1], q * d * e));
-    HIP_CK(copy((char*)lw.wqkv + q * d * e, lt[2], kv * d * e));
-    HIP_CK(copy((char*)lw.wqkv + (q + kv) * d * e, lt[3], kv * d * e));
-    HIP_CK(copy(lw.wo, lt[4], d * q * e));
     HIP_CK(copy(lw.ffn_norm, lt[5], d * 4));
-    HIP_CK(copy(lw.wgu, lt[6], F * d * e));
-    HIP_CK(copy((char*)lw.wgu + F * d * e, lt[7], F * d * e));
-    HIP_CK(copy(lw.wdown, lt[8], d * F * e));
+    if (w->mfma) {
+      HIP_CK(m_pack_weight(lt[1], (int)q, (int)d, lw.wqkv, 0, 1, st));
+      HIP_CK(m_pack_weight(lt[2], (int)kv, (int)d, lw.wqkv, (int)(q / 32), 1, st));
+      HIP_CK(m_pack_weight(lt[3], (int)kv, (int)d, lw.wqkv, (int)((q + kv) / 32), 1, st));
+      HIP_CK(m_pack_weight(lt[4], (int)d, (int)q, lw.wo, 0, 1, st));
+      HIP_CK(m_pack_weight(lt[6], (int)F, (int)d, lw.wgu, 0, 2, st));
+      HIP_CK(m_pack_weight(lt[7], (int)F, (int)d, lw.wgu, 1, 2, st));
+      HIP_CK(m_pack_weight(lt[8], (int)d, (int)F, lw.wdown, 0, 1, st));
+    } else {
+      HIP_CK(copy(lw.wqkv, lt[1], q * d * e));
+      HIP_CK(copy((char*)lw.wqkv + q * d * e, lt[2], kv * d * e));
+      HIP_CK(copy((char*)lw.wqkv + (q + kv) * d * e, lt[3], kv * d * e));
+      HIP_CK(copy(lw.wo, lt[4], d * q * e));
+      HIP_CK(copy(lw.wgu, lt[6], F * d * e));
+      HIP_CK(copy((char*)lw.wgu + F * d * e, lt[7], F * d * e));
+      HIP_CK(copy(lw.wdown, lt[8], d * F * e));
+    }
   }
   const void* const* tail = t + 1 + 9 * c.n_layers;
   if ((rc = dev_alloc(w, d * 4, (void**)&w->final_norm))) return rc;
   HIP_CK(copy(w->final_norm, tail[0], d * 4));
-  if (c.tied_embeddings) {
+  if (w->mfma) {
+    if ((rc = dev_alloc(w, V * d * e, &w->lm_head))) return rc;
+    HIP_CK(m_pack_weight(c.tied_embeddings ? t[0] : tail[1], (int)V, (int)d, w->lm_head, 0, 1, st));
+  } else if (c.tied_embeddings) {
     w->lm_head = w->embed;
   } else {
     if ((rc = dev_alloc(w, V * d * e, &w->lm_head))) return rc;
@@ -157,7 +183,7 @@ extern "C" int sapo_weights_create(const sapo_model_config* cfg, const void* con
   sapo_weights* w = new sapo_weights();
   w->cfg = *cfg;
   w->elt = cfg->dtype == SAPO_DTYPE_F32 ? 4 : 2;
-  w->mfma = false;
+  w->mfma = mfma_eligible(cfg);
   rc = create_impl(w, tensors, (hipStream_t)stream);
   if (rc) {
     sapo_weights_destroy(w);
@@ -187,27 +213,30 @@ struct FwdBufs {      // activations for M rows
   void* a;            // [M, d] norm output (T)
   float* qkv;         // [M, q + 2 kv]
   void* q;            // [M, q] rotated queries (T)
-  void* attn;         // [M, q] attention output (T)
-  float* gu;          // [M, 2 F]
-  void* act;          // [M, F] (T)
+  void* attn;         // [M, q] attention output (T; row-major, or X-packed on the 64-token decode path)
+  float* gu;          // [M, 2 F] (shape-generic kernels only)
+  void* act;          // [M, F] (T; row-major, or X-packed on the 64-token decode path)
 };
 
 static void carve_fwd(Arena& A, const sapo_weights* w, size_t M, FwdBufs& b) {
   const sapo_model_config& c = w->cfg;
   const size_t d = c.d_model, q = (size_t)c.n_q_heads * c.head_dim, kv = (size_t)c.n_kv_heads * c.head_dim, F = c.d_ff;
+  const size_t Mp = (M + 63) / 64 * 64;   // X-packed buffers hold whole 64-token blocks
   b.h = A.take<float>(M * d);
   b.a = A.take_bytes(M * d * w->elt);
   b.qkv = A.take<float>(M * (q + 2 * kv));
   b.q = A.take_bytes(M * q * w->elt);
-  b.attn = A.take_bytes(M * q * w->elt);
-  b.gu = A.take<float>(M * 2 * F);
-  b.act = A.take_bytes(M * F * w->elt);
+  b.attn = A.take_bytes(Mp * q * w->elt);
+  b.gu = w->mfma ? nullptr : A.take<float>(M * 2 * F);
+  b.act = A.take_bytes(Mp * F * w->elt);
 }
 
 struct CacheBufs {
   int* page_table;
   int pages_per_seq;
   size_t n_pages;
+  size_t pool_bytes;         // bytes of one layer's K (or V) pool
+  char* pool;                // all pools, K and V of layer 0, K and V of layer 1, ...
   std::vector<void*> k, v;   // per layer
 };
 
@@ -217,11 +246,13 @@ static void carve_cache(Arena& A, const sapo_weights* w, int n_seq, int pages_pe
   cb.n_pages = n_pages;
   cb.page_table = A.take<int>((size_t)n_seq * pages_per_seq);
   const size_t page_bytes = (size_t)c.n_kv_heads * kPageTokens * c.head_dim * w->elt;
+  cb.pool_bytes = (n_pages * page_bytes + 255) & ~(size_t)255;
+  cb.pool = (char*)A.take_bytes(cb.pool_bytes * 2 * c.n_layers);
   cb.k.resize(c.n_layers);
   cb.v.resize(c.n_layers);
   for (int l = 0; l < c.n_layers; ++l) {
-    cb.k[l] = A.take_bytes(n_pages * page_bytes);
-    cb.v[l] = A.take_bytes(n_pages * page_bytes);
+    cb.k[l] = cb.pool ? cb.pool + cb.pool_bytes * (2 * l) : nullptr;
+    cb.v[l] = cb.pool ? cb.pool + cb.pool_bytes * (2 * l + 1) : nullptr;
   }
 }
 
@@ -236,11 +267,18 @@ static KVCache layer_cache(const sapo_weights* w, const CacheBufs& cb, int l) {
   return kv;
 }
 
+// Cache slots that no token has written yet are multiplied by zero probabilities, so they must
+// hold finite values: clear the pools once per call.
+static int clear_cache(const CacheBufs& cb, int n_layers, hipStream_t st) {
+  HIP_CK(g_fill_i32((int*)cb.pool, 0, cb.pool_bytes * 2 * n_layers / 4, st));
+  return SAPO_OK;
+}
+
 // ---------------------------------------------------------------------------------------
 // the decoder layers on M rows whose residual stream is already in b.h
 // ---------------------------------------------------------------------------------------
-static int run_layers(const sapo_weights* w, const FwdBufs& b, int M, RowMap rm, const CacheBufs& cb, int max_ctx,
-                      hipStream_t st) {
+static int run_layers_generic(const sapo_weights* w, const FwdBufs& b, int M, RowMap rm, const CacheBufs& cb, int max_ctx,
+                              hipStream_t st) {
   const sapo_model_config& c = w->cfg;
   const int dt = c.dtype;
   const int d = c.d_model, q = c.n_q_heads * c.head_dim, kv = c.n_kv_heads * c.head_dim, F = c.d_ff;
@@ -260,6 +298,61 @@ static int run_layers(const sapo_weights* w, const FwdBufs& b, int M, RowMap rm,
   return SAPO_OK;
 }
 
+// MFMA, many rows (prefill, scoring, and decode of more than 64 sequences)
+static int run_layers_big(const sapo_weights* w, const FwdBufs& b, int M, RowMap rm, const CacheBufs& cb, int max_ctx,
+                          hipStream_t st) {
+  const sapo_model_config& c = w->cfg;
+  const int dt = c.dtype;
+  const int d = c.d_model, q = c.n_q_heads * c.head_dim, kv = c.n_kv_heads * c.head_dim, F = c.d_ff;
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerWeights& lw = w->layers[l];
+    const KVCache kvc = layer_cache(w, cb, l);
+    HIP_CK(g_rmsnorm(dt, b.h, lw.attn_norm, c.rms_eps, b.a, M, d, nullptr, st));
+    HIP_CK(m_gemm_big(b.a, d, lw.wqkv, M, q + 2 * kv, d, BigEpi{BIG_STORE_F32, b.qkv, q + 2 * kv, nullptr}, st));
+    if (rm.decode) {
+      HIP_CK(m_decode_attention(b.qkv, w->rope, rm, kvc, (bf16*)b.attn, 0, M, c.n_q_heads, st));
+    } else {
+      HIP_CK(g_rope_append(dt, b.qkv, w->rope, rm, kvc, b.q, M, c.n_q_heads, st));
+      HIP_CK(g_attention(dt, b.q, rm, kvc, b.attn, M, c.n_q_heads, max_ctx, st));
+    }
+    HIP_CK(m_gemm_big(b.attn, q, lw.wo, M, d, q, BigEpi{BIG_ADD_F32, b.h, d, nullptr}, st));
+    HIP_CK(g_rmsnorm(dt, b.h, lw.ffn_norm, c.rms_eps, b.a, M, d, nullptr, st));
+    HIP_CK(m_gemm_big(b.a, d, lw.wgu, M, 2 * F, d, BigEpi{BIG_SWIGLU, nullptr, 0, (bf16*)b.act}, st));
+    HIP_CK(m_gemm_big(b.act, F, lw.wdown, M, d, F, BigEpi{BIG_ADD_F32, b.h, d, nullptr}, st));
+  }
+  return SAPO_OK;
+}
+
+// MFMA, decode of at most 64 sequences: weight-streaming GEMMs with the norms folded in
+static bool skinny_ok(const sapo_weights* w, int S) { return w->mfma && S <= 64 && w->cfg.d_model <= 896; }
+
+static int run_layers_skinny(const sapo_weights* w, const FwdBufs& b, int S, RowMap rm, const CacheBufs& cb,
+                             hipStream_t st) {
+  const sapo_model_config& c = w->cfg;
+  const int d = c.d_model, q = c.n_q_heads * c.head_dim, kv = c.n_kv_heads * c.head_dim, F = c.d_ff;
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerWeights& lw = w->layers[l];
+    const KVCache kvc = layer_cache(w, cb, l);
+    HIP_CK(m_gemm_skinny(SkinnyIn{nullptr, b.h, lw.attn_norm, c.rms_eps}, lw.wqkv, S, q + 2 * kv, d,
+                         SkinnyEpi{SK_STORE_F32, b.qkv, q + 2 * kv, nullptr}, st));
+    HIP_CK(m_decode_attention(b.qkv, w->rope, rm, kvc, (bf16*)b.attn, 1, S, c.n_q_heads, st));
+    HIP_CK(m_gemm_skinny(SkinnyIn{(const bf16*)b.attn, nullptr, nullptr, 0.f}, lw.wo, S, d, q,
+                         SkinnyEpi{SK_ADD_F32, b.h, d, nullptr}, st));
+    HIP_CK(m_gemm_skinny(SkinnyIn{nullptr, b.h, lw.ffn_norm, c.rms_eps}, lw.wgu, S, 2 * F, d,
+                         SkinnyEpi{SK_SWIGLU, nullptr, 0, (bf16*)b.act}, st));
+    HIP_CK(m_gemm_skinny(SkinnyIn{(const bf16*)b.act, nullptr, nullptr, 0.f}, lw.wdown, S, d, F,
+                         SkinnyEpi{SK_ADD_F32, b.h, d, nullptr}, st));
+  }
+  return SAPO_OK;
+}
+
+static int run_layers(const sapo_weights* w, const FwdBufs& b, int M, RowMap rm, const CacheBufs& cb, int max_ctx,
+                      hipStream_t st) {
+  if (!w->mfma) return run_layers_generic(w, b, M, rm, cb, max_ctx, st);
+  if (rm.decode && skinny_ok(w, M)) return run_layers_skinny(w, b, M, rm, cb, st);
+  return run_layers_big(w, b, M, rm, cb, max_ctx, st);
+}
+
 // ---------------------------------------------------------------------------------------
 // rollout generation
 // ---------------------------------------------------------------------------------------
@@ -271,8 +364,10 @@ struct RolloutPlan {
   FwdBufs fwd;
   int* step;        // device step counter
   int* last_rows;   // [P]
+  float* h_last;    // [S, d] residual of each sequence's last prompt position
   void* x_last;     // [max(P, S), d] final-norm output (T)
-  float* logits;    // [max(P, S), V]
+  float* logits;    // [max(P, S), V] (paths that materialise logits)
+  float* partials;  // fused sampler partials
   size_t bytes;
 };
 
@@ -290,8 +385,11 @@ static void plan_rollout(const sapo_weights* w, int P, int Lp, int G, int N, cha
   carve_cache(A, w, pl.S, pl.pages_per_seq, pl.n_pages, pl.cache);
   carve_fwd(A, w, pl.M_max, pl.fwd);
   const size_t R = (size_t)(P > pl.S ? P : pl.S);
+  pl.h_last = A.take<float>((size_t)pl.S * c.d_model);
   pl.x_last = A.take_bytes(R * c.d_model * w->elt);
-  pl.logits = A.take<float>(R * c.vocab);
+  const bool fused = skinny_ok(w, pl.S);
+  pl.logits = fused ? nullptr : A.take<float>(R * c.vocab);
+  pl.partials = fused ? A.take<float>(m_lmhead_sample_partial_floats()) : nullptr;
   pl.bytes = (A.off + 255) & ~(size_t)255;
 }
 
@@ -310,6 +408,24 @@ extern "C" size_t sapo_rollout_workspace_bytes(const sapo_weights* w, int P, int
   return pl.bytes;
 }
 
+// Sample the token of the current step for all S sequences from the residual rows in `h`
+// (row s = sequence s), writing out_tokens[:, step] and out_logprobs[:, step].
+static int sample_step(const sapo_weights* w, const RolloutPlan& pl, const float* h, SampleParams sp, hipStream_t st) {
+  const sapo_model_config& c = w->cfg;
+  const int S = pl.S, d = c.d_model, V = c.vocab;
+  if (skinny_ok(w, S)) {
+    HIP_CK(m_lmhead_sample(SkinnyIn{nullptr, h, w->final_norm, c.rms_eps}, w->lm_head, S, 0, V, d, sp, pl.partials, st));
+    return SAPO_OK;
+  }
+  HIP_CK(g_rmsnorm(c.dtype, h, w->final_norm, c.rms_eps, pl.x_last, S, d, nullptr, st));
+  if (w->mfma)
+    HIP_CK(m_gemm_big(pl.x_last, d, w->lm_head, S, V, d, BigEpi{BIG_STORE_F32, pl.logits, V, nullptr}, st));
+  else
+    HIP_CK(g_gemm(c.dtype, pl.x_last, w->lm_head, pl.logits, S, V, d, V, EPI_STORE_F32, st));
+  HIP_CK(g_sample_rows(pl.logits, S, 1, V, sp, st));
+  return SAPO_OK;
+}
+
 extern "C" int sapo_rollout_generate(const sapo_weights* w, const int32_t* prompts, int P, int Lp, int G, int max_new,
                                      float temperature, uint64_t seed, int32_t* out_tokens, float* out_logprobs,
                                      void* workspace, size_t workspace_bytes, void* stream) {
@@ -323,7 +439,7 @@ extern "C" int sapo_rollout_generate(const sapo_weights* w, const int32_t* promp
   if (workspace_bytes < pl.bytes) return fail(SAPO_EWORKSPACE, "workspace %zu < required %zu", workspace_bytes, pl.bytes);
   hipStream_t st = (hipStream_t)stream;
   const sapo_model_config& c = w->cfg;
-  const int dt = c.dtype, d = c.d_model, V = c.vocab, S = pl.S;
+  const int dt = c.dtype, d = c.d_model, S = pl.S;
 
   SampleParams sp;
   sp.temperature = temperature;
@@ -336,9 +452,10 @@ extern "C" int sapo_rollout_generate(const sapo_weights* w, const int32_t* promp
 
   HIP_CK(g_fill_i32(pl.step, 0, 1, st));
   HIP_CK(g_page_table(pl.cache.page_table, S, pl.pages_per_seq, G, pl.full_prompt_pages, P, st));
-  HIP_CK(g_last_rows(pl.last_rows, P, Lp, st));
+  if ((rc = clear_cache(pl.cache, c.n_layers, st))) return rc;
 
-  // prefill: the P unique prompts, written through the page table of each prompt's first sibling
+  // prefill: the P unique prompts, written through the page table of each prompt's first sibling;
+  // step 0 samples G siblings from each prompt's last-position logits
   {
     const int M = P * Lp;
     RowMap rm{0, Lp, G, 0, nullptr};
@@ -347,9 +464,8 @@ extern "C" int sapo_rollout_generate(const sapo_weights* w, const int32_t* promp
     if (Lp % kPageTokens != 0)
       for (int l = 0; l < c.n_layers; ++l)
         HIP_CK(g_copy_partial_page(dt, layer_cache(w, pl.cache, l), P, G, pl.full_prompt_pages, st));
-    HIP_CK(g_rmsnorm(dt, pl.fwd.h, w->final_norm, c.rms_eps, pl.x_last, P, d, pl.last_rows, st));
-    HIP_CK(g_gemm(dt, pl.x_last, w->lm_head, pl.logits, P, V, d, V, EPI_STORE_F32, st));
-    HIP_CK(g_sample_rows(pl.logits, P, G, V, sp, st));   // step 0: G siblings per prompt row
+    HIP_CK(g_gather_last_rows(pl.fwd.h, pl.h_last, S, G, Lp, d, st));
+    if ((rc = sample_step(w, pl, pl.h_last, sp, st))) return rc;
   }
   // decode: token t-1 of every sequence goes through the layers, token t is sampled
   RowMap rm{1, 0, 1, Lp, pl.step};
@@ -357,9 +473,7 @@ extern "C" int sapo_rollout_generate(const sapo_weights* w, const int32_t* promp
     HIP_CK(g_incr(pl.step, st));
     HIP_CK(g_embed(dt, out_tokens, max_new, pl.step, w->embed, pl.fwd.h, S, d, st));
     if ((rc = run_layers(w, pl.fwd, S, rm, pl.cache, Lp + max_new, st))) return rc;
-    HIP_CK(g_rmsnorm(dt, pl.fwd.h, w->final_norm, c.rms_eps, pl.x_last, S, d, nullptr, st));
-    HIP_CK(g_gemm(dt, pl.x_last, w->lm_head, pl.logits, S, V, d, V, EPI_STORE_F32, st));
-    HIP_CK(g_sample_rows(pl.logits, S, 1, V, sp, st));
+    if ((rc = sample_step(w, pl, pl.fwd.h, sp, st))) return rc;
   }
   return SAPO_OK;
 }
@@ -376,7 +490,8 @@ struct ScorePlan {
   int* rows;        // [chunk_seqs * T, 2] (s, t)
   int* src_rows;    // [chunk_seqs * T]
   void* x;          // [chunk_seqs * T, d] final-norm output of the gathered rows (T)
-  float* logits;    // [row_chunk, V]
+  float* logits;    // [row_chunk, V] (shape-generic kernels)
+  float* partials;  // fused LM-head partials (MFMA kernels)
   size_t bytes;
 };
 
@@ -398,7 +513,8 @@ static void plan_score(const sapo_weights* w, int S, int T, int chunk_seqs, size
   carve_cache(A, w, chunk_seqs, pl.pages_per_seq, (size_t)chunk_seqs * pl.pages_per_seq, pl.cache);
   carve_fwd(A, w, M, pl.fwd);
   pl.x = A.take_bytes(R * c.d_model * w->elt);
-  pl.logits = A.take<float>((size_t)pl.row_chunk * c.vocab);
+  pl.logits = w->mfma ? nullptr : A.take<float>((size_t)pl.row_chunk * c.vocab);
+  pl.partials = w->mfma ? A.take<float>(m_lmhead_score_partial_floats((int)M)) : nullptr;
   pl.bytes = (A.off + 255) & ~(size_t)255;
 }
 
@@ -451,17 +567,23 @@ extern "C" int sapo_score_logprobs(const sapo_weights* w, const int32_t* tokens,
   HIP_CK(g_advantages(rewards, S, G, out_advantages, st));
   HIP_CK(g_fill_f32(out_logprobs, 0.f, (size_t)S * T, st));
   HIP_CK(g_page_table(pl.cache.page_table, pl.chunk_seqs, pl.pages_per_seq, 1, 0, pl.chunk_seqs, st));
+  if ((rc = clear_cache(pl.cache, c.n_layers, st))) return rc;
   for (int s0 = 0; s0 < S; s0 += pl.chunk_seqs) {
     const int ns = (S - s0 < pl.chunk_seqs) ? S - s0 : pl.chunk_seqs;
     const int M = ns * T;
     if ((rc = forward_chunk(w, pl, tokens, s0, ns, st))) return rc;
     HIP_CK(g_masked_rows(completion_mask, T, s0, ns, pl.rows, pl.src_rows, pl.count, st));
     HIP_CK(g_rmsnorm(c.dtype, pl.fwd.h, w->final_norm, c.rms_eps, pl.x, M, c.d_model, pl.src_rows, st));
-    for (int r0 = 0; r0 < M; r0 += pl.row_chunk) {
-      const int nr = (M - r0 < pl.row_chunk) ? M - r0 : pl.row_chunk;
-      HIP_CK(g_gemm(c.dtype, (char*)pl.x + (size_t)r0 * c.d_model * w->elt, w->lm_head, pl.logits, nr, c.vocab,
-                    c.d_model, c.vocab, EPI_STORE_F32, st));
-      HIP_CK(g_score_rows(pl.logits, nr, r0, c.vocab, pl.rows, pl.count, tokens, T, out_logprobs, st));
+    if (w->mfma) {
+      HIP_CK(m_lmhead_score(pl.x, w->lm_head, M, pl.count, c.vocab, c.d_model, pl.rows, tokens, T, pl.partials,
+                            out_logprobs, st));
+    } else {
+      for (int r0 = 0; r0 < M; r0 += pl.row_chunk) {
+        const int nr = (M - r0 < pl.row_chunk) ? M - r0 : pl.row_chunk;
+        HIP_CK(g_gemm(c.dtype, (char*)pl.x + (size_t)r0 * c.d_model * w->elt, w->lm_head, pl.logits, nr, c.vocab,
+                      c.d_model, c.vocab, EPI_STORE_F32, st));
+        HIP_CK(g_score_rows(pl.logits, nr, r0, c.vocab, pl.rows, pl.count, tokens, T, out_logprobs, st));
+      }
     }
   }
   return SAPO_OK;
@@ -490,10 +612,14 @@ extern "C" int sapo_debug_logits(const sapo_weights* w, const int32_t* tokens, i
   hipStream_t st = (hipStream_t)stream;
   const sapo_model_config& c = w->cfg;
   HIP_CK(g_page_table(pl.cache.page_table, S, pl.pages_per_seq, 1, 0, S, st));
+  if ((rc = clear_cache(pl.cache, c.n_layers, st))) return rc;
   if ((rc = forward_chunk(w, pl, tokens, 0, S, st))) return rc;
   HIP_CK(g_rows_from_positions(positions, n, T, pl.src_rows, st));
   HIP_CK(g_rmsnorm(c.dtype, pl.fwd.h, w->final_norm, c.rms_eps, pl.x, n, c.d_model, pl.src_rows, st));
-  HIP_CK(g_gemm(c.dtype, pl.x, w->lm_head, out_logits, n, c.vocab, c.d_model, c.vocab, EPI_STORE_F32, st));
+  if (w->mfma)
+    HIP_CK(m_gemm_big(pl.x, c.d_model, w->lm_head, n, c.vocab, c.d_model, BigEpi{BIG_STORE_F32, out_logits, c.vocab, nullptr}, st));
+  else
+    HIP_CK(g_gemm(c.dtype, pl.x, w->lm_head, out_logits, n, c.vocab, c.d_model, c.vocab, EPI_STORE_F32, st));
   return SAPO_OK;
 }
 

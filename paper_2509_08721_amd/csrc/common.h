@@ -166,3 +166,59 @@ hipError_t g_gumbel(uint32_t seed_lo, uint32_t seed_hi, uint32_t seq, uint32_t s
                     hipStream_t st);
 
 }  // namespace sapo
+
+// =======================================================================================
+// MFMA (bf16) kernels: weights live in "fragment order" so that a wave's operand load for one
+// 32x32x16 MFMA step is one contiguous 1 KiB read:
+//   Wp[((tile * (K/16) + ks) * 64 + lane) * 8 + e] = W[tile*32 + lane%32][ks*16 + (lane/32)*8 + e]
+// Decode-side activations for the skinny GEMMs use the same order over tokens ("X-packed",
+// 64 tokens): Xp[((ks * 2 + tok/32) * 64 + tok%32 + 32*((k%16)/8)) * 8 + k%8], ks = k/16.
+// =======================================================================================
+namespace sapo {
+
+__host__ __device__ __forceinline__ size_t xpack_index(int tok, int k) {
+  return ((((size_t)(k >> 4) * 2 + (tok >> 5)) * 64) + (tok & 31) + 32 * ((k >> 3) & 1)) * 8 + (k & 7);
+}
+
+struct BigEpi {
+  int mode;            // see enum below
+  float* out_f32;      // STORE_F32 / ADD_F32: [M, ldc]
+  int ldc;
+  bf16* out_bf16;      // SWIGLU: act [M, F]
+};
+enum { BIG_STORE_F32 = 0, BIG_ADD_F32 = 1, BIG_SWIGLU = 2 };
+
+hipError_t m_pack_weight(const void* src, int n_rows, int K, void* dst, int dst_tile0, int dst_tile_stride,
+                         hipStream_t st);
+hipError_t m_gemm_big(const void* X, int ldx, const void* Wp, int M, int N, int K, BigEpi epi, hipStream_t st);
+hipError_t m_lmhead_score(const void* X, const void* Wp, int max_rows, const int* n_rows_dev, int V, int K,
+                          const int* row_seq_pos, const int32_t* tokens, int T, float* partials, float* out_logprobs,
+                          hipStream_t st);
+size_t m_lmhead_score_partial_floats(int max_rows);
+
+// decode (64-token) kernels ---------------------------------------------------------------
+struct SkinnyEpi {
+  int mode;            // see enum below
+  float* out_f32;      // STORE_F32: [64, ldc];  ADD_F32: h [64, ldc]
+  int ldc;
+  bf16* out_xp;        // SWIGLU: act, X-packed over K = F
+};
+enum { SK_STORE_F32 = 0, SK_ADD_F32 = 1, SK_SWIGLU = 2 };
+
+// X source of a skinny GEMM: either an X-packed bf16 buffer, or the fp32 residual stream
+// [64, K] that the kernel RMS-normalises itself (gain, eps) while staging it.
+struct SkinnyIn {
+  const bf16* xp;
+  const float* h;
+  const float* gain;
+  float eps;
+};
+hipError_t m_gemm_skinny(SkinnyIn in, const void* Wp, int n_rows, int N, int K, SkinnyEpi epi, hipStream_t st);
+hipError_t m_lmhead_sample(SkinnyIn in, const void* Wp, int n_rows, int seq0, int V, int K, SampleParams sp,
+                           float* partials, hipStream_t st);
+size_t m_lmhead_sample_partial_floats();
+hipError_t m_decode_attention(const float* qkv, const float2* rope, RowMap rm, KVCache kv, bf16* out, int out_xp,
+                              int S, int n_q_heads, hipStream_t st);
+hipError_t g_gather_last_rows(const float* h, float* out, int S, int G, int Lp, int d, hipStream_t st);
+
+}  // namespace sapo

@@ -474,6 +474,17 @@ hipError_t g_last_rows(int* rows, int P, int Lp, hipStream_t st) {
   return hipGetLastError();
 }
 
+// out[s, :] = h[(s / G) * Lp + Lp - 1, :]: the last prompt position's residual, once per sibling.
+__global__ void k_gather_last_rows(const float* __restrict__ h, float* __restrict__ out, int G, int Lp, int d) {
+  const int s = blockIdx.x;
+  const float* src = h + ((size_t)(s / G) * Lp + Lp - 1) * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) out[(size_t)s * d + i] = src[i];
+}
+hipError_t g_gather_last_rows(const float* h, float* out, int S, int G, int Lp, int d, hipStream_t st) {
+  k_gather_last_rows<<<S, 256, 0, st>>>(h, out, G, Lp, d);
+  return hipGetLastError();
+}
+
 __global__ void k_gumbel(uint32_t seed_lo, uint32_t seed_hi, uint32_t seq, uint32_t step, uint32_t v0, int n, float* out) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;

@@ -87,6 +87,13 @@ TINY = ModelShape(n_layers=2, d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16
 HALF_B = ModelShape(n_layers=24, d_model=896, n_q_heads=14, n_kv_heads=2, head_dim=64, d_ff=4864,
                     vocab=151936, rms_eps=1e-6, rope_theta=1e6, tied_embeddings=True, dtype="bf16",
                     max_seq=2048)
+# Small bf16 shapes that satisfy the tile alignment of the MFMA kernels (tests only).
+MINI_BF16 = ModelShape(n_layers=2, d_model=128, n_q_heads=4, n_kv_heads=2, head_dim=64, d_ff=256,
+                       vocab=1024, rms_eps=1e-6, rope_theta=1e4, tied_embeddings=True, dtype="bf16",
+                       max_seq=512)
+MINI_BF16_HD128 = ModelShape(n_layers=2, d_model=256, n_q_heads=6, n_kv_heads=1, head_dim=128, d_ff=320,
+                             vocab=640, rms_eps=1e-6, rope_theta=1e6, tied_embeddings=False, dtype="bf16",
+                             max_seq=512)
 ONE_HALF_B = ModelShape(n_layers=28, d_model=1536, n_q_heads=12, n_kv_heads=2, head_dim=128,
                         d_ff=8960, vocab=151936, rms_eps=1e-6, rope_theta=1e6,
                         tied_embeddings=True, dtype="bf16", max_seq=2048)
