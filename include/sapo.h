@@ -137,6 +137,19 @@ int sapo_debug_logits(const sapo_weights* w, const int32_t* tokens, int S, int T
 int sapo_debug_gumbel(uint64_t seed, uint32_t seq, uint32_t step, uint32_t v0, int n, float* out,
                       void* stream);
 
+/*
+ * Per-kernel timing for benchmarks.  Between sapo_profile_start() and sapo_profile_stop() every
+ * kernel launch the library makes is bracketed by two HIP events on its stream (this slows the
+ * calls down; do not time throughput while it is on).  sapo_profile_stop() synchronises the device
+ * and fills, per kernel symbol i < sapo_profile_kernel_count(), the summed duration in ms and the
+ * number of launches (host arrays of at least sapo_profile_kernel_count() entries).  Not
+ * thread-safe; at most 200000 launches are recorded.
+ */
+int sapo_profile_kernel_count(void);
+const char* sapo_profile_kernel_name(int i);
+int sapo_profile_start(void);
+int sapo_profile_stop(double* total_ms, int64_t* launches, int n);
+
 /* Message for the calling thread's last failed call ("" if none). */
 const char* sapo_last_error(void);
 

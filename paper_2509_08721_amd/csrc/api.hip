@@ -37,6 +37,63 @@ static int fail(int code, const char* fmt, ...) {
 extern "C" const char* sapo_last_error(void) { return g_err.c_str(); }
 
 // ---------------------------------------------------------------------------------------
+// per-kernel timing with HIP events (see ProfScope in common.h)
+// ---------------------------------------------------------------------------------------
+namespace sapo {
+bool g_prof_on = false;
+struct ProfRec { int kid; hipEvent_t e0, e1; };
+static std::vector<ProfRec> g_prof_recs;
+static std::vector<hipEvent_t> g_prof_pool;
+static const size_t kProfMaxRecs = 200000;
+static hipEvent_t prof_event() {
+  if (!g_prof_pool.empty()) { hipEvent_t e = g_prof_pool.back(); g_prof_pool.pop_back(); return e; }
+  hipEvent_t e = nullptr;
+  (void)hipEventCreate(&e);
+  return e;
+}
+void prof_mark(int kid, hipStream_t st, bool begin) {
+  if (begin) {
+    if (g_prof_recs.size() >= kProfMaxRecs) { g_prof_recs.push_back(ProfRec{-1, nullptr, nullptr}); return; }
+    ProfRec r{kid, prof_event(), prof_event()};
+    (void)hipEventRecord(r.e0, st);
+    g_prof_recs.push_back(r);
+  } else {
+    ProfRec& r = g_prof_recs.back();
+    if (r.kid >= 0) (void)hipEventRecord(r.e1, st);
+  }
+}
+}  // namespace sapo
+
+static const char* const kKernelNames[KID_COUNT] = {
+    "k_embed", "k_rmsnorm", "k_gemm", "k_rope_append", "k_attention", "k_swiglu", "k_sample_rows", "k_score_rows",
+    "misc", "k_gemm_big", "k_lmhead_score", "k_lmhead_score_merge", "k_gemm_skinny", "k_lmhead_sample",
+    "k_lmhead_sample_merge", "k_decode_attention", "k_flash_attention"};
+
+extern "C" int sapo_profile_kernel_count(void) { return KID_COUNT; }
+extern "C" const char* sapo_profile_kernel_name(int i) { return (i >= 0 && i < KID_COUNT) ? kKernelNames[i] : ""; }
+extern "C" int sapo_profile_start(void) {
+  for (auto& r : g_prof_recs)
+    if (r.kid >= 0) { g_prof_pool.push_back(r.e0); g_prof_pool.push_back(r.e1); }
+  g_prof_recs.clear();
+  g_prof_on = true;
+  return SAPO_OK;
+}
+extern "C" int sapo_profile_stop(double* total_ms, int64_t* launches, int n) {
+  g_prof_on = false;
+  if (!total_ms || !launches || n < KID_COUNT) return fail(SAPO_EINVAL, "profile buffers too small");
+  for (int i = 0; i < n; ++i) { total_ms[i] = 0.0; launches[i] = 0; }
+  HIP_CK(hipDeviceSynchronize());
+  for (auto& r : g_prof_recs) {
+    if (r.kid < 0) continue;
+    float ms = 0.f;
+    HIP_CK(hipEventElapsedTime(&ms, r.e0, r.e1));
+    total_ms[r.kid] += ms;
+    launches[r.kid] += 1;
+  }
+  return SAPO_OK;
+}
+
+// ---------------------------------------------------------------------------------------
 // weights
 // ---------------------------------------------------------------------------------------
 // Row-major (shape-generic kernels) or fragment order (MFMA kernels); see common.h.

@@ -135,6 +135,22 @@ struct SampleParams {
   float* out_logprobs;    // [S, max_new]
 };
 
+// Optional per-kernel timing: when switched on, every launch below is bracketed by two HIP
+// events on its stream; the totals are read back per kernel symbol.  Off by default (the only
+// cost is one branch per launch).
+enum KernelId {
+  KID_EMBED = 0, KID_RMSNORM, KID_GEMM_GENERIC, KID_ROPE_APPEND, KID_ATTN_GENERIC, KID_SWIGLU, KID_SAMPLE_ROWS,
+  KID_SCORE_ROWS, KID_MISC, KID_GEMM_BIG, KID_LMHEAD_SCORE, KID_LMHEAD_SCORE_MERGE, KID_GEMM_SKINNY,
+  KID_LMHEAD_SAMPLE, KID_LMHEAD_SAMPLE_MERGE, KID_DECODE_ATTN, KID_FLASH_ATTN, KID_COUNT
+};
+extern bool g_prof_on;
+void prof_mark(int kid, hipStream_t st, bool begin);
+struct ProfScope {
+  int kid; hipStream_t st;
+  ProfScope(int k, hipStream_t s) : kid(k), st(s) { if (g_prof_on) prof_mark(kid, st, true); }
+  ~ProfScope() { if (g_prof_on) prof_mark(kid, st, false); }
+};
+
 // generic (shape-agnostic) kernels --------------------------------------------------------
 hipError_t g_embed(int dtype, const int32_t* tokens, int tok_stride, const int* step, const void* embed,
                    float* h, int M, int d, hipStream_t st);

@@ -24,16 +24,19 @@ __global__ void k_fill_f32(float* p, float v, size_t n) {
 __global__ void k_incr(int* p) { if (threadIdx.x == 0) *p += 1; }
 
 hipError_t g_fill_i32(int* p, int v, size_t n, hipStream_t st) {
+  ProfScope prof_(KID_MISC, st);
   if (n == 0) return hipSuccess;
   k_fill_i32<<<dim3((unsigned)((n + 255) / 256)), 256, 0, st>>>(p, v, n);
   return hipGetLastError();
 }
 hipError_t g_fill_f32(float* p, float v, size_t n, hipStream_t st) {
+  ProfScope prof_(KID_MISC, st);
   if (n == 0) return hipSuccess;
   k_fill_f32<<<dim3((unsigned)((n + 255) / 256)), 256, 0, st>>>(p, v, n);
   return hipGetLastError();
 }
 hipError_t g_incr(int* p, hipStream_t st) {
+  ProfScope prof_(KID_MISC, st);
   k_incr<<<1, 64, 0, st>>>(p);
   return hipGetLastError();
 }
@@ -48,6 +51,7 @@ __global__ void k_page_table(int* pt, int n_seq, int pages_per_seq, int G, int f
   pt[i] = (j < fp) ? (s / G) * fp + j : n_prompts * fp + s * own + (j - fp);
 }
 hipError_t g_page_table(int* pt, int n_seq, int pages_per_seq, int G, int fp, int n_prompts, hipStream_t st) {
+  ProfScope prof_(KID_MISC, st);
   int n = n_seq * pages_per_seq;
   k_page_table<<<(n + 255) / 256, 256, 0, st>>>(pt, n_seq, pages_per_seq, G, fp, n_prompts);
   return hipGetLastError();
@@ -68,6 +72,7 @@ __global__ void k_copy_partial_page(KVCache kv, int G, int page_idx) {
   }
 }
 hipError_t g_copy_partial_page(int dtype, KVCache kv, int n_prompts, int G, int page_idx, hipStream_t st) {
+  ProfScope prof_(KID_MISC, st);
   if (G <= 1) return hipSuccess;
   SAPO_DISPATCH_T(dtype, (k_copy_partial_page<T><<<dim3(n_prompts, G - 1), 256, 0, st>>>(kv, G, page_idx)));
   return hipGetLastError();
@@ -85,6 +90,7 @@ __global__ void k_embed(const int32_t* tokens, int tok_stride, const int* step, 
 }
 hipError_t g_embed(int dtype, const int32_t* tokens, int tok_stride, const int* step, const void* embed, float* h,
                    int M, int d, hipStream_t st) {
+  ProfScope prof_(KID_EMBED, st);
   SAPO_DISPATCH_T(dtype, (k_embed<T><<<M, 256, 0, st>>>(tokens, tok_stride, step, (const T*)embed, h, d)));
   return hipGetLastError();
 }
@@ -115,6 +121,7 @@ __global__ void k_rmsnorm(const float* h, const float* gain, float eps, T* out, 
 }
 hipError_t g_rmsnorm(int dtype, const float* h, const float* gain, float eps, void* out, int M, int d,
                      const int* row_index, hipStream_t st) {
+  ProfScope prof_(KID_RMSNORM, st);
   if (M == 0) return hipSuccess;
   SAPO_DISPATCH_T(dtype, (k_rmsnorm<T><<<M, 256, 0, st>>>(h, gain, eps, (T*)out, d, row_index)));
   return hipGetLastError();
@@ -168,6 +175,7 @@ __global__ void __launch_bounds__(256) k_gemm(const T* __restrict__ A, const T* 
 }
 hipError_t g_gemm(int dtype, const void* A, const void* W, float* C, int M, int N, int K, int ldc, GemmEpi epi,
                   hipStream_t st) {
+  ProfScope prof_(KID_GEMM_GENERIC, st);
   if (M == 0 || N == 0) return hipSuccess;
   dim3 grid((N + 63) / 64, (M + 63) / 64);
   SAPO_DISPATCH_T(dtype, {
@@ -218,6 +226,7 @@ __global__ void k_rope_append(const float* __restrict__ qkv, const float2* __res
 }
 hipError_t g_rope_append(int dtype, const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* q_out, int M,
                          int n_q_heads, hipStream_t st) {
+  ProfScope prof_(KID_ROPE_APPEND, st);
   if (M == 0) return hipSuccess;
   SAPO_DISPATCH_T(dtype, (k_rope_append<T><<<M, 256, 0, st>>>(qkv, rope, rm, kv, (T*)q_out, n_q_heads)));
   return hipGetLastError();
@@ -277,6 +286,7 @@ __global__ void __launch_bounds__(256) k_attention(const T* __restrict__ q, RowM
 }
 hipError_t g_attention(int dtype, const void* q, RowMap rm, KVCache kv, void* out, int M, int n_q_heads, int max_ctx,
                        hipStream_t st) {
+  ProfScope prof_(KID_ATTN_GENERIC, st);
   if (M == 0) return hipSuccess;
   const long items = (long)M * n_q_heads;
   const size_t smem = (size_t)4 * (max_ctx + kv.head_dim) * sizeof(float);
@@ -297,6 +307,7 @@ __global__ void k_swiglu(const float* __restrict__ gu, T* __restrict__ act, int 
   act[i] = from_f32<T>(g / (1.0f + expf(-g)) * u);
 }
 hipError_t g_swiglu(int dtype, const float* gu, void* act, int M, int F, hipStream_t st) {
+  ProfScope prof_(KID_SWIGLU, st);
   const size_t n = (size_t)M * F;
   if (n == 0) return hipSuccess;
   SAPO_DISPATCH_T(dtype, (k_swiglu<T><<<(unsigned)((n + 255) / 256), 256, 0, st>>>(gu, (T*)act, M, F)));
@@ -353,6 +364,7 @@ __global__ void __launch_bounds__(256) k_sample_rows(const float* __restrict__ l
   }
 }
 hipError_t g_sample_rows(const float* logits, int n_rows, int G, int V, SampleParams sp, hipStream_t st) {
+  ProfScope prof_(KID_SAMPLE_ROWS, st);
   k_sample_rows<<<n_rows * G, 256, 0, st>>>(logits, G, V, sp);
   return hipGetLastError();
 }
@@ -377,6 +389,7 @@ __global__ void __launch_bounds__(256) k_score_rows(const float* __restrict__ lo
 }
 hipError_t g_score_rows(const float* logits, int n_rows, int row_offset, int V, const int* row_seq_pos,
                         const int* n_rows_dev, const int32_t* tokens, int T, float* out_logprobs, hipStream_t st) {
+  ProfScope prof_(KID_SCORE_ROWS, st);
   if (n_rows == 0) return hipSuccess;
   k_score_rows<<<n_rows, 256, 0, st>>>(logits, row_offset, V, row_seq_pos, n_rows_dev, tokens, T, out_logprobs);
   return hipGetLastError();
@@ -403,6 +416,7 @@ __global__ void k_advantages(const float* __restrict__ r, int n_groups, int G, f
   for (int i = 0; i < G; ++i) out[(size_t)g * G + i] = (float)(((double)rg[i] - mu) / (sd + 1e-6));
 }
 hipError_t g_advantages(const float* rewards, int S, int G, float* out, hipStream_t st) {
+  ProfScope prof_(KID_MISC, st);
   const int ng = S / G;
   k_advantages<<<(ng + 63) / 64, 64, 0, st>>>(rewards, ng, G, out);
   return hipGetLastError();
@@ -450,6 +464,7 @@ __global__ void __launch_bounds__(1024) k_masked_rows(const uint8_t* __restrict_
 }
 hipError_t g_masked_rows(const uint8_t* mask, int T, int s0, int ns, int* rows, int* src_rows, int* count,
                          hipStream_t st) {
+  ProfScope prof_(KID_MISC, st);
   k_masked_rows<<<1, 1024, 0, st>>>(mask, T, s0, ns, rows, src_rows, count);
   return hipGetLastError();
 }
@@ -460,6 +475,7 @@ __global__ void k_rows_from_positions(const int* positions, int n, int T, int* s
   if (i < n) src_rows[i] = positions[2 * i] * T + positions[2 * i + 1];
 }
 hipError_t g_rows_from_positions(const int* positions, int n, int T, int* src_rows, hipStream_t st) {
+  ProfScope prof_(KID_MISC, st);
   k_rows_from_positions<<<(n + 255) / 256, 256, 0, st>>>(positions, n, T, src_rows);
   return hipGetLastError();
 }
@@ -470,6 +486,7 @@ __global__ void k_last_rows(int* rows, int P, int Lp) {
   if (p < P) rows[p] = p * Lp + Lp - 1;
 }
 hipError_t g_last_rows(int* rows, int P, int Lp, hipStream_t st) {
+  ProfScope prof_(KID_MISC, st);
   k_last_rows<<<(P + 255) / 256, 256, 0, st>>>(rows, P, Lp);
   return hipGetLastError();
 }
@@ -481,6 +498,7 @@ __global__ void k_gather_last_rows(const float* __restrict__ h, float* __restric
   for (int i = threadIdx.x; i < d; i += blockDim.x) out[(size_t)s * d + i] = src[i];
 }
 hipError_t g_gather_last_rows(const float* h, float* out, int S, int G, int Lp, int d, hipStream_t st) {
+  ProfScope prof_(KID_MISC, st);
   k_gather_last_rows<<<S, 256, 0, st>>>(h, out, G, Lp, d);
   return hipGetLastError();
 }
@@ -495,6 +513,7 @@ __global__ void k_gumbel(uint32_t seed_lo, uint32_t seed_hi, uint32_t seq, uint3
 }
 hipError_t g_gumbel(uint32_t seed_lo, uint32_t seed_hi, uint32_t seq, uint32_t step, uint32_t v0, int n, float* out,
                     hipStream_t st) {
+  ProfScope prof_(KID_MISC, st);
   if (n == 0) return hipSuccess;
   k_gumbel<<<(n + 255) / 256, 256, 0, st>>>(seed_lo, seed_hi, seq, step, v0, n, out);
   return hipGetLastError();

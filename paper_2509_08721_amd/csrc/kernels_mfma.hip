@@ -42,6 +42,7 @@ __global__ void k_pack_weight(const bf16* __restrict__ src, int n_rows, int K, u
 }
 hipError_t m_pack_weight(const void* src, int n_rows, int K, void* dst, int dst_tile0, int dst_tile_stride,
                          hipStream_t st) {
+  ProfScope prof_(KID_MISC, st);
   const size_t total = (size_t)(n_rows / 32) * (K / 16) * 64;
   if (total == 0) return hipSuccess;
   k_pack_weight<<<(unsigned)((total + 255) / 256), 256, 0, st>>>((const bf16*)src, n_rows, K, (uint4*)dst, dst_tile0,
@@ -166,6 +167,7 @@ __global__ void __launch_bounds__(256) k_gemm_big(const bf16* __restrict__ X, in
   }
 }
 hipError_t m_gemm_big(const void* X, int ldx, const void* Wp, int M, int N, int K, BigEpi epi, hipStream_t st) {
+  ProfScope prof_(KID_GEMM_BIG, st);
   if (M == 0) return hipSuccess;
   dim3 grid(N / 128, (M + 255) / 256);
   k_gemm_big<<<grid, 256, 0, st>>>((const bf16*)X, ldx, (const uint4*)Wp, M, N, K, epi);
@@ -263,10 +265,15 @@ hipError_t m_lmhead_score(const void* X, const void* Wp, int max_rows, const int
                           hipStream_t st) {
   if (max_rows == 0) return hipSuccess;
   dim3 grid((max_rows + 255) / 256, kScoreSplit);
-  k_lmhead_score<<<grid, 256, 0, st>>>((const bf16*)X, (const uint4*)Wp, max_rows, n_rows_dev, V, K, row_seq_pos, tokens,
-                                       T, partials);
-  hipError_t e = hipGetLastError();
+  hipError_t e;
+  {
+    ProfScope prof_(KID_LMHEAD_SCORE, st);
+    k_lmhead_score<<<grid, 256, 0, st>>>((const bf16*)X, (const uint4*)Wp, max_rows, n_rows_dev, V, K, row_seq_pos,
+                                         tokens, T, partials);
+    e = hipGetLastError();
+  }
   if (e != hipSuccess) return e;
+  ProfScope prof2_(KID_LMHEAD_SCORE_MERGE, st);
   k_lmhead_score_merge<<<(max_rows + 255) / 256, 256, 0, st>>>(partials, max_rows, n_rows_dev, row_seq_pos, T,
                                                                out_logprobs);
   return hipGetLastError();
@@ -443,6 +450,7 @@ static hipError_t skinny_attr_once() {
 }
 
 hipError_t m_gemm_skinny(SkinnyIn in, const void* Wp, int n_rows, int N, int K, SkinnyEpi epi, hipStream_t st) {
+  ProfScope prof_(KID_GEMM_SKINNY, st);
   hipError_t e = skinny_attr_once();
   if (e != hipSuccess) return e;
   const int n_tiles = N / 32;
@@ -552,9 +560,14 @@ hipError_t m_lmhead_sample(SkinnyIn in, const void* Wp, int n_rows, int seq0, in
   int n_wg = kSampleWgs;
   const int n_tiles = V / 32;
   if (n_wg > n_tiles) n_wg = n_tiles;
-  k_lmhead_sample<<<n_wg, 512, kSkinnyLds, st>>>(in, (const uint4*)Wp, n_rows, seq0, V, K, sp, partials);
-  hipError_t e = hipGetLastError();
+  hipError_t e;
+  {
+    ProfScope prof_(KID_LMHEAD_SAMPLE, st);
+    k_lmhead_sample<<<n_wg, 512, kSkinnyLds, st>>>(in, (const uint4*)Wp, n_rows, seq0, V, K, sp, partials);
+    e = hipGetLastError();
+  }
   if (e != hipSuccess) return e;
+  ProfScope prof2_(KID_LMHEAD_SAMPLE_MERGE, st);
   k_lmhead_sample_merge<<<n_rows, 64, 0, st>>>(partials, n_wg, n_rows, seq0, sp);
   return hipGetLastError();
 }
@@ -711,6 +724,7 @@ __global__ void __launch_bounds__(256) k_decode_attention(const float* __restric
 
 hipError_t m_decode_attention(const float* qkv, const float2* rope, RowMap rm, KVCache kv, bf16* out, int out_xp, int S,
                               int n_q_heads, hipStream_t st) {
+  ProfScope prof_(KID_DECODE_ATTN, st);
   const int grid = S * kv.n_kv_heads;
   if (kv.head_dim == 64)
     k_decode_attention<64><<<grid, 256, 0, st>>>(qkv, rope, rm, kv, out, out_xp, n_q_heads);

@@ -67,6 +67,14 @@ def load_library() -> C.CDLL:
     lib.sapo_debug_logits.restype = i32
     lib.sapo_debug_gumbel.argtypes = [u64, u32, u32, u32, i32, vp, vp]
     lib.sapo_debug_gumbel.restype = i32
+    lib.sapo_profile_kernel_count.argtypes = []
+    lib.sapo_profile_kernel_count.restype = i32
+    lib.sapo_profile_kernel_name.argtypes = [i32]
+    lib.sapo_profile_kernel_name.restype = C.c_char_p
+    lib.sapo_profile_start.argtypes = []
+    lib.sapo_profile_start.restype = i32
+    lib.sapo_profile_stop.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64), i32]
+    lib.sapo_profile_stop.restype = i32
     lib.sapo_last_error.argtypes = []
     lib.sapo_last_error.restype = C.c_char_p
     _lib = lib
@@ -76,7 +84,8 @@ def load_library() -> C.CDLL:
 EXPORTED = ["sapo_weights_create", "sapo_weights_destroy", "sapo_weights_uses_mfma",
             "sapo_rollout_workspace_bytes", "sapo_score_workspace_bytes",
             "sapo_debug_logits_workspace_bytes", "sapo_rollout_generate", "sapo_score_logprobs",
-            "sapo_debug_logits", "sapo_debug_gumbel", "sapo_last_error"]
+            "sapo_debug_logits", "sapo_debug_gumbel", "sapo_last_error", "sapo_profile_kernel_count",
+            "sapo_profile_kernel_name", "sapo_profile_start", "sapo_profile_stop"]
 
 
 def _check(rc: int):
@@ -246,3 +255,18 @@ def sapo_debug_gumbel(seed: int, seq: int, step: int, v0: int, n: int, stream=No
     out = torch.empty((n,), dtype=torch.float32, device="cuda")
     _check(load_library().sapo_debug_gumbel(int(seed), seq, step, v0, n, out.data_ptr(), _stream_ptr(stream)))
     return out
+
+
+def sapo_profile_start():
+    """Start bracketing every kernel launch of the library with HIP events."""
+    _check(load_library().sapo_profile_start())
+
+
+def sapo_profile_stop() -> dict:
+    """Stop and return {kernel symbol: (total_ms, launches)} for the kernels that ran."""
+    lib = load_library()
+    n = lib.sapo_profile_kernel_count()
+    ms = (C.c_double * n)()
+    cnt = (C.c_int64 * n)()
+    _check(lib.sapo_profile_stop(ms, cnt, n))
+    return {lib.sapo_profile_kernel_name(i).decode(): (ms[i], int(cnt[i])) for i in range(n) if cnt[i] > 0}
