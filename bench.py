@@ -112,6 +112,9 @@ def main():
     setup_s = time.time() - t0
 
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    side = torch.cuda.Stream()      # a non-default stream: the library replays a captured decode step on it
+    torch.cuda.synchronize()
+    torch.cuda.set_stream(side)
 
     def step(i):
         ev[0].record()

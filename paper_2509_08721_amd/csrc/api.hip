@@ -116,7 +116,25 @@ struct sapo_weights {
   float2* rope;                  // [max_seq][hd / 2] (cos, sin)
   std::vector<LayerWeights> layers;
   std::vector<void*> allocs;
+  // one captured decode step, replayed max_new - 1 times per rollout call; rebuilt when a call
+  // uses other buffers or sizes than the cached one
+  struct DecodeGraph {
+    bool valid = false;
+    const void* out_tokens = nullptr; const void* out_logprobs = nullptr; const void* workspace = nullptr;
+    int P = 0, Lp = 0, G = 0, N = 0;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+  };
+  mutable DecodeGraph dgraph;
 };
+
+static void drop_decode_graph(const sapo_weights* w) {
+  if (!w->dgraph.valid) return;
+  (void)hipDeviceSynchronize();           // replays of the old graph may still be in flight
+  if (w->dgraph.exec) (void)hipGraphExecDestroy(w->dgraph.exec);
+  if (w->dgraph.graph) (void)hipGraphDestroy(w->dgraph.graph);
+  w->dgraph = sapo_weights::DecodeGraph();
+}
 
 static int validate_config(const sapo_model_config* c) {
   if (!c) return fail(SAPO_EINVAL, "config is NULL");
@@ -145,6 +163,7 @@ static bool mfma_eligible(const sapo_model_config* c) {
 
 extern "C" void sapo_weights_destroy(sapo_weights* w) {
   if (!w) return;
+  drop_decode_graph(w);
   for (void* p : w->allocs) (void)hipFree(p);
   delete w;
 }
@@ -241,6 +260,13 @@ extern "C" int sapo_weights_create(const sapo_model_config* cfg, const void* con
   w->cfg = *cfg;
   w->elt = cfg->dtype == SAPO_DTYPE_F32 ? 4 : 2;
   w->mfma = mfma_eligible(cfg);
+  if (w->mfma) {
+    hipError_t e = m_init_attributes();
+    if (e != hipSuccess) {
+      delete w;
+      return fail(SAPO_EHIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(e));
+    }
+  }
   rc = create_impl(w, tensors, (hipStream_t)stream);
   if (rc) {
     sapo_weights_destroy(w);
@@ -383,22 +409,69 @@ static int run_layers_big(const sapo_weights* w, const FwdBufs& b, int M, RowMap
 // MFMA, decode of at most 64 sequences: weight-streaming GEMMs with the norms folded in
 static bool skinny_ok(const sapo_weights* w, int S) { return w->mfma && S <= 64 && w->cfg.d_model <= 896; }
 
-static int run_layers_skinny(const sapo_weights* w, const FwdBufs& b, int S, RowMap rm, const CacheBufs& cb,
-                             hipStream_t st) {
+// Workspace of the 64-token decode path: row sums of squares handed from each residual-producing
+// kernel to the GEMM that normalises, and the split-K scratch + arrival counters.
+struct SkinnyBufs {
+  float* ssq_a;     // feeds the attention-side norm (and the final norm): [d/32][64]
+  float* ssq_b;     // feeds the FFN-side norm: [d/32][64]
+  float* scratch;
+  int* counters;    // [kSkinnyCounters], zero between launches
+};
+constexpr int kSkinnyCounters = 1024;
+
+static int skinny_ksplit(int N, int K) {
+  const int units = N / 32, KS = K / 16;
+  int ks = (200 + units / 2) / units;
+  if (ks > 8) ks = 8;
+  const int ks_min = (KS + 55) / 56;
+  if (ks < ks_min) ks = ks_min;
+  if (ks > KS) ks = KS;
+  const int per = (KS + ks - 1) / ks;
+  return (KS + per - 1) / per;
+}
+
+static size_t skinny_scratch_floats(const sapo_weights* w) {
   const sapo_model_config& c = w->cfg;
   const int d = c.d_model, q = c.n_q_heads * c.head_dim, kv = c.n_kv_heads * c.head_dim, F = c.d_ff;
+  size_t m = 0;
+  const int dims[3][2] = {{q + 2 * kv, d}, {d, q}, {d, F}};
+  for (auto& nk : dims) {
+    const size_t n = (size_t)(nk[0] / 32) * skinny_ksplit(nk[0], nk[1]) * 2048;
+    if (n > m) m = n;
+  }
+  return m;
+}
+
+static void carve_skinny(Arena& A, const sapo_weights* w, SkinnyBufs& sb) {
+  const size_t tiles = w->cfg.d_model / 32;
+  sb.ssq_a = A.take<float>(tiles * 64);
+  sb.ssq_b = A.take<float>(tiles * 64);
+  sb.scratch = A.take<float>(skinny_scratch_floats(w));
+  sb.counters = A.take<int>(kSkinnyCounters);
+}
+
+// On entry b.h holds the residual rows and sb.ssq_a their sums of squares in `parts_a` parts.
+// On exit sb.ssq_a holds d/32 parts for the final norm.
+static int run_layers_skinny(const sapo_weights* w, const FwdBufs& b, const SkinnyBufs& sb, int parts_a, int S,
+                             RowMap rm, const CacheBufs& cb, hipStream_t st) {
+  const sapo_model_config& c = w->cfg;
+  const int d = c.d_model, q = c.n_q_heads * c.head_dim, kv = c.n_kv_heads * c.head_dim, F = c.d_ff;
+  const int nqkv = q + 2 * kv;
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerWeights& lw = w->layers[l];
     const KVCache kvc = layer_cache(w, cb, l);
-    HIP_CK(m_gemm_skinny(SkinnyIn{nullptr, b.h, lw.attn_norm, c.rms_eps}, lw.wqkv, S, q + 2 * kv, d,
-                         SkinnyEpi{SK_STORE_F32, b.qkv, q + 2 * kv, nullptr}, st));
+    HIP_CK(m_gemm_skinny(SkinnyIn{nullptr, b.h, lw.attn_norm, sb.ssq_a, l == 0 ? parts_a : d / 32, c.rms_eps}, lw.wqkv,
+                         S, nqkv, d, SkinnyEpi{SK_STORE_F32, b.qkv, nqkv, nullptr, nullptr, sb.scratch, sb.counters},
+                         skinny_ksplit(nqkv, d), st));
     HIP_CK(m_decode_attention(b.qkv, w->rope, rm, kvc, (bf16*)b.attn, 1, S, c.n_q_heads, st));
-    HIP_CK(m_gemm_skinny(SkinnyIn{(const bf16*)b.attn, nullptr, nullptr, 0.f}, lw.wo, S, d, q,
-                         SkinnyEpi{SK_ADD_F32, b.h, d, nullptr}, st));
-    HIP_CK(m_gemm_skinny(SkinnyIn{nullptr, b.h, lw.ffn_norm, c.rms_eps}, lw.wgu, S, 2 * F, d,
-                         SkinnyEpi{SK_SWIGLU, nullptr, 0, (bf16*)b.act}, st));
-    HIP_CK(m_gemm_skinny(SkinnyIn{(const bf16*)b.act, nullptr, nullptr, 0.f}, lw.wdown, S, d, F,
-                         SkinnyEpi{SK_ADD_F32, b.h, d, nullptr}, st));
+    HIP_CK(m_gemm_skinny(SkinnyIn{(const bf16*)b.attn, nullptr, nullptr, nullptr, 0, 0.f}, lw.wo, S, d, q,
+                         SkinnyEpi{SK_ADD_F32, b.h, d, nullptr, sb.ssq_b, sb.scratch, sb.counters}, skinny_ksplit(d, q),
+                         st));
+    HIP_CK(m_gemm_skinny(SkinnyIn{nullptr, b.h, lw.ffn_norm, sb.ssq_b, d / 32, c.rms_eps}, lw.wgu, S, 2 * F, d,
+                         SkinnyEpi{SK_SWIGLU, nullptr, 0, (bf16*)b.act, nullptr, nullptr, nullptr}, 1, st));
+    HIP_CK(m_gemm_skinny(SkinnyIn{(const bf16*)b.act, nullptr, nullptr, nullptr, 0, 0.f}, lw.wdown, S, d, F,
+                         SkinnyEpi{SK_ADD_F32, b.h, d, nullptr, sb.ssq_a, sb.scratch, sb.counters}, skinny_ksplit(d, F),
+                         st));
   }
   return SAPO_OK;
 }
@@ -406,7 +479,6 @@ static int run_layers_skinny(const sapo_weights* w, const FwdBufs& b, int S, Row
 static int run_layers(const sapo_weights* w, const FwdBufs& b, int M, RowMap rm, const CacheBufs& cb, int max_ctx,
                       hipStream_t st) {
   if (!w->mfma) return run_layers_generic(w, b, M, rm, cb, max_ctx, st);
-  if (rm.decode && skinny_ok(w, M)) return run_layers_skinny(w, b, M, rm, cb, st);
   return run_layers_big(w, b, M, rm, cb, max_ctx, st);
 }
 
@@ -425,6 +497,7 @@ struct RolloutPlan {
   void* x_last;     // [max(P, S), d] final-norm output (T)
   float* logits;    // [max(P, S), V] (paths that materialise logits)
   float* partials;  // fused sampler partials
+  SkinnyBufs sk;    // 64-token decode path
   size_t bytes;
 };
 
@@ -447,6 +520,7 @@ static void plan_rollout(const sapo_weights* w, int P, int Lp, int G, int N, cha
   const bool fused = skinny_ok(w, pl.S);
   pl.logits = fused ? nullptr : A.take<float>(R * c.vocab);
   pl.partials = fused ? A.take<float>(m_lmhead_sample_partial_floats()) : nullptr;
+  if (fused) carve_skinny(A, w, pl.sk);
   pl.bytes = (A.off + 255) & ~(size_t)255;
 }
 
@@ -467,11 +541,13 @@ extern "C" size_t sapo_rollout_workspace_bytes(const sapo_weights* w, int P, int
 
 // Sample the token of the current step for all S sequences from the residual rows in `h`
 // (row s = sequence s), writing out_tokens[:, step] and out_logprobs[:, step].
-static int sample_step(const sapo_weights* w, const RolloutPlan& pl, const float* h, SampleParams sp, hipStream_t st) {
+static int sample_step(const sapo_weights* w, const RolloutPlan& pl, const float* h, int ssq_parts, SampleParams sp,
+                       hipStream_t st) {
   const sapo_model_config& c = w->cfg;
   const int S = pl.S, d = c.d_model, V = c.vocab;
   if (skinny_ok(w, S)) {
-    HIP_CK(m_lmhead_sample(SkinnyIn{nullptr, h, w->final_norm, c.rms_eps}, w->lm_head, S, 0, V, d, sp, pl.partials, st));
+    HIP_CK(m_lmhead_sample(SkinnyIn{nullptr, h, w->final_norm, pl.sk.ssq_a, ssq_parts, c.rms_eps}, w->lm_head, S, 0, V, d,
+                           sp, pl.partials, st));
     return SAPO_OK;
   }
   HIP_CK(g_rmsnorm(c.dtype, h, w->final_norm, c.rms_eps, pl.x_last, S, d, nullptr, st));
@@ -497,6 +573,7 @@ extern "C" int sapo_rollout_generate(const sapo_weights* w, const int32_t* promp
   hipStream_t st = (hipStream_t)stream;
   const sapo_model_config& c = w->cfg;
   const int dt = c.dtype, d = c.d_model, S = pl.S;
+  const bool skinny = skinny_ok(w, S);
 
   SampleParams sp;
   sp.temperature = temperature;
@@ -504,10 +581,19 @@ extern "C" int sapo_rollout_generate(const sapo_weights* w, const int32_t* promp
   sp.seed_hi = (uint32_t)(seed >> 32);
   sp.max_new = max_new;
   sp.step = pl.step;
+  sp.dyn = (const uint32_t*)(pl.step + 1);
   sp.out_tokens = out_tokens;
   sp.out_logprobs = out_logprobs;
 
   HIP_CK(g_fill_i32(pl.step, 0, 1, st));
+  {
+    float tf = temperature;
+    int tbits;
+    memcpy(&tbits, &tf, 4);
+    HIP_CK(g_fill_i32(pl.step + 1, (int)sp.seed_lo, 1, st));
+    HIP_CK(g_fill_i32(pl.step + 2, (int)sp.seed_hi, 1, st));
+    HIP_CK(g_fill_i32(pl.step + 3, tbits, 1, st));
+  }
   HIP_CK(g_page_table(pl.cache.page_table, S, pl.pages_per_seq, G, pl.full_prompt_pages, P, st));
   if ((rc = clear_cache(pl.cache, c.n_layers, st))) return rc;
 
@@ -522,16 +608,62 @@ extern "C" int sapo_rollout_generate(const sapo_weights* w, const int32_t* promp
       for (int l = 0; l < c.n_layers; ++l)
         HIP_CK(g_copy_partial_page(dt, layer_cache(w, pl.cache, l), P, G, pl.full_prompt_pages, st));
     HIP_CK(g_gather_last_rows(pl.fwd.h, pl.h_last, S, G, Lp, d, st));
-    if ((rc = sample_step(w, pl, pl.h_last, sp, st))) return rc;
+    if (skinny) {
+      HIP_CK(g_fill_i32(pl.sk.counters, 0, kSkinnyCounters, st));
+      HIP_CK(m_row_ssq(pl.h_last, pl.sk.ssq_a, S, d, st));
+    }
+    if ((rc = sample_step(w, pl, pl.h_last, 1, sp, st))) return rc;
   }
-  // decode: token t-1 of every sequence goes through the layers, token t is sampled
+  // decode: token t-1 of every sequence goes through the layers, token t is sampled.  Everything
+  // that changes from step to step is read from device memory (*step), so one step is captured
+  // into a graph and replayed.
   RowMap rm{1, 0, 1, Lp, pl.step};
-  for (int t = 1; t < max_new; ++t) {
+  auto enqueue_step = [&]() -> int {
+    int rc2;
     HIP_CK(g_incr(pl.step, st));
-    HIP_CK(g_embed(dt, out_tokens, max_new, pl.step, w->embed, pl.fwd.h, S, d, st));
-    if ((rc = run_layers(w, pl.fwd, S, rm, pl.cache, Lp + max_new, st))) return rc;
-    if ((rc = sample_step(w, pl, pl.fwd.h, sp, st))) return rc;
+    if (skinny) {
+      HIP_CK(m_embed_ssq(out_tokens, max_new, pl.step, w->embed, pl.fwd.h, pl.sk.ssq_a, S, d, st));
+      if ((rc2 = run_layers_skinny(w, pl.fwd, pl.sk, 1, S, rm, pl.cache, st))) return rc2;
+      if ((rc2 = sample_step(w, pl, pl.fwd.h, d / 32, sp, st))) return rc2;
+    } else {
+      HIP_CK(g_embed(dt, out_tokens, max_new, pl.step, w->embed, pl.fwd.h, S, d, st));
+      if ((rc2 = run_layers(w, pl.fwd, S, rm, pl.cache, Lp + max_new, st))) return rc2;
+      if ((rc2 = sample_step(w, pl, pl.fwd.h, 0, sp, st))) return rc2;
+    }
+    return SAPO_OK;
+  };
+  const char* no_graph = getenv("SAPO_NO_GRAPH");
+  const bool use_graph = st != nullptr && !g_prof_on && max_new > 2 && !(no_graph && no_graph[0] == '1');
+  if (!use_graph) {
+    for (int t = 1; t < max_new; ++t)
+      if ((rc = enqueue_step())) return rc;
+    return SAPO_OK;
   }
+  sapo_weights::DecodeGraph& dg = w->dgraph;
+  if (!(dg.valid && dg.out_tokens == out_tokens && dg.out_logprobs == out_logprobs && dg.workspace == workspace &&
+        dg.P == P && dg.Lp == Lp && dg.G == G && dg.N == max_new)) {
+    drop_decode_graph(w);
+    HIP_CK(hipStreamBeginCapture(st, hipStreamCaptureModeRelaxed));
+    rc = enqueue_step();
+    hipGraph_t graph = nullptr;
+    const hipError_t e = hipStreamEndCapture(st, &graph);
+    if (rc) {
+      if (graph) (void)hipGraphDestroy(graph);
+      return rc;
+    }
+    if (e != hipSuccess) return fail(SAPO_EHIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
+    hipGraphExec_t exec = nullptr;
+    const hipError_t e2 = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    if (e2 != hipSuccess) {
+      (void)hipGraphDestroy(graph);
+      return fail(SAPO_EHIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e2));
+    }
+    dg.valid = true;
+    dg.out_tokens = out_tokens; dg.out_logprobs = out_logprobs; dg.workspace = workspace;
+    dg.P = P; dg.Lp = Lp; dg.G = G; dg.N = max_new;
+    dg.graph = graph; dg.exec = exec;
+  }
+  for (int t = 1; t < max_new; ++t) HIP_CK(hipGraphLaunch(dg.exec, st));
   return SAPO_OK;
 }
 

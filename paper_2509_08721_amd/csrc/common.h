@@ -131,6 +131,8 @@ struct SampleParams {
   uint32_t seed_lo, seed_hi;
   int max_new;            // row stride of out_tokens / out_logprobs
   const int* step;        // device: index of the token being sampled (0-based)
+  const uint32_t* dyn;    // device, optional: {seed_lo, seed_hi, temperature bits} overriding the fields above
+                          // (lets one captured graph serve calls that differ only in seed / temperature)
   int32_t* out_tokens;    // [S, max_new]
   float* out_logprobs;    // [S, max_new]
 };
@@ -150,6 +152,16 @@ struct ProfScope {
   ProfScope(int k, hipStream_t s) : kid(k), st(s) { if (g_prof_on) prof_mark(kid, st, true); }
   ~ProfScope() { if (g_prof_on) prof_mark(kid, st, false); }
 };
+
+__device__ __forceinline__ void resolve_sample_params(SampleParams& sp) {
+  if (sp.dyn) {
+    sp.seed_lo = sp.dyn[0];
+    sp.seed_hi = sp.dyn[1];
+    sp.temperature = __uint_as_float(sp.dyn[2]);
+  }
+}
+
+hipError_t m_init_attributes();
 
 // generic (shape-agnostic) kernels --------------------------------------------------------
 hipError_t g_embed(int dtype, const int32_t* tokens, int tok_stride, const int* step, const void* embed,
@@ -218,18 +230,27 @@ struct SkinnyEpi {
   float* out_f32;      // STORE_F32: [64, ldc];  ADD_F32: h [64, ldc]
   int ldc;
   bf16* out_xp;        // SWIGLU: act, X-packed over K = F
+  float* ssq_out;      // STORE/ADD: per-tile sums of squares of the written rows [N/32][64] (or NULL)
+  float* scratch;      // split-K partial tiles [N/32][ksplit][2048]
+  int* counters;       // split-K arrival counters [N/32], zero between launches
 };
 enum { SK_STORE_F32 = 0, SK_ADD_F32 = 1, SK_SWIGLU = 2 };
 
 // X source of a skinny GEMM: either an X-packed bf16 buffer, or the fp32 residual stream
-// [64, K] that the kernel RMS-normalises itself (gain, eps) while staging it.
+// [64, K], RMS-normalised while it is staged: scale(tok) = rsqrt(sum_p ssq[p][tok] / K + eps).
 struct SkinnyIn {
   const bf16* xp;
   const float* h;
   const float* gain;
+  const float* ssq;    // [ssq_parts][64]
+  int ssq_parts;
   float eps;
 };
-hipError_t m_gemm_skinny(SkinnyIn in, const void* Wp, int n_rows, int N, int K, SkinnyEpi epi, hipStream_t st);
+hipError_t m_gemm_skinny(SkinnyIn in, const void* Wp, int n_rows, int N, int K, SkinnyEpi epi, int ksplit,
+                         hipStream_t st);
+hipError_t m_embed_ssq(const int32_t* tokens, int tok_stride, const int* step, const void* embed, float* h, float* ssq,
+                       int M, int d, hipStream_t st);
+hipError_t m_row_ssq(const float* h, float* ssq, int M, int d, hipStream_t st);
 hipError_t m_lmhead_sample(SkinnyIn in, const void* Wp, int n_rows, int seq0, int V, int K, SampleParams sp,
                            float* partials, hipStream_t st);
 size_t m_lmhead_sample_partial_floats();

@@ -331,6 +331,7 @@ __device__ __forceinline__ void block_merge_lse(LseAcc& a, float* sm_m, float* s
 
 // Sample one token for sequence s = row * G + sibling from logits[row, :].
 __global__ void __launch_bounds__(256) k_sample_rows(const float* __restrict__ logits, int G, int V, SampleParams sp) {
+  resolve_sample_params(sp);
   const int row = blockIdx.x / G, s = blockIdx.x;   // s = row * G + sibling
   const float* z = logits + (size_t)row * V;
   const int step = *sp.step;

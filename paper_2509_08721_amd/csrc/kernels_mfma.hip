@@ -10,8 +10,10 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 union Frag {
   uint4 u;
+  u32x4 n;
   bf16x8 v;
 };
 
@@ -281,94 +283,121 @@ hipError_t m_lmhead_score(const void* X, const void* Wp, int max_rows, const int
 
 // =======================================================================================
 // Skinny GEMM (decode): up to 64 tokens, weights streamed once from HBM.
-// 512 threads = 8 waves.  The workgroup owns whole 32-feature tiles over the full K; the 8 waves
-// split the k steps (wave w takes steps w, w+8, ...), and their partial 32x64 tiles are summed
-// through LDS in a fixed order (waves 4..7 into 0..3, then 0..3 by all threads), so results do not
-// depend on scheduling.  X (64 tokens x K) sits in LDS in fragment order, up to kChunkSteps k steps
-// at a time; it comes either from an X-packed bf16 buffer or from the fp32 residual stream, which
-// the kernel RMS-normalises while staging.
-// After the reduction thread t owns, for tile ti = t / 256, token ti*32 + lane%32 (lane = t % 64) the
-// four features (lane/32)*4 + 8 i + (0..3) with i = (t / 64) % 4.
+// 512 threads = 8 waves.  A workgroup owns one 32-feature tile (a gate/up tile pair for SwiGLU)
+// over a k range of at most kChunkSteps steps; the 8 waves split the k steps (wave w takes steps
+// w, w+8, ...) and their partial 32x64 tiles are summed through LDS in a fixed order (waves 4..7
+// into 0..3, then 0..3 by all threads).  When K is split over several workgroups, each writes its
+// partial tile to scratch and the last one to arrive (atomic counter per tile) sums all partials in
+// k order, so results never depend on scheduling.  Weight fragments are requested before X is
+// staged: they do not depend on it.
+// X (64 tokens x k range) sits in LDS in fragment order; it comes from an X-packed bf16 buffer, or
+// from the fp32 residual stream, RMS-normalised on the way in with the row sums of squares that the
+// producing kernel left behind (ssq[part][token], summed here).
+// After the reduction thread t owns, for token (t/256)*32 + lane%32 (lane = t % 64), the four
+// features (lane/32)*4 + 8 i + (0..3) of the tile, i = (t / 64) % 4.
 // ---------------------------------------------------------------------------------------
-constexpr int kChunkSteps = 56;                                  // 896 k per chunk
+constexpr int kChunkSteps = 56;                                  // 896 k per workgroup
 constexpr int kSkinnyXBytes = kChunkSteps * 2 * 64 * 16;         // 114688
 constexpr int kSkinnyPartBytes = 4 * 32 * 64 * 4;                // 32768
 constexpr int kSkinnyLds = kSkinnyXBytes + kSkinnyPartBytes;
 
-// Stage k steps [ks0, ks0 + nks) of X into LDS.
-__device__ __forceinline__ void skinny_stage_x(const SkinnyIn& in, int n_rows, int K, int ks0, int nks, uint4* xs) {
+__device__ __forceinline__ void skinny_load_w(const uint4* __restrict__ Wp, int KS, int tile, int ks_begin, int ks_end,
+                                              Frag (&w)[7]) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const uint4* wb = Wp + (size_t)tile * KS * 64 + lane;
+#pragma unroll
+  for (int i = 0; i < 7; ++i) {
+    const int ks = ks_begin + wave + 8 * i;
+    if (ks < ks_end) w[i].n = __builtin_nontemporal_load((const u32x4*)(wb + (size_t)ks * 64));
+  }
+}
+
+// Stage k steps [ks_begin, ks_end) of X into LDS (fragment order, local step index).
+// `part` is used as scratch for the per-token scales in h mode.
+__device__ __forceinline__ void skinny_stage_x(const SkinnyIn& in, int n_rows, int K, int ks_begin, int ks_end,
+                                               uint4* xs, float* part) {
   const int tid = threadIdx.x;
+  const int nks = ks_end - ks_begin;
   if (in.xp) {
-    const uint4* src = (const uint4*)in.xp + (size_t)ks0 * 128;
-    for (int i = tid; i < nks * 128; i += 512) xs[i] = src[i];
+    // contiguous copy, 8 loads in flight per thread
+    const uint4* src = (const uint4*)in.xp + (size_t)ks_begin * 128;
+    const int total = nks * 128;
+    for (int base = 0; base < total; base += 512 * 8) {
+      uint4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = base + u * 512 + tid;
+        if (i < total) v[u] = src[i];
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = base + u * 512 + tid;
+        if (i < total) xs[i] = v[u];
+      }
+    }
   } else {
-    // fp32 residual rows -> RMSNorm -> bf16; one wave per row, 8 rows per wave (requires ks0 == 0, nks*16 == K)
-    const int wave = tid >> 6, lane = tid & 63;
+    float* scale = part;
+    if (tid < 64) {
+      float s = 0.f;
+      if (tid < n_rows)
+        for (int p = 0; p < in.ssq_parts; ++p) s += in.ssq[(size_t)p * 64 + tid];
+      scale[tid] = (tid < n_rows) ? 1.0f / sqrtf(s / (float)K + in.eps) : 0.f;
+    }
+    __syncthreads();
+    const int k0 = ks_begin * 16, nk4 = nks * 4;      // float4 groups per row in this range
+    const float inv_nk4 = 1.0f / (float)nk4;
+    const int total = 64 * nk4;
     bf16* xb = (bf16*)xs;
-    for (int r = wave; r < 64; r += 8) {
-      if (r < n_rows) {
-        const float* row = in.h + (size_t)r * K;
-        float ss = 0.f;
-        for (int k = lane * 2; k < K; k += 128) {
-          const float2 v = *(const float2*)(row + k);
-          ss += v.x * v.x + v.y * v.y;
-        }
-        ss = wave_reduce_sum(ss);
-        const float scale = 1.0f / sqrtf(ss / (float)K + in.eps);
-        for (int k = lane * 2; k < K; k += 128) {
-          const float2 v = *(const float2*)(row + k);
-          const float2 g = *(const float2*)(in.gain + k);
-          const size_t o = xpack_index(r, k);
-          xb[o] = (bf16)(v.x * scale * g.x);
-          xb[o + 1] = (bf16)(v.y * scale * g.y);
-        }
-      } else {
-        for (int k = lane * 2; k < K; k += 128) {
-          const size_t o = xpack_index(r, k);
-          xb[o] = (bf16)0.f;
-          xb[o + 1] = (bf16)0.f;
+    for (int base = 0; base < total; base += 512 * 8) {
+      float4 v[8], g[8];
+      int tk[8], kk[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = base + u * 512 + tid;
+        tk[u] = (int)(((float)i + 0.5f) * inv_nk4);
+        kk[u] = (i - tk[u] * nk4) * 4;
+        if (i < total && tk[u] < n_rows) {
+          v[u] = *(const float4*)(in.h + (size_t)tk[u] * K + k0 + kk[u]);
+          g[u] = *(const float4*)(in.gain + k0 + kk[u]);
+        } else {
+          v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+          g[u] = v[u];
         }
       }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = base + u * 512 + tid;
+        if (i < total) {
+          const float sc = scale[tk[u]];
+          bf16x4 o;
+          o[0] = (bf16)(v[u].x * sc * g[u].x); o[1] = (bf16)(v[u].y * sc * g[u].y);
+          o[2] = (bf16)(v[u].z * sc * g[u].z); o[3] = (bf16)(v[u].w * sc * g[u].w);
+          *(bf16x4*)(xb + xpack_index(tk[u], kk[u])) = o;
+        }
+      }
+    }
+    __syncthreads();   // scale[] lives in `part`, which the reduction reuses
+  }
+}
+
+__device__ __forceinline__ void skinny_mma(const Frag (&w)[7], int nks, const uint4* xs, f32x16& acc0, f32x16& acc1) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll
+  for (int i = 0; i < 7; ++i) {
+    const int ks = wave + 8 * i;     // local step
+    if (ks < nks) {
+      Frag x0, x1;
+      x0.u = xs[(ks * 2 + 0) * 64 + lane];
+      x1.u = xs[(ks * 2 + 1) * 64 + lane];
+      acc0 = mfma32(w[i], x0, acc0);
+      acc1 = mfma32(w[i], x1, acc1);
     }
   }
 }
 
-// One 32-feature tile: every wave accumulates its k steps, then the cross-wave reduction.
-// On return thread t holds its four reduced values in out[4].
-__device__ __forceinline__ void skinny_tile(const SkinnyIn& in, const uint4* __restrict__ Wp, int n_rows, int K, int tile,
-                                            uint4* xs, float* part, bool x_resident, float (&out)[4]) {
+// Cross-wave reduction of the 8 partial tiles; thread t gets its four values in out[4].
+__device__ __forceinline__ void skinny_reduce(f32x16& acc0, f32x16& acc1, float* part, float (&out)[4]) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int KS = K >> 4;
-  f32x16 acc0, acc1;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) { acc0[v] = 0.f; acc1[v] = 0.f; }
-  const uint4* wb = Wp + (size_t)tile * KS * 64 + lane;
-  for (int ks0 = 0; ks0 < KS; ks0 += kChunkSteps) {
-    const int nks = min(kChunkSteps, KS - ks0);
-    if (!x_resident) {
-      __syncthreads();
-      skinny_stage_x(in, n_rows, K, ks0, nks, xs);
-      __syncthreads();
-    }
-    Frag w[7];
-#pragma unroll
-    for (int i = 0; i < 7; ++i) {
-      const int ks = wave + 8 * i;
-      if (ks < nks) w[i].u = wb[(size_t)(ks0 + ks) * 64];
-    }
-#pragma unroll
-    for (int i = 0; i < 7; ++i) {
-      const int ks = wave + 8 * i;
-      if (ks < nks) {
-        Frag x0, x1;
-        x0.u = xs[(ks * 2 + 0) * 64 + lane];
-        x1.u = xs[(ks * 2 + 1) * 64 + lane];
-        acc0 = mfma32(w[i], x0, acc0);
-        acc1 = mfma32(w[i], x1, acc1);
-      }
-    }
-  }
-  // cross-wave reduction: part[w][v][lane]
   __syncthreads();
   if (wave >= 4) {
     float* p = part + (size_t)(wave - 4) * 2048 + lane;
@@ -388,7 +417,7 @@ __device__ __forceinline__ void skinny_tile(const SkinnyIn& in, const uint4* __r
     for (int v = 0; v < 16; ++v) { p[v * 64] = acc0[v]; p[(16 + v) * 64] = acc1[v]; }
   }
   __syncthreads();
-  const int vq = tid >> 6;   // 0..7 -> v = vq*4 + j
+  const int vq = tid >> 6;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const float* p = part + (size_t)(vq * 4 + j) * 64 + lane;
@@ -397,74 +426,118 @@ __device__ __forceinline__ void skinny_tile(const SkinnyIn& in, const uint4* __r
 }
 
 __global__ void __launch_bounds__(512) k_gemm_skinny(SkinnyIn in, const uint4* __restrict__ Wp, int n_rows, int N, int K,
-                                                     SkinnyEpi ep, int tiles_per_wg) {
+                                                     SkinnyEpi ep, int ksplit) {
   extern __shared__ uint4 dyn_smem[];
+  __shared__ int s_last;
   uint4* xs = dyn_smem;
   float* part = (float*)((char*)dyn_smem + kSkinnyXBytes);
   const int tid = threadIdx.x, lane = tid & 63, vq = tid >> 6;
   const int KS = K >> 4;
-  const bool resident = KS <= kChunkSteps;
-  if (resident) {
-    skinny_stage_x(in, n_rows, K, 0, KS, xs);
-    __syncthreads();
-  }
+  const int unit = blockIdx.x / ksplit, c = blockIdx.x % ksplit;
+  const int per = (KS + ksplit - 1) / ksplit;
+  const int ks_begin = c * per, ks_end = min(KS, ks_begin + per);
+  const int nks = ks_end - ks_begin;
+  const int nt = (ep.mode == SK_SWIGLU) ? 2 : 1;
+  const int tile0 = unit * nt;
+
+  Frag w0[7], w1[7];
+  skinny_load_w(Wp, KS, tile0, ks_begin, ks_end, w0);
+  if (nt == 2) skinny_load_w(Wp, KS, tile0 + 1, ks_begin, ks_end, w1);
+  skinny_stage_x(in, n_rows, K, ks_begin, ks_end, xs, part);
+  __syncthreads();
+
   const int tok = (vq >> 2) * 32 + (lane & 31);
   const int fsub = (lane >> 5) * 4 + 8 * (vq & 3);
-  const int n_tiles = N >> 5;
-  const int t_begin = blockIdx.x * tiles_per_wg, t_end = min(n_tiles, t_begin + tiles_per_wg);
-  float gate[4];
-  for (int tile = t_begin; tile < t_end; ++tile) {
-    float r[4];
-    skinny_tile(in, Wp, n_rows, K, tile, xs, part, resident, r);
-    if (ep.mode == SK_SWIGLU) {
-      if ((tile & 1) == 0) {
+  float r[4], gate[4];
+  for (int t = 0; t < nt; ++t) {
+    f32x16 acc0, acc1;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) gate[j] = r[j];
-      } else {
-        const int fidx = (tile >> 1) * 32 + fsub;
-        bf16x4 o;
+    for (int v = 0; v < 16; ++v) { acc0[v] = 0.f; acc1[v] = 0.f; }
+    skinny_mma(t == 0 ? w0 : w1, nks, xs, acc0, acc1);
+    skinny_reduce(acc0, acc1, part, r);
+    if (t == 0 && nt == 2) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) o[j] = (tok < n_rows) ? (bf16)(silu_f(gate[j]) * r[j]) : (bf16)0.f;
-        *(bf16x4*)(ep.out_xp + xpack_index(tok, fidx)) = o;
-      }
-    } else if (tok < n_rows) {
-      float4* p = (float4*)(ep.out_f32 + (size_t)tok * ep.ldc + tile * 32 + fsub);
-      float4 v = make_float4(r[0], r[1], r[2], r[3]);
-      if (ep.mode == SK_ADD_F32) {
-        const float4 o = *p;
-        v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
-      }
-      *p = v;
+      for (int j = 0; j < 4; ++j) gate[j] = r[j];
+    }
+  }
+  const int tile = tile0;
+  if (ksplit > 1) {
+    // split-K fix-up: publish the partial, the last workgroup of the tile sums all of them in k order
+    float* my = ep.scratch + ((size_t)tile * ksplit + c) * 2048 + tid * 4;
+    *(float4*)my = make_float4(r[0], r[1], r[2], r[3]);
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+      const int old = atomicAdd(ep.counters + tile, 1);
+      s_last = (old == ksplit - 1) ? 1 : 0;
+      if (s_last) ep.counters[tile] = 0;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    // the fence above made the other workgroups' partials visible (L1 invalidated): plain loads
+    float4 pv[8];
+#pragma unroll
+    for (int cc = 0; cc < 8; ++cc)
+      pv[cc] = (cc < ksplit) ? *(const float4*)(ep.scratch + ((size_t)tile * ksplit + cc) * 2048 + tid * 4)
+                             : make_float4(0.f, 0.f, 0.f, 0.f);
+    r[0] = r[1] = r[2] = r[3] = 0.f;
+#pragma unroll
+    for (int cc = 0; cc < 8; ++cc) { r[0] += pv[cc].x; r[1] += pv[cc].y; r[2] += pv[cc].z; r[3] += pv[cc].w; }
+  }
+  if (ep.mode == SK_SWIGLU) {
+    const int fidx = (tile >> 1) * 32 + fsub;
+    bf16x4 o;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) o[j] = (tok < n_rows) ? (bf16)(silu_f(gate[j]) * r[j]) : (bf16)0.f;
+    *(bf16x4*)(ep.out_xp + xpack_index(tok, fidx)) = o;
+    return;
+  }
+  float ss = 0.f;
+  if (tok < n_rows) {
+    float4* p = (float4*)(ep.out_f32 + (size_t)tok * ep.ldc + tile * 32 + fsub);
+    float4 v = make_float4(r[0], r[1], r[2], r[3]);
+    if (ep.mode == SK_ADD_F32) {
+      const float4 o = *p;
+      v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+    }
+    *p = v;
+    ss = v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  if (ep.ssq_out) {
+    // sum of squares of the tile's 32 features per token: 8 threads per token, fixed order
+    __syncthreads();
+    part[tid] = ss;
+    __syncthreads();
+    if (tid < 64) {
+      const int ti = tid >> 5, l31 = tid & 31;
+      float s = 0.f;
+      for (int q = 0; q < 4; ++q)
+        for (int hf = 0; hf < 2; ++hf) s += part[(ti * 4 + q) * 64 + hf * 32 + l31];
+      ep.ssq_out[(size_t)tile * 64 + tid] = s;
     }
   }
 }
 
-static hipError_t skinny_attr_once() {
-  static bool done = false;
-  static hipError_t err = hipSuccess;
-  if (!done) {
-    err = hipFuncSetAttribute((const void*)k_gemm_skinny, hipFuncAttributeMaxDynamicSharedMemorySize, kSkinnyLds);
-    done = true;
-  }
-  return err;
-}
-
-hipError_t m_gemm_skinny(SkinnyIn in, const void* Wp, int n_rows, int N, int K, SkinnyEpi epi, hipStream_t st) {
+hipError_t m_gemm_skinny(SkinnyIn in, const void* Wp, int n_rows, int N, int K, SkinnyEpi epi, int ksplit,
+                         hipStream_t st) {
   ProfScope prof_(KID_GEMM_SKINNY, st);
-  hipError_t e = skinny_attr_once();
-  if (e != hipSuccess) return e;
+  const int KS = K / 16;
+  if (ksplit < 1 || (KS + ksplit - 1) / ksplit > kChunkSteps || (ksplit - 1) * ((KS + ksplit - 1) / ksplit) >= KS ||
+      (ksplit > 1 && (epi.mode == SK_SWIGLU || !epi.scratch || !epi.counters)))
+    return hipErrorInvalidValue;
   const int n_tiles = N / 32;
-  int tpw = (epi.mode == SK_SWIGLU) ? 2 : 1;
-  const int grid = (n_tiles + tpw - 1) / tpw;
-  k_gemm_skinny<<<grid, 512, kSkinnyLds, st>>>(in, (const uint4*)Wp, n_rows, N, K, epi, tpw);
+  const int units = (epi.mode == SK_SWIGLU) ? n_tiles / 2 : n_tiles;
+  k_gemm_skinny<<<units * ksplit, 512, kSkinnyLds, st>>>(in, (const uint4*)Wp, n_rows, N, K, epi, ksplit);
   return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------
 // LM head for decode: logits tile -> online log-sum-exp + Gumbel-max, logits never stored.
-// Same skinny tile engine; each workgroup walks a contiguous range of vocabulary tiles keeping, per
-// thread, the running (max, sum exp) and best perturbed score of its token; per-workgroup results
-// go to `partials` [n_wg][64][5] and a second kernel merges them in a fixed order.
+// Same skinny tile engine over the full K; each workgroup walks a contiguous range of vocabulary
+// tiles (next tile's weights in flight while the current one is reduced) keeping, per thread, the
+// running (max, sum exp) and best perturbed score of its token; per-workgroup results go to
+// `partials` [n_wg][64][5] and a second kernel merges them in a fixed order.
 // Row r of X is sequence seq0 + r.
 // ---------------------------------------------------------------------------------------
 constexpr int kSampleWgs = 256;
@@ -477,23 +550,28 @@ __global__ void __launch_bounds__(512) k_lmhead_sample(SkinnyIn in, const uint4*
   float* part = (float*)((char*)dyn_smem + kSkinnyXBytes);
   const int tid = threadIdx.x, lane = tid & 63, vq = tid >> 6;
   const int KS = K >> 4;
-  const bool resident = KS <= kChunkSteps;
-  if (resident) {
-    skinny_stage_x(in, n_rows, K, 0, KS, xs);
-    __syncthreads();
-  }
-  const int tok = (vq >> 2) * 32 + (lane & 31);
-  const int fsub = (lane >> 5) * 4 + 8 * (vq & 3);
   const int n_tiles = V >> 5;
   const int per = (n_tiles + gridDim.x - 1) / gridDim.x;
   const int t_begin = blockIdx.x * per, t_end = min(n_tiles, t_begin + per);
+  Frag wa[7], wb[7];
+  if (t_begin < t_end) skinny_load_w(Wp, KS, t_begin, 0, KS, wa);
+  skinny_stage_x(in, n_rows, K, 0, KS, xs, part);
+  __syncthreads();
+  const int tok = (vq >> 2) * 32 + (lane & 31);
+  const int fsub = (lane >> 5) * 4 + 8 * (vq & 3);
+  resolve_sample_params(sp);
   const int step = *sp.step;
   const bool noisy = sp.temperature != 0.f;
   LseAcc lse; lse.init();
   BestAcc best; best.init();
   for (int tile = t_begin; tile < t_end; ++tile) {
+    if (tile + 1 < t_end) skinny_load_w(Wp, KS, tile + 1, 0, KS, wb);
+    f32x16 acc0, acc1;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { acc0[v] = 0.f; acc1[v] = 0.f; }
+    skinny_mma(wa, KS, xs, acc0, acc1);
     float r[4];
-    skinny_tile(in, Wp, n_rows, K, tile, xs, part, resident, r);
+    skinny_reduce(acc0, acc1, part, r);
     const int v0 = tile * 32 + fsub;
     float g[4] = {0.f, 0.f, 0.f, 0.f};
     if (noisy) gumbel4(sp.seed_lo, sp.seed_hi, (uint32_t)(seq0 + tok), (uint32_t)step, (uint32_t)(v0 >> 2), g);
@@ -503,6 +581,8 @@ __global__ void __launch_bounds__(512) k_lmhead_sample(SkinnyIn in, const uint4*
       const float y = noisy ? r[j] / sp.temperature + g[j] : r[j];
       best.add(y, r[j], v0 + j);
     }
+#pragma unroll
+    for (int i = 0; i < 7; ++i) wa[i] = wb[i];
   }
   // combine the 8 threads that share a token (fixed order), one thread per token writes
   __syncthreads();
@@ -551,12 +631,7 @@ __global__ void k_lmhead_sample_merge(const float* __restrict__ partials, int n_
 
 hipError_t m_lmhead_sample(SkinnyIn in, const void* Wp, int n_rows, int seq0, int V, int K, SampleParams sp,
                            float* partials, hipStream_t st) {
-  static bool done = false;
-  if (!done) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_lmhead_sample, hipFuncAttributeMaxDynamicSharedMemorySize, kSkinnyLds);
-    if (e != hipSuccess) return e;
-    done = true;
-  }
+  if (K / 16 > kChunkSteps) return hipErrorInvalidValue;
   int n_wg = kSampleWgs;
   const int n_tiles = V / 32;
   if (n_wg > n_tiles) n_wg = n_tiles;
@@ -569,6 +644,57 @@ hipError_t m_lmhead_sample(SkinnyIn in, const void* Wp, int n_rows, int seq0, in
   if (e != hipSuccess) return e;
   ProfScope prof2_(KID_LMHEAD_SAMPLE_MERGE, st);
   k_lmhead_sample_merge<<<n_rows, 64, 0, st>>>(partials, n_wg, n_rows, seq0, sp);
+  return hipGetLastError();
+}
+
+// Kernels that use more than 64 KiB of LDS need the limit raised once per process.
+hipError_t m_init_attributes() {
+  hipError_t e = hipFuncSetAttribute((const void*)k_gemm_skinny, hipFuncAttributeMaxDynamicSharedMemorySize, kSkinnyLds);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute((const void*)k_lmhead_sample, hipFuncAttributeMaxDynamicSharedMemorySize, kSkinnyLds);
+}
+
+// Decode-side embedding gather: h[m, :] = embed[token(m), :] plus the row's sum of squares
+// (ssq[m], one part) for the norm that the first GEMM folds in.
+__global__ void __launch_bounds__(256) k_embed_ssq(const int32_t* __restrict__ tokens, int tok_stride, const int* step,
+                                                   const bf16* __restrict__ embed, float* __restrict__ h,
+                                                   float* __restrict__ ssq, int d) {
+  const int m = blockIdx.x;
+  const int tok = tokens[(size_t)m * tok_stride + (*step - 1)];
+  const bf16* e = embed + (size_t)tok * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    const float v = (float)e[i];
+    h[(size_t)m * d + i] = v;
+    ss += v * v;
+  }
+  __shared__ float red[4];
+  ss = wave_reduce_sum(ss);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  if (threadIdx.x == 0) ssq[m] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+hipError_t m_embed_ssq(const int32_t* tokens, int tok_stride, const int* step, const void* embed, float* h, float* ssq,
+                       int M, int d, hipStream_t st) {
+  ProfScope prof_(KID_EMBED, st);
+  k_embed_ssq<<<M, 256, 0, st>>>(tokens, tok_stride, step, (const bf16*)embed, h, ssq, d);
+  return hipGetLastError();
+}
+
+// Sum of squares of each row of h [M, d] -> ssq[m].
+__global__ void __launch_bounds__(256) k_row_ssq(const float* __restrict__ h, float* __restrict__ ssq, int d) {
+  const int m = blockIdx.x;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) { const float v = h[(size_t)m * d + i]; ss += v * v; }
+  __shared__ float red[4];
+  ss = wave_reduce_sum(ss);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  if (threadIdx.x == 0) ssq[m] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+hipError_t m_row_ssq(const float* h, float* ssq, int M, int d, hipStream_t st) {
+  ProfScope prof_(KID_MISC, st);
+  k_row_ssq<<<M, 256, 0, st>>>(h, ssq, d);
   return hipGetLastError();
 }
 

@@ -146,3 +146,35 @@ def test_mfma_rollout_logprobs_equal_scoring(sapo):
     mask = W.make_completion_mask(16, 80, 48)
     lp, _ = sapo.sapo_score_logprobs(gw, dev(seqs), dev(mask), dev(np.zeros(16, dtype=np.float32)), 4)
     assert np.max(np.abs(lp.cpu().numpy()[:, 32:] - lps)) <= LOGPROB_TOL
+
+
+def test_graph_replay_matches_eager_launches(sapo):
+    """On a non-default stream the decode step is captured once and replayed; the result must be
+    bit-identical to eager launches, also when the cached graph is reused with another seed and
+    temperature, and after the buffers change."""
+    import torch
+    shape = W.MINI_BF16
+    w, gw = make(sapo, shape, 95)
+    prompts = dev(np.random.default_rng(3).integers(0, shape.vocab, size=(4, 20)).astype(np.int32))
+    eager = {}
+    for seed, temp in ((1, 1.0), (2, 0.7), (3, 0.0)):
+        t, l = sapo.sapo_rollout_generate(gw, prompts, 4, 25, temp, seed)      # default stream: eager
+        eager[(seed, temp)] = (t.cpu().numpy(), l.cpu().numpy())
+    side = torch.cuda.Stream()
+    nbytes = sapo.sapo_rollout_workspace_bytes(gw, 4, 20, 4, 25)
+    ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+    out_t = torch.empty((16, 25), dtype=torch.int32, device="cuda")
+    out_l = torch.empty((16, 25), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        for rep in range(2):
+            for (seed, temp), (et, el) in eager.items():
+                sapo.sapo_rollout_generate(gw, prompts, 4, 25, temp, seed, workspace=ws, out_tokens=out_t,
+                                           out_logprobs=out_l, stream=side)
+                side.synchronize()
+                assert np.array_equal(out_t.cpu().numpy(), et), (rep, seed)
+                assert np.array_equal(out_l.cpu().numpy().view(np.uint32), el.view(np.uint32)), (rep, seed)
+        # other buffers: the graph is rebuilt
+        t2, l2 = sapo.sapo_rollout_generate(gw, prompts, 4, 25, 1.0, 1, stream=side)
+        side.synchronize()
+        assert np.array_equal(t2.cpu().numpy(), eager[(1, 1.0)][0])
