@@ -104,6 +104,11 @@ struct LayerWeights {
   void* wo;     // [d, q]
   void* wgu;    // [2 F, d]: generic: gate rows then up rows; MFMA: 32-row gate/up tiles interleaved
   void* wdown;  // [d, F]
+  // decode copies in W16 fragment order (MFMA path only)
+  void* wqkv16;
+  void* wo16;
+  void* wgu16;  // 16-row gate / up tiles interleaved
+  void* wdown16;
 };
 
 struct sapo_weights {
@@ -112,6 +117,7 @@ struct sapo_weights {
   bool mfma;
   void* embed;                   // row-major [V, d]
   void* lm_head;                 // generic: row-major [V, d] (== embed when tied); MFMA: fragment order
+  void* lm_head16;               // MFMA: W16 fragment order (decode)
   float* final_norm;
   float2* rope;                  // [max_seq][hd / 2] (cos, sin)
   std::vector<LayerWeights> layers;
@@ -210,6 +216,17 @@ static int create_impl(sapo_weights* w, const void* const* t, hipStream_t st) {
       HIP_CK(m_pack_weight(lt[6], (int)F, (int)d, lw.wgu, 0, 2, st));
       HIP_CK(m_pack_weight(lt[7], (int)F, (int)d, lw.wgu, 1, 2, st));
       HIP_CK(m_pack_weight(lt[8], (int)d, (int)F, lw.wdown, 0, 1, st));
+      if ((rc = dev_alloc(w, (q + 2 * kv) * d * e, &lw.wqkv16))) return rc;
+      if ((rc = dev_alloc(w, d * q * e, &lw.wo16))) return rc;
+      if ((rc = dev_alloc(w, 2 * F * d * e, &lw.wgu16))) return rc;
+      if ((rc = dev_alloc(w, d * F * e, &lw.wdown16))) return rc;
+      HIP_CK(d_pack_weight16(lt[1], (int)q, (int)d, lw.wqkv16, 0, 1, st));
+      HIP_CK(d_pack_weight16(lt[2], (int)kv, (int)d, lw.wqkv16, (int)(q / 16), 1, st));
+      HIP_CK(d_pack_weight16(lt[3], (int)kv, (int)d, lw.wqkv16, (int)((q + kv) / 16), 1, st));
+      HIP_CK(d_pack_weight16(lt[4], (int)d, (int)q, lw.wo16, 0, 1, st));
+      HIP_CK(d_pack_weight16(lt[6], (int)F, (int)d, lw.wgu16, 0, 2, st));
+      HIP_CK(d_pack_weight16(lt[7], (int)F, (int)d, lw.wgu16, 1, 2, st));
+      HIP_CK(d_pack_weight16(lt[8], (int)d, (int)F, lw.wdown16, 0, 1, st));
     } else {
       HIP_CK(copy(lw.wqkv, lt[1], q * d * e));
       HIP_CK(copy((char*)lw.wqkv + q * d * e, lt[2], kv * d * e));
@@ -226,6 +243,8 @@ static int create_impl(sapo_weights* w, const void* const* t, hipStream_t st) {
   if (w->mfma) {
     if ((rc = dev_alloc(w, V * d * e, &w->lm_head))) return rc;
     HIP_CK(m_pack_weight(c.tied_embeddings ? t[0] : tail[1], (int)V, (int)d, w->lm_head, 0, 1, st));
+    if ((rc = dev_alloc(w, V * d * e, &w->lm_head16))) return rc;
+    HIP_CK(d_pack_weight16(c.tied_embeddings ? t[0] : tail[1], (int)V, (int)d, w->lm_head16, 0, 1, st));
   } else if (c.tied_embeddings) {
     w->lm_head = w->embed;
   } else {
@@ -260,13 +279,6 @@ extern "C" int sapo_weights_create(const sapo_model_config* cfg, const void* con
   w->cfg = *cfg;
   w->elt = cfg->dtype == SAPO_DTYPE_F32 ? 4 : 2;
   w->mfma = mfma_eligible(cfg);
-  if (w->mfma) {
-    hipError_t e = m_init_attributes();
-    if (e != hipSuccess) {
-      delete w;
-      return fail(SAPO_EHIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(e));
-    }
-  }
   rc = create_impl(w, tensors, (hipStream_t)stream);
   if (rc) {
     sapo_weights_destroy(w);
@@ -381,7 +393,7 @@ static int run_layers_generic(const sapo_weights* w, const FwdBufs& b, int M, Ro
   return SAPO_OK;
 }
 
-// MFMA, many rows (prefill, scoring, and decode of more than 64 sequences)
+// MFMA, many rows (prefill and scoring)
 static int run_layers_big(const sapo_weights* w, const FwdBufs& b, int M, RowMap rm, const CacheBufs& cb, int max_ctx,
                           hipStream_t st) {
   const sapo_model_config& c = w->cfg;
@@ -392,12 +404,8 @@ static int run_layers_big(const sapo_weights* w, const FwdBufs& b, int M, RowMap
     const KVCache kvc = layer_cache(w, cb, l);
     HIP_CK(g_rmsnorm(dt, b.h, lw.attn_norm, c.rms_eps, b.a, M, d, nullptr, st));
     HIP_CK(m_gemm_big(b.a, d, lw.wqkv, M, q + 2 * kv, d, BigEpi{BIG_STORE_F32, b.qkv, q + 2 * kv, nullptr}, st));
-    if (rm.decode) {
-      HIP_CK(m_decode_attention(b.qkv, w->rope, rm, kvc, (bf16*)b.attn, 0, M, c.n_q_heads, st));
-    } else {
-      HIP_CK(g_rope_append(dt, b.qkv, w->rope, rm, kvc, b.q, M, c.n_q_heads, st));
-      HIP_CK(g_attention(dt, b.q, rm, kvc, b.attn, M, c.n_q_heads, max_ctx, st));
-    }
+    HIP_CK(g_rope_append(dt, b.qkv, w->rope, rm, kvc, b.q, M, c.n_q_heads, st));
+    HIP_CK(g_attention(dt, b.q, rm, kvc, b.attn, M, c.n_q_heads, max_ctx, st));
     HIP_CK(m_gemm_big(b.attn, q, lw.wo, M, d, q, BigEpi{BIG_ADD_F32, b.h, d, nullptr}, st));
     HIP_CK(g_rmsnorm(dt, b.h, lw.ffn_norm, c.rms_eps, b.a, M, d, nullptr, st));
     HIP_CK(m_gemm_big(b.a, d, lw.wgu, M, 2 * F, d, BigEpi{BIG_SWIGLU, nullptr, 0, (bf16*)b.act}, st));
@@ -406,72 +414,64 @@ static int run_layers_big(const sapo_weights* w, const FwdBufs& b, int M, RowMap
   return SAPO_OK;
 }
 
-// MFMA, decode of at most 64 sequences: weight-streaming GEMMs with the norms folded in
-static bool skinny_ok(const sapo_weights* w, int S) { return w->mfma && S <= 64 && w->cfg.d_model <= 896; }
-
-// Workspace of the 64-token decode path: row sums of squares handed from each residual-producing
-// kernel to the GEMM that normalises, and the split-K scratch + arrival counters.
-struct SkinnyBufs {
-  float* ssq_a;     // feeds the attention-side norm (and the final norm): [d/32][64]
-  float* ssq_b;     // feeds the FFN-side norm: [d/32][64]
-  float* scratch;
-  int* counters;    // [kSkinnyCounters], zero between launches
+// MFMA decode path: weight-streaming GEMMs on tokens in X16 order, the norms folded into the
+// producing epilogue (gain) and the consuming GEMM (scale).
+struct DecodeBufs {
+  int s_pad;        // 64 * token blocks
+  void* xa;         // X16 [s_pad, d]: input of the QKV projection (and of the LM head after the last layer)
+  void* xb;         // X16 [s_pad, d]: input of the gate/up projection
+  float* ssq_a;     // [d/16][s_pad] sums of squares behind xa
+  float* ssq_b;     // [d/16][s_pad] sums of squares behind xb
 };
-constexpr int kSkinnyCounters = 1024;
 
-static int skinny_ksplit(int N, int K) {
-  const int units = N / 32, KS = K / 16;
-  int ks = (200 + units / 2) / units;
-  if (ks > 8) ks = 8;
-  const int ks_min = (KS + 55) / 56;
-  if (ks < ks_min) ks = ks_min;
-  if (ks > KS) ks = KS;
-  const int per = (KS + ks - 1) / ks;
-  return (KS + per - 1) / per;
+static void carve_decode(Arena& A, const sapo_weights* w, int S, DecodeBufs& db) {
+  const size_t d = w->cfg.d_model;
+  db.s_pad = (S + 63) / 64 * 64;
+  db.xa = A.take_bytes((size_t)db.s_pad * d * 2);
+  db.xb = A.take_bytes((size_t)db.s_pad * d * 2);
+  db.ssq_a = A.take<float>((d / 16) * db.s_pad);
+  db.ssq_b = A.take<float>((d / 16) * db.s_pad);
 }
 
-static size_t skinny_scratch_floats(const sapo_weights* w) {
-  const sapo_model_config& c = w->cfg;
-  const int d = c.d_model, q = c.n_q_heads * c.head_dim, kv = c.n_kv_heads * c.head_dim, F = c.d_ff;
-  size_t m = 0;
-  const int dims[3][2] = {{q + 2 * kv, d}, {d, q}, {d, F}};
-  for (auto& nk : dims) {
-    const size_t n = (size_t)(nk[0] / 32) * skinny_ksplit(nk[0], nk[1]) * 2048;
-    if (n > m) m = n;
-  }
-  return m;
-}
-
-static void carve_skinny(Arena& A, const sapo_weights* w, SkinnyBufs& sb) {
-  const size_t tiles = w->cfg.d_model / 32;
-  sb.ssq_a = A.take<float>(tiles * 64);
-  sb.ssq_b = A.take<float>(tiles * 64);
-  sb.scratch = A.take<float>(skinny_scratch_floats(w));
-  sb.counters = A.take<int>(kSkinnyCounters);
-}
-
-// On entry b.h holds the residual rows and sb.ssq_a their sums of squares in `parts_a` parts.
-// On exit sb.ssq_a holds d/32 parts for the final norm.
-static int run_layers_skinny(const sapo_weights* w, const FwdBufs& b, const SkinnyBufs& sb, int parts_a, int S,
-                             RowMap rm, const CacheBufs& cb, hipStream_t st) {
+// On entry b.h holds the residual rows, db.xa their X16 form for layer 0's attention norm and
+// db.ssq_a their sums of squares in ONE part.  On exit db.xa / db.ssq_a (d/16 parts) feed the
+// final norm, and b.h holds the final residual rows.
+static int run_layers_decode16(const sapo_weights* w, const FwdBufs& b, const DecodeBufs& db, int S, RowMap rm,
+                               const CacheBufs& cb, hipStream_t st) {
   const sapo_model_config& c = w->cfg;
   const int d = c.d_model, q = c.n_q_heads * c.head_dim, kv = c.n_kv_heads * c.head_dim, F = c.d_ff;
   const int nqkv = q + 2 * kv;
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerWeights& lw = w->layers[l];
     const KVCache kvc = layer_cache(w, cb, l);
-    HIP_CK(m_gemm_skinny(SkinnyIn{nullptr, b.h, lw.attn_norm, sb.ssq_a, l == 0 ? parts_a : d / 32, c.rms_eps}, lw.wqkv,
-                         S, nqkv, d, SkinnyEpi{SK_STORE_F32, b.qkv, nqkv, nullptr, nullptr, sb.scratch, sb.counters},
-                         skinny_ksplit(nqkv, d), st));
-    HIP_CK(m_decode_attention(b.qkv, w->rope, rm, kvc, (bf16*)b.attn, 1, S, c.n_q_heads, st));
-    HIP_CK(m_gemm_skinny(SkinnyIn{(const bf16*)b.attn, nullptr, nullptr, nullptr, 0, 0.f}, lw.wo, S, d, q,
-                         SkinnyEpi{SK_ADD_F32, b.h, d, nullptr, sb.ssq_b, sb.scratch, sb.counters}, skinny_ksplit(d, q),
-                         st));
-    HIP_CK(m_gemm_skinny(SkinnyIn{nullptr, b.h, lw.ffn_norm, sb.ssq_b, d / 32, c.rms_eps}, lw.wgu, S, 2 * F, d,
-                         SkinnyEpi{SK_SWIGLU, nullptr, 0, (bf16*)b.act, nullptr, nullptr, nullptr}, 1, st));
-    HIP_CK(m_gemm_skinny(SkinnyIn{(const bf16*)b.act, nullptr, nullptr, nullptr, 0, 0.f}, lw.wdown, S, d, F,
-                         SkinnyEpi{SK_ADD_F32, b.h, d, nullptr, sb.ssq_a, sb.scratch, sb.counters}, skinny_ksplit(d, F),
-                         st));
+    SkinnyArgs a{};
+    a.n_rows = S; a.s_pad = db.s_pad; a.eps = c.rms_eps; a.norm_dim = d;
+    // QKV projection of the attention-normed residual
+    a.Wp = (const uint4*)lw.wqkv16; a.Xp = (const uint4*)db.xa; a.N = nqkv; a.K = d;
+    a.ssq_in = db.ssq_a; a.ssq_parts = (l == 0) ? 1 : d / 16;
+    a.out_f32 = b.qkv; a.ldc = nqkv;
+    HIP_CK(d_gemm_skinny(a, SKM_STORE, st));
+    HIP_CK(d_decode_attention(b.qkv, w->rope, rm, kvc, b.attn, S, c.n_q_heads, st));
+    // output projection + residual; emits the FFN norm's operand
+    SkinnyArgs o{};
+    o.n_rows = S; o.s_pad = db.s_pad;
+    o.Wp = (const uint4*)lw.wo16; o.Xp = (const uint4*)b.attn; o.N = d; o.K = q;
+    o.h = b.h; o.gain_next = lw.ffn_norm; o.xp_out = (uint4*)db.xb; o.ssq_out = db.ssq_b;
+    HIP_CK(d_gemm_skinny(o, SKM_RESID, st));
+    // gate / up projections + SwiGLU
+    SkinnyArgs g{};
+    g.n_rows = S; g.s_pad = db.s_pad; g.eps = c.rms_eps; g.norm_dim = d;
+    g.Wp = (const uint4*)lw.wgu16; g.Xp = (const uint4*)db.xb; g.N = 2 * F; g.K = d;
+    g.ssq_in = db.ssq_b; g.ssq_parts = d / 16;
+    g.xp_out = (uint4*)b.act;
+    HIP_CK(d_gemm_skinny(g, SKM_SWIGLU, st));
+    // down projection + residual; emits the next norm's operand
+    SkinnyArgs dn{};
+    dn.n_rows = S; dn.s_pad = db.s_pad;
+    dn.Wp = (const uint4*)lw.wdown16; dn.Xp = (const uint4*)b.act; dn.N = d; dn.K = F;
+    dn.h = b.h; dn.gain_next = (l + 1 < c.n_layers) ? w->layers[l + 1].attn_norm : w->final_norm;
+    dn.xp_out = (uint4*)db.xa; dn.ssq_out = db.ssq_a;
+    HIP_CK(d_gemm_skinny(dn, SKM_RESID, st));
   }
   return SAPO_OK;
 }
@@ -497,7 +497,8 @@ struct RolloutPlan {
   void* x_last;     // [max(P, S), d] final-norm output (T)
   float* logits;    // [max(P, S), V] (paths that materialise logits)
   float* partials;  // fused sampler partials
-  SkinnyBufs sk;    // 64-token decode path
+  DecodeBufs dec;   // MFMA decode path
+  bool fused_lm;    // LM head + sampler fused (at most 64 sequences)
   size_t bytes;
 };
 
@@ -517,10 +518,10 @@ static void plan_rollout(const sapo_weights* w, int P, int Lp, int G, int N, cha
   const size_t R = (size_t)(P > pl.S ? P : pl.S);
   pl.h_last = A.take<float>((size_t)pl.S * c.d_model);
   pl.x_last = A.take_bytes(R * c.d_model * w->elt);
-  const bool fused = skinny_ok(w, pl.S);
-  pl.logits = fused ? nullptr : A.take<float>(R * c.vocab);
-  pl.partials = fused ? A.take<float>(m_lmhead_sample_partial_floats()) : nullptr;
-  if (fused) carve_skinny(A, w, pl.sk);
+  pl.fused_lm = w->mfma && d_lmhead_sample_supported(c.d_model, pl.S);
+  pl.logits = pl.fused_lm ? nullptr : A.take<float>(R * c.vocab);
+  pl.partials = pl.fused_lm ? A.take<float>(d_lmhead_sample_partial_floats()) : nullptr;
+  if (w->mfma) carve_decode(A, w, pl.S, pl.dec);
   pl.bytes = (A.off + 255) & ~(size_t)255;
 }
 
@@ -539,15 +540,19 @@ extern "C" size_t sapo_rollout_workspace_bytes(const sapo_weights* w, int P, int
   return pl.bytes;
 }
 
-// Sample the token of the current step for all S sequences from the residual rows in `h`
-// (row s = sequence s), writing out_tokens[:, step] and out_logprobs[:, step].
+// Sample the token of the current step for all S sequences, writing out_tokens[:, step] and
+// out_logprobs[:, step].
+//   fused path : the final norm's operand is in pl.dec.xa / pl.dec.ssq_a (ssq_parts parts); the merge
+//                also gathers the sampled tokens' embedding rows for the next step.
+//   otherwise  : from the residual rows in `h` (row s = sequence s) through materialised logits.
 static int sample_step(const sapo_weights* w, const RolloutPlan& pl, const float* h, int ssq_parts, SampleParams sp,
                        hipStream_t st) {
   const sapo_model_config& c = w->cfg;
   const int S = pl.S, d = c.d_model, V = c.vocab;
-  if (skinny_ok(w, S)) {
-    HIP_CK(m_lmhead_sample(SkinnyIn{nullptr, h, w->final_norm, pl.sk.ssq_a, ssq_parts, c.rms_eps}, w->lm_head, S, 0, V, d,
-                           sp, pl.partials, st));
+  if (pl.fused_lm) {
+    const float* gain_first = c.n_layers > 0 ? w->layers[0].attn_norm : w->final_norm;
+    HIP_CK(d_lmhead_sample(w->lm_head16, pl.dec.xa, d, V, pl.dec.ssq_a, ssq_parts, pl.dec.s_pad, c.rms_eps, S, sp,
+                           pl.partials, w->embed, gain_first, pl.fwd.h, pl.dec.xa, pl.dec.ssq_a, st));
     return SAPO_OK;
   }
   HIP_CK(g_rmsnorm(c.dtype, h, w->final_norm, c.rms_eps, pl.x_last, S, d, nullptr, st));
@@ -573,7 +578,8 @@ extern "C" int sapo_rollout_generate(const sapo_weights* w, const int32_t* promp
   hipStream_t st = (hipStream_t)stream;
   const sapo_model_config& c = w->cfg;
   const int dt = c.dtype, d = c.d_model, S = pl.S;
-  const bool skinny = skinny_ok(w, S);
+  const float* gain_first = c.n_layers > 0 ? w->layers[0].attn_norm : w->final_norm;
+  const int parts_after_layers = c.n_layers > 0 ? d / 16 : 1;
 
   SampleParams sp;
   sp.temperature = temperature;
@@ -608,10 +614,7 @@ extern "C" int sapo_rollout_generate(const sapo_weights* w, const int32_t* promp
       for (int l = 0; l < c.n_layers; ++l)
         HIP_CK(g_copy_partial_page(dt, layer_cache(w, pl.cache, l), P, G, pl.full_prompt_pages, st));
     HIP_CK(g_gather_last_rows(pl.fwd.h, pl.h_last, S, G, Lp, d, st));
-    if (skinny) {
-      HIP_CK(g_fill_i32(pl.sk.counters, 0, kSkinnyCounters, st));
-      HIP_CK(m_row_ssq(pl.h_last, pl.sk.ssq_a, S, d, st));
-    }
+    if (pl.fused_lm) HIP_CK(d_pack_rows_x16(pl.h_last, w->final_norm, S, d, pl.dec.xa, pl.dec.ssq_a, st));
     if ((rc = sample_step(w, pl, pl.h_last, 1, sp, st))) return rc;
   }
   // decode: token t-1 of every sequence goes through the layers, token t is sampled.  Everything
@@ -621,10 +624,11 @@ extern "C" int sapo_rollout_generate(const sapo_weights* w, const int32_t* promp
   auto enqueue_step = [&]() -> int {
     int rc2;
     HIP_CK(g_incr(pl.step, st));
-    if (skinny) {
-      HIP_CK(m_embed_ssq(out_tokens, max_new, pl.step, w->embed, pl.fwd.h, pl.sk.ssq_a, S, d, st));
-      if ((rc2 = run_layers_skinny(w, pl.fwd, pl.sk, 1, S, rm, pl.cache, st))) return rc2;
-      if ((rc2 = sample_step(w, pl, pl.fwd.h, d / 32, sp, st))) return rc2;
+    if (w->mfma) {
+      if (!pl.fused_lm)   // the fused sampler's merge has already gathered the rows
+        HIP_CK(d_embed_x16(out_tokens, max_new, pl.step, w->embed, S, d, gain_first, pl.fwd.h, pl.dec.xa, pl.dec.ssq_a, st));
+      if ((rc2 = run_layers_decode16(w, pl.fwd, pl.dec, S, rm, pl.cache, st))) return rc2;
+      if ((rc2 = sample_step(w, pl, pl.fwd.h, parts_after_layers, sp, st))) return rc2;
     } else {
       HIP_CK(g_embed(dt, out_tokens, max_new, pl.step, w->embed, pl.fwd.h, S, d, st));
       if ((rc2 = run_layers(w, pl.fwd, S, rm, pl.cache, Lp + max_new, st))) return rc2;

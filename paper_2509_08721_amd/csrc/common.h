@@ -161,8 +161,6 @@ __device__ __forceinline__ void resolve_sample_params(SampleParams& sp) {
   }
 }
 
-hipError_t m_init_attributes();
-
 // generic (shape-agnostic) kernels --------------------------------------------------------
 hipError_t g_embed(int dtype, const int32_t* tokens, int tok_stride, const int* step, const void* embed,
                    float* h, int M, int d, hipStream_t st);
@@ -199,14 +197,8 @@ hipError_t g_gumbel(uint32_t seed_lo, uint32_t seed_hi, uint32_t seq, uint32_t s
 // MFMA (bf16) kernels: weights live in "fragment order" so that a wave's operand load for one
 // 32x32x16 MFMA step is one contiguous 1 KiB read:
 //   Wp[((tile * (K/16) + ks) * 64 + lane) * 8 + e] = W[tile*32 + lane%32][ks*16 + (lane/32)*8 + e]
-// Decode-side activations for the skinny GEMMs use the same order over tokens ("X-packed",
-// 64 tokens): Xp[((ks * 2 + tok/32) * 64 + tok%32 + 32*((k%16)/8)) * 8 + k%8], ks = k/16.
 // =======================================================================================
 namespace sapo {
-
-__host__ __device__ __forceinline__ size_t xpack_index(int tok, int k) {
-  return ((((size_t)(k >> 4) * 2 + (tok >> 5)) * 64) + (tok & 31) + 32 * ((k >> 3) & 1)) * 8 + (k & 7);
-}
 
 struct BigEpi {
   int mode;            // see enum below
@@ -224,38 +216,41 @@ hipError_t m_lmhead_score(const void* X, const void* Wp, int max_rows, const int
                           hipStream_t st);
 size_t m_lmhead_score_partial_floats(int max_rows);
 
-// decode (64-token) kernels ---------------------------------------------------------------
-struct SkinnyEpi {
-  int mode;            // see enum below
-  float* out_f32;      // STORE_F32: [64, ldc];  ADD_F32: h [64, ldc]
-  int ldc;
-  bf16* out_xp;        // SWIGLU: act, X-packed over K = F
-  float* ssq_out;      // STORE/ADD: per-tile sums of squares of the written rows [N/32][64] (or NULL)
-  float* scratch;      // split-K partial tiles [N/32][ksplit][2048]
-  int* counters;       // split-K arrival counters [N/32], zero between launches
-};
-enum { SK_STORE_F32 = 0, SK_ADD_F32 = 1, SK_SWIGLU = 2 };
-
-// X source of a skinny GEMM: either an X-packed bf16 buffer, or the fp32 residual stream
-// [64, K], RMS-normalised while it is staged: scale(tok) = rsqrt(sum_p ssq[p][tok] / K + eps).
-struct SkinnyIn {
-  const bf16* xp;
-  const float* h;
-  const float* gain;
-  const float* ssq;    // [ssq_parts][64]
+// decode kernels (kernels_decode.hip) -------------------------------------------------------
+enum { SKM_STORE = 0, SKM_RESID = 1, SKM_SWIGLU = 2 };
+struct SkinnyArgs {
+  const uint4* Wp;        // weights, W16 fragment order [N/16][K/32][64]
+  const uint4* Xp;        // tokens, X16 order [blocks][K/32][4][64]
+  int N, K, n_rows;
+  int s_pad;              // 64 * number of token blocks: row stride of the ssq arrays
+  // STORE, SWIGLU: accumulators are scaled by rsqrt(sum_p ssq_in[p][tok] / norm_dim + eps)
+  const float* ssq_in;    // [ssq_parts][s_pad]
   int ssq_parts;
+  int norm_dim;
   float eps;
+  float* out_f32;         // STORE: [n_rows, ldc]
+  int ldc;
+  float* h;               // RESID: residual stream [n_rows, N], updated in place
+  const float* gain_next; // RESID: gain of the norm that reads the updated residual [N]
+  uint4* xp_out;          // RESID: bf16(h * gain_next), X16 order over K' = N; SWIGLU: act, X16 order over K' = N / 2
+  float* ssq_out;         // RESID: [N/16][s_pad] sums of h^2 over each 16-feature tile
 };
-hipError_t m_gemm_skinny(SkinnyIn in, const void* Wp, int n_rows, int N, int K, SkinnyEpi epi, int ksplit,
-                         hipStream_t st);
-hipError_t m_embed_ssq(const int32_t* tokens, int tok_stride, const int* step, const void* embed, float* h, float* ssq,
-                       int M, int d, hipStream_t st);
-hipError_t m_row_ssq(const float* h, float* ssq, int M, int d, hipStream_t st);
-hipError_t m_lmhead_sample(SkinnyIn in, const void* Wp, int n_rows, int seq0, int V, int K, SampleParams sp,
-                           float* partials, hipStream_t st);
-size_t m_lmhead_sample_partial_floats();
-hipError_t m_decode_attention(const float* qkv, const float2* rope, RowMap rm, KVCache kv, bf16* out, int out_xp,
-                              int S, int n_q_heads, hipStream_t st);
+hipError_t d_pack_weight16(const void* src, int n_rows, int K, void* dst, int dst_tile0, int dst_tile_stride,
+                           hipStream_t st);
+hipError_t d_gemm_skinny(const SkinnyArgs& a, int mode, hipStream_t st);
+hipError_t d_pack_rows_x16(const float* h, const float* gain, int M, int d, void* xp, float* ssq, hipStream_t st);
+hipError_t d_embed_x16(const int32_t* tokens, int tok_stride, const int* step, const void* embed, int M, int d,
+                       const float* gain, float* h, void* xp, float* ssq, hipStream_t st);
+bool d_lmhead_sample_supported(int K, int n_rows);
+size_t d_lmhead_sample_partial_floats();
+// Fused LM head + sampler for at most 64 sequences, followed by the merge that writes token and
+// log-prob of the step and gathers the token's embedding row for the next step (h, X16 row with
+// gain_first, one ssq part).
+hipError_t d_lmhead_sample(const void* Wp, const void* Xp, int K, int V, const float* ssq, int ssq_parts, int s_pad,
+                           float eps, int n_rows, SampleParams sp, float* partials, const void* embed,
+                           const float* gain_first, float* h, void* xp_first, float* ssq_first, hipStream_t st);
+hipError_t d_decode_attention(const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* out_x16, int S,
+                              int n_q_heads, hipStream_t st);
 hipError_t g_gather_last_rows(const float* h, float* out, int S, int G, int Lp, int d, hipStream_t st);
 
 }  // namespace sapo

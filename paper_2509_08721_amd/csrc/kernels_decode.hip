@@ -1,0 +1,764 @@
+// Decode-side bf16 MFMA kernels for gfx950 (one new token per sequence and step).
+//
+// Every projection of a decode step is a "skinny" GEMM: few tokens (64 per block), all weights
+// streamed once from HBM.  The kernels here are built around v_mfma_f32_16x16x32_bf16 with both
+// operands already in fragment order in global memory, so that a wave's operand load is one
+// contiguous 1 KiB read that goes straight into registers:
+//   weights  W16[((tile * KS + ks) * 64 + lane)]           (uint4 = 8 bf16)
+//            = W[tile*16 + lane%16][ks*32 + (lane/16)*8 .. +7],                       KS = K / 32
+//   tokens   X16[(((tok/64) * KS + ks) * 4 + (tok/16)%4) * 64 + tok%16 + 16*((k%32)/8)]
+//            = x[tok][ks*32 + ((k%32)/8)*8 .. +7]
+// D = W-fragment x X-fragment leaves lane l with features (l/16)*4 .. +3 of token l%16.
+//
+// RMSNorm never runs on its own: the kernel that produces the residual stream also writes
+// bf16(h * gain) in X16 order plus per-tile sums of squares of h, and the GEMM that consumes it
+// multiplies its accumulators by rsqrt(mean(h^2) + eps) (the scale is per token, so it commutes
+// with the contraction).
+#include "common.h"
+
+namespace sapo {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+union Frag16 {
+  uint4 u;
+  u32x4 n;
+  bf16x8 v;
+};
+
+__device__ __forceinline__ f32x4 mfma16(const Frag16& a, const Frag16& b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
+}
+__device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
+
+// uint4 index of the chunk that holds x[tok][k .. k+7] (k a multiple of 8) in X16 order.
+__host__ __device__ __forceinline__ size_t x16_chunk(int tok, int k, int KS) {
+  return ((((size_t)(tok >> 6) * KS + (k >> 5)) * 4 + ((tok >> 4) & 3)) * 64) + (tok & 15) + 16 * ((k >> 3) & 3);
+}
+
+// ---------------------------------------------------------------------------------------
+// weight packing: row-major [n_rows, K] -> W16 order; 16-row tile t goes to tile slot
+// tile0 + t * tile_stride (stride 2 interleaves gate and up tiles).
+// ---------------------------------------------------------------------------------------
+__global__ void k_pack_weight16(const bf16* __restrict__ src, int n_rows, int K, uint4* __restrict__ dst, int tile0,
+                                int tile_stride) {
+  const int KS = K >> 5;
+  const size_t total = (size_t)(n_rows >> 4) * KS * 64;
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int lane = (int)(idx & 63);
+  const int ks = (int)((idx >> 6) % KS);
+  const int t = (int)((idx >> 6) / KS);
+  const int row = t * 16 + (lane & 15), k = ks * 32 + (lane >> 4) * 8;
+  dst[((size_t)(tile0 + t * tile_stride) * KS + ks) * 64 + lane] = *(const uint4*)(src + (size_t)row * K + k);
+}
+hipError_t d_pack_weight16(const void* src, int n_rows, int K, void* dst, int dst_tile0, int dst_tile_stride,
+                           hipStream_t st) {
+  ProfScope prof_(KID_MISC, st);
+  const size_t total = (size_t)(n_rows / 16) * (K / 32) * 64;
+  if (total == 0) return hipSuccess;
+  k_pack_weight16<<<(unsigned)((total + 255) / 256), 256, 0, st>>>((const bf16*)src, n_rows, K, (uint4*)dst, dst_tile0,
+                                                                    dst_tile_stride);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Sum of the ssq parts of one token, spread over the 8 waves of a workgroup: thread (grp, tok)
+// loads parts grp, grp + 8, ... early (ssq_issue) and the sums meet in LDS later (ssq_finish).
+// ---------------------------------------------------------------------------------------
+constexpr int kSsqPerThread = 12;   // up to 96 parts
+
+__device__ __forceinline__ void ssq_issue(const float* __restrict__ ssq, int parts, int stride, int tok0,
+                                          float (&sq)[kSsqPerThread]) {
+  const int tok = threadIdx.x & 63, grp = threadIdx.x >> 6;
+#pragma unroll
+  for (int i = 0; i < kSsqPerThread; ++i) {
+    const int p = grp + 8 * i;
+    sq[i] = (ssq != nullptr && p < parts) ? ssq[(size_t)p * stride + tok0 + tok] : 0.f;
+  }
+}
+// s_part: LDS [8][64].  Call before a __syncthreads(); ssq_scale() after it.
+__device__ __forceinline__ void ssq_publish(const float (&sq)[kSsqPerThread], float* s_part) {
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < kSsqPerThread; ++i) s += sq[i];
+  s_part[threadIdx.x] = s;
+}
+__device__ __forceinline__ float ssq_scale(const float* s_part, int tok_local, int norm_dim, float eps) {
+  float s = 0.f;
+#pragma unroll
+  for (int g = 0; g < 8; ++g) s += s_part[g * 64 + tok_local];
+  return 1.0f / sqrtf(s / (float)norm_dim + eps);
+}
+
+// ---------------------------------------------------------------------------------------
+// Skinny GEMM.  512 threads = 8 waves per workgroup.
+// A workgroup owns NT 16-feature tiles x TG 16-token groups over the whole K; wave w takes the
+// k steps w, w + 8, ... (R of them per round, all loads of a round in flight at once), and the
+// 8 partial results are summed through LDS in wave order, so results never depend on timing.
+// Small per-workgroup operands matter more than the number of workgroups: a compute unit ingests
+// roughly 100 GB/s, so a 64-token block is split into 4 / TG workgroups per tile, which re-read
+// the tile's weights from the L2 they share (block ids are laid out so that they land on the
+// same XCD: ids that differ by a multiple of 8).
+// Epilogues:
+//   STORE  : out_f32[tok][feat] = acc * scale(tok)
+//   SWIGLU : tiles come in (gate, up) pairs; act = silu(gate * scale) * (up * scale) -> bf16, X16 order
+//   RESID  : h[tok][feat] += acc;  xp_out = bf16(h * gain_next) in X16 order;  ssq_out[tile][tok] =
+//            sum of h^2 over the tile's 16 features
+// ---------------------------------------------------------------------------------------
+template <int NT, int TG, int R, int MODE>
+__global__ void __launch_bounds__(512) k_skinny16(SkinnyArgs a, int n_units) {
+  extern __shared__ float4 red[];   // [8 waves][NT * TG][64 lanes]
+  __shared__ float s_part[512];
+  constexpr int TS = 4 / TG;        // workgroups per (tile unit, token block)
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int KS = a.K >> 5;
+  const int tb = blockIdx.y;
+  // block id -> (unit, token split): the TS splits of a unit sit 8 ids apart
+  const int unit = (blockIdx.x / (8 * TS)) * 8 + (blockIdx.x & 7);
+  const int tg0 = ((blockIdx.x >> 3) % TS) * TG;
+  if (unit >= n_units) return;
+  const int tile0 = unit * NT;
+  f32x4 acc[NT][TG];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int g = 0; g < TG; ++g) acc[t][g] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float sq[kSsqPerThread];
+  if (MODE != SKM_RESID) ssq_issue(a.ssq_in, a.ssq_parts, a.s_pad, tb * 64, sq);
+  // RESID: this thread's output slot and its residual / gain operands, requested up front
+  float4 h_old = make_float4(0.f, 0.f, 0.f, 0.f), g_next = h_old;
+  if (MODE == SKM_RESID && tid < NT * TG * 64) {
+    const int t = tid / (TG * 64), g = (tid >> 6) % TG, l = tid & 63;
+    const int tok = tb * 64 + (tg0 + g) * 16 + (l & 15);
+    const int f0 = (tile0 + t) * 16 + (l >> 4) * 4;
+    if (tok < a.n_rows) {
+      h_old = *(const float4*)(a.h + (size_t)tok * a.N + f0);
+      g_next = *(const float4*)(a.gain_next + f0);
+    }
+  }
+
+  const uint4* wbase = a.Wp + (size_t)tile0 * KS * 64 + lane;
+  const uint4* xbase = a.Xp + ((size_t)tb * KS * 4 + tg0) * 64 + lane;
+  for (int k0 = wave; k0 < KS; k0 += 8 * R) {
+    Frag16 wf[R][NT], xf[R][TG];
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+      const int ks = k0 + 8 * i;
+      if (ks < KS) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+          wf[i][t].n = __builtin_nontemporal_load((const u32x4*)(wbase + ((size_t)t * KS + ks) * 64));
+#pragma unroll
+        for (int g = 0; g < TG; ++g) xf[i][g].u = xbase[(size_t)(ks * 4 + g) * 64];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+      const int ks = k0 + 8 * i;
+      if (ks < KS) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+          for (int g = 0; g < TG; ++g) acc[t][g] = mfma16(wf[i][t], xf[i][g], acc[t][g]);
+      }
+    }
+  }
+  // cross-wave reduction
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int g = 0; g < TG; ++g)
+      red[(size_t)(wave * NT * TG + t * TG + g) * 64 + lane] = make_float4(acc[t][g][0], acc[t][g][1], acc[t][g][2], acc[t][g][3]);
+  if (MODE != SKM_RESID) ssq_publish(sq, s_part);
+  __syncthreads();
+  auto sum8 = [&](int tg, int l) -> float4 {   // tg = t * TG + g
+    float4 s = red[(size_t)tg * 64 + l];
+#pragma unroll
+    for (int w = 1; w < 8; ++w) {
+      const float4 p = red[(size_t)(w * NT * TG + tg) * 64 + l];
+      s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+    }
+    return s;
+  };
+  if (MODE == SKM_SWIGLU) {
+    const int KSo = (a.N >> 1) >> 5;   // act has F = N / 2 features
+    for (int slot = tid; slot < (NT / 2) * TG * 64; slot += 512) {
+      const int pp = slot / (TG * 64), g = (slot >> 6) % TG, l = slot & 63;
+      const float4 gs = sum8((2 * pp) * TG + g, l), us = sum8((2 * pp + 1) * TG + g, l);
+      const int tl = (tg0 + g) * 16 + (l & 15), tok = tb * 64 + tl;
+      const int f0 = ((tile0 >> 1) + pp) * 16 + (l >> 4) * 4;
+      bf16x4 o;
+      if (tok < a.n_rows) {
+        const float sc = ssq_scale(s_part, tl, a.norm_dim, a.eps);
+        o[0] = (bf16)(silu_f(gs.x * sc) * (us.x * sc)); o[1] = (bf16)(silu_f(gs.y * sc) * (us.y * sc));
+        o[2] = (bf16)(silu_f(gs.z * sc) * (us.z * sc)); o[3] = (bf16)(silu_f(gs.w * sc) * (us.w * sc));
+      } else {
+        o[0] = o[1] = o[2] = o[3] = (bf16)0.f;
+      }
+      *(bf16x4*)((bf16*)a.xp_out + x16_chunk(tok, f0, KSo) * 8 + (f0 & 4)) = o;
+    }
+    return;
+  }
+  if (MODE == SKM_STORE) {
+    for (int slot = tid; slot < NT * TG * 64; slot += 512) {
+      const int t = slot / (TG * 64), g = (slot >> 6) % TG, l = slot & 63;
+      const float4 s = sum8(t * TG + g, l);
+      const int tl = (tg0 + g) * 16 + (l & 15), tok = tb * 64 + tl;
+      const int f0 = (tile0 + t) * 16 + (l >> 4) * 4;
+      if (tok < a.n_rows) {
+        const float sc = ssq_scale(s_part, tl, a.norm_dim, a.eps);
+        *(float4*)(a.out_f32 + (size_t)tok * a.ldc + f0) = make_float4(s.x * sc, s.y * sc, s.z * sc, s.w * sc);
+      }
+    }
+    return;
+  }
+  // RESID: one slot per thread (NT * TG * 64 <= 512)
+  if (tid < NT * TG * 64) {
+    const int t = tid / (TG * 64), g = (tid >> 6) % TG, l = tid & 63;
+    float4 s = sum8(t * TG + g, l);
+    const int tok = tb * 64 + (tg0 + g) * 16 + (l & 15);
+    const int f0 = (tile0 + t) * 16 + (l >> 4) * 4;
+    bf16x4 o;
+    float q = 0.f;
+    if (tok < a.n_rows) {
+      s.x += h_old.x; s.y += h_old.y; s.z += h_old.z; s.w += h_old.w;
+      *(float4*)(a.h + (size_t)tok * a.N + f0) = s;
+      o[0] = (bf16)(s.x * g_next.x); o[1] = (bf16)(s.y * g_next.y); o[2] = (bf16)(s.z * g_next.z); o[3] = (bf16)(s.w * g_next.w);
+      q = s.x * s.x + s.y * s.y + s.z * s.z + s.w * s.w;
+    } else {
+      o[0] = o[1] = o[2] = o[3] = (bf16)0.f;
+    }
+    *(bf16x4*)((bf16*)a.xp_out + x16_chunk(tok, f0, a.N >> 5) * 8 + (f0 & 4)) = o;
+    q += __shfl_xor(q, 16, 64);
+    q += __shfl_xor(q, 32, 64);
+    if (l < 16) a.ssq_out[(size_t)(tile0 + t) * a.s_pad + tok] = q;
+  }
+}
+
+template <int NT, int TG, int R, int MODE>
+static hipError_t launch_skinny(const SkinnyArgs& a, hipStream_t st) {
+  static_assert(MODE != SKM_RESID || NT * TG * 64 <= 512, "RESID epilogue handles one slot per thread");
+  static bool attr_done = false;
+  const size_t smem = (size_t)8 * NT * TG * 64 * sizeof(float4);
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)k_skinny16<NT, TG, R, MODE>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  if ((a.N / 16) % NT != 0) return hipErrorInvalidValue;
+  const int units = a.N / 16 / NT;
+  const int blocks = (a.n_rows + 63) / 64;
+  const int gx = (units + 7) / 8 * 8 * (4 / TG);
+  k_skinny16<NT, TG, R, MODE><<<dim3(gx, blocks), 512, smem, st>>>(a, units);
+  return hipGetLastError();
+}
+
+hipError_t d_gemm_skinny(const SkinnyArgs& a, int mode, hipStream_t st) {
+  ProfScope prof_(KID_GEMM_SKINNY, st);
+  if (a.K % 32 != 0 || a.N % 16 != 0 || a.n_rows <= 0) return hipErrorInvalidValue;
+  if (mode != SKM_RESID && a.ssq_parts > 8 * kSsqPerThread) return hipErrorInvalidValue;
+  const int per_wave = ((a.K >> 5) + 7) / 8;   // k steps per wave
+  if (mode == SKM_SWIGLU) {
+    if (a.N % 64 != 0) return hipErrorInvalidValue;
+    if (per_wave <= 4) return launch_skinny<4, 4, 4, SKM_SWIGLU>(a, st);
+    return launch_skinny<2, 4, 6, SKM_SWIGLU>(a, st);
+  }
+  if (mode == SKM_STORE) {
+    if (per_wave <= 4) return launch_skinny<1, 1, 4, SKM_STORE>(a, st);
+    return launch_skinny<1, 1, 8, SKM_STORE>(a, st);
+  }
+  if (per_wave <= 4) return launch_skinny<1, 1, 4, SKM_RESID>(a, st);
+  if (per_wave <= 8) return launch_skinny<1, 1, 8, SKM_RESID>(a, st);
+  return launch_skinny<1, 1, 20, SKM_RESID>(a, st);
+}
+
+// ---------------------------------------------------------------------------------------
+// Rows of the residual stream -> X16 order: xp = bf16(h * gain), ssq[row] = sum h^2 (one part).
+// One workgroup of 128 threads per row; thread i handles the 8 features 8 i .. 8 i + 7 (+1024 j).
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void row_to_x16(const float (&v)[8], const float* __restrict__ gain, int k, int row, int KS,
+                                           uint4* __restrict__ xp) {
+  bf16x8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = (bf16)(v[e] * gain[k + e]);
+  Frag16 f; f.v = o;
+  xp[x16_chunk(row, k, KS)] = f.u;
+}
+__device__ __forceinline__ float block128_sum(float s, float* red) {
+  s = wave_reduce_sum(s);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+  __syncthreads();
+  return red[0] + red[1];
+}
+
+__global__ void __launch_bounds__(128) k_pack_rows_x16(const float* __restrict__ h, const float* __restrict__ gain, int d,
+                                                       uint4* __restrict__ xp, float* __restrict__ ssq) {
+  __shared__ float red[2];
+  const int row = blockIdx.x;
+  float ss = 0.f;
+  for (int k = threadIdx.x * 8; k < d; k += 1024) {
+    float v[8];
+    const float4 a = *(const float4*)(h + (size_t)row * d + k), b = *(const float4*)(h + (size_t)row * d + k + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ss += v[e] * v[e];
+    row_to_x16(v, gain, k, row, d >> 5, xp);
+  }
+  ss = block128_sum(ss, red);
+  if (threadIdx.x == 0) ssq[row] = ss;
+}
+hipError_t d_pack_rows_x16(const float* h, const float* gain, int M, int d, void* xp, float* ssq, hipStream_t st) {
+  ProfScope prof_(KID_MISC, st);
+  k_pack_rows_x16<<<M, 128, 0, st>>>(h, gain, d, (uint4*)xp, ssq);
+  return hipGetLastError();
+}
+
+// Embedding row of token id `tok` -> h[row] (fp32), X16 bf16(h * gain), ssq[row].  128 threads.
+__device__ __forceinline__ void embed_row_x16(const bf16* __restrict__ embed, int tok, int row, int d,
+                                              const float* __restrict__ gain, float* __restrict__ h,
+                                              uint4* __restrict__ xp, float* __restrict__ ssq, float* red) {
+  float ss = 0.f;
+  for (int k = threadIdx.x * 8; k < d; k += 1024) {
+    Frag16 e; e.u = *(const uint4*)(embed + (size_t)tok * d + k);
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { v[i] = (float)e.v[i]; ss += v[i] * v[i]; }
+    *(float4*)(h + (size_t)row * d + k) = make_float4(v[0], v[1], v[2], v[3]);
+    *(float4*)(h + (size_t)row * d + k + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    row_to_x16(v, gain, k, row, d >> 5, xp);
+  }
+  ss = block128_sum(ss, red);
+  if (threadIdx.x == 0) ssq[row] = ss;
+}
+
+// Decode-side embedding gather of the token sampled at the previous step.
+__global__ void __launch_bounds__(128) k_embed_x16(const int32_t* __restrict__ tokens, int tok_stride, const int* step,
+                                                   const bf16* __restrict__ embed, int d, const float* __restrict__ gain,
+                                                   float* __restrict__ h, uint4* __restrict__ xp, float* __restrict__ ssq) {
+  __shared__ float red[2];
+  const int row = blockIdx.x;
+  const int tok = tokens[(size_t)row * tok_stride + (*step - 1)];
+  embed_row_x16(embed, tok, row, d, gain, h, xp, ssq, red);
+}
+hipError_t d_embed_x16(const int32_t* tokens, int tok_stride, const int* step, const void* embed, int M, int d,
+                       const float* gain, float* h, void* xp, float* ssq, hipStream_t st) {
+  ProfScope prof_(KID_EMBED, st);
+  k_embed_x16<<<M, 128, 0, st>>>(tokens, tok_stride, step, (const bf16*)embed, d, gain, h, (uint4*)xp, ssq);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// LM head for decode: logits tile -> online log-sum-exp + Gumbel-max; logits are never stored.
+// 512 threads = 8 waves; X (64 tokens x K, X16 order) is staged once into LDS and every wave owns
+// whole 16-vocabulary tiles over the full K: tile = global wave index + j * (number of waves), its
+// weights streamed in groups of U k steps with the next group in flight while the current one is
+// multiplied.  A lane keeps, for its token of each 16-token group, the running (max, sum exp) and
+// the best perturbed score; lanes, waves and workgroups are merged in a fixed order.
+// partials: [n_wg][64][5] (max, sum exp, best y, its logit, its id).
+// ---------------------------------------------------------------------------------------
+struct LaneState {
+  float m[4], l[4], by[4], bz[4];
+  int bid[4];
+};
+
+template <int U>
+__global__ void __launch_bounds__(512) k_lmhead_sample16(const uint4* __restrict__ Wp, const uint4* __restrict__ Xp, int KS,
+                                                         int n_tiles, const float* __restrict__ ssq, int ssq_parts,
+                                                         int s_pad, int norm_dim, float eps, int n_rows, int seq0,
+                                                         SampleParams sp, float* __restrict__ partials) {
+  extern __shared__ uint4 xs[];   // [KS][4][64]
+  __shared__ float s_part[512];
+  __shared__ float s_scale[64];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  float sq[kSsqPerThread];
+  ssq_issue(ssq, ssq_parts, s_pad, 0, sq);
+  for (int i = tid; i < KS * 256; i += 512) xs[i] = Xp[i];
+  ssq_publish(sq, s_part);
+  __syncthreads();
+  if (tid < 64) s_scale[tid] = ssq_scale(s_part, tid, norm_dim, eps);
+  __syncthreads();
+  resolve_sample_params(sp);
+  const int step = *sp.step;
+  const bool noisy = sp.temperature != 0.f;
+  const float inv_t = noisy ? 1.0f / sp.temperature : 1.0f;
+  const int fq = lane >> 4, tl = lane & 15;
+  float scale[4];
+#pragma unroll
+  for (int g = 0; g < 4; ++g) scale[g] = s_scale[g * 16 + tl];
+  LaneState stt;
+#pragma unroll
+  for (int g = 0; g < 4; ++g) { stt.m[g] = -INFINITY; stt.l[g] = 0.f; stt.by[g] = -INFINITY; stt.bz[g] = 0.f; stt.bid[g] = 0x7fffffff; }
+
+  const int n_waves = gridDim.x * 8;
+  const int groups_per_tile = KS / U;
+  int tile = blockIdx.x * 8 + wave;
+  Frag16 cur[U], nxt[U];
+  if (tile < n_tiles) {
+    const uint4* wb = Wp + (size_t)tile * KS * 64 + lane;
+#pragma unroll
+    for (int i = 0; i < U; ++i) cur[i].n = __builtin_nontemporal_load((const u32x4*)(wb + (size_t)i * 64));
+  }
+  f32x4 acc[4];
+#pragma unroll
+  for (int g = 0; g < 4; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+  int grp = 0;
+  while (tile < n_tiles) {
+    // prefetch the next group (of this tile, or the first of the wave's next tile)
+    int ntile = tile, ngrp = grp + 1;
+    if (ngrp == groups_per_tile) { ngrp = 0; ntile = tile + n_waves; }
+    if (ntile < n_tiles) {
+      const uint4* wb = Wp + ((size_t)ntile * KS + (size_t)ngrp * U) * 64 + lane;
+#pragma unroll
+      for (int i = 0; i < U; ++i) nxt[i].n = __builtin_nontemporal_load((const u32x4*)(wb + (size_t)i * 64));
+    }
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      const int ks = grp * U + i;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        Frag16 x; x.u = xs[(ks * 4 + g) * 64 + lane];
+        acc[g] = mfma16(cur[i], x, acc[g]);
+      }
+    }
+    if (grp == groups_per_tile - 1) {
+      const int v0 = tile * 16 + fq * 4;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float z[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) z[j] = acc[g][j] * scale[g];
+        const float mt = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+        const float mn = fmaxf(stt.m[g], mt);
+        stt.l[g] = stt.l[g] * __expf(stt.m[g] - mn) + ((__expf(z[0] - mn) + __expf(z[1] - mn)) + (__expf(z[2] - mn) + __expf(z[3] - mn)));
+        stt.m[g] = mn;
+        float gn[4] = {0.f, 0.f, 0.f, 0.f};
+        if (noisy) gumbel4(sp.seed_lo, sp.seed_hi, (uint32_t)(seq0 + g * 16 + tl), (uint32_t)step, (uint32_t)(v0 >> 2), gn);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float y = noisy ? z[j] * inv_t + gn[j] : z[j];
+          if (y > stt.by[g]) { stt.by[g] = y; stt.bz[g] = z[j]; stt.bid[g] = v0 + j; }   // ids ascend: ties keep the lower id
+        }
+        acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < U; ++i) cur[i] = nxt[i];
+    tile = ntile; grp = ngrp;
+  }
+  // merge the 4 lanes that share a token (fixed order), then the 8 waves, one row of partials per token
+  __syncthreads();          // everybody is done reading xs: reuse it
+  float* sm = (float*)xs;   // [8 waves][64 tokens][5]
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    LseAcc a; a.m = stt.m[g]; a.l = stt.l[g];
+    BestAcc b; b.y = stt.by[g]; b.z = stt.bz[g]; b.id = stt.bid[g];
+#pragma unroll
+    for (int o = 16; o <= 32; o <<= 1) {
+      a.merge(__shfl_xor(a.m, o, 64), __shfl_xor(a.l, o, 64));
+      b.add(__shfl_xor(b.y, o, 64), __shfl_xor(b.z, o, 64), __shfl_xor(b.id, o, 64));
+    }
+    if (fq == 0) {
+      float* p = sm + ((size_t)wave * 64 + g * 16 + tl) * 5;
+      p[0] = a.m; p[1] = a.l; p[2] = b.y; p[3] = b.z; ((int*)p)[4] = b.id;
+    }
+  }
+  __syncthreads();
+  if (tid < 64) {
+    LseAcc a; a.init();
+    BestAcc b; b.init();
+    for (int w = 0; w < 8; ++w) {
+      const float* p = sm + ((size_t)w * 64 + tid) * 5;
+      a.merge(p[0], p[1]);
+      b.add(p[2], p[3], ((const int*)p)[4]);
+    }
+    float* p = partials + ((size_t)blockIdx.x * 64 + tid) * 5;
+    p[0] = a.m; p[1] = a.l; p[2] = b.y; p[3] = b.z; ((int*)p)[4] = b.id;
+  }
+}
+
+// Merge the per-workgroup partials of one sequence, write its token and log-prob, and gather the
+// token's embedding row as the input of the next decode step (residual row, X16 row for the first
+// layer's norm gain, sum of squares).  One workgroup of 128 threads per sequence.
+__global__ void __launch_bounds__(128) k_lmhead_merge_embed(const float* __restrict__ partials, int n_wg, int seq0,
+                                                            SampleParams sp, const bf16* __restrict__ embed, int d,
+                                                            const float* __restrict__ gain, float* __restrict__ h,
+                                                            uint4* __restrict__ xp, float* __restrict__ ssq) {
+  __shared__ float red[2];
+  __shared__ int s_tok;
+  const int r = blockIdx.x, lane = threadIdx.x & 63;
+  if (threadIdx.x < 64) {
+    LseAcc a; a.init();
+    BestAcc b; b.init();
+    for (int w = lane; w < n_wg; w += 64) {
+      const float* p = partials + ((size_t)w * 64 + r) * 5;
+      a.merge(p[0], p[1]);
+      b.add(p[2], p[3], ((const int*)p)[4]);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      a.merge(__shfl_xor(a.m, o, 64), __shfl_xor(a.l, o, 64));
+      b.add(__shfl_xor(b.y, o, 64), __shfl_xor(b.z, o, 64), __shfl_xor(b.id, o, 64));
+    }
+    if (lane == 0) {
+      const int step = *sp.step;
+      const size_t o = (size_t)(seq0 + r) * sp.max_new + step;
+      sp.out_tokens[o] = b.id;
+      sp.out_logprobs[o] = b.z - (a.m + logf(a.l));
+      s_tok = b.id;
+    }
+  }
+  __syncthreads();
+  embed_row_x16(embed, s_tok, seq0 + r, d, gain, h, xp, ssq, red);
+}
+
+size_t d_lmhead_sample_partial_floats() { return (size_t)256 * 64 * 5; }
+
+template <int U>
+static hipError_t launch_lmhead(const uint4* Wp, const uint4* Xp, int KS, int n_tiles, const float* ssq, int ssq_parts,
+                                int s_pad, int norm_dim, float eps, int n_rows, int seq0, SampleParams sp, float* partials,
+                                int n_wg, hipStream_t st) {
+  static bool attr_done = false;
+  const size_t smem = (size_t)KS * 256 * sizeof(uint4) < 8 * 64 * 5 * 4 ? 8 * 64 * 5 * 4 : (size_t)KS * 256 * sizeof(uint4);
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)k_lmhead_sample16<U>, hipFuncAttributeMaxDynamicSharedMemorySize, 131072);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  k_lmhead_sample16<U><<<n_wg, 512, smem, st>>>(Wp, Xp, KS, n_tiles, ssq, ssq_parts, s_pad, norm_dim, eps, n_rows, seq0, sp,
+                                                partials);
+  return hipGetLastError();
+}
+
+bool d_lmhead_sample_supported(int K, int n_rows) { return n_rows <= 64 && K % 32 == 0 && (size_t)K * 128 <= 131072; }
+
+hipError_t d_lmhead_sample(const void* Wp, const void* Xp, int K, int V, const float* ssq, int ssq_parts, int s_pad,
+                           float eps, int n_rows, SampleParams sp, float* partials, const void* embed,
+                           const float* gain_first, float* h, void* xp_first, float* ssq_first, hipStream_t st) {
+  if (!d_lmhead_sample_supported(K, n_rows) || V % 16 != 0 || ssq_parts > 8 * kSsqPerThread) return hipErrorInvalidValue;
+  const int KS = K / 32, n_tiles = V / 16;
+  int n_wg = 256;
+  if (n_wg > (n_tiles + 7) / 8) n_wg = (n_tiles + 7) / 8;
+  hipError_t e;
+  {
+    ProfScope prof_(KID_LMHEAD_SAMPLE, st);
+    if (KS % 7 == 0)
+      e = launch_lmhead<7>((const uint4*)Wp, (const uint4*)Xp, KS, n_tiles, ssq, ssq_parts, s_pad, K, eps, n_rows, 0, sp, partials, n_wg, st);
+    else if (KS % 4 == 0)
+      e = launch_lmhead<4>((const uint4*)Wp, (const uint4*)Xp, KS, n_tiles, ssq, ssq_parts, s_pad, K, eps, n_rows, 0, sp, partials, n_wg, st);
+    else
+      e = launch_lmhead<1>((const uint4*)Wp, (const uint4*)Xp, KS, n_tiles, ssq, ssq_parts, s_pad, K, eps, n_rows, 0, sp, partials, n_wg, st);
+  }
+  if (e != hipSuccess) return e;
+  ProfScope prof2_(KID_LMHEAD_SAMPLE_MERGE, st);
+  k_lmhead_merge_embed<<<n_rows, 128, 0, st>>>(partials, n_wg, 0, sp, (const bf16*)embed, K, gain_first, h, (uint4*)xp_first,
+                                               ssq_first);
+  return hipGetLastError();
+}
+
+// =======================================================================================
+// Decode attention over the paged KV cache, fused with rotary + KV append of the new token.
+// One workgroup (4 waves) per (sequence, KV head); all query heads of the group ride together as
+// the 16 columns of 16x16x32 MFMAs.  S^T = K Q^T (tokens x queries) so that each lane owns one
+// query column: the running max / sum are per-lane scalars plus two cross-lane shuffles, and the
+// probabilities a lane produces are exactly its operand of O^T = V^T P^T.  Token rows are permuted
+// inside a 32-token page pair so that a lane's 8 probabilities are 8 consecutive tokens, which is
+// what the token-minor V page delivers in one 16-byte load.  Waves take page pairs round-robin and
+// are merged through LDS.  The output goes out in X16 order (the O projection's operand).
+// ---------------------------------------------------------------------------------------
+template <int HD, int NW>
+__global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __restrict__ qkv,
+                                                               const float2* __restrict__ rope, RowMap rm, KVCache kv,
+                                                               uint4* __restrict__ out, int n_q_heads) {
+  constexpr int KK = HD / 32;   // k steps of S^T = K Q^T
+  constexpr int DT = HD / 16;   // 16-row tiles of O^T
+  __shared__ __attribute__((aligned(16))) bf16 qs[16 * HD];
+  __shared__ __attribute__((aligned(16))) bf16 knew[HD];
+  __shared__ __attribute__((aligned(16))) bf16 vnew[HD];
+  __shared__ float sm_m[NW][16], sm_l[NW][16];
+  __shared__ float sm_o[NW][HD][16];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int hkv = kv.n_kv_heads, rep = n_q_heads / hkv;
+  const int s = blockIdx.x / hkv, kvh = blockIdx.x % hkv;
+  int seq, pos;
+  rm.get(s, seq, pos);
+  const int ctx = pos + 1;
+  const int* pt = kv.page_table + (size_t)seq * kv.pages_per_seq;
+  bf16* kpool = (bf16*)kv.k;
+  bf16* vpool = (bf16*)kv.v;
+  const size_t page_elems = (size_t)hkv * kPageTokens * HD;
+  const int new_page = pt[pos / kPageTokens], new_slot = pos % kPageTokens;
+  // ---- rotary on the group's queries and the new key; append key / value -------------------
+  {
+    const int half = HD / 2;
+    const float* row = qkv + (size_t)s * (n_q_heads + 2 * hkv) * HD;
+    for (int idx = tid; idx < 16 * half; idx += NW * 64) {
+      const int r = idx / half, i = idx % half;
+      float r1 = 0.f, r2 = 0.f;
+      if (r < rep) {
+        const float* x = row + (size_t)(kvh * rep + r) * HD;
+        const float2 cs = rope[(size_t)pos * half + i];
+        r1 = x[i] * cs.x - x[i + half] * cs.y;
+        r2 = x[i + half] * cs.x + x[i] * cs.y;
+      }
+      qs[r * HD + i] = (bf16)r1;
+      qs[r * HD + i + half] = (bf16)r2;
+    }
+    for (int i = tid; i < half; i += NW * 64) {
+      const float* x = row + (size_t)(n_q_heads + kvh) * HD;
+      const float2 cs = rope[(size_t)pos * half + i];
+      bf16* kp = kpool + (size_t)new_page * page_elems + ((size_t)kvh * kPageTokens + new_slot) * HD;
+      const bf16 k1 = (bf16)(x[i] * cs.x - x[i + half] * cs.y), k2 = (bf16)(x[i + half] * cs.x + x[i] * cs.y);
+      kp[i] = k1; kp[i + half] = k2;
+      knew[i] = k1; knew[i + half] = k2;
+    }
+    for (int i = tid; i < HD; i += NW * 64) {
+      const float* x = row + (size_t)(n_q_heads + hkv + kvh) * HD;
+      const bf16 vv = (bf16)x[i];
+      vpool[(size_t)new_page * page_elems + ((size_t)kvh * HD + i) * kPageTokens + new_slot] = vv;
+      vnew[i] = vv;
+    }
+  }
+  __syncthreads();
+  const int qcol = lane & 15, grp = lane >> 4;
+  Frag16 qf[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) qf[kk].u = *(const uint4*)(qs + qcol * HD + kk * 32 + grp * 8);
+  const float scale = 1.0f / sqrtf((float)HD);
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x4 o[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int npairs = (ctx + 31) / 32;
+  const int last_page = (ctx - 1) / kPageTokens;
+  for (int pp = wave; pp < npairs; pp += NW) {
+    const int pa = pt[2 * pp];
+    const int pb = pt[min(2 * pp + 1, last_page)];
+    // issue every load of the pair first: K rows of the two score tiles, then the V tile
+    // key rows: tile t row r is pair-token 8 (r / 4) + 4 t + r % 4
+    Frag16 kf[2][KK], vf[DT];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int r = lane & 15;
+      const int ptok = 8 * (r >> 2) + 4 * t + (r & 3);
+      const bf16* kp = kpool + (size_t)(ptok < 16 ? pa : pb) * page_elems + ((size_t)kvh * kPageTokens + (ptok & 15)) * HD;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) kf[t][kk].u = *(const uint4*)(kp + kk * 32 + grp * 8);
+    }
+    const bf16* vp = vpool + (size_t)(grp < 2 ? pa : pb) * page_elems + (size_t)kvh * HD * kPageTokens + (grp & 1) * 8;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) vf[dt].u = *(const uint4*)(vp + (size_t)(dt * 16 + (lane & 15)) * kPageTokens);
+    // the token appended by this workgroup comes from LDS, not from the global copy written above
+    if (pp == pos / 32) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int r = lane & 15;
+        const int ptok = 8 * (r >> 2) + 4 * t + (r & 3);
+        if (ptok == pos % 32) {
+#pragma unroll
+          for (int kk = 0; kk < KK; ++kk) kf[t][kk].u = *(const uint4*)(knew + kk * 32 + grp * 8);
+        }
+      }
+      if (grp == (pos % 32) / 8) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) vf[dt].v[pos % 8] = vnew[dt * 16 + (lane & 15)];
+      }
+    }
+    f32x4 sc[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      sc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) sc[t] = mfma16(kf[t][kk], qf[kk], sc[t]);
+    }
+    // lane (query qcol, group grp) now holds pair-tokens 8 grp + e, e = 4 t + j
+    float p[8];
+    float m_loc = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int n = pp * 32 + 8 * grp + e;
+      const float sv = sc[e >> 2][e & 3] * scale;
+      p[e] = (n < ctx) ? sv : -INFINITY;
+      m_loc = fmaxf(m_loc, p[e]);
+    }
+    m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 16, 64));
+    m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, 64));
+    const float m_new = fmaxf(m_run, m_loc);
+    const float alpha = __expf(m_run - m_new);
+    float psum = 0.f;
+    Frag16 pf;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float pe = __expf(p[e] - m_new);
+      psum += pe;
+      pf.v[e] = (bf16)pe;
+    }
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
+    // tokens past the context may hold anything in V (even NaN bit patterns): zero them
+    {
+      const int nvalid = ctx - (pp * 32 + 8 * grp);   // lane's 8 tokens: first nvalid are real
+      if (nvalid < 8) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (e >= nvalid) vf[dt].v[e] = (bf16)0.f;
+      }
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) o[dt][j] *= alpha;
+      o[dt] = mfma16(vf[dt], pf, o[dt]);
+    }
+  }
+  l_run += __shfl_xor(l_run, 16, 64);
+  l_run += __shfl_xor(l_run, 32, 64);
+  if (grp == 0) { sm_m[wave][qcol] = m_run; sm_l[wave][qcol] = l_run; }
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) sm_o[wave][dt * 16 + grp * 4 + j][qcol] = o[dt][j];
+  __syncthreads();
+  // thread -> (query q, 8 consecutive head dims): one 16-byte chunk of the X16 output
+  const int KSo = (n_q_heads * HD) >> 5;
+  for (int idx = tid; idx < rep * (HD / 8); idx += NW * 64) {
+    const int q = idx / (HD / 8), d0 = (idx % (HD / 8)) * 8;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) mx = fmaxf(mx, sm_m[w][q]);
+    float den = 0.f, wgt[NW];
+#pragma unroll
+    for (int w = 0; w < NW; ++w) { wgt[w] = __expf(sm_m[w][q] - mx); den += wgt[w] * sm_l[w][q]; }
+    const float inv = 1.0f / den;
+    Frag16 ov;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float num = 0.f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) num += wgt[w] * sm_o[w][d0 + e][q];
+      ov.v[e] = (bf16)(num * inv);
+    }
+    out[x16_chunk(s, (kvh * rep + q) * HD + d0, KSo)] = ov.u;
+  }
+}
+
+hipError_t d_decode_attention(const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* out, int S, int n_q_heads,
+                              hipStream_t st) {
+  ProfScope prof_(KID_DECODE_ATTN, st);
+  const int grid = S * kv.n_kv_heads;
+  if (kv.head_dim == 64)
+    k_decode_attention16<64, 4><<<grid, 256, 0, st>>>(qkv, rope, rm, kv, (uint4*)out, n_q_heads);
+  else if (kv.head_dim == 128)
+    k_decode_attention16<128, 4><<<grid, 256, 0, st>>>(qkv, rope, rm, kv, (uint4*)out, n_q_heads);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+}  // namespace sapo
