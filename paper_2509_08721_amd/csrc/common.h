@@ -215,6 +215,8 @@ hipError_t m_lmhead_score(const void* X, const void* Wp, int max_rows, const int
                           const int* row_seq_pos, const int32_t* tokens, int T, float* partials, float* out_logprobs,
                           hipStream_t st);
 size_t m_lmhead_score_partial_floats(int max_rows);
+// causal GQA attention over rows laid out [n_seq, rm.T] (block mode), K/V from the paged cache
+hipError_t m_flash_attention(const void* q, RowMap rm, KVCache kv, void* out, int n_seq, int n_q_heads, hipStream_t st);
 
 // decode kernels (kernels_decode.hip) -------------------------------------------------------
 enum { SKM_STORE = 0, SKM_RESID = 1, SKM_SWIGLU = 2 };

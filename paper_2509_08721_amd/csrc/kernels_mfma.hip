@@ -281,4 +281,152 @@ hipError_t m_lmhead_score(const void* X, const void* Wp, int max_rows, const int
   return hipGetLastError();
 }
 
+// =======================================================================================
+// Causal GQA attention for prefill and scoring (many positions per sequence), MFMA 16x16x32.
+// grid (64-position blocks, longest first; sequences x KV heads; groups of HPW query heads).
+// A wave owns 16 query positions and up to HPW query heads that share the KV head, and walks the
+// keys 0 .. last query position in 32-key page pairs read straight from the paged cache into
+// fragment registers: S^T = K Q^T puts one query column in each lane, so the running max / sum are
+// per-lane scalars (plus two shuffles) and the probabilities a lane produces are its operand of
+// O^T = V^T P^T; key rows are permuted inside a pair so that a lane's 8 probabilities are 8
+// consecutive tokens, the unit the token-minor V page delivers in one 16-byte load.  No LDS, no
+// block-level synchronisation; waves never exchange data.
+// ---------------------------------------------------------------------------------------
+template <int HD, int HPW>
+__global__ void __launch_bounds__(256) k_flash_attention(const bf16* __restrict__ q, RowMap rm, KVCache kv,
+                                                         bf16* __restrict__ out, int n_q_heads) {
+  constexpr int KK = HD / 32, DT = HD / 16;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int qcol = lane & 15, grp = lane >> 4;
+  const int T = rm.T;
+  const int qb = gridDim.x - 1 - blockIdx.x;
+  const int hkv = kv.n_kv_heads, rep = n_q_heads / hkv;
+  const int sblk = blockIdx.y / hkv, kvh = blockIdx.y % hkv;
+  const int h0 = blockIdx.z * HPW;
+  const int nh = min(HPW, rep - h0);
+  const int q0 = qb * 64 + wave * 16;
+  if (q0 >= T) return;
+  const int* pt = kv.page_table + (size_t)(sblk * rm.seq_stride) * kv.pages_per_seq;
+  const size_t row0 = (size_t)sblk * T;
+  const int qpos = min(q0 + qcol, T - 1);   // columns past T repeat the last position and are not stored
+  const size_t qstride = (size_t)n_q_heads * HD;
+  Frag qf[HPW][KK];
+#pragma unroll
+  for (int h = 0; h < HPW; ++h)
+    if (h < nh) {
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+        qf[h][kk].u = *(const uint4*)(q + (row0 + qpos) * qstride + (size_t)(kvh * rep + h0 + h) * HD + kk * 32 + grp * 8);
+    }
+  float m_run[HPW], l_run[HPW];
+  f32x4 o[HPW][DT];
+#pragma unroll
+  for (int h = 0; h < HPW; ++h) {
+    m_run[h] = -INFINITY; l_run[h] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) o[h][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  const float scale2 = 1.4426950408889634f / sqrtf((float)HD);   // scores in units of log2
+  const int q_hi = min(q0 + 15, T - 1);
+  const int npairs = q_hi / 32 + 1;
+  const int last_page = q_hi / kPageTokens;
+  const bf16* kpool = (const bf16*)kv.k;
+  const bf16* vpool = (const bf16*)kv.v;
+  const size_t page_elems = (size_t)hkv * kPageTokens * HD;
+  for (int pp = 0; pp < npairs; ++pp) {
+    const int pa = pt[2 * pp];
+    const int pb = pt[min(2 * pp + 1, last_page)];
+    Frag kf[2][KK], vf[DT];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int r = lane & 15;
+      const int ptok = 8 * (r >> 2) + 4 * t + (r & 3);   // key row r of score tile t
+      const bf16* kp = kpool + (size_t)(ptok < 16 ? pa : pb) * page_elems + ((size_t)kvh * kPageTokens + (ptok & 15)) * HD;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) kf[t][kk].u = *(const uint4*)(kp + kk * 32 + grp * 8);
+    }
+    const bf16* vp = vpool + (size_t)(grp < 2 ? pa : pb) * page_elems + (size_t)kvh * HD * kPageTokens + (grp & 1) * 8;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) vf[dt].u = *(const uint4*)(vp + (size_t)(dt * 16 + (lane & 15)) * kPageTokens);
+    const bool diag = pp * 32 + 31 > q0;   // some (query, key) of the pair is masked
+#pragma unroll
+    for (int h = 0; h < HPW; ++h) {
+      if (h >= nh) continue;
+      f32x4 sc[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        sc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) sc[t] = mfma16(kf[t][kk], qf[h][kk], sc[t]);
+      }
+      // lane (query qcol, group grp) holds keys pp*32 + 8 grp + e, e = 4 t + j
+      float p[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) p[e] = sc[e >> 2][e & 3] * scale2;
+      if (diag) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (pp * 32 + 8 * grp + e > qpos) p[e] = -INFINITY;
+      }
+      float m_loc = fmaxf(fmaxf(fmaxf(p[0], p[1]), fmaxf(p[2], p[3])), fmaxf(fmaxf(p[4], p[5]), fmaxf(p[6], p[7])));
+      m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 16, 64));
+      m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, 64));
+      const float m_new = fmaxf(m_run[h], m_loc);   // finite: key 0 is visible to every query
+      const float alpha = exp2f(m_run[h] - m_new);
+      float psum = 0.f;
+      Frag pf;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float pe = exp2f(p[e] - m_new);
+        psum += pe;
+        pf.v[e] = (bf16)pe;
+      }
+      l_run[h] = l_run[h] * alpha + psum;
+      m_run[h] = m_new;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[h][dt][j] *= alpha;
+        o[h][dt] = mfma16(vf[dt], pf, o[h][dt]);
+      }
+    }
+  }
+  if (q0 + qcol >= T) return;
+#pragma unroll
+  for (int h = 0; h < HPW; ++h) {
+    if (h >= nh) continue;
+    float l = l_run[h];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    const float inv = 1.0f / l;
+    bf16* op = out + (row0 + qpos) * qstride + (size_t)(kvh * rep + h0 + h) * HD + grp * 4;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      bf16x4 ov;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) ov[j] = (bf16)(o[h][dt][j] * inv);
+      *(bf16x4*)(op + dt * 16) = ov;
+    }
+  }
+}
+
+hipError_t m_flash_attention(const void* q, RowMap rm, KVCache kv, void* out, int n_seq, int n_q_heads, hipStream_t st) {
+  ProfScope prof_(KID_FLASH_ATTN, st);
+  if (n_seq == 0) return hipSuccess;
+  const int rep = n_q_heads / kv.n_kv_heads;
+  const int nqb = (rm.T + 63) / 64;
+  if (kv.head_dim == 64) {
+    constexpr int HPW = 7;
+    dim3 grid(nqb, n_seq * kv.n_kv_heads, (rep + HPW - 1) / HPW);
+    k_flash_attention<64, HPW><<<grid, 256, 0, st>>>((const bf16*)q, rm, kv, (bf16*)out, n_q_heads);
+  } else if (kv.head_dim == 128) {
+    constexpr int HPW = 3;
+    dim3 grid(nqb, n_seq * kv.n_kv_heads, (rep + HPW - 1) / HPW);
+    k_flash_attention<128, HPW><<<grid, 256, 0, st>>>((const bf16*)q, rm, kv, (bf16*)out, n_q_heads);
+  } else {
+    return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
 }  // namespace sapo
