@@ -156,6 +156,8 @@ def main():
     kernels = {}
     roofline = None
     if not args.no_kernel_profile:
+        # every launch carries two HIP events (on the launch stream) that take the kernel's own
+        # start and end timestamps
         sapo.sapo_profile_start()
         step(999)
         prof = sapo.sapo_profile_stop()

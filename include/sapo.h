@@ -73,7 +73,9 @@ typedef struct sapo_weights sapo_weights; /* opaque, library-owned */
  *     lm_head[vocab, d]  (ignored, may be NULL, when tied_embeddings = 1).
  *   n_tensors must be 1 + 9 * n_layers + 2.
  * The copy is complete once `stream` has been synchronised; after that the caller may free
- * the originals.  Allocates device memory (about the size of the model, twice the embedding).
+ * the originals.  Allocates device memory: bf16 models whose shapes fit the MFMA tiles keep two
+ * fragment-ordered copies of every matrix (one per MFMA shape, for decode and for prefill/scoring)
+ * besides the embedding table, about three times the model size; other models about once.
  */
 int sapo_weights_create(const sapo_model_config* cfg, const void* const* tensors, int n_tensors,
                         void* stream, sapo_weights** out);
@@ -139,8 +141,9 @@ int sapo_debug_gumbel(uint64_t seed, uint32_t seq, uint32_t step, uint32_t v0, i
 
 /*
  * Per-kernel timing for benchmarks.  Between sapo_profile_start() and sapo_profile_stop() every
- * kernel launch the library makes is bracketed by two HIP events on its stream (this slows the
- * calls down; do not time throughput while it is on).  sapo_profile_stop() synchronises the device
+ * kernel launch the library makes carries two HIP events that receive the kernel's own start and
+ * end timestamps on its stream (launches are no longer replayed from a captured graph while it is
+ * on; do not time throughput then).  sapo_profile_stop() synchronises the device
  * and fills, per kernel symbol i < sapo_profile_kernel_count(), the summed duration in ms and the
  * number of launches (host arrays of at least sapo_profile_kernel_count() entries).  Not
  * thread-safe; at most 200000 launches are recorded.
@@ -149,7 +152,6 @@ int sapo_profile_kernel_count(void);
 const char* sapo_profile_kernel_name(int i);
 int sapo_profile_start(void);
 int sapo_profile_stop(double* total_ms, int64_t* launches, int n);
-
 /* Message for the calling thread's last failed call ("" if none). */
 const char* sapo_last_error(void);
 

@@ -37,7 +37,7 @@ static int fail(int code, const char* fmt, ...) {
 extern "C" const char* sapo_last_error(void) { return g_err.c_str(); }
 
 // ---------------------------------------------------------------------------------------
-// per-kernel timing with HIP events (see ProfScope in common.h)
+// per-kernel timing with HIP events (see launch() in common.h)
 // ---------------------------------------------------------------------------------------
 namespace sapo {
 bool g_prof_on = false;
@@ -51,16 +51,12 @@ static hipEvent_t prof_event() {
   (void)hipEventCreate(&e);
   return e;
 }
-void prof_mark(int kid, hipStream_t st, bool begin) {
-  if (begin) {
-    if (g_prof_recs.size() >= kProfMaxRecs) { g_prof_recs.push_back(ProfRec{-1, nullptr, nullptr}); return; }
-    ProfRec r{kid, prof_event(), prof_event()};
-    (void)hipEventRecord(r.e0, st);
-    g_prof_recs.push_back(r);
-  } else {
-    ProfRec& r = g_prof_recs.back();
-    if (r.kid >= 0) (void)hipEventRecord(r.e1, st);
-  }
+void prof_events(int kid, hipEvent_t* e0, hipEvent_t* e1) {
+  if (g_prof_recs.size() >= kProfMaxRecs) return;   // beyond the cap launches go untimed (null events)
+  ProfRec r{kid, prof_event(), prof_event()};
+  g_prof_recs.push_back(r);
+  *e0 = r.e0;
+  *e1 = r.e1;
 }
 }  // namespace sapo
 

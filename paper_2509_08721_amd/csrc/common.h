@@ -1,7 +1,9 @@
 // Internal declarations shared by the translation units of libsapo (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
+#include <tuple>
 #include <stddef.h>
 
 #include "../../include/sapo.h"
@@ -137,21 +139,35 @@ struct SampleParams {
   float* out_logprobs;    // [S, max_new]
 };
 
-// Optional per-kernel timing: when switched on, every launch below is bracketed by two HIP
-// events on its stream; the totals are read back per kernel symbol.  Off by default (the only
-// cost is one branch per launch).
+// Optional per-kernel timing: when switched on, every launch carries two HIP events that take
+// the kernel's start and end timestamps; the totals are read back per kernel symbol.  Off by
+// default (the only cost is one branch per launch).
 enum KernelId {
   KID_EMBED = 0, KID_RMSNORM, KID_GEMM_GENERIC, KID_ROPE_APPEND, KID_ATTN_GENERIC, KID_SWIGLU, KID_SAMPLE_ROWS,
   KID_SCORE_ROWS, KID_MISC, KID_GEMM_BIG, KID_LMHEAD_SCORE, KID_LMHEAD_SCORE_MERGE, KID_GEMM_SKINNY,
   KID_LMHEAD_SAMPLE, KID_LMHEAD_SAMPLE_MERGE, KID_DECODE_ATTN, KID_FLASH_ATTN, KID_COUNT
 };
 extern bool g_prof_on;
-void prof_mark(int kid, hipStream_t st, bool begin);
-struct ProfScope {
-  int kid; hipStream_t st;
-  ProfScope(int k, hipStream_t s) : kid(k), st(s) { if (g_prof_on) prof_mark(kid, st, true); }
-  ~ProfScope() { if (g_prof_on) prof_mark(kid, st, false); }
-};
+// A pair of events for one profiled launch of kernel `kid` (recorded for sapo_profile_stop).
+void prof_events(int kid, hipEvent_t* e0, hipEvent_t* e1);
+
+// Every kernel launch of the library goes through here.  Normally a plain launch; while
+// profiling, the launch carries two events that receive the kernel's own start and end
+// timestamps (the figures a kernel trace reports, without the launch gaps around them).
+template <typename... KArgs, typename... Args>
+inline hipError_t launch(int kid, void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t smem, hipStream_t st,
+                         Args... args) {
+  static_assert(sizeof...(KArgs) == sizeof...(Args), "argument count mismatch");
+  std::tuple<KArgs...> vals{static_cast<KArgs>(args)...};
+  void* ptrs[sizeof...(KArgs) + 1];
+  std::apply([&](auto&... v) { int i = 0; ((ptrs[i++] = (void*)&v), ...); }, vals);
+  if (g_prof_on) {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    prof_events(kid, &e0, &e1);
+    return hipExtLaunchKernel((const void*)kernel, grid, block, ptrs, smem, st, e0, e1, 0);
+  }
+  return hipLaunchKernel((const void*)kernel, grid, block, ptrs, smem, st);
+}
 
 __device__ __forceinline__ void resolve_sample_params(SampleParams& sp) {
   if (sp.dyn) {

@@ -57,12 +57,10 @@ __global__ void k_pack_weight16(const bf16* __restrict__ src, int n_rows, int K,
 }
 hipError_t d_pack_weight16(const void* src, int n_rows, int K, void* dst, int dst_tile0, int dst_tile_stride,
                            hipStream_t st) {
-  ProfScope prof_(KID_MISC, st);
   const size_t total = (size_t)(n_rows / 16) * (K / 32) * 64;
   if (total == 0) return hipSuccess;
-  k_pack_weight16<<<(unsigned)((total + 255) / 256), 256, 0, st>>>((const bf16*)src, n_rows, K, (uint4*)dst, dst_tile0,
+  return launch(KID_MISC, k_pack_weight16, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16*)src, n_rows, K, (uint4*)dst, dst_tile0,
                                                                     dst_tile_stride);
-  return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------
@@ -254,12 +252,10 @@ static hipError_t launch_skinny(const SkinnyArgs& a, hipStream_t st) {
   const int units = a.N / 16 / NT;
   const int blocks = (a.n_rows + 63) / 64;
   const int gx = (units + 7) / 8 * 8 * (4 / TG);
-  k_skinny16<NT, TG, R, MODE><<<dim3(gx, blocks), 512, smem, st>>>(a, units);
-  return hipGetLastError();
+  return launch(KID_GEMM_SKINNY, k_skinny16<NT, TG, R, MODE>, dim3(gx, blocks), dim3(512), smem, st, a, units);
 }
 
 hipError_t d_gemm_skinny(const SkinnyArgs& a, int mode, hipStream_t st) {
-  ProfScope prof_(KID_GEMM_SKINNY, st);
   if (a.K % 32 != 0 || a.N % 16 != 0 || a.n_rows <= 0) return hipErrorInvalidValue;
   if (mode != SKM_RESID && a.ssq_parts > 8 * kSsqPerThread) return hipErrorInvalidValue;
   const int per_wave = ((a.K >> 5) + 7) / 8;   // k steps per wave
@@ -313,9 +309,7 @@ __global__ void __launch_bounds__(128) k_pack_rows_x16(const float* __restrict__
   if (threadIdx.x == 0) ssq[row] = ss;
 }
 hipError_t d_pack_rows_x16(const float* h, const float* gain, int M, int d, void* xp, float* ssq, hipStream_t st) {
-  ProfScope prof_(KID_MISC, st);
-  k_pack_rows_x16<<<M, 128, 0, st>>>(h, gain, d, (uint4*)xp, ssq);
-  return hipGetLastError();
+  return launch(KID_MISC, k_pack_rows_x16, dim3(M), dim3(128), 0, st, h, gain, d, (uint4*)xp, ssq);
 }
 
 // Embedding row of token id `tok` -> h[row] (fp32), X16 bf16(h * gain), ssq[row].  128 threads.
@@ -347,9 +341,7 @@ __global__ void __launch_bounds__(128) k_embed_x16(const int32_t* __restrict__ t
 }
 hipError_t d_embed_x16(const int32_t* tokens, int tok_stride, const int* step, const void* embed, int M, int d,
                        const float* gain, float* h, void* xp, float* ssq, hipStream_t st) {
-  ProfScope prof_(KID_EMBED, st);
-  k_embed_x16<<<M, 128, 0, st>>>(tokens, tok_stride, step, (const bf16*)embed, d, gain, h, (uint4*)xp, ssq);
-  return hipGetLastError();
+  return launch(KID_EMBED, k_embed_x16, dim3(M), dim3(128), 0, st, tokens, tok_stride, step, (const bf16*)embed, d, gain, h, (uint4*)xp, ssq);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -529,9 +521,8 @@ static hipError_t launch_lmhead(const uint4* Wp, const uint4* Xp, int KS, int n_
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  k_lmhead_sample16<U><<<n_wg, 512, smem, st>>>(Wp, Xp, KS, n_tiles, ssq, ssq_parts, s_pad, norm_dim, eps, n_rows, seq0, sp,
+  return launch(KID_LMHEAD_SAMPLE, k_lmhead_sample16<U>, dim3(n_wg), dim3(512), smem, st, Wp, Xp, KS, n_tiles, ssq, ssq_parts, s_pad, norm_dim, eps, n_rows, seq0, sp,
                                                 partials);
-  return hipGetLastError();
 }
 
 bool d_lmhead_sample_supported(int K, int n_rows) { return n_rows <= 64 && K % 32 == 0 && (size_t)K * 128 <= 131072; }
@@ -545,7 +536,6 @@ hipError_t d_lmhead_sample(const void* Wp, const void* Xp, int K, int V, const f
   if (n_wg > (n_tiles + 7) / 8) n_wg = (n_tiles + 7) / 8;
   hipError_t e;
   {
-    ProfScope prof_(KID_LMHEAD_SAMPLE, st);
     if (KS % 7 == 0)
       e = launch_lmhead<7>((const uint4*)Wp, (const uint4*)Xp, KS, n_tiles, ssq, ssq_parts, s_pad, K, eps, n_rows, 0, sp, partials, n_wg, st);
     else if (KS % 4 == 0)
@@ -554,10 +544,8 @@ hipError_t d_lmhead_sample(const void* Wp, const void* Xp, int K, int V, const f
       e = launch_lmhead<1>((const uint4*)Wp, (const uint4*)Xp, KS, n_tiles, ssq, ssq_parts, s_pad, K, eps, n_rows, 0, sp, partials, n_wg, st);
   }
   if (e != hipSuccess) return e;
-  ProfScope prof2_(KID_LMHEAD_SAMPLE_MERGE, st);
-  k_lmhead_merge_embed<<<n_rows, 128, 0, st>>>(partials, n_wg, 0, sp, (const bf16*)embed, K, gain_first, h, (uint4*)xp_first,
+  return launch(KID_LMHEAD_SAMPLE_MERGE, k_lmhead_merge_embed, dim3(n_rows), dim3(128), 0, st, partials, n_wg, 0, sp, (const bf16*)embed, K, gain_first, h, (uint4*)xp_first,
                                                ssq_first);
-  return hipGetLastError();
 }
 
 // =======================================================================================
@@ -750,15 +738,12 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
 
 hipError_t d_decode_attention(const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* out, int S, int n_q_heads,
                               hipStream_t st) {
-  ProfScope prof_(KID_DECODE_ATTN, st);
-  const int grid = S * kv.n_kv_heads;
+  const dim3 grid(S * kv.n_kv_heads);
   if (kv.head_dim == 64)
-    k_decode_attention16<64, 4><<<grid, 256, 0, st>>>(qkv, rope, rm, kv, (uint4*)out, n_q_heads);
-  else if (kv.head_dim == 128)
-    k_decode_attention16<128, 4><<<grid, 256, 0, st>>>(qkv, rope, rm, kv, (uint4*)out, n_q_heads);
-  else
-    return hipErrorInvalidValue;
-  return hipGetLastError();
+    return launch(KID_DECODE_ATTN, k_decode_attention16<64, 4>, grid, dim3(256), 0, st, qkv, rope, rm, kv, (uint4*)out, n_q_heads);
+  if (kv.head_dim == 128)
+    return launch(KID_DECODE_ATTN, k_decode_attention16<128, 4>, grid, dim3(256), 0, st, qkv, rope, rm, kv, (uint4*)out, n_q_heads);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace sapo

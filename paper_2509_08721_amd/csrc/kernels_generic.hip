@@ -24,21 +24,15 @@ __global__ void k_fill_f32(float* p, float v, size_t n) {
 __global__ void k_incr(int* p) { if (threadIdx.x == 0) *p += 1; }
 
 hipError_t g_fill_i32(int* p, int v, size_t n, hipStream_t st) {
-  ProfScope prof_(KID_MISC, st);
   if (n == 0) return hipSuccess;
-  k_fill_i32<<<dim3((unsigned)((n + 255) / 256)), 256, 0, st>>>(p, v, n);
-  return hipGetLastError();
+  return launch(KID_MISC, k_fill_i32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, v, n);
 }
 hipError_t g_fill_f32(float* p, float v, size_t n, hipStream_t st) {
-  ProfScope prof_(KID_MISC, st);
   if (n == 0) return hipSuccess;
-  k_fill_f32<<<dim3((unsigned)((n + 255) / 256)), 256, 0, st>>>(p, v, n);
-  return hipGetLastError();
+  return launch(KID_MISC, k_fill_f32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, v, n);
 }
 hipError_t g_incr(int* p, hipStream_t st) {
-  ProfScope prof_(KID_MISC, st);
-  k_incr<<<1, 64, 0, st>>>(p);
-  return hipGetLastError();
+  return launch(KID_MISC, k_incr, dim3(1), dim3(64), 0, st, p);
 }
 
 // Page table: the first `full_prompt_pages` pages of a sequence are its prompt's shared pages,
@@ -51,10 +45,8 @@ __global__ void k_page_table(int* pt, int n_seq, int pages_per_seq, int G, int f
   pt[i] = (j < fp) ? (s / G) * fp + j : n_prompts * fp + s * own + (j - fp);
 }
 hipError_t g_page_table(int* pt, int n_seq, int pages_per_seq, int G, int fp, int n_prompts, hipStream_t st) {
-  ProfScope prof_(KID_MISC, st);
   int n = n_seq * pages_per_seq;
-  k_page_table<<<(n + 255) / 256, 256, 0, st>>>(pt, n_seq, pages_per_seq, G, fp, n_prompts);
-  return hipGetLastError();
+  return launch(KID_MISC, k_page_table, dim3((n + 255) / 256), dim3(256), 0, st, pt, n_seq, pages_per_seq, G, fp, n_prompts);
 }
 
 // Copy the (partially filled) page `page_idx` of each prompt's first sibling to the other
@@ -72,10 +64,10 @@ __global__ void k_copy_partial_page(KVCache kv, int G, int page_idx) {
   }
 }
 hipError_t g_copy_partial_page(int dtype, KVCache kv, int n_prompts, int G, int page_idx, hipStream_t st) {
-  ProfScope prof_(KID_MISC, st);
   if (G <= 1) return hipSuccess;
-  SAPO_DISPATCH_T(dtype, (k_copy_partial_page<T><<<dim3(n_prompts, G - 1), 256, 0, st>>>(kv, G, page_idx)));
-  return hipGetLastError();
+  hipError_t e = hipSuccess;
+  SAPO_DISPATCH_T(dtype, e = launch(KID_MISC, k_copy_partial_page<T>, dim3(n_prompts, G - 1), dim3(256), 0, st, kv, G, page_idx));
+  return e;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -90,9 +82,9 @@ __global__ void k_embed(const int32_t* tokens, int tok_stride, const int* step, 
 }
 hipError_t g_embed(int dtype, const int32_t* tokens, int tok_stride, const int* step, const void* embed, float* h,
                    int M, int d, hipStream_t st) {
-  ProfScope prof_(KID_EMBED, st);
-  SAPO_DISPATCH_T(dtype, (k_embed<T><<<M, 256, 0, st>>>(tokens, tok_stride, step, (const T*)embed, h, d)));
-  return hipGetLastError();
+  hipError_t e = hipSuccess;
+  SAPO_DISPATCH_T(dtype, e = launch(KID_EMBED, k_embed<T>, dim3(M), dim3(256), 0, st, tokens, tok_stride, step, (const T*)embed, h, d));
+  return e;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -121,10 +113,10 @@ __global__ void k_rmsnorm(const float* h, const float* gain, float eps, T* out, 
 }
 hipError_t g_rmsnorm(int dtype, const float* h, const float* gain, float eps, void* out, int M, int d,
                      const int* row_index, hipStream_t st) {
-  ProfScope prof_(KID_RMSNORM, st);
   if (M == 0) return hipSuccess;
-  SAPO_DISPATCH_T(dtype, (k_rmsnorm<T><<<M, 256, 0, st>>>(h, gain, eps, (T*)out, d, row_index)));
-  return hipGetLastError();
+  hipError_t e = hipSuccess;
+  SAPO_DISPATCH_T(dtype, e = launch(KID_RMSNORM, k_rmsnorm<T>, dim3(M), dim3(256), 0, st, h, gain, eps, (T*)out, d, row_index));
+  return e;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -175,14 +167,14 @@ __global__ void __launch_bounds__(256) k_gemm(const T* __restrict__ A, const T* 
 }
 hipError_t g_gemm(int dtype, const void* A, const void* W, float* C, int M, int N, int K, int ldc, GemmEpi epi,
                   hipStream_t st) {
-  ProfScope prof_(KID_GEMM_GENERIC, st);
   if (M == 0 || N == 0) return hipSuccess;
   dim3 grid((N + 63) / 64, (M + 63) / 64);
+  hipError_t e = hipSuccess;
   SAPO_DISPATCH_T(dtype, {
-    if (epi == EPI_ADD_F32) k_gemm<T, EPI_ADD_F32><<<grid, 256, 0, st>>>((const T*)A, (const T*)W, C, M, N, K, ldc);
-    else k_gemm<T, EPI_STORE_F32><<<grid, 256, 0, st>>>((const T*)A, (const T*)W, C, M, N, K, ldc);
+    if (epi == EPI_ADD_F32) e = launch(KID_GEMM_GENERIC, k_gemm<T, EPI_ADD_F32>, grid, dim3(256), 0, st, (const T*)A, (const T*)W, C, M, N, K, ldc);
+    else e = launch(KID_GEMM_GENERIC, k_gemm<T, EPI_STORE_F32>, grid, dim3(256), 0, st, (const T*)A, (const T*)W, C, M, N, K, ldc);
   });
-  return hipGetLastError();
+  return e;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -226,10 +218,10 @@ __global__ void k_rope_append(const float* __restrict__ qkv, const float2* __res
 }
 hipError_t g_rope_append(int dtype, const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* q_out, int M,
                          int n_q_heads, hipStream_t st) {
-  ProfScope prof_(KID_ROPE_APPEND, st);
   if (M == 0) return hipSuccess;
-  SAPO_DISPATCH_T(dtype, (k_rope_append<T><<<M, 256, 0, st>>>(qkv, rope, rm, kv, (T*)q_out, n_q_heads)));
-  return hipGetLastError();
+  hipError_t e = hipSuccess;
+  SAPO_DISPATCH_T(dtype, e = launch(KID_ROPE_APPEND, k_rope_append<T>, dim3(M), dim3(256), 0, st, qkv, rope, rm, kv, (T*)q_out, n_q_heads));
+  return e;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -286,13 +278,13 @@ __global__ void __launch_bounds__(256) k_attention(const T* __restrict__ q, RowM
 }
 hipError_t g_attention(int dtype, const void* q, RowMap rm, KVCache kv, void* out, int M, int n_q_heads, int max_ctx,
                        hipStream_t st) {
-  ProfScope prof_(KID_ATTN_GENERIC, st);
   if (M == 0) return hipSuccess;
   const long items = (long)M * n_q_heads;
   const size_t smem = (size_t)4 * (max_ctx + kv.head_dim) * sizeof(float);
-  SAPO_DISPATCH_T(dtype, (k_attention<T><<<(unsigned)((items + 3) / 4), 256, smem, st>>>((const T*)q, rm, kv, (T*)out,
-                                                                                           M, n_q_heads, max_ctx)));
-  return hipGetLastError();
+  hipError_t e = hipSuccess;
+  SAPO_DISPATCH_T(dtype, e = launch(KID_ATTN_GENERIC, k_attention<T>, dim3((unsigned)((items + 3) / 4)), dim3(256), smem, st, (const T*)q, rm, kv, (T*)out,
+                                                                                           M, n_q_heads, max_ctx));
+  return e;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -307,11 +299,11 @@ __global__ void k_swiglu(const float* __restrict__ gu, T* __restrict__ act, int 
   act[i] = from_f32<T>(g / (1.0f + expf(-g)) * u);
 }
 hipError_t g_swiglu(int dtype, const float* gu, void* act, int M, int F, hipStream_t st) {
-  ProfScope prof_(KID_SWIGLU, st);
   const size_t n = (size_t)M * F;
   if (n == 0) return hipSuccess;
-  SAPO_DISPATCH_T(dtype, (k_swiglu<T><<<(unsigned)((n + 255) / 256), 256, 0, st>>>(gu, (T*)act, M, F)));
-  return hipGetLastError();
+  hipError_t e = hipSuccess;
+  SAPO_DISPATCH_T(dtype, e = launch(KID_SWIGLU, k_swiglu<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, gu, (T*)act, M, F));
+  return e;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -365,9 +357,7 @@ __global__ void __launch_bounds__(256) k_sample_rows(const float* __restrict__ l
   }
 }
 hipError_t g_sample_rows(const float* logits, int n_rows, int G, int V, SampleParams sp, hipStream_t st) {
-  ProfScope prof_(KID_SAMPLE_ROWS, st);
-  k_sample_rows<<<n_rows * G, 256, 0, st>>>(logits, G, V, sp);
-  return hipGetLastError();
+  return launch(KID_SAMPLE_ROWS, k_sample_rows, dim3(n_rows * G), dim3(256), 0, st, logits, G, V, sp);
 }
 
 // log-prob of the teacher-forced token: row i holds the logits after position (s, t-1) where
@@ -390,10 +380,8 @@ __global__ void __launch_bounds__(256) k_score_rows(const float* __restrict__ lo
 }
 hipError_t g_score_rows(const float* logits, int n_rows, int row_offset, int V, const int* row_seq_pos,
                         const int* n_rows_dev, const int32_t* tokens, int T, float* out_logprobs, hipStream_t st) {
-  ProfScope prof_(KID_SCORE_ROWS, st);
   if (n_rows == 0) return hipSuccess;
-  k_score_rows<<<n_rows, 256, 0, st>>>(logits, row_offset, V, row_seq_pos, n_rows_dev, tokens, T, out_logprobs);
-  return hipGetLastError();
+  return launch(KID_SCORE_ROWS, k_score_rows, dim3(n_rows), dim3(256), 0, st, logits, row_offset, V, row_seq_pos, n_rows_dev, tokens, T, out_logprobs);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -417,10 +405,8 @@ __global__ void k_advantages(const float* __restrict__ r, int n_groups, int G, f
   for (int i = 0; i < G; ++i) out[(size_t)g * G + i] = (float)(((double)rg[i] - mu) / (sd + 1e-6));
 }
 hipError_t g_advantages(const float* rewards, int S, int G, float* out, hipStream_t st) {
-  ProfScope prof_(KID_MISC, st);
   const int ng = S / G;
-  k_advantages<<<(ng + 63) / 64, 64, 0, st>>>(rewards, ng, G, out);
-  return hipGetLastError();
+  return launch(KID_MISC, k_advantages, dim3((ng + 63) / 64), dim3(64), 0, st, rewards, ng, G, out);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -465,9 +451,7 @@ __global__ void __launch_bounds__(1024) k_masked_rows(const uint8_t* __restrict_
 }
 hipError_t g_masked_rows(const uint8_t* mask, int T, int s0, int ns, int* rows, int* src_rows, int* count,
                          hipStream_t st) {
-  ProfScope prof_(KID_MISC, st);
-  k_masked_rows<<<1, 1024, 0, st>>>(mask, T, s0, ns, rows, src_rows, count);
-  return hipGetLastError();
+  return launch(KID_MISC, k_masked_rows, dim3(1), dim3(1024), 0, st, mask, T, s0, ns, rows, src_rows, count);
 }
 
 // src_rows for a list of (s, t) positions: row s * T + t (debug logits).
@@ -476,9 +460,7 @@ __global__ void k_rows_from_positions(const int* positions, int n, int T, int* s
   if (i < n) src_rows[i] = positions[2 * i] * T + positions[2 * i + 1];
 }
 hipError_t g_rows_from_positions(const int* positions, int n, int T, int* src_rows, hipStream_t st) {
-  ProfScope prof_(KID_MISC, st);
-  k_rows_from_positions<<<(n + 255) / 256, 256, 0, st>>>(positions, n, T, src_rows);
-  return hipGetLastError();
+  return launch(KID_MISC, k_rows_from_positions, dim3((n + 255) / 256), dim3(256), 0, st, positions, n, T, src_rows);
 }
 
 // rows[p] = index of the last prompt position of prompt p in a [P, Lp] block.
@@ -487,9 +469,7 @@ __global__ void k_last_rows(int* rows, int P, int Lp) {
   if (p < P) rows[p] = p * Lp + Lp - 1;
 }
 hipError_t g_last_rows(int* rows, int P, int Lp, hipStream_t st) {
-  ProfScope prof_(KID_MISC, st);
-  k_last_rows<<<(P + 255) / 256, 256, 0, st>>>(rows, P, Lp);
-  return hipGetLastError();
+  return launch(KID_MISC, k_last_rows, dim3((P + 255) / 256), dim3(256), 0, st, rows, P, Lp);
 }
 
 // out[s, :] = h[(s / G) * Lp + Lp - 1, :]: the last prompt position's residual, once per sibling.
@@ -499,9 +479,7 @@ __global__ void k_gather_last_rows(const float* __restrict__ h, float* __restric
   for (int i = threadIdx.x; i < d; i += blockDim.x) out[(size_t)s * d + i] = src[i];
 }
 hipError_t g_gather_last_rows(const float* h, float* out, int S, int G, int Lp, int d, hipStream_t st) {
-  ProfScope prof_(KID_MISC, st);
-  k_gather_last_rows<<<S, 256, 0, st>>>(h, out, G, Lp, d);
-  return hipGetLastError();
+  return launch(KID_MISC, k_gather_last_rows, dim3(S), dim3(256), 0, st, h, out, G, Lp, d);
 }
 
 __global__ void k_gumbel(uint32_t seed_lo, uint32_t seed_hi, uint32_t seq, uint32_t step, uint32_t v0, int n, float* out) {
@@ -514,10 +492,8 @@ __global__ void k_gumbel(uint32_t seed_lo, uint32_t seed_hi, uint32_t seq, uint3
 }
 hipError_t g_gumbel(uint32_t seed_lo, uint32_t seed_hi, uint32_t seq, uint32_t step, uint32_t v0, int n, float* out,
                     hipStream_t st) {
-  ProfScope prof_(KID_MISC, st);
   if (n == 0) return hipSuccess;
-  k_gumbel<<<(n + 255) / 256, 256, 0, st>>>(seed_lo, seed_hi, seq, step, v0, n, out);
-  return hipGetLastError();
+  return launch(KID_MISC, k_gumbel, dim3((n + 255) / 256), dim3(256), 0, st, seed_lo, seed_hi, seq, step, v0, n, out);
 }
 
 }  // namespace sapo

@@ -44,12 +44,10 @@ __global__ void k_pack_weight(const bf16* __restrict__ src, int n_rows, int K, u
 }
 hipError_t m_pack_weight(const void* src, int n_rows, int K, void* dst, int dst_tile0, int dst_tile_stride,
                          hipStream_t st) {
-  ProfScope prof_(KID_MISC, st);
   const size_t total = (size_t)(n_rows / 32) * (K / 16) * 64;
   if (total == 0) return hipSuccess;
-  k_pack_weight<<<(unsigned)((total + 255) / 256), 256, 0, st>>>((const bf16*)src, n_rows, K, (uint4*)dst, dst_tile0,
+  return launch(KID_MISC, k_pack_weight, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16*)src, n_rows, K, (uint4*)dst, dst_tile0,
                                                                   dst_tile_stride);
-  return hipGetLastError();
 }
 
 // =======================================================================================
@@ -169,11 +167,9 @@ __global__ void __launch_bounds__(256) k_gemm_big(const bf16* __restrict__ X, in
   }
 }
 hipError_t m_gemm_big(const void* X, int ldx, const void* Wp, int M, int N, int K, BigEpi epi, hipStream_t st) {
-  ProfScope prof_(KID_GEMM_BIG, st);
   if (M == 0) return hipSuccess;
   dim3 grid(N / 128, (M + 255) / 256);
-  k_gemm_big<<<grid, 256, 0, st>>>((const bf16*)X, ldx, (const uint4*)Wp, M, N, K, epi);
-  return hipGetLastError();
+  return launch(KID_GEMM_BIG, k_gemm_big, grid, dim3(256), 0, st, (const bf16*)X, ldx, (const uint4*)Wp, M, N, K, epi);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -267,18 +263,11 @@ hipError_t m_lmhead_score(const void* X, const void* Wp, int max_rows, const int
                           hipStream_t st) {
   if (max_rows == 0) return hipSuccess;
   dim3 grid((max_rows + 255) / 256, kScoreSplit);
-  hipError_t e;
-  {
-    ProfScope prof_(KID_LMHEAD_SCORE, st);
-    k_lmhead_score<<<grid, 256, 0, st>>>((const bf16*)X, (const uint4*)Wp, max_rows, n_rows_dev, V, K, row_seq_pos,
-                                         tokens, T, partials);
-    e = hipGetLastError();
-  }
+  const hipError_t e = launch(KID_LMHEAD_SCORE, k_lmhead_score, grid, dim3(256), 0, st, (const bf16*)X, (const uint4*)Wp, max_rows,
+                              n_rows_dev, V, K, row_seq_pos, tokens, T, partials);
   if (e != hipSuccess) return e;
-  ProfScope prof2_(KID_LMHEAD_SCORE_MERGE, st);
-  k_lmhead_score_merge<<<(max_rows + 255) / 256, 256, 0, st>>>(partials, max_rows, n_rows_dev, row_seq_pos, T,
+  return launch(KID_LMHEAD_SCORE_MERGE, k_lmhead_score_merge, dim3((max_rows + 255) / 256), dim3(256), 0, st, partials, max_rows, n_rows_dev, row_seq_pos, T,
                                                                out_logprobs);
-  return hipGetLastError();
 }
 
 // =======================================================================================
@@ -411,22 +400,20 @@ __global__ void __launch_bounds__(256) k_flash_attention(const bf16* __restrict_
 }
 
 hipError_t m_flash_attention(const void* q, RowMap rm, KVCache kv, void* out, int n_seq, int n_q_heads, hipStream_t st) {
-  ProfScope prof_(KID_FLASH_ATTN, st);
   if (n_seq == 0) return hipSuccess;
   const int rep = n_q_heads / kv.n_kv_heads;
   const int nqb = (rm.T + 63) / 64;
   if (kv.head_dim == 64) {
     constexpr int HPW = 7;
     dim3 grid(nqb, n_seq * kv.n_kv_heads, (rep + HPW - 1) / HPW);
-    k_flash_attention<64, HPW><<<grid, 256, 0, st>>>((const bf16*)q, rm, kv, (bf16*)out, n_q_heads);
-  } else if (kv.head_dim == 128) {
+    return launch(KID_FLASH_ATTN, k_flash_attention<64, HPW>, grid, dim3(256), 0, st, (const bf16*)q, rm, kv, (bf16*)out, n_q_heads);
+  }
+  if (kv.head_dim == 128) {
     constexpr int HPW = 3;
     dim3 grid(nqb, n_seq * kv.n_kv_heads, (rep + HPW - 1) / HPW);
-    k_flash_attention<128, HPW><<<grid, 256, 0, st>>>((const bf16*)q, rm, kv, (bf16*)out, n_q_heads);
-  } else {
-    return hipErrorInvalidValue;
+    return launch(KID_FLASH_ATTN, k_flash_attention<128, HPW>, grid, dim3(256), 0, st, (const bf16*)q, rm, kv, (bf16*)out, n_q_heads);
   }
-  return hipGetLastError();
+  return hipErrorInvalidValue;
 }
 
 }  // namespace sapo

@@ -270,3 +270,4 @@ def sapo_profile_stop() -> dict:
     cnt = (C.c_int64 * n)()
     _check(lib.sapo_profile_stop(ms, cnt, n))
     return {lib.sapo_profile_kernel_name(i).decode(): (ms[i], int(cnt[i])) for i in range(n) if cnt[i] > 0}
+
