@@ -312,9 +312,9 @@ struct FwdBufs {      // activations for M rows
 static void carve_fwd(Arena& A, const sapo_weights* w, size_t M, FwdBufs& b) {
   const sapo_model_config& c = w->cfg;
   const size_t d = c.d_model, q = (size_t)c.n_q_heads * c.head_dim, kv = (size_t)c.n_kv_heads * c.head_dim, F = c.d_ff;
-  const size_t Mp = (M + 63) / 64 * 64;   // X-packed buffers hold whole 64-token blocks
+  const size_t Mp = (M + 63) / 64 * 64;   // fragment-ordered buffers hold whole 64-token blocks
   b.h = A.take<float>(M * d);
-  b.a = A.take_bytes(M * d * w->elt);
+  b.a = A.take_bytes(Mp * d * w->elt);
   b.qkv = A.take<float>(M * (q + 2 * kv));
   b.q = A.take_bytes(M * q * w->elt);
   b.attn = A.take_bytes(Mp * q * w->elt);
@@ -398,14 +398,14 @@ static int run_layers_big(const sapo_weights* w, const FwdBufs& b, int M, RowMap
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerWeights& lw = w->layers[l];
     const KVCache kvc = layer_cache(w, cb, l);
-    HIP_CK(g_rmsnorm(dt, b.h, lw.attn_norm, c.rms_eps, b.a, M, d, nullptr, st));
-    HIP_CK(m_gemm_big(b.a, d, lw.wqkv, M, q + 2 * kv, d, BigEpi{BIG_STORE_F32, b.qkv, q + 2 * kv, nullptr}, st));
+    HIP_CK(m_rmsnorm_x32(b.h, lw.attn_norm, c.rms_eps, b.a, M, d, nullptr, st));
+    HIP_CK(m_gemm_big(b.a, lw.wqkv, M, q + 2 * kv, d, BigEpi{BIG_STORE_F32, b.qkv, q + 2 * kv, nullptr}, st));
     HIP_CK(g_rope_append(dt, b.qkv, w->rope, rm, kvc, b.q, M, c.n_q_heads, st));
     HIP_CK(m_flash_attention(b.q, rm, kvc, b.attn, M / rm.T, c.n_q_heads, st));
-    HIP_CK(m_gemm_big(b.attn, q, lw.wo, M, d, q, BigEpi{BIG_ADD_F32, b.h, d, nullptr}, st));
-    HIP_CK(g_rmsnorm(dt, b.h, lw.ffn_norm, c.rms_eps, b.a, M, d, nullptr, st));
-    HIP_CK(m_gemm_big(b.a, d, lw.wgu, M, 2 * F, d, BigEpi{BIG_SWIGLU, nullptr, 0, (bf16*)b.act}, st));
-    HIP_CK(m_gemm_big(b.act, F, lw.wdown, M, d, F, BigEpi{BIG_ADD_F32, b.h, d, nullptr}, st));
+    HIP_CK(m_gemm_big(b.attn, lw.wo, M, d, q, BigEpi{BIG_ADD_F32, b.h, d, nullptr}, st));
+    HIP_CK(m_rmsnorm_x32(b.h, lw.ffn_norm, c.rms_eps, b.a, M, d, nullptr, st));
+    HIP_CK(m_gemm_big(b.a, lw.wgu, M, 2 * F, d, BigEpi{BIG_SWIGLU, nullptr, 0, (bf16*)b.act}, st));
+    HIP_CK(m_gemm_big(b.act, lw.wdown, M, d, F, BigEpi{BIG_ADD_F32, b.h, d, nullptr}, st));
   }
   return SAPO_OK;
 }
@@ -513,7 +513,7 @@ static void plan_rollout(const sapo_weights* w, int P, int Lp, int G, int N, cha
   carve_fwd(A, w, pl.M_max, pl.fwd);
   const size_t R = (size_t)(P > pl.S ? P : pl.S);
   pl.h_last = A.take<float>((size_t)pl.S * c.d_model);
-  pl.x_last = A.take_bytes(R * c.d_model * w->elt);
+  pl.x_last = A.take_bytes((R + 63) / 64 * 64 * c.d_model * w->elt);
   pl.fused_lm = w->mfma && d_lmhead_sample_supported(c.d_model, pl.S);
   pl.logits = pl.fused_lm ? nullptr : A.take<float>(R * c.vocab);
   pl.partials = pl.fused_lm ? A.take<float>(d_lmhead_sample_partial_floats()) : nullptr;
@@ -551,11 +551,13 @@ static int sample_step(const sapo_weights* w, const RolloutPlan& pl, const float
                            pl.partials, w->embed, gain_first, pl.fwd.h, pl.dec.xa, pl.dec.ssq_a, st));
     return SAPO_OK;
   }
-  HIP_CK(g_rmsnorm(c.dtype, h, w->final_norm, c.rms_eps, pl.x_last, S, d, nullptr, st));
-  if (w->mfma)
-    HIP_CK(m_gemm_big(pl.x_last, d, w->lm_head, S, V, d, BigEpi{BIG_STORE_F32, pl.logits, V, nullptr}, st));
-  else
+  if (w->mfma) {
+    HIP_CK(m_rmsnorm_x32(h, w->final_norm, c.rms_eps, pl.x_last, S, d, nullptr, st));
+    HIP_CK(m_gemm_big(pl.x_last, w->lm_head, S, V, d, BigEpi{BIG_STORE_F32, pl.logits, V, nullptr}, st));
+  } else {
+    HIP_CK(g_rmsnorm(c.dtype, h, w->final_norm, c.rms_eps, pl.x_last, S, d, nullptr, st));
     HIP_CK(g_gemm(c.dtype, pl.x_last, w->lm_head, pl.logits, S, V, d, V, EPI_STORE_F32, st));
+  }
   HIP_CK(g_sample_rows(pl.logits, S, 1, V, sp, st));
   return SAPO_OK;
 }
@@ -701,9 +703,9 @@ static void plan_score(const sapo_weights* w, int S, int T, int chunk_seqs, size
   pl.src_rows = A.take<int>(R);
   carve_cache(A, w, chunk_seqs, pl.pages_per_seq, (size_t)chunk_seqs * pl.pages_per_seq, pl.cache);
   carve_fwd(A, w, M, pl.fwd);
-  pl.x = A.take_bytes(R * c.d_model * w->elt);
+  pl.x = A.take_bytes((R + 63) / 64 * 64 * c.d_model * w->elt);
   pl.logits = w->mfma ? nullptr : A.take<float>((size_t)pl.row_chunk * c.vocab);
-  pl.partials = w->mfma ? A.take<float>(m_lmhead_score_partial_floats((int)M)) : nullptr;
+  pl.partials = w->mfma ? A.take<float>(m_lmhead_score_partial_floats((int)M, c.vocab)) : nullptr;
   pl.bytes = (A.off + 255) & ~(size_t)255;
 }
 
@@ -762,11 +764,12 @@ extern "C" int sapo_score_logprobs(const sapo_weights* w, const int32_t* tokens,
     const int M = ns * T;
     if ((rc = forward_chunk(w, pl, tokens, s0, ns, st))) return rc;
     HIP_CK(g_masked_rows(completion_mask, T, s0, ns, pl.rows, pl.src_rows, pl.count, st));
-    HIP_CK(g_rmsnorm(c.dtype, pl.fwd.h, w->final_norm, c.rms_eps, pl.x, M, c.d_model, pl.src_rows, st));
     if (w->mfma) {
+      HIP_CK(m_rmsnorm_x32(pl.fwd.h, w->final_norm, c.rms_eps, pl.x, M, c.d_model, pl.src_rows, st));
       HIP_CK(m_lmhead_score(pl.x, w->lm_head, M, pl.count, c.vocab, c.d_model, pl.rows, tokens, T, pl.partials,
                             out_logprobs, st));
     } else {
+      HIP_CK(g_rmsnorm(c.dtype, pl.fwd.h, w->final_norm, c.rms_eps, pl.x, M, c.d_model, pl.src_rows, st));
       for (int r0 = 0; r0 < M; r0 += pl.row_chunk) {
         const int nr = (M - r0 < pl.row_chunk) ? M - r0 : pl.row_chunk;
         HIP_CK(g_gemm(c.dtype, (char*)pl.x + (size_t)r0 * c.d_model * w->elt, w->lm_head, pl.logits, nr, c.vocab,
@@ -804,11 +807,13 @@ extern "C" int sapo_debug_logits(const sapo_weights* w, const int32_t* tokens, i
   if ((rc = clear_cache(pl.cache, c.n_layers, st))) return rc;
   if ((rc = forward_chunk(w, pl, tokens, 0, S, st))) return rc;
   HIP_CK(g_rows_from_positions(positions, n, T, pl.src_rows, st));
-  HIP_CK(g_rmsnorm(c.dtype, pl.fwd.h, w->final_norm, c.rms_eps, pl.x, n, c.d_model, pl.src_rows, st));
-  if (w->mfma)
-    HIP_CK(m_gemm_big(pl.x, c.d_model, w->lm_head, n, c.vocab, c.d_model, BigEpi{BIG_STORE_F32, out_logits, c.vocab, nullptr}, st));
-  else
+  if (w->mfma) {
+    HIP_CK(m_rmsnorm_x32(pl.fwd.h, w->final_norm, c.rms_eps, pl.x, n, c.d_model, pl.src_rows, st));
+    HIP_CK(m_gemm_big(pl.x, w->lm_head, n, c.vocab, c.d_model, BigEpi{BIG_STORE_F32, out_logits, c.vocab, nullptr}, st));
+  } else {
+    HIP_CK(g_rmsnorm(c.dtype, pl.fwd.h, w->final_norm, c.rms_eps, pl.x, n, c.d_model, pl.src_rows, st));
     HIP_CK(g_gemm(c.dtype, pl.x, w->lm_head, out_logits, n, c.vocab, c.d_model, c.vocab, EPI_STORE_F32, st));
+  }
   return SAPO_OK;
 }
 

@@ -220,18 +220,22 @@ struct BigEpi {
   int mode;            // see enum below
   float* out_f32;      // STORE_F32 / ADD_F32: [M, ldc]
   int ldc;
-  bf16* out_bf16;      // SWIGLU: act [M, F]
+  bf16* out_bf16;      // SWIGLU: act, X32 order over F = N / 2
 };
 enum { BIG_STORE_F32 = 0, BIG_ADD_F32 = 1, BIG_SWIGLU = 2 };
 
 hipError_t m_pack_weight(const void* src, int n_rows, int K, void* dst, int dst_tile0, int dst_tile_stride,
                          hipStream_t st);
-hipError_t m_gemm_big(const void* X, int ldx, const void* Wp, int M, int N, int K, BigEpi epi, hipStream_t st);
-hipError_t m_lmhead_score(const void* X, const void* Wp, int max_rows, const int* n_rows_dev, int V, int K,
+// Xp: tokens in X32 fragment order (rows padded to a multiple of 32); Wp: weights in W32 order
+hipError_t m_gemm_big(const void* Xp, const void* Wp, int M, int N, int K, BigEpi epi, hipStream_t st);
+hipError_t m_rmsnorm_x32(const float* h, const float* gain, float eps, void* out, int M, int d, const int* row_index,
+                         hipStream_t st);
+hipError_t m_lmhead_score(const void* Xp, const void* Wp, int max_rows, const int* n_rows_dev, int V, int K,
                           const int* row_seq_pos, const int32_t* tokens, int T, float* partials, float* out_logprobs,
                           hipStream_t st);
-size_t m_lmhead_score_partial_floats(int max_rows);
-// causal GQA attention over rows laid out [n_seq, rm.T] (block mode), K/V from the paged cache
+size_t m_lmhead_score_partial_floats(int max_rows, int V);
+// causal GQA attention over rows laid out [n_seq, rm.T] (block mode), K/V from the paged cache;
+// q row-major, out in X32 order
 hipError_t m_flash_attention(const void* q, RowMap rm, KVCache kv, void* out, int n_seq, int n_q_heads, hipStream_t st);
 
 // decode kernels (kernels_decode.hip) -------------------------------------------------------

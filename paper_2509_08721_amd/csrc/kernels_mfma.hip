@@ -51,111 +51,144 @@ hipError_t m_pack_weight(const void* src, int n_rows, int K, void* dst, int dst_
 }
 
 // =======================================================================================
-// Big GEMM:  C^T[feat, tok] = sum_k W[feat, k] X[tok, k]
-// Workgroup tile 128 features x 256 tokens, 4 waves as 2 (features) x 2 (tokens); each wave owns
-// 64 features x 128 tokens = 2 x 4 MFMA 32x32 tiles.  W fragments go straight from global memory
-// (fragment order, 1 KiB per wave per step) into registers; X is staged through LDS in fragment
-// order, 32 k per stage, double buffered.
-// Accumulator layout: acc[fi][tj][4 i + j] = C^T[feat = fi*32 + (lane/32)*4 + 8 i + j][tok = tj*32 + lane%32].
+// Token-parallel ("big") GEMM:  C[tok, feat] = sum_k X[tok, k] W[feat, k]
+//
+// Both operands are in 32-row fragment order in global memory (one MFMA 32x32x16 operand of one
+// wave = one contiguous 1 KiB block):
+//   W32[((fblk * KS + ks) * 64 + lane)] = W[fblk*32 + lane%32][ks*16 + (lane/32)*8 .. +7],  KS = K / 16
+//   X32[((tblk * KS + ks) * 64 + lane)] = X[tblk*32 + lane%32][ks*16 + (lane/32)*8 .. +7]
+// so a fragment moves from global memory to LDS with one direct-to-LDS load per wave and is read
+// back with one conflict-free ds_read_b128.
+// Workgroup tile 256 tokens x 128 features, 4 waves as 2 (tokens) x 2 (features), each 128 x 64 =
+// 4 x 2 MFMA tiles; 32 k per stage (24 fragments), three stages in an LDS ring with two in flight.
+// Two workgroups fit a compute unit (72 KiB LDS, <= 256 registers), which is what overlaps one
+// workgroup's barrier and LDS latency with the other's MFMAs.
+// The direct-to-LDS loads are issued from inline assembly: the compiler would otherwise wait for
+// all of them before any LDS read, which removes the prefetch distance.  Their completion is
+// awaited with explicit s_waitcnt vmcnt(N) (loads retire in order).
+// Accumulator layout: acc[fi][tj][4 r + j] = C[tok = tj*32 + lane%32][feat = fi*32 + 8 r + (lane/32)*4 + j].
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ void big_mainloop(const bf16* __restrict__ X, int ldx, const uint4* __restrict__ Wp, int M,
-                                             int K, int ft, int tok0, uint4* smem, f32x16 (&acc)[2][4]) {
+__host__ __device__ __forceinline__ size_t x32_chunk(int tok, int k, int KS) {
+  return (((size_t)(tok >> 5) * KS + (k >> 4)) * 64) + (tok & 31) + 32 * ((k >> 3) & 1);
+}
+
+constexpr int kStageFrags = 24;   // 16 token fragments + 8 feature fragments per 32-k stage
+constexpr int kStages = 3;
+constexpr int kBigLds = kStages * kStageFrags * 1024;
+
+__device__ __forceinline__ unsigned lds_addr(const void* p) {
+  return (unsigned)(size_t)(const __attribute__((address_space(3))) void*)p;
+}
+// one wave-wide 1 KiB copy global -> LDS: lane l's 16 bytes land at lds + 16 l
+__device__ __forceinline__ void dma16(const void* g, unsigned lds) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds), "v"(g) : "memory");
+}
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// Block id -> (feature tile bx, token tile by).  Block ids are dealt round-robin to the 8 XCDs, each
+// with its own L2: XCD c owns the token tiles 8 y' + c and walks them in supertiles of 8 token
+// tiles x 8 feature tiles (feature tiles fastest), the 64 workgroups it runs at a time.
+__device__ __forceinline__ bool big_raster(int NX, int NY, int& bx, int& by) {
+  const int NXs = (NX + 7) >> 3;
+  const int b = blockIdx.x, xcd = b & 7, j = b >> 3;
+  const int sti = j >> 6, w = j & 63;
+  bx = (sti % NXs) * 8 + (w & 7);
+  by = ((sti / NXs) * 8 + (w >> 3)) * 8 + xcd;
+  return bx < NX && by < NY;
+}
+static int big_grid(int NX, int NY) { return 8 * ((NX + 7) / 8) * ((((NY + 7) / 8) + 7) / 8) * 64; }
+
+// acc = X[tblk0*32 .. +255][:] . W[fblk0*32 .. +127][:]^T over the whole K.  Token blocks past the end
+// are clamped to the last one (their results are never stored).
+__device__ __forceinline__ void big_mainloop(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int n_tblk,
+                                             int KS, int tblk0, int fblk0, uint4* smem, f32x16 (&acc)[2][4]) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wf = wave & 1, wt = wave >> 1;
-  const int KS = K >> 4, nst = KS >> 1;
-  const uint4* wb0 = Wp + ((size_t)(ft * 4 + wf * 2 + 0) * KS) * 64 + lane;
-  const uint4* wb1 = Wp + ((size_t)(ft * 4 + wf * 2 + 1) * KS) * 64 + lane;
-  uint4 xr[4];
-  Frag wc[4], wn[4];
+  const int nst = KS >> 1;
+  const uint4* src[6];
+  unsigned dst[6];
+#pragma unroll
+  for (int i = 0; i < 6; ++i) {
+    const int f = wave * 6 + i;
+    if (f < 16) {
+      int tb = tblk0 + (f >> 1);
+      if (tb > n_tblk - 1) tb = n_tblk - 1;
+      src[i] = Xp + ((size_t)tb * KS + (f & 1)) * 64 + lane;
+    } else {
+      const int g = f - 16;
+      src[i] = Wp + ((size_t)(fblk0 + (g >> 1)) * KS + (g & 1)) * 64 + lane;
+    }
+    dst[i] = __builtin_amdgcn_readfirstlane(lds_addr(smem + f * 64));
+  }
+  auto issue = [&](int st) {
+    const unsigned sbase = (unsigned)((st % kStages) * kStageFrags * 1024);
+#pragma unroll
+    for (int i = 0; i < 6; ++i) dma16(src[i] + (size_t)st * 128, dst[i] + sbase);
+  };
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
     for (int b = 0; b < 4; ++b)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
-
-  auto load_x = [&](int st) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int c = i * 256 + tid, tok = c >> 2, kc = c & 3;
-      const int gt = tok0 + tok;
-      xr[i] = (gt < M) ? *(const uint4*)(X + (size_t)gt * ldx + st * 32 + kc * 8) : make_uint4(0, 0, 0, 0);
-    }
-  };
-  auto store_x = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int c = i * 256 + tid, tok = c >> 2, kc = c & 3;
-      smem[buf * 1024 + ((kc >> 1) * 8 + (tok >> 5)) * 64 + (tok & 31) + 32 * (kc & 1)] = xr[i];
-    }
-  };
-  auto load_w = [&](int st, Frag* w) {
-#pragma unroll
-    for (int s2 = 0; s2 < 2; ++s2) {
-      w[s2 * 2 + 0].u = wb0[(size_t)(st * 2 + s2) * 64];
-      w[s2 * 2 + 1].u = wb1[(size_t)(st * 2 + s2) * 64];
-    }
-  };
-
-  load_x(0);
-  load_w(0, wc);
-  store_x(0);
-  __syncthreads();
+  wg_barrier();   // a previous pass over the ring (fused LM head) is over in every wave
+  issue(0);
+  if (nst > 1) issue(1);
   for (int st = 0; st < nst; ++st) {
-    const int buf = st & 1;
-    if (st + 1 < nst) {
-      load_x(st + 1);
-      load_w(st + 1, wn);
-    }
+    if (st + 1 < nst) wait_vmcnt<6>(); else wait_vmcnt<0>();   // this wave's part of stage st has landed
+    wg_barrier();                                               // ... and everybody's; stage st-1 is consumed
+    if (st + 2 < nst) issue(st + 2);
+    const uint4* buf = smem + (st % kStages) * kStageFrags * 64;
 #pragma unroll
     for (int s2 = 0; s2 < 2; ++s2) {
-      Frag xf[4];
+      Frag xf[4], wfr[2];
 #pragma unroll
-      for (int tj = 0; tj < 4; ++tj) xf[tj].u = smem[buf * 1024 + (s2 * 8 + wt * 4 + tj) * 64 + lane];
+      for (int tj = 0; tj < 4; ++tj) xf[tj].u = buf[((wt * 4 + tj) * 2 + s2) * 64 + lane];
+#pragma unroll
+      for (int fi = 0; fi < 2; ++fi) wfr[fi].u = buf[(16 + (wf * 2 + fi) * 2 + s2) * 64 + lane];
 #pragma unroll
       for (int fi = 0; fi < 2; ++fi)
 #pragma unroll
-        for (int tj = 0; tj < 4; ++tj) acc[fi][tj] = mfma32(wc[s2 * 2 + fi], xf[tj], acc[fi][tj]);
+        for (int tj = 0; tj < 4; ++tj) acc[fi][tj] = mfma32(wfr[fi], xf[tj], acc[fi][tj]);
     }
-    if (st + 1 < nst) {
-      store_x(buf ^ 1);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) wc[i] = wn[i];
-    }
-    __syncthreads();
   }
 }
 
-__global__ void __launch_bounds__(256) k_gemm_big(const bf16* __restrict__ X, int ldx, const uint4* __restrict__ Wp,
-                                                  int M, int N, int K, BigEpi ep) {
-  __shared__ uint4 smem[2048];
-  const int ft = blockIdx.x, tok0 = blockIdx.y * 256;
+__global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int M,
+                                                     int N, int K, BigEpi ep) {
+  extern __shared__ uint4 smem[];
+  int bx, by;
+  if (!big_raster(N >> 7, (M + 255) >> 8, bx, by)) return;
   f32x16 acc[2][4];
-  big_mainloop(X, ldx, Wp, M, K, ft, tok0, smem, acc);
+  big_mainloop(Xp, Wp, (M + 31) >> 5, K >> 4, by * 8, bx * 4, smem, acc);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wf = wave & 1, wt = wave >> 1;
 #pragma unroll
   for (int tj = 0; tj < 4; ++tj) {
-    const int tok = tok0 + wt * 128 + tj * 32 + (lane & 31);
+    const int tok = by * 256 + wt * 128 + tj * 32 + (lane & 31);
     if (tok >= M) continue;
     if (ep.mode == BIG_SWIGLU) {
+      // fi = 0 is a gate tile, fi = 1 the matching up tile; act goes out in X32 order over F = N / 2
       const int F = N >> 1;
-      const int f0 = (ft * 2 + wf) * 32 + (lane >> 5) * 4;
+      const int f0 = (bx * 2 + wf) * 32 + (lane >> 5) * 4;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int r = 0; r < 4; ++r) {
         bf16x4 o;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) o[j] = (bf16)(silu_f(acc[0][tj][4 * i + j]) * acc[1][tj][4 * i + j]);
-        *(bf16x4*)(ep.out_bf16 + (size_t)tok * F + f0 + 8 * i) = o;
+        for (int j = 0; j < 4; ++j) o[j] = (bf16)(silu_f(acc[0][tj][4 * r + j]) * acc[1][tj][4 * r + j]);
+        *(bf16x4*)(ep.out_bf16 + x32_chunk(tok, f0 + 8 * r, F >> 4) * 8 + ((lane >> 5) << 2)) = o;
       }
     } else {
 #pragma unroll
       for (int fi = 0; fi < 2; ++fi) {
-        const int f0 = ft * 128 + wf * 64 + fi * 32 + (lane >> 5) * 4;
+        const int f0 = bx * 128 + wf * 64 + fi * 32 + (lane >> 5) * 4;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          float4* p = (float4*)(ep.out_f32 + (size_t)tok * ep.ldc + f0 + 8 * i);
-          float4 v = make_float4(acc[fi][tj][4 * i], acc[fi][tj][4 * i + 1], acc[fi][tj][4 * i + 2], acc[fi][tj][4 * i + 3]);
+        for (int r = 0; r < 4; ++r) {
+          float4* p = (float4*)(ep.out_f32 + (size_t)tok * ep.ldc + f0 + 8 * r);
+          float4 v = make_float4(acc[fi][tj][4 * r], acc[fi][tj][4 * r + 1], acc[fi][tj][4 * r + 2], acc[fi][tj][4 * r + 3]);
           if (ep.mode == BIG_ADD_F32) {
             const float4 o = *p;
             v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
@@ -166,35 +199,86 @@ __global__ void __launch_bounds__(256) k_gemm_big(const bf16* __restrict__ X, in
     }
   }
 }
-hipError_t m_gemm_big(const void* X, int ldx, const void* Wp, int M, int N, int K, BigEpi epi, hipStream_t st) {
+hipError_t m_gemm_big(const void* Xp, const void* Wp, int M, int N, int K, BigEpi epi, hipStream_t st) {
   if (M == 0) return hipSuccess;
-  dim3 grid(N / 128, (M + 255) / 256);
-  return launch(KID_GEMM_BIG, k_gemm_big, grid, dim3(256), 0, st, (const bf16*)X, ldx, (const uint4*)Wp, M, N, K, epi);
+  if (N % 128 != 0 || K % 32 != 0) return hipErrorInvalidValue;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)k_gemm_big, hipFuncAttributeMaxDynamicSharedMemorySize, kBigLds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  return launch(KID_GEMM_BIG, k_gemm_big, dim3(big_grid(N / 128, (M + 255) / 256)), dim3(256), kBigLds, st, (const uint4*)Xp,
+                (const uint4*)Wp, M, N, K, epi);
+}
+
+// ---------------------------------------------------------------------------------------
+// RMSNorm of residual rows into X32 order: out[i] = bf16( h[r] * rsqrt(mean(h[r]^2) + eps) * gain ),
+// r = row_index ? row_index[i] : i; negative r (padding) gives zeros.  One workgroup per row.
+// ---------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(128) k_rmsnorm_x32(const float* __restrict__ h, const float* __restrict__ gain, float eps,
+                                                     uint4* __restrict__ out, int d, const int* __restrict__ row_index) {
+  __shared__ float red[2];
+  const int i = blockIdx.x;
+  const int r = row_index ? row_index[i] : i;
+  const int KS = d >> 4;
+  if (r < 0) {
+    for (int k = threadIdx.x * 8; k < d; k += 1024) out[x32_chunk(i, k, KS)] = make_uint4(0, 0, 0, 0);
+    return;
+  }
+  const float* x = h + (size_t)r * d;
+  float ss = 0.f;
+  for (int k = threadIdx.x * 4; k < d; k += 512) {
+    const float4 v = *(const float4*)(x + k);
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  ss = wave_reduce_sum(ss);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float scale = 1.0f / sqrtf((red[0] + red[1]) / (float)d + eps);
+  for (int k = threadIdx.x * 8; k < d; k += 1024) {
+    const float4 a = *(const float4*)(x + k), b = *(const float4*)(x + k + 4);
+    const float4 ga = *(const float4*)(gain + k), gb = *(const float4*)(gain + k + 4);
+    Frag o;
+    o.v[0] = (bf16)(a.x * scale * ga.x); o.v[1] = (bf16)(a.y * scale * ga.y);
+    o.v[2] = (bf16)(a.z * scale * ga.z); o.v[3] = (bf16)(a.w * scale * ga.w);
+    o.v[4] = (bf16)(b.x * scale * gb.x); o.v[5] = (bf16)(b.y * scale * gb.y);
+    o.v[6] = (bf16)(b.z * scale * gb.z); o.v[7] = (bf16)(b.w * scale * gb.w);
+    out[x32_chunk(i, k, KS)] = o.u;
+  }
+}
+hipError_t m_rmsnorm_x32(const float* h, const float* gain, float eps, void* out, int M, int d, const int* row_index,
+                         hipStream_t st) {
+  if (M == 0) return hipSuccess;
+  return launch(KID_RMSNORM, k_rmsnorm_x32, dim3(M), dim3(128), 0, st, h, gain, eps, (uint4*)out, d, row_index);
 }
 
 // ---------------------------------------------------------------------------------------
 // LM head for scoring: log-softmax + target gather without materialising logits.
-// grid (token tiles of 256, kScoreSplit vocabulary ranges).  Each workgroup walks its range of
-// 128-feature tiles for its 256 rows keeping a running (max, sum exp) per row, and the one lane
-// that sees the row's target id writes the target logit.  A second kernel merges the ranges.
-// partials: [kScoreSplit][max_rows][2] then ztarget [max_rows].
+// Rastered like the GEMM over (256-row tiles) x (groups of kScoreGroup 128-feature tiles): a workgroup
+// walks the tiles of its group for its 256 rows keeping a running (max, sum exp) per row, and the
+// one lane that sees a row's target id writes the target logit.  A second kernel merges the groups
+// in a fixed order.  partials: [n_groups][max_rows][2], then ztarget [max_rows].
 // ---------------------------------------------------------------------------------------
-constexpr int kScoreSplit = 8;
-size_t m_lmhead_score_partial_floats(int max_rows) { return (size_t)max_rows * (2 * kScoreSplit + 1); }
+constexpr int kScoreGroup = 16;
+static int score_groups(int V) { return (V / 128 + kScoreGroup - 1) / kScoreGroup; }
+size_t m_lmhead_score_partial_floats(int max_rows, int V) { return (size_t)max_rows * (2 * score_groups(V) + 1); }
 
-__global__ void __launch_bounds__(256) k_lmhead_score(const bf16* __restrict__ X, const uint4* __restrict__ Wp,
-                                                      int max_rows, const int* __restrict__ n_rows_dev, int V, int K,
-                                                      const int* __restrict__ row_seq_pos,
-                                                      const int32_t* __restrict__ tokens, int T,
-                                                      float* __restrict__ partials) {
-  __shared__ uint4 smem[2048];
+__global__ void __launch_bounds__(256, 2) k_lmhead_score(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp,
+                                                         int max_rows, const int* __restrict__ n_rows_dev, int V, int K,
+                                                         const int* __restrict__ row_seq_pos,
+                                                         const int32_t* __restrict__ tokens, int T,
+                                                         float* __restrict__ partials) {
+  extern __shared__ uint4 smem[];
   __shared__ float red_m[2][256], red_l[2][256];
   const int n_rows = *n_rows_dev;
-  const int tok0 = blockIdx.x * 256;
+  const int n_ft = V >> 7;
+  const int n_groups = (n_ft + kScoreGroup - 1) / kScoreGroup;
+  int bx, by;
+  if (!big_raster(n_groups, (max_rows + 255) >> 8, bx, by)) return;
+  const int tok0 = by * 256;
   if (tok0 >= n_rows) return;
-  const int n_ft = V / 128;
-  const int per = (n_ft + kScoreSplit - 1) / kScoreSplit;
-  const int ft_begin = blockIdx.y * per, ft_end = min(n_ft, ft_begin + per);
+  const int ft_begin = bx * kScoreGroup, ft_end = min(n_ft, ft_begin + kScoreGroup);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wf = wave & 1, wt = wave >> 1;
   LseAcc lse[4];
@@ -206,21 +290,30 @@ __global__ void __launch_bounds__(256) k_lmhead_score(const bf16* __restrict__ X
     target[tj] = -1;
     if (row < n_rows) target[tj] = tokens[(size_t)row_seq_pos[2 * row] * T + row_seq_pos[2 * row + 1]];
   }
-  float* ztarget = partials + (size_t)max_rows * 2 * kScoreSplit;
+  float* ztarget = partials + (size_t)max_rows * 2 * n_groups;
   for (int ft = ft_begin; ft < ft_end; ++ft) {
     f32x16 acc[2][4];
-    big_mainloop(X, K, Wp, n_rows, K, ft, tok0, smem, acc);
+    big_mainloop(Xp, Wp, (n_rows + 31) >> 5, K >> 4, by * 8, ft * 4, smem, acc);
 #pragma unroll
     for (int tj = 0; tj < 4; ++tj) {
       const int row = tok0 + wt * 128 + tj * 32 + (lane & 31);
 #pragma unroll
       for (int fi = 0; fi < 2; ++fi) {
         const int f0 = ft * 128 + wf * 64 + fi * 32 + (lane >> 5) * 4;
+        float mt = acc[fi][tj][0];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float z = acc[fi][tj][v];
-          lse[tj].add(z);
-          if (f0 + 8 * (v >> 2) + (v & 3) == target[tj]) ztarget[row] = z;
+        for (int v = 1; v < 16; ++v) mt = fmaxf(mt, acc[fi][tj][v]);
+        const float mn = fmaxf(lse[tj].m, mt);
+        float su = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) su += __expf(acc[fi][tj][v] - mn);
+        lse[tj].l = lse[tj].l * __expf(lse[tj].m - mn) + su;
+        lse[tj].m = mn;
+        const int dt = target[tj] - f0;   // target among this lane's 4 x 4 features?
+        if (dt >= 0 && dt < 32 && (dt & 4) == 0) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            if (dt == 8 * (v >> 2) + (v & 3)) ztarget[row] = acc[fi][tj][v];
         }
       }
     }
@@ -240,34 +333,43 @@ __global__ void __launch_bounds__(256) k_lmhead_score(const bf16* __restrict__ X
     LseAcc a;
     a.m = red_m[0][threadIdx.x]; a.l = red_l[0][threadIdx.x];
     a.merge(red_m[1][threadIdx.x], red_l[1][threadIdx.x]);
-    float* p = partials + ((size_t)blockIdx.y * max_rows + row) * 2;
+    float* p = partials + ((size_t)bx * max_rows + row) * 2;
     p[0] = a.m; p[1] = a.l;
   }
 }
 
-__global__ void k_lmhead_score_merge(const float* __restrict__ partials, int max_rows, const int* __restrict__ n_rows_dev,
-                                     const int* __restrict__ row_seq_pos, int T, float* __restrict__ out_logprobs) {
+__global__ void k_lmhead_score_merge(const float* __restrict__ partials, int max_rows, int n_groups,
+                                     const int* __restrict__ n_rows_dev, const int* __restrict__ row_seq_pos, int T,
+                                     float* __restrict__ out_logprobs) {
   const int row = blockIdx.x * blockDim.x + threadIdx.x;
   if (row >= *n_rows_dev) return;
   LseAcc a; a.init();
-  for (int s = 0; s < kScoreSplit; ++s) {
+  for (int s = 0; s < n_groups; ++s) {
     const float* p = partials + ((size_t)s * max_rows + row) * 2;
     a.merge(p[0], p[1]);
   }
-  const float zt = partials[(size_t)max_rows * 2 * kScoreSplit + row];
+  const float zt = partials[(size_t)max_rows * 2 * n_groups + row];
   out_logprobs[(size_t)row_seq_pos[2 * row] * T + row_seq_pos[2 * row + 1]] = zt - (a.m + logf(a.l));
 }
 
-hipError_t m_lmhead_score(const void* X, const void* Wp, int max_rows, const int* n_rows_dev, int V, int K,
+hipError_t m_lmhead_score(const void* Xp, const void* Wp, int max_rows, const int* n_rows_dev, int V, int K,
                           const int* row_seq_pos, const int32_t* tokens, int T, float* partials, float* out_logprobs,
                           hipStream_t st) {
   if (max_rows == 0) return hipSuccess;
-  dim3 grid((max_rows + 255) / 256, kScoreSplit);
-  const hipError_t e = launch(KID_LMHEAD_SCORE, k_lmhead_score, grid, dim3(256), 0, st, (const bf16*)X, (const uint4*)Wp, max_rows,
-                              n_rows_dev, V, K, row_seq_pos, tokens, T, partials);
+  if (V % 128 != 0 || K % 32 != 0) return hipErrorInvalidValue;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)k_lmhead_score, hipFuncAttributeMaxDynamicSharedMemorySize, kBigLds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int n_groups = score_groups(V);
+  const hipError_t e = launch(KID_LMHEAD_SCORE, k_lmhead_score, dim3(big_grid(n_groups, (max_rows + 255) / 256)), dim3(256),
+                              kBigLds, st, (const uint4*)Xp, (const uint4*)Wp, max_rows, n_rows_dev, V, K, row_seq_pos, tokens,
+                              T, partials);
   if (e != hipSuccess) return e;
-  return launch(KID_LMHEAD_SCORE_MERGE, k_lmhead_score_merge, dim3((max_rows + 255) / 256), dim3(256), 0, st, partials, max_rows, n_rows_dev, row_seq_pos, T,
-                                                               out_logprobs);
+  return launch(KID_LMHEAD_SCORE_MERGE, k_lmhead_score_merge, dim3((max_rows + 255) / 256), dim3(256), 0, st, partials,
+                max_rows, n_groups, n_rows_dev, row_seq_pos, T, out_logprobs);
 }
 
 // =======================================================================================
@@ -279,7 +381,8 @@ hipError_t m_lmhead_score(const void* X, const void* Wp, int max_rows, const int
 // per-lane scalars (plus two shuffles) and the probabilities a lane produces are its operand of
 // O^T = V^T P^T; key rows are permuted inside a pair so that a lane's 8 probabilities are 8
 // consecutive tokens, the unit the token-minor V page delivers in one 16-byte load.  No LDS, no
-// block-level synchronisation; waves never exchange data.
+// block-level synchronisation; waves never exchange data.  q is row-major [rows, Hq hd]; the output
+// goes out in X32 order (the O projection's operand).
 // ---------------------------------------------------------------------------------------
 template <int HD, int HPW>
 __global__ void __launch_bounds__(256) k_flash_attention(const bf16* __restrict__ q, RowMap rm, KVCache kv,
@@ -388,13 +491,14 @@ __global__ void __launch_bounds__(256) k_flash_attention(const bf16* __restrict_
     l += __shfl_xor(l, 16, 64);
     l += __shfl_xor(l, 32, 64);
     const float inv = 1.0f / l;
-    bf16* op = out + (row0 + qpos) * qstride + (size_t)(kvh * rep + h0 + h) * HD + grp * 4;
+    const int col0 = (kvh * rep + h0 + h) * HD + grp * 4;   // lane's 4 consecutive head dims, per 16-row tile
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
       bf16x4 ov;
 #pragma unroll
       for (int j = 0; j < 4; ++j) ov[j] = (bf16)(o[h][dt][j] * inv);
-      *(bf16x4*)(op + dt * 16) = ov;
+      const int col = col0 + dt * 16;
+      *(bf16x4*)(out + x32_chunk((int)row0 + qpos, col, (int)(qstride >> 4)) * 8 + (col & 4)) = ov;
     }
   }
 }
