@@ -400,11 +400,11 @@ static int run_layers_big(const sapo_weights* w, const FwdBufs& b, int M, RowMap
     const KVCache kvc = layer_cache(w, cb, l);
     HIP_CK(m_rmsnorm_x32(b.h, lw.attn_norm, c.rms_eps, b.a, M, d, nullptr, st));
     HIP_CK(m_gemm_big(b.a, lw.wqkv, M, q + 2 * kv, d, BigEpi{BIG_STORE_F32, b.qkv, q + 2 * kv, nullptr}, st));
-    HIP_CK(g_rope_append(dt, b.qkv, w->rope, rm, kvc, b.q, M, c.n_q_heads, st));
+    HIP_CK(g_rope_append_f16(b.qkv, w->rope, rm, kvc, b.q, M, c.n_q_heads, st));
     HIP_CK(m_flash_attention(b.q, rm, kvc, b.attn, M / rm.T, c.n_q_heads, st));
     HIP_CK(m_gemm_big(b.attn, lw.wo, M, d, q, BigEpi{BIG_ADD_F32, b.h, d, nullptr}, st));
     HIP_CK(m_rmsnorm_x32(b.h, lw.ffn_norm, c.rms_eps, b.a, M, d, nullptr, st));
-    HIP_CK(m_gemm_big(b.a, lw.wgu, M, 2 * F, d, BigEpi{BIG_SWIGLU, nullptr, 0, (bf16*)b.act}, st));
+    HIP_CK(m_gemm_big(b.a, lw.wgu, M, 2 * F, d, BigEpi{BIG_SWIGLU, nullptr, 0, (f16*)b.act}, st));
     HIP_CK(m_gemm_big(b.act, lw.wdown, M, d, F, BigEpi{BIG_ADD_F32, b.h, d, nullptr}, st));
   }
   return SAPO_OK;

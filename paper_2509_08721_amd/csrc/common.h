@@ -11,6 +11,7 @@
 namespace sapo {
 
 typedef __bf16 bf16;
+typedef _Float16 f16;   // MFMA operand type: packed weights, activations, KV cache of the MFMA path
 
 constexpr int kPageTokens = 16;
 constexpr int kWave = 64;
@@ -43,6 +44,9 @@ struct RowMap {
 
 // Paged KV cache of one layer.  K page: [Hkv][16 tokens][hd]; V page: [Hkv][hd][16 tokens]
 // (V is kept token-minor so that a fixed feature's 16 tokens are contiguous).
+// Element type: fp32 for fp32 models; for bf16 models the shape-generic kernels keep bf16 and the
+// MFMA kernels keep IEEE half (same 2 bytes, 3 more mantissa bits: attention involves no weights,
+// so its operands need not share the weights' type; values are clamped to the half range).
 struct KVCache {
   void* k;                // [n_pages][Hkv][16][hd]
   void* v;                // [n_pages][Hkv][hd][16]
@@ -57,6 +61,7 @@ struct KVCache {
 // ---------------------------------------------------------------------------------------
 template <typename T> __device__ __forceinline__ float to_f32(T x) { return static_cast<float>(x); }
 template <typename T> __device__ __forceinline__ T from_f32(float x) { return static_cast<T>(x); }
+template <> __device__ __forceinline__ f16 from_f32<f16>(float x) { return (f16)fminf(fmaxf(x, -65504.f), 65504.f); }
 
 __device__ __forceinline__ float wave_reduce_max(float v) {
 #pragma unroll
@@ -187,6 +192,9 @@ hipError_t g_gemm(int dtype, const void* A, const void* W, float* C, int M, int 
                   hipStream_t st);
 hipError_t g_rope_append(int dtype, const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* q_out,
                          int M, int n_q_heads, hipStream_t st);
+// same, with q_out and the cache in IEEE half (MFMA path)
+hipError_t g_rope_append_f16(const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* q_out, int M,
+                             int n_q_heads, hipStream_t st);
 hipError_t g_attention(int dtype, const void* q, RowMap rm, KVCache kv, void* out, int M, int n_q_heads,
                        int max_ctx, hipStream_t st);
 hipError_t g_swiglu(int dtype, const float* gu, void* act, int M, int F, hipStream_t st);
@@ -220,7 +228,7 @@ struct BigEpi {
   int mode;            // see enum below
   float* out_f32;      // STORE_F32 / ADD_F32: [M, ldc]
   int ldc;
-  bf16* out_bf16;      // SWIGLU: act, X32 order over F = N / 2
+  f16* out_act;        // SWIGLU: act, X32 order over F = N / 2
 };
 enum { BIG_STORE_F32 = 0, BIG_ADD_F32 = 1, BIG_SWIGLU = 2 };
 

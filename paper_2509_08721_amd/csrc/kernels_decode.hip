@@ -1,17 +1,19 @@
-// Decode-side bf16 MFMA kernels for gfx950 (one new token per sequence and step).
+// Decode-side 16-bit MFMA kernels for gfx950 (one new token per sequence and step).  Operands are
+// IEEE half: packed weights hold the model's bf16 values converted to half, activations are rounded
+// to half (see the note at the top of kernels_mfma.hip).
 //
 // Every projection of a decode step is a "skinny" GEMM: few tokens (64 per block), all weights
-// streamed once from HBM.  The kernels here are built around v_mfma_f32_16x16x32_bf16 with both
+// streamed once from HBM.  The kernels here are built around v_mfma_f32_16x16x32_f16 with both
 // operands already in fragment order in global memory, so that a wave's operand load is one
 // contiguous 1 KiB read that goes straight into registers:
-//   weights  W16[((tile * KS + ks) * 64 + lane)]           (uint4 = 8 bf16)
+//   weights  W16[((tile * KS + ks) * 64 + lane)]           (uint4 = 8 half)
 //            = W[tile*16 + lane%16][ks*32 + (lane/16)*8 .. +7],                       KS = K / 32
 //   tokens   X16[(((tok/64) * KS + ks) * 4 + (tok/16)%4) * 64 + tok%16 + 16*((k%32)/8)]
 //            = x[tok][ks*32 + ((k%32)/8)*8 .. +7]
 // D = W-fragment x X-fragment leaves lane l with features (l/16)*4 .. +3 of token l%16.
 //
 // RMSNorm never runs on its own: the kernel that produces the residual stream also writes
-// bf16(h * gain) in X16 order plus per-tile sums of squares of h, and the GEMM that consumes it
+// half(h * gain) in X16 order plus per-tile sums of squares of h, and the GEMM that consumes it
 // multiplies its accumulators by rsqrt(mean(h^2) + eps) (the scale is per token, so it commutes
 // with the contraction).
 #include "common.h"
@@ -19,18 +21,20 @@
 namespace sapo {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 union Frag16 {
   uint4 u;
   u32x4 n;
   bf16x8 v;
+  f16x8 h;
 };
 
 __device__ __forceinline__ f32x4 mfma16(const Frag16& a, const Frag16& b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, b.h, c, 0, 0, 0);
 }
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
 
@@ -40,7 +44,7 @@ __host__ __device__ __forceinline__ size_t x16_chunk(int tok, int k, int KS) {
 }
 
 // ---------------------------------------------------------------------------------------
-// weight packing: row-major [n_rows, K] -> W16 order; 16-row tile t goes to tile slot
+// weight packing: row-major bf16 [n_rows, K] -> half, W16 order; 16-row tile t goes to tile slot
 // tile0 + t * tile_stride (stride 2 interleaves gate and up tiles).
 // ---------------------------------------------------------------------------------------
 __global__ void k_pack_weight16(const bf16* __restrict__ src, int n_rows, int K, uint4* __restrict__ dst, int tile0,
@@ -53,7 +57,11 @@ __global__ void k_pack_weight16(const bf16* __restrict__ src, int n_rows, int K,
   const int ks = (int)((idx >> 6) % KS);
   const int t = (int)((idx >> 6) / KS);
   const int row = t * 16 + (lane & 15), k = ks * 32 + (lane >> 4) * 8;
-  dst[((size_t)(tile0 + t * tile_stride) * KS + ks) * 64 + lane] = *(const uint4*)(src + (size_t)row * K + k);
+  Frag16 v, o;
+  v.u = *(const uint4*)(src + (size_t)row * K + k);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o.h[e] = from_f32<f16>((float)v.v[e]);   // bf16 value -> half
+  dst[((size_t)(tile0 + t * tile_stride) * KS + ks) * 64 + lane] = o.u;
 }
 hipError_t d_pack_weight16(const void* src, int n_rows, int K, void* dst, int dst_tile0, int dst_tile_stride,
                            hipStream_t st) {
@@ -189,15 +197,15 @@ __global__ void __launch_bounds__(512) k_skinny16(SkinnyArgs a, int n_units) {
       const float4 gs = sum8((2 * pp) * TG + g, l), us = sum8((2 * pp + 1) * TG + g, l);
       const int tl = (tg0 + g) * 16 + (l & 15), tok = tb * 64 + tl;
       const int f0 = ((tile0 >> 1) + pp) * 16 + (l >> 4) * 4;
-      bf16x4 o;
+      f16x4 o;
       if (tok < a.n_rows) {
         const float sc = ssq_scale(s_part, tl, a.norm_dim, a.eps);
-        o[0] = (bf16)(silu_f(gs.x * sc) * (us.x * sc)); o[1] = (bf16)(silu_f(gs.y * sc) * (us.y * sc));
-        o[2] = (bf16)(silu_f(gs.z * sc) * (us.z * sc)); o[3] = (bf16)(silu_f(gs.w * sc) * (us.w * sc));
+        o[0] = from_f32<f16>(silu_f(gs.x * sc) * (us.x * sc)); o[1] = from_f32<f16>(silu_f(gs.y * sc) * (us.y * sc));
+        o[2] = from_f32<f16>(silu_f(gs.z * sc) * (us.z * sc)); o[3] = from_f32<f16>(silu_f(gs.w * sc) * (us.w * sc));
       } else {
-        o[0] = o[1] = o[2] = o[3] = (bf16)0.f;
+        o[0] = o[1] = o[2] = o[3] = (f16)0.f;
       }
-      *(bf16x4*)((bf16*)a.xp_out + x16_chunk(tok, f0, KSo) * 8 + (f0 & 4)) = o;
+      *(f16x4*)((f16*)a.xp_out + x16_chunk(tok, f0, KSo) * 8 + (f0 & 4)) = o;
     }
     return;
   }
@@ -220,17 +228,18 @@ __global__ void __launch_bounds__(512) k_skinny16(SkinnyArgs a, int n_units) {
     float4 s = sum8(t * TG + g, l);
     const int tok = tb * 64 + (tg0 + g) * 16 + (l & 15);
     const int f0 = (tile0 + t) * 16 + (l >> 4) * 4;
-    bf16x4 o;
+    f16x4 o;
     float q = 0.f;
     if (tok < a.n_rows) {
       s.x += h_old.x; s.y += h_old.y; s.z += h_old.z; s.w += h_old.w;
       *(float4*)(a.h + (size_t)tok * a.N + f0) = s;
-      o[0] = (bf16)(s.x * g_next.x); o[1] = (bf16)(s.y * g_next.y); o[2] = (bf16)(s.z * g_next.z); o[3] = (bf16)(s.w * g_next.w);
+      o[0] = from_f32<f16>(s.x * g_next.x); o[1] = from_f32<f16>(s.y * g_next.y);
+      o[2] = from_f32<f16>(s.z * g_next.z); o[3] = from_f32<f16>(s.w * g_next.w);
       q = s.x * s.x + s.y * s.y + s.z * s.z + s.w * s.w;
     } else {
-      o[0] = o[1] = o[2] = o[3] = (bf16)0.f;
+      o[0] = o[1] = o[2] = o[3] = (f16)0.f;
     }
-    *(bf16x4*)((bf16*)a.xp_out + x16_chunk(tok, f0, a.N >> 5) * 8 + (f0 & 4)) = o;
+    *(f16x4*)((f16*)a.xp_out + x16_chunk(tok, f0, a.N >> 5) * 8 + (f0 & 4)) = o;
     q += __shfl_xor(q, 16, 64);
     q += __shfl_xor(q, 32, 64);
     if (l < 16) a.ssq_out[(size_t)(tile0 + t) * a.s_pad + tok] = q;
@@ -279,10 +288,9 @@ hipError_t d_gemm_skinny(const SkinnyArgs& a, int mode, hipStream_t st) {
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ void row_to_x16(const float (&v)[8], const float* __restrict__ gain, int k, int row, int KS,
                                            uint4* __restrict__ xp) {
-  bf16x8 o;
+  Frag16 f;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) o[e] = (bf16)(v[e] * gain[k + e]);
-  Frag16 f; f.v = o;
+  for (int e = 0; e < 8; ++e) f.h[e] = from_f32<f16>(v[e] * gain[k + e]);
   xp[x16_chunk(row, k, KS)] = f.u;
 }
 __device__ __forceinline__ float block128_sum(float s, float* red) {
@@ -556,7 +564,8 @@ hipError_t d_lmhead_sample(const void* Wp, const void* Xp, int K, int V, const f
 // probabilities a lane produces are exactly its operand of O^T = V^T P^T.  Token rows are permuted
 // inside a 32-token page pair so that a lane's 8 probabilities are 8 consecutive tokens, which is
 // what the token-minor V page delivers in one 16-byte load.  Waves take page pairs round-robin and
-// are merged through LDS.  The output goes out in X16 order (the O projection's operand).
+// are merged through LDS.  Queries, keys, values and probabilities are IEEE half (the cache's
+// type on this path); the output goes out as half in X16 order (the O projection's operand).
 // ---------------------------------------------------------------------------------------
 template <int HD, int NW>
 __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __restrict__ qkv,
@@ -564,9 +573,9 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
                                                                uint4* __restrict__ out, int n_q_heads) {
   constexpr int KK = HD / 32;   // k steps of S^T = K Q^T
   constexpr int DT = HD / 16;   // 16-row tiles of O^T
-  __shared__ __attribute__((aligned(16))) bf16 qs[16 * HD];
-  __shared__ __attribute__((aligned(16))) bf16 knew[HD];
-  __shared__ __attribute__((aligned(16))) bf16 vnew[HD];
+  __shared__ __attribute__((aligned(16))) f16 qs[16 * HD];
+  __shared__ __attribute__((aligned(16))) f16 knew[HD];
+  __shared__ __attribute__((aligned(16))) f16 vnew[HD];
   __shared__ float sm_m[NW][16], sm_l[NW][16];
   __shared__ float sm_o[NW][HD][16];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -576,8 +585,8 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
   rm.get(s, seq, pos);
   const int ctx = pos + 1;
   const int* pt = kv.page_table + (size_t)seq * kv.pages_per_seq;
-  bf16* kpool = (bf16*)kv.k;
-  bf16* vpool = (bf16*)kv.v;
+  f16* kpool = (f16*)kv.k;
+  f16* vpool = (f16*)kv.v;
   const size_t page_elems = (size_t)hkv * kPageTokens * HD;
   const int new_page = pt[pos / kPageTokens], new_slot = pos % kPageTokens;
   // ---- rotary on the group's queries and the new key; append key / value -------------------
@@ -593,20 +602,20 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
         r1 = x[i] * cs.x - x[i + half] * cs.y;
         r2 = x[i + half] * cs.x + x[i] * cs.y;
       }
-      qs[r * HD + i] = (bf16)r1;
-      qs[r * HD + i + half] = (bf16)r2;
+      qs[r * HD + i] = from_f32<f16>(r1);
+      qs[r * HD + i + half] = from_f32<f16>(r2);
     }
     for (int i = tid; i < half; i += NW * 64) {
       const float* x = row + (size_t)(n_q_heads + kvh) * HD;
       const float2 cs = rope[(size_t)pos * half + i];
-      bf16* kp = kpool + (size_t)new_page * page_elems + ((size_t)kvh * kPageTokens + new_slot) * HD;
-      const bf16 k1 = (bf16)(x[i] * cs.x - x[i + half] * cs.y), k2 = (bf16)(x[i + half] * cs.x + x[i] * cs.y);
+      f16* kp = kpool + (size_t)new_page * page_elems + ((size_t)kvh * kPageTokens + new_slot) * HD;
+      const f16 k1 = from_f32<f16>(x[i] * cs.x - x[i + half] * cs.y), k2 = from_f32<f16>(x[i + half] * cs.x + x[i] * cs.y);
       kp[i] = k1; kp[i + half] = k2;
       knew[i] = k1; knew[i + half] = k2;
     }
     for (int i = tid; i < HD; i += NW * 64) {
       const float* x = row + (size_t)(n_q_heads + hkv + kvh) * HD;
-      const bf16 vv = (bf16)x[i];
+      const f16 vv = from_f32<f16>(x[i]);
       vpool[(size_t)new_page * page_elems + ((size_t)kvh * HD + i) * kPageTokens + new_slot] = vv;
       vnew[i] = vv;
     }
@@ -633,11 +642,11 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
     for (int t = 0; t < 2; ++t) {
       const int r = lane & 15;
       const int ptok = 8 * (r >> 2) + 4 * t + (r & 3);
-      const bf16* kp = kpool + (size_t)(ptok < 16 ? pa : pb) * page_elems + ((size_t)kvh * kPageTokens + (ptok & 15)) * HD;
+      const f16* kp = kpool + (size_t)(ptok < 16 ? pa : pb) * page_elems + ((size_t)kvh * kPageTokens + (ptok & 15)) * HD;
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) kf[t][kk].u = *(const uint4*)(kp + kk * 32 + grp * 8);
     }
-    const bf16* vp = vpool + (size_t)(grp < 2 ? pa : pb) * page_elems + (size_t)kvh * HD * kPageTokens + (grp & 1) * 8;
+    const f16* vp = vpool + (size_t)(grp < 2 ? pa : pb) * page_elems + (size_t)kvh * HD * kPageTokens + (grp & 1) * 8;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) vf[dt].u = *(const uint4*)(vp + (size_t)(dt * 16 + (lane & 15)) * kPageTokens);
     // the token appended by this workgroup comes from LDS, not from the global copy written above
@@ -653,7 +662,7 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
       }
       if (grp == (pos % 32) / 8) {
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) vf[dt].v[pos % 8] = vnew[dt * 16 + (lane & 15)];
+        for (int dt = 0; dt < DT; ++dt) vf[dt].h[pos % 8] = vnew[dt * 16 + (lane & 15)];
       }
     }
     f32x4 sc[2];
@@ -683,7 +692,7 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
     for (int e = 0; e < 8; ++e) {
       const float pe = __expf(p[e] - m_new);
       psum += pe;
-      pf.v[e] = (bf16)pe;
+      pf.h[e] = (f16)pe;
     }
     l_run = l_run * alpha + psum;
     m_run = m_new;
@@ -695,7 +704,7 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
           for (int e = 0; e < 8; ++e)
-            if (e >= nvalid) vf[dt].v[e] = (bf16)0.f;
+            if (e >= nvalid) vf[dt].h[e] = (f16)0.f;
       }
     }
 #pragma unroll
@@ -730,7 +739,7 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
       float num = 0.f;
 #pragma unroll
       for (int w = 0; w < NW; ++w) num += wgt[w] * sm_o[w][d0 + e][q];
-      ov.v[e] = (bf16)(num * inv);
+      ov.h[e] = from_f32<f16>(num * inv);
     }
     out[x16_chunk(s, (kvh * rep + q) * HD + d0, KSo)] = ov.u;
   }

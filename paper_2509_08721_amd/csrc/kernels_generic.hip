@@ -224,6 +224,12 @@ hipError_t g_rope_append(int dtype, const float* qkv, const float2* rope, RowMap
   return e;
 }
 
+hipError_t g_rope_append_f16(const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* q_out, int M,
+                             int n_q_heads, hipStream_t st) {
+  if (M == 0) return hipSuccess;
+  return launch(KID_ROPE_APPEND, k_rope_append<f16>, dim3(M), dim3(256), 0, st, qkv, rope, rm, kv, (f16*)q_out, n_q_heads);
+}
+
 // ---------------------------------------------------------------------------------------
 // Causal grouped-query attention over the paged cache, one wave per (row, query head).
 // Scores of the row's context are kept in LDS: pass 1 scores + max, pass 2 exp + sum, pass 3 PV.

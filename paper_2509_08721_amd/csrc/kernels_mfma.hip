@@ -1,32 +1,41 @@
-// bf16 MFMA kernels for gfx950 used when many tokens go through the layers at once (prefill and
+// 16-bit MFMA kernels for gfx950 used when many tokens go through the layers at once (prefill and
 // scoring): weight packing, the token-parallel ("big") GEMM, and the fused LM head of the scoring
 // pass (log-softmax + target gather).
+//
+// Operand type: the model's weights are bf16 values; the packed copies hold the same values as IEEE
+// half (exact for 6.1e-5 <= |w| <= 65504, absolute error below 3e-8 under that) and activations
+// are rounded to half (clamped to its range) instead of bf16.  Both run the MFMA at the same rate;
+// half keeps 3 more mantissa bits, which is what keeps 28-layer models inside the stated logit and
+// log-prob tolerances (with bf16 activations the rounding points alone put the 1.5B-class model's
+// logits 6e-2 away from the definition).
 #include "common.h"
 
 namespace sapo {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 union Frag {
   uint4 u;
   u32x4 n;
   bf16x8 v;
+  f16x8 h;
 };
 
 __device__ __forceinline__ f32x16 mfma32(const Frag& a, const Frag& b, f32x16 c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, b.v, c, 0, 0, 0);
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(a.h, b.h, c, 0, 0, 0);
 }
-__device__ __forceinline__ f32x4 mfma16(const Frag& a, const Frag& b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
+__device__ __forceinline__ f32x4 mfma16h(const Frag& a, const Frag& b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, b.h, c, 0, 0, 0);
 }
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
 
 // ---------------------------------------------------------------------------------------
-// weight packing: row-major [n_rows, K] -> fragment order, 32-row tiles placed at
+// weight packing: row-major bf16 [n_rows, K] -> half, fragment order, 32-row tiles placed at
 // dst_tile0 + t * dst_tile_stride (stride 2 interleaves gate and up tiles).
 // ---------------------------------------------------------------------------------------
 __global__ void k_pack_weight(const bf16* __restrict__ src, int n_rows, int K, uint4* __restrict__ dst, int tile0,
@@ -39,8 +48,11 @@ __global__ void k_pack_weight(const bf16* __restrict__ src, int n_rows, int K, u
   const int ks = (int)((idx >> 6) % KS);
   const int t = (int)((idx >> 6) / KS);
   const int row = t * 32 + (lane & 31), k = ks * 16 + (lane >> 5) * 8;
-  const uint4 v = *(const uint4*)(src + (size_t)row * K + k);
-  dst[((size_t)(tile0 + t * tile_stride) * KS + ks) * 64 + lane] = v;
+  Frag v, o;
+  v.u = *(const uint4*)(src + (size_t)row * K + k);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o.h[e] = from_f32<f16>((float)v.v[e]);   // bf16 value -> half
+  dst[((size_t)(tile0 + t * tile_stride) * KS + ks) * 64 + lane] = o.u;
 }
 hipError_t m_pack_weight(const void* src, int n_rows, int K, void* dst, int dst_tile0, int dst_tile_stride,
                          hipStream_t st) {
@@ -176,10 +188,10 @@ __global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ X
       const int f0 = (bx * 2 + wf) * 32 + (lane >> 5) * 4;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        bf16x4 o;
+        f16x4 o;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) o[j] = (bf16)(silu_f(acc[0][tj][4 * r + j]) * acc[1][tj][4 * r + j]);
-        *(bf16x4*)(ep.out_bf16 + x32_chunk(tok, f0 + 8 * r, F >> 4) * 8 + ((lane >> 5) << 2)) = o;
+        for (int j = 0; j < 4; ++j) o[j] = from_f32<f16>(silu_f(acc[0][tj][4 * r + j]) * acc[1][tj][4 * r + j]);
+        *(f16x4*)(ep.out_act + x32_chunk(tok, f0 + 8 * r, F >> 4) * 8 + ((lane >> 5) << 2)) = o;
       }
     } else {
 #pragma unroll
@@ -213,7 +225,7 @@ hipError_t m_gemm_big(const void* Xp, const void* Wp, int M, int N, int K, BigEp
 }
 
 // ---------------------------------------------------------------------------------------
-// RMSNorm of residual rows into X32 order: out[i] = bf16( h[r] * rsqrt(mean(h[r]^2) + eps) * gain ),
+// RMSNorm of residual rows into X32 order: out[i] = half( h[r] * rsqrt(mean(h[r]^2) + eps) * gain ),
 // r = row_index ? row_index[i] : i; negative r (padding) gives zeros.  One workgroup per row.
 // ---------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(128) k_rmsnorm_x32(const float* __restrict__ h, const float* __restrict__ gain, float eps,
@@ -240,10 +252,10 @@ __global__ void __launch_bounds__(128) k_rmsnorm_x32(const float* __restrict__ h
     const float4 a = *(const float4*)(x + k), b = *(const float4*)(x + k + 4);
     const float4 ga = *(const float4*)(gain + k), gb = *(const float4*)(gain + k + 4);
     Frag o;
-    o.v[0] = (bf16)(a.x * scale * ga.x); o.v[1] = (bf16)(a.y * scale * ga.y);
-    o.v[2] = (bf16)(a.z * scale * ga.z); o.v[3] = (bf16)(a.w * scale * ga.w);
-    o.v[4] = (bf16)(b.x * scale * gb.x); o.v[5] = (bf16)(b.y * scale * gb.y);
-    o.v[6] = (bf16)(b.z * scale * gb.z); o.v[7] = (bf16)(b.w * scale * gb.w);
+    o.h[0] = from_f32<f16>(a.x * scale * ga.x); o.h[1] = from_f32<f16>(a.y * scale * ga.y);
+    o.h[2] = from_f32<f16>(a.z * scale * ga.z); o.h[3] = from_f32<f16>(a.w * scale * ga.w);
+    o.h[4] = from_f32<f16>(b.x * scale * gb.x); o.h[5] = from_f32<f16>(b.y * scale * gb.y);
+    o.h[6] = from_f32<f16>(b.z * scale * gb.z); o.h[7] = from_f32<f16>(b.w * scale * gb.w);
     out[x32_chunk(i, k, KS)] = o.u;
   }
 }
@@ -381,12 +393,12 @@ hipError_t m_lmhead_score(const void* Xp, const void* Wp, int max_rows, const in
 // per-lane scalars (plus two shuffles) and the probabilities a lane produces are its operand of
 // O^T = V^T P^T; key rows are permuted inside a pair so that a lane's 8 probabilities are 8
 // consecutive tokens, the unit the token-minor V page delivers in one 16-byte load.  No LDS, no
-// block-level synchronisation; waves never exchange data.  q is row-major [rows, Hq hd]; the output
-// goes out in X32 order (the O projection's operand).
+// block-level synchronisation; waves never exchange data.  q (row-major [rows, Hq hd]), K, V and the
+// probabilities are IEEE half; the output goes out as half in X32 order (the O projection's operand).
 // ---------------------------------------------------------------------------------------
 template <int HD, int HPW>
-__global__ void __launch_bounds__(256) k_flash_attention(const bf16* __restrict__ q, RowMap rm, KVCache kv,
-                                                         bf16* __restrict__ out, int n_q_heads) {
+__global__ void __launch_bounds__(256) k_flash_attention(const f16* __restrict__ q, RowMap rm, KVCache kv,
+                                                         f16* __restrict__ out, int n_q_heads) {
   constexpr int KK = HD / 32, DT = HD / 16;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int qcol = lane & 15, grp = lane >> 4;
@@ -422,8 +434,8 @@ __global__ void __launch_bounds__(256) k_flash_attention(const bf16* __restrict_
   const int q_hi = min(q0 + 15, T - 1);
   const int npairs = q_hi / 32 + 1;
   const int last_page = q_hi / kPageTokens;
-  const bf16* kpool = (const bf16*)kv.k;
-  const bf16* vpool = (const bf16*)kv.v;
+  const f16* kpool = (const f16*)kv.k;
+  const f16* vpool = (const f16*)kv.v;
   const size_t page_elems = (size_t)hkv * kPageTokens * HD;
   for (int pp = 0; pp < npairs; ++pp) {
     const int pa = pt[2 * pp];
@@ -433,11 +445,11 @@ __global__ void __launch_bounds__(256) k_flash_attention(const bf16* __restrict_
     for (int t = 0; t < 2; ++t) {
       const int r = lane & 15;
       const int ptok = 8 * (r >> 2) + 4 * t + (r & 3);   // key row r of score tile t
-      const bf16* kp = kpool + (size_t)(ptok < 16 ? pa : pb) * page_elems + ((size_t)kvh * kPageTokens + (ptok & 15)) * HD;
+      const f16* kp = kpool + (size_t)(ptok < 16 ? pa : pb) * page_elems + ((size_t)kvh * kPageTokens + (ptok & 15)) * HD;
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) kf[t][kk].u = *(const uint4*)(kp + kk * 32 + grp * 8);
     }
-    const bf16* vp = vpool + (size_t)(grp < 2 ? pa : pb) * page_elems + (size_t)kvh * HD * kPageTokens + (grp & 1) * 8;
+    const f16* vp = vpool + (size_t)(grp < 2 ? pa : pb) * page_elems + (size_t)kvh * HD * kPageTokens + (grp & 1) * 8;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) vf[dt].u = *(const uint4*)(vp + (size_t)(dt * 16 + (lane & 15)) * kPageTokens);
     const bool diag = pp * 32 + 31 > q0;   // some (query, key) of the pair is masked
@@ -449,7 +461,7 @@ __global__ void __launch_bounds__(256) k_flash_attention(const bf16* __restrict_
       for (int t = 0; t < 2; ++t) {
         sc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) sc[t] = mfma16(kf[t][kk], qf[h][kk], sc[t]);
+        for (int kk = 0; kk < KK; ++kk) sc[t] = mfma16h(kf[t][kk], qf[h][kk], sc[t]);
       }
       // lane (query qcol, group grp) holds keys pp*32 + 8 grp + e, e = 4 t + j
       float p[8];
@@ -471,7 +483,7 @@ __global__ void __launch_bounds__(256) k_flash_attention(const bf16* __restrict_
       for (int e = 0; e < 8; ++e) {
         const float pe = exp2f(p[e] - m_new);
         psum += pe;
-        pf.v[e] = (bf16)pe;
+        pf.h[e] = (f16)pe;
       }
       l_run[h] = l_run[h] * alpha + psum;
       m_run[h] = m_new;
@@ -479,7 +491,7 @@ __global__ void __launch_bounds__(256) k_flash_attention(const bf16* __restrict_
       for (int dt = 0; dt < DT; ++dt) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) o[h][dt][j] *= alpha;
-        o[h][dt] = mfma16(vf[dt], pf, o[h][dt]);
+        o[h][dt] = mfma16h(vf[dt], pf, o[h][dt]);
       }
     }
   }
@@ -494,11 +506,11 @@ __global__ void __launch_bounds__(256) k_flash_attention(const bf16* __restrict_
     const int col0 = (kvh * rep + h0 + h) * HD + grp * 4;   // lane's 4 consecutive head dims, per 16-row tile
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
-      bf16x4 ov;
+      f16x4 ov;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) ov[j] = (bf16)(o[h][dt][j] * inv);
+      for (int j = 0; j < 4; ++j) ov[j] = from_f32<f16>(o[h][dt][j] * inv);
       const int col = col0 + dt * 16;
-      *(bf16x4*)(out + x32_chunk((int)row0 + qpos, col, (int)(qstride >> 4)) * 8 + (col & 4)) = ov;
+      *(f16x4*)(out + x32_chunk((int)row0 + qpos, col, (int)(qstride >> 4)) * 8 + (col & 4)) = ov;
     }
   }
 }
@@ -510,12 +522,12 @@ hipError_t m_flash_attention(const void* q, RowMap rm, KVCache kv, void* out, in
   if (kv.head_dim == 64) {
     constexpr int HPW = 7;
     dim3 grid(nqb, n_seq * kv.n_kv_heads, (rep + HPW - 1) / HPW);
-    return launch(KID_FLASH_ATTN, k_flash_attention<64, HPW>, grid, dim3(256), 0, st, (const bf16*)q, rm, kv, (bf16*)out, n_q_heads);
+    return launch(KID_FLASH_ATTN, k_flash_attention<64, HPW>, grid, dim3(256), 0, st, (const f16*)q, rm, kv, (f16*)out, n_q_heads);
   }
   if (kv.head_dim == 128) {
     constexpr int HPW = 3;
     dim3 grid(nqb, n_seq * kv.n_kv_heads, (rep + HPW - 1) / HPW);
-    return launch(KID_FLASH_ATTN, k_flash_attention<128, HPW>, grid, dim3(256), 0, st, (const bf16*)q, rm, kv, (bf16*)out, n_q_heads);
+    return launch(KID_FLASH_ATTN, k_flash_attention<128, HPW>, grid, dim3(256), 0, st, (const f16*)q, rm, kv, (f16*)out, n_q_heads);
   }
   return hipErrorInvalidValue;
 }

@@ -56,3 +56,34 @@ def oracle_logprobs_for(model: O.Model, prompts, group, gpu_tokens, seqs):
         lp = O.log_softmax(z)
         out[s] = lp[np.arange(N), gpu_tokens[s]]
     return out
+
+
+def check_rollout_steps(model: O.Model, prompts, group, gpu_tokens, gpu_logprobs, temperature, seed, seq_steps,
+                        delta):
+    """One oracle forward per checked sequence, used for tokens and log-probs alike.
+
+    seq_steps: dict sequence -> list of steps (None = every step).  The oracle runs on the GPU's own
+    prefix (teacher-forced), recomputes the perturbed scores and the log-prob of the GPU's token.
+    Returns dict(n, exact, near, bad, max_lp_err, max_gap) with near/bad lists of
+    (s, t, v_oracle, v_gpu, gap)."""
+    gpu_tokens = np.asarray(gpu_tokens)
+    Lp, N = prompts.shape[1], gpu_tokens.shape[1]
+    out = dict(n=0, exact=0, near=[], bad=[], max_lp_err=0.0, max_gap=0.0)
+    for s, steps in seq_steps.items():
+        ts = list(range(N)) if steps is None else sorted(steps)
+        seq = np.concatenate([prompts[s // group], gpu_tokens[s]])
+        z = O.forward_logits(model, seq[: Lp + ts[-1]], at=[Lp - 1 + t for t in ts])
+        lp = O.log_softmax(z)
+        for i, t in enumerate(ts):
+            v_gpu = int(gpu_tokens[s, t])
+            out["max_lp_err"] = max(out["max_lp_err"], abs(float(lp[i, v_gpu]) - float(gpu_logprobs[s, t])))
+            y = O.perturbed_scores(z[i], temperature, seed, s, t)
+            v_star = int(np.argmax(y))
+            out["n"] += 1
+            if v_star == v_gpu:
+                out["exact"] += 1
+                continue
+            gap = float(y[v_star]) - float(y[v_gpu])
+            out["max_gap"] = max(out["max_gap"], gap)
+            (out["near"] if gap <= delta else out["bad"]).append((s, t, v_star, v_gpu, gap))
+    return out

@@ -1,0 +1,179 @@
+"""GPU parity at the full sizes of the five configurations, in the launch configuration the
+benchmark times (bf16 MFMA kernels, captured decode graph on a side stream).
+
+The oracle costs about 1 GFLOP (fp64) per token and billion parameters, so it checks samples:
+whole sequences where that takes seconds, otherwise chosen (sequence, step) pairs whose prefix the
+oracle re-runs from scratch.  Every check is teacher-forced on the GPU's own tokens, so a flip
+cannot cascade.  Token rule: the GPU's token is the oracle's argmax of the perturbed scores, or a
+stated near-tie (gap <= 1e-3 + 2 * 5e-2 / T: the literal band widened by the bf16 logit tolerance);
+log-probs within 2e-2 of the definition (oracle mode A)."""
+import numpy as np
+import pytest
+
+from oracle import sapo_oracle as O
+from paper_2509_08721_amd import workloads as W
+from tests.parity import check_rollout_steps
+
+pytestmark = pytest.mark.gpu
+
+LOGIT_TOL_BF16 = 5e-2
+LOGPROB_TOL = 2e-2
+NEAR_TIE = 1e-3
+
+
+def band(temp):
+    return NEAR_TIE + 2 * LOGIT_TOL_BF16 / (temp if temp > 0 else 1.0)
+
+
+@pytest.fixture(scope="module")
+def sapo():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2509_08721_amd import sapo as binding
+    binding.load_library()
+    return binding
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+class Loaded:
+    """Weights of one workload on the device and in the oracle."""
+
+    def __init__(self, sapo, wl, seed=None):
+        self.w = W.make_weights(wl.shape, wl.weight_seed if seed is None else seed)
+        self.gw = sapo.sapo_weights_create(wl.shape, self.w)
+        assert self.gw.uses_mfma
+        self._oracle = None
+        self.shape = wl.shape
+
+    @property
+    def oracle(self):
+        if self._oracle is None:
+            self._oracle = O.Model(self.shape, self.w)
+        return self._oracle
+
+
+@pytest.fixture(scope="module")
+def halfb(sapo):
+    return Loaded(sapo, W.WORKLOADS["halfb_rollout"])
+
+
+def rollout_on_side_stream(sapo, gw, prompts, G, N, temp, seed):
+    import torch
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        toks, lps = sapo.sapo_rollout_generate(gw, dev(prompts), G, N, temp, seed, stream=side)
+        side.synchronize()
+    return toks.cpu().numpy(), lps.cpu().numpy()
+
+
+def assert_rollout(res, n_tokens_total):
+    assert not res["bad"], res["bad"][:10]
+    assert res["n"] - res["exact"] <= max(2, 0.05 * res["n"]), (res["n"], res["exact"], res["near"][:10])
+    assert res["max_lp_err"] <= LOGPROB_TOL, res["max_lp_err"]
+
+
+def test_config2_rollout_0p5b(sapo, halfb):
+    """8 prompts x 8 completions, prompt 128, 256 new tokens, temperature 1."""
+    wl = W.WORKLOADS["halfb_rollout"]
+    prompts = W.make_prompts(wl)
+    toks, lps = rollout_on_side_stream(sapo, halfb.gw, prompts, wl.group, wl.n_new, wl.temperature, wl.rollout_seed)
+    assert toks.shape == (64, 256) and toks.min() >= 0 and toks.max() < wl.shape.vocab and np.isfinite(lps).all()
+    # siblings of a prompt draw from the same step-0 logits with different noise: not all equal
+    assert len(set(toks[:8, 0].tolist())) > 1
+    rng = np.random.default_rng(2)
+    seq_steps = {0: None, 63: None}                                   # two whole sequences
+    for s in (9, 22, 37, 50):                                         # one more per few groups, sampled steps
+        seq_steps[s] = sorted(rng.choice(wl.n_new, size=6, replace=False).tolist())
+    res = check_rollout_steps(halfb.oracle, prompts, wl.group, toks, lps, wl.temperature, wl.rollout_seed, seq_steps,
+                              band(wl.temperature))
+    print("config 2: %d steps checked, %d exact, %d near-ties (max gap %.4f), max |dlogp| %.4f"
+          % (res["n"], res["exact"], len(res["near"]), res["max_gap"], res["max_lp_err"]))
+    assert_rollout(res, toks.size)
+    # the scoring pass reproduces the rollout's log-probs (decode with the cache == teacher-forced recompute)
+    seqs = np.concatenate([np.repeat(prompts, wl.group, axis=0), toks], axis=1).astype(np.int32)
+    mask = W.make_completion_mask(64, 384, 256)
+    rew = W.make_rewards(64, wl.reward_p, wl.reward_seed)
+    lp, adv = sapo.sapo_score_logprobs(halfb.gw, dev(seqs), dev(mask), dev(rew), wl.group)
+    lp, adv = lp.cpu().numpy(), adv.cpu().numpy()
+    assert np.max(np.abs(lp[:, 128:] - lps)) <= 2 * LOGPROB_TOL      # two device paths, each within tolerance of the definition
+    assert np.max(np.abs(adv - O.group_advantages(rew, wl.group))) <= 1e-5
+
+
+def test_config3_long_generation_0p5b(sapo, halfb):
+    """Prompt 512, 1024 new tokens, temperature 0.7: contexts up to 1535 over 96 pages per sequence."""
+    wl = W.WORKLOADS["halfb_long"]
+    prompts = W.make_prompts(wl)
+    toks, lps = rollout_on_side_stream(sapo, halfb.gw, prompts, wl.group, wl.n_new, wl.temperature, wl.rollout_seed)
+    assert toks.shape == (64, 1024) and toks.min() >= 0 and toks.max() < wl.shape.vocab and np.isfinite(lps).all()
+    seq_steps = {3: list(range(0, 48)),            # the first steps of one sequence, contiguous
+                 40: [0, 15, 16, 17, 500, 1023],   # page boundary (512 + 16) and the deepest context
+                 63: [255, 777]}
+    res = check_rollout_steps(halfb.oracle, prompts, wl.group, toks, lps, wl.temperature, wl.rollout_seed, seq_steps,
+                              band(wl.temperature))
+    print("config 3: %d steps checked, %d exact, %d near-ties (max gap %.4f), max |dlogp| %.4f"
+          % (res["n"], res["exact"], len(res["near"]), res["max_gap"], res["max_lp_err"]))
+    assert_rollout(res, toks.size)
+
+
+def test_config4_mixed_scoring_0p5b(sapo, halfb):
+    """64 sequences of 768 tokens: groups 0-3 rolled out by the local weights, groups 4-7 by an
+    independently seeded copy ("external" rollouts of another node); all scored under the local
+    policy; mask = last 512 positions; rewards Bernoulli(0.3) in groups of 8."""
+    wl = W.WORKLOADS["halfb_score_mixed"]
+    other = Loaded(sapo, wl, seed=wl.external_weight_seed)
+    prompts = W.make_prompts(W.scaled(wl, n_prompts=8))
+    t_loc, _ = rollout_on_side_stream(sapo, halfb.gw, prompts[:4], 8, 512, 1.0, wl.rollout_seed)
+    t_ext, _ = rollout_on_side_stream(sapo, other.gw, prompts[4:], 8, 512, 1.0, wl.rollout_seed + 1)
+    del other
+    seqs = np.concatenate([np.repeat(prompts, 8, axis=0), np.concatenate([t_loc, t_ext], axis=0)], axis=1).astype(np.int32)
+    assert seqs.shape == (64, 768)
+    mask = W.make_completion_mask(64, 768, 512)
+    rew = W.make_rewards(64, wl.reward_p, wl.reward_seed)
+    rew[8:16] = 1.0                                              # a zero-advantage group
+    lp, adv = sapo.sapo_score_logprobs(halfb.gw, dev(seqs), dev(mask), dev(rew), 8)
+    lp, adv = lp.cpu().numpy(), adv.cpu().numpy()
+    assert np.isfinite(lp).all() and np.all(lp[:, :256] == 0.0)
+    assert np.max(np.abs(adv - O.group_advantages(rew, 8))) <= 1e-5 and np.all(adv[8:16] == 0.0)
+    # external rollouts are less likely under the local policy than its own (random weights are
+    # close to uniform over the vocabulary, so the margin is small), and finite
+    assert lp[32:, 256:].mean() < lp[:32, 256:].mean() - 0.2
+    check = [5, 44]                                              # one local, one external sequence
+    o_lp = O.score_logprobs(halfb.oracle, seqs[check], mask[check])
+    err = float(np.max(np.abs(lp[check] - o_lp)))
+    print("config 4: 2 x 512 log-probs checked, max |dlogp| %.4f (local mean %.2f, external mean %.2f)"
+          % (err, lp[:32, 256:].mean(), lp[32:, 256:].mean()))
+    assert err <= LOGPROB_TOL
+    # batch-composition invariance: the local half alone gives the same bytes as inside the mixed batch
+    lp_half, _ = sapo.sapo_score_logprobs(halfb.gw, dev(seqs[:32]), dev(mask[:32]), dev(rew[:32]), 8)
+    assert np.array_equal(lp_half.cpu().numpy(), lp[:32])
+
+
+def test_config5_1p5b_rollout_and_scoring(sapo):
+    """1.5B-class decoder, 32 prompts x 8 completions, prompt 256, 512 new tokens, then scoring of all 256."""
+    wl = W.WORKLOADS["onehalfb"]
+    m = Loaded(sapo, wl)
+    prompts = W.make_prompts(wl)
+    toks, lps = rollout_on_side_stream(sapo, m.gw, prompts, wl.group, wl.n_new, wl.temperature, wl.rollout_seed)
+    assert toks.shape == (256, 512) and toks.min() >= 0 and toks.max() < wl.shape.vocab and np.isfinite(lps).all()
+    seq_steps = {17: list(range(0, 24)), 200: [0, 100, 511], 255: [300]}
+    res = check_rollout_steps(m.oracle, prompts, wl.group, toks, lps, wl.temperature, wl.rollout_seed, seq_steps,
+                              band(wl.temperature))
+    print("config 5 rollout: %d steps checked, %d exact, %d near-ties (max gap %.4f), max |dlogp| %.4f"
+          % (res["n"], res["exact"], len(res["near"]), res["max_gap"], res["max_lp_err"]))
+    assert_rollout(res, toks.size)
+    seqs = np.concatenate([np.repeat(prompts, wl.group, axis=0), toks], axis=1).astype(np.int32)
+    mask = W.make_completion_mask(256, 768, 512)
+    rew = W.make_rewards(256, wl.reward_p, wl.reward_seed)
+    lp, adv = sapo.sapo_score_logprobs(m.gw, dev(seqs), dev(mask), dev(rew), wl.group)
+    lp, adv = lp.cpu().numpy(), adv.cpu().numpy()
+    assert np.isfinite(lp).all()
+    assert np.max(np.abs(adv - O.group_advantages(rew, wl.group))) <= 1e-5
+    o_lp = O.score_logprobs(m.oracle, seqs[[130]], mask[[130]])
+    err = float(np.max(np.abs(lp[[130]] - o_lp)))
+    print("config 5 scoring: 512 log-probs checked, max |dlogp| %.4f" % err)
+    assert err <= LOGPROB_TOL
