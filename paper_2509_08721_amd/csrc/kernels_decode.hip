@@ -558,27 +558,31 @@ hipError_t d_lmhead_sample(const void* Wp, const void* Xp, int K, int V, const f
 
 // =======================================================================================
 // Decode attention over the paged KV cache, fused with rotary + KV append of the new token.
-// One workgroup (4 waves) per (sequence, KV head); all query heads of the group ride together as
+// One workgroup (NW waves) per (sequence, KV head); all query heads of the group ride together as
 // the 16 columns of 16x16x32 MFMAs.  S^T = K Q^T (tokens x queries) so that each lane owns one
 // query column: the running max / sum are per-lane scalars plus two cross-lane shuffles, and the
 // probabilities a lane produces are exactly its operand of O^T = V^T P^T.  Token rows are permuted
 // inside a 32-token page pair so that a lane's 8 probabilities are 8 consecutive tokens, which is
-// what the token-minor V page delivers in one 16-byte load.  Waves take page pairs round-robin and
-// are merged through LDS.  Queries, keys, values and probabilities are IEEE half (the cache's
-// type on this path); the output goes out as half in X16 order (the O projection's operand).
+// what the token-minor V page delivers in one 16-byte load.  Waves take page pairs round-robin, PD
+// pairs at a time with all their K/V fragments in flight at once; the first chunk is requested
+// before the query rows are even read (K/V addresses depend on the page table only), so a step
+// pays one memory round trip, not one per dependent stage.  Waves are merged through LDS.
+// Queries, keys, values and probabilities are IEEE half (the cache's type on this path); the
+// output goes out as half in X16 order (the O projection's operand).
 // ---------------------------------------------------------------------------------------
-template <int HD, int NW>
+template <int HD, int NW, int PD>
 __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __restrict__ qkv,
                                                                const float2* __restrict__ rope, RowMap rm, KVCache kv,
                                                                uint4* __restrict__ out, int n_q_heads) {
   constexpr int KK = HD / 32;   // k steps of S^T = K Q^T
   constexpr int DT = HD / 16;   // 16-row tiles of O^T
+  extern __shared__ float sm_o[];   // [NW][HD][16]
   __shared__ __attribute__((aligned(16))) f16 qs[16 * HD];
   __shared__ __attribute__((aligned(16))) f16 knew[HD];
   __shared__ __attribute__((aligned(16))) f16 vnew[HD];
   __shared__ float sm_m[NW][16], sm_l[NW][16];
-  __shared__ float sm_o[NW][HD][16];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int qcol = lane & 15, grp = lane >> 4;
   const int hkv = kv.n_kv_heads, rep = n_q_heads / hkv;
   const int s = blockIdx.x / hkv, kvh = blockIdx.x % hkv;
   int seq, pos;
@@ -588,10 +592,35 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
   f16* kpool = (f16*)kv.k;
   f16* vpool = (f16*)kv.v;
   const size_t page_elems = (size_t)hkv * kPageTokens * HD;
-  const int new_page = pt[pos / kPageTokens], new_slot = pos % kPageTokens;
+  const int npairs = (ctx + 31) / 32;
+  const int last_page = (ctx - 1) / kPageTokens;
+
+  // K rows of the two score tiles and the V tile of page pair pp: tile t row r is pair-token
+  // 8 (r / 4) + 4 t + r % 4; the lane's V chunk holds pair-tokens 8 grp .. 8 grp + 7
+  auto load_pair = [&](int pp, Frag16 (&kf)[2][KK], Frag16 (&vf)[DT]) {
+    const int pa = pt[2 * pp];
+    const int pb = pt[min(2 * pp + 1, last_page)];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int r = lane & 15;
+      const int ptok = 8 * (r >> 2) + 4 * t + (r & 3);
+      const f16* kp = kpool + (size_t)(ptok < 16 ? pa : pb) * page_elems + ((size_t)kvh * kPageTokens + (ptok & 15)) * HD;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) kf[t][kk].u = *(const uint4*)(kp + kk * 32 + grp * 8);
+    }
+    const f16* vp = vpool + (size_t)(grp < 2 ? pa : pb) * page_elems + (size_t)kvh * HD * kPageTokens + (grp & 1) * 8;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) vf[dt].u = *(const uint4*)(vp + (size_t)(dt * 16 + (lane & 15)) * kPageTokens);
+  };
+  Frag16 kf[PD][2][KK], vf[PD][DT];
+#pragma unroll
+  for (int j = 0; j < PD; ++j)
+    if (wave + NW * j < npairs) load_pair(wave + NW * j, kf[j], vf[j]);
+
   // ---- rotary on the group's queries and the new key; append key / value -------------------
   {
     const int half = HD / 2;
+    const int new_page = pt[pos / kPageTokens], new_slot = pos % kPageTokens;
     const float* row = qkv + (size_t)s * (n_q_heads + 2 * hkv) * HD;
     for (int idx = tid; idx < 16 * half; idx += NW * 64) {
       const int r = idx / half, i = idx % half;
@@ -621,7 +650,6 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
     }
   }
   __syncthreads();
-  const int qcol = lane & 15, grp = lane >> 4;
   Frag16 qf[KK];
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) qf[kk].u = *(const uint4*)(qs + qcol * HD + kk * 32 + grp * 8);
@@ -630,88 +658,81 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
   f32x4 o[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const int npairs = (ctx + 31) / 32;
-  const int last_page = (ctx - 1) / kPageTokens;
-  for (int pp = wave; pp < npairs; pp += NW) {
-    const int pa = pt[2 * pp];
-    const int pb = pt[min(2 * pp + 1, last_page)];
-    // issue every load of the pair first: K rows of the two score tiles, then the V tile
-    // key rows: tile t row r is pair-token 8 (r / 4) + 4 t + r % 4
-    Frag16 kf[2][KK], vf[DT];
+
+  for (int c0 = 0; wave + NW * c0 < npairs; c0 += PD) {
+    if (c0 > 0) {
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int r = lane & 15;
-      const int ptok = 8 * (r >> 2) + 4 * t + (r & 3);
-      const f16* kp = kpool + (size_t)(ptok < 16 ? pa : pb) * page_elems + ((size_t)kvh * kPageTokens + (ptok & 15)) * HD;
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) kf[t][kk].u = *(const uint4*)(kp + kk * 32 + grp * 8);
+      for (int j = 0; j < PD; ++j)
+        if (wave + NW * (c0 + j) < npairs) load_pair(wave + NW * (c0 + j), kf[j], vf[j]);
     }
-    const f16* vp = vpool + (size_t)(grp < 2 ? pa : pb) * page_elems + (size_t)kvh * HD * kPageTokens + (grp & 1) * 8;
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) vf[dt].u = *(const uint4*)(vp + (size_t)(dt * 16 + (lane & 15)) * kPageTokens);
-    // the token appended by this workgroup comes from LDS, not from the global copy written above
-    if (pp == pos / 32) {
+    for (int j = 0; j < PD; ++j) {
+      const int pp = wave + NW * (c0 + j);
+      if (pp >= npairs) break;
+      // the token appended by this workgroup comes from LDS, not from the global copy written above
+      if (pp == pos / 32) {
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const int r = lane & 15;
-        const int ptok = 8 * (r >> 2) + 4 * t + (r & 3);
-        if (ptok == pos % 32) {
+        for (int t = 0; t < 2; ++t) {
+          const int r = lane & 15;
+          const int ptok = 8 * (r >> 2) + 4 * t + (r & 3);
+          if (ptok == pos % 32) {
 #pragma unroll
-          for (int kk = 0; kk < KK; ++kk) kf[t][kk].u = *(const uint4*)(knew + kk * 32 + grp * 8);
+            for (int kk = 0; kk < KK; ++kk) kf[j][t][kk].u = *(const uint4*)(knew + kk * 32 + grp * 8);
+          }
+        }
+        if (grp == (pos % 32) / 8) {
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) vf[j][dt].h[pos % 8] = vnew[dt * 16 + (lane & 15)];
         }
       }
-      if (grp == (pos % 32) / 8) {
+      f32x4 sc[2];
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) vf[dt].h[pos % 8] = vnew[dt * 16 + (lane & 15)];
+      for (int t = 0; t < 2; ++t) {
+        sc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) sc[t] = mfma16(kf[j][t][kk], qf[kk], sc[t]);
       }
-    }
-    f32x4 sc[2];
+      // lane (query qcol, group grp) now holds pair-tokens 8 grp + e, e = 4 t + i
+      float p[8];
+      float m_loc = -INFINITY;
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      sc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) sc[t] = mfma16(kf[t][kk], qf[kk], sc[t]);
-    }
-    // lane (query qcol, group grp) now holds pair-tokens 8 grp + e, e = 4 t + j
-    float p[8];
-    float m_loc = -INFINITY;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int n = pp * 32 + 8 * grp + e;
-      const float sv = sc[e >> 2][e & 3] * scale;
-      p[e] = (n < ctx) ? sv : -INFINITY;
-      m_loc = fmaxf(m_loc, p[e]);
-    }
-    m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 16, 64));
-    m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, 64));
-    const float m_new = fmaxf(m_run, m_loc);
-    const float alpha = __expf(m_run - m_new);
-    float psum = 0.f;
-    Frag16 pf;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float pe = __expf(p[e] - m_new);
-      psum += pe;
-      pf.h[e] = (f16)pe;
-    }
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
-    // tokens past the context may hold anything in V (even NaN bit patterns): zero them
-    {
-      const int nvalid = ctx - (pp * 32 + 8 * grp);   // lane's 8 tokens: first nvalid are real
-      if (nvalid < 8) {
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-          for (int e = 0; e < 8; ++e)
-            if (e >= nvalid) vf[dt].h[e] = (f16)0.f;
+      for (int e = 0; e < 8; ++e) {
+        const int n = pp * 32 + 8 * grp + e;
+        const float sv = sc[e >> 2][e & 3] * scale;
+        p[e] = (n < ctx) ? sv : -INFINITY;
+        m_loc = fmaxf(m_loc, p[e]);
       }
-    }
+      m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 16, 64));
+      m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, 64));
+      const float m_new = fmaxf(m_run, m_loc);
+      const float alpha = __expf(m_run - m_new);
+      float psum = 0.f;
+      Frag16 pf;
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
+      for (int e = 0; e < 8; ++e) {
+        const float pe = __expf(p[e] - m_new);
+        psum += pe;
+        pf.h[e] = (f16)pe;
+      }
+      l_run = l_run * alpha + psum;
+      m_run = m_new;
+      // tokens past the context may hold anything in V (even NaN bit patterns): zero them
+      {
+        const int nvalid = ctx - (pp * 32 + 8 * grp);   // lane's 8 tokens: first nvalid are real
+        if (nvalid < 8) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) o[dt][j] *= alpha;
-      o[dt] = mfma16(vf[dt], pf, o[dt]);
+          for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              if (e >= nvalid) vf[j][dt].h[e] = (f16)0.f;
+        }
+      }
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[dt][i] *= alpha;
+        o[dt] = mfma16(vf[j][dt], pf, o[dt]);
+      }
     }
   }
   l_run += __shfl_xor(l_run, 16, 64);
@@ -720,9 +741,10 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) sm_o[wave][dt * 16 + grp * 4 + j][qcol] = o[dt][j];
+    for (int i = 0; i < 4; ++i) sm_o[((size_t)wave * HD + dt * 16 + grp * 4 + i) * 16 + qcol] = o[dt][i];
   __syncthreads();
-  // thread -> (query q, 8 consecutive head dims): one 16-byte chunk of the X16 output
+  // thread -> (query q, 8 consecutive head dims): one 16-byte chunk of the X16 output.  Waves that
+  // had no page pair carry (m = -inf, l = 0, o = 0) and drop out of the merge.
   const int KSo = (n_q_heads * HD) >> 5;
   for (int idx = tid; idx < rep * (HD / 8); idx += NW * 64) {
     const int q = idx / (HD / 8), d0 = (idx % (HD / 8)) * 8;
@@ -738,20 +760,32 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
     for (int e = 0; e < 8; ++e) {
       float num = 0.f;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) num += wgt[w] * sm_o[w][d0 + e][q];
+      for (int w = 0; w < NW; ++w) num += wgt[w] * sm_o[((size_t)w * HD + d0 + e) * 16 + q];
       ov.h[e] = from_f32<f16>(num * inv);
     }
     out[x16_chunk(s, (kvh * rep + q) * HD + d0, KSo)] = ov.u;
   }
 }
 
+template <int HD, int NW, int PD>
+static hipError_t launch_decode_attention(const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* out, int S,
+                                          int n_q_heads, hipStream_t st) {
+  static bool attr_done = false;
+  const size_t smem = (size_t)NW * HD * 16 * sizeof(float);
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)k_decode_attention16<HD, NW, PD>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  return launch(KID_DECODE_ATTN, k_decode_attention16<HD, NW, PD>, dim3(S * kv.n_kv_heads), dim3(NW * 64), smem, st, qkv, rope,
+                rm, kv, (uint4*)out, n_q_heads);
+}
+
 hipError_t d_decode_attention(const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* out, int S, int n_q_heads,
                               hipStream_t st) {
-  const dim3 grid(S * kv.n_kv_heads);
-  if (kv.head_dim == 64)
-    return launch(KID_DECODE_ATTN, k_decode_attention16<64, 4>, grid, dim3(256), 0, st, qkv, rope, rm, kv, (uint4*)out, n_q_heads);
-  if (kv.head_dim == 128)
-    return launch(KID_DECODE_ATTN, k_decode_attention16<128, 4>, grid, dim3(256), 0, st, qkv, rope, rm, kv, (uint4*)out, n_q_heads);
+  if (kv.head_dim == 64) return launch_decode_attention<64, 8, 3>(qkv, rope, rm, kv, out, S, n_q_heads, st);
+  if (kv.head_dim == 128) return launch_decode_attention<128, 8, 2>(qkv, rope, rm, kv, out, S, n_q_heads, st);
   return hipErrorInvalidValue;
 }
 
