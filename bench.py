@@ -7,8 +7,11 @@ completions) followed by the scoring pass over the generated batch (sapo_score_l
 teacher-forced log-probs on the completion positions + group-relative advantages).
 The default workload is one node-round of the paper's experiment (8 questions x 8
 completions, Sec. 4.1 / Sec. 5) on the 0.5B-class decoder with synthetic weights and prompts.
+Other workloads (--workload): halfb_long (rollout only, long generation), halfb_score_mixed
+(scoring only, half local / half external rollouts; the batch is prepared untimed), onehalfb
+(1.5B-class decoder, rollout + scoring), tiny.
 
-Prints ONE JSON line (see README / DESIGN for the fields).
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -23,8 +26,8 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
-MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
+MFMA_16BIT_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 / fp16 MFMA, published
 
 
 def algorithmic_bytes_rollout(shape, P, G, Lp, N):
@@ -47,27 +50,31 @@ def algorithmic_flops_score(shape, S, T, Tm):
     return {"layers": layers, "lm_head": lm, "attention": attn, "total": layers + lm + attn}
 
 
-def per_launch_work(shape, wl, kernel, launches):
+def per_launch_work(shape, plan, kernel, launches):
     """Algorithmic bytes (HBM-bound kernels) or flops (MFMA-bound kernels) one launch of a kernel
-    processes on this workload, averaged over the launches of one step."""
-    S, N, Lp, P = wl.n_seqs, wl.n_new, wl.prompt_len, wl.n_prompts
+    processes in one step of this workload, averaged over the launches of the step."""
     L, d, V = shape.n_layers, shape.d_model, shape.vocab
-    T, Tm = wl.score_len, wl.score_masked
+    S, N, Lp, P = plan["S"], plan["N"], plan["Lp"], plan["P"]
+    T, Tm, Ss = plan["T"], plan["Tm"], plan["S_score"]
+    dec_steps = max(N - 1, 0) if plan["rollout"] else 0
+    big_tokens = (P * Lp if plan["rollout"] else 0) + (Ss * T if plan["score"] else 0)
     if kernel == "k_gemm_skinny":       # the four projection GEMMs of a decode layer
-        return "hbm", 2.0 * shape.matmul_params_per_layer() * L * (N - 1) / launches
+        return "hbm", 2.0 * shape.matmul_params_per_layer() * L * dec_steps / launches
     if kernel == "k_lmhead_sample":     # LM head of one decode step: the whole [V, d] matrix
         return "hbm", 2.0 * V * d
     if kernel == "k_decode_attention":  # K and V of every cached token of every sequence, one layer
         kv_layer = 2 * shape.kv_dim * 2
         tot = kv_layer * S * sum(Lp + t for t in range(1, N)) * L
         return "hbm", tot / launches
-    if kernel == "k_gemm_big":          # projection GEMMs of prefill + scoring
-        fl = 2.0 * L * shape.matmul_params_per_layer() * (P * Lp + S * T)
+    if kernel == "k_gemm_big":          # projection GEMMs of prefill + scoring (+ LM head where logits are materialised)
+        fl = 2.0 * L * shape.matmul_params_per_layer() * big_tokens
+        if plan["rollout"] and not plan["fused_lm"]:
+            fl += 2.0 * V * d * S * N
         return "mfma", fl / launches
     if kernel == "k_lmhead_score":
-        return "mfma", 2.0 * V * d * S * Tm / launches
+        return "mfma", 2.0 * V * d * Ss * Tm / launches
     if kernel in ("k_attention", "k_flash_attention"):
-        fl = 2.0 * shape.q_dim * L * (S * T * T + P * Lp * Lp)
+        fl = 2.0 * shape.q_dim * L * ((Ss * T * T if plan["score"] else 0) + (P * Lp * Lp if plan["rollout"] else 0))
         return "mfma", fl / launches
     return None, 0.0
 
@@ -80,6 +87,8 @@ def main():
     ap.add_argument("--workload", default="halfb_rollout")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-profile", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one 1 GiB device copy (a kernel of known traffic, for scaling profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not "
@@ -96,34 +105,71 @@ def main():
     t0 = time.time()
     weights = W.make_weights(shape, wl.weight_seed)
     gw = sapo.sapo_weights_create(shape, weights)
-    prompts_np = W.make_prompts(wl)
-    prompts = torch.from_numpy(prompts_np).cuda()
-    S, N, Lp, G, P = wl.n_seqs, wl.n_new, wl.prompt_len, wl.group, wl.n_prompts
-    T, Tm = Lp + N, N
-    rewards = torch.from_numpy(W.make_rewards(S, wl.reward_p, wl.reward_seed)).cuda()
-    mask = torch.from_numpy(W.make_completion_mask(S, T, Tm)).cuda()
-    ws_r = torch.empty(sapo.sapo_rollout_workspace_bytes(gw, P, Lp, G, N) + 256, dtype=torch.uint8, device="cuda")
-    ws_s = torch.empty(sapo.sapo_score_workspace_bytes(gw, S, T) + 256, dtype=torch.uint8, device="cuda")
-    out_tok = torch.empty((S, N), dtype=torch.int32, device="cuda")
-    out_lp = torch.empty((S, N), dtype=torch.float32, device="cuda")
-    sc_lp = torch.empty((S, T), dtype=torch.float32, device="cuda")
-    sc_adv = torch.empty((S,), dtype=torch.float32, device="cuda")
-    prompt_rep = prompts.repeat_interleave(G, dim=0)
-    setup_s = time.time() - t0
-
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    G = wl.group
+    do_rollout = wl.n_new > 0 and args.workload != "halfb_score_mixed"
+    do_score = wl.score_seqs > 0
     side = torch.cuda.Stream()      # a non-default stream: the library replays a captured decode step on it
     torch.cuda.synchronize()
     torch.cuda.set_stream(side)
 
+    if do_rollout:
+        P, Lp, N = wl.n_prompts, wl.prompt_len, wl.n_new
+        S = P * G
+        prompts_np = W.make_prompts(wl)
+        T, Tm, S_score = (Lp + N, N, S) if do_score else (0, 0, 0)
+        seq_src = None
+    else:
+        # scoring only (Sec. 5's 4 local / 4 external mix): half the groups are rolled out by the local
+        # weights, half by an independently seeded copy; this preparation is input generation, untimed
+        S_score, T, Tm = wl.score_seqs, wl.score_len, wl.score_masked
+        P, Lp, N = S_score // G, T - Tm, Tm
+        S = S_score
+        prompts_np = W.make_prompts(W.scaled(wl, n_prompts=P, prompt_len=Lp))
+        other = sapo.sapo_weights_create(shape, W.make_weights(shape, wl.external_weight_seed))
+        half = P // 2
+        t_loc, _ = sapo.sapo_rollout_generate(gw, torch.from_numpy(prompts_np[:half]).cuda(), G, N, 1.0, wl.rollout_seed)
+        t_ext, _ = sapo.sapo_rollout_generate(other, torch.from_numpy(prompts_np[half:]).cuda(), G, N, 1.0,
+                                              wl.rollout_seed + 1)
+        torch.cuda.synchronize()
+        del other
+        seq_src = torch.cat([torch.from_numpy(np.repeat(prompts_np, G, axis=0)).cuda(),
+                             torch.cat([t_loc, t_ext], dim=0)], dim=1).contiguous()
+    prompts = torch.from_numpy(prompts_np).cuda()
+    plan = {"S": S, "N": N, "Lp": Lp, "P": P, "T": T, "Tm": Tm, "S_score": S_score, "rollout": do_rollout,
+            "score": do_score, "fused_lm": S <= 64 and shape.d_model <= 1024}
+
+    if do_rollout:
+        ws_r = torch.empty(sapo.sapo_rollout_workspace_bytes(gw, P, Lp, G, N) + 256, dtype=torch.uint8, device="cuda")
+        out_tok = torch.empty((S, N), dtype=torch.int32, device="cuda")
+        out_lp = torch.empty((S, N), dtype=torch.float32, device="cuda")
+        prompt_rep = prompts.repeat_interleave(G, dim=0)
+    if do_score:
+        rewards = torch.from_numpy(W.make_rewards(S_score, wl.reward_p, wl.reward_seed)).cuda()
+        mask = torch.from_numpy(W.make_completion_mask(S_score, T, Tm)).cuda()
+        ws_s = torch.empty(sapo.sapo_score_workspace_bytes(gw, S_score, T) + 256, dtype=torch.uint8, device="cuda")
+        sc_lp = torch.empty((S_score, T), dtype=torch.float32, device="cuda")
+        sc_adv = torch.empty((S_score,), dtype=torch.float32, device="cuda")
+    setup_s = time.time() - t0
+
+    if args.copy_probe:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+
     def step(i):
         ev[0].record()
-        sapo.sapo_rollout_generate(gw, prompts, G, N, wl.temperature, wl.rollout_seed + i, workspace=ws_r,
-                                   out_tokens=out_tok, out_logprobs=out_lp)
+        if do_rollout:
+            sapo.sapo_rollout_generate(gw, prompts, G, N, wl.temperature, wl.rollout_seed + i, workspace=ws_r,
+                                       out_tokens=out_tok, out_logprobs=out_lp)
         ev[1].record()
-        seqs = torch.cat([prompt_rep, out_tok], dim=1).contiguous()
-        sapo.sapo_score_logprobs(gw, seqs, mask, rewards, G, workspace=ws_s, out_logprobs=sc_lp,
-                                 out_advantages=sc_adv)
+        if do_score:
+            seqs = seq_src if seq_src is not None else torch.cat([prompt_rep, out_tok], dim=1).contiguous()
+            sapo.sapo_score_logprobs(gw, seqs, mask, rewards, G, workspace=ws_s, out_logprobs=sc_lp,
+                                     out_advantages=sc_adv)
         ev[2].record()
 
     for i in range(args.warmup):
@@ -139,30 +185,64 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t_start) * 1e3 / max(1, args.steps)
     r_ms, s_ms = float(np.median(roll_ms)), float(np.median(score_ms))
+    step_ms = r_ms + s_ms
 
-    # sanity: the path produced finite log-probs and self-consistent outputs
-    lp_gap = float((sc_lp[:, Lp:] - out_lp).abs().max().item())
-    assert torch.isfinite(sc_lp).all() and lp_gap < 5e-2, lp_gap
+    # sanity: finite outputs; decode with the cache reproduces the teacher-forced log-probs
+    lp_gap = None
+    if do_score:
+        assert torch.isfinite(sc_lp).all()
+    if do_rollout and do_score:
+        lp_gap = float((sc_lp[:, Lp:] - out_lp).abs().max().item())
+        assert lp_gap < 4e-2, lp_gap
 
-    gen_tokens, scored_tokens = S * N, S * T
-    ab = algorithmic_bytes_rollout(shape, P, G, Lp, N)
-    bytes_shared = ab["weights"] + ab["kv_read_shared"] + ab["kv_write"]
-    bytes_unshared = ab["weights"] + ab["kv_read_unshared"] + ab["kv_write"]
-    fl = algorithmic_flops_score(shape, S, T, Tm)
-    roll_gbs = bytes_shared / (r_ms * 1e-3) / 1e9
-    score_tflops = fl["total"] / (s_ms * 1e-3) / 1e12
+    gen_tokens = S * N if do_rollout else 0
+    scored_tokens = S_score * T if do_score else 0
+    out = {
+        "metric": "rollout tokens/s + scored tokens/s (0.5B GQA, 1 GPU)" if shape.d_model == 896 else
+                  "rollout tokens/s + scored tokens/s (%s, 1 GPU)" % wl.name,
+        "value": round((gen_tokens + scored_tokens) / (step_ms * 1e-3), 1),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(step_ms, 3), "wall_ms_per_step": round(wall_ms, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if shape.dtype == "f32" else "f16", "data": "synthetic",
+        "config": {"workload": wl.name, "layers": shape.n_layers, "d_model": shape.d_model,
+                   "heads": "%dq/%dkv x %d" % (shape.n_q_heads, shape.n_kv_heads, shape.head_dim),
+                   "d_ff": shape.d_ff, "vocab": shape.vocab,
+                   "weights": "fp32" if shape.dtype == "f32" else "bf16 values, MFMA operands in IEEE half, fp32 accumulation",
+                   "prompts": P, "completions_per_prompt": G, "prompt_len": Lp, "new_tokens": N,
+                   "temperature": wl.temperature, "timed": ("rollout+" if do_rollout else "") + ("score" if do_score else ""),
+                   "score_seqs": S_score, "score_len": T, "score_masked": Tm, "mfma_path": bool(gw.uses_mfma)},
+    }
+    if do_rollout:
+        ab = algorithmic_bytes_rollout(shape, P, G, Lp, N)
+        bytes_shared = ab["weights"] + ab["kv_read_shared"] + ab["kv_write"]
+        bytes_unshared = ab["weights"] + ab["kv_read_unshared"] + ab["kv_write"]
+        roll_gbs = bytes_shared / (r_ms * 1e-3) / 1e9
+        out.update({"rollout_tokens_per_s": round(gen_tokens / (r_ms * 1e-3), 1), "rollout_ms": round(r_ms, 3),
+                    "rollout_hbm": {"algorithmic_bytes_shared": bytes_shared, "algorithmic_bytes_unshared": bytes_unshared,
+                                    "achieved_GBs": round(roll_gbs, 1), "peak_GBs": HBM_PEAK_GBS,
+                                    "frac": round(roll_gbs / HBM_PEAK_GBS, 4)}})
+    if do_score:
+        fl = algorithmic_flops_score(shape, S_score, T, Tm)
+        score_tflops = fl["total"] / (s_ms * 1e-3) / 1e12
+        out.update({"scored_tokens_per_s": round(scored_tokens / (s_ms * 1e-3), 1), "score_ms": round(s_ms, 3),
+                    "score_mfma": {"algorithmic_flops": fl["total"], "achieved_TFLOPs": round(score_tflops, 2),
+                                   "peak_TFLOPs": MFMA_16BIT_PEAK_TFLOPS,
+                                   "frac": round(score_tflops / MFMA_16BIT_PEAK_TFLOPS, 4)}})
+    if lp_gap is not None:
+        out["rollout_vs_score_logprob_max_abs"] = round(lp_gap, 6)
 
-    # per-kernel durations with HIP events (one extra, untimed-for-throughput step)
+    # per-kernel durations: one extra step in which every launch carries two HIP events (on the launch
+    # stream) that take the kernel's own start and end timestamps
     kernels = {}
     roofline = None
     if not args.no_kernel_profile:
-        # every launch carries two HIP events (on the launch stream) that take the kernel's own
-        # start and end timestamps
         sapo.sapo_profile_start()
         step(999)
         prof = sapo.sapo_profile_stop()
         for name, (ms, cnt) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
-            bound, work = per_launch_work(shape, wl, name, cnt)
+            bound, work = per_launch_work(shape, plan, name, cnt)
             avg_us = ms * 1e3 / cnt
             ent = {"launches": cnt, "total_ms": round(ms, 3), "avg_us": round(avg_us, 3)}
             if bound == "hbm":
@@ -172,13 +252,13 @@ def main():
             elif bound == "mfma":
                 ach = work / (avg_us * 1e-6) / 1e12
                 ent.update(bound="mfma", work_per_launch=work, achieved=round(ach, 2), unit="TFLOP/s",
-                           frac=round(ach / MFMA_BF16_PEAK_TFLOPS, 4))
+                           frac=round(ach / MFMA_16BIT_PEAK_TFLOPS, 4))
             kernels[name] = ent
         dom = next((n for n in kernels if "bound" in kernels[n]), None)
         if dom:
             k = kernels[dom]
             roofline = {"kernel": dom, "bound": k["bound"], "achieved": k["achieved"],
-                        "peak": HBM_PEAK_GBS if k["bound"] == "hbm" else MFMA_BF16_PEAK_TFLOPS, "unit": k["unit"],
+                        "peak": HBM_PEAK_GBS if k["bound"] == "hbm" else MFMA_16BIT_PEAK_TFLOPS, "unit": k["unit"],
                         "frac": k["frac"], "traffic": None, "avg_us": k["avg_us"], "launches": k["launches"],
                         "work_per_launch": k["work_per_launch"]}
 
@@ -189,50 +269,32 @@ def main():
         ncores = len(os.sched_getaffinity(0))
         m = O.Model(shape, weights)
         big = shape.d_model >= 512
-        p_n, g_n, n_n = (1, 2, 6) if big else (P, G, N)
-        s_n = 1 if big else S
-        t1 = time.perf_counter()
-        O.rollout_generate(m, prompts_np[:p_n], g_n, n_n, wl.temperature, wl.rollout_seed)
-        t2 = time.perf_counter()
-        seq_np = np.concatenate([np.repeat(prompts_np, G, axis=0), out_tok.cpu().numpy()], axis=1)[:s_n]
-        O.score_logprobs(m, seq_np, W.make_completion_mask(s_n, T, Tm))
-        t3 = time.perf_counter()
-        cpu_roll = p_n * g_n * n_n / (t2 - t1)
-        cpu_score = s_n * T / (t3 - t2)
-        cpu_step_s = gen_tokens / cpu_roll + scored_tokens / cpu_score
+        parts, cpu_step_s = [], 0.0
+        res = {}
+        if do_rollout:
+            p_n, g_n, n_n = (1, 2, 6) if big else (P, G, N)
+            t1 = time.perf_counter()
+            O.rollout_generate(m, prompts_np[:p_n], g_n, n_n, wl.temperature, wl.rollout_seed)
+            dt = time.perf_counter() - t1
+            res["rollout_tokens_per_s"] = round(p_n * g_n * n_n / dt, 3)
+            cpu_step_s += gen_tokens / (p_n * g_n * n_n / dt)
+            parts.append("rollout of %d prompt(s) x %d completions x %d new tokens (prompt %d) in %.1f s"
+                         % (p_n, g_n, n_n, Lp, dt))
+        if do_score:
+            s_n = 1 if big else S_score
+            seq_np = (seq_src if seq_src is not None else torch.cat([prompt_rep, out_tok], dim=1))[:s_n].cpu().numpy()
+            t1 = time.perf_counter()
+            O.score_logprobs(m, seq_np, W.make_completion_mask(s_n, T, Tm))
+            dt = time.perf_counter() - t1
+            res["scored_tokens_per_s"] = round(s_n * T / dt, 2)
+            cpu_step_s += scored_tokens / (s_n * T / dt)
+            parts.append("scoring of %d sequence(s) x %d tokens in %.1f s" % (s_n, T, dt))
         cpu = {"value": round((gen_tokens + scored_tokens) / cpu_step_s, 2), "unit": "tokens/s", "cores": ncores,
                "kind": "oracle",
-               "sample": "numpy fp64 oracle: rollout of %d prompt(s) x %d completions x %d new tokens (prompt %d) in "
-                         "%.1f s, scoring of %d sequence(s) x %d tokens in %.1f s; whole-step rate extrapolated from "
-                         "the two slice rates" % (p_n, g_n, n_n, Lp, t2 - t1, s_n, T, t3 - t2),
-               "rollout_tokens_per_s": round(cpu_roll, 3), "scored_tokens_per_s": round(cpu_score, 2)}
+               "sample": "numpy fp64 oracle: " + ", ".join(parts) + "; whole-step rate extrapolated from the slice rates"}
+        cpu.update(res)
 
-    step_ms = r_ms + s_ms
-    out = {
-        "metric": "rollout tokens/s + scored tokens/s (0.5B GQA, 1 GPU)" if "halfb" in wl.name else
-                  "rollout tokens/s + scored tokens/s (%s, 1 GPU)" % wl.name,
-        "value": round((gen_tokens + scored_tokens) / (step_ms * 1e-3), 1),
-        "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(step_ms, 3), "wall_ms_per_step": round(wall_ms, 3),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": wl.name, "layers": shape.n_layers, "d_model": shape.d_model,
-                   "heads": "%dq/%dkv x %d" % (shape.n_q_heads, shape.n_kv_heads, shape.head_dim),
-                   "d_ff": shape.d_ff, "vocab": shape.vocab, "prompts": P, "completions_per_prompt": G,
-                   "prompt_len": Lp, "new_tokens": N, "temperature": wl.temperature,
-                   "score_seqs": S, "score_len": T, "score_masked": Tm, "mfma_path": bool(gw.uses_mfma)},
-        "rollout_tokens_per_s": round(gen_tokens / (r_ms * 1e-3), 1), "rollout_ms": round(r_ms, 3),
-        "scored_tokens_per_s": round(scored_tokens / (s_ms * 1e-3), 1), "score_ms": round(s_ms, 3),
-        "rollout_hbm": {"algorithmic_bytes_shared": bytes_shared, "algorithmic_bytes_unshared": bytes_unshared,
-                        "achieved_GBs": round(roll_gbs, 1), "peak_GBs": HBM_PEAK_GBS,
-                        "frac": round(roll_gbs / HBM_PEAK_GBS, 4)},
-        "score_mfma": {"algorithmic_flops": fl["total"], "achieved_TFLOPs": round(score_tflops, 2),
-                       "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS, "frac": round(score_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
-        "rollout_vs_score_logprob_max_abs": round(lp_gap, 6),
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
-        "setup_s": round(setup_s, 1),
-    }
+    out.update({"roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "setup_s": round(setup_s, 1)})
     print(json.dumps(out))
 
 
