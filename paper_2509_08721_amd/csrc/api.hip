@@ -494,7 +494,8 @@ struct RolloutPlan {
   float* logits;    // [max(P, S), V] (paths that materialise logits)
   float* partials;  // fused sampler partials
   DecodeBufs dec;   // MFMA decode path
-  bool fused_lm;    // LM head + sampler fused (at most 64 sequences)
+  bool fused_lm;    // LM head + sampler fused, 64-token kernel
+  bool big_lm;      // LM head + sampler fused, token-parallel kernel (more sequences or a wider model)
   size_t bytes;
 };
 
@@ -515,8 +516,10 @@ static void plan_rollout(const sapo_weights* w, int P, int Lp, int G, int N, cha
   pl.h_last = A.take<float>((size_t)pl.S * c.d_model);
   pl.x_last = A.take_bytes((R + 63) / 64 * 64 * c.d_model * w->elt);
   pl.fused_lm = w->mfma && d_lmhead_sample_supported(c.d_model, pl.S);
-  pl.logits = pl.fused_lm ? nullptr : A.take<float>(R * c.vocab);
-  pl.partials = pl.fused_lm ? A.take<float>(d_lmhead_sample_partial_floats()) : nullptr;
+  pl.big_lm = w->mfma && !pl.fused_lm;
+  pl.logits = w->mfma ? nullptr : A.take<float>(R * c.vocab);
+  pl.partials = pl.fused_lm ? A.take<float>(d_lmhead_sample_partial_floats())
+                : pl.big_lm ? A.take<float>((size_t)m_lmhead_sample_big_groups(c.vocab) * pl.S * 5) : nullptr;
   if (w->mfma) carve_decode(A, w, pl.S, pl.dec);
   pl.bytes = (A.off + 255) & ~(size_t)255;
 }
@@ -551,9 +554,13 @@ static int sample_step(const sapo_weights* w, const RolloutPlan& pl, const float
                            pl.partials, w->embed, gain_first, pl.fwd.h, pl.dec.xa, pl.dec.ssq_a, st));
     return SAPO_OK;
   }
-  if (w->mfma) {
+  if (pl.big_lm) {
+    const float* gain_first = c.n_layers > 0 ? w->layers[0].attn_norm : w->final_norm;
     HIP_CK(m_rmsnorm_x32(h, w->final_norm, c.rms_eps, pl.x_last, S, d, nullptr, st));
-    HIP_CK(m_gemm_big(pl.x_last, w->lm_head, S, V, d, BigEpi{BIG_STORE_F32, pl.logits, V, nullptr}, st));
+    HIP_CK(m_lmhead_sample_big(pl.x_last, w->lm_head, S, V, d, sp, pl.partials, st));
+    HIP_CK(d_lmhead_merge_embed(pl.partials, m_lmhead_sample_big_groups(V), S, S, sp, w->embed, d, gain_first, pl.fwd.h,
+                                pl.dec.xa, pl.dec.ssq_a, st));
+    return SAPO_OK;
   } else {
     HIP_CK(g_rmsnorm(c.dtype, h, w->final_norm, c.rms_eps, pl.x_last, S, d, nullptr, st));
     HIP_CK(g_gemm(c.dtype, pl.x_last, w->lm_head, pl.logits, S, V, d, V, EPI_STORE_F32, st));
@@ -623,8 +630,7 @@ extern "C" int sapo_rollout_generate(const sapo_weights* w, const int32_t* promp
     int rc2;
     HIP_CK(g_incr(pl.step, st));
     if (w->mfma) {
-      if (!pl.fused_lm)   // the fused sampler's merge has already gathered the rows
-        HIP_CK(d_embed_x16(out_tokens, max_new, pl.step, w->embed, S, d, gain_first, pl.fwd.h, pl.dec.xa, pl.dec.ssq_a, st));
+      // (the sampler's merge has already gathered the embedding rows of the previous step's tokens)
       if ((rc2 = run_layers_decode16(w, pl.fwd, pl.dec, S, rm, pl.cache, st))) return rc2;
       if ((rc2 = sample_step(w, pl, pl.fwd.h, parts_after_layers, sp, st))) return rc2;
     } else {

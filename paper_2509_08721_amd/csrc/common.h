@@ -242,6 +242,11 @@ hipError_t m_lmhead_score(const void* Xp, const void* Wp, int max_rows, const in
                           const int* row_seq_pos, const int32_t* tokens, int T, float* partials, float* out_logprobs,
                           hipStream_t st);
 size_t m_lmhead_score_partial_floats(int max_rows, int V);
+// Fused LM head + sampler for any number of sequences and any K: Xp = final-normed rows in X32 order.
+// partials: [m_lmhead_sample_big_groups(V)][n_rows][5].
+int m_lmhead_sample_big_groups(int V);
+hipError_t m_lmhead_sample_big(const void* Xp, const void* Wp, int n_rows, int V, int K, SampleParams sp, float* partials,
+                               hipStream_t st);
 // causal GQA attention over rows laid out [n_seq, rm.T] (block mode), K/V from the paged cache;
 // q row-major, out in X32 order
 hipError_t m_flash_attention(const void* q, RowMap rm, KVCache kv, void* out, int n_seq, int n_q_heads, hipStream_t st);
@@ -279,6 +284,11 @@ size_t d_lmhead_sample_partial_floats();
 hipError_t d_lmhead_sample(const void* Wp, const void* Xp, int K, int V, const float* ssq, int ssq_parts, int s_pad,
                            float eps, int n_rows, SampleParams sp, float* partials, const void* embed,
                            const float* gain_first, float* h, void* xp_first, float* ssq_first, hipStream_t st);
+// Merge of sampler partials [n_parts][row_stride][5] of n_rows sequences: token + log-prob of the step,
+// then the embedding gather for the next step.
+hipError_t d_lmhead_merge_embed(const float* partials, int n_parts, int row_stride, int n_rows, SampleParams sp,
+                                const void* embed, int d, const float* gain_first, float* h, void* xp_first,
+                                float* ssq_first, hipStream_t st);
 hipError_t d_decode_attention(const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* out_x16, int S,
                               int n_q_heads, hipStream_t st);
 hipError_t g_gather_last_rows(const float* h, float* out, int S, int G, int Lp, int d, hipStream_t st);

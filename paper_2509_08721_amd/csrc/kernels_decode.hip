@@ -117,7 +117,11 @@ __device__ __forceinline__ float ssq_scale(const float* s_part, int tok_local, i
 // ---------------------------------------------------------------------------------------
 template <int NT, int TG, int R, int MODE>
 __global__ void __launch_bounds__(512) k_skinny16(SkinnyArgs a, int n_units) {
-  extern __shared__ float4 red[];   // [8 waves][NT * TG][64 lanes]
+  // the 8 partial results meet in LDS CH tiles at a time: [8 waves][CH * TG][64 lanes] float4 <= 128 KiB
+  constexpr int CH = (NT * TG > 16) ? 16 / TG : NT;
+  static_assert(NT % CH == 0 && (MODE != SKM_SWIGLU || CH % 2 == 0), "tile chunking");
+  constexpr int RS = (CH * TG * 64 + 511) / 512;   // output slots per thread and chunk
+  extern __shared__ float4 red[];
   __shared__ float s_part[512];
   constexpr int TS = 4 / TG;        // workgroups per (tile unit, token block)
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -135,15 +139,23 @@ __global__ void __launch_bounds__(512) k_skinny16(SkinnyArgs a, int n_units) {
     for (int g = 0; g < TG; ++g) acc[t][g] = f32x4{0.f, 0.f, 0.f, 0.f};
   float sq[kSsqPerThread];
   if (MODE != SKM_RESID) ssq_issue(a.ssq_in, a.ssq_parts, a.s_pad, tb * 64, sq);
-  // RESID: this thread's output slot and its residual / gain operands, requested up front
-  float4 h_old = make_float4(0.f, 0.f, 0.f, 0.f), g_next = h_old;
-  if (MODE == SKM_RESID && tid < NT * TG * 64) {
-    const int t = tid / (TG * 64), g = (tid >> 6) % TG, l = tid & 63;
-    const int tok = tb * 64 + (tg0 + g) * 16 + (l & 15);
-    const int f0 = (tile0 + t) * 16 + (l >> 4) * 4;
-    if (tok < a.n_rows) {
-      h_old = *(const float4*)(a.h + (size_t)tok * a.N + f0);
-      g_next = *(const float4*)(a.gain_next + f0);
+  // RESID, single chunk: this thread's residual / gain operands are requested up front
+  float4 h_old[RS], g_next[RS];
+  if (MODE == SKM_RESID && CH == NT) {
+#pragma unroll
+    for (int i = 0; i < RS; ++i) {
+      const int slot = tid + 512 * i;
+      h_old[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      g_next[i] = h_old[i];
+      if (slot < NT * TG * 64) {
+        const int t = slot / (TG * 64), g = (slot >> 6) % TG, l = slot & 63;
+        const int tok = tb * 64 + (tg0 + g) * 16 + (l & 15);
+        const int f0 = (tile0 + t) * 16 + (l >> 4) * 4;
+        if (tok < a.n_rows) {
+          h_old[i] = *(const float4*)(a.h + (size_t)tok * a.N + f0);
+          g_next[i] = *(const float4*)(a.gain_next + f0);
+        }
+      }
     }
   }
 
@@ -173,84 +185,92 @@ __global__ void __launch_bounds__(512) k_skinny16(SkinnyArgs a, int n_units) {
       }
     }
   }
-  // cross-wave reduction
-#pragma unroll
-  for (int t = 0; t < NT; ++t)
-#pragma unroll
-    for (int g = 0; g < TG; ++g)
-      red[(size_t)(wave * NT * TG + t * TG + g) * 64 + lane] = make_float4(acc[t][g][0], acc[t][g][1], acc[t][g][2], acc[t][g][3]);
   if (MODE != SKM_RESID) ssq_publish(sq, s_part);
-  __syncthreads();
-  auto sum8 = [&](int tg, int l) -> float4 {   // tg = t * TG + g
+  auto sum8 = [&](int tg, int l) -> float4 {   // tg = (t - chunk start) * TG + g
     float4 s = red[(size_t)tg * 64 + l];
 #pragma unroll
     for (int w = 1; w < 8; ++w) {
-      const float4 p = red[(size_t)(w * NT * TG + tg) * 64 + l];
+      const float4 p = red[(size_t)(w * CH * TG + tg) * 64 + l];
       s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
     }
     return s;
   };
-  if (MODE == SKM_SWIGLU) {
-    const int KSo = (a.N >> 1) >> 5;   // act has F = N / 2 features
-    for (int slot = tid; slot < (NT / 2) * TG * 64; slot += 512) {
-      const int pp = slot / (TG * 64), g = (slot >> 6) % TG, l = slot & 63;
-      const float4 gs = sum8((2 * pp) * TG + g, l), us = sum8((2 * pp + 1) * TG + g, l);
-      const int tl = (tg0 + g) * 16 + (l & 15), tok = tb * 64 + tl;
-      const int f0 = ((tile0 >> 1) + pp) * 16 + (l >> 4) * 4;
-      f16x4 o;
-      if (tok < a.n_rows) {
-        const float sc = ssq_scale(s_part, tl, a.norm_dim, a.eps);
-        o[0] = from_f32<f16>(silu_f(gs.x * sc) * (us.x * sc)); o[1] = from_f32<f16>(silu_f(gs.y * sc) * (us.y * sc));
-        o[2] = from_f32<f16>(silu_f(gs.z * sc) * (us.z * sc)); o[3] = from_f32<f16>(silu_f(gs.w * sc) * (us.w * sc));
-      } else {
-        o[0] = o[1] = o[2] = o[3] = (f16)0.f;
+#pragma unroll
+  for (int c0 = 0; c0 < NT; c0 += CH) {
+    // cross-wave reduction of tiles c0 .. c0 + CH - 1
+    if (c0 > 0) __syncthreads();
+#pragma unroll
+    for (int t = 0; t < CH; ++t)
+#pragma unroll
+      for (int g = 0; g < TG; ++g)
+        red[(size_t)(wave * CH * TG + t * TG + g) * 64 + lane] =
+            make_float4(acc[c0 + t][g][0], acc[c0 + t][g][1], acc[c0 + t][g][2], acc[c0 + t][g][3]);
+    __syncthreads();
+    if (MODE == SKM_SWIGLU) {
+      const int KSo = (a.N >> 1) >> 5;   // act has F = N / 2 features
+      for (int slot = tid; slot < (CH / 2) * TG * 64; slot += 512) {
+        const int pp = slot / (TG * 64), g = (slot >> 6) % TG, l = slot & 63;
+        const float4 gs = sum8((2 * pp) * TG + g, l), us = sum8((2 * pp + 1) * TG + g, l);
+        const int tl = (tg0 + g) * 16 + (l & 15), tok = tb * 64 + tl;
+        const int f0 = (((tile0 + c0) >> 1) + pp) * 16 + (l >> 4) * 4;
+        f16x4 o;
+        if (tok < a.n_rows) {
+          const float sc = ssq_scale(s_part, tl, a.norm_dim, a.eps);
+          o[0] = from_f32<f16>(silu_f(gs.x * sc) * (us.x * sc)); o[1] = from_f32<f16>(silu_f(gs.y * sc) * (us.y * sc));
+          o[2] = from_f32<f16>(silu_f(gs.z * sc) * (us.z * sc)); o[3] = from_f32<f16>(silu_f(gs.w * sc) * (us.w * sc));
+        } else {
+          o[0] = o[1] = o[2] = o[3] = (f16)0.f;
+        }
+        *(f16x4*)((f16*)a.xp_out + x16_chunk(tok, f0, KSo) * 8 + (f0 & 4)) = o;
       }
-      *(f16x4*)((f16*)a.xp_out + x16_chunk(tok, f0, KSo) * 8 + (f0 & 4)) = o;
-    }
-    return;
-  }
-  if (MODE == SKM_STORE) {
-    for (int slot = tid; slot < NT * TG * 64; slot += 512) {
-      const int t = slot / (TG * 64), g = (slot >> 6) % TG, l = slot & 63;
-      const float4 s = sum8(t * TG + g, l);
-      const int tl = (tg0 + g) * 16 + (l & 15), tok = tb * 64 + tl;
-      const int f0 = (tile0 + t) * 16 + (l >> 4) * 4;
-      if (tok < a.n_rows) {
-        const float sc = ssq_scale(s_part, tl, a.norm_dim, a.eps);
-        *(float4*)(a.out_f32 + (size_t)tok * a.ldc + f0) = make_float4(s.x * sc, s.y * sc, s.z * sc, s.w * sc);
+    } else if (MODE == SKM_STORE) {
+      for (int slot = tid; slot < CH * TG * 64; slot += 512) {
+        const int t = slot / (TG * 64), g = (slot >> 6) % TG, l = slot & 63;
+        const float4 s = sum8(t * TG + g, l);
+        const int tl = (tg0 + g) * 16 + (l & 15), tok = tb * 64 + tl;
+        const int f0 = (tile0 + c0 + t) * 16 + (l >> 4) * 4;
+        if (tok < a.n_rows) {
+          const float sc = ssq_scale(s_part, tl, a.norm_dim, a.eps);
+          *(float4*)(a.out_f32 + (size_t)tok * a.ldc + f0) = make_float4(s.x * sc, s.y * sc, s.z * sc, s.w * sc);
+        }
       }
-    }
-    return;
-  }
-  // RESID: one slot per thread (NT * TG * 64 <= 512)
-  if (tid < NT * TG * 64) {
-    const int t = tid / (TG * 64), g = (tid >> 6) % TG, l = tid & 63;
-    float4 s = sum8(t * TG + g, l);
-    const int tok = tb * 64 + (tg0 + g) * 16 + (l & 15);
-    const int f0 = (tile0 + t) * 16 + (l >> 4) * 4;
-    f16x4 o;
-    float q = 0.f;
-    if (tok < a.n_rows) {
-      s.x += h_old.x; s.y += h_old.y; s.z += h_old.z; s.w += h_old.w;
-      *(float4*)(a.h + (size_t)tok * a.N + f0) = s;
-      o[0] = from_f32<f16>(s.x * g_next.x); o[1] = from_f32<f16>(s.y * g_next.y);
-      o[2] = from_f32<f16>(s.z * g_next.z); o[3] = from_f32<f16>(s.w * g_next.w);
-      q = s.x * s.x + s.y * s.y + s.z * s.z + s.w * s.w;
     } else {
-      o[0] = o[1] = o[2] = o[3] = (f16)0.f;
+#pragma unroll
+      for (int i = 0; i < RS; ++i) {
+        const int slot = tid + 512 * i;
+        if (slot >= CH * TG * 64) break;   // a whole wave leaves together (64 slots per wave)
+        const int t = slot / (TG * 64), g = (slot >> 6) % TG, l = slot & 63;
+        float4 s = sum8(t * TG + g, l);
+        const int tok = tb * 64 + (tg0 + g) * 16 + (l & 15);
+        const int f0 = (tile0 + c0 + t) * 16 + (l >> 4) * 4;
+        f16x4 o;
+        float q = 0.f;
+        if (tok < a.n_rows) {
+          float4 ho, gn;
+          if (CH == NT) { ho = h_old[i]; gn = g_next[i]; }
+          else { ho = *(const float4*)(a.h + (size_t)tok * a.N + f0); gn = *(const float4*)(a.gain_next + f0); }
+          s.x += ho.x; s.y += ho.y; s.z += ho.z; s.w += ho.w;
+          *(float4*)(a.h + (size_t)tok * a.N + f0) = s;
+          o[0] = from_f32<f16>(s.x * gn.x); o[1] = from_f32<f16>(s.y * gn.y);
+          o[2] = from_f32<f16>(s.z * gn.z); o[3] = from_f32<f16>(s.w * gn.w);
+          q = s.x * s.x + s.y * s.y + s.z * s.z + s.w * s.w;
+        } else {
+          o[0] = o[1] = o[2] = o[3] = (f16)0.f;
+        }
+        *(f16x4*)((f16*)a.xp_out + x16_chunk(tok, f0, a.N >> 5) * 8 + (f0 & 4)) = o;
+        q += __shfl_xor(q, 16, 64);
+        q += __shfl_xor(q, 32, 64);
+        if (l < 16) a.ssq_out[(size_t)(tile0 + c0 + t) * a.s_pad + tok] = q;
+      }
     }
-    *(f16x4*)((f16*)a.xp_out + x16_chunk(tok, f0, a.N >> 5) * 8 + (f0 & 4)) = o;
-    q += __shfl_xor(q, 16, 64);
-    q += __shfl_xor(q, 32, 64);
-    if (l < 16) a.ssq_out[(size_t)(tile0 + t) * a.s_pad + tok] = q;
   }
 }
 
 template <int NT, int TG, int R, int MODE>
 static hipError_t launch_skinny(const SkinnyArgs& a, hipStream_t st) {
-  static_assert(MODE != SKM_RESID || NT * TG * 64 <= 512, "RESID epilogue handles one slot per thread");
+  constexpr int CH = (NT * TG > 16) ? 16 / TG : NT;
   static bool attr_done = false;
-  const size_t smem = (size_t)8 * NT * TG * 64 * sizeof(float4);
+  const size_t smem = (size_t)8 * CH * TG * 64 * sizeof(float4);
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void*)k_skinny16<NT, TG, R, MODE>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -264,19 +284,29 @@ static hipError_t launch_skinny(const SkinnyArgs& a, hipStream_t st) {
   return launch(KID_GEMM_SKINNY, k_skinny16<NT, TG, R, MODE>, dim3(gx, blocks), dim3(512), smem, st, a, units);
 }
 
+// Blocking.  A workgroup reads NT weight tiles and TG token groups over the whole K, so what it must
+// ingest is (NT + TG) * K * 32 bytes for NT * TG output tiles.  With one 64-token block the kernels
+// are latency-bound and small workgroups win (1 x 1; the gate/up pairs 4 x 4); with several blocks
+// the re-reads of the token operand dominate and the blocking goes towards square.
 hipError_t d_gemm_skinny(const SkinnyArgs& a, int mode, hipStream_t st) {
   if (a.K % 32 != 0 || a.N % 16 != 0 || a.n_rows <= 0) return hipErrorInvalidValue;
   if (mode != SKM_RESID && a.ssq_parts > 8 * kSsqPerThread) return hipErrorInvalidValue;
   const int per_wave = ((a.K >> 5) + 7) / 8;   // k steps per wave
+  const int tiles = a.N / 16;
+  const bool multi = a.n_rows > 64;
   if (mode == SKM_SWIGLU) {
     if (a.N % 64 != 0) return hipErrorInvalidValue;
+    if (multi && tiles % 8 == 0) return launch_skinny<8, 4, 2, SKM_SWIGLU>(a, st);
     if (per_wave <= 4) return launch_skinny<4, 4, 4, SKM_SWIGLU>(a, st);
     return launch_skinny<2, 4, 6, SKM_SWIGLU>(a, st);
   }
   if (mode == SKM_STORE) {
+    if (multi && tiles % 4 == 0) return launch_skinny<4, 4, 3, SKM_STORE>(a, st);
     if (per_wave <= 4) return launch_skinny<1, 1, 4, SKM_STORE>(a, st);
     return launch_skinny<1, 1, 8, SKM_STORE>(a, st);
   }
+  if (multi && per_wave <= 8 && tiles % 4 == 0) return launch_skinny<4, 4, 3, SKM_RESID>(a, st);
+  if (multi && tiles % 2 == 0) return launch_skinny<2, 2, 9, SKM_RESID>(a, st);
   if (per_wave <= 4) return launch_skinny<1, 1, 4, SKM_RESID>(a, st);
   if (per_wave <= 8) return launch_skinny<1, 1, 8, SKM_RESID>(a, st);
   return launch_skinny<1, 1, 20, SKM_RESID>(a, st);
@@ -484,8 +514,8 @@ __global__ void __launch_bounds__(512) k_lmhead_sample16(const uint4* __restrict
 // Merge the per-workgroup partials of one sequence, write its token and log-prob, and gather the
 // token's embedding row as the input of the next decode step (residual row, X16 row for the first
 // layer's norm gain, sum of squares).  One workgroup of 128 threads per sequence.
-__global__ void __launch_bounds__(128) k_lmhead_merge_embed(const float* __restrict__ partials, int n_wg, int seq0,
-                                                            SampleParams sp, const bf16* __restrict__ embed, int d,
+__global__ void __launch_bounds__(128) k_lmhead_merge_embed(const float* __restrict__ partials, int n_wg, int row_stride,
+                                                            int seq0, SampleParams sp, const bf16* __restrict__ embed, int d,
                                                             const float* __restrict__ gain, float* __restrict__ h,
                                                             uint4* __restrict__ xp, float* __restrict__ ssq) {
   __shared__ float red[2];
@@ -495,7 +525,7 @@ __global__ void __launch_bounds__(128) k_lmhead_merge_embed(const float* __restr
     LseAcc a; a.init();
     BestAcc b; b.init();
     for (int w = lane; w < n_wg; w += 64) {
-      const float* p = partials + ((size_t)w * 64 + r) * 5;
+      const float* p = partials + ((size_t)w * row_stride + r) * 5;
       a.merge(p[0], p[1]);
       b.add(p[2], p[3], ((const int*)p)[4]);
     }
@@ -552,8 +582,14 @@ hipError_t d_lmhead_sample(const void* Wp, const void* Xp, int K, int V, const f
       e = launch_lmhead<1>((const uint4*)Wp, (const uint4*)Xp, KS, n_tiles, ssq, ssq_parts, s_pad, K, eps, n_rows, 0, sp, partials, n_wg, st);
   }
   if (e != hipSuccess) return e;
-  return launch(KID_LMHEAD_SAMPLE_MERGE, k_lmhead_merge_embed, dim3(n_rows), dim3(128), 0, st, partials, n_wg, 0, sp, (const bf16*)embed, K, gain_first, h, (uint4*)xp_first,
-                                               ssq_first);
+  return d_lmhead_merge_embed(partials, n_wg, 64, n_rows, sp, embed, K, gain_first, h, xp_first, ssq_first, st);
+}
+
+hipError_t d_lmhead_merge_embed(const float* partials, int n_parts, int row_stride, int n_rows, SampleParams sp,
+                                const void* embed, int d, const float* gain_first, float* h, void* xp_first,
+                                float* ssq_first, hipStream_t st) {
+  return launch(KID_LMHEAD_SAMPLE_MERGE, k_lmhead_merge_embed, dim3(n_rows), dim3(128), 0, st, partials, n_parts, row_stride,
+                0, sp, (const bf16*)embed, d, gain_first, h, (uint4*)xp_first, ssq_first);
 }
 
 // =======================================================================================

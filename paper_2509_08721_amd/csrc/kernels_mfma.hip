@@ -101,17 +101,27 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
 // Block id -> (feature tile bx, token tile by).  Block ids are dealt round-robin to the 8 XCDs, each
-// with its own L2: XCD c owns the token tiles 8 y' + c and walks them in supertiles of 8 token
-// tiles x 8 feature tiles (feature tiles fastest), the 64 workgroups it runs at a time.
+// with its own L2.  With 8 or more token tiles XCD c owns the token tiles 8 y' + c and walks them in
+// supertiles of 8 token tiles x 8 feature tiles (feature tiles fastest), the 64 workgroups it runs at
+// a time.  With fewer token tiles XCD c owns the feature tiles 8 x' + c instead and walks each one's
+// token tiles back to back, so every weight tile is fetched into one L2 only.
 __device__ __forceinline__ bool big_raster(int NX, int NY, int& bx, int& by) {
-  const int NXs = (NX + 7) >> 3;
   const int b = blockIdx.x, xcd = b & 7, j = b >> 3;
+  if (NY < 8) {
+    by = j % NY;
+    bx = (j / NY) * 8 + xcd;
+    return bx < NX;
+  }
+  const int NXs = (NX + 7) >> 3;
   const int sti = j >> 6, w = j & 63;
   bx = (sti % NXs) * 8 + (w & 7);
   by = ((sti / NXs) * 8 + (w >> 3)) * 8 + xcd;
   return bx < NX && by < NY;
 }
-static int big_grid(int NX, int NY) { return 8 * ((NX + 7) / 8) * ((((NY + 7) / 8) + 7) / 8) * 64; }
+static int big_grid(int NX, int NY) {
+  if (NY < 8) return 8 * NY * ((NX + 7) / 8);
+  return 8 * ((NX + 7) / 8) * ((((NY + 7) / 8) + 7) / 8) * 64;
+}
 
 // acc = X[tblk0*32 .. +255][:] . W[fblk0*32 .. +127][:]^T over the whole K.  Token blocks past the end
 // are clamped to the last one (their results are never stored).
@@ -382,6 +392,100 @@ hipError_t m_lmhead_score(const void* Xp, const void* Wp, int max_rows, const in
   if (e != hipSuccess) return e;
   return launch(KID_LMHEAD_SCORE_MERGE, k_lmhead_score_merge, dim3((max_rows + 255) / 256), dim3(256), 0, st, partials,
                 max_rows, n_groups, n_rows_dev, row_seq_pos, T, out_logprobs);
+}
+
+// ---------------------------------------------------------------------------------------
+// LM head for decode with many sequences (or a K too large for the 64-token kernel): the scoring
+// GEMM's main loop with the sampler's epilogue, one (256 sequences x 128 vocabulary ids) tile per
+// workgroup.  A lane turns its quads of consecutive vocabulary ids into perturbed scores (one Philox
+// block per quad) and reduces, for each of its 4 sequences, (max, sum exp) and the best perturbed
+// score.  partials: [V / 128][n_rows][5].
+// ---------------------------------------------------------------------------------------
+int m_lmhead_sample_big_groups(int V) { return V >> 7; }
+
+__global__ void __launch_bounds__(256, 2) k_lmhead_sample_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp,
+                                                              int n_rows, int V, int K, SampleParams sp,
+                                                              float* __restrict__ partials) {
+  extern __shared__ uint4 smem[];
+  int ft, by;
+  if (!big_raster(V >> 7, (n_rows + 255) >> 8, ft, by)) return;
+  const int tok0 = by * 256;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wf = wave & 1, wt = wave >> 1;
+  f32x16 acc[2][4];
+  big_mainloop(Xp, Wp, (n_rows + 31) >> 5, K >> 4, by * 8, ft * 4, smem, acc);
+  resolve_sample_params(sp);
+  const int step = *sp.step;
+  const bool noisy = sp.temperature != 0.f;
+  const float inv_t = noisy ? 1.0f / sp.temperature : 1.0f;
+  wg_barrier();   // the ring is free: it carries the cross-wave merge
+  float* red = (float*)smem;   // [2][256][5]
+#pragma unroll
+  for (int tj = 0; tj < 4; ++tj) {
+    const int seq = tok0 + wt * 128 + tj * 32 + (lane & 31);
+    LseAcc lse;
+    BestAcc best;
+    lse.init();
+    best.init();
+#pragma unroll
+    for (int fi = 0; fi < 2; ++fi) {
+      float mt = acc[fi][tj][0];
+#pragma unroll
+      for (int v = 1; v < 16; ++v) mt = fmaxf(mt, acc[fi][tj][v]);
+      const float mn = fmaxf(lse.m, mt);
+      float su = 0.f;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) su += __expf(acc[fi][tj][v] - mn);
+      lse.l = lse.l * __expf(lse.m - mn) + su;
+      lse.m = mn;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int v0 = ft * 128 + wf * 64 + fi * 32 + 8 * r + (lane >> 5) * 4;
+        float gn[4] = {0.f, 0.f, 0.f, 0.f};
+        if (noisy) gumbel4(sp.seed_lo, sp.seed_hi, (uint32_t)seq, (uint32_t)step, (uint32_t)(v0 >> 2), gn);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float z = acc[fi][tj][4 * r + j];
+          const float y = noisy ? z * inv_t + gn[j] : z;
+          if (y > best.y) { best.y = y; best.z = z; best.id = v0 + j; }   // ids ascend within a lane
+        }
+      }
+    }
+    // the two lane halves (fixed order); the two feature waves meet in LDS
+    lse.merge(__shfl_xor(lse.m, 32, 64), __shfl_xor(lse.l, 32, 64));
+    best.add(__shfl_xor(best.y, 32, 64), __shfl_xor(best.z, 32, 64), __shfl_xor(best.id, 32, 64));
+    if (lane < 32) {
+      float* p = red + ((size_t)wf * 256 + wt * 128 + tj * 32 + lane) * 5;
+      p[0] = lse.m; p[1] = lse.l; p[2] = best.y; p[3] = best.z; ((int*)p)[4] = best.id;
+    }
+  }
+  __syncthreads();
+  const int row = tok0 + threadIdx.x;
+  if (row < n_rows) {
+    LseAcc a; a.init();
+    BestAcc b; b.init();
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+      const float* p = red + ((size_t)w * 256 + threadIdx.x) * 5;
+      a.merge(p[0], p[1]);
+      b.add(p[2], p[3], ((const int*)p)[4]);
+    }
+    float* p = partials + ((size_t)ft * n_rows + row) * 5;
+    p[0] = a.m; p[1] = a.l; p[2] = b.y; p[3] = b.z; ((int*)p)[4] = b.id;
+  }
+}
+
+hipError_t m_lmhead_sample_big(const void* Xp, const void* Wp, int n_rows, int V, int K, SampleParams sp, float* partials,
+                               hipStream_t st) {
+  if (n_rows <= 0 || V % 128 != 0 || K % 32 != 0) return hipErrorInvalidValue;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)k_lmhead_sample_big, hipFuncAttributeMaxDynamicSharedMemorySize, kBigLds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  return launch(KID_LMHEAD_SAMPLE, k_lmhead_sample_big, dim3(big_grid(V >> 7, (n_rows + 255) / 256)), dim3(256),
+                kBigLds, st, (const uint4*)Xp, (const uint4*)Wp, n_rows, V, K, sp, partials);
 }
 
 // =======================================================================================
