@@ -715,11 +715,14 @@ static void plan_score(const sapo_weights* w, int S, int T, int chunk_seqs, size
   pl.bytes = (A.off + 255) & ~(size_t)255;
 }
 
+// Sequences per forward pass of the scoring call: about 32768 tokens (enough tiles to fill the chip even
+// for the narrow projections), the passes balanced so that the last one is not a sliver.
 static int score_chunk_seqs(int S, int T) {
-  int cs = 8192 / T;
+  int cs = 32768 / T;
   if (cs < 1) cs = 1;
   if (cs > S) cs = S;
-  return cs;
+  const int n_chunks = (S + cs - 1) / cs;
+  return (S + n_chunks - 1) / n_chunks;
 }
 
 static int check_score_args(const sapo_weights* w, int S, int T) {
