@@ -307,6 +307,7 @@ struct FwdBufs {      // activations for M rows
   void* attn;         // [M, q] attention output (T; row-major, or X-packed on the 64-token decode path)
   float* gu;          // [M, 2 F] (shape-generic kernels only)
   void* act;          // [M, F] (T; row-major, or X-packed on the 64-token decode path)
+  float* ssq;         // [M, d / 128 rounded up to 4] sum-of-squares parts of the residual rows (token-parallel MFMA path)
 };
 
 static void carve_fwd(Arena& A, const sapo_weights* w, size_t M, FwdBufs& b) {
@@ -320,6 +321,7 @@ static void carve_fwd(Arena& A, const sapo_weights* w, size_t M, FwdBufs& b) {
   b.attn = A.take_bytes(Mp * q * w->elt);
   b.gu = w->mfma ? nullptr : A.take<float>(M * 2 * F);
   b.act = A.take_bytes(Mp * F * w->elt);
+  b.ssq = w->mfma ? A.take<float>(M * ((d / 128 + 3) / 4 * 4)) : nullptr;
 }
 
 struct CacheBufs {
@@ -398,14 +400,33 @@ static int run_layers_big(const sapo_weights* w, const FwdBufs& b, int M, RowMap
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerWeights& lw = w->layers[l];
     const KVCache kvc = layer_cache(w, cb, l);
-    HIP_CK(m_rmsnorm_x32(b.h, lw.attn_norm, c.rms_eps, b.a, M, d, nullptr, st));
-    HIP_CK(m_gemm_big(b.a, lw.wqkv, M, q + 2 * kv, d, BigEpi{BIG_STORE_F32, b.qkv, q + 2 * kv, nullptr}, st));
+    // RMSNorm is folded around the GEMMs: the O and down projections' epilogues emit the next operand
+    // (row * gain, half) and the row's sum-of-squares parts; the consumer scales its accumulators.
+    const int parts = d / 128;
+    const bool fold = parts <= 16;
+    BigEpi qkv_ep{BIG_STORE_F32, b.qkv, q + 2 * kv, nullptr};
+    if (l == 0 || !fold) {
+      HIP_CK(m_rmsnorm_x32(b.h, lw.attn_norm, c.rms_eps, b.a, M, d, nullptr, st));
+    } else {
+      qkv_ep.ssq_in = b.ssq; qkv_ep.ssq_parts = parts; qkv_ep.norm_dim = (float)d; qkv_ep.eps = c.rms_eps;
+    }
+    HIP_CK(m_gemm_big(b.a, lw.wqkv, M, q + 2 * kv, d, qkv_ep, st));
     HIP_CK(g_rope_append_f16(b.qkv, w->rope, rm, kvc, b.q, M, c.n_q_heads, st));
     HIP_CK(m_flash_attention(b.q, rm, kvc, b.attn, M / rm.T, c.n_q_heads, st));
-    HIP_CK(m_gemm_big(b.attn, lw.wo, M, d, q, BigEpi{BIG_ADD_F32, b.h, d, nullptr}, st));
-    HIP_CK(m_rmsnorm_x32(b.h, lw.ffn_norm, c.rms_eps, b.a, M, d, nullptr, st));
-    HIP_CK(m_gemm_big(b.a, lw.wgu, M, 2 * F, d, BigEpi{BIG_SWIGLU, nullptr, 0, (f16*)b.act}, st));
-    HIP_CK(m_gemm_big(b.act, lw.wdown, M, d, F, BigEpi{BIG_ADD_F32, b.h, d, nullptr}, st));
+    BigEpi o_ep{BIG_ADD_F32, b.h, d, nullptr};
+    BigEpi gu_ep{BIG_SWIGLU, nullptr, 0, (f16*)b.act};
+    if (fold) {
+      o_ep.gain_next = lw.ffn_norm; o_ep.xn_out = (f16*)b.a; o_ep.ssq_out = b.ssq;
+      gu_ep.ssq_in = b.ssq; gu_ep.ssq_parts = parts; gu_ep.norm_dim = (float)d; gu_ep.eps = c.rms_eps;
+    }
+    HIP_CK(m_gemm_big(b.attn, lw.wo, M, d, q, o_ep, st));
+    if (!fold) HIP_CK(m_rmsnorm_x32(b.h, lw.ffn_norm, c.rms_eps, b.a, M, d, nullptr, st));
+    HIP_CK(m_gemm_big(b.a, lw.wgu, M, 2 * F, d, gu_ep, st));
+    BigEpi down_ep{BIG_ADD_F32, b.h, d, nullptr};
+    if (fold && l + 1 < c.n_layers) {
+      down_ep.gain_next = w->layers[l + 1].attn_norm; down_ep.xn_out = (f16*)b.a; down_ep.ssq_out = b.ssq;
+    }
+    HIP_CK(m_gemm_big(b.act, lw.wdown, M, d, F, down_ep, st));
   }
   return SAPO_OK;
 }

@@ -229,6 +229,17 @@ struct BigEpi {
   float* out_f32;      // STORE_F32 / ADD_F32: [M, ldc]
   int ldc;
   f16* out_act;        // SWIGLU: act, X32 order over F = N / 2
+  // RMSNorm folded around the GEMM (a row's scale commutes with the contraction).  Consumer side: the
+  // token operand holds x * gain without the row scale; the accumulators are multiplied by
+  // rsqrt(sum of the row's ssq parts / norm_dim + eps) before the epilogue proper.
+  const float* ssq_in = nullptr;   // [M, ssq_parts rounded up to a multiple of 4]; at most 16 parts
+  int ssq_parts = 0;
+  float norm_dim = 0.f, eps = 0.f;
+  // Producer side (ADD_F32 only): the updated residual row, times gain_next, goes out as half in X32
+  // order (the next GEMM's operand), and its sum of squares in N / 128 parts per row.
+  const float* gain_next = nullptr;   // [N]
+  f16* xn_out = nullptr;
+  float* ssq_out = nullptr;           // [M, N / 128 rounded up to a multiple of 4]
 };
 enum { BIG_STORE_F32 = 0, BIG_ADD_F32 = 1, BIG_SWIGLU = 2 };
 

@@ -125,8 +125,12 @@ static int big_grid(int NX, int NY) {
 
 // acc = X[tblk0*32 .. +255][:] . W[fblk0*32 .. +127][:]^T over the whole K.  Token blocks past the end
 // are clamped to the last one (their results are never stored).
+struct NoPrologue { __device__ __forceinline__ void operator()() const {} };
+// `prologue` runs once the first two stages are requested (loads it issues ride on the same latency).
+template <class Prologue = NoPrologue>
 __device__ __forceinline__ void big_mainloop(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int n_tblk,
-                                             int KS, int tblk0, int fblk0, uint4* smem, f32x16 (&acc)[2][4]) {
+                                             int KS, int tblk0, int fblk0, uint4* smem, f32x16 (&acc)[2][4],
+                                             Prologue prologue = Prologue()) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wf = wave & 1, wt = wave >> 1;
   const int nst = KS >> 1;
@@ -159,6 +163,7 @@ __device__ __forceinline__ void big_mainloop(const uint4* __restrict__ Xp, const
   wg_barrier();   // a previous pass over the ring (fused LM head) is over in every wave
   issue(0);
   if (nst > 1) issue(1);
+  prologue();
   for (int st = 0; st < nst; ++st) {
     if (st + 1 < nst) wait_vmcnt<6>(); else wait_vmcnt<0>();   // this wave's part of stage st has landed
     wg_barrier();                                               // ... and everybody's; stage st-1 is consumed
@@ -185,13 +190,45 @@ __global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ X
   int bx, by;
   if (!big_raster(N >> 7, (M + 255) >> 8, bx, by)) return;
   f32x16 acc[2][4];
-  big_mainloop(Xp, Wp, (M + 31) >> 5, K >> 4, by * 8, bx * 4, smem, acc);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wf = wave & 1, wt = wave >> 1;
+  float row_scale[4] = {1.f, 1.f, 1.f, 1.f};
+  big_mainloop(Xp, Wp, (M + 31) >> 5, K >> 4, by * 8, bx * 4, smem, acc, [&]() {
+    if (!ep.ssq_in) return;
+    const int ps = (ep.ssq_parts + 3) & ~3;   // row stride of the parts; at most 16 parts
+    float4 part[4][4];
+#pragma unroll
+    for (int tj = 0; tj < 4; ++tj) {
+      const int tok = min(by * 256 + wt * 128 + tj * 32 + (lane & 31), M - 1);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        part[tj][i] = (4 * i < ps) ? *(const float4*)(ep.ssq_in + (size_t)tok * ps + 4 * i) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int tj = 0; tj < 4; ++tj) {
+      float ss = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {   // padding slots are never written: select, do not add
+        ss += (4 * i + 0 < ep.ssq_parts) ? part[tj][i].x : 0.f;
+        ss += (4 * i + 1 < ep.ssq_parts) ? part[tj][i].y : 0.f;
+        ss += (4 * i + 2 < ep.ssq_parts) ? part[tj][i].z : 0.f;
+        ss += (4 * i + 3 < ep.ssq_parts) ? part[tj][i].w : 0.f;
+      }
+      row_scale[tj] = rsqrtf(ss / ep.norm_dim + ep.eps);
+    }
+  });
+  float ssq_mine[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int tj = 0; tj < 4; ++tj) {
     const int tok = by * 256 + wt * 128 + tj * 32 + (lane & 31);
-    if (tok >= M) continue;
+    if (tok >= M) continue;   // lanes l and l + 32 hold the same token: they leave together
+    if (ep.ssq_in) {
+      const float sc = row_scale[tj];
+#pragma unroll
+      for (int fi = 0; fi < 2; ++fi)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[fi][tj][v] *= sc;
+    }
     if (ep.mode == BIG_SWIGLU) {
       // fi = 0 is a gate tile, fi = 1 the matching up tile; act goes out in X32 order over F = N / 2
       const int F = N >> 1;
@@ -204,6 +241,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ X
         *(f16x4*)(ep.out_act + x32_chunk(tok, f0 + 8 * r, F >> 4) * 8 + ((lane >> 5) << 2)) = o;
       }
     } else {
+      float ssq = 0.f;
 #pragma unroll
       for (int fi = 0; fi < 2; ++fi) {
         const int f0 = bx * 128 + wf * 64 + fi * 32 + (lane >> 5) * 4;
@@ -216,7 +254,32 @@ __global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ X
             v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
           }
           *p = v;
+          if (ep.gain_next) {
+            const float4 g = *(const float4*)(ep.gain_next + f0 + 8 * r);
+            ssq += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+            f16x4 o;
+            o[0] = from_f32<f16>(v.x * g.x); o[1] = from_f32<f16>(v.y * g.y);
+            o[2] = from_f32<f16>(v.z * g.z); o[3] = from_f32<f16>(v.w * g.w);
+            *(f16x4*)(ep.xn_out + x32_chunk(tok, f0 + 8 * r, N >> 4) * 8 + ((lane >> 5) << 2)) = o;
+          }
         }
+      }
+      ssq_mine[tj] = ssq + __shfl_xor(ssq, 32, 64);
+    }
+  }
+  if (ep.gain_next) {   // uniform: the two feature waves of a token half meet in LDS, summed in wave order
+    __shared__ float red[256];
+    if (wf == 1 && lane < 32) {
+#pragma unroll
+      for (int tj = 0; tj < 4; ++tj) red[wt * 128 + tj * 32 + lane] = ssq_mine[tj];
+    }
+    __syncthreads();
+    if (wf == 0 && lane < 32) {
+      const int ps = ((N >> 7) + 3) & ~3;
+#pragma unroll
+      for (int tj = 0; tj < 4; ++tj) {
+        const int tok = by * 256 + wt * 128 + tj * 32 + lane;
+        if (tok < M) ep.ssq_out[(size_t)tok * ps + bx] = ssq_mine[tj] + red[wt * 128 + tj * 32 + lane];
       }
     }
   }
@@ -541,21 +604,32 @@ __global__ void __launch_bounds__(256) k_flash_attention(const f16* __restrict__
   const f16* kpool = (const f16*)kv.k;
   const f16* vpool = (const f16*)kv.v;
   const size_t page_elems = (size_t)hkv * kPageTokens * HD;
-  for (int pp = 0; pp < npairs; ++pp) {
+  // K / V fragments of a page pair; the next pair's are requested before the current one is multiplied
+  Frag kf[2][KK], vf[DT], kn[2][KK], vn[DT];
+  auto fetch = [&](int pp, Frag (&kd)[2][KK], Frag (&vd)[DT]) {
     const int pa = pt[2 * pp];
     const int pb = pt[min(2 * pp + 1, last_page)];
-    Frag kf[2][KK], vf[DT];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int r = lane & 15;
       const int ptok = 8 * (r >> 2) + 4 * t + (r & 3);   // key row r of score tile t
       const f16* kp = kpool + (size_t)(ptok < 16 ? pa : pb) * page_elems + ((size_t)kvh * kPageTokens + (ptok & 15)) * HD;
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) kf[t][kk].u = *(const uint4*)(kp + kk * 32 + grp * 8);
+      for (int kk = 0; kk < KK; ++kk) kd[t][kk].u = *(const uint4*)(kp + kk * 32 + grp * 8);
     }
     const f16* vp = vpool + (size_t)(grp < 2 ? pa : pb) * page_elems + (size_t)kvh * HD * kPageTokens + (grp & 1) * 8;
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) vf[dt].u = *(const uint4*)(vp + (size_t)(dt * 16 + (lane & 15)) * kPageTokens);
+    for (int dt = 0; dt < DT; ++dt) vd[dt].u = *(const uint4*)(vp + (size_t)(dt * 16 + (lane & 15)) * kPageTokens);
+  };
+  fetch(0, kn, vn);
+  for (int pp = 0; pp < npairs; ++pp) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) kf[t][kk] = kn[t][kk];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) vf[dt] = vn[dt];
+    if (pp + 1 < npairs) fetch(pp + 1, kn, vn);
     const bool diag = pp * 32 + 31 > q0;   // some (query, key) of the pair is masked
 #pragma unroll
     for (int h = 0; h < HPW; ++h) {
@@ -568,9 +642,9 @@ __global__ void __launch_bounds__(256) k_flash_attention(const f16* __restrict__
         for (int kk = 0; kk < KK; ++kk) sc[t] = mfma16h(kf[t][kk], qf[h][kk], sc[t]);
       }
       // lane (query qcol, group grp) holds keys pp*32 + 8 grp + e, e = 4 t + j
-      float p[8];
+      float p[8];   // raw scores; the softmax scale enters through the exponent's fma
 #pragma unroll
-      for (int e = 0; e < 8; ++e) p[e] = sc[e >> 2][e & 3] * scale2;
+      for (int e = 0; e < 8; ++e) p[e] = sc[e >> 2][e & 3];
       if (diag) {
 #pragma unroll
         for (int e = 0; e < 8; ++e)
@@ -579,22 +653,25 @@ __global__ void __launch_bounds__(256) k_flash_attention(const f16* __restrict__
       float m_loc = fmaxf(fmaxf(fmaxf(p[0], p[1]), fmaxf(p[2], p[3])), fmaxf(fmaxf(p[4], p[5]), fmaxf(p[6], p[7])));
       m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 16, 64));
       m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, 64));
-      const float m_new = fmaxf(m_run[h], m_loc);   // finite: key 0 is visible to every query
-      const float alpha = exp2f(m_run[h] - m_new);
+      const float m_new = fmaxf(m_run[h], m_loc * scale2);   // finite: key 0 is visible to every query
+      const float alpha = __builtin_amdgcn_exp2f(m_run[h] - m_new);   // exp2(-inf) = 0 on the first pair
       float psum = 0.f;
       Frag pf;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const float pe = exp2f(p[e] - m_new);
+        const float pe = __builtin_amdgcn_exp2f(fmaf(p[e], scale2, -m_new));
         psum += pe;
         pf.h[e] = (f16)pe;
       }
       l_run[h] = l_run[h] * alpha + psum;
       m_run[h] = m_new;
+      const bool rescale = __builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0;   // the running max moved in some lane
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
+        if (rescale) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) o[h][dt][j] *= alpha;
+          for (int j = 0; j < 4; ++j) o[h][dt][j] *= alpha;
+        }
         o[h][dt] = mfma16h(vf[dt], pf, o[h][dt]);
       }
     }
