@@ -16,6 +16,7 @@ Prints ONE JSON line.
 from __future__ import annotations
 
 import argparse
+from dataclasses import replace
 import json
 import os
 import sys
@@ -89,6 +90,10 @@ def main():
     ap.add_argument("--no-kernel-profile", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, for scaling profiler byte counters)")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="counter runs only: same kernels and shapes with this many layers (fewer launches); "
+                         "the printed line is then not a benchmark result")
+    ap.add_argument("--new-tokens", type=int, default=0, help="counter runs only: generate this many tokens")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not "
@@ -100,6 +105,10 @@ def main():
     from paper_2509_08721_amd import sapo, workloads as W
 
     wl = W.WORKLOADS[args.workload]
+    if args.layers > 0:
+        wl = replace(wl, shape=replace(wl.shape, n_layers=args.layers))
+    if args.new_tokens > 0:
+        wl = replace(wl, n_new=args.new_tokens)
     shape = wl.shape
     torch.cuda.set_device(0)
     t0 = time.time()
@@ -206,7 +215,7 @@ def main():
         "ms_per_step": round(step_ms, 3), "wall_ms_per_step": round(wall_ms, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if shape.dtype == "f32" else "f16", "data": "synthetic",
-        "config": {"workload": wl.name, "layers": shape.n_layers, "d_model": shape.d_model,
+        "config": {"workload": wl.name if not (args.layers or args.new_tokens) else wl.name + " (cut down for a counter run: NOT a result)", "layers": shape.n_layers, "d_model": shape.d_model,
                    "heads": "%dq/%dkv x %d" % (shape.n_q_heads, shape.n_kv_heads, shape.head_dim),
                    "d_ff": shape.d_ff, "vocab": shape.vocab,
                    "weights": "fp32" if shape.dtype == "f32" else "bf16 values, MFMA operands in IEEE half, fp32 accumulation",
@@ -257,9 +266,11 @@ def main():
         dom = next((n for n in kernels if "bound" in kernels[n]), None)
         if dom:
             k = kernels[dom]
+            from paper_2509_08721_amd import traffic as TR
+            cut = bool(args.layers or args.new_tokens)
             roofline = {"kernel": dom, "bound": k["bound"], "achieved": k["achieved"],
                         "peak": HBM_PEAK_GBS if k["bound"] == "hbm" else MFMA_16BIT_PEAK_TFLOPS, "unit": k["unit"],
-                        "frac": k["frac"], "traffic": None, "avg_us": k["avg_us"], "launches": k["launches"],
+                        "frac": k["frac"], "traffic": None if cut else TR.lookup(wl.name, dom), "avg_us": k["avg_us"], "launches": k["launches"],
                         "work_per_launch": k["work_per_launch"]}
 
     # CPU baseline: the oracle as it stands, on a bounded slice of the same workload
