@@ -204,6 +204,21 @@ def main():
         lp_gap = float((sc_lp[:, Lp:] - out_lp).abs().max().item())
         assert lp_gap < 4e-2, lp_gap
 
+    # prefill alone (max_new = 1: the prompts' forward and the first sampled token), for a decode-only rate
+    prefill_ms = None
+    if do_rollout and N > 1:
+        t1 = torch.empty((S, 1), dtype=torch.int32, device="cuda")
+        l1 = torch.empty((S, 1), dtype=torch.float32, device="cuda")
+        pm = []
+        for i in range(3):
+            ev[0].record()
+            sapo.sapo_rollout_generate(gw, prompts, G, 1, wl.temperature, wl.rollout_seed, workspace=ws_r,
+                                       out_tokens=t1, out_logprobs=l1)
+            ev[1].record()
+            torch.cuda.synchronize()
+            pm.append(ev[0].elapsed_time(ev[1]))
+        prefill_ms = float(np.median(pm))
+
     gen_tokens = S * N if do_rollout else 0
     scored_tokens = S_score * T if do_score else 0
     out = {
@@ -228,6 +243,9 @@ def main():
         bytes_shared = ab["weights"] + ab["kv_read_shared"] + ab["kv_write"]
         bytes_unshared = ab["weights"] + ab["kv_read_unshared"] + ab["kv_write"]
         roll_gbs = bytes_shared / (r_ms * 1e-3) / 1e9
+        if prefill_ms is not None and r_ms > prefill_ms:
+            out.update({"prefill_ms": round(prefill_ms, 3),
+                        "decode_only_tokens_per_s": round(S * (N - 1) / ((r_ms - prefill_ms) * 1e-3), 1)})
         out.update({"rollout_tokens_per_s": round(gen_tokens / (r_ms * 1e-3), 1), "rollout_ms": round(r_ms, 3),
                     "rollout_hbm": {"algorithmic_bytes_shared": bytes_shared, "algorithmic_bytes_unshared": bytes_unshared,
                                     "achieved_GBs": round(roll_gbs, 1), "peak_GBs": HBM_PEAK_GBS,
@@ -236,6 +254,7 @@ def main():
         fl = algorithmic_flops_score(shape, S_score, T, Tm)
         score_tflops = fl["total"] / (s_ms * 1e-3) / 1e12
         out.update({"scored_tokens_per_s": round(scored_tokens / (s_ms * 1e-3), 1), "score_ms": round(s_ms, 3),
+                    "masked_tokens_per_s": round(S_score * Tm / (s_ms * 1e-3), 1),
                     "score_mfma": {"algorithmic_flops": fl["total"], "achieved_TFLOPs": round(score_tflops, 2),
                                    "peak_TFLOPs": MFMA_16BIT_PEAK_TFLOPS,
                                    "frac": round(score_tflops / MFMA_16BIT_PEAK_TFLOPS, 4)}})

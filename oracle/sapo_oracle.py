@@ -14,6 +14,8 @@ What it follows (SAPO paper):
   * Sec. 3.2 / Sec. 4.2 / Sec. 5: GRPO consumes group-relative advantages;
     rollouts of a group whose rewards are all equal have zero advantage and
     are discarded                                        -> group_advantages()
+  * Sec. 4.2: the local update is GRPO without a KL term and with asymmetric
+    clipping (0.2 / 0.28) of the probability ratio       -> clipped_surrogate_loss()
 The paper names the policy only as a 0.5B-parameter decoder-only LM; the block
 structure used here (RMSNorm, rotary positions with the rotate-half pairing,
 grouped-query attention, SwiGLU FFN, tied LM head) is the reading recorded in
@@ -30,8 +32,10 @@ comparison with a bf16 device path and is not the definition.
 Pins (tests/test_oracle_*.py): Philox known-answer vectors, Gumbel moments,
 sampler histogram vs softmax, brute-force attention, rotary closed forms,
 KV-cache decode == full recompute, log-softmax normalisation, advantage closed
-forms, zero-layer model, causality, batch invariance, and library routines
-(torch CPU) for the individual blocks.
+forms, zero-layer model, causality, batch invariance, library routines
+(torch CPU) for the individual blocks; for the clipped surrogate: hand-worked
+tokens on each side of each clip bound, the on-policy closed form, torch
+autograd, finite differences, mask invariance.
 """
 from __future__ import annotations
 
@@ -368,3 +372,39 @@ def group_advantages(rewards: np.ndarray, group: int, eps: float = 1e-6) -> np.n
 def score(m: Model, tokens, completion_mask, rewards, group: int):
     """The scoring call: (log-probs [S, T], advantages [S])."""
     return score_logprobs(m, tokens, completion_mask), group_advantages(rewards, group)
+
+
+def clipped_surrogate_loss(logp_new: np.ndarray, logp_old: np.ndarray, completion_mask: np.ndarray,
+                           advantages: np.ndarray, eps_low: float = 0.2, eps_high: float = 0.28):
+    """GRPO's clipped surrogate as the paper configures it (Sec. 4.2): no KL term,
+    asymmetric clipping of the probability ratio to [1 - eps_low, 1 + eps_high] (0.2 / 0.28).
+
+    Per masked token (s, t): rho = exp(logp_new - logp_old), A = advantages[s],
+        term = min(rho * A, clip(rho, 1 - eps_low, 1 + eps_high) * A)
+    loss = - mean of term over the masked tokens of the whole batch (the token-level mean
+    of the DAPO recipe the section cites); 0 if nothing is masked.
+    Also returns d loss / d logp_new [S, T]: -A * rho / N where the unclipped branch is the
+    minimum (A >= 0 and rho <= 1 + eps_high, or A < 0 and rho >= 1 - eps_low), else 0; the
+    two branches coincide inside the clip range, so the choice at equality does not matter.
+    float64 throughout; returns (float, float64 [S, T]).
+    """
+    ln = np.asarray(logp_new, dtype=np.float64)
+    lo = np.asarray(logp_old, dtype=np.float64)
+    mk = np.asarray(completion_mask) != 0
+    adv = np.asarray(advantages, dtype=np.float64)
+    assert ln.shape == lo.shape == mk.shape and adv.shape == (ln.shape[0],)
+    n = int(mk.sum())
+    grad = np.zeros(ln.shape, dtype=np.float64)
+    if n == 0:
+        return 0.0, grad
+    total = 0.0
+    for s in range(ln.shape[0]):
+        a = adv[s]
+        for t in np.nonzero(mk[s])[0]:
+            rho = math.exp(ln[s, t] - lo[s, t])
+            clipped = min(max(rho, 1.0 - eps_low), 1.0 + eps_high)
+            total += min(rho * a, clipped * a)
+            active = (rho <= 1.0 + eps_high) if a >= 0 else (rho >= 1.0 - eps_low)
+            if active:
+                grad[s, t] = -a * rho / n
+    return -total / n, grad

@@ -396,3 +396,78 @@ def test_group_advantages_closed_forms():
     # partial credit rewards are accepted (floats, not booleans)
     a = O.group_advantages(np.array([0.5, 1.0, 0.0, 0.5], dtype=np.float32), 4)
     assert abs(a[0]) < 1e-7 and a[1] > 0 > a[2]
+
+
+# ----------------------------------------------------------------------------- clipped surrogate (Sec. 4.2)
+def test_clipped_surrogate_hand_cases():
+    # four tokens, one per (sign of A, side of the clip range); values worked by hand
+    ln = np.log(np.array([[1.5, 0.5], [1.5, 0.5]]))
+    lo = np.zeros((2, 2))
+    mask = np.ones((2, 2), dtype=np.uint8)
+    adv = np.array([1.0, -1.0])
+    loss, g = O.clipped_surrogate_loss(ln, lo, mask, adv, 0.2, 0.28)
+    # A=+1: rho 1.5 -> clipped 1.28 (flat), rho 0.5 -> 0.5 (unclipped is smaller)
+    # A=-1: rho 1.5 -> -1.5 (unclipped is smaller), rho 0.5 -> -0.8 (clipped, flat)
+    assert loss == pytest.approx(-(1.28 + 0.5 - 1.5 - 0.8) / 4, abs=1e-15)
+    np.testing.assert_allclose(g, np.array([[0.0, -0.5 / 4], [1.5 / 4, 0.0]]), atol=1e-15)
+
+
+def test_clipped_surrogate_on_policy_is_minus_mean_advantage():
+    rng = np.random.default_rng(3)
+    lp = rng.normal(-2.0, 1.0, (6, 9))
+    mask = rng.random((6, 9)) < 0.6
+    adv = rng.normal(0, 1, 6)
+    loss, g = O.clipped_surrogate_loss(lp, lp, mask, adv)
+    n = mask.sum()
+    assert loss == pytest.approx(-(adv[:, None] * mask).sum() / n, abs=1e-14)
+    np.testing.assert_allclose(g, -(adv[:, None] * mask) / n, atol=1e-15)
+
+
+def test_clipped_surrogate_vs_torch_autograd_and_masking():
+    rng = np.random.default_rng(11)
+    S, T = 8, 16
+    lo = rng.normal(-2.0, 1.0, (S, T))
+    ln = lo + rng.normal(0, 0.25, (S, T))           # ratios on both sides of both clip bounds
+    mask = rng.random((S, T)) < 0.5
+    adv = rng.normal(0, 1, S)
+    loss, g = O.clipped_surrogate_loss(ln, lo, mask, adv, 0.2, 0.28)
+    x = torch.tensor(ln, dtype=torch.float64, requires_grad=True)
+    rho = torch.exp(x - torch.tensor(lo))
+    a = torch.tensor(adv)[:, None]
+    term = torch.minimum(rho * a, torch.clamp(rho, 1 - 0.2, 1 + 0.28) * a)
+    m = torch.tensor(mask)
+    tl = -(term * m).sum() / m.sum()
+    tl.backward()
+    assert loss == pytest.approx(float(tl.detach()), abs=1e-14)
+    np.testing.assert_allclose(g, x.grad.numpy(), atol=1e-14)
+    assert (np.abs(g) > 0).sum() < mask.sum()       # some tokens really are clipped
+    # what sits under a zero mask never matters
+    ln2, lo2 = ln.copy(), lo.copy()
+    ln2[~mask] = np.nan
+    lo2[~mask] = np.inf
+    loss2, g2 = O.clipped_surrogate_loss(ln2, lo2, mask, adv, 0.2, 0.28)
+    assert loss2 == loss and np.array_equal(g2, g)
+    # nothing masked: zero loss, zero gradient
+    l0, g0 = O.clipped_surrogate_loss(ln, lo, np.zeros((S, T), bool), adv)
+    assert l0 == 0.0 and not g0.any()
+
+
+def test_clipped_surrogate_gradient_is_the_derivative():
+    rng = np.random.default_rng(5)
+    S, T = 4, 6
+    lo = rng.normal(-2.0, 1.0, (S, T))
+    ln = lo + rng.normal(0, 0.3, (S, T))
+    mask = np.ones((S, T), bool)
+    adv = rng.normal(0, 1, S)
+    _, g = O.clipped_surrogate_loss(ln, lo, mask, adv)
+    h = 1e-6
+    for s in range(S):
+        for t in range(T):
+            rho = math.exp(ln[s, t] - lo[s, t])
+            if min(abs(rho - 0.8), abs(rho - 1.28)) < 1e-3:
+                continue                              # a kink
+            up, dn = ln.copy(), ln.copy()
+            up[s, t] += h
+            dn[s, t] -= h
+            fd = (O.clipped_surrogate_loss(up, lo, mask, adv)[0] - O.clipped_surrogate_loss(dn, lo, mask, adv)[0]) / (2 * h)
+            assert g[s, t] == pytest.approx(fd, abs=1e-8)
