@@ -219,6 +219,23 @@ def main():
             pm.append(ev[0].elapsed_time(ev[1]))
         prefill_ms = float(np.median(pm))
 
+    # the update's clipped surrogate on this batch (Sec. 4.2), outside the timed step: a few small kernels
+    surrogate = None
+    if do_score:
+        lp_old = sc_lp + 0.05 * torch.randn_like(sc_lp)
+        ws_l = torch.empty(sapo.sapo_surrogate_workspace_bytes() + 256, dtype=torch.uint8, device="cuda")
+        lm = []
+        for i in range(5):
+            ev[0].record()
+            sapo.sapo_clipped_surrogate(sc_lp, lp_old, mask, sc_adv, workspace=ws_l)
+            ev[1].record()
+            torch.cuda.synchronize()
+            lm.append(ev[0].elapsed_time(ev[1]))
+        l_ms = float(np.median(lm))
+        l_bytes = S_score * T * (4 + 4 + 1 + 4 + 1) + S_score * Tm * (4 + 4)   # mask twice, logp pair twice where set, gradient out
+        surrogate = {"ms": round(l_ms, 4), "algorithmic_bytes": l_bytes, "GBs": round(l_bytes / (l_ms * 1e-3) / 1e9, 2),
+                     "note": "three dependent launches on under 2 MB: launch-latency-bound, not a roofline case"}
+
     gen_tokens = S * N if do_rollout else 0
     scored_tokens = S_score * T if do_score else 0
     out = {
@@ -324,7 +341,8 @@ def main():
                "sample": "numpy fp64 oracle: " + ", ".join(parts) + "; whole-step rate extrapolated from the slice rates"}
         cpu.update(res)
 
-    out.update({"roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "setup_s": round(setup_s, 1)})
+    out.update({"roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "surrogate_loss": surrogate,
+                "setup_s": round(setup_s, 1)})
     print(json.dumps(out))
 
 

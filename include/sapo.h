@@ -133,6 +133,30 @@ int sapo_debug_logits(const sapo_weights* w, const int32_t* tokens, int S, int T
                       size_t workspace_bytes, void* stream);
 
 /*
+ * Clipped surrogate of the local policy update (Sec. 4.2: GRPO with the KL weight at zero and
+ * asymmetric clipping, eps_low = 0.2, eps_high = 0.28), consuming what the two calls above produce.
+ * Per masked token: rho = exp(logp_new - logp_old), A = advantages[s],
+ *   term = min(rho A, clip(rho, 1 - eps_low, 1 + eps_high) A);
+ * loss = - (sum of term) / (number of masked tokens), 0 when nothing is masked (the section does
+ * not print the normalisation; this is the token-level mean of the recipe it cites).
+ *   logp_new, logp_old  dev fp32 [S, T]   only read where the mask is set
+ *   completion_mask     dev uint8 [S, T]
+ *   advantages          dev fp32 [S]
+ *   out_loss            dev fp32 [1]
+ *   out_dlogp           dev fp32 [S, T] or NULL: d loss / d logp_new = -A rho / N where the unclipped
+ *                       branch is the minimum (A >= 0 and rho <= 1 + eps_high, or A < 0 and
+ *                       rho >= 1 - eps_low), 0 elsewhere and where the mask is clear
+ *   workspace           dev, >= sapo_surrogate_workspace_bytes(), 256-byte aligned
+ * rho and the branch are taken in fp32, the sums in fp64 in a fixed order (no atomics).
+ * Returns SAPO_EINVAL for NULL buffers, non-positive sizes or eps outside [0, 1) / [0, inf).
+ */
+size_t sapo_surrogate_workspace_bytes(void);
+int sapo_clipped_surrogate(const float* logp_new, const float* logp_old, const uint8_t* completion_mask,
+                           const float* advantages, int S, int T, float eps_low, float eps_high,
+                           float* out_loss, float* out_dlogp, void* workspace, size_t workspace_bytes,
+                           void* stream);
+
+/*
  * Test hook: the sampler's noise.  out[i] = g for (seed, seq, step, v = v0 + i), i < n.
  * out dev fp32 [n].
  */

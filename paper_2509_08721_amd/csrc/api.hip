@@ -847,6 +847,24 @@ extern "C" int sapo_debug_logits(const sapo_weights* w, const int32_t* tokens, i
   return SAPO_OK;
 }
 
+extern "C" size_t sapo_surrogate_workspace_bytes(void) { return (g_surrogate_workspace_bytes() + 255) & ~(size_t)255; }
+
+extern "C" int sapo_clipped_surrogate(const float* logp_new, const float* logp_old, const uint8_t* completion_mask,
+                                      const float* advantages, int S, int T, float eps_low, float eps_high,
+                                      float* out_loss, float* out_dlogp, void* workspace, size_t workspace_bytes,
+                                      void* stream) {
+  if (S <= 0 || T <= 0 || (long)S * T > (1L << 31)) return fail(SAPO_EINVAL, "S and T must be positive (S * T <= 2^31)");
+  if (!logp_new || !logp_old || !completion_mask || !advantages || !out_loss || !workspace)
+    return fail(SAPO_EINVAL, "NULL buffer");
+  if (!(eps_low >= 0.f && eps_low < 1.f && eps_high >= 0.f)) return fail(SAPO_EINVAL, "clip bounds out of range");
+  if (((uintptr_t)workspace & 255) != 0) return fail(SAPO_EINVAL, "workspace must be 256-byte aligned");
+  if (workspace_bytes < sapo_surrogate_workspace_bytes())
+    return fail(SAPO_EWORKSPACE, "workspace %zu < required %zu", workspace_bytes, sapo_surrogate_workspace_bytes());
+  HIP_CK(g_surrogate_loss(logp_new, logp_old, completion_mask, advantages, S, T, eps_low, eps_high, out_loss, out_dlogp,
+                          workspace, (hipStream_t)stream));
+  return SAPO_OK;
+}
+
 extern "C" int sapo_debug_gumbel(uint64_t seed, uint32_t seq, uint32_t step, uint32_t v0, int n, float* out,
                                  void* stream) {
   if (n < 0 || !out) return fail(SAPO_EINVAL, "bad arguments");

@@ -202,6 +202,10 @@ hipError_t g_sample_rows(const float* logits, int n_prompt_rows, int G, int V, S
 hipError_t g_score_rows(const float* logits, int n_rows, int row_offset, int V, const int* row_seq_pos,
                         const int* n_rows_dev, const int32_t* tokens, int T, float* out_logprobs, hipStream_t st);
 hipError_t g_advantages(const float* rewards, int S, int G, float* out, hipStream_t st);
+size_t g_surrogate_workspace_bytes();
+hipError_t g_surrogate_loss(const float* logp_new, const float* logp_old, const uint8_t* mask, const float* adv, int S, int T,
+                            float eps_low, float eps_high, float* out_loss, float* out_dlogp, void* workspace,
+                            hipStream_t st);
 hipError_t g_page_table(int* pt, int n_seq, int pages_per_seq, int G, int full_prompt_pages, int n_prompts,
                         hipStream_t st);
 hipError_t g_copy_partial_page(int dtype, KVCache kv, int n_prompts, int G, int page_idx, hipStream_t st);

@@ -416,6 +416,85 @@ hipError_t g_advantages(const float* rewards, int S, int G, float* out, hipStrea
 }
 
 // ---------------------------------------------------------------------------------------
+// Clipped surrogate of the local GRPO update (Sec. 4.2: no KL term, asymmetric clip).
+// Pass 1: every block walks a contiguous slice of the [S, T] tokens and leaves (sum of
+// min(rho A, clip(rho) A), number of masked tokens) in its slot; pass 2: one block adds the
+// slots in index order (fp64) and writes loss and count; pass 3: the gradient, which needs
+// the count.  rho and the branch decision are fp32; no atomics, so the result is reproducible.
+// ---------------------------------------------------------------------------------------
+constexpr int kLossBlocks = 256;
+struct LossPartial { double sum; long long count; };
+
+__device__ __forceinline__ float surrogate_term(float ln, float lo, float a, float eps_low, float eps_high, float& rho,
+                                                bool& active) {
+  rho = expf(ln - lo);
+  const float clipped = fminf(fmaxf(rho, 1.0f - eps_low), 1.0f + eps_high);
+  active = a >= 0.f ? (rho <= 1.0f + eps_high) : (rho >= 1.0f - eps_low);
+  return fminf(rho * a, clipped * a);
+}
+
+__global__ void __launch_bounds__(256) k_surrogate_partial(const float* __restrict__ logp_new, const float* __restrict__ logp_old,
+                                                           const uint8_t* __restrict__ mask, const float* __restrict__ adv,
+                                                           int T, size_t n, float eps_low, float eps_high,
+                                                           LossPartial* __restrict__ part) {
+  const size_t per = (n + gridDim.x - 1) / gridDim.x;
+  const size_t i0 = (size_t)blockIdx.x * per, i1 = (i0 + per < n) ? i0 + per : n;
+  double sum = 0.0;
+  long long cnt = 0;
+  for (size_t i = i0 + threadIdx.x; i < i1; i += 256) {
+    if (!mask[i]) continue;
+    float rho; bool act;
+    sum += (double)surrogate_term(logp_new[i], logp_old[i], adv[i / T], eps_low, eps_high, rho, act);
+    ++cnt;
+  }
+  __shared__ double s_sum[256];
+  __shared__ long long s_cnt[256];
+  s_sum[threadIdx.x] = sum; s_cnt[threadIdx.x] = cnt;
+  __syncthreads();
+  if (threadIdx.x == 0) {   // thread order: the same sum whatever the hardware does
+    double t = 0.0; long long c = 0;
+    for (int j = 0; j < 256; ++j) { t += s_sum[j]; c += s_cnt[j]; }
+    part[blockIdx.x].sum = t; part[blockIdx.x].count = c;
+  }
+}
+__global__ void k_surrogate_finish(LossPartial* __restrict__ part, int n_part, float* __restrict__ out_loss) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  double t = 0.0; long long c = 0;
+  for (int j = 0; j < n_part; ++j) { t += part[j].sum; c += part[j].count; }
+  part[n_part].sum = t; part[n_part].count = c;   // slot n_part: the totals, read by the gradient pass
+  out_loss[0] = c > 0 ? (float)(-t / (double)c) : 0.f;
+}
+__global__ void __launch_bounds__(256) k_surrogate_grad(const float* __restrict__ logp_new, const float* __restrict__ logp_old,
+                                                        const uint8_t* __restrict__ mask, const float* __restrict__ adv,
+                                                        int T, size_t n, float eps_low, float eps_high,
+                                                        const LossPartial* __restrict__ total, float* __restrict__ out) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  float g = 0.f;
+  if (mask[i]) {
+    const float a = adv[i / T];
+    float rho; bool act;
+    surrogate_term(logp_new[i], logp_old[i], a, eps_low, eps_high, rho, act);
+    if (act) g = (float)(-(double)a * (double)rho / (double)total->count);
+  }
+  out[i] = g;
+}
+size_t g_surrogate_workspace_bytes() { return (kLossBlocks + 1) * sizeof(LossPartial); }
+hipError_t g_surrogate_loss(const float* logp_new, const float* logp_old, const uint8_t* mask, const float* adv, int S, int T,
+                            float eps_low, float eps_high, float* out_loss, float* out_dlogp, void* workspace,
+                            hipStream_t st) {
+  const size_t n = (size_t)S * T;
+  LossPartial* part = (LossPartial*)workspace;
+  hipError_t e = launch(KID_MISC, k_surrogate_partial, dim3(kLossBlocks), dim3(256), 0, st, logp_new, logp_old, mask, adv, T,
+                        n, eps_low, eps_high, part);
+  if (e != hipSuccess) return e;
+  e = launch(KID_MISC, k_surrogate_finish, dim3(1), dim3(64), 0, st, part, kLossBlocks, out_loss);
+  if (e != hipSuccess || !out_dlogp) return e;
+  return launch(KID_MISC, k_surrogate_grad, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, logp_new, logp_old, mask,
+                adv, T, n, eps_low, eps_high, (const LossPartial*)(part + kLossBlocks), out_dlogp);
+}
+
+// ---------------------------------------------------------------------------------------
 // Ordered compaction of the positions to score in sequences [s0, s0 + ns): entry i of `rows`
 // is (s, t) with mask[s, t] != 0 and t >= 1, in (s, t) order; *count = number of entries.
 // `src_rows[i]` = local row (s - s0) * T + t - 1 whose hidden state predicts token (s, t).

@@ -63,6 +63,10 @@ def load_library() -> C.CDLL:
     lib.sapo_rollout_generate.restype = i32
     lib.sapo_score_logprobs.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
     lib.sapo_score_logprobs.restype = i32
+    lib.sapo_surrogate_workspace_bytes.argtypes = []
+    lib.sapo_surrogate_workspace_bytes.restype = sz
+    lib.sapo_clipped_surrogate.argtypes = [vp, vp, vp, vp, i32, i32, f32, f32, vp, vp, vp, sz, vp]
+    lib.sapo_clipped_surrogate.restype = i32
     lib.sapo_debug_logits.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, sz, vp]
     lib.sapo_debug_logits.restype = i32
     lib.sapo_debug_gumbel.argtypes = [u64, u32, u32, u32, i32, vp, vp]
@@ -84,6 +88,7 @@ def load_library() -> C.CDLL:
 EXPORTED = ["sapo_weights_create", "sapo_weights_destroy", "sapo_weights_uses_mfma",
             "sapo_rollout_workspace_bytes", "sapo_score_workspace_bytes",
             "sapo_debug_logits_workspace_bytes", "sapo_rollout_generate", "sapo_score_logprobs",
+            "sapo_surrogate_workspace_bytes", "sapo_clipped_surrogate",
             "sapo_debug_logits", "sapo_debug_gumbel", "sapo_last_error", "sapo_profile_kernel_count",
             "sapo_profile_kernel_name", "sapo_profile_start", "sapo_profile_stop"]
 
@@ -229,6 +234,34 @@ def sapo_score_logprobs(w: Weights, tokens, completion_mask, rewards, G: int, wo
                                    S, T, G, out_logprobs.data_ptr(), out_advantages.data_ptr(),
                                    _aligned_ptr(workspace), nbytes, _stream_ptr(stream)))
     return out_logprobs, out_advantages
+
+
+def sapo_surrogate_workspace_bytes() -> int:
+    return int(load_library().sapo_surrogate_workspace_bytes())
+
+
+def sapo_clipped_surrogate(logp_new, logp_old, completion_mask, advantages, eps_low: float = 0.2,
+                           eps_high: float = 0.28, want_grad: bool = True, workspace=None, stream=None):
+    """logp_new / logp_old float32 [S, T], completion_mask uint8 [S, T], advantages float32 [S] (device).
+    Returns (loss float32 [1], d loss / d logp_new float32 [S, T] or None)."""
+    torch = _torch()
+    lib = load_library()
+    S, T = int(logp_new.shape[0]), int(logp_new.shape[1])
+    for t in (logp_new, logp_old):
+        assert t.dtype == torch.float32 and t.is_cuda and t.is_contiguous() and tuple(t.shape) == (S, T)
+    assert completion_mask.dtype == torch.uint8 and completion_mask.is_cuda and completion_mask.is_contiguous()
+    assert tuple(completion_mask.shape) == (S, T)
+    assert advantages.dtype == torch.float32 and advantages.is_cuda and advantages.is_contiguous() and advantages.numel() == S
+    loss = torch.empty((1,), dtype=torch.float32, device="cuda")
+    grad = torch.empty((S, T), dtype=torch.float32, device="cuda") if want_grad else None
+    nbytes = sapo_surrogate_workspace_bytes()
+    if workspace is None:
+        workspace = _workspace(nbytes)
+    _check(lib.sapo_clipped_surrogate(logp_new.data_ptr(), logp_old.data_ptr(), completion_mask.data_ptr(),
+                                      advantages.data_ptr(), S, T, eps_low, eps_high, loss.data_ptr(),
+                                      grad.data_ptr() if want_grad else None, _aligned_ptr(workspace), nbytes,
+                                      _stream_ptr(stream)))
+    return loss, grad
 
 
 def sapo_debug_logits(w: Weights, tokens, positions: Sequence[Sequence[int]], stream=None):
