@@ -96,7 +96,7 @@ def main():
     ap.add_argument("--new-tokens", type=int, default=0, help="counter runs only: generate this many tokens")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not "
+        print("bench.py: this library runs on ONE GPU (no sharding, no collectives); --gpus %d is not "
               "supported. Sequences are independent, so N GPUs would each take P/N prompts." % args.gpus,
               file=sys.stderr)
         sys.exit(2)

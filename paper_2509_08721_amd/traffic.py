@@ -6,7 +6,7 @@ reads for a plain 1 GiB device copy in the same run (``bench.py --copy-probe``).
 next to this module together with hashes of the kernel sources; ``lookup`` returns nothing once a
 source has changed since the counters were taken.
 
-Build the table (on the GPU box, after the two rocprofv3 runs)::
+Build the table (on the machine with the GPU, after the two rocprofv3 runs)::
 
     python -m paper_2509_08721_amd.traffic WORKLOAD FETCH_counter_collection.csv WRITE_counter_collection.csv "NOTE"
 """
