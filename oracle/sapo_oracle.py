@@ -16,6 +16,9 @@ What it follows (SAPO paper):
     are discarded                                        -> group_advantages()
   * Sec. 4.2: the local update is GRPO without a KL term and with asymmetric
     clipping (0.2 / 0.28) of the probability ratio       -> clipped_surrogate_loss()
+  * Sec. 3.2 / Algorithm 1: the training set is I datapoints of the node's own
+    and J sampled uniformly from the swarm's after discarding those with zero
+    advantage                                            -> assemble_training_set()
 The paper names the policy only as a 0.5B-parameter decoder-only LM; the block
 structure used here (RMSNorm, rotary positions with the rotate-half pairing,
 grouped-query attention, SwiGLU FFN, tied LM head) is the reading recorded in
@@ -35,7 +38,9 @@ KV-cache decode == full recompute, log-softmax normalisation, advantage closed
 forms, zero-layer model, causality, batch invariance, library routines
 (torch CPU) for the individual blocks; for the clipped surrogate: hand-worked
 tokens on each side of each clip bound, the on-policy closed form, torch
-autograd, finite differences, mask invariance.
+autograd, finite differences, mask invariance; for the assembly: inclusion,
+first-draw and pair frequencies of the sampled subsets against those of a
+uniform subset, eligibility, edge sizes, stream separation, row-exact gathers.
 """
 from __future__ import annotations
 
@@ -408,3 +413,61 @@ def clipped_surrogate_loss(logp_new: np.ndarray, logp_old: np.ndarray, completio
             if active:
                 grad[s, t] = -a * rho / n
     return -total / n, grad
+
+
+# --------------------------------------------------------------------------- #
+# Training-set assembly (Sec. 3.2; Algorithm 1 "Assemble training set")
+# --------------------------------------------------------------------------- #
+STREAM_EXTERNAL, STREAM_LOCAL = 1, 2   # word 3 of the Philox counter (0 is the token sampler's)
+
+
+def subset_keys(seed: int, stream: int, n_groups: int) -> np.ndarray:
+    """uint32[n_groups]: the random key of each datapoint, word 0 of the Philox block with counter
+    (g, 0, 0, stream) under the seed's key."""
+    ctr = np.zeros((n_groups, 4), dtype=np.uint32)
+    ctr[:, 0] = np.arange(n_groups, dtype=np.uint32)
+    ctr[:, 3] = np.uint32(stream)
+    key = np.array([seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF], dtype=np.uint32)
+    return philox4x32_10(ctr, key)[:, 0]
+
+
+def uniform_subset(eligible: np.ndarray, k: int, seed: int, stream: int) -> np.ndarray:
+    """Indices of a uniformly random subset of min(k, #eligible) of the eligible datapoints, in the
+    order drawn: every eligible datapoint gets an independent random key, the k smallest
+    (key, index) pairs are the sample (a uniform subset because the keys are exchangeable)."""
+    elig = np.nonzero(np.asarray(eligible))[0]
+    keys = subset_keys(seed, stream, len(eligible))
+    order = sorted(elig.tolist(), key=lambda g: (int(keys[g]), g))
+    return np.asarray(order[:max(0, k)], dtype=np.int64)
+
+
+def assemble_training_set(local_tokens: np.ndarray, local_rewards: np.ndarray, ext_tokens: np.ndarray,
+                          ext_rewards: np.ndarray, group: int, n_local: int, n_ext: int, seed: int):
+    """The training set T^n of one round: n_local datapoints (a question's whole rollout of `group`
+    answers) drawn uniformly from the node's own, followed by n_ext drawn uniformly from those
+    swarm datapoints whose advantage is not identically zero (all `group` rewards equal means zero
+    advantage: discarded first, as in the paper's experiments).  Fewer are returned when the pool
+    runs out.  Returns (tokens int32 [(n_local + n_ext) * group, T], rewards float32 [...],
+    source int32 [n_local + n_ext], counts (taken local, taken external)); source g >= 0 is local
+    datapoint g, external datapoint g is n_local_pool + g; unfilled slots hold zeros and source -1."""
+    lt, et = np.asarray(local_tokens, np.int32), np.asarray(ext_tokens, np.int32)
+    lr, er = np.asarray(local_rewards, np.float32), np.asarray(ext_rewards, np.float32)
+    T = lt.shape[1] if lt.size else et.shape[1]
+    pl, pe = lt.shape[0] // group, et.shape[0] // group
+    take_l = uniform_subset(np.ones(pl, bool), n_local, seed, STREAM_LOCAL)
+    live = np.array([not np.all(er[g * group:(g + 1) * group] == er[g * group]) for g in range(pe)], dtype=bool)
+    take_e = uniform_subset(live, n_ext, seed, STREAM_EXTERNAL)
+    n = n_local + n_ext
+    tokens = np.zeros((n * group, T), np.int32)
+    rewards = np.zeros(n * group, np.float32)
+    source = np.full(n, -1, np.int32)
+    for slot, g in enumerate(take_l):
+        tokens[slot * group:(slot + 1) * group] = lt[g * group:(g + 1) * group]
+        rewards[slot * group:(slot + 1) * group] = lr[g * group:(g + 1) * group]
+        source[slot] = g
+    for i, g in enumerate(take_e):
+        slot = n_local + i
+        tokens[slot * group:(slot + 1) * group] = et[g * group:(g + 1) * group]
+        rewards[slot * group:(slot + 1) * group] = er[g * group:(g + 1) * group]
+        source[slot] = pl + g
+    return tokens, rewards, source, (len(take_l), len(take_e))

@@ -471,3 +471,79 @@ def test_clipped_surrogate_gradient_is_the_derivative():
             dn[s, t] -= h
             fd = (O.clipped_surrogate_loss(up, lo, mask, adv)[0] - O.clipped_surrogate_loss(dn, lo, mask, adv)[0]) / (2 * h)
             assert g[s, t] == pytest.approx(fd, abs=1e-8)
+
+
+# ----------------------------------------------------------------------------- training-set assembly (Sec. 3.2)
+def test_uniform_subset_is_uniform_and_respects_eligibility():
+    elig = np.array([1, 0, 1, 1, 0, 1, 1, 1, 0, 1], bool)          # 7 eligible of 10
+    k, trials = 3, 6000
+    hits = np.zeros(10)
+    first = np.zeros(10)
+    pairs = np.zeros((10, 10))
+    for seed in range(trials):
+        s = O.uniform_subset(elig, k, seed * 7919 + 1, O.STREAM_EXTERNAL)
+        assert len(s) == k and len(set(s.tolist())) == k and elig[s].all()
+        hits[s] += 1
+        first[s[0]] += 1
+        for a in s:
+            for b in s:
+                if a < b:
+                    pairs[a, b] += 1
+    p = k / 7
+    sd = math.sqrt(trials * p * (1 - p))
+    assert (np.abs(hits[elig] - trials * p) < 4.5 * sd).all()        # marginal inclusion probability k / E
+    assert not hits[~elig].any()
+    assert (np.abs(first[elig] - trials / 7) < 4.5 * math.sqrt(trials / 7 * 6 / 7)).all()   # order is uniform too
+    pp = k * (k - 1) / (7 * 6)                                        # pair inclusion of a uniform k-subset
+    e = np.nonzero(elig)[0]
+    for i, a in enumerate(e):
+        for b in e[i + 1:]:
+            assert abs(pairs[a, b] - trials * pp) < 4.5 * math.sqrt(trials * pp * (1 - pp))
+
+
+def test_uniform_subset_edges_and_streams():
+    elig = np.ones(6, bool)
+    assert sorted(O.uniform_subset(elig, 6, 5, 1).tolist()) == list(range(6))       # k = E: everything
+    assert sorted(O.uniform_subset(elig, 9, 5, 1).tolist()) == list(range(6))       # k > E: everything, no more
+    assert len(O.uniform_subset(elig, 0, 5, 1)) == 0
+    assert len(O.uniform_subset(np.zeros(6, bool), 3, 5, 1)) == 0
+    a, b = O.uniform_subset(np.ones(64, bool), 64, 5, 1), O.uniform_subset(np.ones(64, bool), 64, 5, 2)
+    assert not np.array_equal(a, b)                                                 # streams differ
+    assert np.array_equal(a, O.uniform_subset(np.ones(64, bool), 64, 5, 1))         # and are reproducible
+    # the keys are the generator's published stream, not the token sampler's (counter word 3 differs)
+    k = O.subset_keys(5, 1, 4)
+    ref = O.philox4x32_10(np.array([[2, 0, 0, 1]], np.uint32), np.array([5, 0], np.uint32))[0, 0]
+    assert k[2] == ref and k[2] != O.sampling_uniform_bits(5, 0, 0, 12)[8]
+
+
+def test_assemble_training_set_structure():
+    rng = np.random.default_rng(2)
+    G, T = 4, 9
+    lt = rng.integers(0, 1000, (5 * G, T)).astype(np.int32)
+    et = rng.integers(1000, 2000, (6 * G, T)).astype(np.int32)
+    lr = rng.integers(0, 2, 5 * G).astype(np.float32)
+    er = rng.integers(0, 2, 6 * G).astype(np.float32)
+    er[0:G] = 1.0           # external datapoint 0: all right  -> zero advantage
+    er[2 * G:3 * G] = 0.0   # external datapoint 2: all wrong  -> zero advantage
+    er[G:2 * G] = [1, 0, 0, 0]; er[3 * G:4 * G] = [0, 1, 1, 0]; er[4 * G:5 * G] = [1, 1, 0, 1]; er[5 * G:] = [0, 0, 1, 0]
+    tok, rew, src, (nl, ne) = O.assemble_training_set(lt, lr, et, er, G, 3, 5, seed=77)
+    assert (nl, ne) == (3, 4)                       # only 4 external datapoints have a non-zero advantage
+    assert tok.shape == (8 * G, T) and src.shape == (8,)
+    assert sorted(src[3:7].tolist()) == [5 + 1, 5 + 3, 5 + 4, 5 + 5] and src[7] == -1
+    assert len(set(src[:3].tolist())) == 3 and all(0 <= g < 5 for g in src[:3])
+    for slot, g in enumerate(src):
+        rows = slice(slot * G, (slot + 1) * G)
+        if g < 0:
+            assert not tok[rows].any() and not rew[rows].any()
+        elif g < 5:
+            assert np.array_equal(tok[rows], lt[g * G:(g + 1) * G]) and np.array_equal(rew[rows], lr[g * G:(g + 1) * G])
+        else:
+            h = g - 5
+            assert np.array_equal(tok[rows], et[h * G:(h + 1) * G]) and np.array_equal(rew[rows], er[h * G:(h + 1) * G])
+    # every selected external group has a non-zero advantage under the scoring call's own definition
+    adv = O.group_advantages(rew, G)
+    for slot in range(3, 7):
+        assert np.abs(adv[slot * G:(slot + 1) * G]).max() > 0
+    # J = 0 reduces to the node's own rollouts (the paper's remark on standard RL fine-tuning)
+    tok0, _, src0, (nl0, ne0) = O.assemble_training_set(lt, lr, et, er, G, 5, 0, seed=77)
+    assert (nl0, ne0) == (5, 0) and sorted(src0.tolist()) == [0, 1, 2, 3, 4]
