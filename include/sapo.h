@@ -133,6 +133,33 @@ int sapo_debug_logits(const sapo_weights* w, const int32_t* tokens, int S, int T
                       size_t workspace_bytes, void* stream);
 
 /*
+ * Training-set assembly (Sec. 3.2; Algorithm 1 "Assemble training set": SampleSelf and
+ * SampleExternal).  A datapoint is one question's whole rollout: G consecutive rows of a pool.
+ * n_local datapoints are drawn uniformly without replacement from the node's own pool, then n_ext
+ * from the swarm pool after discarding the datapoints whose G rewards are all equal (zero
+ * advantage; the filter the paper's experiments use).  Draw: datapoint g of a pool gets the key
+ * Philox4x32-10(counter (g, 0, 0, stream), key seed)[0], stream 2 for the own pool and 1 for the
+ * swarm pool; the sample is the eligible datapoints with the smallest (key, g), in that order.
+ *   local_tokens  dev int32 [n_local_pool * G, T]   local_rewards  dev fp32 [n_local_pool * G]
+ *   ext_tokens    dev int32 [n_ext_pool * G, T]     ext_rewards    dev fp32 [n_ext_pool * G]
+ *   out_tokens    dev int32 [(n_local + n_ext) * G, T]   own datapoints first
+ *   out_rewards   dev fp32  [(n_local + n_ext) * G]
+ *   out_source    dev int32 [n_local + n_ext]   g for own datapoint g, n_local_pool + g for swarm
+ *                                               datapoint g, -1 for a slot the pool could not fill
+ *                                               (its rows are zero)
+ *   out_counts    dev int32 [2]                 datapoints taken from the own / the swarm pool
+ *   workspace     dev, >= sapo_assemble_workspace_bytes(n_local_pool, n_ext_pool), 256-byte aligned
+ * Pools may be empty (pointers may then be NULL); each holds at most 16384 datapoints.
+ * Exact (integer work).  n_ext = 0 is plain local fine-tuning.
+ */
+size_t sapo_assemble_workspace_bytes(int n_local_pool, int n_ext_pool);
+int sapo_assemble_training_set(const int32_t* local_tokens, const float* local_rewards, int n_local_pool,
+                               const int32_t* ext_tokens, const float* ext_rewards, int n_ext_pool, int G,
+                               int T, int n_local, int n_ext, uint64_t seed, int32_t* out_tokens,
+                               float* out_rewards, int32_t* out_source, int32_t* out_counts,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Clipped surrogate of the local policy update (Sec. 4.2: GRPO with the KL weight at zero and
  * asymmetric clipping, eps_low = 0.2, eps_high = 0.28), consuming what the two calls above produce.
  * Per masked token: rho = exp(logp_new - logp_old), A = advantages[s],

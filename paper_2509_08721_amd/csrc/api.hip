@@ -847,6 +847,35 @@ extern "C" int sapo_debug_logits(const sapo_weights* w, const int32_t* tokens, i
   return SAPO_OK;
 }
 
+static const int kMaxPoolDatapoints = 16384;   // the subset ranks are computed all-against-all
+
+extern "C" size_t sapo_assemble_workspace_bytes(int n_local_pool, int n_ext_pool) {
+  const size_t n = (size_t)(n_local_pool > n_ext_pool ? n_local_pool : n_ext_pool);
+  return (n * 8 + 255) & ~(size_t)255;
+}
+
+extern "C" int sapo_assemble_training_set(const int32_t* local_tokens, const float* local_rewards, int n_local_pool,
+                                          const int32_t* ext_tokens, const float* ext_rewards, int n_ext_pool, int G, int T,
+                                          int n_local, int n_ext, uint64_t seed, int32_t* out_tokens, float* out_rewards,
+                                          int32_t* out_source, int32_t* out_counts, void* workspace,
+                                          size_t workspace_bytes, void* stream) {
+  if (G <= 0 || T <= 0 || n_local_pool < 0 || n_ext_pool < 0 || n_local < 0 || n_ext < 0)
+    return fail(SAPO_EINVAL, "negative size, or G / T not positive");
+  if (n_local_pool > kMaxPoolDatapoints || n_ext_pool > kMaxPoolDatapoints)
+    return fail(SAPO_EINVAL, "a pool holds more than %d datapoints", kMaxPoolDatapoints);
+  if ((long)(n_local + n_ext) * G * T > (1L << 31)) return fail(SAPO_EINVAL, "training set too large");
+  if ((n_local_pool > 0 && (!local_tokens || !local_rewards)) || (n_ext_pool > 0 && (!ext_tokens || !ext_rewards)) ||
+      !out_counts || !workspace || (n_local + n_ext > 0 && (!out_tokens || !out_rewards || !out_source)))
+    return fail(SAPO_EINVAL, "NULL buffer");
+  if (((uintptr_t)workspace & 255) != 0) return fail(SAPO_EINVAL, "workspace must be 256-byte aligned");
+  const size_t need = sapo_assemble_workspace_bytes(n_local_pool, n_ext_pool);
+  if (workspace_bytes < need) return fail(SAPO_EWORKSPACE, "workspace %zu < required %zu", workspace_bytes, need);
+  HIP_CK(g_assemble(local_tokens, local_rewards, n_local_pool, ext_tokens, ext_rewards, n_ext_pool, G, T, n_local, n_ext,
+                    (uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32), out_tokens, out_rewards, out_source, out_counts,
+                    workspace, (hipStream_t)stream));
+  return SAPO_OK;
+}
+
 extern "C" size_t sapo_surrogate_workspace_bytes(void) { return (g_surrogate_workspace_bytes() + 255) & ~(size_t)255; }
 
 extern "C" int sapo_clipped_surrogate(const float* logp_new, const float* logp_old, const uint8_t* completion_mask,

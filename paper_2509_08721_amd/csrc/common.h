@@ -202,6 +202,10 @@ hipError_t g_sample_rows(const float* logits, int n_prompt_rows, int G, int V, S
 hipError_t g_score_rows(const float* logits, int n_rows, int row_offset, int V, const int* row_seq_pos,
                         const int* n_rows_dev, const int32_t* tokens, int T, float* out_logprobs, hipStream_t st);
 hipError_t g_advantages(const float* rewards, int S, int G, float* out, hipStream_t st);
+hipError_t g_assemble(const int32_t* local_tokens, const float* local_rewards, int n_local_pool, const int32_t* ext_tokens,
+                      const float* ext_rewards, int n_ext_pool, int G, int T, int n_local, int n_ext, uint32_t seed_lo,
+                      uint32_t seed_hi, int32_t* out_tokens, float* out_rewards, int* out_source, int* out_counts,
+                      void* workspace, hipStream_t st);
 size_t g_surrogate_workspace_bytes();
 hipError_t g_surrogate_loss(const float* logp_new, const float* logp_old, const uint8_t* mask, const float* adv, int S, int T,
                             float eps_low, float eps_high, float* out_loss, float* out_dlogp, void* workspace,

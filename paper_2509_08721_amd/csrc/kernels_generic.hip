@@ -495,6 +495,90 @@ hipError_t g_surrogate_loss(const float* logp_new, const float* logp_old, const 
 }
 
 // ---------------------------------------------------------------------------------------
+// Training-set assembly (Sec. 3.2; Algorithm 1 "Assemble training set").  A datapoint is one
+// question's whole rollout (G sequences).  k_subset_keys gives every datapoint of a pool its random
+// key (word 0 of the Philox block with counter (g, 0, 0, stream)) and its eligibility (swarm pool:
+// the G rewards are not all equal, i.e. the advantage is not identically zero); k_subset_rank takes
+// the `take` eligible datapoints with the smallest (key, index) and gives slot slot0 + rank to each;
+// k_gather_datapoints copies the rows.  Integer work only: the result is exact.
+// ---------------------------------------------------------------------------------------
+__global__ void k_subset_keys(const float* __restrict__ rewards, int n_groups, int G, int filter, uint32_t seed_lo,
+                              uint32_t seed_hi, uint32_t stream, uint32_t* __restrict__ keys, int* __restrict__ elig) {
+  const int g = blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= n_groups) return;
+  keys[g] = philox4x32_10((uint32_t)g, 0u, 0u, stream, seed_lo, seed_hi).x;
+  int live = 1;
+  if (filter) {
+    live = 0;
+    const float* rg = rewards + (size_t)g * G;
+    for (int i = 1; i < G; ++i) live |= (rg[i] != rg[0]);
+  }
+  elig[g] = live;
+}
+__global__ void k_subset_rank(const uint32_t* __restrict__ keys, const int* __restrict__ elig, int n_groups, int take,
+                              int slot0, int src0, int* __restrict__ out_source, int* __restrict__ out_count) {
+  const int g = blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= n_groups || !elig[g]) return;
+  const uint32_t kg = keys[g];
+  int rank = 0;
+  for (int h = 0; h < n_groups; ++h) {
+    const uint32_t kh = keys[h];
+    rank += (elig[h] && (kh < kg || (kh == kg && h < g))) ? 1 : 0;
+  }
+  if (rank < take) {
+    out_source[slot0 + rank] = src0 + g;
+    atomicAdd(out_count, 1);   // integer count: the order of the additions does not matter
+  }
+}
+__global__ void __launch_bounds__(256) k_gather_datapoints(const int32_t* __restrict__ local_tokens,
+                                                           const float* __restrict__ local_rewards, int n_local_pool,
+                                                           const int32_t* __restrict__ ext_tokens,
+                                                           const float* __restrict__ ext_rewards, int G, int T,
+                                                           const int* __restrict__ source, int32_t* __restrict__ out_tokens,
+                                                           float* __restrict__ out_rewards) {
+  const int slot = blockIdx.x, i = blockIdx.y;
+  const int src = source[slot];
+  int32_t* dst = out_tokens + ((size_t)slot * G + i) * T;
+  if (src < 0) {
+    for (int t = threadIdx.x; t < T; t += 256) dst[t] = 0;
+    if (threadIdx.x == 0) out_rewards[(size_t)slot * G + i] = 0.f;
+    return;
+  }
+  const bool loc = src < n_local_pool;
+  const size_t row = (size_t)(loc ? src : src - n_local_pool) * G + i;
+  const int32_t* from = (loc ? local_tokens : ext_tokens) + row * T;
+  for (int t = threadIdx.x; t < T; t += 256) dst[t] = from[t];
+  if (threadIdx.x == 0) out_rewards[(size_t)slot * G + i] = (loc ? local_rewards : ext_rewards)[row];
+}
+hipError_t g_assemble(const int32_t* local_tokens, const float* local_rewards, int n_local_pool, const int32_t* ext_tokens,
+                      const float* ext_rewards, int n_ext_pool, int G, int T, int n_local, int n_ext, uint32_t seed_lo,
+                      uint32_t seed_hi, int32_t* out_tokens, float* out_rewards, int* out_source, int* out_counts,
+                      void* workspace, hipStream_t st) {
+  const int n_slots = n_local + n_ext;
+  const int n_max = n_local_pool > n_ext_pool ? n_local_pool : n_ext_pool;
+  uint32_t* keys = (uint32_t*)workspace;
+  int* elig = (int*)workspace + n_max;
+  hipError_t e = g_fill_i32(out_counts, 0, 2, st);
+  if (e != hipSuccess) return e;
+  if (n_slots > 0 && (e = g_fill_i32(out_source, -1, (size_t)n_slots, st)) != hipSuccess) return e;
+  struct Pool { const float* r; int n, take, slot0, src0, filter; uint32_t stream; int* count; };
+  const Pool pools[2] = {{local_rewards, n_local_pool, n_local, 0, 0, 0, 2u, out_counts},
+                         {ext_rewards, n_ext_pool, n_ext, n_local, n_local_pool, 1, 1u, out_counts + 1}};
+  for (const Pool& p : pools) {
+    if (p.n == 0 || p.take == 0) continue;
+    const dim3 grid((p.n + 255) / 256);
+    e = launch(KID_MISC, k_subset_keys, grid, dim3(256), 0, st, p.r, p.n, G, p.filter, seed_lo, seed_hi, p.stream, keys, elig);
+    if (e != hipSuccess) return e;
+    e = launch(KID_MISC, k_subset_rank, grid, dim3(256), 0, st, (const uint32_t*)keys, (const int*)elig, p.n, p.take, p.slot0,
+               p.src0, out_source, p.count);
+    if (e != hipSuccess) return e;
+  }
+  if (n_slots == 0) return hipSuccess;
+  return launch(KID_MISC, k_gather_datapoints, dim3(n_slots, G), dim3(256), 0, st, local_tokens, local_rewards, n_local_pool,
+                ext_tokens, ext_rewards, G, T, (const int*)out_source, out_tokens, out_rewards);
+}
+
+// ---------------------------------------------------------------------------------------
 // Ordered compaction of the positions to score in sequences [s0, s0 + ns): entry i of `rows`
 // is (s, t) with mask[s, t] != 0 and t >= 1, in (s, t) order; *count = number of entries.
 // `src_rows[i]` = local row (s - s0) * T + t - 1 whose hidden state predicts token (s, t).

@@ -63,6 +63,10 @@ def load_library() -> C.CDLL:
     lib.sapo_rollout_generate.restype = i32
     lib.sapo_score_logprobs.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
     lib.sapo_score_logprobs.restype = i32
+    lib.sapo_assemble_workspace_bytes.argtypes = [i32, i32]
+    lib.sapo_assemble_workspace_bytes.restype = sz
+    lib.sapo_assemble_training_set.argtypes = [vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, u64, vp, vp, vp, vp, vp, sz, vp]
+    lib.sapo_assemble_training_set.restype = i32
     lib.sapo_surrogate_workspace_bytes.argtypes = []
     lib.sapo_surrogate_workspace_bytes.restype = sz
     lib.sapo_clipped_surrogate.argtypes = [vp, vp, vp, vp, i32, i32, f32, f32, vp, vp, vp, sz, vp]
@@ -89,6 +93,7 @@ EXPORTED = ["sapo_weights_create", "sapo_weights_destroy", "sapo_weights_uses_mf
             "sapo_rollout_workspace_bytes", "sapo_score_workspace_bytes",
             "sapo_debug_logits_workspace_bytes", "sapo_rollout_generate", "sapo_score_logprobs",
             "sapo_surrogate_workspace_bytes", "sapo_clipped_surrogate",
+            "sapo_assemble_workspace_bytes", "sapo_assemble_training_set",
             "sapo_debug_logits", "sapo_debug_gumbel", "sapo_last_error", "sapo_profile_kernel_count",
             "sapo_profile_kernel_name", "sapo_profile_start", "sapo_profile_stop"]
 
@@ -234,6 +239,37 @@ def sapo_score_logprobs(w: Weights, tokens, completion_mask, rewards, G: int, wo
                                    S, T, G, out_logprobs.data_ptr(), out_advantages.data_ptr(),
                                    _aligned_ptr(workspace), nbytes, _stream_ptr(stream)))
     return out_logprobs, out_advantages
+
+
+def sapo_assemble_workspace_bytes(n_local_pool: int, n_ext_pool: int) -> int:
+    return int(load_library().sapo_assemble_workspace_bytes(n_local_pool, n_ext_pool))
+
+
+def sapo_assemble_training_set(local_tokens, local_rewards, ext_tokens, ext_rewards, G: int, n_local: int, n_ext: int,
+                               seed: int, workspace=None, stream=None):
+    """Pools: tokens int32 [n_pool * G, T] and rewards float32 [n_pool * G] (device tensors; a pool may have 0 rows).
+    Returns (tokens int32 [(n_local + n_ext) * G, T], rewards float32, source int32 [n_local + n_ext], counts int32 [2])."""
+    torch = _torch()
+    lib = load_library()
+    T = int(local_tokens.shape[1]) if local_tokens.shape[0] else int(ext_tokens.shape[1])
+    for tk, rw in ((local_tokens, local_rewards), (ext_tokens, ext_rewards)):
+        assert tk.dtype == torch.int32 and tk.is_cuda and tk.is_contiguous() and rw.dtype == torch.float32 and rw.is_cuda
+        assert tk.shape[0] % G == 0 and rw.numel() == tk.shape[0] and (tk.shape[0] == 0 or tk.shape[1] == T)
+    pl, pe = int(local_tokens.shape[0]) // G, int(ext_tokens.shape[0]) // G
+    n = n_local + n_ext
+    out_t = torch.empty((n * G, T), dtype=torch.int32, device="cuda")
+    out_r = torch.empty((n * G,), dtype=torch.float32, device="cuda")
+    out_s = torch.empty((n,), dtype=torch.int32, device="cuda")
+    out_c = torch.empty((2,), dtype=torch.int32, device="cuda")
+    nbytes = sapo_assemble_workspace_bytes(pl, pe)
+    if workspace is None:
+        workspace = _workspace(max(nbytes, 256))
+    _check(lib.sapo_assemble_training_set(local_tokens.data_ptr() if pl else None, local_rewards.data_ptr() if pl else None, pl,
+                                          ext_tokens.data_ptr() if pe else None, ext_rewards.data_ptr() if pe else None, pe,
+                                          G, T, n_local, n_ext, int(seed), out_t.data_ptr() if n else None,
+                                          out_r.data_ptr() if n else None, out_s.data_ptr() if n else None, out_c.data_ptr(),
+                                          _aligned_ptr(workspace), max(nbytes, 256), _stream_ptr(stream)))
+    return out_t, out_r, out_s, out_c
 
 
 def sapo_surrogate_workspace_bytes() -> int:
