@@ -105,6 +105,21 @@ int sapo_rollout_generate(const sapo_weights* w, const int32_t* prompts, int P, 
                           void* stream);
 
 /*
+ * Rollout generation with a stop token (answers of different lengths, Sec. 3.1: an answer a_i(q)
+ * ends where the policy ends it).  As sapo_rollout_generate, and in addition: the first stop_token a
+ * sequence samples ends it (the token and its log-prob are kept); the rest of its row is stop_token
+ * with log-prob 0.  The noise is keyed on (seed, sequence, step), so a row equals the row of the
+ * plain call up to and including its stop.  Every 32 steps the host reads a counter (this call then
+ * synchronises the stream) and returns early once every sequence has ended.
+ *   stop_token   a vocabulary id
+ *   out_lengths  dev int32 [P*G]   tokens generated including the stop token; max_new if none
+ */
+int sapo_rollout_generate_stop(const sapo_weights* w, const int32_t* prompts, int P, int Lp, int G,
+                               int max_new, float temperature, uint64_t seed, int32_t stop_token,
+                               int32_t* out_tokens, float* out_logprobs, int32_t* out_lengths,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Scoring pass (Sec. 3.2: token-level values of any rollout under the node's own policy;
  * Sec. 4.2: GRPO's group-relative advantage).
  *   tokens           dev int32 [S, T]   prompt + completion of every training-set sequence

@@ -335,6 +335,39 @@ def rollout_generate(m: Model, prompts: np.ndarray, group: int, max_new: int, te
     return out_tok, out_lp
 
 
+def rollout_generate_stop(m: Model, prompts: np.ndarray, group: int, max_new: int, temperature: float,
+                          seed: int, stop_token: int):
+    """rollout_generate with a stop token: an answer ends with the first stop_token it samples
+    (that token and its log-prob are kept); the rest of its row is stop_token with log-prob 0.
+    Nothing else changes: the sampler's noise is keyed on (seed, sequence, step), so a row equals
+    the unstopped row up to and including its stop.  Returns (tokens, logprobs, lengths int32 [S]),
+    lengths counting the stop token, max_new where none was sampled."""
+    prompts = np.asarray(prompts)
+    P, Lp = prompts.shape
+    S = P * group
+    out_tok = np.full((S, max_new), stop_token, dtype=np.int32)
+    out_lp = np.zeros((S, max_new), dtype=np.float32)
+    lengths = np.full(S, max_new, dtype=np.int32)
+    for p in range(P):
+        pcache = [[None, None] for _ in range(m.n_layers)]
+        x_last = hidden_states(m, prompts[p], pcache)[-1:]
+        for g in range(group):
+            s = p * group + g
+            cache = [[k.copy(), v.copy()] for k, v in pcache]
+            x = x_last
+            for t in range(max_new):
+                z = logits_from_hidden(m, x)[0]
+                tok = sample_token(z, temperature, seed, s, t)
+                out_tok[s, t] = tok
+                out_lp[s, t] = log_softmax(z)[tok]
+                if tok == stop_token:
+                    lengths[s] = t + 1
+                    break
+                if t + 1 < max_new:
+                    x = hidden_states(m, np.array([tok]), cache)
+    return out_tok, out_lp, lengths
+
+
 def score_logprobs(m: Model, tokens: np.ndarray, completion_mask: np.ndarray) -> np.ndarray:
     """Teacher-forced per-token log-probs under the policy.
 

@@ -509,6 +509,7 @@ struct RolloutPlan {
   CacheBufs cache;
   FwdBufs fwd;
   int* step;        // device step counter
+  int* stop;        // device: {stop token or -1, sequences ended, length of each sequence (0 = running)}
   int* last_rows;   // [P]
   float* h_last;    // [S, d] residual of each sequence's last prompt position
   void* x_last;     // [max(P, S), d] final-norm output (T)
@@ -530,6 +531,7 @@ static void plan_rollout(const sapo_weights* w, int P, int Lp, int G, int N, cha
   pl.M_max = (size_t)P * Lp > (size_t)pl.S ? (size_t)P * Lp : (size_t)pl.S;
   Arena A{base, 0};
   pl.step = A.take<int>(64);
+  pl.stop = A.take<int>((size_t)pl.S + 2);
   pl.last_rows = A.take<int>(P);
   carve_cache(A, w, pl.S, pl.pages_per_seq, pl.n_pages, pl.cache);
   carve_fwd(A, w, pl.M_max, pl.fwd);
@@ -590,12 +592,13 @@ static int sample_step(const sapo_weights* w, const RolloutPlan& pl, const float
   return SAPO_OK;
 }
 
-extern "C" int sapo_rollout_generate(const sapo_weights* w, const int32_t* prompts, int P, int Lp, int G, int max_new,
-                                     float temperature, uint64_t seed, int32_t* out_tokens, float* out_logprobs,
-                                     void* workspace, size_t workspace_bytes, void* stream) {
+static int rollout_impl(const sapo_weights* w, const int32_t* prompts, int P, int Lp, int G, int max_new,
+                        float temperature, uint64_t seed, int stop_token, int32_t* out_tokens, float* out_logprobs,
+                        int32_t* out_lengths, void* workspace, size_t workspace_bytes, void* stream) {
   int rc = check_rollout_args(w, P, Lp, G, max_new);
   if (rc) return rc;
   if (!prompts || !out_tokens || !out_logprobs || !workspace) return fail(SAPO_EINVAL, "NULL buffer");
+  if (stop_token >= w->cfg.vocab) return fail(SAPO_EINVAL, "stop token %d is outside the vocabulary", stop_token);
   if (!(temperature >= 0.f)) return fail(SAPO_EINVAL, "temperature must be >= 0");
   if (((uintptr_t)workspace & 255) != 0) return fail(SAPO_EINVAL, "workspace must be 256-byte aligned");
   RolloutPlan pl;
@@ -616,6 +619,28 @@ extern "C" int sapo_rollout_generate(const sapo_weights* w, const int32_t* promp
   sp.dyn = (const uint32_t*)(pl.step + 1);
   sp.out_tokens = out_tokens;
   sp.out_logprobs = out_logprobs;
+  sp.stop = pl.stop;
+  const bool stopping = stop_token >= 0;
+  HIP_CK(g_fill_i32(pl.stop, stop_token, 1, st));
+  HIP_CK(g_fill_i32(pl.stop + 1, 0, (size_t)S + 1, st));
+  if (stopping) {   // whatever is not generated because every sequence has ended is padding already
+    HIP_CK(g_fill_i32(out_tokens, stop_token, (size_t)S * max_new, st));
+    HIP_CK(g_fill_f32(out_logprobs, 0.f, (size_t)S * max_new, st));
+  }
+  // lengths: stop[2 + s], with 0 (never stopped) read as max_new
+  auto finish = [&]() -> int {
+    if (out_lengths) HIP_CK(g_lengths_out(pl.stop + 2, S, max_new, out_lengths, st));
+    return SAPO_OK;
+  };
+  // with a stop token the host looks, every kStopPoll steps, whether every sequence has ended
+  const int kStopPoll = 32;
+  auto all_stopped = [&](bool& yes) -> int {
+    int n = 0;
+    HIP_CK(hipMemcpyAsync(&n, pl.stop + 1, sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_CK(hipStreamSynchronize(st));
+    yes = (n >= S);
+    return SAPO_OK;
+  };
 
   HIP_CK(g_fill_i32(pl.step, 0, 1, st));
   {
@@ -664,9 +689,15 @@ extern "C" int sapo_rollout_generate(const sapo_weights* w, const int32_t* promp
   const char* no_graph = getenv("SAPO_NO_GRAPH");
   const bool use_graph = st != nullptr && !g_prof_on && max_new > 2 && !(no_graph && no_graph[0] == '1');
   if (!use_graph) {
-    for (int t = 1; t < max_new; ++t)
+    for (int t = 1; t < max_new; ++t) {
+      if (stopping && t % kStopPoll == 0) {
+        bool done = false;
+        if ((rc = all_stopped(done))) return rc;
+        if (done) break;
+      }
       if ((rc = enqueue_step())) return rc;
-    return SAPO_OK;
+    }
+    return finish();
   }
   sapo_weights::DecodeGraph& dg = w->dgraph;
   if (!(dg.valid && dg.out_tokens == out_tokens && dg.out_logprobs == out_logprobs && dg.workspace == workspace &&
@@ -692,8 +723,32 @@ extern "C" int sapo_rollout_generate(const sapo_weights* w, const int32_t* promp
     dg.P = P; dg.Lp = Lp; dg.G = G; dg.N = max_new;
     dg.graph = graph; dg.exec = exec;
   }
-  for (int t = 1; t < max_new; ++t) HIP_CK(hipGraphLaunch(dg.exec, st));
-  return SAPO_OK;
+  for (int t = 1; t < max_new; ++t) {
+    if (stopping && t % kStopPoll == 0) {
+      bool done = false;
+      if ((rc = all_stopped(done))) return rc;
+      if (done) break;
+    }
+    HIP_CK(hipGraphLaunch(dg.exec, st));
+  }
+  return finish();
+}
+
+extern "C" int sapo_rollout_generate(const sapo_weights* w, const int32_t* prompts, int P, int Lp, int G, int max_new,
+                                     float temperature, uint64_t seed, int32_t* out_tokens, float* out_logprobs,
+                                     void* workspace, size_t workspace_bytes, void* stream) {
+  return rollout_impl(w, prompts, P, Lp, G, max_new, temperature, seed, -1, out_tokens, out_logprobs, nullptr, workspace,
+                      workspace_bytes, stream);
+}
+
+extern "C" int sapo_rollout_generate_stop(const sapo_weights* w, const int32_t* prompts, int P, int Lp, int G, int max_new,
+                                          float temperature, uint64_t seed, int32_t stop_token, int32_t* out_tokens,
+                                          float* out_logprobs, int32_t* out_lengths, void* workspace,
+                                          size_t workspace_bytes, void* stream) {
+  if (stop_token < 0) return fail(SAPO_EINVAL, "stop token must be a vocabulary id");
+  if (!out_lengths) return fail(SAPO_EINVAL, "NULL buffer");
+  return rollout_impl(w, prompts, P, Lp, G, max_new, temperature, seed, stop_token, out_tokens, out_logprobs, out_lengths,
+                      workspace, workspace_bytes, stream);
 }
 
 // ---------------------------------------------------------------------------------------

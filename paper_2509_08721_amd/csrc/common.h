@@ -142,6 +142,9 @@ struct SampleParams {
                           // (lets one captured graph serve calls that differ only in seed / temperature)
   int32_t* out_tokens;    // [S, max_new]
   float* out_logprobs;    // [S, max_new]
+  // Stop token (optional): stop[0] = the token id that ends a sequence (< 0: none), stop[1] = number of
+  // finished sequences, stop[2 + s] = length of sequence s once it has ended (0 while it runs).
+  int* stop = nullptr;
 };
 
 // Optional per-kernel timing: when switched on, every launch carries two HIP events that take
@@ -174,6 +177,25 @@ inline hipError_t launch(int kid, void (*kernel)(KArgs...), dim3 grid, dim3 bloc
   return hipLaunchKernel((const void*)kernel, grid, block, ptrs, smem, st);
 }
 
+// The one place a sampled token is written.  A sequence that has emitted the stop token keeps
+// emitting it with log-prob 0 (padding); the token returned is the one the next step embeds.
+__device__ __forceinline__ int emit_token(const SampleParams& sp, int seq, int step, int token, float logprob) {
+  if (sp.stop && sp.stop[0] >= 0) {
+    int* len = sp.stop + 2 + seq;
+    if (*len > 0) {
+      token = sp.stop[0];
+      logprob = 0.f;
+    } else if (token == sp.stop[0]) {
+      *len = step + 1;
+      atomicAdd(sp.stop + 1, 1);
+    }
+  }
+  const size_t o = (size_t)seq * sp.max_new + step;
+  sp.out_tokens[o] = token;
+  sp.out_logprobs[o] = logprob;
+  return token;
+}
+
 __device__ __forceinline__ void resolve_sample_params(SampleParams& sp) {
   if (sp.dyn) {
     sp.seed_lo = sp.dyn[0];
@@ -202,6 +224,8 @@ hipError_t g_sample_rows(const float* logits, int n_prompt_rows, int G, int V, S
 hipError_t g_score_rows(const float* logits, int n_rows, int row_offset, int V, const int* row_seq_pos,
                         const int* n_rows_dev, const int32_t* tokens, int T, float* out_logprobs, hipStream_t st);
 hipError_t g_advantages(const float* rewards, int S, int G, float* out, hipStream_t st);
+// out[s] = len[s] if the sequence has stopped (len > 0), else max_new
+hipError_t g_lengths_out(const int* len, int S, int max_new, int32_t* out, hipStream_t st);
 hipError_t g_assemble(const int32_t* local_tokens, const float* local_rewards, int n_local_pool, const int32_t* ext_tokens,
                       const float* ext_rewards, int n_ext_pool, int G, int T, int n_local, int n_ext, uint32_t seed_lo,
                       uint32_t seed_hi, int32_t* out_tokens, float* out_rewards, int* out_source, int* out_counts,

@@ -535,11 +535,7 @@ __global__ void __launch_bounds__(128) k_lmhead_merge_embed(const float* __restr
       b.add(__shfl_xor(b.y, o, 64), __shfl_xor(b.z, o, 64), __shfl_xor(b.id, o, 64));
     }
     if (lane == 0) {
-      const int step = *sp.step;
-      const size_t o = (size_t)(seq0 + r) * sp.max_new + step;
-      sp.out_tokens[o] = b.id;
-      sp.out_logprobs[o] = b.z - (a.m + logf(a.l));
-      s_tok = b.id;
+      s_tok = emit_token(sp, seq0 + r, *sp.step, b.id, b.z - (a.m + logf(a.l)));
     }
   }
   __syncthreads();

@@ -358,8 +358,7 @@ __global__ void __launch_bounds__(256) k_sample_rows(const float* __restrict__ l
   __syncthreads();
   if (threadIdx.x == 0) {
     for (int w = 1; w < 4; ++w) best.add(sm_y[w], sm_z[w], sm_id[w]);
-    sp.out_tokens[(size_t)s * sp.max_new + step] = best.id;
-    sp.out_logprobs[(size_t)s * sp.max_new + step] = best.z - (lse.m + logf(lse.l));
+    emit_token(sp, s, step, best.id, best.z - (lse.m + logf(lse.l)));
   }
 }
 hipError_t g_sample_rows(const float* logits, int n_rows, int G, int V, SampleParams sp, hipStream_t st) {
@@ -409,6 +408,13 @@ __global__ void k_advantages(const float* __restrict__ r, int n_groups, int G, f
   for (int i = 0; i < G; ++i) { const double dlt = (double)rg[i] - mu; var += dlt * dlt; }
   const double sd = sqrt(var / G);
   for (int i = 0; i < G; ++i) out[(size_t)g * G + i] = (float)(((double)rg[i] - mu) / (sd + 1e-6));
+}
+__global__ void k_lengths_out(const int* __restrict__ len, int S, int max_new, int32_t* __restrict__ out) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s < S) out[s] = len[s] > 0 ? len[s] : max_new;
+}
+hipError_t g_lengths_out(const int* len, int S, int max_new, int32_t* out, hipStream_t st) {
+  return launch(KID_MISC, k_lengths_out, dim3((S + 255) / 256), dim3(256), 0, st, len, S, max_new, out);
 }
 hipError_t g_advantages(const float* rewards, int S, int G, float* out, hipStream_t st) {
   const int ng = S / G;

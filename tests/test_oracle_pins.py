@@ -547,3 +547,28 @@ def test_assemble_training_set_structure():
     # J = 0 reduces to the node's own rollouts (the paper's remark on standard RL fine-tuning)
     tok0, _, src0, (nl0, ne0) = O.assemble_training_set(lt, lr, et, er, G, 5, 0, seed=77)
     assert (nl0, ne0) == (5, 0) and sorted(src0.tolist()) == [0, 1, 2, 3, 4]
+
+
+# ----------------------------------------------------------------------------- stop token
+def test_stop_token_rows_are_prefixes_of_unstopped_rows():
+    shape, w, m = tiny_model(seed=4)
+    prompts = np.random.default_rng(0).integers(0, shape.vocab, size=(2, 6))
+    G, N, seed = 3, 24, 9
+    tok, lp = O.rollout_generate(m, prompts, G, N, 1.0, seed)
+    # a stop token that some rows do sample and some do not
+    vals, counts = np.unique(tok[:, 2:N - 2], return_counts=True)
+    stop = int(vals[np.argmax(counts)])
+    t2, l2, ln = O.rollout_generate_stop(m, prompts, G, N, 1.0, seed, stop)
+    hit = 0
+    for s in range(tok.shape[0]):
+        where = np.nonzero(tok[s] == stop)[0]
+        n = int(where[0]) + 1 if where.size else N
+        hit += bool(where.size)
+        assert ln[s] == n
+        assert np.array_equal(t2[s, :n], tok[s, :n]) and np.array_equal(l2[s, :n], lp[s, :n])
+        assert (t2[s, n:] == stop).all() and not l2[s, n:].any()
+    assert 0 < hit
+    # a token nobody samples: identical to the unstopped call
+    unused = next(v for v in range(shape.vocab) if v not in set(tok.ravel().tolist()))
+    t3, l3, ln3 = O.rollout_generate_stop(m, prompts, G, N, 1.0, seed, unused)
+    assert np.array_equal(t3, tok) and np.array_equal(l3, lp) and (ln3 == N).all()
