@@ -134,15 +134,19 @@ def main():
         P, Lp, N = S_score // G, T - Tm, Tm
         S = S_score
         prompts_np = W.make_prompts(W.scaled(wl, n_prompts=P, prompt_len=Lp))
-        other = sapo.sapo_weights_create(shape, W.make_weights(shape, wl.external_weight_seed))
-        half = P // 2
-        t_loc, _ = sapo.sapo_rollout_generate(gw, torch.from_numpy(prompts_np[:half]).cuda(), G, N, 1.0, wl.rollout_seed)
-        t_ext, _ = sapo.sapo_rollout_generate(other, torch.from_numpy(prompts_np[half:]).cuda(), G, N, 1.0,
-                                              wl.rollout_seed + 1)
-        torch.cuda.synchronize()
-        del other
-        seq_src = torch.cat([torch.from_numpy(np.repeat(prompts_np, G, axis=0)).cuda(),
-                             torch.cat([t_loc, t_ext], dim=0)], dim=1).contiguous()
+        if args.layers > 0:
+            # counter run: traffic does not depend on token values, and the preparation rollouts would only add launches
+            seq_src = torch.from_numpy(W.make_random_tokens(S_score, T, shape.vocab, wl.rollout_seed)).cuda()
+        else:
+            other = sapo.sapo_weights_create(shape, W.make_weights(shape, wl.external_weight_seed))
+            half = P // 2
+            t_loc, _ = sapo.sapo_rollout_generate(gw, torch.from_numpy(prompts_np[:half]).cuda(), G, N, 1.0, wl.rollout_seed)
+            t_ext, _ = sapo.sapo_rollout_generate(other, torch.from_numpy(prompts_np[half:]).cuda(), G, N, 1.0,
+                                                  wl.rollout_seed + 1)
+            torch.cuda.synchronize()
+            del other
+            seq_src = torch.cat([torch.from_numpy(np.repeat(prompts_np, G, axis=0)).cuda(),
+                                 torch.cat([t_loc, t_ext], dim=0)], dim=1).contiguous()
     prompts = torch.from_numpy(prompts_np).cuda()
     plan = {"S": S, "N": N, "Lp": Lp, "P": P, "T": T, "Tm": Tm, "S_score": S_score, "rollout": do_rollout,
             "score": do_score, "fused_lm": S <= 64 and shape.d_model <= 1024}
