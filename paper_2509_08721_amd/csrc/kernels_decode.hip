@@ -126,10 +126,14 @@ __global__ void __launch_bounds__(512) k_skinny16(SkinnyArgs a, int n_units) {
   constexpr int TS = 4 / TG;        // workgroups per (tile unit, token block)
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int KS = a.K >> 5;
-  const int tb = blockIdx.y;
-  // block id -> (unit, token split): the TS splits of a unit sit 8 ids apart
-  const int unit = (blockIdx.x / (8 * TS)) * 8 + (blockIdx.x & 7);
-  const int tg0 = ((blockIdx.x >> 3) % TS) * TG;
+  // block id -> (unit, token block, token split).  Ids are dealt round-robin to the 8 XCDs; the workgroups
+  // that read the same weight tiles (all token blocks and splits of a unit) sit 8 ids apart, so they run on
+  // one XCD at about the same time and the tiles come from HBM once.
+  const int nblk = (a.n_rows + 63) >> 6;
+  const int j = blockIdx.x >> 3, inner = j % (TS * nblk);
+  const int unit = (j / (TS * nblk)) * 8 + (blockIdx.x & 7);
+  const int tb = inner / TS;
+  const int tg0 = (inner % TS) * TG;
   if (unit >= n_units) return;
   const int tile0 = unit * NT;
   f32x4 acc[NT][TG];
@@ -280,8 +284,8 @@ static hipError_t launch_skinny(const SkinnyArgs& a, hipStream_t st) {
   if ((a.N / 16) % NT != 0) return hipErrorInvalidValue;
   const int units = a.N / 16 / NT;
   const int blocks = (a.n_rows + 63) / 64;
-  const int gx = (units + 7) / 8 * 8 * (4 / TG);
-  return launch(KID_GEMM_SKINNY, k_skinny16<NT, TG, R, MODE>, dim3(gx, blocks), dim3(512), smem, st, a, units);
+  const int gx = (units + 7) / 8 * 8 * (4 / TG) * blocks;
+  return launch(KID_GEMM_SKINNY, k_skinny16<NT, TG, R, MODE>, dim3(gx), dim3(512), smem, st, a, units);
 }
 
 // Blocking.  A workgroup reads NT weight tiles and TG token groups over the whole K, so what it must
