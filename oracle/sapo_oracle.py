@@ -217,9 +217,10 @@ def _layer(m: Model, lw: dict, h: np.ndarray, positions: np.ndarray, k_prev, v_p
     """
     n = h.shape[0]
     a = m.rnd(rmsnorm(h, lw["attn_norm"], m.eps))
-    q = (a @ lw["wq"].T).reshape(n, m.hq, m.hd)
-    k = (a @ lw["wk"].T).reshape(n, m.hkv, m.hd)
-    v = (a @ lw["wv"].T).reshape(n, m.hkv, m.hd)
+    q, k, v = a @ lw["wq"].T, a @ lw["wk"].T, a @ lw["wv"].T
+    if "bq" in lw:   # optional biases of the three projections (the 0.5B model family the paper ran has them)
+        q, k, v = q + lw["bq"], k + lw["bk"], v + lw["bv"]
+    q, k, v = q.reshape(n, m.hq, m.hd), k.reshape(n, m.hkv, m.hd), v.reshape(n, m.hkv, m.hd)
     q = m.rnd(rope_rotate(q, positions, m.theta))
     k = m.rnd(rope_rotate(k, positions, m.theta))
     v = m.rnd(v)

@@ -205,6 +205,21 @@ def make_weights(shape: ModelShape, seed: int, std: float = 0.02) -> dict:
     return w
 
 
+def add_qkv_bias(weights: dict, shape: ModelShape, seed: int, std: float = 0.1) -> dict:
+    """A copy of the weights with float32 biases bq [q], bk [kv], bv [kv] on the three attention
+    projections of every layer (N(0, std^2), generator default_rng([seed, 7, layer]))."""
+    out = dict(weights)
+    out["layers"] = []
+    for l, lw in enumerate(weights["layers"]):
+        rng = np.random.default_rng([seed, 7, l])
+        lw = dict(lw)
+        lw["bq"] = (rng.standard_normal(shape.q_dim) * std).astype(np.float32)
+        lw["bk"] = (rng.standard_normal(shape.kv_dim) * std).astype(np.float32)
+        lw["bv"] = (rng.standard_normal(shape.kv_dim) * std).astype(np.float32)
+        out["layers"].append(lw)
+    return out
+
+
 def perturb_norm_gains(weights: dict, seed: int, spread: float = 0.25) -> dict:
     """Same weights but with non-trivial RMSNorm gains 1 + U(-spread, spread) (test helper:
     all-ones gains would hide a missing or misplaced gain multiply)."""

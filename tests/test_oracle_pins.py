@@ -230,6 +230,10 @@ def scalar_forward(shape, wf, tokens):
         for t in range(T):
             a = norm(hs[t], lw["attn_norm"])
             q, k, v = matvec(lw["wq"], a), matvec(lw["wk"], a), matvec(lw["wv"], a)
+            if "bq" in lw:
+                q = [x + float(b) for x, b in zip(q, lw["bq"])]
+                k = [x + float(b) for x, b in zip(k, lw["bk"])]
+                v = [x + float(b) for x, b in zip(v, lw["bv"])]
             qs.append([rot(q[h * hd:(h + 1) * hd], t) for h in range(hq)])
             ks.append([rot(k[h * hd:(h + 1) * hd], t) for h in range(hkv)])
             vs.append([v[h * hd:(h + 1) * hd] for h in range(hkv)])
@@ -263,6 +267,36 @@ def test_forward_vs_scalar_loops():
     got = O.forward_logits(m, tokens)
     ref = scalar_forward(shape, W.weights_as_f32(shape, w), tokens)
     assert np.allclose(got, ref, atol=1e-12)
+
+
+def test_qkv_bias_scalar_loops_and_closed_form():
+    from dataclasses import replace
+    shape = replace(W.TINY, n_layers=2, d_model=16, n_q_heads=4, n_kv_heads=2, head_dim=4, d_ff=12, vocab=20)
+    w0 = W.perturb_norm_gains(W.make_weights(shape, 11, std=0.3), 11)
+    w = W.add_qkv_bias(w0, shape, 5, std=0.5)
+    tokens = np.array([3, 19, 0, 7, 7, 12])
+    got = O.forward_logits(O.Model(shape, w), tokens)
+    ref = scalar_forward(shape, W.weights_as_f32(shape, w), tokens)
+    assert np.allclose(got, ref, atol=1e-12)
+    assert np.abs(got - O.forward_logits(O.Model(shape, w0), tokens)).max() > 1e-3      # the biases matter
+    # zero biases are no biases
+    wz = W.add_qkv_bias(w0, shape, 5, std=0.0)
+    assert np.array_equal(O.forward_logits(O.Model(shape, wz), tokens), O.forward_logits(O.Model(shape, w0), tokens))
+    # closed form: with wq = wk = wv = 0 every key and value is the bias itself, so attention returns bv of the
+    # head's KV group whatever the scores are, and one layer adds wo . repeat(bv) to the residual
+    one = replace(shape, n_layers=1)
+    w1 = W.add_qkv_bias(W.make_weights(one, 3, std=0.3), one, 9, std=0.7)
+    lw = w1["layers"][0]
+    for k in ("wq", "wk", "wv", "w_down"):
+        lw[k] = np.zeros_like(lw[k])
+    m = O.Model(one, w1)
+    h = O.hidden_states(m, tokens)
+    f = W.weights_as_f32(one, w1)
+    rep = one.n_q_heads // one.n_kv_heads
+    o = np.concatenate([np.asarray(lw["bv"], np.float64)[(hh // rep) * one.head_dim:(hh // rep + 1) * one.head_dim]
+                        for hh in range(one.n_q_heads)])
+    expect = np.asarray(f["embed"], np.float64)[tokens] + np.asarray(f["layers"][0]["wo"], np.float64) @ o
+    assert np.allclose(h, O.rmsnorm(expect, np.asarray(f["final_norm"], np.float64), one.rms_eps), atol=1e-12)
 
 
 def test_zero_layer_model_is_norm_times_embedding():
