@@ -81,6 +81,16 @@ int sapo_weights_create(const sapo_model_config* cfg, const void* const* tensors
                         void* stream, sapo_weights** out);
 void sapo_weights_destroy(sapo_weights* w);
 
+/*
+ * Optional biases on the query / key / value projections of one layer (the decoder family the
+ * paper's experiments ran, Sec. 4, carries them; sapo_weights_create builds a model without):
+ * q = W_q x + bq, k = W_k x + bk, v = W_v x + bv, before the rotary embedding.
+ *   bq dev fp32 [Hq*hd], bk, bv dev fp32 [Hkv*hd]; copied (complete once `stream` is synchronised).
+ * May be called again to replace them.  Not to be called while a call using `w` is in flight.
+ */
+int sapo_weights_set_qkv_bias(sapo_weights* w, int layer, const float* bq, const float* bk, const float* bv,
+                              void* stream);
+
 /* Workspace sizes in bytes (0 on invalid arguments). */
 size_t sapo_rollout_workspace_bytes(const sapo_weights* w, int P, int Lp, int G, int max_new);
 size_t sapo_score_workspace_bytes(const sapo_weights* w, int S, int T);

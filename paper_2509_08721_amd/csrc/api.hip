@@ -97,6 +97,7 @@ struct LayerWeights {
   float* attn_norm;
   float* ffn_norm;
   void* wqkv;   // [q + 2 kv, d]
+  float* bqkv = nullptr;   // [q + 2 kv] optional biases of the three projections (fp32)
   void* wo;     // [d, q]
   void* wgu;    // [2 F, d]: generic: gate rows then up rows; MFMA: 32-row gate/up tiles interleaved
   void* wdown;  // [d, F]
@@ -171,6 +172,26 @@ extern "C" void sapo_weights_destroy(sapo_weights* w) {
 }
 
 extern "C" int sapo_weights_uses_mfma(const sapo_weights* w) { return (w && w->mfma) ? 1 : 0; }
+
+static int dev_alloc(sapo_weights* w, size_t bytes, void** out);
+static void drop_decode_graph(const sapo_weights* w);
+
+extern "C" int sapo_weights_set_qkv_bias(sapo_weights* w, int layer, const float* bq, const float* bk, const float* bv,
+                                         void* stream) {
+  if (!w) return fail(SAPO_EINVAL, "weights is NULL");
+  if (layer < 0 || layer >= w->cfg.n_layers) return fail(SAPO_EINVAL, "layer %d out of range", layer);
+  if (!bq || !bk || !bv) return fail(SAPO_EINVAL, "NULL buffer");
+  const size_t q = (size_t)w->cfg.n_q_heads * w->cfg.head_dim, kv = (size_t)w->cfg.n_kv_heads * w->cfg.head_dim;
+  LayerWeights& lw = w->layers[layer];
+  int rc;
+  if (!lw.bqkv && (rc = dev_alloc(w, (q + 2 * kv) * sizeof(float), (void**)&lw.bqkv))) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  HIP_CK(hipMemcpyAsync(lw.bqkv, bq, q * sizeof(float), hipMemcpyDeviceToDevice, st));
+  HIP_CK(hipMemcpyAsync(lw.bqkv + q, bk, kv * sizeof(float), hipMemcpyDeviceToDevice, st));
+  HIP_CK(hipMemcpyAsync(lw.bqkv + q + kv, bv, kv * sizeof(float), hipMemcpyDeviceToDevice, st));
+  drop_decode_graph(w);   // a captured decode step holds the old kernel arguments
+  return SAPO_OK;
+}
 
 static int dev_alloc(sapo_weights* w, size_t bytes, void** out) {
   void* p = nullptr;
@@ -380,6 +401,7 @@ static int run_layers_generic(const sapo_weights* w, const FwdBufs& b, int M, Ro
     const KVCache kvc = layer_cache(w, cb, l);
     HIP_CK(g_rmsnorm(dt, b.h, lw.attn_norm, c.rms_eps, b.a, M, d, nullptr, st));
     HIP_CK(g_gemm(dt, b.a, lw.wqkv, b.qkv, M, q + 2 * kv, d, q + 2 * kv, EPI_STORE_F32, st));
+    if (lw.bqkv) HIP_CK(g_add_row_bias(b.qkv, lw.bqkv, M, q + 2 * kv, st));
     HIP_CK(g_rope_append(dt, b.qkv, w->rope, rm, kvc, b.q, M, c.n_q_heads, st));
     HIP_CK(g_attention(dt, b.q, rm, kvc, b.attn, M, c.n_q_heads, max_ctx, st));
     HIP_CK(g_gemm(dt, b.attn, lw.wo, b.h, M, d, q, d, EPI_ADD_F32, st));
@@ -405,6 +427,7 @@ static int run_layers_big(const sapo_weights* w, const FwdBufs& b, int M, RowMap
     const int parts = d / 128;
     const bool fold = parts <= 16;
     BigEpi qkv_ep{BIG_STORE_F32, b.qkv, q + 2 * kv, nullptr};
+    qkv_ep.bias = lw.bqkv;
     if (l == 0 || !fold) {
       HIP_CK(m_rmsnorm_x32(b.h, lw.attn_norm, c.rms_eps, b.a, M, d, nullptr, st));
     } else {
@@ -466,7 +489,7 @@ static int run_layers_decode16(const sapo_weights* w, const FwdBufs& b, const De
     // QKV projection of the attention-normed residual
     a.Wp = (const uint4*)lw.wqkv16; a.Xp = (const uint4*)db.xa; a.N = nqkv; a.K = d;
     a.ssq_in = db.ssq_a; a.ssq_parts = (l == 0) ? 1 : d / 16;
-    a.out_f32 = b.qkv; a.ldc = nqkv;
+    a.out_f32 = b.qkv; a.ldc = nqkv; a.bias = lw.bqkv;
     HIP_CK(d_gemm_skinny(a, SKM_STORE, st));
     HIP_CK(d_decode_attention(b.qkv, w->rope, rm, kvc, b.attn, S, c.n_q_heads, st));
     // output projection + residual; emits the FFN norm's operand

@@ -224,6 +224,8 @@ hipError_t g_sample_rows(const float* logits, int n_prompt_rows, int G, int V, S
 hipError_t g_score_rows(const float* logits, int n_rows, int row_offset, int V, const int* row_seq_pos,
                         const int* n_rows_dev, const int32_t* tokens, int T, float* out_logprobs, hipStream_t st);
 hipError_t g_advantages(const float* rewards, int S, int G, float* out, hipStream_t st);
+// x[m][n] += bias[n]
+hipError_t g_add_row_bias(float* x, const float* bias, int M, int N, hipStream_t st);
 // out[s] = len[s] if the sequence has stopped (len > 0), else max_new
 hipError_t g_lengths_out(const int* len, int S, int max_new, int32_t* out, hipStream_t st);
 hipError_t g_assemble(const int32_t* local_tokens, const float* local_rewards, int n_local_pool, const int32_t* ext_tokens,
@@ -264,6 +266,7 @@ struct BigEpi {
   // RMSNorm folded around the GEMM (a row's scale commutes with the contraction).  Consumer side: the
   // token operand holds x * gain without the row scale; the accumulators are multiplied by
   // rsqrt(sum of the row's ssq parts / norm_dim + eps) before the epilogue proper.
+  const float* bias = nullptr;     // STORE_F32, optional: [N] added after the row scale
   const float* ssq_in = nullptr;   // [M, ssq_parts rounded up to a multiple of 4]; at most 16 parts
   int ssq_parts = 0;
   float norm_dim = 0.f, eps = 0.f;
@@ -308,6 +311,7 @@ struct SkinnyArgs {
   float eps;
   float* out_f32;         // STORE: [n_rows, ldc]
   int ldc;
+  const float* bias;      // STORE, optional: [N] added after the scale
   float* h;               // RESID: residual stream [n_rows, N], updated in place
   const float* gain_next; // RESID: gain of the norm that reads the updated residual [N]
   uint4* xp_out;          // RESID: bf16(h * gain_next), X16 order over K' = N; SWIGLU: act, X16 order over K' = N / 2

@@ -235,7 +235,12 @@ __global__ void __launch_bounds__(512) k_skinny16(SkinnyArgs a, int n_units) {
         const int f0 = (tile0 + c0 + t) * 16 + (l >> 4) * 4;
         if (tok < a.n_rows) {
           const float sc = ssq_scale(s_part, tl, a.norm_dim, a.eps);
-          *(float4*)(a.out_f32 + (size_t)tok * a.ldc + f0) = make_float4(s.x * sc, s.y * sc, s.z * sc, s.w * sc);
+          float4 o = make_float4(s.x * sc, s.y * sc, s.z * sc, s.w * sc);
+          if (a.bias) {
+            const float4 bb = *(const float4*)(a.bias + f0);
+            o.x += bb.x; o.y += bb.y; o.z += bb.z; o.w += bb.w;
+          }
+          *(float4*)(a.out_f32 + (size_t)tok * a.ldc + f0) = o;
         }
       }
     } else {

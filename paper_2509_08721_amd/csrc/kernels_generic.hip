@@ -409,6 +409,14 @@ __global__ void k_advantages(const float* __restrict__ r, int n_groups, int G, f
   const double sd = sqrt(var / G);
   for (int i = 0; i < G; ++i) out[(size_t)g * G + i] = (float)(((double)rg[i] - mu) / (sd + 1e-6));
 }
+__global__ void k_add_row_bias(float* __restrict__ x, const float* __restrict__ bias, size_t total, int N) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < total) x[i] += bias[i % N];
+}
+hipError_t g_add_row_bias(float* x, const float* bias, int M, int N, hipStream_t st) {
+  const size_t total = (size_t)M * N;
+  return launch(KID_MISC, k_add_row_bias, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, x, bias, total, N);
+}
 __global__ void k_lengths_out(const int* __restrict__ len, int S, int max_new, int32_t* __restrict__ out) {
   const int s = blockIdx.x * blockDim.x + threadIdx.x;
   if (s < S) out[s] = len[s] > 0 ? len[s] : max_new;

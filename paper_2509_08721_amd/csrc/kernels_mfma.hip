@@ -252,6 +252,9 @@ __global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ X
           if (ep.mode == BIG_ADD_F32) {
             const float4 o = *p;
             v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+          } else if (ep.bias) {
+            const float4 bb = *(const float4*)(ep.bias + f0 + 8 * r);
+            v.x += bb.x; v.y += bb.y; v.z += bb.z; v.w += bb.w;
           }
           *p = v;
           if (ep.gain_next) {

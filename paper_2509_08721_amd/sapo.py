@@ -51,6 +51,8 @@ def load_library() -> C.CDLL:
     lib.sapo_weights_create.restype = i32
     lib.sapo_weights_destroy.argtypes = [vp]
     lib.sapo_weights_destroy.restype = None
+    lib.sapo_weights_set_qkv_bias.argtypes = [vp, i32, vp, vp, vp, vp]
+    lib.sapo_weights_set_qkv_bias.restype = i32
     lib.sapo_weights_uses_mfma.argtypes = [vp]
     lib.sapo_weights_uses_mfma.restype = i32
     lib.sapo_rollout_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
@@ -91,7 +93,7 @@ def load_library() -> C.CDLL:
     return lib
 
 
-EXPORTED = ["sapo_weights_create", "sapo_weights_destroy", "sapo_weights_uses_mfma",
+EXPORTED = ["sapo_weights_create", "sapo_weights_destroy", "sapo_weights_uses_mfma", "sapo_weights_set_qkv_bias",
             "sapo_rollout_workspace_bytes", "sapo_score_workspace_bytes",
             "sapo_debug_logits_workspace_bytes", "sapo_rollout_generate", "sapo_rollout_generate_stop",
             "sapo_score_logprobs",
@@ -173,8 +175,22 @@ def sapo_weights_create(shape, weights: dict, stream=None) -> Weights:
     ptrs = (C.c_void_p * len(dev))(*[None if t is None else t.data_ptr() for t in dev])
     out = C.c_void_p()
     _check(lib.sapo_weights_create(C.byref(cfg), ptrs, len(dev), _stream_ptr(stream), C.byref(out)))
+    wts = Weights(out.value, cfg)
+    for l, lw in enumerate(weights["layers"]):
+        if "bq" in lw:
+            sapo_weights_set_qkv_bias(wts, l, _to_device(lw["bq"]), _to_device(lw["bk"]), _to_device(lw["bv"]), stream)
     torch.cuda.synchronize()          # the originals in `dev` may be freed after this
-    return Weights(out.value, cfg)
+    return wts
+
+
+def sapo_weights_set_qkv_bias(w: Weights, layer: int, bq, bk, bv, stream=None):
+    """bq float32 [Hq*hd], bk / bv float32 [Hkv*hd] device tensors."""
+    torch = _torch()
+    for t in (bq, bk, bv):
+        assert t.dtype == torch.float32 and t.is_cuda and t.is_contiguous()
+    _check(load_library().sapo_weights_set_qkv_bias(w.handle, layer, bq.data_ptr(), bk.data_ptr(), bv.data_ptr(),
+                                                    _stream_ptr(stream)))
+    torch.cuda.synchronize()
 
 
 def sapo_weights_destroy(w: Weights):
