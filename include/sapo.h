@@ -130,6 +130,23 @@ int sapo_rollout_generate_stop(const sapo_weights* w, const int32_t* prompts, in
                                void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Rollout generation for prompts of different lengths (questions are presented directly as prompts,
+ * Sec. 3.1; real question sets are not of one length), with an optional stop token.
+ *   prompts      dev int32 [P, Lp_max]   prompt p occupies the first prompt_lens[p] entries of its row;
+ *                                        the rest of the row is padding (any vocabulary ids)
+ *   prompt_lens  HOST int32 [P]          1 <= prompt_lens[p] <= Lp_max
+ *   stop_token   a vocabulary id, or -1 for none (then out_lengths may be NULL)
+ * Sequence s = p * G + g continues prompt p from position prompt_lens[p]; everything else is as in
+ * sapo_rollout_generate / sapo_rollout_generate_stop: the result for prompt p equals what a call with
+ * that prompt alone at its own length returns for the same sequence indices.  Workspace:
+ * sapo_rollout_workspace_bytes(w, P, Lp_max, G, max_new).  Requires Lp_max + max_new <= cfg.max_seq.
+ */
+int sapo_rollout_generate_ragged(const sapo_weights* w, const int32_t* prompts, const int32_t* prompt_lens,
+                                 int P, int Lp_max, int G, int max_new, float temperature, uint64_t seed,
+                                 int32_t stop_token, int32_t* out_tokens, float* out_logprobs,
+                                 int32_t* out_lengths, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Scoring pass (Sec. 3.2: token-level values of any rollout under the node's own policy;
  * Sec. 4.2: GRPO's group-relative advantage).
  *   tokens           dev int32 [S, T]   prompt + completion of every training-set sequence

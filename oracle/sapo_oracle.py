@@ -299,10 +299,10 @@ def sample_token(z: np.ndarray, temperature: float, seed: int, seq: int, step: i
 # The two calls of the path
 # --------------------------------------------------------------------------- #
 def rollout_generate(m: Model, prompts: np.ndarray, group: int, max_new: int, temperature: float,
-                     seed: int, return_logits: bool = False):
+                     seed: int, return_logits: bool = False, first_seq: int = 0):
     """Generate `group` sampled completions of max_new tokens for each prompt.
 
-    prompts int[P, Lp].  Sequence s = p * group + g.  Returns
+    prompts int[P, Lp].  Sequence s = first_seq + p * group + g (the index that keys the noise).  Returns
     (tokens int32 [S, max_new], logprobs float32 [S, max_new]) with
     logprobs[s, t] = log softmax(z)[token] at temperature 1 (the policy's own
     log-prob, the quantity the scoring pass reproduces).  Incremental decoding
@@ -324,7 +324,7 @@ def rollout_generate(m: Model, prompts: np.ndarray, group: int, max_new: int, te
             x = x_last
             for t in range(max_new):
                 z = logits_from_hidden(m, x)[0]
-                tok = sample_token(z, temperature, seed, s, t)
+                tok = sample_token(z, temperature, seed, first_seq + s, t)
                 out_tok[s, t] = tok
                 out_lp[s, t] = log_softmax(z)[tok]
                 if return_logits:
@@ -334,6 +334,18 @@ def rollout_generate(m: Model, prompts: np.ndarray, group: int, max_new: int, te
     if return_logits:
         return out_tok, out_lp, all_logits
     return out_tok, out_lp
+
+
+def rollout_generate_ragged(m: Model, prompts: Sequence[np.ndarray], group: int, max_new: int, temperature: float,
+                            seed: int):
+    """Prompts of different lengths: prompt p (a 1-D array of its own length) is answered exactly as
+    if it were alone, by the sequences p * group .. p * group + group - 1."""
+    toks, lps = [], []
+    for p, prompt in enumerate(prompts):
+        t, l = rollout_generate(m, np.asarray(prompt)[None, :], group, max_new, temperature, seed, first_seq=p * group)
+        toks.append(t)
+        lps.append(l)
+    return np.concatenate(toks, axis=0), np.concatenate(lps, axis=0)
 
 
 def rollout_generate_stop(m: Model, prompts: np.ndarray, group: int, max_new: int, temperature: float,

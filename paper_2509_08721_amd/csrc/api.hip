@@ -125,6 +125,7 @@ struct sapo_weights {
     bool valid = false;
     const void* out_tokens = nullptr; const void* out_logprobs = nullptr; const void* workspace = nullptr;
     int P = 0, Lp = 0, G = 0, N = 0;
+    bool ragged = false;
     hipGraph_t graph = nullptr;
     hipGraphExec_t exec = nullptr;
   };
@@ -533,6 +534,8 @@ struct RolloutPlan {
   FwdBufs fwd;
   int* step;        // device step counter
   int* stop;        // device: {stop token or -1, sequences ended, length of each sequence (0 = running)}
+  int* lens;        // device [P]: prompt lengths (calls with prompts of different lengths)
+  int own_pages;    // pages of its own per sequence
   int* last_rows;   // [P]
   float* h_last;    // [S, d] residual of each sequence's last prompt position
   void* x_last;     // [max(P, S), d] final-norm output (T)
@@ -549,12 +552,15 @@ static void plan_rollout(const sapo_weights* w, int P, int Lp, int G, int N, cha
   pl.P = P; pl.Lp = Lp; pl.G = G; pl.N = N; pl.S = P * G;
   pl.full_prompt_pages = Lp / kPageTokens;
   pl.pages_per_seq = (Lp + N + kPageTokens - 1) / kPageTokens;
-  const int own = pl.pages_per_seq - pl.full_prompt_pages;
+  // one page more than equal-length prompts need: a shorter prompt's partly filled last page is the sequence's own
+  const int own = pl.pages_per_seq - pl.full_prompt_pages + 1;
+  pl.own_pages = own;
   pl.n_pages = (size_t)P * pl.full_prompt_pages + (size_t)pl.S * own;
   pl.M_max = (size_t)P * Lp > (size_t)pl.S ? (size_t)P * Lp : (size_t)pl.S;
   Arena A{base, 0};
   pl.step = A.take<int>(64);
   pl.stop = A.take<int>((size_t)pl.S + 2);
+  pl.lens = A.take<int>(P);
   pl.last_rows = A.take<int>(P);
   carve_cache(A, w, pl.S, pl.pages_per_seq, pl.n_pages, pl.cache);
   carve_fwd(A, w, pl.M_max, pl.fwd);
@@ -615,9 +621,9 @@ static int sample_step(const sapo_weights* w, const RolloutPlan& pl, const float
   return SAPO_OK;
 }
 
-static int rollout_impl(const sapo_weights* w, const int32_t* prompts, int P, int Lp, int G, int max_new,
-                        float temperature, uint64_t seed, int stop_token, int32_t* out_tokens, float* out_logprobs,
-                        int32_t* out_lengths, void* workspace, size_t workspace_bytes, void* stream) {
+static int rollout_impl(const sapo_weights* w, const int32_t* prompts, const int32_t* lens_host, int P, int Lp, int G,
+                        int max_new, float temperature, uint64_t seed, int stop_token, int32_t* out_tokens,
+                        float* out_logprobs, int32_t* out_lengths, void* workspace, size_t workspace_bytes, void* stream) {
   int rc = check_rollout_args(w, P, Lp, G, max_new);
   if (rc) return rc;
   if (!prompts || !out_tokens || !out_logprobs || !workspace) return fail(SAPO_EINVAL, "NULL buffer");
@@ -674,27 +680,43 @@ static int rollout_impl(const sapo_weights* w, const int32_t* prompts, int P, in
     HIP_CK(g_fill_i32(pl.step + 2, (int)sp.seed_hi, 1, st));
     HIP_CK(g_fill_i32(pl.step + 3, tbits, 1, st));
   }
-  HIP_CK(g_page_table(pl.cache.page_table, S, pl.pages_per_seq, G, pl.full_prompt_pages, P, st));
+  const bool ragged = lens_host != nullptr;
+  if (ragged) {
+    for (int p = 0; p < P; ++p)
+      if (lens_host[p] < 1 || lens_host[p] > Lp)
+        return fail(SAPO_EINVAL, "prompt %d has length %d, outside 1 .. %d", p, lens_host[p], Lp);
+    HIP_CK(hipMemcpyAsync(pl.lens, lens_host, (size_t)P * sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_CK(g_page_table_ragged(pl.cache.page_table, S, pl.pages_per_seq, G, pl.full_prompt_pages, pl.own_pages, P, pl.lens,
+                               st));
+  } else {
+    HIP_CK(g_page_table(pl.cache.page_table, S, pl.pages_per_seq, G, pl.full_prompt_pages, P, st));
+  }
   if ((rc = clear_cache(pl.cache, c.n_layers, st))) return rc;
 
   // prefill: the P unique prompts, written through the page table of each prompt's first sibling;
   // step 0 samples G siblings from each prompt's last-position logits
   {
     const int M = P * Lp;
-    RowMap rm{0, Lp, G, 0, nullptr};
+    RowMap rm{0, Lp, G, 0, nullptr, ragged ? pl.lens : nullptr, G};
     HIP_CK(g_embed(dt, prompts, 1, nullptr, w->embed, pl.fwd.h, M, d, st));
     if ((rc = run_layers(w, pl.fwd, M, rm, pl.cache, Lp, st))) return rc;
-    if (Lp % kPageTokens != 0)
+    if (ragged) {
       for (int l = 0; l < c.n_layers; ++l)
-        HIP_CK(g_copy_partial_page(dt, layer_cache(w, pl.cache, l), P, G, pl.full_prompt_pages, st));
-    HIP_CK(g_gather_last_rows(pl.fwd.h, pl.h_last, S, G, Lp, d, st));
+        HIP_CK(g_copy_partial_page_ragged(dt, layer_cache(w, pl.cache, l), P, G, pl.lens, st));
+      HIP_CK(g_gather_last_rows_ragged(pl.fwd.h, pl.h_last, S, G, Lp, pl.lens, d, st));
+    } else {
+      if (Lp % kPageTokens != 0)
+        for (int l = 0; l < c.n_layers; ++l)
+          HIP_CK(g_copy_partial_page(dt, layer_cache(w, pl.cache, l), P, G, pl.full_prompt_pages, st));
+      HIP_CK(g_gather_last_rows(pl.fwd.h, pl.h_last, S, G, Lp, d, st));
+    }
     if (pl.fused_lm) HIP_CK(d_pack_rows_x16(pl.h_last, w->final_norm, S, d, pl.dec.xa, pl.dec.ssq_a, st));
     if ((rc = sample_step(w, pl, pl.h_last, 1, sp, st))) return rc;
   }
   // decode: token t-1 of every sequence goes through the layers, token t is sampled.  Everything
   // that changes from step to step is read from device memory (*step), so one step is captured
   // into a graph and replayed.
-  RowMap rm{1, 0, 1, Lp, pl.step};
+  RowMap rm{1, 0, 1, Lp, pl.step, ragged ? pl.lens : nullptr, G};
   auto enqueue_step = [&]() -> int {
     int rc2;
     HIP_CK(g_incr(pl.step, st));
@@ -724,7 +746,7 @@ static int rollout_impl(const sapo_weights* w, const int32_t* prompts, int P, in
   }
   sapo_weights::DecodeGraph& dg = w->dgraph;
   if (!(dg.valid && dg.out_tokens == out_tokens && dg.out_logprobs == out_logprobs && dg.workspace == workspace &&
-        dg.P == P && dg.Lp == Lp && dg.G == G && dg.N == max_new)) {
+        dg.P == P && dg.Lp == Lp && dg.G == G && dg.N == max_new && dg.ragged == ragged)) {
     drop_decode_graph(w);
     HIP_CK(hipStreamBeginCapture(st, hipStreamCaptureModeRelaxed));
     rc = enqueue_step();
@@ -743,7 +765,7 @@ static int rollout_impl(const sapo_weights* w, const int32_t* prompts, int P, in
     }
     dg.valid = true;
     dg.out_tokens = out_tokens; dg.out_logprobs = out_logprobs; dg.workspace = workspace;
-    dg.P = P; dg.Lp = Lp; dg.G = G; dg.N = max_new;
+    dg.P = P; dg.Lp = Lp; dg.G = G; dg.N = max_new; dg.ragged = ragged;
     dg.graph = graph; dg.exec = exec;
   }
   for (int t = 1; t < max_new; ++t) {
@@ -760,8 +782,8 @@ static int rollout_impl(const sapo_weights* w, const int32_t* prompts, int P, in
 extern "C" int sapo_rollout_generate(const sapo_weights* w, const int32_t* prompts, int P, int Lp, int G, int max_new,
                                      float temperature, uint64_t seed, int32_t* out_tokens, float* out_logprobs,
                                      void* workspace, size_t workspace_bytes, void* stream) {
-  return rollout_impl(w, prompts, P, Lp, G, max_new, temperature, seed, -1, out_tokens, out_logprobs, nullptr, workspace,
-                      workspace_bytes, stream);
+  return rollout_impl(w, prompts, nullptr, P, Lp, G, max_new, temperature, seed, -1, out_tokens, out_logprobs, nullptr,
+                      workspace, workspace_bytes, stream);
 }
 
 extern "C" int sapo_rollout_generate_stop(const sapo_weights* w, const int32_t* prompts, int P, int Lp, int G, int max_new,
@@ -770,8 +792,18 @@ extern "C" int sapo_rollout_generate_stop(const sapo_weights* w, const int32_t* 
                                           size_t workspace_bytes, void* stream) {
   if (stop_token < 0) return fail(SAPO_EINVAL, "stop token must be a vocabulary id");
   if (!out_lengths) return fail(SAPO_EINVAL, "NULL buffer");
-  return rollout_impl(w, prompts, P, Lp, G, max_new, temperature, seed, stop_token, out_tokens, out_logprobs, out_lengths,
-                      workspace, workspace_bytes, stream);
+  return rollout_impl(w, prompts, nullptr, P, Lp, G, max_new, temperature, seed, stop_token, out_tokens, out_logprobs,
+                      out_lengths, workspace, workspace_bytes, stream);
+}
+
+extern "C" int sapo_rollout_generate_ragged(const sapo_weights* w, const int32_t* prompts, const int32_t* prompt_lens,
+                                            int P, int Lp_max, int G, int max_new, float temperature, uint64_t seed,
+                                            int32_t stop_token, int32_t* out_tokens, float* out_logprobs,
+                                            int32_t* out_lengths, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!prompt_lens) return fail(SAPO_EINVAL, "NULL buffer");
+  if (stop_token >= 0 && !out_lengths) return fail(SAPO_EINVAL, "NULL buffer");
+  return rollout_impl(w, prompts, prompt_lens, P, Lp_max, G, max_new, temperature, seed, stop_token < 0 ? -1 : stop_token,
+                      out_tokens, out_logprobs, out_lengths, workspace, workspace_bytes, stream);
 }
 
 // ---------------------------------------------------------------------------------------

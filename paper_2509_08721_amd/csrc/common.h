@@ -24,6 +24,9 @@ constexpr int kWave = 64;
 //   decode mode: row m is sequence m at position Lp + *step - 1 (the token sampled at the
 //                previous step); *step lives in device memory so that one captured graph
 //                can be replayed for every step.
+// Prompts of different lengths (optional): lens[p] is the length of prompt p = sequence / G.  Block rows
+// at or past their prompt's length are padding: they run through the layers but leave no K/V behind;
+// decode rows sit at lens[p] + *step - 1.
 // ---------------------------------------------------------------------------------------
 struct RowMap {
   int decode;       // 0 block, 1 decode
@@ -31,15 +34,19 @@ struct RowMap {
   int seq_stride;   // block mode: cache-sequence stride
   int Lp;           // decode mode: prompt length
   const int* step;  // decode mode: device pointer to the current step index (>= 1)
+  const int* lens;  // optional, device: prompt lengths
+  int G;            // sequences per prompt (with lens)
   __device__ __forceinline__ void get(int m, int& seq, int& pos) const {
     if (decode) {
       seq = m;
-      pos = Lp + *step - 1;
+      pos = (lens ? lens[m / G] : Lp) + *step - 1;
     } else {
       seq = (m / T) * seq_stride;
       pos = m % T;
     }
   }
+  // does row m leave K/V in the cache?
+  __device__ __forceinline__ bool keeps_kv(int m) const { return decode || !lens || (m % T) < lens[m / T]; }
 };
 
 // Paged KV cache of one layer.  K page: [Hkv][16 tokens][hd]; V page: [Hkv][hd][16 tokens]
@@ -239,6 +246,11 @@ hipError_t g_surrogate_loss(const float* logp_new, const float* logp_old, const 
 hipError_t g_page_table(int* pt, int n_seq, int pages_per_seq, int G, int full_prompt_pages, int n_prompts,
                         hipStream_t st);
 hipError_t g_copy_partial_page(int dtype, KVCache kv, int n_prompts, int G, int page_idx, hipStream_t st);
+// the same with one prompt length per prompt (device): page lens[p] / 16 of prompt p, if partly filled
+hipError_t g_copy_partial_page_ragged(int dtype, KVCache kv, int n_prompts, int G, const int* lens, hipStream_t st);
+// page table for prompts of different lengths: fp_max shared page slots per prompt, `own` pages per sequence
+hipError_t g_page_table_ragged(int* pt, int n_seq, int pages_per_seq, int G, int fp_max, int own, int n_prompts,
+                               const int* lens, hipStream_t st);
 hipError_t g_fill_i32(int* p, int v, size_t n, hipStream_t st);
 hipError_t g_fill_f32(float* p, float v, size_t n, hipStream_t st);
 hipError_t g_incr(int* p, hipStream_t st);
@@ -339,5 +351,8 @@ hipError_t d_lmhead_merge_embed(const float* partials, int n_parts, int row_stri
 hipError_t d_decode_attention(const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* out_x16, int S,
                               int n_q_heads, hipStream_t st);
 hipError_t g_gather_last_rows(const float* h, float* out, int S, int G, int Lp, int d, hipStream_t st);
+// with per-prompt lengths (device): row p * Lp + lens[p] - 1
+hipError_t g_gather_last_rows_ragged(const float* h, float* out, int S, int G, int Lp, const int* lens, int d,
+                                     hipStream_t st);
 
 }  // namespace sapo

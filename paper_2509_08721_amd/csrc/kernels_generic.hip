@@ -44,6 +44,21 @@ __global__ void k_page_table(int* pt, int n_seq, int pages_per_seq, int G, int f
   int own = pages_per_seq - fp;
   pt[i] = (j < fp) ? (s / G) * fp + j : n_prompts * fp + s * own + (j - fp);
 }
+__global__ void k_page_table_ragged(int* pt, int n_seq, int pages_per_seq, int G, int fp_max, int own, int n_prompts,
+                                    const int* __restrict__ lens) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_seq * pages_per_seq) return;
+  int s = i / pages_per_seq, j = i % pages_per_seq;
+  int fp = lens[s / G] / kPageTokens;
+  // entries past the pages the sequence can reach point at its last own page (only padding rows read them)
+  pt[i] = (j < fp) ? (s / G) * fp_max + j : n_prompts * fp_max + s * own + min(j - fp, own - 1);
+}
+hipError_t g_page_table_ragged(int* pt, int n_seq, int pages_per_seq, int G, int fp_max, int own, int n_prompts,
+                               const int* lens, hipStream_t st) {
+  int n = n_seq * pages_per_seq;
+  return launch(KID_MISC, k_page_table_ragged, dim3((n + 255) / 256), dim3(256), 0, st, pt, n_seq, pages_per_seq, G, fp_max,
+                own, n_prompts, lens);
+}
 hipError_t g_page_table(int* pt, int n_seq, int pages_per_seq, int G, int fp, int n_prompts, hipStream_t st) {
   int n = n_seq * pages_per_seq;
   return launch(KID_MISC, k_page_table, dim3((n + 255) / 256), dim3(256), 0, st, pt, n_seq, pages_per_seq, G, fp, n_prompts);
@@ -52,8 +67,12 @@ hipError_t g_page_table(int* pt, int n_seq, int pages_per_seq, int G, int fp, in
 // Copy the (partially filled) page `page_idx` of each prompt's first sibling to the other
 // siblings, both K and V.
 template <typename T>
-__global__ void k_copy_partial_page(KVCache kv, int G, int page_idx) {
+__global__ void k_copy_partial_page(KVCache kv, int G, int page_idx, const int* __restrict__ lens) {
   const int p = blockIdx.x, g = blockIdx.y + 1;
+  if (lens) {
+    if (lens[p] % kPageTokens == 0) return;
+    page_idx = lens[p] / kPageTokens;
+  }
   const int src = kv.page_table[(size_t)(p * G) * kv.pages_per_seq + page_idx];
   const int dst = kv.page_table[(size_t)(p * G + g) * kv.pages_per_seq + page_idx];
   const size_t n = (size_t)kv.n_kv_heads * kPageTokens * kv.head_dim;
@@ -66,7 +85,14 @@ __global__ void k_copy_partial_page(KVCache kv, int G, int page_idx) {
 hipError_t g_copy_partial_page(int dtype, KVCache kv, int n_prompts, int G, int page_idx, hipStream_t st) {
   if (G <= 1) return hipSuccess;
   hipError_t e = hipSuccess;
-  SAPO_DISPATCH_T(dtype, e = launch(KID_MISC, k_copy_partial_page<T>, dim3(n_prompts, G - 1), dim3(256), 0, st, kv, G, page_idx));
+  SAPO_DISPATCH_T(dtype, e = launch(KID_MISC, k_copy_partial_page<T>, dim3(n_prompts, G - 1), dim3(256), 0, st, kv, G, page_idx,
+                                    (const int*)nullptr));
+  return e;
+}
+hipError_t g_copy_partial_page_ragged(int dtype, KVCache kv, int n_prompts, int G, const int* lens, hipStream_t st) {
+  if (G <= 1) return hipSuccess;
+  hipError_t e = hipSuccess;
+  SAPO_DISPATCH_T(dtype, e = launch(KID_MISC, k_copy_partial_page<T>, dim3(n_prompts, G - 1), dim3(256), 0, st, kv, G, 0, lens));
   return e;
 }
 
@@ -190,6 +216,7 @@ __global__ void k_rope_append(const float* __restrict__ qkv, const float2* __res
   const int n_heads = n_q_heads + 2 * hkv;
   int seq, pos;
   rm.get(m, seq, pos);
+  const bool keep = rm.keeps_kv(m);
   const int page = kv.page_table[(size_t)seq * kv.pages_per_seq + pos / kPageTokens];
   const int slot = pos % kPageTokens;
   const float* row = qkv + (size_t)m * n_heads * hd;
@@ -202,13 +229,13 @@ __global__ void k_rope_append(const float* __restrict__ qkv, const float2* __res
       if (head < n_q_heads) {
         q_out[((size_t)m * n_q_heads + head) * hd + i] = from_f32<T>(r1);
         q_out[((size_t)m * n_q_heads + head) * hd + i + half] = from_f32<T>(r2);
-      } else {
+      } else if (keep) {
         const int kh = head - n_q_heads;
         T* kp = (T*)kv.k + (((size_t)page * hkv + kh) * kPageTokens + slot) * hd;
         kp[i] = from_f32<T>(r1);
         kp[i + half] = from_f32<T>(r2);
       }
-    } else {
+    } else if (keep) {
       const int vh = head - n_q_heads - hkv;
       T* vp = (T*)kv.v + ((size_t)page * hkv + vh) * hd * kPageTokens;
       vp[(size_t)i * kPageTokens + slot] = from_f32<T>(x1);
@@ -656,13 +683,18 @@ hipError_t g_last_rows(int* rows, int P, int Lp, hipStream_t st) {
 }
 
 // out[s, :] = h[(s / G) * Lp + Lp - 1, :]: the last prompt position's residual, once per sibling.
-__global__ void k_gather_last_rows(const float* __restrict__ h, float* __restrict__ out, int G, int Lp, int d) {
+__global__ void k_gather_last_rows(const float* __restrict__ h, float* __restrict__ out, int G, int Lp, int d,
+                                   const int* __restrict__ lens) {
   const int s = blockIdx.x;
-  const float* src = h + ((size_t)(s / G) * Lp + Lp - 1) * d;
+  const float* src = h + ((size_t)(s / G) * Lp + (lens ? lens[s / G] : Lp) - 1) * d;
   for (int i = threadIdx.x; i < d; i += blockDim.x) out[(size_t)s * d + i] = src[i];
 }
 hipError_t g_gather_last_rows(const float* h, float* out, int S, int G, int Lp, int d, hipStream_t st) {
-  return launch(KID_MISC, k_gather_last_rows, dim3(S), dim3(256), 0, st, h, out, G, Lp, d);
+  return launch(KID_MISC, k_gather_last_rows, dim3(S), dim3(256), 0, st, h, out, G, Lp, d, (const int*)nullptr);
+}
+hipError_t g_gather_last_rows_ragged(const float* h, float* out, int S, int G, int Lp, const int* lens, int d,
+                                     hipStream_t st) {
+  return launch(KID_MISC, k_gather_last_rows, dim3(S), dim3(256), 0, st, h, out, G, Lp, d, lens);
 }
 
 __global__ void k_gumbel(uint32_t seed_lo, uint32_t seed_hi, uint32_t seq, uint32_t step, uint32_t v0, int n, float* out) {

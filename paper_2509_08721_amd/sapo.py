@@ -65,6 +65,8 @@ def load_library() -> C.CDLL:
     lib.sapo_rollout_generate.restype = i32
     lib.sapo_rollout_generate_stop.argtypes = [vp, vp, i32, i32, i32, i32, f32, u64, i32, vp, vp, vp, vp, sz, vp]
     lib.sapo_rollout_generate_stop.restype = i32
+    lib.sapo_rollout_generate_ragged.argtypes = [vp, vp, vp, i32, i32, i32, i32, f32, u64, i32, vp, vp, vp, vp, sz, vp]
+    lib.sapo_rollout_generate_ragged.restype = i32
     lib.sapo_score_logprobs.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
     lib.sapo_score_logprobs.restype = i32
     lib.sapo_assemble_workspace_bytes.argtypes = [i32, i32]
@@ -95,7 +97,7 @@ def load_library() -> C.CDLL:
 
 EXPORTED = ["sapo_weights_create", "sapo_weights_destroy", "sapo_weights_uses_mfma", "sapo_weights_set_qkv_bias",
             "sapo_rollout_workspace_bytes", "sapo_score_workspace_bytes",
-            "sapo_debug_logits_workspace_bytes", "sapo_rollout_generate", "sapo_rollout_generate_stop",
+            "sapo_debug_logits_workspace_bytes", "sapo_rollout_generate", "sapo_rollout_generate_stop", "sapo_rollout_generate_ragged",
             "sapo_score_logprobs",
             "sapo_surrogate_workspace_bytes", "sapo_clipped_surrogate",
             "sapo_assemble_workspace_bytes", "sapo_assemble_training_set",
@@ -253,6 +255,29 @@ def sapo_rollout_generate_stop(w: Weights, prompts, G: int, max_new: int, temper
     _check(lib.sapo_rollout_generate_stop(w.handle, prompts.data_ptr(), P, Lp, G, max_new, float(temperature),
                                           int(seed), int(stop_token), out_tokens.data_ptr(), out_logprobs.data_ptr(),
                                           out_lengths.data_ptr(), _aligned_ptr(workspace), nbytes, _stream_ptr(stream)))
+    return out_tokens, out_logprobs, out_lengths
+
+
+def sapo_rollout_generate_ragged(w: Weights, prompts, prompt_lens, G: int, max_new: int, temperature: float, seed: int,
+                                 stop_token: int = -1, workspace=None, stream=None):
+    """prompts int32 device tensor [P, Lp_max] (rows padded), prompt_lens a host sequence of P lengths.
+    Returns (tokens, logprobs, lengths or None)."""
+    torch = _torch()
+    lib = load_library()
+    P, Lp = int(prompts.shape[0]), int(prompts.shape[1])
+    assert prompts.dtype == torch.int32 and prompts.is_cuda and prompts.is_contiguous()
+    lens = np.ascontiguousarray(np.asarray(prompt_lens, dtype=np.int32))
+    assert lens.shape == (P,)
+    out_tokens = torch.empty((P * G, max_new), dtype=torch.int32, device="cuda")
+    out_logprobs = torch.empty((P * G, max_new), dtype=torch.float32, device="cuda")
+    out_lengths = torch.empty((P * G,), dtype=torch.int32, device="cuda") if stop_token >= 0 else None
+    nbytes = sapo_rollout_workspace_bytes(w, P, Lp, G, max_new)
+    if workspace is None:
+        workspace = _workspace(nbytes)
+    _check(lib.sapo_rollout_generate_ragged(w.handle, prompts.data_ptr(), lens.ctypes.data, P, Lp, G, max_new,
+                                            float(temperature), int(seed), int(stop_token), out_tokens.data_ptr(),
+                                            out_logprobs.data_ptr(), None if out_lengths is None else out_lengths.data_ptr(),
+                                            _aligned_ptr(workspace), nbytes, _stream_ptr(stream)))
     return out_tokens, out_logprobs, out_lengths
 
 

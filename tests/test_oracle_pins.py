@@ -606,3 +606,21 @@ def test_stop_token_rows_are_prefixes_of_unstopped_rows():
     unused = next(v for v in range(shape.vocab) if v not in set(tok.ravel().tolist()))
     t3, l3, ln3 = O.rollout_generate_stop(m, prompts, G, N, 1.0, seed, unused)
     assert np.array_equal(t3, tok) and np.array_equal(l3, lp) and (ln3 == N).all()
+
+
+# ----------------------------------------------------------------------------- prompts of different lengths
+def test_ragged_rollout_reduces_to_the_batch_call_and_ignores_padding():
+    shape, w, m = tiny_model(seed=4)
+    rng = np.random.default_rng(0)
+    G, N, seed = 2, 6, 9
+    same = rng.integers(0, shape.vocab, size=(3, 7))
+    t0, l0 = O.rollout_generate(m, same, G, N, 1.0, seed)
+    t1, l1 = O.rollout_generate_ragged(m, [same[0], same[1], same[2]], G, N, 1.0, seed)
+    assert np.array_equal(t0, t1) and np.array_equal(l0, l1)
+    # a prompt's rows depend on its own tokens and its sequence indices only
+    rag = [same[0][:3], same[1], same[2][:5]]
+    t2, l2 = O.rollout_generate_ragged(m, rag, G, N, 1.0, seed)
+    assert np.array_equal(t2[G:2 * G], t0[G:2 * G]) and np.array_equal(l2[G:2 * G], l0[G:2 * G])
+    assert not np.array_equal(t2[:G], t0[:G])
+    t3, _ = O.rollout_generate(m, same[2][None, :5], G, N, 1.0, seed, first_seq=2 * G)
+    assert np.array_equal(t3, t2[2 * G:])
