@@ -463,7 +463,19 @@ struct DecodeBufs {
   void* xb;         // X16 [s_pad, d]: input of the gate/up projection
   float* ssq_a;     // [d/16][s_pad] sums of squares behind xa
   float* ssq_b;     // [d/16][s_pad] sums of squares behind xb
+  // more than 64 sequences: the FFN runs on the token-parallel GEMM, the down projection split over K
+  int down_splits;  // 0: not used
+  float* partial;   // [down_splits][S, d]
 };
+
+// Splits of the down projection's K: a multiple of 8 (one residue class per XCD) that brings the grid to about
+// 200 workgroups and leaves every split at least 4 stages of 32 k.
+static int pick_down_splits(int d, int F) {
+  const int tiles = d / 128, nst = F / 32;
+  int s = 8;
+  while (tiles * (s + 8) <= 224 && nst / (s + 8) >= 4) s += 8;
+  return nst >= s ? s : 0;
+}
 
 static void carve_decode(Arena& A, const sapo_weights* w, int S, DecodeBufs& db) {
   const size_t d = w->cfg.d_model;
@@ -472,6 +484,12 @@ static void carve_decode(Arena& A, const sapo_weights* w, int S, DecodeBufs& db)
   db.xb = A.take_bytes((size_t)db.s_pad * d * 2);
   db.ssq_a = A.take<float>((d / 16) * db.s_pad);
   db.ssq_b = A.take<float>((d / 16) * db.s_pad);
+  db.down_splits = 0;
+  db.partial = nullptr;
+  if (S > 64 && S <= 256 && d % 128 == 0 && (2 * w->cfg.d_ff) % 128 == 0 && w->cfg.d_ff % 32 == 0) {
+    db.down_splits = pick_down_splits((int)d, w->cfg.d_ff);
+    if (db.down_splits > 0) db.partial = A.take<float>((size_t)db.down_splits * S * d);
+  }
 }
 
 // On entry b.h holds the residual rows, db.xa their X16 form for layer 0's attention norm and
@@ -489,7 +507,7 @@ static int run_layers_decode16(const sapo_weights* w, const FwdBufs& b, const De
     a.n_rows = S; a.s_pad = db.s_pad; a.eps = c.rms_eps; a.norm_dim = d;
     // QKV projection of the attention-normed residual
     a.Wp = (const uint4*)lw.wqkv16; a.Xp = (const uint4*)db.xa; a.N = nqkv; a.K = d;
-    a.ssq_in = db.ssq_a; a.ssq_parts = (l == 0) ? 1 : d / 16;
+    a.ssq_in = db.ssq_a; a.ssq_parts = (l == 0) ? 1 : db.down_splits > 0 ? (d + 1023) / 1024 : d / 16;
     a.out_f32 = b.qkv; a.ldc = nqkv; a.bias = lw.bqkv;
     HIP_CK(d_gemm_skinny(a, SKM_STORE, st));
     HIP_CK(d_decode_attention(b.qkv, w->rope, rm, kvc, b.attn, S, c.n_q_heads, st));
@@ -499,6 +517,20 @@ static int run_layers_decode16(const sapo_weights* w, const FwdBufs& b, const De
     o.Wp = (const uint4*)lw.wo16; o.Xp = (const uint4*)b.attn; o.N = d; o.K = q;
     o.h = b.h; o.gain_next = lw.ffn_norm; o.xp_out = (uint4*)db.xb; o.ssq_out = db.ssq_b;
     HIP_CK(d_gemm_skinny(o, SKM_RESID, st));
+    const float* gain_after = (l + 1 < c.n_layers) ? w->layers[l + 1].attn_norm : w->final_norm;
+    if (db.down_splits > 0) {
+      // many sequences: the register-direct GEMMs re-read the token operand once per workgroup and are
+      // ingest-bound here; the FFN goes through the LDS-staged token-parallel GEMM instead (256-token tiles),
+      // the down projection split over K with its partial sums added, in split order, by a row kernel
+      HIP_CK(m_rmsnorm_x32(b.h, lw.ffn_norm, c.rms_eps, b.a, S, d, nullptr, st));
+      HIP_CK(m_gemm_big(b.a, lw.wgu, S, 2 * F, d, BigEpi{BIG_SWIGLU, nullptr, 0, (f16*)b.act}, st));
+      BigEpi pe{BIG_STORE_F32, db.partial, d, nullptr};
+      pe.splits = db.down_splits; pe.split_stride = (size_t)S * d;
+      HIP_CK(m_gemm_big(b.act, lw.wdown, S, d, F, pe, st));
+      HIP_CK(d_resid_finish_x16(db.partial, db.down_splits, (size_t)S * d, b.h, gain_after, S, d, db.s_pad, db.xa, db.ssq_a,
+                                st));
+      continue;
+    }
     // gate / up projections + SwiGLU
     SkinnyArgs g{};
     g.n_rows = S; g.s_pad = db.s_pad; g.eps = c.rms_eps; g.norm_dim = d;
@@ -510,7 +542,7 @@ static int run_layers_decode16(const sapo_weights* w, const FwdBufs& b, const De
     SkinnyArgs dn{};
     dn.n_rows = S; dn.s_pad = db.s_pad;
     dn.Wp = (const uint4*)lw.wdown16; dn.Xp = (const uint4*)b.act; dn.N = d; dn.K = F;
-    dn.h = b.h; dn.gain_next = (l + 1 < c.n_layers) ? w->layers[l + 1].attn_norm : w->final_norm;
+    dn.h = b.h; dn.gain_next = gain_after;
     dn.xp_out = (uint4*)db.xa; dn.ssq_out = db.ssq_a;
     HIP_CK(d_gemm_skinny(dn, SKM_RESID, st));
   }
@@ -637,7 +669,7 @@ static int rollout_impl(const sapo_weights* w, const int32_t* prompts, const int
   const sapo_model_config& c = w->cfg;
   const int dt = c.dtype, d = c.d_model, S = pl.S;
   const float* gain_first = c.n_layers > 0 ? w->layers[0].attn_norm : w->final_norm;
-  const int parts_after_layers = c.n_layers > 0 ? d / 16 : 1;
+  const int parts_after_layers = c.n_layers == 0 ? 1 : (w->mfma && pl.dec.down_splits > 0) ? (d + 1023) / 1024 : d / 16;
 
   SampleParams sp;
   sp.temperature = temperature;

@@ -279,6 +279,10 @@ struct BigEpi {
   // token operand holds x * gain without the row scale; the accumulators are multiplied by
   // rsqrt(sum of the row's ssq parts / norm_dim + eps) before the epilogue proper.
   const float* bias = nullptr;     // STORE_F32, optional: [N] added after the row scale
+  // Split-K (STORE_F32, M <= 256 only): split z of `splits` (a multiple of 8) covers about 1/splits of K and stores
+  // to out_f32 + z * split_stride.
+  int splits = 1;
+  size_t split_stride = 0;
   const float* ssq_in = nullptr;   // [M, ssq_parts rounded up to a multiple of 4]; at most 16 parts
   int ssq_parts = 0;
   float norm_dim = 0.f, eps = 0.f;
@@ -333,6 +337,9 @@ hipError_t d_pack_weight16(const void* src, int n_rows, int K, void* dst, int ds
                            hipStream_t st);
 hipError_t d_gemm_skinny(const SkinnyArgs& a, int mode, hipStream_t st);
 hipError_t d_pack_rows_x16(const float* h, const float* gain, int M, int d, void* xp, float* ssq, hipStream_t st);
+// h += sum_z partial[z] (z < splits, each [M, d], split_stride floats apart), then xp and ssq[(d + 1023) / 1024][s_pad]
+hipError_t d_resid_finish_x16(const float* partial, int splits, size_t split_stride, float* h, const float* gain, int M, int d,
+                              int s_pad, void* xp, float* ssq, hipStream_t st);
 hipError_t d_embed_x16(const int32_t* tokens, int tok_stride, const int* step, const void* embed, int M, int d,
                        const float* gain, float* h, void* xp, float* ssq, hipStream_t st);
 bool d_lmhead_sample_supported(int K, int n_rows);

@@ -359,6 +359,41 @@ hipError_t d_pack_rows_x16(const float* h, const float* gain, int M, int d, void
   return launch(KID_MISC, k_pack_rows_x16, dim3(M), dim3(128), 0, st, h, gain, d, (uint4*)xp, ssq);
 }
 
+// The same after a split-K GEMM: h[row] += sum over the splits of partial[z][row] (added in split order),
+// then xp and the sums of squares of the updated row, one part per 1024 features: ssq[part][s_pad].
+// One workgroup of 128 threads per (row, 1024 features).
+__global__ void __launch_bounds__(128) k_resid_finish_x16(const float* __restrict__ partial, int splits, size_t split_stride,
+                                                          float* __restrict__ h, const float* __restrict__ gain, int d,
+                                                          int s_pad, uint4* __restrict__ xp, float* __restrict__ ssq) {
+  __shared__ float red[2];
+  const int row = blockIdx.x, k = blockIdx.y * 1024 + threadIdx.x * 8;
+  float ss = 0.f;
+  if (k < d) {
+    float v[8];
+    float* hp = h + (size_t)row * d + k;
+    const float4 a = *(const float4*)hp, b = *(const float4*)(hp + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+#pragma unroll 4
+    for (int z = 0; z < splits; ++z) {
+      const float* pp = partial + (size_t)z * split_stride + (size_t)row * d + k;
+      const float4 pa = *(const float4*)pp, pb = *(const float4*)(pp + 4);
+      v[0] += pa.x; v[1] += pa.y; v[2] += pa.z; v[3] += pa.w; v[4] += pb.x; v[5] += pb.y; v[6] += pb.z; v[7] += pb.w;
+    }
+    *(float4*)hp = make_float4(v[0], v[1], v[2], v[3]);
+    *(float4*)(hp + 4) = make_float4(v[4], v[5], v[6], v[7]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ss += v[e] * v[e];
+    row_to_x16(v, gain, k, row, d >> 5, xp);
+  }
+  ss = block128_sum(ss, red);
+  if (threadIdx.x == 0) ssq[(size_t)blockIdx.y * s_pad + row] = ss;
+}
+hipError_t d_resid_finish_x16(const float* partial, int splits, size_t split_stride, float* h, const float* gain, int M, int d,
+                              int s_pad, void* xp, float* ssq, hipStream_t st) {
+  return launch(KID_MISC, k_resid_finish_x16, dim3(M, (d + 1023) / 1024), dim3(128), 0, st, partial, splits, split_stride, h,
+                gain, d, s_pad, (uint4*)xp, ssq);
+}
+
 // Embedding row of token id `tok` -> h[row] (fp32), X16 bf16(h * gain), ssq[row].  128 threads.
 __device__ __forceinline__ void embed_row_x16(const bf16* __restrict__ embed, int tok, int row, int d,
                                               const float* __restrict__ gain, float* __restrict__ h,

@@ -127,13 +127,14 @@ static int big_grid(int NX, int NY) {
 // are clamped to the last one (their results are never stored).
 struct NoPrologue { __device__ __forceinline__ void operator()() const {} };
 // `prologue` runs once the first two stages are requested (loads it issues ride on the same latency).
-template <class Prologue = NoPrologue>
+// NS: depth of the LDS ring (NS - 1 stages in flight).
+template <int NS = kStages, class Prologue = NoPrologue>
 __device__ __forceinline__ void big_mainloop(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int n_tblk,
                                              int KS, int tblk0, int fblk0, uint4* smem, f32x16 (&acc)[2][4],
-                                             Prologue prologue = Prologue()) {
+                                             Prologue prologue = Prologue(), int st0 = 0, int n_stages = -1) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wf = wave & 1, wt = wave >> 1;
-  const int nst = KS >> 1;
+  const int nst = n_stages < 0 ? (KS >> 1) : n_stages;   // stages of 32 k; a split-K workgroup runs st0 .. st0 + nst - 1
   const uint4* src[6];
   unsigned dst[6];
 #pragma unroll
@@ -142,15 +143,15 @@ __device__ __forceinline__ void big_mainloop(const uint4* __restrict__ Xp, const
     if (f < 16) {
       int tb = tblk0 + (f >> 1);
       if (tb > n_tblk - 1) tb = n_tblk - 1;
-      src[i] = Xp + ((size_t)tb * KS + (f & 1)) * 64 + lane;
+      src[i] = Xp + ((size_t)tb * KS + 2 * st0 + (f & 1)) * 64 + lane;
     } else {
       const int g = f - 16;
-      src[i] = Wp + ((size_t)(fblk0 + (g >> 1)) * KS + (g & 1)) * 64 + lane;
+      src[i] = Wp + ((size_t)(fblk0 + (g >> 1)) * KS + 2 * st0 + (g & 1)) * 64 + lane;
     }
     dst[i] = __builtin_amdgcn_readfirstlane(lds_addr(smem + f * 64));
   }
   auto issue = [&](int st) {
-    const unsigned sbase = (unsigned)((st % kStages) * kStageFrags * 1024);
+    const unsigned sbase = (unsigned)((st % NS) * kStageFrags * 1024);
 #pragma unroll
     for (int i = 0; i < 6; ++i) dma16(src[i] + (size_t)st * 128, dst[i] + sbase);
   };
@@ -161,14 +162,21 @@ __device__ __forceinline__ void big_mainloop(const uint4* __restrict__ Xp, const
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
   wg_barrier();   // a previous pass over the ring (fused LM head) is over in every wave
-  issue(0);
-  if (nst > 1) issue(1);
+#pragma unroll
+  for (int p = 0; p < NS - 1; ++p)
+    if (p < nst) issue(p);
   prologue();
   for (int st = 0; st < nst; ++st) {
-    if (st + 1 < nst) wait_vmcnt<6>(); else wait_vmcnt<0>();   // this wave's part of stage st has landed
+    // this wave's part of stage st has landed once at most the newer stages' requests are outstanding
+    const int newer = min(NS - 2, nst - 1 - st);
+    if (newer >= 4) wait_vmcnt<24>();
+    else if (newer == 3) wait_vmcnt<18>();
+    else if (newer == 2) wait_vmcnt<12>();
+    else if (newer == 1) wait_vmcnt<6>();
+    else wait_vmcnt<0>();
     wg_barrier();                                               // ... and everybody's; stage st-1 is consumed
-    if (st + 2 < nst) issue(st + 2);
-    const uint4* buf = smem + (st % kStages) * kStageFrags * 64;
+    if (st + NS - 1 < nst) issue(st + NS - 1);
+    const uint4* buf = smem + (st % NS) * kStageFrags * 64;
 #pragma unroll
     for (int s2 = 0; s2 < 2; ++s2) {
       Frag xf[4], wfr[2];
@@ -187,8 +195,19 @@ __device__ __forceinline__ void big_mainloop(const uint4* __restrict__ Xp, const
 __global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int M,
                                                      int N, int K, BigEpi ep) {
   extern __shared__ uint4 smem[];
-  int bx, by;
-  if (!big_raster(N >> 7, (M + 255) >> 8, bx, by)) return;
+  int bx, by, st0 = 0, n_st = K >> 5;
+  if (ep.splits > 1) {
+    // split-K (one token tile): XCD c runs the splits c, c + 8, ... of every feature tile, so the K range of
+    // the token operand that a split reads sits in one L2; split z covers stages z nst / s .. (z + 1) nst / s
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3, per = ep.splits >> 3;
+    const int z = (j % per) * 8 + xcd;
+    bx = j / per; by = 0;
+    st0 = (int)((long)z * n_st / ep.splits);
+    n_st = (int)((long)(z + 1) * n_st / ep.splits) - st0;
+    ep.out_f32 += (size_t)z * ep.split_stride;
+  } else if (!big_raster(N >> 7, (M + 255) >> 8, bx, by)) {
+    return;
+  }
   f32x16 acc[2][4];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wf = wave & 1, wt = wave >> 1;
@@ -216,7 +235,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ X
       }
       row_scale[tj] = rsqrtf(ss / ep.norm_dim + ep.eps);
     }
-  });
+  }, st0, n_st);
   float ssq_mine[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int tj = 0; tj < 4; ++tj) {
@@ -296,8 +315,11 @@ hipError_t m_gemm_big(const void* Xp, const void* Wp, int M, int N, int K, BigEp
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  return launch(KID_GEMM_BIG, k_gemm_big, dim3(big_grid(N / 128, (M + 255) / 256)), dim3(256), kBigLds, st, (const uint4*)Xp,
-                (const uint4*)Wp, M, N, K, epi);
+  if (epi.splits < 1 || (epi.splits > 1 && (epi.splits % 8 != 0 || K / 32 < epi.splits || M > 256 ||
+                                            epi.mode != BIG_STORE_F32 || epi.ssq_in || epi.bias)))
+    return hipErrorInvalidValue;
+  const int g = epi.splits > 1 ? epi.splits * (N / 128) : big_grid(N / 128, (M + 255) / 256);
+  return launch(KID_GEMM_BIG, k_gemm_big, dim3(g), dim3(256), kBigLds, st, (const uint4*)Xp, (const uint4*)Wp, M, N, K, epi);
 }
 
 // ---------------------------------------------------------------------------------------
