@@ -59,8 +59,12 @@ def per_launch_work(shape, plan, kernel, launches):
     T, Tm, Ss = plan["T"], plan["Tm"], plan["S_score"]
     dec_steps = max(N - 1, 0) if plan["rollout"] else 0
     big_tokens = (P * Lp if plan["rollout"] else 0) + (Ss * T if plan["score"] else 0)
-    if kernel == "k_gemm_skinny":       # the four projection GEMMs of a decode layer
-        return "hbm", 2.0 * shape.matmul_params_per_layer() * L * dec_steps / launches
+    ffn_params = 3.0 * d * shape.d_ff
+    if kernel == "k_gemm_skinny":       # the projection GEMMs of a decode layer that run on the register-direct kernel
+        params = shape.matmul_params_per_layer() - (ffn_params if plan["ffn_big"] else 0.0)
+        return "hbm", 2.0 * params * L * dec_steps / launches
+    if kernel == "k_gemm_big_decode":   # gate/up and down projections of a decode layer on the token-parallel kernel
+        return "hbm", 2.0 * ffn_params * L * dec_steps / launches
     if kernel == "k_lmhead_sample":     # LM head of one decode step: the whole [V, d] matrix
         return "hbm", 2.0 * V * d
     if kernel == "k_decode_attention":  # K and V of every cached token of every sequence, one layer
@@ -149,7 +153,8 @@ def main():
                                  torch.cat([t_loc, t_ext], dim=0)], dim=1).contiguous()
     prompts = torch.from_numpy(prompts_np).cuda()
     plan = {"S": S, "N": N, "Lp": Lp, "P": P, "T": T, "Tm": Tm, "S_score": S_score, "rollout": do_rollout,
-            "score": do_score, "fused_lm": S <= 64 and shape.d_model <= 1024}
+            "score": do_score, "fused_lm": S <= 64 and shape.d_model <= 1024,
+            "ffn_big": 64 < S <= 256 and bool(gw.uses_mfma)}
 
     if do_rollout:
         ws_r = torch.empty(sapo.sapo_rollout_workspace_bytes(gw, P, Lp, G, N) + 256, dtype=torch.uint8, device="cuda")

@@ -63,7 +63,7 @@ void prof_events(int kid, hipEvent_t* e0, hipEvent_t* e1) {
 static const char* const kKernelNames[KID_COUNT] = {
     "k_embed", "k_rmsnorm", "k_gemm", "k_rope_append", "k_attention", "k_swiglu", "k_sample_rows", "k_score_rows",
     "misc", "k_gemm_big", "k_lmhead_score", "k_lmhead_score_merge", "k_gemm_skinny", "k_lmhead_sample",
-    "k_lmhead_sample_merge", "k_decode_attention", "k_flash_attention"};
+    "k_lmhead_sample_merge", "k_decode_attention", "k_flash_attention", "k_gemm_big_decode"};
 
 extern "C" int sapo_profile_kernel_count(void) { return KID_COUNT; }
 extern "C" const char* sapo_profile_kernel_name(int i) { return (i >= 0 && i < KID_COUNT) ? kKernelNames[i] : ""; }
@@ -523,9 +523,11 @@ static int run_layers_decode16(const sapo_weights* w, const FwdBufs& b, const De
       // ingest-bound here; the FFN goes through the LDS-staged token-parallel GEMM instead (256-token tiles),
       // the down projection split over K with its partial sums added, in split order, by a row kernel
       HIP_CK(m_rmsnorm_x32(b.h, lw.ffn_norm, c.rms_eps, b.a, S, d, nullptr, st));
-      HIP_CK(m_gemm_big(b.a, lw.wgu, S, 2 * F, d, BigEpi{BIG_SWIGLU, nullptr, 0, (f16*)b.act}, st));
+      BigEpi ge{BIG_SWIGLU, nullptr, 0, (f16*)b.act};
+      ge.decode = true;
+      HIP_CK(m_gemm_big(b.a, lw.wgu, S, 2 * F, d, ge, st));
       BigEpi pe{BIG_STORE_F32, db.partial, d, nullptr};
-      pe.splits = db.down_splits; pe.split_stride = (size_t)S * d;
+      pe.splits = db.down_splits; pe.split_stride = (size_t)S * d; pe.decode = true;
       HIP_CK(m_gemm_big(b.act, lw.wdown, S, d, F, pe, st));
       HIP_CK(d_resid_finish_x16(db.partial, db.down_splits, (size_t)S * d, b.h, gain_after, S, d, db.s_pad, db.xa, db.ssq_a,
                                 st));

@@ -160,7 +160,7 @@ struct SampleParams {
 enum KernelId {
   KID_EMBED = 0, KID_RMSNORM, KID_GEMM_GENERIC, KID_ROPE_APPEND, KID_ATTN_GENERIC, KID_SWIGLU, KID_SAMPLE_ROWS,
   KID_SCORE_ROWS, KID_MISC, KID_GEMM_BIG, KID_LMHEAD_SCORE, KID_LMHEAD_SCORE_MERGE, KID_GEMM_SKINNY,
-  KID_LMHEAD_SAMPLE, KID_LMHEAD_SAMPLE_MERGE, KID_DECODE_ATTN, KID_FLASH_ATTN, KID_COUNT
+  KID_LMHEAD_SAMPLE, KID_LMHEAD_SAMPLE_MERGE, KID_DECODE_ATTN, KID_FLASH_ATTN, KID_GEMM_BIG_DECODE, KID_COUNT
 };
 extern bool g_prof_on;
 // A pair of events for one profiled launch of kernel `kid` (recorded for sapo_profile_stop).
@@ -283,6 +283,7 @@ struct BigEpi {
   // to out_f32 + z * split_stride.
   int splits = 1;
   size_t split_stride = 0;
+  bool decode = false;   // accounting only: a launch of the decode step (weight-streaming-bound)
   const float* ssq_in = nullptr;   // [M, ssq_parts rounded up to a multiple of 4]; at most 16 parts
   int ssq_parts = 0;
   float norm_dim = 0.f, eps = 0.f;
@@ -330,7 +331,7 @@ struct SkinnyArgs {
   const float* bias;      // STORE, optional: [N] added after the scale
   float* h;               // RESID: residual stream [n_rows, N], updated in place
   const float* gain_next; // RESID: gain of the norm that reads the updated residual [N]
-  uint4* xp_out;          // RESID: bf16(h * gain_next), X16 order over K' = N; SWIGLU: act, X16 order over K' = N / 2
+  uint4* xp_out;          // RESID: half(h * gain_next), X16 order over K' = N; SWIGLU: act, X16 order over K' = N / 2
   float* ssq_out;         // RESID: [N/16][s_pad] sums of h^2 over each 16-feature tile
 };
 hipError_t d_pack_weight16(const void* src, int n_rows, int K, void* dst, int dst_tile0, int dst_tile_stride,

@@ -111,8 +111,8 @@ __device__ __forceinline__ float ssq_scale(const float* s_part, int tok_local, i
 // same XCD: ids that differ by a multiple of 8).
 // Epilogues:
 //   STORE  : out_f32[tok][feat] = acc * scale(tok)
-//   SWIGLU : tiles come in (gate, up) pairs; act = silu(gate * scale) * (up * scale) -> bf16, X16 order
-//   RESID  : h[tok][feat] += acc;  xp_out = bf16(h * gain_next) in X16 order;  ssq_out[tile][tok] =
+//   SWIGLU : tiles come in (gate, up) pairs; act = silu(gate * scale) * (up * scale) -> half, X16 order
+//   RESID  : h[tok][feat] += acc;  xp_out = half(h * gain_next) in X16 order;  ssq_out[tile][tok] =
 //            sum of h^2 over the tile's 16 features
 // ---------------------------------------------------------------------------------------
 template <int NT, int TG, int R, int MODE>
@@ -322,7 +322,7 @@ hipError_t d_gemm_skinny(const SkinnyArgs& a, int mode, hipStream_t st) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Rows of the residual stream -> X16 order: xp = bf16(h * gain), ssq[row] = sum h^2 (one part).
+// Rows of the residual stream -> X16 order: xp = half(h * gain), ssq[row] = sum h^2 (one part).
 // One workgroup of 128 threads per row; thread i handles the 8 features 8 i .. 8 i + 7 (+1024 j).
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ void row_to_x16(const float (&v)[8], const float* __restrict__ gain, int k, int row, int KS,
@@ -394,7 +394,7 @@ hipError_t d_resid_finish_x16(const float* partial, int splits, size_t split_str
                 gain, d, s_pad, (uint4*)xp, ssq);
 }
 
-// Embedding row of token id `tok` -> h[row] (fp32), X16 bf16(h * gain), ssq[row].  128 threads.
+// Embedding row of token id `tok` -> h[row] (fp32), X16 half(h * gain), ssq[row].  128 threads.
 __device__ __forceinline__ void embed_row_x16(const bf16* __restrict__ embed, int tok, int row, int d,
                                               const float* __restrict__ gain, float* __restrict__ h,
                                               uint4* __restrict__ xp, float* __restrict__ ssq, float* red) {

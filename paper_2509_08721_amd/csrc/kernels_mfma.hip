@@ -319,7 +319,8 @@ hipError_t m_gemm_big(const void* Xp, const void* Wp, int M, int N, int K, BigEp
                                             epi.mode != BIG_STORE_F32 || epi.ssq_in || epi.bias)))
     return hipErrorInvalidValue;
   const int g = epi.splits > 1 ? epi.splits * (N / 128) : big_grid(N / 128, (M + 255) / 256);
-  return launch(KID_GEMM_BIG, k_gemm_big, dim3(g), dim3(256), kBigLds, st, (const uint4*)Xp, (const uint4*)Wp, M, N, K, epi);
+  return launch(epi.decode ? KID_GEMM_BIG_DECODE : KID_GEMM_BIG, k_gemm_big, dim3(g), dim3(256), kBigLds, st, (const uint4*)Xp,
+                (const uint4*)Wp, M, N, K, epi);
 }
 
 // ---------------------------------------------------------------------------------------

@@ -29,7 +29,7 @@ FAMILIES = {
     "k_gemm_skinny": (("k_skinny16",), ("kernels_decode.hip", "common.h")),
     "k_decode_attention": (("k_decode_attention16",), ("kernels_decode.hip", "common.h")),
     "k_lmhead_sample": (("k_lmhead_sample16", "k_lmhead_sample_big"), ("kernels_decode.hip", "kernels_mfma.hip", "common.h")),
-    "k_gemm_big": (("k_gemm_big",), ("kernels_mfma.hip", "common.h")),
+    "k_gemm_big": (("k_gemm_big",), ("kernels_mfma.hip", "common.h")),   # a trace does not tell decode launches apart
     "k_flash_attention": (("k_flash_attention",), ("kernels_mfma.hip", "common.h")),
     "k_lmhead_score": (("k_lmhead_score(", "k_lmhead_score<", "k_lmhead_score"), ("kernels_mfma.hip", "common.h")),
 }
