@@ -29,6 +29,13 @@
  *     human-readable message for the calling thread's last failure.
  *   - Token ids in inputs must lie in [0, vocab); this is not checked on the device.
  *   - Sequences of a rollout are ordered s = p * G + g (prompt-major); group of s is s / G.
+ *   - Threads: calls that use the same sapo_weights handle, or the same workspace, must not
+ *     overlap (a handle caches the captured decode step of its last rollout call); the first
+ *     call of each kind in a process sets kernel attributes and must not race with another
+ *     first call.  Different handles with different workspaces may be used from different
+ *     threads after that.
+ *   - A rollout call on a non-default stream replays one captured decode step (HIP graph);
+ *     the calls with a stop token additionally synchronise the stream every 32 steps.
  */
 #ifndef SAPO_H
 #define SAPO_H

@@ -683,6 +683,11 @@ static int rollout_impl(const sapo_weights* w, const int32_t* prompts, const int
   sp.out_tokens = out_tokens;
   sp.out_logprobs = out_logprobs;
   sp.stop = pl.stop;
+  const bool merge_steps = w->mfma;   // both fused samplers end in the merge kernel, which then advances *step
+  if (merge_steps) {
+    sp.arrivals = pl.step + 8;
+    HIP_CK(g_fill_i32(pl.step + 8, 0, 1, st));
+  }
   const bool stopping = stop_token >= 0;
   HIP_CK(g_fill_i32(pl.stop, stop_token, 1, st));
   HIP_CK(g_fill_i32(pl.stop + 1, 0, (size_t)S + 1, st));
@@ -753,7 +758,7 @@ static int rollout_impl(const sapo_weights* w, const int32_t* prompts, const int
   RowMap rm{1, 0, 1, Lp, pl.step, ragged ? pl.lens : nullptr, G};
   auto enqueue_step = [&]() -> int {
     int rc2;
-    HIP_CK(g_incr(pl.step, st));
+    if (!merge_steps) HIP_CK(g_incr(pl.step, st));
     if (w->mfma) {
       // (the sampler's merge has already gathered the embedding rows of the previous step's tokens)
       if ((rc2 = run_layers_decode16(w, pl.fwd, pl.dec, S, rm, pl.cache, st))) return rc2;

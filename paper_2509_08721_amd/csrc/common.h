@@ -152,6 +152,9 @@ struct SampleParams {
   // Stop token (optional): stop[0] = the token id that ends a sequence (< 0: none), stop[1] = number of
   // finished sequences, stop[2 + s] = length of sequence s once it has ended (0 while it runs).
   int* stop = nullptr;
+  // Optional: arrival counter of the sampler's merge kernel.  When set, the last workgroup of the merge to
+  // have read *step advances it (the step counter then needs no kernel of its own).
+  int* arrivals = nullptr;
 };
 
 // Optional per-kernel timing: when switched on, every launch carries two HIP events that take

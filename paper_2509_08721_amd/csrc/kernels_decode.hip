@@ -579,7 +579,13 @@ __global__ void __launch_bounds__(128) k_lmhead_merge_embed(const float* __restr
       b.add(__shfl_xor(b.y, o, 64), __shfl_xor(b.z, o, 64), __shfl_xor(b.id, o, 64));
     }
     if (lane == 0) {
-      s_tok = emit_token(sp, seq0 + r, *sp.step, b.id, b.z - (a.m + logf(a.l)));
+      const int step = *sp.step;
+      s_tok = emit_token(sp, seq0 + r, step, b.id, b.z - (a.m + logf(a.l)));
+      // every workgroup has used the step index before it arrives here: the last one to arrive moves it on
+      if (sp.arrivals && atomicAdd(sp.arrivals, 1) == (int)gridDim.x - 1) {
+        *sp.arrivals = 0;
+        *const_cast<int*>(sp.step) = step + 1;
+      }
     }
   }
   __syncthreads();
