@@ -590,7 +590,7 @@ hipError_t m_lmhead_sample_big(const void* Xp, const void* Wp, int n_rows, int V
 // probabilities are IEEE half; the output goes out as half in X32 order (the O projection's operand).
 // ---------------------------------------------------------------------------------------
 template <int HD, int HPW>
-__global__ void __launch_bounds__(256) k_flash_attention(const f16* __restrict__ q, RowMap rm, KVCache kv,
+__global__ void __launch_bounds__(256, 2) k_flash_attention(const f16* __restrict__ q, RowMap rm, KVCache kv,
                                                          f16* __restrict__ out, int n_q_heads) {
   constexpr int KK = HD / 32, DT = HD / 16;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -727,12 +727,13 @@ hipError_t m_flash_attention(const void* q, RowMap rm, KVCache kv, void* out, in
   const int rep = n_q_heads / kv.n_kv_heads;
   const int nqb = (rm.T + 63) / 64;
   if (kv.head_dim == 64) {
-    constexpr int HPW = 7;
+    constexpr int HPW = 4;   // a 7-head group goes to two workgroups (4 + 3 heads): two waves per SIMD, which hide
+                             // the softmax arithmetic, pay for the second read of K / V (2 heads each: slower again)
     dim3 grid(nqb, n_seq * kv.n_kv_heads, (rep + HPW - 1) / HPW);
     return launch(KID_FLASH_ATTN, k_flash_attention<64, HPW>, grid, dim3(256), 0, st, (const f16*)q, rm, kv, (f16*)out, n_q_heads);
   }
   if (kv.head_dim == 128) {
-    constexpr int HPW = 3;
+    constexpr int HPW = 2;
     dim3 grid(nqb, n_seq * kv.n_kv_heads, (rep + HPW - 1) / HPW);
     return launch(KID_FLASH_ATTN, k_flash_attention<128, HPW>, grid, dim3(256), 0, st, (const f16*)q, rm, kv, (f16*)out, n_q_heads);
   }
