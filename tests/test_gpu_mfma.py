@@ -148,33 +148,37 @@ def test_mfma_rollout_logprobs_equal_scoring(sapo):
     assert np.max(np.abs(lp.cpu().numpy()[:, 32:] - lps)) <= LOGPROB_TOL
 
 
-def test_graph_replay_matches_eager_launches(sapo):
+@pytest.mark.parametrize("shape_name,P,G", [("MINI_BF16", 4, 4),          # 64-token decode kernels, fused sampler
+                                            ("MINI_BF16", 9, 8),          # 72 sequences: FFN on the token-parallel GEMM, split-K
+                                            ("MINI_BF16_HD128", 11, 6)])  # the same with head dim 128 and an untied LM head
+def test_graph_replay_matches_eager_launches(sapo, shape_name, P, G):
     """On a non-default stream the decode step is captured once and replayed; the result must be
     bit-identical to eager launches, also when the cached graph is reused with another seed and
     temperature, and after the buffers change."""
     import torch
-    shape = W.MINI_BF16
+    shape = getattr(W, shape_name)
     w, gw = make(sapo, shape, 95)
-    prompts = dev(np.random.default_rng(3).integers(0, shape.vocab, size=(4, 20)).astype(np.int32))
+    S, N = P * G, 25
+    prompts = dev(np.random.default_rng(3).integers(0, shape.vocab, size=(P, 20)).astype(np.int32))
     eager = {}
     for seed, temp in ((1, 1.0), (2, 0.7), (3, 0.0)):
-        t, l = sapo.sapo_rollout_generate(gw, prompts, 4, 25, temp, seed)      # default stream: eager
+        t, l = sapo.sapo_rollout_generate(gw, prompts, G, N, temp, seed)      # default stream: eager
         eager[(seed, temp)] = (t.cpu().numpy(), l.cpu().numpy())
     side = torch.cuda.Stream()
-    nbytes = sapo.sapo_rollout_workspace_bytes(gw, 4, 20, 4, 25)
+    nbytes = sapo.sapo_rollout_workspace_bytes(gw, P, 20, G, N)
     ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
-    out_t = torch.empty((16, 25), dtype=torch.int32, device="cuda")
-    out_l = torch.empty((16, 25), dtype=torch.float32, device="cuda")
+    out_t = torch.empty((S, N), dtype=torch.int32, device="cuda")
+    out_l = torch.empty((S, N), dtype=torch.float32, device="cuda")
     torch.cuda.synchronize()
     with torch.cuda.stream(side):
         for rep in range(2):
             for (seed, temp), (et, el) in eager.items():
-                sapo.sapo_rollout_generate(gw, prompts, 4, 25, temp, seed, workspace=ws, out_tokens=out_t,
+                sapo.sapo_rollout_generate(gw, prompts, G, N, temp, seed, workspace=ws, out_tokens=out_t,
                                            out_logprobs=out_l, stream=side)
                 side.synchronize()
                 assert np.array_equal(out_t.cpu().numpy(), et), (rep, seed)
                 assert np.array_equal(out_l.cpu().numpy().view(np.uint32), el.view(np.uint32)), (rep, seed)
         # other buffers: the graph is rebuilt
-        t2, l2 = sapo.sapo_rollout_generate(gw, prompts, 4, 25, 1.0, 1, stream=side)
+        t2, l2 = sapo.sapo_rollout_generate(gw, prompts, G, N, 1.0, 1, stream=side)
         side.synchronize()
         assert np.array_equal(t2.cpu().numpy(), eager[(1, 1.0)][0])
