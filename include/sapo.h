@@ -141,7 +141,8 @@ int sapo_rollout_generate_stop(const sapo_weights* w, const int32_t* prompts, in
  * Sec. 3.1; real question sets are not of one length), with an optional stop token.
  *   prompts      dev int32 [P, Lp_max]   prompt p occupies the first prompt_lens[p] entries of its row;
  *                                        the rest of the row is padding (any vocabulary ids)
- *   prompt_lens  HOST int32 [P]          1 <= prompt_lens[p] <= Lp_max
+ *   prompt_lens  HOST int32 [P]          1 <= prompt_lens[p] <= Lp_max; copied to the device on `stream`:
+ *                                        keep it unchanged until the stream has been synchronised
  *   stop_token   a vocabulary id, or -1 for none (then out_lengths may be NULL)
  * Sequence s = p * G + g continues prompt p from position prompt_lens[p]; everything else is as in
  * sapo_rollout_generate / sapo_rollout_generate_stop: the result for prompt p equals what a call with
