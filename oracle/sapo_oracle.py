@@ -381,13 +381,14 @@ def rollout_generate_stop(m: Model, prompts: np.ndarray, group: int, max_new: in
     return out_tok, out_lp, lengths
 
 
-def score_logprobs(m: Model, tokens: np.ndarray, completion_mask: np.ndarray) -> np.ndarray:
+def score_logprobs(m: Model, tokens: np.ndarray, completion_mask: np.ndarray, temperature: float = 1.0) -> np.ndarray:
     """Teacher-forced per-token log-probs under the policy.
 
     tokens int[S, T], completion_mask uint8[S, T].  out[s, t] =
-    log softmax(z_{t-1})[tokens[s, t]] where z_{t-1} are the logits after
+    log softmax(z_{t-1} / temperature)[tokens[s, t]] where z_{t-1} are the logits after
     consuming tokens[s, 0..t-1], for every masked (s, t) with t >= 1; 0.0
-    elsewhere.  float32 [S, T].
+    elsewhere.  float32 [S, T].  temperature 1 is the policy's own distribution; another value
+    gives the log-probs of the distribution a rollout at that temperature was sampled from.
     """
     tokens = np.asarray(tokens)
     S, T = tokens.shape
@@ -398,7 +399,7 @@ def score_logprobs(m: Model, tokens: np.ndarray, completion_mask: np.ndarray) ->
         if tpos.size == 0:
             continue
         x = hidden_states(m, tokens[s])
-        lp = log_softmax(logits_from_hidden(m, x[tpos - 1]))
+        lp = log_softmax(logits_from_hidden(m, x[tpos - 1]) / temperature)
         out[s, tpos] = lp[np.arange(tpos.size), tokens[s, tpos]]
     return out
 

@@ -624,3 +624,31 @@ def test_ragged_rollout_reduces_to_the_batch_call_and_ignores_padding():
     assert not np.array_equal(t2[:G], t0[:G])
     t3, _ = O.rollout_generate(m, same[2][None, :5], G, N, 1.0, seed, first_seq=2 * G)
     assert np.array_equal(t3, t2[2 * G:])
+
+
+# ----------------------------------------------------------------------------- scoring at a temperature
+def test_score_logprobs_at_a_temperature():
+    shape, w, m = tiny_model(seed=6)
+    rng = np.random.default_rng(1)
+    toks = rng.integers(0, shape.vocab, size=(2, 9))
+    mask = np.ones((2, 9), np.uint8)
+    base = O.score_logprobs(m, toks, mask)
+    assert np.array_equal(O.score_logprobs(m, toks, mask, temperature=1.0), base)
+    for temp in (0.5, 0.7, 3.0):
+        lp = O.score_logprobs(m, toks, mask, temperature=temp)
+        # library routine on the teacher-forced logits
+        for s in range(2):
+            z = O.forward_logits(m, toks[s])
+            ref = torch.log_softmax(torch.tensor(z) / temp, dim=-1).numpy()
+            assert np.allclose(lp[s, 1:], ref[np.arange(8), toks[s, 1:]], atol=1e-6)
+        assert not np.allclose(lp[:, 1:], base[:, 1:], atol=1e-3)
+    # a very high temperature flattens the distribution to uniform over the vocabulary
+    hot = O.score_logprobs(m, toks, mask, temperature=1e9)
+    assert np.allclose(hot[:, 1:], -math.log(shape.vocab), atol=1e-6)
+    # a low temperature sharpens it: the greedy token's log-prob tends to 0
+    z = O.forward_logits(m, toks[0])
+    greedy = toks[0].copy()
+    greedy[1:] = np.argmax(z[:-1], axis=-1)
+    z2 = O.forward_logits(m, greedy[:2])
+    g2 = np.array([[greedy[0], int(np.argmax(z2[0]))]])
+    assert O.score_logprobs(m, g2, np.ones((1, 2), np.uint8), temperature=1e-3)[0, 1] > -1e-3
