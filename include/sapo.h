@@ -173,6 +173,16 @@ int sapo_score_logprobs(const sapo_weights* w, const int32_t* tokens,
                         size_t workspace_bytes, void* stream);
 
 /*
+ * The same at a temperature: out_logprobs = log softmax(z_{t-1} / temperature)[tokens[s, t]], the
+ * log-probs of the distribution a rollout at that temperature was sampled from (the rollout calls
+ * themselves return the policy's log-probs at temperature 1).  temperature > 0.
+ */
+int sapo_score_logprobs_at(const sapo_weights* w, const int32_t* tokens,
+                           const uint8_t* completion_mask, const float* rewards, int S, int T, int G,
+                           float temperature, float* out_logprobs, float* out_advantages,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Test hook: teacher-forced logits z (Sec. 3.2's re-encoding, before the log-softmax) at n
  * chosen (sequence, position) pairs: out_logits[i, :] are the logits after consuming
  * tokens[s_i, 0 .. t_i].

@@ -859,6 +859,7 @@ struct ScorePlan {
   void* x;          // [chunk_seqs * T, d] final-norm output of the gathered rows (T)
   float* logits;    // [row_chunk, V] (shape-generic kernels)
   float* partials;  // fused LM-head partials (MFMA kernels)
+  float* gain_t;    // [d] final-norm gains divided by the temperature (scoring at a temperature)
   size_t bytes;
 };
 
@@ -882,6 +883,7 @@ static void plan_score(const sapo_weights* w, int S, int T, int chunk_seqs, size
   pl.x = A.take_bytes((R + 63) / 64 * 64 * c.d_model * w->elt);
   pl.logits = w->mfma ? nullptr : A.take<float>((size_t)pl.row_chunk * c.vocab);
   pl.partials = w->mfma ? A.take<float>(m_lmhead_score_partial_floats((int)M, c.vocab)) : nullptr;
+  pl.gain_t = A.take<float>(c.d_model);
   pl.bytes = (A.off + 255) & ~(size_t)255;
 }
 
@@ -919,11 +921,12 @@ static int forward_chunk(const sapo_weights* w, const ScorePlan& pl, const int32
   return run_layers(w, pl.fwd, M, rm, pl.cache, pl.T, st);
 }
 
-extern "C" int sapo_score_logprobs(const sapo_weights* w, const int32_t* tokens, const uint8_t* completion_mask,
-                                   const float* rewards, int S, int T, int G, float* out_logprobs,
-                                   float* out_advantages, void* workspace, size_t workspace_bytes, void* stream) {
+static int score_impl(const sapo_weights* w, const int32_t* tokens, const uint8_t* completion_mask, const float* rewards,
+                      int S, int T, int G, float temperature, float* out_logprobs, float* out_advantages, void* workspace,
+                      size_t workspace_bytes, void* stream) {
   int rc = check_score_args(w, S, T);
   if (rc) return rc;
+  if (!(temperature > 0.f)) return fail(SAPO_EINVAL, "temperature must be > 0");
   if (G <= 0 || S % G != 0) return fail(SAPO_EINVAL, "S = %d is not a multiple of G = %d", S, G);
   if (!tokens || !completion_mask || !rewards || !out_logprobs || !out_advantages || !workspace)
     return fail(SAPO_EINVAL, "NULL buffer");
@@ -934,6 +937,12 @@ extern "C" int sapo_score_logprobs(const sapo_weights* w, const int32_t* tokens,
   hipStream_t st = (hipStream_t)stream;
   const sapo_model_config& c = w->cfg;
 
+  // log softmax(z / T): z is linear in the final norm's gains, so the temperature goes into them
+  const float* final_gain = w->final_norm;
+  if (temperature != 1.0f) {
+    HIP_CK(g_scale_f32(w->final_norm, 1.0f / temperature, pl.gain_t, (size_t)c.d_model, st));
+    final_gain = pl.gain_t;
+  }
   HIP_CK(g_advantages(rewards, S, G, out_advantages, st));
   HIP_CK(g_fill_f32(out_logprobs, 0.f, (size_t)S * T, st));
   HIP_CK(g_page_table(pl.cache.page_table, pl.chunk_seqs, pl.pages_per_seq, 1, 0, pl.chunk_seqs, st));
@@ -944,11 +953,11 @@ extern "C" int sapo_score_logprobs(const sapo_weights* w, const int32_t* tokens,
     if ((rc = forward_chunk(w, pl, tokens, s0, ns, st))) return rc;
     HIP_CK(g_masked_rows(completion_mask, T, s0, ns, pl.rows, pl.src_rows, pl.count, st));
     if (w->mfma) {
-      HIP_CK(m_rmsnorm_x32(pl.fwd.h, w->final_norm, c.rms_eps, pl.x, M, c.d_model, pl.src_rows, st));
+      HIP_CK(m_rmsnorm_x32(pl.fwd.h, final_gain, c.rms_eps, pl.x, M, c.d_model, pl.src_rows, st));
       HIP_CK(m_lmhead_score(pl.x, w->lm_head, M, pl.count, c.vocab, c.d_model, pl.rows, tokens, T, pl.partials,
                             out_logprobs, st));
     } else {
-      HIP_CK(g_rmsnorm(c.dtype, pl.fwd.h, w->final_norm, c.rms_eps, pl.x, M, c.d_model, pl.src_rows, st));
+      HIP_CK(g_rmsnorm(c.dtype, pl.fwd.h, final_gain, c.rms_eps, pl.x, M, c.d_model, pl.src_rows, st));
       for (int r0 = 0; r0 < M; r0 += pl.row_chunk) {
         const int nr = (M - r0 < pl.row_chunk) ? M - r0 : pl.row_chunk;
         HIP_CK(g_gemm(c.dtype, (char*)pl.x + (size_t)r0 * c.d_model * w->elt, w->lm_head, pl.logits, nr, c.vocab,
@@ -958,6 +967,20 @@ extern "C" int sapo_score_logprobs(const sapo_weights* w, const int32_t* tokens,
     }
   }
   return SAPO_OK;
+}
+
+extern "C" int sapo_score_logprobs(const sapo_weights* w, const int32_t* tokens, const uint8_t* completion_mask,
+                                   const float* rewards, int S, int T, int G, float* out_logprobs,
+                                   float* out_advantages, void* workspace, size_t workspace_bytes, void* stream) {
+  return score_impl(w, tokens, completion_mask, rewards, S, T, G, 1.0f, out_logprobs, out_advantages, workspace,
+                    workspace_bytes, stream);
+}
+
+extern "C" int sapo_score_logprobs_at(const sapo_weights* w, const int32_t* tokens, const uint8_t* completion_mask,
+                                      const float* rewards, int S, int T, int G, float temperature, float* out_logprobs,
+                                      float* out_advantages, void* workspace, size_t workspace_bytes, void* stream) {
+  return score_impl(w, tokens, completion_mask, rewards, S, T, G, temperature, out_logprobs, out_advantages, workspace,
+                    workspace_bytes, stream);
 }
 
 // ---------------------------------------------------------------------------------------

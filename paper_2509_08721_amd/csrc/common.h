@@ -234,6 +234,8 @@ hipError_t g_sample_rows(const float* logits, int n_prompt_rows, int G, int V, S
 hipError_t g_score_rows(const float* logits, int n_rows, int row_offset, int V, const int* row_seq_pos,
                         const int* n_rows_dev, const int32_t* tokens, int T, float* out_logprobs, hipStream_t st);
 hipError_t g_advantages(const float* rewards, int S, int G, float* out, hipStream_t st);
+// y = a x
+hipError_t g_scale_f32(const float* x, float a, float* y, size_t n, hipStream_t st);
 // x[m][n] += bias[n]
 hipError_t g_add_row_bias(float* x, const float* bias, int M, int N, hipStream_t st);
 // out[s] = len[s] if the sequence has stopped (len > 0), else max_new

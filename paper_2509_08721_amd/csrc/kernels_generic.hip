@@ -436,6 +436,13 @@ __global__ void k_advantages(const float* __restrict__ r, int n_groups, int G, f
   const double sd = sqrt(var / G);
   for (int i = 0; i < G; ++i) out[(size_t)g * G + i] = (float)(((double)rg[i] - mu) / (sd + 1e-6));
 }
+__global__ void k_scale_f32(const float* __restrict__ x, float a, float* __restrict__ y, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) y[i] = x[i] * a;
+}
+hipError_t g_scale_f32(const float* x, float a, float* y, size_t n, hipStream_t st) {
+  return launch(KID_MISC, k_scale_f32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, x, a, y, n);
+}
 __global__ void k_add_row_bias(float* __restrict__ x, const float* __restrict__ bias, size_t total, int N) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < total) x[i] += bias[i % N];

@@ -69,6 +69,8 @@ def load_library() -> C.CDLL:
     lib.sapo_rollout_generate_ragged.restype = i32
     lib.sapo_score_logprobs.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
     lib.sapo_score_logprobs.restype = i32
+    lib.sapo_score_logprobs_at.argtypes = [vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, sz, vp]
+    lib.sapo_score_logprobs_at.restype = i32
     lib.sapo_assemble_workspace_bytes.argtypes = [i32, i32]
     lib.sapo_assemble_workspace_bytes.restype = sz
     lib.sapo_assemble_training_set.argtypes = [vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, u64, vp, vp, vp, vp, vp, sz, vp]
@@ -98,7 +100,7 @@ def load_library() -> C.CDLL:
 EXPORTED = ["sapo_weights_create", "sapo_weights_destroy", "sapo_weights_uses_mfma", "sapo_weights_set_qkv_bias",
             "sapo_rollout_workspace_bytes", "sapo_score_workspace_bytes",
             "sapo_debug_logits_workspace_bytes", "sapo_rollout_generate", "sapo_rollout_generate_stop", "sapo_rollout_generate_ragged",
-            "sapo_score_logprobs",
+            "sapo_score_logprobs", "sapo_score_logprobs_at",
             "sapo_surrogate_workspace_bytes", "sapo_clipped_surrogate",
             "sapo_assemble_workspace_bytes", "sapo_assemble_training_set",
             "sapo_debug_logits", "sapo_debug_gumbel", "sapo_last_error", "sapo_profile_kernel_count",
@@ -279,6 +281,26 @@ def sapo_rollout_generate_ragged(w: Weights, prompts, prompt_lens, G: int, max_n
                                             out_logprobs.data_ptr(), None if out_lengths is None else out_lengths.data_ptr(),
                                             _aligned_ptr(workspace), nbytes, _stream_ptr(stream)))
     return out_tokens, out_logprobs, out_lengths
+
+
+def sapo_score_logprobs_at(w: Weights, tokens, completion_mask, rewards, G: int, temperature: float, workspace=None,
+                           stream=None):
+    """sapo_score_logprobs at a temperature: log softmax(z / temperature)[token]."""
+    torch = _torch()
+    lib = load_library()
+    S, T = int(tokens.shape[0]), int(tokens.shape[1])
+    assert tokens.dtype == torch.int32 and tokens.is_cuda and tokens.is_contiguous()
+    assert completion_mask.dtype == torch.uint8 and completion_mask.is_cuda and completion_mask.is_contiguous()
+    assert rewards.dtype == torch.float32 and rewards.is_cuda and rewards.is_contiguous()
+    out_logprobs = torch.empty((S, T), dtype=torch.float32, device="cuda")
+    out_advantages = torch.empty((S,), dtype=torch.float32, device="cuda")
+    nbytes = sapo_score_workspace_bytes(w, S, T)
+    if workspace is None:
+        workspace = _workspace(nbytes)
+    _check(lib.sapo_score_logprobs_at(w.handle, tokens.data_ptr(), completion_mask.data_ptr(), rewards.data_ptr(),
+                                      S, T, G, float(temperature), out_logprobs.data_ptr(), out_advantages.data_ptr(),
+                                      _aligned_ptr(workspace), nbytes, _stream_ptr(stream)))
+    return out_logprobs, out_advantages
 
 
 def sapo_score_logprobs(w: Weights, tokens, completion_mask, rewards, G: int, workspace=None, stream=None,
