@@ -427,15 +427,15 @@ static int run_layers_big(const sapo_weights* w, const FwdBufs& b, int M, RowMap
     // (row * gain, half) and the row's sum-of-squares parts; the consumer scales its accumulators.
     const int parts = d / 128;
     const bool fold = parts <= 16;
-    BigEpi qkv_ep{BIG_STORE_F32, b.qkv, q + 2 * kv, nullptr};
-    qkv_ep.bias = lw.bqkv;
+    QkvEpi qkv_ep;
+    qkv_ep.bias = lw.bqkv; qkv_ep.rope = w->rope; qkv_ep.rm = rm; qkv_ep.kv = kvc; qkv_ep.q_out = (f16*)b.q;
+    qkv_ep.n_q_heads = c.n_q_heads;
     if (l == 0 || !fold) {
       HIP_CK(m_rmsnorm_x32(b.h, lw.attn_norm, c.rms_eps, b.a, M, d, nullptr, st));
     } else {
       qkv_ep.ssq_in = b.ssq; qkv_ep.ssq_parts = parts; qkv_ep.norm_dim = (float)d; qkv_ep.eps = c.rms_eps;
     }
-    HIP_CK(m_gemm_big(b.a, lw.wqkv, M, q + 2 * kv, d, qkv_ep, st));
-    HIP_CK(g_rope_append_f16(b.qkv, w->rope, rm, kvc, b.q, M, c.n_q_heads, st));
+    HIP_CK(m_gemm_qkv_rope(b.a, lw.wqkv, M, q + 2 * kv, d, qkv_ep, st));
     HIP_CK(m_flash_attention(b.q, rm, kvc, b.attn, M / rm.T, c.n_q_heads, st));
     BigEpi o_ep{BIG_ADD_F32, b.h, d, nullptr};
     BigEpi gu_ep{BIG_SWIGLU, nullptr, 0, (f16*)b.act};

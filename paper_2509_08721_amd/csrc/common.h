@@ -300,6 +300,20 @@ struct BigEpi {
 };
 enum { BIG_STORE_F32 = 0, BIG_ADD_F32 = 1, BIG_SWIGLU = 2 };
 
+// QKV projection with rotary embedding + KV append in the epilogue (head_dim 64 or 128)
+struct QkvEpi {
+  const float* ssq_in = nullptr;   // row scale of the folded norm, as in BigEpi
+  int ssq_parts = 0;
+  float norm_dim = 0.f, eps = 0.f;
+  const float* bias = nullptr;     // [N] optional
+  const float2* rope = nullptr;    // [max_seq][hd / 2] (cos, sin)
+  RowMap rm;
+  KVCache kv;
+  f16* q_out = nullptr;            // [M, Hq hd] rotated queries, half
+  int n_q_heads = 0;
+};
+hipError_t m_gemm_qkv_rope(const void* Xp, const void* Wp, int M, int N, int K, const QkvEpi& epi, hipStream_t st);
+
 hipError_t m_pack_weight(const void* src, int n_rows, int K, void* dst, int dst_tile0, int dst_tile_stride,
                          hipStream_t st);
 // Xp: tokens in X32 fragment order (rows padded to a multiple of 32); Wp: weights in W32 order

@@ -306,6 +306,192 @@ __global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ X
     }
   }
 }
+// ---------------------------------------------------------------------------------------
+// QKV projection with the rotary embedding and the KV append in its epilogue (token-parallel path): the
+// fp32 q/k/v rows never exist in memory.  Same main loop as k_gemm_big.  A 128-feature tile is two
+// heads of 64 (one per feature wave: the rotation partner i + 32 sits in the same lane, accumulator
+// block fi = 1) or one head of 128 (the partner i + 64 sits in the other feature wave: the two waves
+// swap their accumulators through LDS, two token blocks at a time).  q goes out as half row-major
+// [M, Hq hd] (flash attention's operand), rotated k and v go to the row's cache page.
+// ---------------------------------------------------------------------------------------
+template <int HD>
+__global__ void __launch_bounds__(256, 2) k_gemm_qkv_rope(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int M,
+                                                          int N, int K, QkvEpi ep) {
+  extern __shared__ uint4 smem[];
+  int bx, by;
+  if (!big_raster(N >> 7, (M + 255) >> 8, bx, by)) return;
+  f32x16 acc[2][4];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wf = wave & 1, wt = wave >> 1;
+  float row_scale[4] = {1.f, 1.f, 1.f, 1.f};
+  big_mainloop(Xp, Wp, (M + 31) >> 5, K >> 4, by * 8, bx * 4, smem, acc, [&]() {
+    if (!ep.ssq_in) return;
+    const int ps = (ep.ssq_parts + 3) & ~3;
+    float4 part[4][4];
+#pragma unroll
+    for (int tj = 0; tj < 4; ++tj) {
+      const int tok = min(by * 256 + wt * 128 + tj * 32 + (lane & 31), M - 1);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        part[tj][i] = (4 * i < ps) ? *(const float4*)(ep.ssq_in + (size_t)tok * ps + 4 * i) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int tj = 0; tj < 4; ++tj) {
+      float ss = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        ss += (4 * i + 0 < ep.ssq_parts) ? part[tj][i].x : 0.f;
+        ss += (4 * i + 1 < ep.ssq_parts) ? part[tj][i].y : 0.f;
+        ss += (4 * i + 2 < ep.ssq_parts) ? part[tj][i].z : 0.f;
+        ss += (4 * i + 3 < ep.ssq_parts) ? part[tj][i].w : 0.f;
+      }
+      row_scale[tj] = rsqrtf(ss / ep.norm_dim + ep.eps);
+    }
+  });
+  const int hq = ep.n_q_heads, hkv = ep.kv.n_kv_heads;
+  const int head = (HD == 64) ? bx * 2 + wf : bx;            // among Hq + 2 Hkv heads
+  const bool is_v = head >= hq + hkv;
+  const int half_sel = lane >> 5;
+  // row scale and bias first: what is rotated is the finished projection
+#pragma unroll
+  for (int tj = 0; tj < 4; ++tj)
+#pragma unroll
+    for (int fi = 0; fi < 2; ++fi) {
+      const int f0 = bx * 128 + wf * 64 + fi * 32 + half_sel * 4;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float4 bb = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ep.bias) bb = *(const float4*)(ep.bias + f0 + 8 * r);
+        acc[fi][tj][4 * r + 0] = acc[fi][tj][4 * r + 0] * row_scale[tj] + bb.x;
+        acc[fi][tj][4 * r + 1] = acc[fi][tj][4 * r + 1] * row_scale[tj] + bb.y;
+        acc[fi][tj][4 * r + 2] = acc[fi][tj][4 * r + 2] * row_scale[tj] + bb.z;
+        acc[fi][tj][4 * r + 3] = acc[fi][tj][4 * r + 3] * row_scale[tj] + bb.w;
+      }
+    }
+  f16* kpool = (f16*)ep.kv.k;
+  f16* vpool = (f16*)ep.kv.v;
+  // one token block (tj) of this wave: `other` holds the rotation partners (HD = 128) or is unused
+  auto finish = [&](const f32x16& mine0, const f32x16& mine1, int tj, const f32x16 (&other)[2]) {
+    const f32x16* const mine_p[2] = {&mine0, &mine1};
+#define mine(fi) (*mine_p[fi])
+    const int tok = by * 256 + wt * 128 + tj * 32 + (lane & 31);
+    if (tok >= M) return;
+    int seq, pos;
+    ep.rm.get(tok, seq, pos);
+    const bool keep = ep.rm.keeps_kv(tok);
+    const int page = ep.kv.page_table[(size_t)seq * ep.kv.pages_per_seq + pos / kPageTokens];
+    const int slot = pos % kPageTokens;
+    if (is_v) {
+      if (!keep) return;
+      const int vh = head - hq - hkv;
+      f16* vp = vpool + ((size_t)page * hkv + vh) * HD * kPageTokens + slot;
+#pragma unroll
+      for (int fi = 0; fi < 2; ++fi)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int f = (HD == 64 ? 0 : wf * 64) + fi * 32 + 8 * (v >> 2) + (v & 3) + half_sel * 4;
+          vp[(size_t)f * kPageTokens] = from_f32<f16>(mine(fi)[v]);
+        }
+      return;
+    }
+    f16* dst;   // start of this row's head: q row-major, k in its page slot
+    if (head < hq) dst = ep.q_out + ((size_t)tok * hq + head) * HD;
+    else dst = kpool + (((size_t)page * hkv + (head - hq)) * kPageTokens + slot) * HD;
+    if (head >= hq && !keep) return;
+    const float2* cs_row = ep.rope + (size_t)pos * (HD / 2);
+    if (HD == 64) {
+      // pair (i, i + 32): x1 = block fi = 0, x2 = block fi = 1, i = 8 r + j + 4 half_sel
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int i0 = 8 * r + half_sel * 4;
+        const float4 c01 = *(const float4*)(cs_row + i0), c23 = *(const float4*)(cs_row + i0 + 2);
+        const float cs[8] = {c01.x, c01.y, c01.z, c01.w, c23.x, c23.y, c23.z, c23.w};
+        f16x4 o1, o2;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float x1 = mine0[4 * r + j], x2 = mine1[4 * r + j], c = cs[2 * j], sn = cs[2 * j + 1];
+          o1[j] = from_f32<f16>(x1 * c - x2 * sn);
+          o2[j] = from_f32<f16>(x2 * c + x1 * sn);
+        }
+        *(f16x4*)(dst + i0) = o1;
+        *(f16x4*)(dst + i0 + 32) = o2;
+      }
+    } else {
+      // pair (i, i + 64): this wave holds x1 (wf = 0) or x2 (wf = 1) at i = fi 32 + 8 r + j + 4 half_sel
+#pragma unroll
+      for (int fi = 0; fi < 2; ++fi)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int i0 = fi * 32 + 8 * r + half_sel * 4;
+          const float4 c01 = *(const float4*)(cs_row + i0), c23 = *(const float4*)(cs_row + i0 + 2);
+          const float cs[8] = {c01.x, c01.y, c01.z, c01.w, c23.x, c23.y, c23.z, c23.w};
+          f16x4 o;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float a = mine(fi)[4 * r + j], b = other[fi][4 * r + j], c = cs[2 * j], sn = cs[2 * j + 1];
+            o[j] = from_f32<f16>(wf == 0 ? a * c - b * sn : a * c + b * sn);
+          }
+          *(f16x4*)(dst + wf * 64 + i0) = o;
+        }
+    }
+#undef mine
+  };
+  if (HD == 64 || is_v) {
+#pragma unroll
+    for (int tj = 0; tj < 4; ++tj) {
+      const f32x16 none[2] = {};
+      finish(acc[0][tj], acc[1][tj], tj, none);
+      __builtin_amdgcn_sched_barrier(0);   // one token block at a time: hoisted loads of all four spill
+    }
+    return;
+  }
+  // HD = 128, q or k head: swap accumulators with the other feature wave through LDS, two token blocks at a time
+  float* ex = (float*)smem;   // [wt][wf][tj2][fi][v][lane]: 2 x 2 x 2 x 2 x 16 x 64 floats = 64 KiB
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    wg_barrier();   // the ring (first round) or the previous round's partners have been read
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+      for (int fi = 0; fi < 2; ++fi)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          ex[((((wt * 2 + wf) * 2 + t2) * 2 + fi) * 16 + v) * 64 + lane] = acc[fi][2 * h + t2][v];
+    __syncthreads();
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2) {
+      f32x16 other[2];
+#pragma unroll
+      for (int fi = 0; fi < 2; ++fi)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) other[fi][v] = ex[((((wt * 2 + (wf ^ 1)) * 2 + t2) * 2 + fi) * 16 + v) * 64 + lane];
+      finish(acc[0][2 * h + t2], acc[1][2 * h + t2], 2 * h + t2, other);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
+
+hipError_t m_gemm_qkv_rope(const void* Xp, const void* Wp, int M, int N, int K, const QkvEpi& epi, hipStream_t st) {
+  if (M == 0) return hipSuccess;
+  const int hd = epi.kv.head_dim;
+  if (N % 128 != 0 || K % 32 != 0 || (hd != 64 && hd != 128) || N != (epi.n_q_heads + 2 * epi.kv.n_kv_heads) * hd)
+    return hipErrorInvalidValue;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)k_gemm_qkv_rope<64>, hipFuncAttributeMaxDynamicSharedMemorySize, kBigLds);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void*)k_gemm_qkv_rope<128>, hipFuncAttributeMaxDynamicSharedMemorySize, kBigLds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const dim3 grid(big_grid(N / 128, (M + 255) / 256));
+  if (hd == 64)
+    return launch(KID_GEMM_BIG, k_gemm_qkv_rope<64>, grid, dim3(256), kBigLds, st, (const uint4*)Xp, (const uint4*)Wp, M, N, K,
+                  epi);
+  return launch(KID_GEMM_BIG, k_gemm_qkv_rope<128>, grid, dim3(256), kBigLds, st, (const uint4*)Xp, (const uint4*)Wp, M, N, K,
+                epi);
+}
+
 hipError_t m_gemm_big(const void* Xp, const void* Wp, int M, int N, int K, BigEpi epi, hipStream_t st) {
   if (M == 0) return hipSuccess;
   if (N % 128 != 0 || K % 32 != 0) return hipErrorInvalidValue;
