@@ -9,7 +9,8 @@ The default workload is one node-round of the paper's experiment (8 questions x 
 completions, Sec. 4.1 / Sec. 5) on the 0.5B-class decoder with synthetic weights and prompts.
 Other workloads (--workload): halfb_long (rollout only, long generation), halfb_score_mixed
 (scoring only, half local / half external rollouts; the batch is prepared untimed), onehalfb
-(1.5B-class decoder, rollout + scoring), tiny.
+(1.5B-class decoder, rollout + scoring), tiny, halfb_pass1 (one sequence: the latency of a
+decode step at batch 1).
 
 Prints ONE JSON line.
 """

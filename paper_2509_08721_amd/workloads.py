@@ -154,6 +154,11 @@ WORKLOADS: Dict[str, Workload] = {
                          prompt_len=256, n_new=512, temperature=1.0, prompt_seed=502,
                          rollout_seed=503, score_seqs=256, score_len=768, score_masked=512,
                          reward_p=0.3, reward_seed=504),
+    # not one of the five: the shape of the paper's pass@1 judge (Sec. 5, the demo's evaluation):
+    # one question, one completion - decode at batch 1, bound by latency, not by bandwidth.
+    "halfb_pass1": Workload("halfb_pass1", HALF_B, weight_seed=201, n_prompts=1, group=1,
+                            prompt_len=128, n_new=256, temperature=1.0, prompt_seed=602,
+                            rollout_seed=603),
 }
 
 
