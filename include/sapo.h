@@ -244,6 +244,67 @@ int sapo_clipped_surrogate(const float* logp_new, const float* logp_old, const u
                            void* stream);
 
 /*
+ * The local policy update (Algorithm 1, the PolicyGradient step; Sec. 4.2: GRPO with the KL weight
+ * at zero, the clipped surrogate above, Adam with its default hyper-parameters: learning rate
+ * 1e-3, beta1 0.9, beta2 0.999, eps 1e-8, no weight decay).
+ *
+ * A trainer owns fp32 master copies of every tensor of the model (embedding, projection matrices,
+ * RMSNorm gains, the LM head when it is untied), their gradient and the two Adam moments: four
+ * times the model in fp32, allocated by sapo_trainer_create and released by sapo_trainer_destroy.
+ *   cfg, tensors, n_tensors   as for sapo_weights_create (device pointers, element type per
+ *                             cfg->dtype, gains fp32); bf16 values become the fp32 masters unchanged.
+ *                             head_dim at most 128.  A model with projection biases is not
+ *                             supported (the biases would stay untrained).
+ *   opt                       Adam's constants, or NULL for the defaults named above
+ * Complete once `stream` has been synchronised.
+ */
+typedef struct { float lr, beta1, beta2, eps; } sapo_adam_config;
+typedef struct sapo_trainer sapo_trainer; /* opaque, library-owned */
+int sapo_trainer_create(const sapo_model_config* cfg, const void* const* tensors, int n_tensors,
+                        const sapo_adam_config* opt, void* stream, sapo_trainer** out);
+void sapo_trainer_destroy(sapo_trainer* tr);
+/* Workspace of one update over S sequences of T tokens (every layer's activations are kept for the
+ * backward pass: about 4 (4 d + 2 Hq hd + 2 Hkv hd + 3 F) bytes per token and layer); 0 on invalid
+ * arguments (T < 2 or T > max_seq). */
+size_t sapo_trainer_workspace_bytes(const sapo_trainer* tr, int S, int T);
+/*
+ * One update on the training set: teacher-forced forward pass under the masters, loss =
+ * sapo_clipped_surrogate(logp_new, logp_old, mask, advantages), backward pass, one Adam step on
+ * every tensor.
+ *   tokens           dev int32 [S, T]   the assembled training set (prompt + completion per row)
+ *   completion_mask  dev uint8 [S, T]   a set entry at t = 0 has no prediction behind it: it enters the
+ *                                       loss with logp_new = 0 and carries no gradient
+ *   logp_old         dev fp32 [S, T]    log-probs of the policy that is being improved (the scoring
+ *                                       call's output); read where the mask is set
+ *   advantages       dev fp32 [S]
+ *   out_loss         dev fp32 [1]       the loss before the step
+ *   out_logp_new     dev fp32 [S, T] or NULL: the log-probs under the masters before the step (0 where
+ *                                       the mask is clear)
+ *   workspace        dev, >= sapo_trainer_workspace_bytes(tr, S, T), 256-byte aligned
+ * fp32 arithmetic throughout, every sum in a fixed order (no atomics): the same call on the same
+ * state gives the same bits.  Asynchronous on `stream`; the trainer's state is updated in place, so
+ * calls on one trainer must not overlap.  Errors: SAPO_EINVAL (NULL, sizes, eps), SAPO_EWORKSPACE.
+ */
+int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const uint8_t* completion_mask,
+                       const float* logp_old, const float* advantages, int S, int T, float eps_low,
+                       float eps_high, float* out_loss, float* out_logp_new, void* workspace,
+                       size_t workspace_bytes, void* stream);
+/*
+ * The masters in the model's storage type, for a new sapo_weights_create (the policy the next
+ * round's rollouts are generated with): tensors_out is a host array of n_tensors device buffers in
+ * the order and with the sizes of `tensors` above; matrices are written as cfg->dtype (bf16: round
+ * to nearest even), gains as fp32.
+ */
+int sapo_trainer_export(const sapo_trainer* tr, void* const* tensors_out, int n_tensors, void* stream);
+/* Number of Adam steps taken (-1 for NULL). */
+int sapo_trainer_steps(const sapo_trainer* tr);
+/*
+ * Test hook: copies one tensor of the trainer's state to out (dev fp32 [n], n = the tensor's element
+ * count).  what: 0 masters, 1 the last update's gradient, 2 / 3 Adam's first / second moment.
+ */
+int sapo_trainer_read(const sapo_trainer* tr, int what, int tensor, float* out, size_t n, void* stream);
+
+/*
  * Test hook: the sampler's noise.  out[i] = g for (seed, seq, step, v = v0 + i), i < n.
  * out dev fp32 [n].
  */

@@ -36,6 +36,18 @@ static int fail(int code, const char* fmt, ...) {
 
 extern "C" const char* sapo_last_error(void) { return g_err.c_str(); }
 
+namespace sapo {
+int set_error(int code, const char* fmt, ...) {   // for the other translation units with entry points
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof(buf), fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+}  // namespace sapo
+
 // ---------------------------------------------------------------------------------------
 // per-kernel timing with HIP events (see launch() in common.h)
 // ---------------------------------------------------------------------------------------

@@ -1,0 +1,796 @@
+// The local policy update of a SAPO node (Algorithm 1, the PolicyGradient step; Sec. 4.2: GRPO without a
+// KL term, asymmetric clipping, Adam with its default hyper-parameters): kernels, orchestration, C ABI.
+//
+// Everything here is fp32 on row-major buffers: master parameters, activations, gradients and the two
+// Adam moments.  One update = forward pass over the whole training set with every layer's activations
+// kept (HBM is large enough: about 80 KB per token and layer for the 0.5B shape), the clipped surrogate,
+// the backward pass, one Adam step.  No atomics: every sum has a fixed order, so an update is
+// reproducible bit for bit.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <vector>
+
+#include "train.h"
+
+using namespace sapo;
+
+#define T_CK(expr)                                                                                     \
+  do {                                                                                                 \
+    hipError_t e__ = (expr);                                                                           \
+    if (e__ != hipSuccess)                                                                             \
+      return set_error(SAPO_EHIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__), __FILE__, __LINE__); \
+  } while (0)
+
+namespace {
+
+// ---------------------------------------------------------------------------------------
+// C[M, N] (ldc) = beta * C + op(A) op(B), fp32.  op(A) is M x K: A[m * lda + k], or A[k * lda + m] when
+// TA; op(B) is K x N: B[k * ldb + n], or B[n * ldb + k] when TB.  64 x 64 tile per workgroup of 256
+// threads, 4 x 4 outputs per thread, 16-deep k steps staged through LDS.  The three forms used:
+//   y = x W^T (TA 0, TB 1), dx = dy W (0, 0), dW = dy^T x (1, 0).
+// ---------------------------------------------------------------------------------------
+constexpr int kTM = 64, kTN = 64, kTK = 16, kPitch = 68;
+
+template <int TA, int TB>
+__global__ void __launch_bounds__(256) k_sgemm(const float* __restrict__ A, int lda, const float* __restrict__ B, int ldb,
+                                               float* __restrict__ C, int ldc, int M, int N, int K, float beta) {
+  __shared__ __align__(16) float As[kTK][kPitch];
+  __shared__ __align__(16) float Bs[kTK][kPitch];
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  const int m0 = blockIdx.y * kTM, n0 = blockIdx.x * kTN;
+  float acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+  for (int k0 = 0; k0 < K; k0 += kTK) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int e = tid + 256 * i;
+      {
+        const int mm = TA ? (e & 63) : (e >> 4), kk = TA ? (e >> 6) : (e & 15);
+        const int m = m0 + mm, k = k0 + kk;
+        float v = 0.f;
+        if (m < M && k < K) v = TA ? A[(size_t)k * lda + m] : A[(size_t)m * lda + k];
+        As[kk][mm] = v;
+      }
+      {
+        const int nn = TB ? (e >> 4) : (e & 63), kk = TB ? (e & 15) : (e >> 6);
+        const int n = n0 + nn, k = k0 + kk;
+        float v = 0.f;
+        if (n < N && k < K) v = TB ? B[(size_t)n * ldb + k] : B[(size_t)k * ldb + n];
+        Bs[kk][nn] = v;
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < kTK; ++kk) {
+      const float4 a = *(const float4*)&As[kk][ty * 4];
+      const float4 b = *(const float4*)&Bs[kk][tx * 4];
+      const float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + ty * 4 + i;
+    if (m >= M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = n0 + tx * 4 + j;
+      if (n >= N) continue;
+      float* c = C + (size_t)m * ldc + n;
+      *c = (beta != 0.f) ? fmaf(beta, *c, acc[i][j]) : acc[i][j];
+    }
+  }
+}
+
+template <int TA, int TB>
+hipError_t sgemm(const float* A, int lda, const float* B, int ldb, float* C, int ldc, int M, int N, int K, float beta,
+                 hipStream_t st) {
+  if (M <= 0 || N <= 0 || K <= 0) return hipErrorInvalidValue;
+  return launch(KID_GEMM_GENERIC, k_sgemm<TA, TB>, dim3((N + kTN - 1) / kTN, (M + kTM - 1) / kTM), dim3(256), 0, st, A, lda, B,
+                ldb, C, ldc, M, N, K, beta);
+}
+
+__device__ __forceinline__ float block_sum256(float v, float* red) {
+  v = wave_reduce_sum(v);
+  __syncthreads();   // red may still be read from a previous call
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+__device__ __forceinline__ float block_max256(float v, float* red) {
+  v = wave_reduce_max(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+
+// ---------------------------------------------------------------------------------------
+// storage type <-> fp32 masters
+// ---------------------------------------------------------------------------------------
+__global__ void k_bf16_to_f32(const bf16* __restrict__ src, float* __restrict__ dst, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = (float)src[i];
+}
+__global__ void k_f32_to_bf16(const float* __restrict__ src, bf16* __restrict__ dst, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = from_f32<bf16>(src[i]);   // round to nearest even
+}
+
+// ---------------------------------------------------------------------------------------
+// forward pieces
+// ---------------------------------------------------------------------------------------
+// token ids outside [0, V) are clamped into it (a caller's mistake must not become a wild access)
+__device__ __forceinline__ int clamp_token(int t, int V) { return min(max(t, 0), V - 1); }
+
+__global__ void __launch_bounds__(256) k_embed_rows(const int32_t* __restrict__ tokens, const float* __restrict__ embed,
+                                                    float* __restrict__ h, int d, int V) {
+  const size_t m = blockIdx.x;
+  const float* src = embed + (size_t)clamp_token(tokens[m], V) * d;
+  for (int i = threadIdx.x; i < d; i += 256) h[m * d + i] = src[i];
+}
+
+// xn = h * rstd * gain, rstd = 1 / sqrt(mean(h^2) + eps); one workgroup per row
+__global__ void __launch_bounds__(256) k_rmsnorm_fwd(const float* __restrict__ h, const float* __restrict__ gain, float eps,
+                                                     int d, float* __restrict__ xn, float* __restrict__ rstd) {
+  __shared__ float red[4];
+  const size_t m = blockIdx.x;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) { const float v = h[m * d + i]; ss = fmaf(v, v, ss); }
+  ss = block_sum256(ss, red);
+  const float r = 1.0f / sqrtf(ss / (float)d + eps);
+  if (threadIdx.x == 0) rstd[m] = r;
+  for (int i = threadIdx.x; i < d; i += 256) xn[m * d + i] = h[m * d + i] * r * gain[i];
+}
+
+// Rotary embedding in place on the query and key heads of qkv[M, (Hq + 2 Hkv) hd]; position = row % T.
+// dir = +1 rotates by the angle, -1 by its negative (the transpose: what the backward pass applies).
+__global__ void k_rope(float* __restrict__ qkv, const float2* __restrict__ rope, int T, int n_rot_heads, int hd, int row_len,
+                       float dir, size_t total) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const int half = hd >> 1;
+  const int i = (int)(idx % half);
+  const int head = (int)((idx / half) % n_rot_heads);
+  const size_t m = idx / ((size_t)half * n_rot_heads);
+  const float2 cs = rope[(size_t)(m % T) * half + i];
+  float* p = qkv + m * row_len + (size_t)head * hd + i;
+  const float x1 = p[0], x2 = p[half], s = cs.y * dir;
+  p[0] = x1 * cs.x - x2 * s;
+  p[half] = x2 * cs.x + x1 * s;
+}
+
+// Causal grouped-query attention, one wave per (query position, query head, sequence).
+//   qkv[M, q + 2 kv] (rotated q and k), out[M, q], lse[S, Hq, T] = log sum_j exp(s_ij).
+// Scores of the visible keys go through LDS (T floats); lanes run over keys for the scores and over
+// the head dimension for the weighted sum.
+__global__ void __launch_bounds__(64) k_attn_fwd(const float* __restrict__ qkv, int T, int hq, int hkv, int hd,
+                                                 float* __restrict__ out, float* __restrict__ lse) {
+  extern __shared__ float sc[];   // [T]
+  const int i = blockIdx.x, h = blockIdx.y, s = blockIdx.z, lane = threadIdx.x;
+  const int rep = hq / hkv, kvh = h / rep;
+  const int qd = hq * hd, kvd = hkv * hd, row_len = qd + 2 * kvd;
+  const size_t row0 = (size_t)s * T;
+  const float* q = qkv + (row0 + i) * row_len + (size_t)h * hd;
+  const float scale = 1.0f / sqrtf((float)hd);
+  float mx = -INFINITY;
+  for (int j = lane; j <= i; j += 64) {
+    const float* k = qkv + (row0 + j) * row_len + qd + (size_t)kvh * hd;
+    float a = 0.f;
+    for (int e = 0; e < hd; ++e) a = fmaf(q[e], k[e], a);
+    a *= scale;
+    sc[j] = a;
+    mx = fmaxf(mx, a);
+  }
+  mx = wave_reduce_max(mx);
+  float sum = 0.f;
+  for (int j = lane; j <= i; j += 64) {
+    const float p = expf(sc[j] - mx);
+    sc[j] = p;
+    sum += p;
+  }
+  sum = wave_reduce_sum(sum);
+  __syncthreads();
+  const float inv = 1.0f / sum;
+  if (lane == 0) lse[((size_t)s * hq + h) * T + i] = mx + logf(sum);
+  for (int e = lane; e < hd; e += 64) {
+    float o = 0.f;
+    for (int j = 0; j <= i; ++j) o = fmaf(sc[j], qkv[(row0 + j) * row_len + qd + kvd + (size_t)kvh * hd + e], o);
+    out[(row0 + i) * qd + (size_t)h * hd + e] = o * inv;
+  }
+}
+
+// act = silu(gate) * up from gu[M, 2F] (gate columns first)
+__global__ void k_swiglu_fwd(const float* __restrict__ gu, float* __restrict__ act, int F, size_t total) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const size_t m = idx / F;
+  const int f = (int)(idx % F);
+  const float g = gu[m * 2 * F + f], u = gu[m * 2 * F + F + f];
+  act[idx] = g / (1.0f + expf(-g)) * u;
+}
+
+// ---------------------------------------------------------------------------------------
+// LM head rows.  Row r = (s, t) of the final-normed states predicts tokens[s, t + 1].
+// k_logp_rows : lse[r] and logp_new[s, t + 1] (masked positions only) from one chunk of logits.
+// k_dlogits   : logits -> d loss / d logits = w * (onehot(target) - softmax), w = dlogp[s, t + 1]
+//               (rows with w = 0, and the last row of every sequence, become zero).
+// One workgroup per row of the chunk.
+// ---------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_logp_rows(const float* __restrict__ logits, int V, int r0, int T,
+                                                   const int32_t* __restrict__ tokens, const uint8_t* __restrict__ mask,
+                                                   float* __restrict__ lse, float* __restrict__ logp_new) {
+  __shared__ float red[4];
+  const int r = r0 + blockIdx.x;
+  const int t = r % T;
+  if (t == T - 1 || !mask[r + 1]) return;   // uniform over the workgroup
+  const float* z = logits + (size_t)blockIdx.x * V;
+  float mx = -INFINITY;
+  for (int v = threadIdx.x; v < V; v += 256) mx = fmaxf(mx, z[v]);
+  mx = block_max256(mx, red);
+  float sum = 0.f;
+  for (int v = threadIdx.x; v < V; v += 256) sum += expf(z[v] - mx);
+  sum = block_sum256(sum, red);
+  if (threadIdx.x == 0) {
+    const float l = mx + logf(sum);
+    lse[r] = l;
+    logp_new[r + 1] = z[clamp_token(tokens[r + 1], V)] - l;
+  }
+}
+__global__ void __launch_bounds__(256) k_dlogits(float* __restrict__ logits, int V, int r0, int T,
+                                                 const int32_t* __restrict__ tokens, const uint8_t* __restrict__ mask,
+                                                 const float* __restrict__ lse, const float* __restrict__ dlogp) {
+  const int r = r0 + blockIdx.x;
+  const int t = r % T;
+  float* z = logits + (size_t)blockIdx.x * V;
+  const float w = (t == T - 1 || !mask[r + 1]) ? 0.f : dlogp[r + 1];
+  if (w == 0.f) {
+    for (int v = threadIdx.x; v < V; v += 256) z[v] = 0.f;
+    return;
+  }
+  const float l = lse[r];
+  const int target = clamp_token(tokens[r + 1], V);
+  for (int v = threadIdx.x; v < V; v += 256) z[v] = w * ((v == target ? 1.f : 0.f) - expf(z[v] - l));
+}
+
+// ---------------------------------------------------------------------------------------
+// backward pieces
+// ---------------------------------------------------------------------------------------
+// RMSNorm: dh (+)= rstd * gain * dxn - rstd^3 * h * mean_j(dxn_j gain_j h_j); one workgroup per row.
+__global__ void __launch_bounds__(256) k_rmsnorm_bwd(const float* __restrict__ dxn, const float* __restrict__ h,
+                                                     const float* __restrict__ rstd, const float* __restrict__ gain, int d,
+                                                     float* __restrict__ dh, int accumulate) {
+  __shared__ float red[4];
+  const size_t m = blockIdx.x;
+  float dot = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) dot = fmaf(dxn[m * d + i] * gain[i], h[m * d + i], dot);
+  dot = block_sum256(dot, red);
+  const float r = rstd[m];
+  const float c = r * r * r * dot / (float)d;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    const float g = r * gain[i] * dxn[m * d + i] - c * h[m * d + i];
+    dh[m * d + i] = accumulate ? dh[m * d + i] + g : g;
+  }
+}
+// d gain_i = sum_m dxn[m, i] h[m, i] rstd[m]: partial sums over blocks of 256 rows, then over the blocks in order
+__global__ void __launch_bounds__(256) k_gain_grad_partial(const float* __restrict__ dxn, const float* __restrict__ h,
+                                                           const float* __restrict__ rstd, int M, int d,
+                                                           float* __restrict__ part) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= d) return;
+  const int m0 = blockIdx.y * 256, m1 = min(M, m0 + 256);
+  float s = 0.f;
+  for (int m = m0; m < m1; ++m) s = fmaf(dxn[(size_t)m * d + i] * h[(size_t)m * d + i], rstd[m], s);
+  part[(size_t)blockIdx.y * d + i] = s;
+}
+__global__ void __launch_bounds__(256) k_gain_grad_finish(const float* __restrict__ part, int n_part, int d,
+                                                          float* __restrict__ dgain) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= d) return;
+  float s = 0.f;
+  for (int p = 0; p < n_part; ++p) s += part[(size_t)p * d + i];
+  dgain[i] = s;
+}
+
+// dgu from dact: d gate = dact * up * sig(g) (1 + g (1 - sig(g))), d up = dact * silu(g)
+__global__ void k_swiglu_bwd(const float* __restrict__ dact, const float* __restrict__ gu, float* __restrict__ dgu, int F,
+                             size_t total) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const size_t m = idx / F;
+  const int f = (int)(idx % F);
+  const float g = gu[m * 2 * F + f], u = gu[m * 2 * F + F + f], da = dact[idx];
+  const float sg = 1.0f / (1.0f + expf(-g));
+  dgu[m * 2 * F + f] = da * u * sg * (1.0f + g * (1.0f - sg));
+  dgu[m * 2 * F + F + f] = da * g * sg;
+}
+
+// Attention backward, queries: one wave per (query position i, query head, sequence).
+//   p_ij = exp(s_ij - lse_i); delta_i = dO_i . O_i; dS_ij = p_ij (dO_i . v_j - delta_i); dq_i = sum_j dS_ij k_j / sqrt(hd)
+// writes dq into dqkv's query columns and delta[S, Hq, T].
+__global__ void __launch_bounds__(64) k_attn_bwd_q(const float* __restrict__ qkv, const float* __restrict__ out,
+                                                   const float* __restrict__ dout, const float* __restrict__ lse, int T, int hq,
+                                                   int hkv, int hd, float* __restrict__ dqkv, float* __restrict__ delta) {
+  extern __shared__ float ds[];   // [T]
+  const int i = blockIdx.x, h = blockIdx.y, s = blockIdx.z, lane = threadIdx.x;
+  const int rep = hq / hkv, kvh = h / rep;
+  const int qd = hq * hd, kvd = hkv * hd, row_len = qd + 2 * kvd;
+  const size_t row0 = (size_t)s * T;
+  const float* q = qkv + (row0 + i) * row_len + (size_t)h * hd;
+  const float* dO = dout + (row0 + i) * qd + (size_t)h * hd;
+  const float* O = out + (row0 + i) * qd + (size_t)h * hd;
+  const float scale = 1.0f / sqrtf((float)hd);
+  float dl = 0.f;
+  for (int e = lane; e < hd; e += 64) dl = fmaf(dO[e], O[e], dl);
+  dl = wave_reduce_sum(dl);
+  const float l = lse[((size_t)s * hq + h) * T + i];
+  if (lane == 0) delta[((size_t)s * hq + h) * T + i] = dl;
+  for (int j = lane; j <= i; j += 64) {
+    const float* k = qkv + (row0 + j) * row_len + qd + (size_t)kvh * hd;
+    const float* v = k + kvd;
+    float a = 0.f, dp = 0.f;
+    for (int e = 0; e < hd; ++e) { a = fmaf(q[e], k[e], a); dp = fmaf(dO[e], v[e], dp); }
+    ds[j] = expf(a * scale - l) * (dp - dl);
+  }
+  __syncthreads();
+  for (int e = lane; e < hd; e += 64) {
+    float g = 0.f;
+    for (int j = 0; j <= i; ++j) g = fmaf(ds[j], qkv[(row0 + j) * row_len + qd + (size_t)kvh * hd + e], g);
+    dqkv[(row0 + i) * row_len + (size_t)h * hd + e] = g * scale;
+  }
+}
+// Attention backward, keys and values: one wave per (key position j, KV head, sequence); the query heads of
+// the group and the query positions i >= j are walked in a fixed order.
+//   dk_j = sum_{h, i} dS_ij q_i / sqrt(hd);   dv_j = sum_{h, i} p_ij dO_i
+__global__ void __launch_bounds__(64) k_attn_bwd_kv(const float* __restrict__ qkv, const float* __restrict__ dout,
+                                                    const float* __restrict__ lse, const float* __restrict__ delta, int T,
+                                                    int hq, int hkv, int hd, float* __restrict__ dqkv) {
+  extern __shared__ float sm[];   // p[T], ds[T]
+  float* pj = sm;
+  float* dsj = sm + T;
+  const int j = blockIdx.x, kvh = blockIdx.y, s = blockIdx.z, lane = threadIdx.x;
+  const int rep = hq / hkv;
+  const int qd = hq * hd, kvd = hkv * hd, row_len = qd + 2 * kvd;
+  const size_t row0 = (size_t)s * T;
+  const float* k = qkv + (row0 + j) * row_len + qd + (size_t)kvh * hd;
+  const float* v = k + kvd;
+  const float scale = 1.0f / sqrtf((float)hd);
+  float dk[2] = {0.f, 0.f}, dv[2] = {0.f, 0.f};   // head dims lane, lane + 64 (hd <= 128)
+  for (int hh = 0; hh < rep; ++hh) {
+    const int h = kvh * rep + hh;
+    __syncthreads();
+    for (int i = j + lane; i < T; i += 64) {
+      const float* q = qkv + (row0 + i) * row_len + (size_t)h * hd;
+      const float* dO = dout + (row0 + i) * qd + (size_t)h * hd;
+      float a = 0.f, dp = 0.f;
+      for (int e = 0; e < hd; ++e) { a = fmaf(q[e], k[e], a); dp = fmaf(dO[e], v[e], dp); }
+      const size_t li = ((size_t)s * hq + h) * T + i;
+      const float p = expf(a * scale - lse[li]);
+      pj[i] = p;
+      dsj[i] = p * (dp - delta[li]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      const int e = lane + 64 * c;
+      if (e >= hd) continue;
+      float gk = 0.f, gv = 0.f;
+      for (int i = j; i < T; ++i) {
+        gk = fmaf(dsj[i], qkv[(row0 + i) * row_len + (size_t)h * hd + e], gk);
+        gv = fmaf(pj[i], dout[(row0 + i) * qd + (size_t)h * hd + e], gv);
+      }
+      dk[c] += gk * scale;
+      dv[c] += gv;
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < 2; ++c) {
+    const int e = lane + 64 * c;
+    if (e >= hd) continue;
+    dqkv[(row0 + j) * row_len + qd + (size_t)kvh * hd + e] = dk[c];
+    dqkv[(row0 + j) * row_len + qd + kvd + (size_t)kvh * hd + e] = dv[c];
+  }
+}
+
+// Embedding rows: dE[tokens[m]] += dh[m], rows taken in order m = 0, 1, ... by the thread that owns the column.
+__global__ void __launch_bounds__(256) k_embed_bwd(const int32_t* __restrict__ tokens, const float* __restrict__ dh, int M, int d,
+                                                   int V, float* __restrict__ dE) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= d) return;
+  for (int m = 0; m < M; ++m) {
+    float* p = dE + (size_t)clamp_token(tokens[m], V) * d + i;
+    *p += dh[(size_t)m * d + i];
+  }
+}
+
+// Adam (Kingma & Ba, Algorithm 1): c1 = 1 - beta1^t, c2 = 1 - beta2^t
+__global__ void k_adam(float* __restrict__ theta, const float* __restrict__ g, float* __restrict__ m, float* __restrict__ v,
+                       size_t n, float lr, float beta1, float beta2, float eps, float c1, float c2) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const float gi = g[i];
+  const float mi = beta1 * m[i] + (1.0f - beta1) * gi;
+  const float vi = beta2 * v[i] + (1.0f - beta2) * gi * gi;
+  m[i] = mi;
+  v[i] = vi;
+  theta[i] -= lr * (mi / c1) / (sqrtf(vi / c2) + eps);
+}
+
+unsigned blocks256(size_t n) { return (unsigned)((n + 255) / 256); }
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------
+// the trainer
+// ---------------------------------------------------------------------------------------
+struct sapo_trainer {
+  sapo_model_config cfg;
+  sapo_adam_config opt;
+  int t = 0;                      // Adam steps taken
+  int device = 0;
+  size_t n_params = 0;
+  float* theta = nullptr;         // [n_params] masters, tensors back to back in tensor-list order
+  float* grad = nullptr;
+  float* m = nullptr;
+  float* v = nullptr;
+  float2* rope = nullptr;         // [max_seq][hd / 2] (cos, sin)
+  std::vector<size_t> off, len;   // per tensor
+};
+
+namespace {
+
+struct Dims {
+  size_t d, q, kv, nqkv, F, V;
+  int L;
+  explicit Dims(const sapo_model_config& c)
+      : d(c.d_model), q((size_t)c.n_q_heads * c.head_dim), kv((size_t)c.n_kv_heads * c.head_dim), nqkv(q + 2 * kv), F(c.d_ff),
+        V(c.vocab), L(c.n_layers) {}
+};
+
+int n_tensors_of(const sapo_model_config& c) { return 1 + 9 * c.n_layers + 1 + (c.tied_embeddings ? 0 : 1); }
+
+void tensor_sizes(const sapo_model_config& c, std::vector<size_t>& len) {
+  const Dims D(c);
+  len.clear();
+  len.push_back(D.V * D.d);
+  for (int l = 0; l < D.L; ++l) {
+    const size_t s[9] = {D.d, D.q * D.d, D.kv * D.d, D.kv * D.d, D.d * D.q, D.d, D.F * D.d, D.F * D.d, D.d * D.F};
+    for (size_t x : s) len.push_back(x);
+  }
+  len.push_back(D.d);
+  if (!c.tied_embeddings) len.push_back(D.V * D.d);
+}
+
+// rows of logits held at once: about 512 MB, at least 64 rows
+size_t lm_chunk_rows(const Dims& D, size_t M) {
+  size_t r = ((size_t)512 << 20) / (D.V * sizeof(float));
+  if (r < 64) r = 64;
+  return r < M ? r : M;
+}
+
+struct Arena {
+  char* base;
+  size_t off;
+  template <typename T> T* take(size_t n) {
+    off = (off + 255) & ~(size_t)255;
+    T* p = base ? (T*)(base + off) : nullptr;
+    off += n * sizeof(T);
+    return p;
+  }
+};
+
+struct LayerActs {
+  float *h, *r1, *xn, *qkv, *lse, *ao, *h2, *r2, *xn2, *gu, *act;
+};
+struct TrainPlan {
+  std::vector<LayerActs> layer;
+  float *h_last, *rf, *xf;                      // final residual rows, their rstd, final-normed rows
+  float *dh, *dx, *dact, *dgu, *dao, *dqkv;     // backward temporaries
+  float *delta, *gpart, *logits, *row_lse, *logp_new, *dlogp, *loss;
+  void* sur_ws;
+  size_t chunk;
+  size_t bytes;
+};
+
+void make_plan(const sapo_model_config& c, size_t S, size_t T, char* base, TrainPlan& p) {
+  const Dims D(c);
+  const size_t M = S * T;
+  Arena A{base, 0};
+  p.layer.resize(D.L);
+  for (int l = 0; l < D.L; ++l) {
+    LayerActs& a = p.layer[l];
+    a.h = A.take<float>(M * D.d);
+    a.r1 = A.take<float>(M);
+    a.xn = A.take<float>(M * D.d);
+    a.qkv = A.take<float>(M * D.nqkv);
+    a.lse = A.take<float>(S * c.n_q_heads * T);
+    a.ao = A.take<float>(M * D.q);
+    a.h2 = A.take<float>(M * D.d);
+    a.r2 = A.take<float>(M);
+    a.xn2 = A.take<float>(M * D.d);
+    a.gu = A.take<float>(M * 2 * D.F);
+    a.act = A.take<float>(M * D.F);
+  }
+  p.h_last = A.take<float>(M * D.d);
+  p.rf = A.take<float>(M);
+  p.xf = A.take<float>(M * D.d);
+  p.dh = A.take<float>(M * D.d);
+  p.dx = A.take<float>(M * D.d);
+  p.dact = A.take<float>(M * D.F);
+  p.dgu = A.take<float>(M * 2 * D.F);
+  p.dao = A.take<float>(M * D.q);
+  p.dqkv = A.take<float>(M * D.nqkv);
+  p.delta = A.take<float>(S * c.n_q_heads * T);
+  p.gpart = A.take<float>(((M + 255) / 256) * D.d);
+  p.chunk = lm_chunk_rows(D, M);
+  p.logits = A.take<float>(p.chunk * D.V);
+  p.row_lse = A.take<float>(M);
+  p.logp_new = A.take<float>(M);
+  p.dlogp = A.take<float>(M);
+  p.loss = A.take<float>(4);
+  p.sur_ws = A.take<char>(g_surrogate_workspace_bytes());
+  p.bytes = (A.off + 255) & ~(size_t)255;
+}
+
+int check_cfg(const sapo_model_config* c) {
+  if (!c) return set_error(SAPO_EINVAL, "cfg is NULL");
+  if (c->n_layers <= 0 || c->d_model <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 || c->d_ff <= 0 ||
+      c->vocab <= 0 || c->max_seq <= 0)
+    return set_error(SAPO_EINVAL, "model sizes must be positive");
+  if (c->n_q_heads % c->n_kv_heads != 0) return set_error(SAPO_ESHAPE, "n_q_heads must be a multiple of n_kv_heads");
+  if (c->head_dim % 2 != 0 || c->head_dim > 128) return set_error(SAPO_ESHAPE, "head_dim must be even and at most 128");
+  if (c->dtype != SAPO_DTYPE_F32 && c->dtype != SAPO_DTYPE_BF16) return set_error(SAPO_EINVAL, "unknown dtype");
+  if (!(c->rms_eps > 0.f) || !(c->rope_theta > 0.f)) return set_error(SAPO_EINVAL, "rms_eps and rope_theta must be > 0");
+  return SAPO_OK;
+}
+
+bool gain_tensor(const sapo_model_config& c, int i) {
+  if (i == 0) return false;
+  const int last_layer_tensor = 9 * c.n_layers;
+  if (i <= last_layer_tensor) { const int k = (i - 1) % 9; return k == 0 || k == 5; }
+  return i == last_layer_tensor + 1;
+}
+
+}  // namespace
+
+extern "C" void sapo_trainer_destroy(sapo_trainer* tr) {
+  if (!tr) return;
+  (void)hipSetDevice(tr->device);
+  for (void* p : {(void*)tr->theta, (void*)tr->grad, (void*)tr->m, (void*)tr->v, (void*)tr->rope})
+    if (p) (void)hipFree(p);
+  delete tr;
+}
+
+extern "C" int sapo_trainer_create(const sapo_model_config* cfg, const void* const* tensors, int n_tensors,
+                                   const sapo_adam_config* opt, void* stream, sapo_trainer** out) {
+  if (!out) return set_error(SAPO_EINVAL, "out is NULL");
+  *out = nullptr;
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  if (!tensors) return set_error(SAPO_EINVAL, "tensors is NULL");
+  if (n_tensors != n_tensors_of(*cfg))
+    return set_error(SAPO_EINVAL, "n_tensors is %d, expected %d", n_tensors, n_tensors_of(*cfg));
+  for (int i = 0; i < n_tensors; ++i)
+    if (!tensors[i]) return set_error(SAPO_EINVAL, "tensor %d is NULL", i);
+  sapo_adam_config o{1e-3f, 0.9f, 0.999f, 1e-8f};
+  if (opt) o = *opt;
+  if (!(o.lr > 0.f) || !(o.beta1 >= 0.f && o.beta1 < 1.f) || !(o.beta2 >= 0.f && o.beta2 < 1.f) || !(o.eps > 0.f))
+    return set_error(SAPO_EINVAL, "Adam needs lr > 0, beta1 and beta2 in [0, 1), eps > 0");
+  hipStream_t st = (hipStream_t)stream;
+  sapo_trainer* tr = new sapo_trainer;
+  tr->cfg = *cfg;
+  tr->opt = o;
+  (void)hipGetDevice(&tr->device);
+  tensor_sizes(*cfg, tr->len);
+  tr->off.resize(tr->len.size());
+  size_t n = 0;
+  for (size_t i = 0; i < tr->len.size(); ++i) { tr->off[i] = n; n += tr->len[i]; }
+  tr->n_params = n;
+  auto bail = [&](int code) { sapo_trainer_destroy(tr); return code; };
+  for (float** p : {&tr->theta, &tr->grad, &tr->m, &tr->v}) {
+    hipError_t e = hipMalloc((void**)p, n * sizeof(float));
+    if (e != hipSuccess) return bail(set_error(SAPO_EHIP, "hipMalloc of %zu bytes failed: %s", n * sizeof(float), hipGetErrorString(e)));
+  }
+  for (int i = 0; i < n_tensors; ++i) {
+    float* dst = tr->theta + tr->off[i];
+    hipError_t e;
+    if (cfg->dtype == SAPO_DTYPE_F32 || gain_tensor(*cfg, i))
+      e = hipMemcpyAsync(dst, tensors[i], tr->len[i] * sizeof(float), hipMemcpyDeviceToDevice, st);
+    else
+      e = launch(KID_MISC, k_bf16_to_f32, dim3(blocks256(tr->len[i])), dim3(256), 0, st, (const bf16*)tensors[i], dst, tr->len[i]);
+    if (e != hipSuccess) return bail(set_error(SAPO_EHIP, "copy of tensor %d failed: %s", i, hipGetErrorString(e)));
+  }
+  for (float* p : {tr->grad, tr->m, tr->v}) {
+    hipError_t e = g_fill_f32(p, 0.f, n, st);
+    if (e != hipSuccess) return bail(set_error(SAPO_EHIP, "fill failed: %s", hipGetErrorString(e)));
+  }
+  const int half = cfg->head_dim / 2;
+  std::vector<float2> tab((size_t)cfg->max_seq * half);
+  for (int pos = 0; pos < cfg->max_seq; ++pos)
+    for (int i = 0; i < half; ++i) {
+      const double ang = (double)pos * pow((double)cfg->rope_theta, -2.0 * i / cfg->head_dim);
+      tab[(size_t)pos * half + i] = make_float2((float)cos(ang), (float)sin(ang));
+    }
+  hipError_t e = hipMalloc((void**)&tr->rope, tab.size() * sizeof(float2));
+  if (e == hipSuccess) e = hipMemcpy(tr->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice);
+  if (e != hipSuccess) return bail(set_error(SAPO_EHIP, "rotary table: %s", hipGetErrorString(e)));
+  *out = tr;
+  return SAPO_OK;
+}
+
+extern "C" size_t sapo_trainer_workspace_bytes(const sapo_trainer* tr, int S, int T) {
+  if (!tr || S <= 0 || T < 2 || T > tr->cfg.max_seq) return 0;
+  TrainPlan p;
+  make_plan(tr->cfg, (size_t)S, (size_t)T, nullptr, p);
+  return p.bytes;
+}
+
+extern "C" int sapo_trainer_steps(const sapo_trainer* tr) { return tr ? tr->t : -1; }
+
+extern "C" int sapo_trainer_read(const sapo_trainer* tr, int what, int tensor, float* out, size_t n, void* stream) {
+  if (!tr || !out) return set_error(SAPO_EINVAL, "NULL argument");
+  if (tensor < 0 || tensor >= (int)tr->len.size()) return set_error(SAPO_EINVAL, "tensor index %d out of range", tensor);
+  if (n != tr->len[tensor]) return set_error(SAPO_EINVAL, "tensor %d has %zu elements, not %zu", tensor, tr->len[tensor], n);
+  const float* src = what == 0 ? tr->theta : what == 1 ? tr->grad : what == 2 ? tr->m : what == 3 ? tr->v : nullptr;
+  if (!src) return set_error(SAPO_EINVAL, "what must be 0 (parameters), 1 (gradient), 2 or 3 (Adam moments)");
+  T_CK(hipMemcpyAsync(out, src + tr->off[tensor], n * sizeof(float), hipMemcpyDeviceToDevice, (hipStream_t)stream));
+  return SAPO_OK;
+}
+
+extern "C" int sapo_trainer_export(const sapo_trainer* tr, void* const* tensors_out, int n_tensors, void* stream) {
+  if (!tr || !tensors_out) return set_error(SAPO_EINVAL, "NULL argument");
+  if (n_tensors != (int)tr->len.size()) return set_error(SAPO_EINVAL, "n_tensors is %d, expected %zu", n_tensors, tr->len.size());
+  hipStream_t st = (hipStream_t)stream;
+  for (int i = 0; i < n_tensors; ++i) {
+    if (!tensors_out[i]) return set_error(SAPO_EINVAL, "tensor %d is NULL", i);
+    const float* src = tr->theta + tr->off[i];
+    if (tr->cfg.dtype == SAPO_DTYPE_F32 || gain_tensor(tr->cfg, i))
+      T_CK(hipMemcpyAsync(tensors_out[i], src, tr->len[i] * sizeof(float), hipMemcpyDeviceToDevice, st));
+    else
+      T_CK(launch(KID_MISC, k_f32_to_bf16, dim3(blocks256(tr->len[i])), dim3(256), 0, st, src, (bf16*)tensors_out[i], tr->len[i]));
+  }
+  return SAPO_OK;
+}
+
+extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const uint8_t* completion_mask,
+                                  const float* logp_old, const float* advantages, int S_, int T_, float eps_low,
+                                  float eps_high, float* out_loss, float* out_logp_new, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+  if (!tr || !tokens || !completion_mask || !logp_old || !advantages || !out_loss || !workspace)
+    return set_error(SAPO_EINVAL, "NULL argument");
+  if (S_ <= 0 || T_ < 2) return set_error(SAPO_EINVAL, "S must be positive and T at least 2");
+  if (T_ > tr->cfg.max_seq) return set_error(SAPO_EINVAL, "T = %d exceeds max_seq = %d", T_, tr->cfg.max_seq);
+  if (T_ > 8192 || S_ > 65535) return set_error(SAPO_EINVAL, "at most 65535 sequences of at most 8192 tokens");
+  if (!(eps_low >= 0.f && eps_low < 1.f) || !(eps_high >= 0.f)) return set_error(SAPO_EINVAL, "eps_low in [0, 1), eps_high >= 0");
+  const sapo_model_config& c = tr->cfg;
+  const Dims D(c);
+  const size_t S = S_, T = T_, M = S * T;
+  if (M * D.V >= ((size_t)1 << 40) || M >= ((size_t)1 << 30)) return set_error(SAPO_EINVAL, "batch too large");
+  TrainPlan p;
+  make_plan(c, S, T, (char*)workspace, p);
+  if (workspace_bytes < p.bytes) return set_error(SAPO_EWORKSPACE, "workspace is %zu bytes, %zu needed", workspace_bytes, p.bytes);
+  hipStream_t st = (hipStream_t)stream;
+  const int d = (int)D.d, q = (int)D.q, kv = (int)D.kv, nqkv = (int)D.nqkv, F = (int)D.F, V = (int)D.V;
+  const int hq = c.n_q_heads, hkv = c.n_kv_heads, hd = c.head_dim;
+  const int Mi = (int)M;
+  auto TH = [&](int tensor) { return tr->theta + tr->off[tensor]; };
+  auto GR = [&](int tensor) { return tr->grad + tr->off[tensor]; };
+  const int t_final = 1 + 9 * D.L, t_head = c.tied_embeddings ? 0 : t_final + 1;
+  const size_t attn_lds = T * sizeof(float);
+
+  // ---- forward, every activation kept
+  float* h = p.layer[0].h;
+  T_CK(launch(KID_EMBED, k_embed_rows, dim3(Mi), dim3(256), 0, st, tokens, (const float*)TH(0), h, d, V));
+  for (int l = 0; l < D.L; ++l) {
+    const LayerActs& a = p.layer[l];
+    const int t0 = 1 + 9 * l;   // attn_norm, wq, wk, wv, wo, ffn_norm, w_gate, w_up, w_down
+    T_CK(launch(KID_RMSNORM, k_rmsnorm_fwd, dim3(Mi), dim3(256), 0, st, (const float*)a.h, (const float*)TH(t0), c.rms_eps, d,
+                a.xn, a.r1));
+    T_CK((sgemm<0, 1>(a.xn, d, TH(t0 + 1), d, a.qkv, nqkv, Mi, nqkv, d, 0.f, st)));   // wq, wk, wv are adjacent
+    {
+      const size_t total = M * (size_t)(hq + hkv) * (hd / 2);
+      T_CK(launch(KID_ROPE_APPEND, k_rope, dim3(blocks256(total)), dim3(256), 0, st, a.qkv, (const float2*)tr->rope, (int)T,
+                  hq + hkv, hd, nqkv, 1.0f, total));
+    }
+    T_CK(launch(KID_ATTN_GENERIC, k_attn_fwd, dim3((unsigned)T, hq, (unsigned)S), dim3(64), attn_lds, st, (const float*)a.qkv,
+                (int)T, hq, hkv, hd, a.ao, a.lse));
+    T_CK(hipMemcpyAsync(a.h2, a.h, M * D.d * sizeof(float), hipMemcpyDeviceToDevice, st));
+    T_CK((sgemm<0, 1>(a.ao, q, TH(t0 + 4), q, a.h2, d, Mi, d, q, 1.f, st)));
+    T_CK(launch(KID_RMSNORM, k_rmsnorm_fwd, dim3(Mi), dim3(256), 0, st, (const float*)a.h2, (const float*)TH(t0 + 5), c.rms_eps,
+                d, a.xn2, a.r2));
+    T_CK((sgemm<0, 1>(a.xn2, d, TH(t0 + 6), d, a.gu, 2 * F, Mi, 2 * F, d, 0.f, st)));   // w_gate, w_up are adjacent
+    T_CK(launch(KID_SWIGLU, k_swiglu_fwd, dim3(blocks256(M * D.F)), dim3(256), 0, st, (const float*)a.gu, a.act, F, M * D.F));
+    float* h_next = (l + 1 < D.L) ? p.layer[l + 1].h : p.h_last;
+    T_CK(hipMemcpyAsync(h_next, a.h2, M * D.d * sizeof(float), hipMemcpyDeviceToDevice, st));
+    T_CK((sgemm<0, 1>(a.act, F, TH(t0 + 8), F, h_next, d, Mi, d, F, 1.f, st)));
+  }
+  T_CK(launch(KID_RMSNORM, k_rmsnorm_fwd, dim3(Mi), dim3(256), 0, st, (const float*)p.h_last, (const float*)TH(t_final),
+              c.rms_eps, d, p.xf, p.rf));
+
+  // ---- LM head, first pass: log-probs of the taken tokens
+  T_CK(g_fill_f32(p.logp_new, 0.f, M, st));
+  for (size_t r0 = 0; r0 < M; r0 += p.chunk) {
+    const int R = (int)((M - r0 < p.chunk) ? M - r0 : p.chunk);
+    T_CK((sgemm<0, 1>(p.xf + r0 * D.d, d, TH(t_head), d, p.logits, V, R, V, d, 0.f, st)));
+    T_CK(launch(KID_SCORE_ROWS, k_logp_rows, dim3(R), dim3(256), 0, st, (const float*)p.logits, V, (int)r0, (int)T, tokens,
+                completion_mask, p.row_lse, p.logp_new));
+  }
+  // ---- loss and d loss / d logp (the surrogate of sapo_clipped_surrogate)
+  T_CK(g_surrogate_loss(p.logp_new, logp_old, completion_mask, advantages, S_, T_, eps_low, eps_high, p.loss, p.dlogp, p.sur_ws,
+                        st));
+  T_CK(hipMemcpyAsync(out_loss, p.loss, sizeof(float), hipMemcpyDeviceToDevice, st));
+  if (out_logp_new) T_CK(hipMemcpyAsync(out_logp_new, p.logp_new, M * sizeof(float), hipMemcpyDeviceToDevice, st));
+
+  // ---- backward
+  T_CK(g_fill_f32(tr->grad, 0.f, tr->n_params, st));
+  // LM head, second pass: d logits, then d xf (into p.dx) and d head
+  for (size_t r0 = 0; r0 < M; r0 += p.chunk) {
+    const int R = (int)((M - r0 < p.chunk) ? M - r0 : p.chunk);
+    T_CK((sgemm<0, 1>(p.xf + r0 * D.d, d, TH(t_head), d, p.logits, V, R, V, d, 0.f, st)));
+    T_CK(launch(KID_SCORE_ROWS, k_dlogits, dim3(R), dim3(256), 0, st, p.logits, V, (int)r0, (int)T, tokens, completion_mask,
+                (const float*)p.row_lse, (const float*)p.dlogp));
+    T_CK((sgemm<0, 0>(p.logits, V, TH(t_head), d, p.dx + r0 * D.d, d, R, d, V, 0.f, st)));
+    T_CK((sgemm<1, 0>(p.logits, V, p.xf + r0 * D.d, d, GR(t_head), d, V, d, R, 1.f, st)));
+  }
+  const int n_gpart = (Mi + 255) / 256;
+  auto norm_bwd = [&](const float* dxn, const float* hin, const float* rstd, int gain_tensor_idx, int accumulate) -> hipError_t {
+    hipError_t e = launch(KID_MISC, k_gain_grad_partial, dim3((d + 255) / 256, n_gpart), dim3(256), 0, st, dxn, hin, rstd, Mi, d,
+                          p.gpart);
+    if (e != hipSuccess) return e;
+    e = launch(KID_MISC, k_gain_grad_finish, dim3((d + 255) / 256), dim3(256), 0, st, (const float*)p.gpart, n_gpart, d,
+               GR(gain_tensor_idx));
+    if (e != hipSuccess) return e;
+    return launch(KID_RMSNORM, k_rmsnorm_bwd, dim3(Mi), dim3(256), 0, st, dxn, hin, rstd, (const float*)TH(gain_tensor_idx), d,
+                  p.dh, accumulate);
+  };
+  T_CK(norm_bwd(p.dx, p.h_last, p.rf, t_final, 0));
+  for (int l = D.L - 1; l >= 0; --l) {
+    const LayerActs& a = p.layer[l];
+    const int t0 = 1 + 9 * l;
+    // down projection
+    T_CK((sgemm<0, 0>(p.dh, d, TH(t0 + 8), F, p.dact, F, Mi, F, d, 0.f, st)));
+    T_CK((sgemm<1, 0>(p.dh, d, a.act, F, GR(t0 + 8), F, d, F, Mi, 0.f, st)));
+    T_CK(launch(KID_SWIGLU, k_swiglu_bwd, dim3(blocks256(M * D.F)), dim3(256), 0, st, (const float*)p.dact, (const float*)a.gu,
+                p.dgu, F, M * D.F));
+    // gate / up projections
+    T_CK((sgemm<0, 0>(p.dgu, 2 * F, TH(t0 + 6), d, p.dx, d, Mi, d, 2 * F, 0.f, st)));
+    T_CK((sgemm<1, 0>(p.dgu, 2 * F, a.xn2, d, GR(t0 + 6), d, 2 * F, d, Mi, 0.f, st)));
+    T_CK(norm_bwd(p.dx, a.h2, a.r2, t0 + 5, 1));
+    // output projection
+    T_CK((sgemm<0, 0>(p.dh, d, TH(t0 + 4), q, p.dao, q, Mi, q, d, 0.f, st)));
+    T_CK((sgemm<1, 0>(p.dh, d, a.ao, q, GR(t0 + 4), q, d, q, Mi, 0.f, st)));
+    // attention and the rotary embedding
+    T_CK(launch(KID_ATTN_GENERIC, k_attn_bwd_q, dim3((unsigned)T, hq, (unsigned)S), dim3(64), attn_lds, st, (const float*)a.qkv,
+                (const float*)a.ao, (const float*)p.dao, (const float*)a.lse, (int)T, hq, hkv, hd, p.dqkv, p.delta));
+    T_CK(launch(KID_ATTN_GENERIC, k_attn_bwd_kv, dim3((unsigned)T, hkv, (unsigned)S), dim3(64), 2 * attn_lds, st,
+                (const float*)a.qkv, (const float*)p.dao, (const float*)a.lse, (const float*)p.delta, (int)T, hq, hkv, hd,
+                p.dqkv));
+    {
+      const size_t total = M * (size_t)(hq + hkv) * (hd / 2);
+      T_CK(launch(KID_ROPE_APPEND, k_rope, dim3(blocks256(total)), dim3(256), 0, st, p.dqkv, (const float2*)tr->rope, (int)T,
+                  hq + hkv, hd, nqkv, -1.0f, total));
+    }
+    // query / key / value projections
+    T_CK((sgemm<0, 0>(p.dqkv, nqkv, TH(t0 + 1), d, p.dx, d, Mi, d, nqkv, 0.f, st)));
+    T_CK((sgemm<1, 0>(p.dqkv, nqkv, a.xn, d, GR(t0 + 1), d, nqkv, d, Mi, 0.f, st)));
+    T_CK(norm_bwd(p.dx, a.h, a.r1, t0, 1));
+  }
+  T_CK(launch(KID_EMBED, k_embed_bwd, dim3((d + 255) / 256), dim3(256), 0, st, tokens, (const float*)p.dh, Mi, d, V, GR(0)));
+
+  // ---- Adam
+  tr->t += 1;
+  const float c1 = (float)(1.0 - pow((double)tr->opt.beta1, (double)tr->t));
+  const float c2 = (float)(1.0 - pow((double)tr->opt.beta2, (double)tr->t));
+  T_CK(launch(KID_MISC, k_adam, dim3(blocks256(tr->n_params)), dim3(256), 0, st, tr->theta, (const float*)tr->grad, tr->m, tr->v,
+              tr->n_params, tr->opt.lr, tr->opt.beta1, tr->opt.beta2, tr->opt.eps, c1, c2));
+  return SAPO_OK;
+}

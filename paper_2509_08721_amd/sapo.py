@@ -34,6 +34,10 @@ class sapo_model_config(C.Structure):
                 ("max_seq", C.c_int32)]
 
 
+class sapo_adam_config(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float)]
+
+
 _lib = None
 
 
@@ -79,6 +83,21 @@ def load_library() -> C.CDLL:
     lib.sapo_surrogate_workspace_bytes.restype = sz
     lib.sapo_clipped_surrogate.argtypes = [vp, vp, vp, vp, i32, i32, f32, f32, vp, vp, vp, sz, vp]
     lib.sapo_clipped_surrogate.restype = i32
+    lib.sapo_trainer_create.argtypes = [C.POINTER(sapo_model_config), C.POINTER(vp), i32, C.POINTER(sapo_adam_config), vp,
+                                        C.POINTER(vp)]
+    lib.sapo_trainer_create.restype = i32
+    lib.sapo_trainer_destroy.argtypes = [vp]
+    lib.sapo_trainer_destroy.restype = None
+    lib.sapo_trainer_workspace_bytes.argtypes = [vp, i32, i32]
+    lib.sapo_trainer_workspace_bytes.restype = sz
+    lib.sapo_policy_update.argtypes = [vp, vp, vp, vp, vp, i32, i32, f32, f32, vp, vp, vp, sz, vp]
+    lib.sapo_policy_update.restype = i32
+    lib.sapo_trainer_export.argtypes = [vp, C.POINTER(vp), i32, vp]
+    lib.sapo_trainer_export.restype = i32
+    lib.sapo_trainer_steps.argtypes = [vp]
+    lib.sapo_trainer_steps.restype = i32
+    lib.sapo_trainer_read.argtypes = [vp, i32, i32, vp, sz, vp]
+    lib.sapo_trainer_read.restype = i32
     lib.sapo_debug_logits.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, sz, vp]
     lib.sapo_debug_logits.restype = i32
     lib.sapo_debug_gumbel.argtypes = [u64, u32, u32, u32, i32, vp, vp]
@@ -103,6 +122,8 @@ EXPORTED = ["sapo_weights_create", "sapo_weights_destroy", "sapo_weights_uses_mf
             "sapo_score_logprobs", "sapo_score_logprobs_at",
             "sapo_surrogate_workspace_bytes", "sapo_clipped_surrogate",
             "sapo_assemble_workspace_bytes", "sapo_assemble_training_set",
+            "sapo_trainer_create", "sapo_trainer_destroy", "sapo_trainer_workspace_bytes", "sapo_policy_update",
+            "sapo_trainer_export", "sapo_trainer_steps", "sapo_trainer_read",
             "sapo_debug_logits", "sapo_debug_gumbel", "sapo_last_error", "sapo_profile_kernel_count",
             "sapo_profile_kernel_name", "sapo_profile_start", "sapo_profile_stop"]
 
@@ -212,6 +233,12 @@ def _aligned_ptr(t) -> int:
     return (t.data_ptr() + 255) & ~255
 
 
+def _ws_args(t):
+    """(256-byte aligned pointer into a workspace tensor, bytes available from there)."""
+    p = _aligned_ptr(t)
+    return p, max(0, t.numel() * t.element_size() - (p - t.data_ptr()))
+
+
 def sapo_rollout_workspace_bytes(w: Weights, P: int, Lp: int, G: int, max_new: int) -> int:
     return int(load_library().sapo_rollout_workspace_bytes(w.handle, P, Lp, G, max_new))
 
@@ -237,7 +264,7 @@ def sapo_rollout_generate(w: Weights, prompts, G: int, max_new: int, temperature
         workspace = _workspace(nbytes)
     _check(lib.sapo_rollout_generate(w.handle, prompts.data_ptr(), P, Lp, G, max_new, float(temperature),
                                      int(seed), out_tokens.data_ptr(), out_logprobs.data_ptr(),
-                                     _aligned_ptr(workspace), nbytes, _stream_ptr(stream)))
+                                     *_ws_args(workspace), _stream_ptr(stream)))
     return out_tokens, out_logprobs
 
 
@@ -256,7 +283,7 @@ def sapo_rollout_generate_stop(w: Weights, prompts, G: int, max_new: int, temper
         workspace = _workspace(nbytes)
     _check(lib.sapo_rollout_generate_stop(w.handle, prompts.data_ptr(), P, Lp, G, max_new, float(temperature),
                                           int(seed), int(stop_token), out_tokens.data_ptr(), out_logprobs.data_ptr(),
-                                          out_lengths.data_ptr(), _aligned_ptr(workspace), nbytes, _stream_ptr(stream)))
+                                          out_lengths.data_ptr(), *_ws_args(workspace), _stream_ptr(stream)))
     return out_tokens, out_logprobs, out_lengths
 
 
@@ -279,7 +306,7 @@ def sapo_rollout_generate_ragged(w: Weights, prompts, prompt_lens, G: int, max_n
     _check(lib.sapo_rollout_generate_ragged(w.handle, prompts.data_ptr(), lens.ctypes.data, P, Lp, G, max_new,
                                             float(temperature), int(seed), int(stop_token), out_tokens.data_ptr(),
                                             out_logprobs.data_ptr(), None if out_lengths is None else out_lengths.data_ptr(),
-                                            _aligned_ptr(workspace), nbytes, _stream_ptr(stream)))
+                                            *_ws_args(workspace), _stream_ptr(stream)))
     return out_tokens, out_logprobs, out_lengths
 
 
@@ -299,7 +326,7 @@ def sapo_score_logprobs_at(w: Weights, tokens, completion_mask, rewards, G: int,
         workspace = _workspace(nbytes)
     _check(lib.sapo_score_logprobs_at(w.handle, tokens.data_ptr(), completion_mask.data_ptr(), rewards.data_ptr(),
                                       S, T, G, float(temperature), out_logprobs.data_ptr(), out_advantages.data_ptr(),
-                                      _aligned_ptr(workspace), nbytes, _stream_ptr(stream)))
+                                      *_ws_args(workspace), _stream_ptr(stream)))
     return out_logprobs, out_advantages
 
 
@@ -322,7 +349,7 @@ def sapo_score_logprobs(w: Weights, tokens, completion_mask, rewards, G: int, wo
         workspace = _workspace(nbytes)
     _check(lib.sapo_score_logprobs(w.handle, tokens.data_ptr(), completion_mask.data_ptr(), rewards.data_ptr(),
                                    S, T, G, out_logprobs.data_ptr(), out_advantages.data_ptr(),
-                                   _aligned_ptr(workspace), nbytes, _stream_ptr(stream)))
+                                   *_ws_args(workspace), _stream_ptr(stream)))
     return out_logprobs, out_advantages
 
 
@@ -353,7 +380,7 @@ def sapo_assemble_training_set(local_tokens, local_rewards, ext_tokens, ext_rewa
                                           ext_tokens.data_ptr() if pe else None, ext_rewards.data_ptr() if pe else None, pe,
                                           G, T, n_local, n_ext, int(seed), out_t.data_ptr() if n else None,
                                           out_r.data_ptr() if n else None, out_s.data_ptr() if n else None, out_c.data_ptr(),
-                                          _aligned_ptr(workspace), max(nbytes, 256), _stream_ptr(stream)))
+                                          *_ws_args(workspace), _stream_ptr(stream)))
     return out_t, out_r, out_s, out_c
 
 
@@ -380,9 +407,131 @@ def sapo_clipped_surrogate(logp_new, logp_old, completion_mask, advantages, eps_
         workspace = _workspace(nbytes)
     _check(lib.sapo_clipped_surrogate(logp_new.data_ptr(), logp_old.data_ptr(), completion_mask.data_ptr(),
                                       advantages.data_ptr(), S, T, eps_low, eps_high, loss.data_ptr(),
-                                      grad.data_ptr() if want_grad else None, _aligned_ptr(workspace), nbytes,
+                                      grad.data_ptr() if want_grad else None, *_ws_args(workspace),
                                       _stream_ptr(stream)))
     return loss, grad
+
+
+# --------------------------------------------------------------------------- #
+# the local policy update
+# --------------------------------------------------------------------------- #
+LAYER_TENSORS = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
+
+
+def _tensor_order(weights: dict) -> list:
+    order = [weights["embed"]]
+    for lw in weights["layers"]:
+        order += [lw[k] for k in LAYER_TENSORS]
+    order.append(weights["final_norm"])
+    if weights.get("lm_head") is not None:
+        order.append(weights["lm_head"])
+    return order
+
+
+class Trainer:
+    """Owner of a sapo_trainer handle."""
+
+    def __init__(self, handle: int, cfg: sapo_model_config, shape, tensor_shapes):
+        self.handle = handle
+        self.cfg = cfg
+        self.shape = shape
+        self.tensor_shapes = tensor_shapes     # per tensor of the list: (shape tuple, is fp32 gain)
+
+    @property
+    def steps(self) -> int:
+        return int(load_library().sapo_trainer_steps(self.handle))
+
+    def close(self):
+        if self.handle:
+            load_library().sapo_trainer_destroy(self.handle)
+            self.handle = 0
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def sapo_trainer_create(shape, weights: dict, lr: float = 1e-3, beta1: float = 0.9, beta2: float = 0.999,
+                        eps: float = 1e-8, stream=None) -> Trainer:
+    """Upload the tensors of workloads.make_weights() as the trainer's fp32 masters."""
+    torch = _torch()
+    lib = load_library()
+    cfg = make_config(shape)
+    order = _tensor_order(weights)
+    dev = [_to_device(a) for a in order]
+    ptrs = (C.c_void_p * len(dev))(*[t.data_ptr() for t in dev])
+    opt = sapo_adam_config(lr, beta1, beta2, eps)
+    out = C.c_void_p()
+    _check(lib.sapo_trainer_create(C.byref(cfg), ptrs, len(dev), C.byref(opt), _stream_ptr(stream), C.byref(out)))
+    torch.cuda.synchronize()          # the originals in `dev` may be freed after this
+    return Trainer(out.value, cfg, shape, [(tuple(a.shape), a.ndim == 1) for a in order])
+
+
+def sapo_trainer_destroy(tr: Trainer):
+    tr.close()
+
+
+def sapo_trainer_steps(tr: Trainer) -> int:
+    return tr.steps
+
+
+def sapo_trainer_workspace_bytes(tr: Trainer, S: int, T: int) -> int:
+    return int(load_library().sapo_trainer_workspace_bytes(tr.handle, S, T))
+
+
+def sapo_policy_update(tr: Trainer, tokens, completion_mask, logp_old, advantages, eps_low: float = 0.2,
+                       eps_high: float = 0.28, want_logp: bool = True, workspace=None, stream=None):
+    """tokens int32 [S, T], completion_mask uint8 [S, T], logp_old float32 [S, T], advantages float32 [S]
+    (device).  Returns (loss before the step float32 [1], logp_new float32 [S, T] or None)."""
+    torch = _torch()
+    lib = load_library()
+    S, T = int(tokens.shape[0]), int(tokens.shape[1])
+    assert tokens.dtype == torch.int32 and tokens.is_cuda and tokens.is_contiguous()
+    assert completion_mask.dtype == torch.uint8 and completion_mask.is_cuda and completion_mask.is_contiguous()
+    assert tuple(completion_mask.shape) == (S, T)
+    assert logp_old.dtype == torch.float32 and logp_old.is_cuda and logp_old.is_contiguous() and tuple(logp_old.shape) == (S, T)
+    assert advantages.dtype == torch.float32 and advantages.is_cuda and advantages.is_contiguous() and advantages.numel() == S
+    nbytes = sapo_trainer_workspace_bytes(tr, S, T)
+    if workspace is None:
+        workspace = _workspace(nbytes)
+    loss = torch.empty((1,), dtype=torch.float32, device="cuda")
+    logp = torch.empty((S, T), dtype=torch.float32, device="cuda") if want_logp else None
+    _check(lib.sapo_policy_update(tr.handle, tokens.data_ptr(), completion_mask.data_ptr(), logp_old.data_ptr(),
+                                  advantages.data_ptr(), S, T, eps_low, eps_high, loss.data_ptr(),
+                                  logp.data_ptr() if want_logp else None, *_ws_args(workspace),
+                                  _stream_ptr(stream)))
+    return loss, logp
+
+
+def sapo_trainer_read(tr: Trainer, what: int, tensor: int, stream=None):
+    """One tensor of the trainer's state as a float32 device tensor (what: 0 masters, 1 gradient, 2 / 3 moments)."""
+    torch = _torch()
+    shp = tr.tensor_shapes[tensor][0]
+    out = torch.empty(shp, dtype=torch.float32, device="cuda")
+    _check(load_library().sapo_trainer_read(tr.handle, what, tensor, out.data_ptr(), out.numel(), _stream_ptr(stream)))
+    return out
+
+
+def sapo_trainer_export(tr: Trainer, stream=None) -> dict:
+    """The masters in the model's storage type as a weights dict of numpy arrays (the layout of
+    workloads.make_weights(): uint16 bf16 bit patterns for a bf16 model), ready for sapo_weights_create."""
+    torch = _torch()
+    bf16 = tr.cfg.dtype == SAPO_DTYPE_BF16
+    dev = [torch.empty(shp, dtype=torch.float32 if (gain or not bf16) else torch.bfloat16, device="cuda")
+           for shp, gain in tr.tensor_shapes]
+    ptrs = (C.c_void_p * len(dev))(*[t.data_ptr() for t in dev])
+    _check(load_library().sapo_trainer_export(tr.handle, ptrs, len(dev), _stream_ptr(stream)))
+    torch.cuda.synchronize()
+    host = [(t.view(torch.int16).cpu().numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.cpu().numpy()) for t in dev]
+    it = iter(host)
+    w = {"embed": next(it), "layers": []}
+    for _ in range(tr.cfg.n_layers):
+        w["layers"].append({k: next(it) for k in LAYER_TENSORS})
+    w["final_norm"] = next(it)
+    w["lm_head"] = None if tr.cfg.tied_embeddings else next(it)
+    return w
 
 
 def sapo_debug_logits(w: Weights, tokens, positions: Sequence[Sequence[int]], stream=None):

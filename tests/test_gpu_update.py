@@ -1,0 +1,211 @@
+"""GPU parity of the local policy update (sapo_policy_update) against the update oracle:
+log-probs, loss, the gradient of every tensor, the Adam state and the updated parameters."""
+import numpy as np
+import pytest
+
+from paper_2509_08721_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = {
+    # the tiny configuration's model
+    "tiny": W.TINY,
+    # sizes that are not multiples of the GEMM tile, untied head, one KV head
+    "ragged_untied": W.ModelShape(n_layers=1, d_model=96, n_q_heads=3, n_kv_heads=1, head_dim=32, d_ff=80, vocab=300,
+                                  rms_eps=1e-5, rope_theta=1e6, tied_embeddings=False, dtype="f32", max_seq=64),
+    # head_dim 128 (two head dims per lane in the attention kernels)
+    "hd128": W.ModelShape(n_layers=2, d_model=64, n_q_heads=2, n_kv_heads=1, head_dim=128, d_ff=72, vocab=130,
+                          rms_eps=1e-6, rope_theta=1e4, tied_embeddings=True, dtype="f32", max_seq=128),
+}
+
+
+@pytest.fixture(scope="module")
+def sapo():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2509_08721_amd import sapo as S
+    S.load_library()
+    return S
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def make_case(shape, seed, S, T, masked, std=0.25, spread=0.4):
+    """Weights with visible logit differences, gains off 1, advantages of both signs (one zero), old
+    log-probs off the new ones by up to +-spread so that both clip bounds are hit."""
+    from oracle import sapo_update_oracle as U
+    w = W.perturb_norm_gains(W.make_weights(shape, seed, std=std), seed)
+    rng = np.random.default_rng([seed, 1])
+    tokens = rng.integers(0, shape.vocab, size=(S, T)).astype(np.int32)
+    mask = np.zeros((S, T), dtype=np.uint8)
+    mask[:, T - masked:] = 1
+    mask[0, T - masked + 1] = 0
+    adv = rng.standard_normal(S).astype(np.float32)
+    adv[1] = 0.0
+    params = U.parameter_list(shape, w)
+    zero_old = np.zeros((S, T), dtype=np.float32)
+    _, lp, _ = U.loss_and_gradients(shape, params, tokens, mask, zero_old, adv)
+    u = rng.uniform(-spread, spread, size=lp.shape)
+    # keep the ratio exp(-u) clear of the two clip bounds: there fp32 and fp64 may pick different branches
+    near = (np.abs(np.exp(-u) - 1.28) < 0.02) | (np.abs(np.exp(-u) - 0.8) < 0.02)
+    u[near] = 0.0
+    logp_old = (lp + u * (mask != 0)).astype(np.float32)
+    return w, params, tokens, mask, logp_old, adv
+
+
+# the ABI takes Adam's constants as fp32: those values are the constants
+ADAM = dict(lr=float(np.float32(1e-3)), beta1=float(np.float32(0.9)), beta2=float(np.float32(0.999)),
+            eps=float(np.float32(1e-8)))
+
+
+def read_all(sapo, tr, what):
+    return [sapo.sapo_trainer_read(tr, what, i).cpu().numpy().astype(np.float64) for i in range(len(tr.tensor_shapes))]
+
+
+@pytest.mark.parametrize("name,S,T,masked", [("tiny", 8, 32, 16), ("ragged_untied", 3, 13, 9), ("hd128", 4, 70, 33)])
+def test_update_matches_oracle(sapo, name, S, T, masked):
+    import torch
+    from oracle import sapo_update_oracle as U
+    shape = SHAPES[name]
+    w, params, tokens, mask, logp_old, adv = make_case(shape, 700 + len(name), S, T, masked)
+    ref_loss, ref_lp, ref_g = U.loss_and_gradients(shape, params, tokens, mask, logp_old, adv)
+    rho = np.exp(ref_lp - logp_old)[mask != 0]
+    assert (rho > 1.28).any() and (rho < 0.8).any()          # the case exercises both clip bounds
+
+    tr = sapo.sapo_trainer_create(shape, w)
+    assert tr.steps == 0
+    before = read_all(sapo, tr, 0)
+    for a, b in zip(before, params):
+        assert np.array_equal(a, b)                            # masters = the stored values
+    loss, lp = sapo.sapo_policy_update(tr, dev(tokens), dev(mask), dev(logp_old), dev(adv))
+    torch.cuda.synchronize()
+    assert tr.steps == 1
+    # forward: fp32 against fp64
+    assert np.max(np.abs(lp.cpu().numpy() - ref_lp)) < 2e-4
+    assert abs(float(loss.cpu()[0]) - ref_loss) < 1e-4 * max(1.0, abs(ref_loss))
+    # gradient of every tensor
+    g = read_all(sapo, tr, 1)
+    gmax = max(float(np.max(np.abs(x))) for x in ref_g)
+    assert gmax > 1e-4
+    for i, (a, b) in enumerate(zip(g, ref_g)):
+        err = float(np.max(np.abs(a - b)))
+        assert err <= 2e-4 * max(float(np.max(np.abs(b))), 1e-3 * gmax) + 1e-7, (i, err, float(np.max(np.abs(b))))
+    # Adam on the gradient the kernels produced: moments and parameters, fp32 against fp64
+    st = U.AdamState(before)
+    want = U.adam_step(before, g, st, **ADAM)
+    m, v, after = read_all(sapo, tr, 2), read_all(sapo, tr, 3), read_all(sapo, tr, 0)
+    for i in range(len(want)):
+        assert np.allclose(m[i], st.m[i], rtol=1e-6, atol=1e-30)
+        assert np.allclose(v[i], st.v[i], rtol=1e-6, atol=1e-30)
+        assert np.max(np.abs(after[i] - want[i])) <= 1e-6 * 1e-3 + 2e-7 * np.max(np.abs(want[i])), i
+    # a second step on the same batch: bias corrections of t = 2
+    loss2, _ = sapo.sapo_policy_update(tr, dev(tokens), dev(mask), dev(logp_old), dev(adv), want_logp=False)
+    torch.cuda.synchronize()
+    assert tr.steps == 2
+    g2 = read_all(sapo, tr, 1)
+    want2 = U.adam_step(after, g2, st, **ADAM)
+    after2 = read_all(sapo, tr, 0)
+    for i in range(len(want2)):
+        assert np.max(np.abs(after2[i] - want2[i])) <= 1e-6 * 1e-3 + 2e-7 * np.max(np.abs(want2[i])), i
+    # and the second gradient against the oracle at the parameters the first step produced
+    ref_loss2, _, ref_g2 = U.loss_and_gradients(shape, after, tokens, mask, logp_old, adv)
+    assert abs(float(loss2.cpu()[0]) - ref_loss2) < 1e-4 * max(1.0, abs(ref_loss2))
+    for a, b in zip(g2, ref_g2):
+        assert float(np.max(np.abs(a - b))) <= 2e-4 * max(float(np.max(np.abs(b))), 1e-3 * gmax) + 1e-7
+    tr.close()
+
+
+def test_update_is_reproducible_and_lowers_the_loss(sapo):
+    import torch
+    shape = SHAPES["tiny"]
+    w, params, tokens, mask, logp_old, adv = make_case(shape, 811, 6, 24, 12)
+    outs = []
+    for _ in range(2):
+        tr = sapo.sapo_trainer_create(shape, w, lr=1e-4)
+        losses = []
+        for _ in range(4):
+            loss, _ = sapo.sapo_policy_update(tr, dev(tokens), dev(mask), dev(logp_old), dev(adv), want_logp=False)
+            losses.append(float(loss.cpu()[0]))
+        torch.cuda.synchronize()
+        outs.append((losses, [sapo.sapo_trainer_read(tr, 0, i).cpu().numpy() for i in range(len(tr.tensor_shapes))]))
+        tr.close()
+    assert outs[0][0] == outs[1][0]
+    for a, b in zip(outs[0][1], outs[1][1]):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    assert outs[0][0][-1] < outs[0][0][0]
+
+
+def test_bf16_model_masters_and_export(sapo):
+    """A bf16 model: the masters start at the bf16 values, the update runs in fp32, the export rounds to
+    nearest even; the exported tensors build a policy the rollout call accepts."""
+    import torch
+    from oracle import sapo_update_oracle as U
+    from oracle import sapo_oracle as O
+    shape = W.MINI_BF16
+    w = W.make_weights(shape, 909, std=0.05)
+    params = U.parameter_list(shape, w)
+    rng = np.random.default_rng(3)
+    S, T = 4, 20
+    tokens = rng.integers(0, shape.vocab, size=(S, T)).astype(np.int32)
+    mask = np.zeros((S, T), dtype=np.uint8)
+    mask[:, 8:] = 1
+    adv = np.array([1.0, -1.0, 0.5, -0.5], dtype=np.float32)
+    _, lp, _ = U.loss_and_gradients(shape, params, tokens, mask, np.zeros((S, T), np.float32), adv)
+    logp_old = lp.astype(np.float32)
+    ref_loss, _, ref_g = U.loss_and_gradients(shape, params, tokens, mask, logp_old, adv)
+    tr = sapo.sapo_trainer_create(shape, w)
+    loss, lp_new = sapo.sapo_policy_update(tr, dev(tokens), dev(mask), dev(logp_old), dev(adv))
+    torch.cuda.synchronize()
+    assert np.max(np.abs(lp_new.cpu().numpy() - lp)) < 2e-4
+    assert abs(float(loss.cpu()[0]) - ref_loss) < 1e-5
+    g = read_all(sapo, tr, 1)
+    gmax = max(float(np.max(np.abs(x))) for x in ref_g)
+    for a, b in zip(g, ref_g):
+        assert float(np.max(np.abs(a - b))) <= 2e-4 * max(float(np.max(np.abs(b))), 1e-3 * gmax) + 1e-7
+    masters = read_all(sapo, tr, 0)
+    out = sapo.sapo_trainer_export(tr)
+    flat = [out["embed"]] + [lw[k] for lw in out["layers"] for k in sapo.LAYER_TENSORS] + [out["final_norm"]]
+    assert out["lm_head"] is None
+    for a, mst, (shp, gain) in zip(flat, masters, tr.tensor_shapes):
+        assert tuple(a.shape) == shp
+        if gain:
+            assert a.dtype == np.float32 and np.array_equal(a.astype(np.float64), mst)
+        else:
+            assert a.dtype == np.uint16
+            assert np.array_equal(W.bf16_bits_to_f32(a).astype(np.float64), O.round_bf16(mst))
+    # the exported policy differs from the old one and runs
+    assert any(not np.array_equal(a, b) for a, b in zip(flat[1:], [lw[k] for lw in w["layers"] for k in sapo.LAYER_TENSORS]))
+    gw = sapo.sapo_weights_create(shape, out)
+    prompts = rng.integers(0, shape.vocab, size=(2, 8)).astype(np.int32)
+    toks, lps = sapo.sapo_rollout_generate(gw, dev(prompts), 2, 6, 1.0, 5)
+    torch.cuda.synchronize()
+    assert toks.shape == (4, 6) and np.all(np.isfinite(lps.cpu().numpy()))
+    gw.close()
+    tr.close()
+
+
+def test_update_rejects_bad_arguments(sapo):
+    import torch
+    shape = SHAPES["tiny"]
+    w, params, tokens, mask, logp_old, adv = make_case(shape, 5, 2, 8, 4)
+    tr = sapo.sapo_trainer_create(shape, w)
+    assert sapo.sapo_trainer_workspace_bytes(tr, 2, 1) == 0
+    assert sapo.sapo_trainer_workspace_bytes(tr, 0, 8) == 0
+    assert sapo.sapo_trainer_workspace_bytes(tr, 2, shape.max_seq + 1) == 0
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    with pytest.raises(sapo.SapoError) as e:
+        sapo.sapo_policy_update(tr, dev(tokens), dev(mask), dev(logp_old), dev(adv), workspace=small)
+    assert e.value.code == sapo.SAPO_EWORKSPACE or e.value.code == sapo.SAPO_EINVAL
+    with pytest.raises(sapo.SapoError):
+        sapo.sapo_policy_update(tr, dev(tokens), dev(mask), dev(logp_old), dev(adv), eps_low=1.5)
+    assert tr.steps == 0
+    with pytest.raises(sapo.SapoError):
+        sapo.sapo_trainer_create(shape, w, lr=0.0)
+    bad = W.ModelShape(n_layers=1, d_model=32, n_q_heads=3, n_kv_heads=2, head_dim=8, d_ff=16, vocab=32)
+    with pytest.raises(sapo.SapoError):
+        sapo.sapo_trainer_create(bad, W.make_weights(bad, 1))
+    tr.close()
