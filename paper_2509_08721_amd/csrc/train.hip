@@ -33,11 +33,27 @@ namespace {
 // ---------------------------------------------------------------------------------------
 constexpr int kTM = 64, kTN = 64, kTK = 16, kPitch = 68;
 
+// Batched launches (blockIdx.z = batch b): with s = b / nh and h = b % nh the operands start at
+// A + s a1 + h a2, B + s b1 + (h / bdiv) b2, C + s c1 + h c2 (elements).  nh = 1 and zeros: one GEMM.
+struct Batch {
+  int nh = 1, bdiv = 1;
+  long a1 = 0, a2 = 0, b1 = 0, b2 = 0, c1 = 0, c2 = 0;
+  int count = 1;
+};
+__device__ __forceinline__ void batch_offsets(const Batch& bt, const float* __restrict__& A, const float* __restrict__& B,
+                                              float* __restrict__& C) {
+  const int b = blockIdx.z, s = b / bt.nh, h = b % bt.nh;
+  A += s * bt.a1 + h * bt.a2;
+  B += s * bt.b1 + (h / bt.bdiv) * bt.b2;
+  C += s * bt.c1 + h * bt.c2;
+}
+
 template <int TA, int TB>
 __global__ void __launch_bounds__(256) k_sgemm(const float* __restrict__ A, int lda, const float* __restrict__ B, int ldb,
-                                               float* __restrict__ C, int ldc, int M, int N, int K, float beta) {
+                                               float* __restrict__ C, int ldc, int M, int N, int K, float beta, Batch bt) {
   __shared__ __align__(16) float As[kTK][kPitch];
   __shared__ __align__(16) float Bs[kTK][kPitch];
+  batch_offsets(bt, A, B, C);
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
   const int m0 = blockIdx.y * kTM, n0 = blockIdx.x * kTN;
   float acc[4][4];
@@ -91,12 +107,119 @@ __global__ void __launch_bounds__(256) k_sgemm(const float* __restrict__ A, int 
   }
 }
 
+// The same contraction on the matrix cores (v_mfma_f32_32x32x2_f32: fp32 operands, fp32 accumulation), for
+// operands whose sizes and leading dimensions are multiples of 4 and whose bases are 16-byte aligned.
+// 128 x 128 tile per workgroup, 4 waves of 64 x 64 (2 x 2 MFMA tiles), 16-deep k steps, two LDS buffers: the
+// next step's operands are fetched into registers while the current step is multiplied.  LDS rows are k,
+// 160 floats apart, so the two k rows a wave reads at once fall into disjoint banks.
+constexpr int kGM = 128, kGK = 16, kGP = 160;
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+template <int TRANS>   // TRANS 0: src[row * ld + k] (k contiguous); 1: src[k * ld + row] (row contiguous)
+__device__ __forceinline__ void gemm_fetch(const float* __restrict__ src, int ld, int row0, int n_rows, int k0, int K,
+                                           float4 (&r)[2]) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int e = threadIdx.x + 256 * i;
+    r[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (TRANS == 0) {
+      const int row = row0 + (e >> 2), k = k0 + (e & 3) * 4;
+      if (row < n_rows && k < K) r[i] = *(const float4*)(src + (size_t)row * ld + k);
+    } else {
+      const int k = k0 + (e >> 5), row = row0 + (e & 31) * 4;
+      if (row < n_rows && k < K) r[i] = *(const float4*)(src + (size_t)k * ld + row);
+    }
+  }
+}
+template <int TRANS>
+__device__ __forceinline__ void gemm_stage(float (*buf)[kGP], const float4 (&r)[2]) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int e = threadIdx.x + 256 * i;
+    if (TRANS == 0) {
+      const int row = e >> 2, k = (e & 3) * 4;
+      buf[k][row] = r[i].x; buf[k + 1][row] = r[i].y; buf[k + 2][row] = r[i].z; buf[k + 3][row] = r[i].w;
+    } else {
+      *(float4*)&buf[e >> 5][(e & 31) * 4] = r[i];
+    }
+  }
+}
+
+template <int TA, int TB>
+__global__ void __launch_bounds__(256) k_sgemm_mfma(const float* __restrict__ A, int lda, const float* __restrict__ B, int ldb,
+                                                    float* __restrict__ C, int ldc, int M, int N, int K, float beta,
+                                                    Batch bt) {
+  __shared__ __align__(16) float As[2][kGK][kGP];
+  __shared__ __align__(16) float Bs[2][kGK][kGP];
+  batch_offsets(bt, A, B, C);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int m0 = blockIdx.y * kGM, n0 = blockIdx.x * kGM;
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  f32x16_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  float4 ra[2], rb[2];
+  // op(A) rows are m: A is "k contiguous" unless TA; op(B) rows are n: B is "k contiguous" when TB
+  gemm_fetch<TA>(A, lda, m0, M, 0, K, ra);
+  gemm_fetch<TB ? 0 : 1>(B, ldb, n0, N, 0, K, rb);
+  gemm_stage<TA>(As[0], ra);
+  gemm_stage<TB ? 0 : 1>(Bs[0], rb);
+  __syncthreads();
+  const int nk = (K + kGK - 1) / kGK;
+  for (int t = 0; t < nk; ++t) {
+    const int cur = t & 1;
+    if (t + 1 < nk) {
+      gemm_fetch<TA>(A, lda, m0, M, (t + 1) * kGK, K, ra);
+      gemm_fetch<TB ? 0 : 1>(B, ldb, n0, N, (t + 1) * kGK, K, rb);
+    }
+#pragma unroll
+    for (int kk = 0; kk < kGK; kk += 2) {
+      const int kr = kk + (lane >> 5), c = lane & 31;
+      const float a0 = As[cur][kr][wm + c], a1 = As[cur][kr][wm + 32 + c];
+      const float b0 = Bs[cur][kr][wn + c], b1 = Bs[cur][kr][wn + 32 + c];
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+    }
+    if (t + 1 < nk) {
+      gemm_stage<TA>(As[cur ^ 1], ra);
+      gemm_stage<TB ? 0 : 1>(Bs[cur ^ 1], rb);
+    }
+    __syncthreads();
+  }
+  // accumulator v of lane l: row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32 of the 32 x 32 tile
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int n = n0 + wn + j * 32 + (lane & 31);
+      if (n >= N) continue;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int m = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (m >= M) continue;
+        float* c = C + (size_t)m * ldc + n;
+        *c = (beta != 0.f) ? fmaf(beta, *c, acc[i][j][v]) : acc[i][j][v];
+      }
+    }
+}
+
 template <int TA, int TB>
 hipError_t sgemm(const float* A, int lda, const float* B, int ldb, float* C, int ldc, int M, int N, int K, float beta,
-                 hipStream_t st) {
-  if (M <= 0 || N <= 0 || K <= 0) return hipErrorInvalidValue;
-  return launch(KID_GEMM_GENERIC, k_sgemm<TA, TB>, dim3((N + kTN - 1) / kTN, (M + kTM - 1) / kTM), dim3(256), 0, st, A, lda, B,
-                ldb, C, ldc, M, N, K, beta);
+                 hipStream_t st, const Batch& bt = Batch()) {
+  if (M <= 0 || N <= 0 || K <= 0 || bt.count <= 0 || bt.count > 65535) return hipErrorInvalidValue;
+  const long strides = bt.a1 | bt.a2 | bt.b1 | bt.b2;
+  const bool aligned = ((M | N | K | lda | ldb) & 3) == 0 && (strides & 3) == 0 && (((uintptr_t)A | (uintptr_t)B) & 15) == 0;
+  if (aligned && (long)M * N * bt.count >= 128 * 128)
+    return launch(KID_GEMM_GENERIC, k_sgemm_mfma<TA, TB>, dim3((N + kGM - 1) / kGM, (M + kGM - 1) / kGM, bt.count), dim3(256), 0,
+                  st, A, lda, B, ldb, C, ldc, M, N, K, beta, bt);
+  return launch(KID_GEMM_GENERIC, k_sgemm<TA, TB>, dim3((N + kTN - 1) / kTN, (M + kTM - 1) / kTM, bt.count), dim3(256), 0, st, A,
+                lda, B, ldb, C, ldc, M, N, K, beta, bt);
 }
 
 __device__ __forceinline__ float block_sum256(float v, float* red) {
@@ -169,44 +292,30 @@ __global__ void k_rope(float* __restrict__ qkv, const float2* __restrict__ rope,
   p[half] = x2 * cs.x + x1 * s;
 }
 
-// Causal grouped-query attention, one wave per (query position, query head, sequence).
-//   qkv[M, q + 2 kv] (rotated q and k), out[M, q], lse[S, Hq, T] = log sum_j exp(s_ij).
-// Scores of the visible keys go through LDS (T floats); lanes run over keys for the scores and over
-// the head dimension for the weighted sum.
-__global__ void __launch_bounds__(64) k_attn_fwd(const float* __restrict__ qkv, int T, int hq, int hkv, int hd,
-                                                 float* __restrict__ out, float* __restrict__ lse) {
-  extern __shared__ float sc[];   // [T]
-  const int i = blockIdx.x, h = blockIdx.y, s = blockIdx.z, lane = threadIdx.x;
-  const int rep = hq / hkv, kvh = h / rep;
-  const int qd = hq * hd, kvd = hkv * hd, row_len = qd + 2 * kvd;
-  const size_t row0 = (size_t)s * T;
-  const float* q = qkv + (row0 + i) * row_len + (size_t)h * hd;
-  const float scale = 1.0f / sqrtf((float)hd);
+// Causal grouped-query attention through batched GEMMs: scores[s, h] = Q_h K^T (T x T per sequence and
+// query head), the row kernels below, out = P V.  Row r = (s * Hq + h) * T + i of the score buffer.
+// k_softmax_causal: in place, p_ij = softmax_j(scale * s_ij) over j <= i, 0 for j > i; lse[r] = log sum_j exp(scale * s_ij).
+__global__ void __launch_bounds__(64) k_softmax_causal(float* __restrict__ sc, float* __restrict__ lse, int T, float scale) {
+  const size_t r = blockIdx.x;
+  const int i = (int)(r % T), lane = threadIdx.x;
+  float* row = sc + r * T;
   float mx = -INFINITY;
-  for (int j = lane; j <= i; j += 64) {
-    const float* k = qkv + (row0 + j) * row_len + qd + (size_t)kvh * hd;
-    float a = 0.f;
-    for (int e = 0; e < hd; ++e) a = fmaf(q[e], k[e], a);
-    a *= scale;
-    sc[j] = a;
-    mx = fmaxf(mx, a);
-  }
+  for (int j = lane; j <= i; j += 64) mx = fmaxf(mx, row[j] * scale);
   mx = wave_reduce_max(mx);
   float sum = 0.f;
-  for (int j = lane; j <= i; j += 64) {
-    const float p = expf(sc[j] - mx);
-    sc[j] = p;
-    sum += p;
-  }
+  for (int j = lane; j <= i; j += 64) sum += expf(row[j] * scale - mx);
   sum = wave_reduce_sum(sum);
-  __syncthreads();
-  const float inv = 1.0f / sum;
-  if (lane == 0) lse[((size_t)s * hq + h) * T + i] = mx + logf(sum);
-  for (int e = lane; e < hd; e += 64) {
-    float o = 0.f;
-    for (int j = 0; j <= i; ++j) o = fmaf(sc[j], qkv[(row0 + j) * row_len + qd + kvd + (size_t)kvh * hd + e], o);
-    out[(row0 + i) * qd + (size_t)h * hd + e] = o * inv;
-  }
+  const float l = mx + logf(sum);
+  if (lane == 0) lse[r] = l;
+  for (int j = lane; j < T; j += 64) row[j] = (j <= i) ? expf(row[j] * scale - l) : 0.f;
+}
+// the same probabilities from kept log-sum-exps (backward pass): p_ij = exp(scale * s_ij - lse[r]), 0 for j > i
+__global__ void k_probs_from_lse(float* __restrict__ sc, const float* __restrict__ lse, int T, float scale, size_t total) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const size_t r = idx / T;
+  const int j = (int)(idx % T), i = (int)(r % T);
+  sc[idx] = (j <= i) ? expf(sc[idx] * scale - lse[r]) : 0.f;
 }
 
 // act = silu(gate) * up from gu[M, 2F] (gate columns first)
@@ -314,91 +423,26 @@ __global__ void k_swiglu_bwd(const float* __restrict__ dact, const float* __rest
   dgu[m * 2 * F + F + f] = da * g * sg;
 }
 
-// Attention backward, queries: one wave per (query position i, query head, sequence).
-//   p_ij = exp(s_ij - lse_i); delta_i = dO_i . O_i; dS_ij = p_ij (dO_i . v_j - delta_i); dq_i = sum_j dS_ij k_j / sqrt(hd)
-// writes dq into dqkv's query columns and delta[S, Hq, T].
-__global__ void __launch_bounds__(64) k_attn_bwd_q(const float* __restrict__ qkv, const float* __restrict__ out,
-                                                   const float* __restrict__ dout, const float* __restrict__ lse, int T, int hq,
-                                                   int hkv, int hd, float* __restrict__ dqkv, float* __restrict__ delta) {
-  extern __shared__ float ds[];   // [T]
-  const int i = blockIdx.x, h = blockIdx.y, s = blockIdx.z, lane = threadIdx.x;
-  const int rep = hq / hkv, kvh = h / rep;
-  const int qd = hq * hd, kvd = hkv * hd, row_len = qd + 2 * kvd;
-  const size_t row0 = (size_t)s * T;
-  const float* q = qkv + (row0 + i) * row_len + (size_t)h * hd;
-  const float* dO = dout + (row0 + i) * qd + (size_t)h * hd;
-  const float* O = out + (row0 + i) * qd + (size_t)h * hd;
-  const float scale = 1.0f / sqrtf((float)hd);
-  float dl = 0.f;
-  for (int e = lane; e < hd; e += 64) dl = fmaf(dO[e], O[e], dl);
-  dl = wave_reduce_sum(dl);
-  const float l = lse[((size_t)s * hq + h) * T + i];
-  if (lane == 0) delta[((size_t)s * hq + h) * T + i] = dl;
-  for (int j = lane; j <= i; j += 64) {
-    const float* k = qkv + (row0 + j) * row_len + qd + (size_t)kvh * hd;
-    const float* v = k + kvd;
-    float a = 0.f, dp = 0.f;
-    for (int e = 0; e < hd; ++e) { a = fmaf(q[e], k[e], a); dp = fmaf(dO[e], v[e], dp); }
-    ds[j] = expf(a * scale - l) * (dp - dl);
-  }
-  __syncthreads();
-  for (int e = lane; e < hd; e += 64) {
-    float g = 0.f;
-    for (int j = 0; j <= i; ++j) g = fmaf(ds[j], qkv[(row0 + j) * row_len + qd + (size_t)kvh * hd + e], g);
-    dqkv[(row0 + i) * row_len + (size_t)h * hd + e] = g * scale;
-  }
+// Attention backward pieces (the contractions are batched GEMMs):
+// delta[(s Hq + h) T + i] = dO_i . O_i over the head's dims; one wave per (s, i, h)
+__global__ void __launch_bounds__(64) k_attn_delta(const float* __restrict__ dout, const float* __restrict__ out, int T, int hq,
+                                                   int hd, float* __restrict__ delta) {
+  const size_t b = blockIdx.x;            // (s * T + i) * hq + h
+  const int h = (int)(b % hq);
+  const size_t si = b / hq, s = si / T, i = si % T;
+  const float* a = dout + (si * hq + h) * hd;
+  const float* o = out + (si * hq + h) * hd;
+  float d = 0.f;
+  for (int e = threadIdx.x; e < hd; e += 64) d = fmaf(a[e], o[e], d);
+  d = wave_reduce_sum(d);
+  if (threadIdx.x == 0) delta[(s * hq + h) * T + i] = d;
 }
-// Attention backward, keys and values: one wave per (key position j, KV head, sequence); the query heads of
-// the group and the query positions i >= j are walked in a fixed order.
-//   dk_j = sum_{h, i} dS_ij q_i / sqrt(hd);   dv_j = sum_{h, i} p_ij dO_i
-__global__ void __launch_bounds__(64) k_attn_bwd_kv(const float* __restrict__ qkv, const float* __restrict__ dout,
-                                                    const float* __restrict__ lse, const float* __restrict__ delta, int T,
-                                                    int hq, int hkv, int hd, float* __restrict__ dqkv) {
-  extern __shared__ float sm[];   // p[T], ds[T]
-  float* pj = sm;
-  float* dsj = sm + T;
-  const int j = blockIdx.x, kvh = blockIdx.y, s = blockIdx.z, lane = threadIdx.x;
-  const int rep = hq / hkv;
-  const int qd = hq * hd, kvd = hkv * hd, row_len = qd + 2 * kvd;
-  const size_t row0 = (size_t)s * T;
-  const float* k = qkv + (row0 + j) * row_len + qd + (size_t)kvh * hd;
-  const float* v = k + kvd;
-  const float scale = 1.0f / sqrtf((float)hd);
-  float dk[2] = {0.f, 0.f}, dv[2] = {0.f, 0.f};   // head dims lane, lane + 64 (hd <= 128)
-  for (int hh = 0; hh < rep; ++hh) {
-    const int h = kvh * rep + hh;
-    __syncthreads();
-    for (int i = j + lane; i < T; i += 64) {
-      const float* q = qkv + (row0 + i) * row_len + (size_t)h * hd;
-      const float* dO = dout + (row0 + i) * qd + (size_t)h * hd;
-      float a = 0.f, dp = 0.f;
-      for (int e = 0; e < hd; ++e) { a = fmaf(q[e], k[e], a); dp = fmaf(dO[e], v[e], dp); }
-      const size_t li = ((size_t)s * hq + h) * T + i;
-      const float p = expf(a * scale - lse[li]);
-      pj[i] = p;
-      dsj[i] = p * (dp - delta[li]);
-    }
-    __syncthreads();
-#pragma unroll
-    for (int c = 0; c < 2; ++c) {
-      const int e = lane + 64 * c;
-      if (e >= hd) continue;
-      float gk = 0.f, gv = 0.f;
-      for (int i = j; i < T; ++i) {
-        gk = fmaf(dsj[i], qkv[(row0 + i) * row_len + (size_t)h * hd + e], gk);
-        gv = fmaf(pj[i], dout[(row0 + i) * qd + (size_t)h * hd + e], gv);
-      }
-      dk[c] += gk * scale;
-      dv[c] += gv;
-    }
-  }
-#pragma unroll
-  for (int c = 0; c < 2; ++c) {
-    const int e = lane + 64 * c;
-    if (e >= hd) continue;
-    dqkv[(row0 + j) * row_len + qd + (size_t)kvh * hd + e] = dk[c];
-    dqkv[(row0 + j) * row_len + qd + kvd + (size_t)kvh * hd + e] = dv[c];
-  }
+// d(q . k)_ij = scale * p_ij (dP_ij - delta_i), in place over dP
+__global__ void k_dscores(const float* __restrict__ prob, float* __restrict__ dp, const float* __restrict__ delta, int T,
+                          float scale, size_t total) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  dp[idx] = scale * prob[idx] * (dp[idx] - delta[idx / T]);
 }
 
 // Embedding rows: dE[tokens[m]] += dh[m], rows taken in order m = 0, 1, ... by the thread that owns the column.
@@ -470,10 +514,10 @@ void tensor_sizes(const sapo_model_config& c, std::vector<size_t>& len) {
   if (!c.tied_embeddings) len.push_back(D.V * D.d);
 }
 
-// rows of logits held at once: about 512 MB, at least 64 rows
+// rows of logits held at once: about 1 GB, a multiple of the GEMM tile
 size_t lm_chunk_rows(const Dims& D, size_t M) {
-  size_t r = ((size_t)512 << 20) / (D.V * sizeof(float));
-  if (r < 64) r = 64;
+  size_t r = ((size_t)1 << 30) / (D.V * sizeof(float)) / 128 * 128;
+  if (r < 128) r = 128;
   return r < M ? r : M;
 }
 
@@ -495,7 +539,7 @@ struct TrainPlan {
   std::vector<LayerActs> layer;
   float *h_last, *rf, *xf;                      // final residual rows, their rstd, final-normed rows
   float *dh, *dx, *dact, *dgu, *dao, *dqkv;     // backward temporaries
-  float *delta, *gpart, *logits, *row_lse, *logp_new, *dlogp, *loss;
+  float *delta, *prob, *dsc, *gpart, *logits, *row_lse, *logp_new, *dlogp, *loss;
   void* sur_ws;
   size_t chunk;
   size_t bytes;
@@ -530,6 +574,8 @@ void make_plan(const sapo_model_config& c, size_t S, size_t T, char* base, Train
   p.dao = A.take<float>(M * D.q);
   p.dqkv = A.take<float>(M * D.nqkv);
   p.delta = A.take<float>(S * c.n_q_heads * T);
+  p.prob = A.take<float>(S * c.n_q_heads * T * T);
+  p.dsc = A.take<float>(S * c.n_q_heads * T * T);
   p.gpart = A.take<float>(((M + 255) / 256) * D.d);
   p.chunk = lm_chunk_rows(D, M);
   p.logits = A.take<float>(p.chunk * D.V);
@@ -669,7 +715,8 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
     return set_error(SAPO_EINVAL, "NULL argument");
   if (S_ <= 0 || T_ < 2) return set_error(SAPO_EINVAL, "S must be positive and T at least 2");
   if (T_ > tr->cfg.max_seq) return set_error(SAPO_EINVAL, "T = %d exceeds max_seq = %d", T_, tr->cfg.max_seq);
-  if (T_ > 8192 || S_ > 65535) return set_error(SAPO_EINVAL, "at most 65535 sequences of at most 8192 tokens");
+  if (T_ > 8192 || (long)S_ * tr->cfg.n_q_heads > 65535)
+    return set_error(SAPO_EINVAL, "at most 8192 tokens per sequence and 65535 (sequence, query head) pairs");
   if (!(eps_low >= 0.f && eps_low < 1.f) || !(eps_high >= 0.f)) return set_error(SAPO_EINVAL, "eps_low in [0, 1), eps_high >= 0");
   const sapo_model_config& c = tr->cfg;
   const Dims D(c);
@@ -685,7 +732,24 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
   auto TH = [&](int tensor) { return tr->theta + tr->off[tensor]; };
   auto GR = [&](int tensor) { return tr->grad + tr->off[tensor]; };
   const int t_final = 1 + 9 * D.L, t_head = c.tied_embeddings ? 0 : t_final + 1;
-  const size_t attn_lds = T * sizeof(float);
+  const int rep = hq / hkv;
+  const float att_scale = 1.0f / sqrtf((float)hd);
+  const size_t n_sc = S * hq * T * T;
+  const long TT = (long)(T * T), Trow = (long)(T * D.nqkv), Tq = (long)(T * D.q);
+  Batch b_scores, b_pv, b_dp, b_dq, b_dk, b_dv;
+  // per (sequence, query head): Q_h and the group's K -> scores
+  b_scores.nh = hq; b_scores.bdiv = rep; b_scores.count = S_ * hq;
+  b_scores.a1 = Trow; b_scores.a2 = hd; b_scores.b1 = Trow; b_scores.b2 = hd; b_scores.c1 = hq * TT; b_scores.c2 = TT;
+  // P and the group's V -> the head's columns of the attention output
+  b_pv = b_scores; b_pv.a1 = hq * TT; b_pv.a2 = TT; b_pv.c1 = Tq; b_pv.c2 = hd;
+  // dO_h and the group's V -> dP
+  b_dp = b_scores; b_dp.a1 = Tq; b_dp.a2 = hd;
+  // dS and the group's K -> dQ_h
+  b_dq = b_scores; b_dq.a1 = hq * TT; b_dq.a2 = TT; b_dq.c1 = Trow; b_dq.c2 = hd;
+  // per (sequence, KV head), one query head of the group at a time: dS_h^T Q_h -> dK, P_h^T dO_h -> dV
+  b_dk.nh = hkv; b_dk.bdiv = 1; b_dk.count = S_ * hkv;
+  b_dk.a1 = hq * TT; b_dk.a2 = rep * TT; b_dk.b1 = Trow; b_dk.b2 = (long)rep * hd; b_dk.c1 = Trow; b_dk.c2 = hd;
+  b_dv = b_dk; b_dv.b1 = Tq;
 
   // ---- forward, every activation kept
   float* h = p.layer[0].h;
@@ -701,8 +765,10 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
       T_CK(launch(KID_ROPE_APPEND, k_rope, dim3(blocks256(total)), dim3(256), 0, st, a.qkv, (const float2*)tr->rope, (int)T,
                   hq + hkv, hd, nqkv, 1.0f, total));
     }
-    T_CK(launch(KID_ATTN_GENERIC, k_attn_fwd, dim3((unsigned)T, hq, (unsigned)S), dim3(64), attn_lds, st, (const float*)a.qkv,
-                (int)T, hq, hkv, hd, a.ao, a.lse));
+    T_CK((sgemm<0, 1>(a.qkv, nqkv, a.qkv + q, nqkv, p.prob, (int)T, (int)T, (int)T, hd, 0.f, st, b_scores)));
+    T_CK(launch(KID_ATTN_GENERIC, k_softmax_causal, dim3((unsigned)(S * hq * T)), dim3(64), 0, st, p.prob, a.lse, (int)T,
+                att_scale));
+    T_CK((sgemm<0, 0>(p.prob, (int)T, a.qkv + q + kv, nqkv, a.ao, q, (int)T, hd, (int)T, 0.f, st, b_pv)));
     T_CK(hipMemcpyAsync(a.h2, a.h, M * D.d * sizeof(float), hipMemcpyDeviceToDevice, st));
     T_CK((sgemm<0, 1>(a.ao, q, TH(t0 + 4), q, a.h2, d, Mi, d, q, 1.f, st)));
     T_CK(launch(KID_RMSNORM, k_rmsnorm_fwd, dim3(Mi), dim3(256), 0, st, (const float*)a.h2, (const float*)TH(t0 + 5), c.rms_eps,
@@ -769,11 +835,22 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
     T_CK((sgemm<0, 0>(p.dh, d, TH(t0 + 4), q, p.dao, q, Mi, q, d, 0.f, st)));
     T_CK((sgemm<1, 0>(p.dh, d, a.ao, q, GR(t0 + 4), q, d, q, Mi, 0.f, st)));
     // attention and the rotary embedding
-    T_CK(launch(KID_ATTN_GENERIC, k_attn_bwd_q, dim3((unsigned)T, hq, (unsigned)S), dim3(64), attn_lds, st, (const float*)a.qkv,
-                (const float*)a.ao, (const float*)p.dao, (const float*)a.lse, (int)T, hq, hkv, hd, p.dqkv, p.delta));
-    T_CK(launch(KID_ATTN_GENERIC, k_attn_bwd_kv, dim3((unsigned)T, hkv, (unsigned)S), dim3(64), 2 * attn_lds, st,
-                (const float*)a.qkv, (const float*)p.dao, (const float*)a.lse, (const float*)p.delta, (int)T, hq, hkv, hd,
-                p.dqkv));
+    T_CK((sgemm<0, 1>(a.qkv, nqkv, a.qkv + q, nqkv, p.prob, (int)T, (int)T, (int)T, hd, 0.f, st, b_scores)));
+    T_CK(launch(KID_ATTN_GENERIC, k_probs_from_lse, dim3(blocks256(n_sc)), dim3(256), 0, st, p.prob, (const float*)a.lse, (int)T,
+                att_scale, n_sc));
+    T_CK((sgemm<0, 1>(p.dao, q, a.qkv + q + kv, nqkv, p.dsc, (int)T, (int)T, (int)T, hd, 0.f, st, b_dp)));     // dP = dO V^T
+    T_CK(launch(KID_ATTN_GENERIC, k_attn_delta, dim3((unsigned)(M * hq)), dim3(64), 0, st, (const float*)p.dao, (const float*)a.ao,
+                (int)T, hq, hd, p.delta));
+    T_CK(launch(KID_ATTN_GENERIC, k_dscores, dim3(blocks256(n_sc)), dim3(256), 0, st, (const float*)p.prob, p.dsc,
+                (const float*)p.delta, (int)T, att_scale, n_sc));
+    T_CK((sgemm<0, 0>(p.dsc, (int)T, a.qkv + q, nqkv, p.dqkv, nqkv, (int)T, hd, (int)T, 0.f, st, b_dq)));       // dQ = dS K
+    for (int hh = 0; hh < rep; ++hh) {   // the query heads of a group add up in a fixed order
+      const float beta = hh > 0 ? 1.f : 0.f;
+      T_CK((sgemm<1, 0>(p.dsc + (size_t)hh * T * T, (int)T, a.qkv + (size_t)hh * hd, nqkv, p.dqkv + q, nqkv, (int)T, hd, (int)T,
+                        beta, st, b_dk)));                                                                       // dK += dS^T Q
+      T_CK((sgemm<1, 0>(p.prob + (size_t)hh * T * T, (int)T, p.dao + (size_t)hh * hd, q, p.dqkv + q + kv, nqkv, (int)T, hd,
+                        (int)T, beta, st, b_dv)));                                                               // dV += P^T dO
+    }
     {
       const size_t total = M * (size_t)(hq + hkv) * (hd / 2);
       T_CK(launch(KID_ROPE_APPEND, k_rope, dim3(blocks256(total)), dim3(256), 0, st, p.dqkv, (const float2*)tr->rope, (int)T,
