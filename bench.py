@@ -10,7 +10,8 @@ completions, Sec. 4.1 / Sec. 5) on the 0.5B-class decoder with synthetic weights
 Other workloads (--workload): halfb_long (rollout only, long generation), halfb_score_mixed
 (scoring only, half local / half external rollouts; the batch is prepared untimed), onehalfb
 (1.5B-class decoder, rollout + scoring), tiny, halfb_pass1 (one sequence: the latency of a
-decode step at batch 1).
+decode step at batch 1), halfb_update (the local policy update on configuration 2's training set:
+trained tokens/s).
 
 Prints ONE JSON line.
 """
@@ -85,6 +86,102 @@ def per_launch_work(shape, plan, kernel, launches):
     return None, 0.0
 
 
+FP32_MFMA_PEAK_TFLOPS = 157.3
+
+
+def update_flops(shape, S, T, n_chunks_rows):
+    """fp32 multiply-adds x 2 of one policy update as the library runs it: every projection and the LM head
+    three times (forward, d input, d weight), attention as full T x T products (scores twice, P V, dP, dQ,
+    dK, dV)."""
+    M = S * T
+    per_layer = shape.matmul_params_per_layer()
+    proj = 2 * M * 3 * per_layer * shape.n_layers
+    head = 2 * M * 3 * shape.vocab * shape.d_model
+    attn = 2 * 7 * S * shape.n_q_heads * T * T * shape.head_dim * shape.n_layers
+    return proj + head + attn
+
+
+def bench_update(args, wl):
+    """The local policy update on one training set: trained tokens/s of sapo_policy_update."""
+    import torch
+    from paper_2509_08721_amd import sapo, workloads as W
+    shape = wl.shape
+    torch.cuda.set_device(0)
+    t0 = time.time()
+    weights = W.make_weights(shape, wl.weight_seed)
+    S, T, Tm, G = wl.score_seqs, wl.score_len, wl.score_masked, wl.group
+    # the training set: Zipf prompts repeated G times + random completions; old log-probs and advantages from
+    # the scoring call under the same weights (what a node holds when it reaches the update)
+    prompts = W.make_prompts(wl)
+    rng = np.random.default_rng([wl.prompt_seed, 7])
+    comp = rng.integers(0, shape.vocab, size=(S, T - wl.prompt_len)).astype(np.int32)
+    tokens_np = np.concatenate([np.repeat(prompts, G, axis=0), comp], axis=1)
+    mask_np = W.make_completion_mask(S, T, Tm)
+    tokens, mask = torch.from_numpy(tokens_np).cuda(), torch.from_numpy(mask_np).cuda()
+    rewards = torch.from_numpy(W.make_rewards(S, wl.reward_p, wl.reward_seed)).cuda()
+    gw = sapo.sapo_weights_create(shape, weights)
+    logp_old, adv = sapo.sapo_score_logprobs(gw, tokens, mask, rewards, G)
+    torch.cuda.synchronize()
+    gw.close()
+    tr = sapo.sapo_trainer_create(shape, weights)
+    nbytes = sapo.sapo_trainer_workspace_bytes(tr, S, T)
+    ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+    setup_s = time.time() - t0
+    losses = []
+    for _ in range(args.warmup):
+        loss, _ = sapo.sapo_policy_update(tr, tokens, mask, logp_old, adv, want_logp=False, workspace=ws)
+        losses.append(loss)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        loss, _ = sapo.sapo_policy_update(tr, tokens, mask, logp_old, adv, want_logp=False, workspace=ws)
+        losses.append(loss)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t1) / args.steps
+    flops = update_flops(shape, S, T, 0)
+    kernels, roofline = {}, None
+    if not args.no_kernel_profile:
+        sapo.sapo_profile_start()
+        sapo.sapo_policy_update(tr, tokens, mask, logp_old, adv, want_logp=False, workspace=ws)
+        prof = sapo.sapo_profile_stop()
+        for name, (ms, cnt) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
+            kernels[name] = {"launches": cnt, "total_ms": round(ms, 3), "avg_us": round(ms * 1e3 / cnt, 3)}
+        if "k_gemm" in kernels:
+            k = kernels["k_gemm"]
+            ach = flops / (k["total_ms"] * 1e-3) / 1e12
+            k.update(bound="mfma", work_per_launch=flops / k["launches"], achieved=round(ach, 2), unit="TFLOP/s",
+                     frac=round(ach / FP32_MFMA_PEAK_TFLOPS, 4))
+            roofline = {"kernel": "k_sgemm_mfma (all GEMMs of the update)", "bound": "mfma", "achieved": k["achieved"],
+                        "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": k["frac"], "traffic": None,
+                        "avg_us": k["avg_us"], "launches": k["launches"], "work_per_launch": k["work_per_launch"]}
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import sapo_update_oracle as U
+        ncores = len(os.sched_getaffinity(0))
+        big = shape.d_model >= 512
+        s_n, t_n = (1, T) if big else (S, T)
+        params = U.parameter_list(shape, weights)
+        t2 = time.perf_counter()
+        U.loss_and_gradients(shape, params, tokens_np[:s_n, :t_n], W.make_completion_mask(s_n, t_n, 2 * t_n // 3),
+                             np.full((s_n, t_n), -10.0, dtype=np.float32), np.ones(s_n, dtype=np.float32))
+        dtc = time.perf_counter() - t2
+        cpu = {"value": round(s_n * t_n / dtc, 2), "unit": "tokens/s", "cores": ncores, "kind": "oracle",
+               "sample": "torch fp64 autograd oracle: loss and gradient of %d sequence(s) x %d tokens in %.1f s "
+                         "(no optimiser step)" % (s_n, t_n, dtc)}
+    out = {"metric": "trained tokens/s of one policy update (forward + clipped surrogate + backward + Adam)",
+           "value": round(S * T / dt, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(dt * 1e3, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32", "data": "synthetic",
+           "config": {"workload": wl.name, "layers": shape.n_layers, "d_model": shape.d_model, "vocab": shape.vocab,
+                      "seqs": S, "seq_len": T, "masked": Tm, "optimizer": "Adam lr 1e-3 (defaults)",
+                      "weights": "fp32 masters of the bf16 model"},
+           "update_flops": flops, "achieved_TFLOPs": round(flops / dt / 1e12, 2),
+           "workspace_GB": round(nbytes / 2 ** 30, 2), "loss_first": round(float(losses[0].cpu()[0]), 6),
+           "loss_last": round(float(losses[-1].cpu()[0]), 6),
+           "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "setup_s": round(setup_s, 1)}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -110,6 +207,8 @@ def main():
     from paper_2509_08721_amd import sapo, workloads as W
 
     wl = W.WORKLOADS[args.workload]
+    if args.workload.endswith("_update"):
+        return bench_update(args, wl)
     if args.layers > 0:
         wl = replace(wl, shape=replace(wl.shape, n_layers=args.layers))
     if args.new_tokens > 0:

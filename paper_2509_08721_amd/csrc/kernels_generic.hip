@@ -1,6 +1,7 @@
 // Shape-generic kernels: any model shape, fp32 or bf16 storage, plain ALU arithmetic.
 // They run the fp32 configuration and every step that has no tile-aligned MFMA kernel.
 #include "common.h"
+#include "surrogate.h"
 
 namespace sapo {
 
@@ -473,14 +474,6 @@ hipError_t g_advantages(const float* rewards, int S, int G, float* out, hipStrea
 constexpr int kLossBlocks = 256;
 struct LossPartial { double sum; long long count; };
 
-__device__ __forceinline__ float surrogate_term(float ln, float lo, float a, float eps_low, float eps_high, float& rho,
-                                                bool& active) {
-  rho = expf(ln - lo);
-  const float clipped = fminf(fmaxf(rho, 1.0f - eps_low), 1.0f + eps_high);
-  active = a >= 0.f ? (rho <= 1.0f + eps_high) : (rho >= 1.0f - eps_low);
-  return fminf(rho * a, clipped * a);
-}
-
 __global__ void __launch_bounds__(256) k_surrogate_partial(const float* __restrict__ logp_new, const float* __restrict__ logp_old,
                                                            const uint8_t* __restrict__ mask, const float* __restrict__ adv,
                                                            int T, size_t n, float eps_low, float eps_high,
@@ -523,7 +516,7 @@ __global__ void __launch_bounds__(256) k_surrogate_grad(const float* __restrict_
     const float a = adv[i / T];
     float rho; bool act;
     surrogate_term(logp_new[i], logp_old[i], a, eps_low, eps_high, rho, act);
-    if (act) g = (float)(-(double)a * (double)rho / (double)total->count);
+    g = surrogate_dlogp(a, rho, act, total->count);
   }
   out[i] = g;
 }

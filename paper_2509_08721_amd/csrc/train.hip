@@ -12,6 +12,7 @@
 
 #include <vector>
 
+#include "surrogate.h"
 #include "train.h"
 
 using namespace sapo;
@@ -222,6 +223,27 @@ hipError_t sgemm(const float* A, int lda, const float* B, int ldb, float* C, int
                 lda, B, ldb, C, ldc, M, N, K, beta, bt);
 }
 
+// C[Mg, Ng] = op(A) op(B) for a weight gradient (TA 1, TB 0; the contraction runs over the Kg tokens): when the
+// output has too few tiles to fill the chip the token range is split into parts whose products are added in
+// part order by k_sum_parts (declared below).
+__global__ void k_sum_parts(const float* __restrict__ part, int n_part, size_t n, float beta, float* __restrict__ out);
+hipError_t sgemm_wgrad(const float* A, int lda, const float* B, int ldb, float* C, int Mg, int Ng, int Kg, float* parts,
+                       size_t parts_cap, hipStream_t st) {
+  const long tiles = (long)((Mg + kGM - 1) / kGM) * ((Ng + kGM - 1) / kGM);
+  int splits = 1;
+  while (splits < 8 && tiles * splits < 192 && Kg % (splits * 2 * kGK) == 0 && Kg / (splits * 2) >= 256) splits *= 2;
+  if (splits == 1 || (size_t)splits * Mg * Ng > parts_cap || ((Mg | Ng | lda | ldb) & 3) != 0)
+    return sgemm<1, 0>(A, lda, B, ldb, C, Ng, Mg, Ng, Kg, 0.f, st);
+  const int ks = Kg / splits;
+  Batch bt;
+  bt.count = splits;
+  bt.a1 = (long)ks * lda; bt.b1 = (long)ks * ldb; bt.c1 = (long)Mg * Ng;
+  hipError_t e = sgemm<1, 0>(A, lda, B, ldb, parts, Ng, Mg, Ng, ks, 0.f, st, bt);
+  if (e != hipSuccess) return e;
+  const size_t n = (size_t)Mg * Ng;
+  return launch(KID_MISC, k_sum_parts, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const float*)parts, splits, n, 0.f, C);
+}
+
 __device__ __forceinline__ float block_sum256(float v, float* red) {
   v = wave_reduce_sum(v);
   __syncthreads();   // red may still be read from a previous call
@@ -329,46 +351,62 @@ __global__ void k_swiglu_fwd(const float* __restrict__ gu, float* __restrict__ a
 }
 
 // ---------------------------------------------------------------------------------------
-// LM head rows.  Row r = (s, t) of the final-normed states predicts tokens[s, t + 1].
-// k_logp_rows : lse[r] and logp_new[s, t + 1] (masked positions only) from one chunk of logits.
-// k_dlogits   : logits -> d loss / d logits = w * (onehot(target) - softmax), w = dlogp[s, t + 1]
-//               (rows with w = 0, and the last row of every sequence, become zero).
-// One workgroup per row of the chunk.
+// LM head rows.  Row r = (s, t) of the final-normed states predicts tokens[s, t + 1].  One workgroup per row
+// of a chunk of logits: log-sum-exp, logp_new[s, t + 1] = z[target] - lse, the token's surrogate gradient
+// w = d loss / d logp (it needs only this token's log-probs, its sequence's advantage and the number of
+// masked tokens), then in place  logits <- d loss / d logits = w (onehot(target) - softmax).
+// Rows whose target is not masked, and the last row of every sequence, become zero.
 // ---------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_logp_rows(const float* __restrict__ logits, int V, int r0, int T,
-                                                   const int32_t* __restrict__ tokens, const uint8_t* __restrict__ mask,
-                                                   float* __restrict__ lse, float* __restrict__ logp_new) {
+__global__ void __launch_bounds__(256) k_count_mask(const uint8_t* __restrict__ mask, size_t n, long long* __restrict__ out) {
+  __shared__ int part[256];
+  int c = 0;
+  for (size_t i = threadIdx.x; i < n; i += 256) c += mask[i] != 0;
+  part[threadIdx.x] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    long long t = 0;
+    for (int j = 0; j < 256; ++j) t += part[j];
+    *out = t;
+  }
+}
+__global__ void __launch_bounds__(256) k_logp_dlogits(float* __restrict__ logits, int V, int r0, int T,
+                                                      const int32_t* __restrict__ tokens, const uint8_t* __restrict__ mask,
+                                                      const float* __restrict__ logp_old, const float* __restrict__ adv,
+                                                      float eps_low, float eps_high, const long long* __restrict__ n_masked,
+                                                      float* __restrict__ logp_new) {
   __shared__ float red[4];
   const int r = r0 + blockIdx.x;
   const int t = r % T;
-  if (t == T - 1 || !mask[r + 1]) return;   // uniform over the workgroup
-  const float* z = logits + (size_t)blockIdx.x * V;
+  float* z = logits + (size_t)blockIdx.x * V;
+  if (t == T - 1 || !mask[r + 1]) {   // uniform over the workgroup
+    for (int v = threadIdx.x; v < V; v += 256) z[v] = 0.f;
+    return;
+  }
   float mx = -INFINITY;
   for (int v = threadIdx.x; v < V; v += 256) mx = fmaxf(mx, z[v]);
   mx = block_max256(mx, red);
   float sum = 0.f;
   for (int v = threadIdx.x; v < V; v += 256) sum += expf(z[v] - mx);
   sum = block_sum256(sum, red);
-  if (threadIdx.x == 0) {
-    const float l = mx + logf(sum);
-    lse[r] = l;
-    logp_new[r + 1] = z[clamp_token(tokens[r + 1], V)] - l;
-  }
-}
-__global__ void __launch_bounds__(256) k_dlogits(float* __restrict__ logits, int V, int r0, int T,
-                                                 const int32_t* __restrict__ tokens, const uint8_t* __restrict__ mask,
-                                                 const float* __restrict__ lse, const float* __restrict__ dlogp) {
-  const int r = r0 + blockIdx.x;
-  const int t = r % T;
-  float* z = logits + (size_t)blockIdx.x * V;
-  const float w = (t == T - 1 || !mask[r + 1]) ? 0.f : dlogp[r + 1];
-  if (w == 0.f) {
-    for (int v = threadIdx.x; v < V; v += 256) z[v] = 0.f;
-    return;
-  }
-  const float l = lse[r];
+  const float l = mx + logf(sum);
   const int target = clamp_token(tokens[r + 1], V);
-  for (int v = threadIdx.x; v < V; v += 256) z[v] = w * ((v == target ? 1.f : 0.f) - expf(z[v] - l));
+  const float lp = z[target] - l;
+  float rho; bool active;
+  const float a = adv[r / T];
+  surrogate_term(lp, logp_old[r + 1], a, eps_low, eps_high, rho, active);
+  const float w = surrogate_dlogp(a, rho, active, *n_masked);
+  __syncthreads();   // every thread has read z[target]
+  if (threadIdx.x == 0) logp_new[r + 1] = lp;
+  for (int v = threadIdx.x; v < V; v += 256) z[v] = (w == 0.f) ? 0.f : w * ((v == target ? 1.f : 0.f) - expf(z[v] - l));
+}
+
+// out = (beta ? out : 0) + sum over the parts, in part order
+__global__ void k_sum_parts(const float* __restrict__ part, int n_part, size_t n, float beta, float* __restrict__ out) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  float s = beta != 0.f ? beta * out[i] : 0.f;
+  for (int p = 0; p < n_part; ++p) s += part[(size_t)p * n + i];
+  out[i] = s;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -514,9 +552,10 @@ void tensor_sizes(const sapo_model_config& c, std::vector<size_t>& len) {
   if (!c.tied_embeddings) len.push_back(D.V * D.d);
 }
 
-// rows of logits held at once: about 1 GB, a multiple of the GEMM tile
+// rows of logits held at once: about 5 GB (enough rows for the d-input GEMM of the head, whose output is only
+// d_model wide, to fill the chip), a multiple of the GEMM tile
 size_t lm_chunk_rows(const Dims& D, size_t M) {
-  size_t r = ((size_t)1 << 30) / (D.V * sizeof(float)) / 128 * 128;
+  size_t r = ((size_t)5 << 30) / (D.V * sizeof(float)) / 128 * 128;
   if (r < 128) r = 128;
   return r < M ? r : M;
 }
@@ -532,6 +571,10 @@ struct Arena {
   }
 };
 
+// Weight-gradient GEMMs with few output tiles (dW of the attention projections: 49 - 63 tiles of 128 x 128 on 256
+// compute units) are split over the token dimension into up to 8 parts that are added in part order.
+constexpr size_t kSplitParts = (size_t)8 * 192 * 128 * 128;
+
 struct LayerActs {
   float *h, *r1, *xn, *qkv, *lse, *ao, *h2, *r2, *xn2, *gu, *act;
 };
@@ -539,8 +582,10 @@ struct TrainPlan {
   std::vector<LayerActs> layer;
   float *h_last, *rf, *xf;                      // final residual rows, their rstd, final-normed rows
   float *dh, *dx, *dact, *dgu, *dao, *dqkv;     // backward temporaries
-  float *delta, *prob, *dsc, *gpart, *logits, *row_lse, *logp_new, *dlogp, *loss;
+  float *delta, *prob, *dsc, *gpart, *logits, *logp_new, *loss;
   void* sur_ws;
+  long long* n_masked;
+  float* kparts;                                // partial products of the split weight-gradient GEMMs
   size_t chunk;
   size_t bytes;
 };
@@ -579,10 +624,10 @@ void make_plan(const sapo_model_config& c, size_t S, size_t T, char* base, Train
   p.gpart = A.take<float>(((M + 255) / 256) * D.d);
   p.chunk = lm_chunk_rows(D, M);
   p.logits = A.take<float>(p.chunk * D.V);
-  p.row_lse = A.take<float>(M);
   p.logp_new = A.take<float>(M);
-  p.dlogp = A.take<float>(M);
   p.loss = A.take<float>(4);
+  p.n_masked = A.take<long long>(1);
+  p.kparts = A.take<float>(kSplitParts);
   p.sur_ws = A.take<char>(g_surrogate_workspace_bytes());
   p.bytes = (A.off + 255) & ~(size_t)255;
 }
@@ -782,31 +827,25 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
   T_CK(launch(KID_RMSNORM, k_rmsnorm_fwd, dim3(Mi), dim3(256), 0, st, (const float*)p.h_last, (const float*)TH(t_final),
               c.rms_eps, d, p.xf, p.rf));
 
-  // ---- LM head, first pass: log-probs of the taken tokens
+  // ---- LM head, one pass over chunks of rows: logits, log-probs, d logits, then d xf (into p.dx) and d head
+  T_CK(g_fill_f32(tr->grad, 0.f, tr->n_params, st));
   T_CK(g_fill_f32(p.logp_new, 0.f, M, st));
+  T_CK(launch(KID_MISC, k_count_mask, dim3(1), dim3(256), 0, st, completion_mask, M, p.n_masked));
   for (size_t r0 = 0; r0 < M; r0 += p.chunk) {
     const int R = (int)((M - r0 < p.chunk) ? M - r0 : p.chunk);
     T_CK((sgemm<0, 1>(p.xf + r0 * D.d, d, TH(t_head), d, p.logits, V, R, V, d, 0.f, st)));
-    T_CK(launch(KID_SCORE_ROWS, k_logp_rows, dim3(R), dim3(256), 0, st, (const float*)p.logits, V, (int)r0, (int)T, tokens,
-                completion_mask, p.row_lse, p.logp_new));
+    T_CK(launch(KID_SCORE_ROWS, k_logp_dlogits, dim3(R), dim3(256), 0, st, p.logits, V, (int)r0, (int)T, tokens, completion_mask,
+                logp_old, advantages, eps_low, eps_high, (const long long*)p.n_masked, p.logp_new));
+    T_CK((sgemm<0, 0>(p.logits, V, TH(t_head), d, p.dx + r0 * D.d, d, R, d, V, 0.f, st)));
+    T_CK((sgemm<1, 0>(p.logits, V, p.xf + r0 * D.d, d, GR(t_head), d, V, d, R, 1.f, st)));
   }
-  // ---- loss and d loss / d logp (the surrogate of sapo_clipped_surrogate)
-  T_CK(g_surrogate_loss(p.logp_new, logp_old, completion_mask, advantages, S_, T_, eps_low, eps_high, p.loss, p.dlogp, p.sur_ws,
+  // ---- the loss (the surrogate of sapo_clipped_surrogate on the log-probs just computed)
+  T_CK(g_surrogate_loss(p.logp_new, logp_old, completion_mask, advantages, S_, T_, eps_low, eps_high, p.loss, nullptr, p.sur_ws,
                         st));
   T_CK(hipMemcpyAsync(out_loss, p.loss, sizeof(float), hipMemcpyDeviceToDevice, st));
   if (out_logp_new) T_CK(hipMemcpyAsync(out_logp_new, p.logp_new, M * sizeof(float), hipMemcpyDeviceToDevice, st));
 
-  // ---- backward
-  T_CK(g_fill_f32(tr->grad, 0.f, tr->n_params, st));
-  // LM head, second pass: d logits, then d xf (into p.dx) and d head
-  for (size_t r0 = 0; r0 < M; r0 += p.chunk) {
-    const int R = (int)((M - r0 < p.chunk) ? M - r0 : p.chunk);
-    T_CK((sgemm<0, 1>(p.xf + r0 * D.d, d, TH(t_head), d, p.logits, V, R, V, d, 0.f, st)));
-    T_CK(launch(KID_SCORE_ROWS, k_dlogits, dim3(R), dim3(256), 0, st, p.logits, V, (int)r0, (int)T, tokens, completion_mask,
-                (const float*)p.row_lse, (const float*)p.dlogp));
-    T_CK((sgemm<0, 0>(p.logits, V, TH(t_head), d, p.dx + r0 * D.d, d, R, d, V, 0.f, st)));
-    T_CK((sgemm<1, 0>(p.logits, V, p.xf + r0 * D.d, d, GR(t_head), d, V, d, R, 1.f, st)));
-  }
+  // ---- backward through the layers
   const int n_gpart = (Mi + 255) / 256;
   auto norm_bwd = [&](const float* dxn, const float* hin, const float* rstd, int gain_tensor_idx, int accumulate) -> hipError_t {
     hipError_t e = launch(KID_MISC, k_gain_grad_partial, dim3((d + 255) / 256, n_gpart), dim3(256), 0, st, dxn, hin, rstd, Mi, d,
@@ -824,16 +863,16 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
     const int t0 = 1 + 9 * l;
     // down projection
     T_CK((sgemm<0, 0>(p.dh, d, TH(t0 + 8), F, p.dact, F, Mi, F, d, 0.f, st)));
-    T_CK((sgemm<1, 0>(p.dh, d, a.act, F, GR(t0 + 8), F, d, F, Mi, 0.f, st)));
+    T_CK(sgemm_wgrad(p.dh, d, a.act, F, GR(t0 + 8), d, F, Mi, p.kparts, kSplitParts, st));
     T_CK(launch(KID_SWIGLU, k_swiglu_bwd, dim3(blocks256(M * D.F)), dim3(256), 0, st, (const float*)p.dact, (const float*)a.gu,
                 p.dgu, F, M * D.F));
     // gate / up projections
     T_CK((sgemm<0, 0>(p.dgu, 2 * F, TH(t0 + 6), d, p.dx, d, Mi, d, 2 * F, 0.f, st)));
-    T_CK((sgemm<1, 0>(p.dgu, 2 * F, a.xn2, d, GR(t0 + 6), d, 2 * F, d, Mi, 0.f, st)));
+    T_CK(sgemm_wgrad(p.dgu, 2 * F, a.xn2, d, GR(t0 + 6), 2 * F, d, Mi, p.kparts, kSplitParts, st));
     T_CK(norm_bwd(p.dx, a.h2, a.r2, t0 + 5, 1));
     // output projection
     T_CK((sgemm<0, 0>(p.dh, d, TH(t0 + 4), q, p.dao, q, Mi, q, d, 0.f, st)));
-    T_CK((sgemm<1, 0>(p.dh, d, a.ao, q, GR(t0 + 4), q, d, q, Mi, 0.f, st)));
+    T_CK(sgemm_wgrad(p.dh, d, a.ao, q, GR(t0 + 4), d, q, Mi, p.kparts, kSplitParts, st));
     // attention and the rotary embedding
     T_CK((sgemm<0, 1>(a.qkv, nqkv, a.qkv + q, nqkv, p.prob, (int)T, (int)T, (int)T, hd, 0.f, st, b_scores)));
     T_CK(launch(KID_ATTN_GENERIC, k_probs_from_lse, dim3(blocks256(n_sc)), dim3(256), 0, st, p.prob, (const float*)a.lse, (int)T,
@@ -858,7 +897,7 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
     }
     // query / key / value projections
     T_CK((sgemm<0, 0>(p.dqkv, nqkv, TH(t0 + 1), d, p.dx, d, Mi, d, nqkv, 0.f, st)));
-    T_CK((sgemm<1, 0>(p.dqkv, nqkv, a.xn, d, GR(t0 + 1), d, nqkv, d, Mi, 0.f, st)));
+    T_CK(sgemm_wgrad(p.dqkv, nqkv, a.xn, d, GR(t0 + 1), nqkv, d, Mi, p.kparts, kSplitParts, st));
     T_CK(norm_bwd(p.dx, a.h, a.r1, t0, 1));
   }
   T_CK(launch(KID_EMBED, k_embed_bwd, dim3((d + 255) / 256), dim3(256), 0, st, tokens, (const float*)p.dh, Mi, d, V, GR(0)));

@@ -156,6 +156,11 @@ WORKLOADS: Dict[str, Workload] = {
                          reward_p=0.3, reward_seed=504),
     # not one of the five: the shape of the paper's pass@1 judge (Sec. 5, the demo's evaluation):
     # one question, one completion - decode at batch 1, bound by latency, not by bandwidth.
+    # not one of the five: the local policy update (Algorithm 1's PolicyGradient step) on the training set of
+    # one node-round of configuration 2 (64 sequences of 128 + 256 tokens, completions masked).
+    "halfb_update": Workload("halfb_update", HALF_B, weight_seed=201, n_prompts=8, group=8, prompt_len=128,
+                             n_new=0, prompt_seed=202, score_seqs=64, score_len=384, score_masked=256,
+                             reward_p=0.3, reward_seed=204),
     "halfb_pass1": Workload("halfb_pass1", HALF_B, weight_seed=201, n_prompts=1, group=1,
                             prompt_len=128, n_new=256, temperature=1.0, prompt_seed=602,
                             rollout_seed=603),

@@ -66,7 +66,8 @@ def read_all(sapo, tr, what):
     return [sapo.sapo_trainer_read(tr, what, i).cpu().numpy().astype(np.float64) for i in range(len(tr.tensor_shapes))]
 
 
-@pytest.mark.parametrize("name,S,T,masked", [("tiny", 8, 32, 16), ("ragged_untied", 3, 13, 9), ("hd128", 4, 70, 33)])
+@pytest.mark.parametrize("name,S,T,masked", [("tiny", 8, 32, 16), ("ragged_untied", 3, 13, 9), ("hd128", 4, 70, 33),
+                                             ("tiny", 16, 64, 30)])   # 1024 tokens: split weight-gradient GEMMs
 def test_update_matches_oracle(sapo, name, S, T, masked):
     import torch
     from oracle import sapo_update_oracle as U
