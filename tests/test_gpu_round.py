@@ -1,0 +1,102 @@
+"""One whole round of Algorithm 1 on the GPU for one node, every step through the C ABI:
+rollouts -> rewards -> training set (own + swarm datapoints) -> scoring -> policy update -> the new policy
+generates the next round's rollouts.  The update is checked against the update oracle on the very training
+set the GPU assembled; the rest of the chain has its own parity tests."""
+import numpy as np
+import pytest
+
+from paper_2509_08721_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sapo():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2509_08721_amd import sapo as S
+    S.load_library()
+    return S
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def verifier(completions: np.ndarray) -> np.ndarray:
+    """Stand-in for a rule-based verifier (Sec. 4.3): reward 1 when the completion's first token id is even."""
+    return (completions[:, 0] % 2 == 0).astype(np.float32)
+
+
+def test_one_round_of_algorithm_1(sapo):
+    import torch
+    from oracle import sapo_update_oracle as U
+    shape = W.TINY
+    P, G, Lp, N = 6, 4, 8, 12
+    T = Lp + N
+    own = W.perturb_norm_gains(W.make_weights(shape, 31, std=0.2), 31)
+    other = W.make_weights(shape, 32, std=0.2)              # another node of the swarm
+    rng = np.random.default_rng(33)
+    prompts = rng.integers(0, shape.vocab, size=(P, Lp)).astype(np.int32)
+
+    def rollouts(weights, seed):
+        gw = sapo.sapo_weights_create(shape, weights)
+        toks, _ = sapo.sapo_rollout_generate(gw, dev(prompts), G, N, 1.0, seed)
+        torch.cuda.synchronize()
+        gw.close()
+        comp = toks.cpu().numpy()
+        return np.concatenate([np.repeat(prompts, G, axis=0), comp], axis=1).astype(np.int32), verifier(comp)
+
+    own_tok, own_rew = rollouts(own, 1001)
+    ext_tok, ext_rew = rollouts(other, 1002)
+    # training set: 3 own datapoints + 3 of the swarm's with non-zero advantage
+    n_local, n_ext = 3, 3
+    tok, rew, src, cnt = sapo.sapo_assemble_training_set(dev(own_tok), dev(own_rew), dev(ext_tok), dev(ext_rew), G, n_local,
+                                                         n_ext, 77)
+    torch.cuda.synchronize()
+    cnt = cnt.cpu().numpy()
+    assert cnt[0] == n_local and 0 < cnt[1] <= n_ext
+    n_dp = int(cnt[0] + cnt[1])
+    S = n_dp * G
+    tok, rew = tok[:S].contiguous(), rew[:S].contiguous()
+    mask = dev(W.make_completion_mask(S, T, N))
+    gw = sapo.sapo_weights_create(shape, own)
+    logp_old, adv = sapo.sapo_score_logprobs(gw, tok, mask, rew, G)
+    torch.cuda.synchronize()
+    assert float(adv.abs().max().cpu()) > 0
+
+    tr = sapo.sapo_trainer_create(shape, own, lr=1e-3)
+    loss, logp_new = sapo.sapo_policy_update(tr, tok, mask, logp_old, adv)
+    torch.cuda.synchronize()
+    # the trainer's forward is the scoring pass in another arrangement of the same fp32 arithmetic
+    assert float((logp_new - logp_old).abs().max().cpu()) < 2e-4
+    # on-policy, nothing is clipped: loss = -(sum of A over the masked tokens) / count
+    a = adv.cpu().numpy()
+    assert abs(float(loss.cpu()[0]) + float(a.mean())) < 1e-3
+    # gradient against the oracle on the training set the GPU assembled
+    params = U.parameter_list(shape, own)
+    ref_loss, _, ref_g = U.loss_and_gradients(shape, params, tok.cpu().numpy(), mask.cpu().numpy(), logp_old.cpu().numpy(), a)
+    assert abs(float(loss.cpu()[0]) - ref_loss) < 5e-4
+    gmax = max(float(np.max(np.abs(x))) for x in ref_g)
+    for i, b in enumerate(ref_g):
+        g = sapo.sapo_trainer_read(tr, 1, i).cpu().numpy().astype(np.float64)
+        assert float(np.max(np.abs(g - b))) <= 2e-4 * max(float(np.max(np.abs(b))), 1e-3 * gmax) + 1e-7, i
+
+    # a few more steps on the same set, then the new policy: rollouts with positive advantage became more
+    # likely relative to those with negative advantage
+    for _ in range(3):
+        sapo.sapo_policy_update(tr, tok, mask, logp_old, adv, want_logp=False)
+    new = sapo.sapo_trainer_export(tr)
+    gw2 = sapo.sapo_weights_create(shape, new)
+    logp_after, _ = sapo.sapo_score_logprobs(gw2, tok, mask, rew, G)
+    torch.cuda.synchronize()
+    d = (logp_after - logp_old).sum(dim=1).cpu().numpy()
+    assert d[a > 0].mean() > d[a < 0].mean()
+    # and it generates the next round
+    toks2, lps2 = sapo.sapo_rollout_generate(gw2, dev(prompts), G, N, 1.0, 2001)
+    torch.cuda.synchronize()
+    assert toks2.shape == (P * G, N) and np.all(np.isfinite(lps2.cpu().numpy()))
+    assert tr.steps == 4
+    gw.close(); gw2.close(); tr.close()
