@@ -10,6 +10,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <vector>
 
 #include "surrogate.h"
@@ -41,6 +42,22 @@ struct Batch {
   long a1 = 0, a2 = 0, b1 = 0, b2 = 0, c1 = 0, c2 = 0;
   int count = 1;
 };
+// Tile of a 1-D launch of nx * ny workgroups.  Workgroup ids are dealt round-robin to the 8 XCDs (each with its
+// own L2), so XCD x = id % 8 takes the contiguous tile range [x per, (x + 1) per) and walks it in panels of 8
+// tile rows, column by column: the ~100 workgroups an XCD runs at once then share 8 row blocks and a dozen
+// column blocks through its L2 instead of streaming every block from the memory side.
+__device__ __forceinline__ bool raster_tile(int nx, int ny, int& tx, int& ty) {
+  const int nt = nx * ny, per = (nt + 7) >> 3;
+  const int j = blockIdx.x >> 3, t = (blockIdx.x & 7) * per + j;
+  if (j >= per || t >= nt) return false;
+  const int panel = t / (8 * nx), w = t - panel * 8 * nx;
+  const int rows = min(8, ny - panel * 8);
+  ty = panel * 8 + w % rows;
+  tx = w / rows;
+  return true;
+}
+inline unsigned raster_grid(int nx, int ny) { return (unsigned)(((long)nx * ny + 7) / 8 * 8); }
+
 __device__ __forceinline__ void batch_offsets(const Batch& bt, const float* __restrict__& A, const float* __restrict__& B,
                                               float* __restrict__& C) {
   const int b = blockIdx.z, s = b / bt.nh, h = b % bt.nh;
@@ -154,7 +171,9 @@ __global__ void __launch_bounds__(256) k_sgemm_mfma(const float* __restrict__ A,
   __shared__ __align__(16) float Bs[2][kGK][kGP];
   batch_offsets(bt, A, B, C);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int m0 = blockIdx.y * kGM, n0 = blockIdx.x * kGM;
+  int tx, ty;
+  if (!raster_tile((N + kGM - 1) / kGM, (M + kGM - 1) / kGM, tx, ty)) return;
+  const int m0 = ty * kGM, n0 = tx * kGM;
   const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
   f32x16_t acc[2][2];
 #pragma unroll
@@ -210,6 +229,219 @@ __global__ void __launch_bounds__(256) k_sgemm_mfma(const float* __restrict__ A,
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// The large GEMMs at fp32 accuracy on the bf16 matrix cores.  An fp32 value is the exact sum of three bf16
+// values (its 24-bit mantissa cut into three 8-bit pieces: hi, mid, lo); a product a b is taken as the six
+// partial products of weight >= 2^-16 (hi hi, hi mid, mid hi, hi lo, lo hi, mid mid), each exact in fp32,
+// the three dropped ones being below 2^-23 of the product: the rounding of an fp32 multiply.  Six
+// v_mfma_f32_32x32x16_bf16 (32 cycles each) do the work of sixteen v_mfma_f32_32x32x2_f32 (64 cycles each).
+// With one piece (hi only) the same kernels are a plain bf16 GEMM with fp32 accumulation.
+//
+// Operands are cut once per GEMM by k_pack_x3 into the order a workgroup stages them in: for every block of
+// 128 rows and every 16-k step, [piece][k half][row] entries of 8 bf16 (16 bytes): one contiguous 2 KB x
+// pieces x 2 run per step, and the LDS image needs no rearrangement.  Rows and k are zero-padded to the
+// blocks.  "Rows" are the M side of op(A) or the N side of op(B); k is the contraction.
+// ---------------------------------------------------------------------------------------
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+// 16-byte entries as a plain vector type: with HIP's uint4 struct the compiler kept the kernel's prefetch registers
+// in scratch memory (every load waited for at once, then re-read), 2.7x slower
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+union Frag8 { u32x4_t u; bf16x8_t v; };
+
+__device__ __forceinline__ void split3(float x, uint32_t& hi, uint32_t& mid, uint32_t& lo) {   // bf16 bits in the high halves
+  hi = __float_as_uint(x) & 0xFFFF0000u;
+  const float r = x - __uint_as_float(hi);
+  mid = __float_as_uint(r) & 0xFFFF0000u;
+  const float r2 = r - __uint_as_float(mid);
+  lo = __float_as_uint(r2) & 0xFFFF0000u;
+}
+__device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | b; }   // a low half, b high half
+
+// entry (16 bytes) of (piece, row, k / 8) in a packed operand with KB = padded K / 16 steps
+__device__ __forceinline__ size_t x3_entry(int NP, int KB, int piece, int row, int k8) {
+  return ((((size_t)(row >> 7) * KB + (k8 >> 1)) * NP + piece) * 2 + (k8 & 1)) * 128 + (row & 127);
+}
+__device__ __forceinline__ void x3_store(uint4* __restrict__ dst, int NP, int KB, int row, int k8, const float (&x)[8]) {
+  uint32_t p[3][8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) split3(x[j], p[0][j], p[1][j], p[2][j]);
+  for (int pc = 0; pc < NP; ++pc)
+    dst[x3_entry(NP, KB, pc, row, k8)] = make_uint4(pack_hi(p[pc][0], p[pc][1]), pack_hi(p[pc][2], p[pc][3]),
+                                                    pack_hi(p[pc][4], p[pc][5]), pack_hi(p[pc][6], p[pc][7]));
+}
+// src[row * ld + k]: one workgroup per (block of 128 rows, 8 k steps); thread (row, k half) reads 8 consecutive
+// k per step, so a row is read in 64-byte runs and every piece of a step goes out as two 2 KB runs
+__global__ void __launch_bounds__(256) k_pack_x3(const float* __restrict__ src, int ld, int rows, int K, int rows_pad, int KB,
+                                                 int NP, uint4* __restrict__ dst) {
+  const int row = blockIdx.x * 128 + (threadIdx.x >> 1), kh = threadIdx.x & 1;
+  const float* rp = src + (size_t)row * ld;
+  const bool vec = ((ld & 3) == 0) && ((((uintptr_t)src) & 15) == 0);
+  for (int kb = blockIdx.y * 8; kb < min(KB, blockIdx.y * 8 + 8); ++kb) {
+    const int k0 = kb * 16 + kh * 8;
+    float x[8];
+    if (row < rows && k0 + 8 <= K && vec) {
+      const float4 a = *(const float4*)(rp + k0), b = *(const float4*)(rp + k0 + 4);
+      x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) x[j] = (row < rows && k0 + j < K) ? rp[k0 + j] : 0.f;
+    }
+    x3_store(dst, NP, KB, row, kb * 2 + kh, x);
+  }
+}
+// src[k * ld + row] (rows contiguous): 64 rows x 64 k per workgroup through LDS
+__global__ void __launch_bounds__(256) k_pack_x3_t(const float* __restrict__ src, int ld, int rows, int K, int rows_pad, int KB,
+                                                   int NP, uint4* __restrict__ dst) {
+  __shared__ float tile[64][65];
+  const int r0 = blockIdx.x * 64, k0 = blockIdx.y * 64;
+  for (int e = threadIdx.x; e < 64 * 64; e += 256) {
+    const int kk = e >> 6, rr = e & 63;
+    const int k = k0 + kk, row = r0 + rr;
+    tile[kk][rr] = (row < rows && k < K) ? src[(size_t)k * ld + row] : 0.f;
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < 64 * 8; e += 256) {
+    const int rr = e & 63, kq = e >> 6;           // 8 groups of 8 k
+    const int row = r0 + rr, k8 = (k0 >> 3) + kq;
+    if (row >= rows_pad || k8 >= KB * 2) continue;
+    float x[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) x[j] = tile[kq * 8 + j][rr];
+    x3_store(dst, NP, KB, row, k8, x);
+  }
+}
+
+template <int NP>
+__global__ void __launch_bounds__(256) k_gemm_x3(const u32x4_t* __restrict__ Ap, const u32x4_t* __restrict__ Bp, float* __restrict__ C,
+                                                 int ldc, int M, int N, int KB, float beta, int kb_split, size_t c_split) {
+  constexpr int E = NP * 256;                 // 16-byte entries per operand and k step
+  __shared__ u32x4_t As[2][E];
+  __shared__ u32x4_t Bs[2][E];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int tx, ty;
+  if (!raster_tile((N + kGM - 1) / kGM, (M + kGM - 1) / kGM, tx, ty)) return;
+  const int m0 = ty * kGM, n0 = tx * kGM;
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  const u32x4_t* ap = Ap + (size_t)ty * KB * E + threadIdx.x;
+  const u32x4_t* bp = Bp + (size_t)tx * KB * E + threadIdx.x;
+  f32x16_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  // blockIdx.z takes the k steps [z kb_split, (z + 1) kb_split) and writes its own copy of C (split weight gradients)
+  const int t0 = blockIdx.z * kb_split, t1 = min(KB, t0 + kb_split);
+  C += (size_t)blockIdx.z * c_split;
+  u32x4_t ra[NP], rb[NP];
+#pragma unroll
+  for (int pc = 0; pc < NP; ++pc) { ra[pc] = ap[(size_t)t0 * E + pc * 256]; rb[pc] = bp[(size_t)t0 * E + pc * 256]; }
+#pragma unroll
+  for (int pc = 0; pc < NP; ++pc) { As[0][pc * 256 + threadIdx.x] = ra[pc]; Bs[0][pc * 256 + threadIdx.x] = rb[pc]; }
+  __syncthreads();
+  const int kh = lane >> 5, c = lane & 31;
+  for (int t = t0; t < t1; ++t) {
+    const int cur = (t - t0) & 1;
+    if (t + 1 < t1) {
+#pragma unroll
+      for (int pc = 0; pc < NP; ++pc) { ra[pc] = ap[(size_t)(t + 1) * E + pc * 256]; rb[pc] = bp[(size_t)(t + 1) * E + pc * 256]; }
+    }
+    Frag8 a[2][NP], b[2][NP];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int pc = 0; pc < NP; ++pc) {
+        a[i][pc].u = As[cur][(pc * 2 + kh) * 128 + wm + i * 32 + c];
+        b[i][pc].u = Bs[cur][(pc * 2 + kh) * 128 + wn + i * 32 + c];
+      }
+    // smallest partial products first: (hi lo), (lo hi), (mid mid), (hi mid), (mid hi), (hi hi)
+    constexpr int n_terms = NP == 3 ? 6 : 1;
+    constexpr int pa[6] = {0, 2, 1, 0, 1, 0}, pb[6] = {2, 0, 1, 1, 0, 0};
+#pragma unroll
+    for (int term = 6 - n_terms; term < 6; ++term)
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][pa[term]].v, b[j][pb[term]].v, acc[i][j], 0, 0, 0);
+    if (t + 1 < t1) {
+#pragma unroll
+      for (int pc = 0; pc < NP; ++pc) { As[cur ^ 1][pc * 256 + threadIdx.x] = ra[pc]; Bs[cur ^ 1][pc * 256 + threadIdx.x] = rb[pc]; }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int n = n0 + wn + j * 32 + (lane & 31);
+      if (n >= N) continue;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int m = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (m >= M) continue;
+        float* cp = C + (size_t)m * ldc + n;
+        *cp = (beta != 0.f) ? fmaf(beta, *cp, acc[i][j][v]) : acc[i][j][v];
+      }
+    }
+}
+
+// One operand of a packed GEMM: `rows` x K values at src[row * ld + k], or src[k * ld + row] when `trans`.
+struct X3Op { const float* src; int ld, rows, K; bool trans; };
+inline size_t x3_pack_bytes(int NP, size_t rows, size_t K) {
+  return ((rows + 127) / 128 * 128) * ((K + 15) / 16 * 16) * 2 * NP;
+}
+struct X3Bufs { void* a; void* b; size_t a_cap, b_cap; int NP; float* parts; size_t parts_cap; };
+__global__ void k_sum_parts(const float* __restrict__ part, int n_part, size_t n, float beta, float* __restrict__ out);
+
+hipError_t x3_pack(const X3Op& op, void* dst, size_t cap, int NP, hipStream_t st) {
+  if (x3_pack_bytes(NP, op.rows, op.K) > cap) return hipErrorInvalidValue;
+  const int rows_pad = (op.rows + 127) / 128 * 128, KB = (op.K + 15) / 16;
+  if (!op.trans)
+    return launch(KID_MISC, k_pack_x3, dim3(rows_pad / 128, (KB + 7) / 8), dim3(256), 0, st, op.src, op.ld, op.rows, op.K, rows_pad,
+                  KB, NP, (uint4*)dst);
+  return launch(KID_MISC, k_pack_x3_t, dim3(rows_pad / 64, (KB * 16 + 63) / 64), dim3(256), 0, st, op.src, op.ld, op.rows, op.K,
+                rows_pad, KB, NP, (uint4*)dst);
+}
+// C[M, N] = beta C + op(A) op(B)^T-style product of two operands given row-wise over the same K
+hipError_t gemm_x3(const X3Op& A, const X3Op& B, float* C, int ldc, float beta, const X3Bufs& bufs, hipStream_t st,
+                   bool split_ok = false, const void* a_packed = nullptr, const void* b_packed = nullptr) {
+  if (A.K != B.K || A.rows <= 0 || B.rows <= 0 || A.K <= 0) return hipErrorInvalidValue;
+  hipError_t e;
+  // an operand packed earlier (a_packed / b_packed) is used as it is
+  if (!a_packed && (e = x3_pack(A, bufs.a, bufs.a_cap, bufs.NP, st)) != hipSuccess) return e;
+  if (!b_packed && (e = x3_pack(B, bufs.b, bufs.b_cap, bufs.NP, st)) != hipSuccess) return e;
+  const u32x4_t* pa_ = (const u32x4_t*)(a_packed ? a_packed : bufs.a);
+  const u32x4_t* pb_ = (const u32x4_t*)(b_packed ? b_packed : bufs.b);
+  const int KB = (A.K + 15) / 16;
+  const int gnx = (B.rows + kGM - 1) / kGM, gny = (A.rows + kGM - 1) / kGM;
+  dim3 grid(raster_grid(gnx, gny), 1);
+  // an output with few tiles and a long contraction (weight gradients of the narrow projections): the k steps
+  // are split into parts, each part writes its own product and k_sum_parts adds them in part order
+  const long tiles = (long)gnx * gny;
+  int splits = 1;
+  if (split_ok && beta == 0.f && ldc == B.rows) {
+    while (splits < 8 && tiles * splits < 192 && KB / (splits * 2) >= 16) splits *= 2;
+    if ((size_t)splits * A.rows * B.rows > bufs.parts_cap) splits = 1;
+  }
+  const int kbs = (KB + splits - 1) / splits;
+  splits = (KB + kbs - 1) / kbs;
+  grid.z = splits;
+  float* out = splits > 1 ? bufs.parts : C;
+  const size_t c_split = splits > 1 ? (size_t)A.rows * B.rows : 0;
+  if (bufs.NP == 3)
+    e = launch(KID_GEMM_GENERIC, k_gemm_x3<3>, grid, dim3(256), 0, st, pa_, pb_, out, ldc, A.rows, B.rows, KB, beta, kbs,
+               c_split);
+  else
+    e = launch(KID_GEMM_GENERIC, k_gemm_x3<1>, grid, dim3(256), 0, st, pa_, pb_, out, ldc, A.rows, B.rows, KB, beta, kbs,
+               c_split);
+  if (e != hipSuccess || splits == 1) return e;
+  const size_t n = (size_t)A.rows * B.rows;
+  return launch(KID_MISC, k_sum_parts, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const float*)bufs.parts, splits, n, 0.f,
+                C);
+}
+
 template <int TA, int TB>
 hipError_t sgemm(const float* A, int lda, const float* B, int ldb, float* C, int ldc, int M, int N, int K, float beta,
                  hipStream_t st, const Batch& bt = Batch()) {
@@ -217,31 +449,10 @@ hipError_t sgemm(const float* A, int lda, const float* B, int ldb, float* C, int
   const long strides = bt.a1 | bt.a2 | bt.b1 | bt.b2;
   const bool aligned = ((M | N | K | lda | ldb) & 3) == 0 && (strides & 3) == 0 && (((uintptr_t)A | (uintptr_t)B) & 15) == 0;
   if (aligned && (long)M * N * bt.count >= 128 * 128)
-    return launch(KID_GEMM_GENERIC, k_sgemm_mfma<TA, TB>, dim3((N + kGM - 1) / kGM, (M + kGM - 1) / kGM, bt.count), dim3(256), 0,
-                  st, A, lda, B, ldb, C, ldc, M, N, K, beta, bt);
+    return launch(KID_GEMM_GENERIC, k_sgemm_mfma<TA, TB>, dim3(raster_grid((N + kGM - 1) / kGM, (M + kGM - 1) / kGM), 1, bt.count),
+                  dim3(256), 0, st, A, lda, B, ldb, C, ldc, M, N, K, beta, bt);
   return launch(KID_GEMM_GENERIC, k_sgemm<TA, TB>, dim3((N + kTN - 1) / kTN, (M + kTM - 1) / kTM, bt.count), dim3(256), 0, st, A,
                 lda, B, ldb, C, ldc, M, N, K, beta, bt);
-}
-
-// C[Mg, Ng] = op(A) op(B) for a weight gradient (TA 1, TB 0; the contraction runs over the Kg tokens): when the
-// output has too few tiles to fill the chip the token range is split into parts whose products are added in
-// part order by k_sum_parts (declared below).
-__global__ void k_sum_parts(const float* __restrict__ part, int n_part, size_t n, float beta, float* __restrict__ out);
-hipError_t sgemm_wgrad(const float* A, int lda, const float* B, int ldb, float* C, int Mg, int Ng, int Kg, float* parts,
-                       size_t parts_cap, hipStream_t st) {
-  const long tiles = (long)((Mg + kGM - 1) / kGM) * ((Ng + kGM - 1) / kGM);
-  int splits = 1;
-  while (splits < 8 && tiles * splits < 192 && Kg % (splits * 2 * kGK) == 0 && Kg / (splits * 2) >= 256) splits *= 2;
-  if (splits == 1 || (size_t)splits * Mg * Ng > parts_cap || ((Mg | Ng | lda | ldb) & 3) != 0)
-    return sgemm<1, 0>(A, lda, B, ldb, C, Ng, Mg, Ng, Kg, 0.f, st);
-  const int ks = Kg / splits;
-  Batch bt;
-  bt.count = splits;
-  bt.a1 = (long)ks * lda; bt.b1 = (long)ks * ldb; bt.c1 = (long)Mg * Ng;
-  hipError_t e = sgemm<1, 0>(A, lda, B, ldb, parts, Ng, Mg, Ng, ks, 0.f, st, bt);
-  if (e != hipSuccess) return e;
-  const size_t n = (size_t)Mg * Ng;
-  return launch(KID_MISC, k_sum_parts, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const float*)parts, splits, n, 0.f, C);
 }
 
 __device__ __forceinline__ float block_sum256(float v, float* red) {
@@ -552,10 +763,10 @@ void tensor_sizes(const sapo_model_config& c, std::vector<size_t>& len) {
   if (!c.tied_embeddings) len.push_back(D.V * D.d);
 }
 
-// rows of logits held at once: about 5 GB (enough rows for the d-input GEMM of the head, whose output is only
+// rows of logits held at once: about 2.5 GB (enough rows for the d-input GEMM of the head, whose output is only
 // d_model wide, to fill the chip), a multiple of the GEMM tile
 size_t lm_chunk_rows(const Dims& D, size_t M) {
-  size_t r = ((size_t)5 << 30) / (D.V * sizeof(float)) / 128 * 128;
+  size_t r = ((size_t)5 << 29) / (D.V * sizeof(float)) / 128 * 128;
   if (r < 128) r = 128;
   return r < M ? r : M;
 }
@@ -574,6 +785,7 @@ struct Arena {
 // Weight-gradient GEMMs with few output tiles (dW of the attention projections: 49 - 63 tiles of 128 x 128 on 256
 // compute units) are split over the token dimension into up to 8 parts that are added in part order.
 constexpr size_t kSplitParts = (size_t)8 * 192 * 128 * 128;
+constexpr int kPieces = 3;   // bf16 pieces per fp32 value in the packed GEMMs (3: fp32 accuracy)
 
 struct LayerActs {
   float *h, *r1, *xn, *qkv, *lse, *ao, *h2, *r2, *xn2, *gu, *act;
@@ -586,6 +798,8 @@ struct TrainPlan {
   void* sur_ws;
   long long* n_masked;
   float* kparts;                                // partial products of the split weight-gradient GEMMs
+  char *packa, *packb, *head_nt, *head_t;       // packed operands; the LM head packed once per update, both ways
+  size_t packa_cap, packb_cap, head_cap, head_t_cap;
   size_t chunk;
   size_t bytes;
 };
@@ -628,6 +842,23 @@ void make_plan(const sapo_model_config& c, size_t S, size_t T, char* base, Train
   p.loss = A.take<float>(4);
   p.n_masked = A.take<long long>(1);
   p.kparts = A.take<float>(kSplitParts);
+  // packed GEMM operands: the largest row-side (A) and column-side (B) operand of any GEMM of the update
+  {
+    const size_t R = p.chunk, twoF = 2 * D.F;
+    const size_t a_shapes[][2] = {{M, D.d}, {M, D.q}, {M, D.F}, {M, twoF}, {M, D.nqkv}, {D.d, M}, {twoF, M}, {D.nqkv, M},
+                                  {R, D.d}, {R, D.V}, {D.V, R}};
+    const size_t b_shapes[][2] = {{D.nqkv, D.d}, {D.d, D.q}, {twoF, D.d}, {D.d, D.F}, {D.F, D.d}, {D.F, M}, {D.d, twoF},
+                                  {D.d, M}, {D.q, D.d}, {D.q, M}, {D.d, D.nqkv}, {D.d, R}};
+    p.packa_cap = p.packb_cap = 0;
+    for (auto& sh : a_shapes) p.packa_cap = std::max(p.packa_cap, x3_pack_bytes(kPieces, sh[0], sh[1]));
+    for (auto& sh : b_shapes) p.packb_cap = std::max(p.packb_cap, x3_pack_bytes(kPieces, sh[0], sh[1]));
+    p.head_cap = x3_pack_bytes(kPieces, D.V, D.d);
+    p.head_t_cap = x3_pack_bytes(kPieces, D.d, D.V);
+    p.packa = A.take<char>(p.packa_cap);
+    p.packb = A.take<char>(p.packb_cap);
+    p.head_nt = A.take<char>(p.head_cap);
+    p.head_t = A.take<char>(p.head_t_cap);
+  }
   p.sur_ws = A.take<char>(g_surrogate_workspace_bytes());
   p.bytes = (A.off + 255) & ~(size_t)255;
 }
@@ -796,6 +1027,20 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
   b_dk.a1 = hq * TT; b_dk.a2 = rep * TT; b_dk.b1 = Trow; b_dk.b2 = (long)rep * hd; b_dk.c1 = Trow; b_dk.c2 = hd;
   b_dv = b_dk; b_dv.b1 = Tq;
 
+  // The projections and the LM head run on the packed bf16-piece GEMM; forms as in sgemm<TA, TB>.
+  const X3Bufs xb{p.packa, p.packb, p.packa_cap, p.packb_cap, kPieces, p.kparts, kSplitParts};
+  auto mm_nt = [&](const float* X, int ldx, const float* W, int ldw, float* C, int ldc, int M_, int N_, int K_, float beta,
+                   const void* w_packed = nullptr) {   // C = beta C + X W^T
+    return gemm_x3(X3Op{X, ldx, M_, K_, false}, X3Op{W, ldw, N_, K_, false}, C, ldc, beta, xb, st, false, nullptr, w_packed);
+  };
+  auto mm_nn = [&](const float* A_, int lda, const float* B_, int ldb, float* C, int ldc, int M_, int N_, int K_, float beta,
+                   const void* b_packed = nullptr) {   // C = beta C + A B
+    return gemm_x3(X3Op{A_, lda, M_, K_, false}, X3Op{B_, ldb, N_, K_, true}, C, ldc, beta, xb, st, false, nullptr, b_packed);
+  };
+  auto mm_tn = [&](const float* A_, int lda, const float* B_, int ldb, float* C, int Mg, int Ng, int Kg, float beta) {
+    return gemm_x3(X3Op{A_, lda, Mg, Kg, true}, X3Op{B_, ldb, Ng, Kg, true}, C, Ng, beta, xb, st, true);   // C = beta C + A^T B
+  };
+
   // ---- forward, every activation kept
   float* h = p.layer[0].h;
   T_CK(launch(KID_EMBED, k_embed_rows, dim3(Mi), dim3(256), 0, st, tokens, (const float*)TH(0), h, d, V));
@@ -804,7 +1049,7 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
     const int t0 = 1 + 9 * l;   // attn_norm, wq, wk, wv, wo, ffn_norm, w_gate, w_up, w_down
     T_CK(launch(KID_RMSNORM, k_rmsnorm_fwd, dim3(Mi), dim3(256), 0, st, (const float*)a.h, (const float*)TH(t0), c.rms_eps, d,
                 a.xn, a.r1));
-    T_CK((sgemm<0, 1>(a.xn, d, TH(t0 + 1), d, a.qkv, nqkv, Mi, nqkv, d, 0.f, st)));   // wq, wk, wv are adjacent
+    T_CK(mm_nt(a.xn, d, TH(t0 + 1), d, a.qkv, nqkv, Mi, nqkv, d, 0.f));   // wq, wk, wv are adjacent
     {
       const size_t total = M * (size_t)(hq + hkv) * (hd / 2);
       T_CK(launch(KID_ROPE_APPEND, k_rope, dim3(blocks256(total)), dim3(256), 0, st, a.qkv, (const float2*)tr->rope, (int)T,
@@ -815,14 +1060,14 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
                 att_scale));
     T_CK((sgemm<0, 0>(p.prob, (int)T, a.qkv + q + kv, nqkv, a.ao, q, (int)T, hd, (int)T, 0.f, st, b_pv)));
     T_CK(hipMemcpyAsync(a.h2, a.h, M * D.d * sizeof(float), hipMemcpyDeviceToDevice, st));
-    T_CK((sgemm<0, 1>(a.ao, q, TH(t0 + 4), q, a.h2, d, Mi, d, q, 1.f, st)));
+    T_CK(mm_nt(a.ao, q, TH(t0 + 4), q, a.h2, d, Mi, d, q, 1.f));
     T_CK(launch(KID_RMSNORM, k_rmsnorm_fwd, dim3(Mi), dim3(256), 0, st, (const float*)a.h2, (const float*)TH(t0 + 5), c.rms_eps,
                 d, a.xn2, a.r2));
-    T_CK((sgemm<0, 1>(a.xn2, d, TH(t0 + 6), d, a.gu, 2 * F, Mi, 2 * F, d, 0.f, st)));   // w_gate, w_up are adjacent
+    T_CK(mm_nt(a.xn2, d, TH(t0 + 6), d, a.gu, 2 * F, Mi, 2 * F, d, 0.f));   // w_gate, w_up are adjacent
     T_CK(launch(KID_SWIGLU, k_swiglu_fwd, dim3(blocks256(M * D.F)), dim3(256), 0, st, (const float*)a.gu, a.act, F, M * D.F));
     float* h_next = (l + 1 < D.L) ? p.layer[l + 1].h : p.h_last;
     T_CK(hipMemcpyAsync(h_next, a.h2, M * D.d * sizeof(float), hipMemcpyDeviceToDevice, st));
-    T_CK((sgemm<0, 1>(a.act, F, TH(t0 + 8), F, h_next, d, Mi, d, F, 1.f, st)));
+    T_CK(mm_nt(a.act, F, TH(t0 + 8), F, h_next, d, Mi, d, F, 1.f));
   }
   T_CK(launch(KID_RMSNORM, k_rmsnorm_fwd, dim3(Mi), dim3(256), 0, st, (const float*)p.h_last, (const float*)TH(t_final),
               c.rms_eps, d, p.xf, p.rf));
@@ -831,13 +1076,15 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
   T_CK(g_fill_f32(tr->grad, 0.f, tr->n_params, st));
   T_CK(g_fill_f32(p.logp_new, 0.f, M, st));
   T_CK(launch(KID_MISC, k_count_mask, dim3(1), dim3(256), 0, st, completion_mask, M, p.n_masked));
+  T_CK(x3_pack(X3Op{TH(t_head), d, V, d, false}, p.head_nt, p.head_cap, kPieces, st));   // rows = vocabulary, k = d
+  T_CK(x3_pack(X3Op{TH(t_head), d, d, V, true}, p.head_t, p.head_t_cap, kPieces, st));    // rows = d, k = vocabulary
   for (size_t r0 = 0; r0 < M; r0 += p.chunk) {
     const int R = (int)((M - r0 < p.chunk) ? M - r0 : p.chunk);
-    T_CK((sgemm<0, 1>(p.xf + r0 * D.d, d, TH(t_head), d, p.logits, V, R, V, d, 0.f, st)));
+    T_CK(mm_nt(p.xf + r0 * D.d, d, TH(t_head), d, p.logits, V, R, V, d, 0.f, p.head_nt));
     T_CK(launch(KID_SCORE_ROWS, k_logp_dlogits, dim3(R), dim3(256), 0, st, p.logits, V, (int)r0, (int)T, tokens, completion_mask,
                 logp_old, advantages, eps_low, eps_high, (const long long*)p.n_masked, p.logp_new));
-    T_CK((sgemm<0, 0>(p.logits, V, TH(t_head), d, p.dx + r0 * D.d, d, R, d, V, 0.f, st)));
-    T_CK((sgemm<1, 0>(p.logits, V, p.xf + r0 * D.d, d, GR(t_head), d, V, d, R, 1.f, st)));
+    T_CK(mm_nn(p.logits, V, TH(t_head), d, p.dx + r0 * D.d, d, R, d, V, 0.f, p.head_t));
+    T_CK(mm_tn(p.logits, V, p.xf + r0 * D.d, d, GR(t_head), V, d, R, 1.f));
   }
   // ---- the loss (the surrogate of sapo_clipped_surrogate on the log-probs just computed)
   T_CK(g_surrogate_loss(p.logp_new, logp_old, completion_mask, advantages, S_, T_, eps_low, eps_high, p.loss, nullptr, p.sur_ws,
@@ -862,17 +1109,17 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
     const LayerActs& a = p.layer[l];
     const int t0 = 1 + 9 * l;
     // down projection
-    T_CK((sgemm<0, 0>(p.dh, d, TH(t0 + 8), F, p.dact, F, Mi, F, d, 0.f, st)));
-    T_CK(sgemm_wgrad(p.dh, d, a.act, F, GR(t0 + 8), d, F, Mi, p.kparts, kSplitParts, st));
+    T_CK(mm_nn(p.dh, d, TH(t0 + 8), F, p.dact, F, Mi, F, d, 0.f));
+    T_CK(mm_tn(p.dh, d, a.act, F, GR(t0 + 8), d, F, Mi, 0.f));
     T_CK(launch(KID_SWIGLU, k_swiglu_bwd, dim3(blocks256(M * D.F)), dim3(256), 0, st, (const float*)p.dact, (const float*)a.gu,
                 p.dgu, F, M * D.F));
     // gate / up projections
-    T_CK((sgemm<0, 0>(p.dgu, 2 * F, TH(t0 + 6), d, p.dx, d, Mi, d, 2 * F, 0.f, st)));
-    T_CK(sgemm_wgrad(p.dgu, 2 * F, a.xn2, d, GR(t0 + 6), 2 * F, d, Mi, p.kparts, kSplitParts, st));
+    T_CK(mm_nn(p.dgu, 2 * F, TH(t0 + 6), d, p.dx, d, Mi, d, 2 * F, 0.f));
+    T_CK(mm_tn(p.dgu, 2 * F, a.xn2, d, GR(t0 + 6), 2 * F, d, Mi, 0.f));
     T_CK(norm_bwd(p.dx, a.h2, a.r2, t0 + 5, 1));
     // output projection
-    T_CK((sgemm<0, 0>(p.dh, d, TH(t0 + 4), q, p.dao, q, Mi, q, d, 0.f, st)));
-    T_CK(sgemm_wgrad(p.dh, d, a.ao, q, GR(t0 + 4), d, q, Mi, p.kparts, kSplitParts, st));
+    T_CK(mm_nn(p.dh, d, TH(t0 + 4), q, p.dao, q, Mi, q, d, 0.f));
+    T_CK(mm_tn(p.dh, d, a.ao, q, GR(t0 + 4), d, q, Mi, 0.f));
     // attention and the rotary embedding
     T_CK((sgemm<0, 1>(a.qkv, nqkv, a.qkv + q, nqkv, p.prob, (int)T, (int)T, (int)T, hd, 0.f, st, b_scores)));
     T_CK(launch(KID_ATTN_GENERIC, k_probs_from_lse, dim3(blocks256(n_sc)), dim3(256), 0, st, p.prob, (const float*)a.lse, (int)T,
@@ -896,8 +1143,8 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
                   hq + hkv, hd, nqkv, -1.0f, total));
     }
     // query / key / value projections
-    T_CK((sgemm<0, 0>(p.dqkv, nqkv, TH(t0 + 1), d, p.dx, d, Mi, d, nqkv, 0.f, st)));
-    T_CK(sgemm_wgrad(p.dqkv, nqkv, a.xn, d, GR(t0 + 1), nqkv, d, Mi, p.kparts, kSplitParts, st));
+    T_CK(mm_nn(p.dqkv, nqkv, TH(t0 + 1), d, p.dx, d, Mi, d, nqkv, 0.f));
+    T_CK(mm_tn(p.dqkv, nqkv, a.xn, d, GR(t0 + 1), nqkv, d, Mi, 0.f));
     T_CK(norm_bwd(p.dx, a.h, a.r1, t0, 1));
   }
   T_CK(launch(KID_EMBED, k_embed_bwd, dim3((d + 255) / 256), dim3(256), 0, st, tokens, (const float*)p.dh, Mi, d, V, GR(0)));
