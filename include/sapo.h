@@ -264,8 +264,9 @@ int sapo_trainer_create(const sapo_model_config* cfg, const void* const* tensors
                         const sapo_adam_config* opt, void* stream, sapo_trainer** out);
 void sapo_trainer_destroy(sapo_trainer* tr);
 /* Workspace of one update over S sequences of T tokens (every layer's activations are kept for the
- * backward pass: about 4 (4 d + 2 Hq hd + 2 Hkv hd + 3 F) bytes per token and layer); 0 on invalid
- * arguments (T < 2 or T > max_seq). */
+ * backward pass: about 4 (4 d + 2 Hq hd + 2 Hkv hd + 3 F) bytes per token and layer, plus score
+ * matrices, a chunk of logits and packed GEMM operands); 0 on invalid arguments (T < 2 or
+ * T > max_seq).  At most 8192 tokens per sequence and 65535 (sequence, query head) pairs per call. */
 size_t sapo_trainer_workspace_bytes(const sapo_trainer* tr, int S, int T);
 /*
  * One update on the training set: teacher-forced forward pass under the masters, loss =
@@ -281,8 +282,9 @@ size_t sapo_trainer_workspace_bytes(const sapo_trainer* tr, int S, int T);
  *   out_logp_new     dev fp32 [S, T] or NULL: the log-probs under the masters before the step (0 where
  *                                       the mask is clear)
  *   workspace        dev, >= sapo_trainer_workspace_bytes(tr, S, T), 256-byte aligned
- * fp32 arithmetic throughout, every sum in a fixed order (no atomics): the same call on the same
- * state gives the same bits.  Asynchronous on `stream`; the trainer's state is updated in place, so
+ * fp32 values throughout (the large matrix products are formed from bf16 pieces on the matrix cores
+ * with the accuracy of fp32 products), every sum in a fixed order (no atomics): the same call on the
+ * same state gives the same bits.  Asynchronous on `stream`; the trainer's state is updated in place, so
  * calls on one trainer must not overlap.  Errors: SAPO_EINVAL (NULL, sizes, eps), SAPO_EWORKSPACE.
  */
 int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const uint8_t* completion_mask,

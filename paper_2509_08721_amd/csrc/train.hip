@@ -1,8 +1,9 @@
 // The local policy update of a SAPO node (Algorithm 1, the PolicyGradient step; Sec. 4.2: GRPO without a
 // KL term, asymmetric clipping, Adam with its default hyper-parameters): kernels, orchestration, C ABI.
 //
-// Everything here is fp32 on row-major buffers: master parameters, activations, gradients and the two
-// Adam moments.  One update = forward pass over the whole training set with every layer's activations
+// Values are fp32 on row-major buffers: master parameters, activations, gradients and the two Adam
+// moments; the large GEMMs form their products from bf16 pieces on the matrix cores at fp32 accuracy
+// (k_gemm_x3).  One update = forward pass over the whole training set with every layer's activations
 // kept (HBM is large enough: about 80 KB per token and layer for the 0.5B shape), the clipped surrogate,
 // the backward pass, one Adam step.  No atomics: every sum has a fixed order, so an update is
 // reproducible bit for bit.
