@@ -164,7 +164,7 @@ __device__ __forceinline__ void gemm_stage(float (*buf)[kGP], const float4 (&r)[
   }
 }
 
-template <int TA, int TB>
+template <int TA, int TB, int NARROW>   // NARROW: N <= 64, the four waves stack along M (32 rows x 64 columns each)
 __global__ void __launch_bounds__(256) k_sgemm_mfma(const float* __restrict__ A, int lda, const float* __restrict__ B, int ldb,
                                                     float* __restrict__ C, int ldc, int M, int N, int K, float beta,
                                                     Batch bt) {
@@ -175,10 +175,11 @@ __global__ void __launch_bounds__(256) k_sgemm_mfma(const float* __restrict__ A,
   int tx, ty;
   if (!raster_tile((N + kGM - 1) / kGM, (M + kGM - 1) / kGM, tx, ty)) return;
   const int m0 = ty * kGM, n0 = tx * kGM;
-  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
-  f32x16_t acc[2][2];
+  constexpr int MI = NARROW ? 1 : 2;
+  const int wm = NARROW ? wave * 32 : (wave >> 1) * 64, wn = NARROW ? 0 : (wave & 1) * 64;
+  f32x16_t acc[MI][2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -200,12 +201,13 @@ __global__ void __launch_bounds__(256) k_sgemm_mfma(const float* __restrict__ A,
 #pragma unroll
     for (int kk = 0; kk < kGK; kk += 2) {
       const int kr = kk + (lane >> 5), c = lane & 31;
-      const float a0 = As[cur][kr][wm + c], a1 = As[cur][kr][wm + 32 + c];
       const float b0 = Bs[cur][kr][wn + c], b1 = Bs[cur][kr][wn + 32 + c];
-      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < MI; ++i) {
+        const float a = As[cur][kr][wm + i * 32 + c];
+        acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b0, acc[i][0], 0, 0, 0);
+        acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b1, acc[i][1], 0, 0, 0);
+      }
     }
     if (t + 1 < nk) {
       gemm_stage<TA>(As[cur ^ 1], ra);
@@ -215,7 +217,7 @@ __global__ void __launch_bounds__(256) k_sgemm_mfma(const float* __restrict__ A,
   }
   // accumulator v of lane l: row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32 of the 32 x 32 tile
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int n = n0 + wn + j * 32 + (lane & 31);
@@ -449,9 +451,12 @@ hipError_t sgemm(const float* A, int lda, const float* B, int ldb, float* C, int
   if (M <= 0 || N <= 0 || K <= 0 || bt.count <= 0 || bt.count > 65535) return hipErrorInvalidValue;
   const long strides = bt.a1 | bt.a2 | bt.b1 | bt.b2;
   const bool aligned = ((M | N | K | lda | ldb) & 3) == 0 && (strides & 3) == 0 && (((uintptr_t)A | (uintptr_t)B) & 15) == 0;
-  if (aligned && (long)M * N * bt.count >= 128 * 128)
-    return launch(KID_GEMM_GENERIC, k_sgemm_mfma<TA, TB>, dim3(raster_grid((N + kGM - 1) / kGM, (M + kGM - 1) / kGM), 1, bt.count),
-                  dim3(256), 0, st, A, lda, B, ldb, C, ldc, M, N, K, beta, bt);
+  if (aligned && (long)M * N * bt.count >= 128 * 128) {
+    const dim3 grid(raster_grid((N + kGM - 1) / kGM, (M + kGM - 1) / kGM), 1, bt.count);
+    if (N <= 64)
+      return launch(KID_GEMM_GENERIC, k_sgemm_mfma<TA, TB, 1>, grid, dim3(256), 0, st, A, lda, B, ldb, C, ldc, M, N, K, beta, bt);
+    return launch(KID_GEMM_GENERIC, k_sgemm_mfma<TA, TB, 0>, grid, dim3(256), 0, st, A, lda, B, ldb, C, ldc, M, N, K, beta, bt);
+  }
   return launch(KID_GEMM_GENERIC, k_sgemm<TA, TB>, dim3((N + kTN - 1) / kTN, (M + kTM - 1) / kTM, bt.count), dim3(256), 0, st, A,
                 lda, B, ldb, C, ldc, M, N, K, beta, bt);
 }
