@@ -42,6 +42,10 @@ struct Batch {
   int nh = 1, bdiv = 1;
   long a1 = 0, a2 = 0, b1 = 0, b2 = 0, c1 = 0, c2 = 0;
   int count = 1;
+  // causal attention products (rows and columns are positions of one sequence): 1 = only output tiles with
+  // column <= row are needed (scores, dP); 2 = op(A)[i][k] is zero for k > i, the k loop ends at the tile's last
+  // row (P V, dS K); 3 = op(A)[j][k] is zero for k < j, the k loop starts at the tile's first row (dS^T Q, P^T dO)
+  int causal = 0;
 };
 // Tile of a 1-D launch of nx * ny workgroups.  Workgroup ids are dealt round-robin to the 8 XCDs (each with its
 // own L2), so XCD x = id % 8 takes the contiguous tile range [x per, (x + 1) per) and walks it in panels of 8
@@ -184,15 +188,18 @@ __global__ void __launch_bounds__(256) k_sgemm_mfma(const float* __restrict__ A,
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  if (bt.causal == 1 && n0 > m0 + kGM - 1) return;   // the whole tile lies above the diagonal
+  int t_begin = 0, nk = (K + kGK - 1) / kGK;
+  if (bt.causal == 2) nk = min(nk, (m0 + kGM + kGK - 1) / kGK);
+  if (bt.causal == 3) t_begin = min(m0 / kGK, nk - 1);
   float4 ra[2], rb[2];
   // op(A) rows are m: A is "k contiguous" unless TA; op(B) rows are n: B is "k contiguous" when TB
-  gemm_fetch<TA>(A, lda, m0, M, 0, K, ra);
-  gemm_fetch<TB ? 0 : 1>(B, ldb, n0, N, 0, K, rb);
-  gemm_stage<TA>(As[0], ra);
-  gemm_stage<TB ? 0 : 1>(Bs[0], rb);
+  gemm_fetch<TA>(A, lda, m0, M, t_begin * kGK, K, ra);
+  gemm_fetch<TB ? 0 : 1>(B, ldb, n0, N, t_begin * kGK, K, rb);
+  gemm_stage<TA>(As[t_begin & 1], ra);
+  gemm_stage<TB ? 0 : 1>(Bs[t_begin & 1], rb);
   __syncthreads();
-  const int nk = (K + kGK - 1) / kGK;
-  for (int t = 0; t < nk; ++t) {
+  for (int t = t_begin; t < nk; ++t) {
     const int cur = t & 1;
     if (t + 1 < nk) {
       gemm_fetch<TA>(A, lda, m0, M, (t + 1) * kGK, K, ra);
@@ -697,7 +704,8 @@ __global__ void k_dscores(const float* __restrict__ prob, float* __restrict__ dp
                           float scale, size_t total) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total) return;
-  dp[idx] = scale * prob[idx] * (dp[idx] - delta[idx / T]);
+  const float pr = prob[idx];   // zero above the diagonal, where dP was not computed
+  dp[idx] = pr == 0.f ? 0.f : scale * pr * (dp[idx] - delta[idx / T]);
 }
 
 // Embedding rows: dE[tokens[m]] += dh[m], rows taken in order m = 0, 1, ... by the thread that owns the column.
@@ -1032,6 +1040,7 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
   b_dk.nh = hkv; b_dk.bdiv = 1; b_dk.count = S_ * hkv;
   b_dk.a1 = hq * TT; b_dk.a2 = rep * TT; b_dk.b1 = Trow; b_dk.b2 = (long)rep * hd; b_dk.c1 = Trow; b_dk.c2 = hd;
   b_dv = b_dk; b_dv.b1 = Tq;
+  b_scores.causal = 1; b_dp.causal = 1; b_pv.causal = 2; b_dq.causal = 2; b_dk.causal = 3; b_dv.causal = 3;
 
   // The projections and the LM head run on the packed bf16-piece GEMM; forms as in sgemm<TA, TB>.
   const X3Bufs xb{p.packa, p.packb, p.packa_cap, p.packb_cap, kPieces, p.kparts, kSplitParts};

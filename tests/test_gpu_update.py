@@ -7,7 +7,11 @@ from paper_2509_08721_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
 
+from dataclasses import replace
+
 SHAPES = {
+    # several 128-position tiles per sequence: the causal shortcuts of the attention products
+    "tiny_long": replace(W.TINY, max_seq=512),
     # the tiny configuration's model
     "tiny": W.TINY,
     # sizes that are not multiples of the GEMM tile, untied head, one KV head
@@ -67,7 +71,8 @@ def read_all(sapo, tr, what):
 
 
 @pytest.mark.parametrize("name,S,T,masked", [("tiny", 8, 32, 16), ("ragged_untied", 3, 13, 9), ("hd128", 4, 70, 33),
-                                             ("tiny", 16, 64, 30)])   # 1024 tokens: split weight-gradient GEMMs
+                                             ("tiny", 16, 64, 30),    # 1024 tokens: split weight-gradient GEMMs
+                                             ("tiny_long", 2, 300, 140)])
 def test_update_matches_oracle(sapo, name, S, T, masked):
     import torch
     from oracle import sapo_update_oracle as U
