@@ -215,3 +215,80 @@ def test_update_rejects_bad_arguments(sapo):
     with pytest.raises(sapo.SapoError):
         sapo.sapo_trainer_create(bad, W.make_weights(bad, 1))
     tr.close()
+
+
+def test_update_on_the_0p5b_shapes(sapo):
+    """The 0.5B model itself (24 layers, d 896, F 4864, 14 query / 2 KV heads of 64, vocabulary 151936, bf16 values as
+    fp32 masters) on two sequences the oracle differentiates in seconds: the kernels, tiles and packed layouts of
+    the full training set with fewer rows.  Also: the update's log-probs against the scoring call's (the bf16 MFMA
+    path), two independent implementations of the same forward."""
+    import torch
+    from oracle import sapo_update_oracle as U
+    shape = W.HALF_B
+    w = W.make_weights(shape, 201)
+    S, T, masked = 2, 128, 64
+    rng = np.random.default_rng(77)
+    tokens = rng.integers(0, shape.vocab, size=(S, T)).astype(np.int32)
+    mask = W.make_completion_mask(S, T, masked)
+    adv = np.array([0.8, -1.3], dtype=np.float32)
+    params = U.parameter_list(shape, w)
+    _, lp, _ = U.loss_and_gradients(shape, params, tokens, mask, np.zeros((S, T), np.float32), adv)
+    u = rng.uniform(-0.4, 0.4, size=lp.shape)
+    u[(np.abs(np.exp(-u) - 1.28) < 0.02) | (np.abs(np.exp(-u) - 0.8) < 0.02)] = 0.0
+    logp_old = (lp + u * (mask != 0)).astype(np.float32)
+    ref_loss, ref_lp, ref_g = U.loss_and_gradients(shape, params, tokens, mask, logp_old, adv)
+
+    tr = sapo.sapo_trainer_create(shape, w)
+    loss, lp_new = sapo.sapo_policy_update(tr, dev(tokens), dev(mask), dev(logp_old), dev(adv))
+    torch.cuda.synchronize()
+    assert np.max(np.abs(lp_new.cpu().numpy() - ref_lp)) < 2e-4
+    assert abs(float(loss.cpu()[0]) - ref_loss) < 1e-4
+    gmax = max(float(np.max(np.abs(x))) for x in ref_g)
+    worst = 0.0
+    for i, b in enumerate(ref_g):
+        g = sapo.sapo_trainer_read(tr, 1, i).cpu().numpy().astype(np.float64)
+        err = float(np.max(np.abs(g - b)))
+        worst = max(worst, err / max(float(np.max(np.abs(b))), 1e-3 * gmax))
+        assert err <= 2e-4 * max(float(np.max(np.abs(b))), 1e-3 * gmax) + 1e-7, (i, err, float(np.max(np.abs(b))))
+    print("0.5B update: worst relative gradient error %.2e" % worst)
+    tr.close()
+    # the scoring call on the same tokens (bf16 weights, half MFMA operands): log-prob tolerance of that path
+    gw = sapo.sapo_weights_create(shape, w)
+    lp_score, _ = sapo.sapo_score_logprobs(gw, dev(tokens), dev(mask), dev(np.zeros(S, np.float32)), 2)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(lp_score.cpu().numpy() - ref_lp)) < 2e-2
+    gw.close()
+
+
+def test_update_degenerate_batches(sapo):
+    """Nothing masked: loss 0, zero gradient, parameters unchanged (Adam of a zero gradient).  All advantages zero:
+    the same.  The shortest sequences the call accepts (T = 2)."""
+    import torch
+    shape = SHAPES["tiny"]
+    w, params, tokens, mask, logp_old, adv = make_case(shape, 9, 4, 8, 4)
+    tr = sapo.sapo_trainer_create(shape, w)
+    before = read_all(sapo, tr, 0)
+    loss, lp = sapo.sapo_policy_update(tr, dev(tokens), dev(np.zeros_like(mask)), dev(logp_old), dev(adv))
+    torch.cuda.synchronize()
+    assert float(loss.cpu()[0]) == 0.0 and not lp.cpu().numpy().any()
+    assert all(not g.any() for g in read_all(sapo, tr, 1))
+    assert all(np.array_equal(a, b) for a, b in zip(before, read_all(sapo, tr, 0)))
+    loss, _ = sapo.sapo_policy_update(tr, dev(tokens), dev(mask), dev(logp_old), dev(np.zeros_like(adv)))
+    torch.cuda.synchronize()
+    assert float(loss.cpu()[0]) == 0.0
+    assert all(not g.any() for g in read_all(sapo, tr, 1))
+    assert all(np.array_equal(a, b) for a, b in zip(before, read_all(sapo, tr, 0)))
+    assert tr.steps == 2
+    # T = 2: one prediction per sequence
+    from oracle import sapo_update_oracle as U
+    t2 = tokens[:, :2].copy()
+    m2 = np.ones((4, 2), dtype=np.uint8)
+    lo2 = np.full((4, 2), -6.0, dtype=np.float32)
+    ref_loss, ref_lp, ref_g = U.loss_and_gradients(shape, params, t2, m2, lo2, adv)
+    loss, lp = sapo.sapo_policy_update(tr, dev(t2), dev(m2), dev(lo2), dev(adv))
+    torch.cuda.synchronize()
+    assert np.max(np.abs(lp.cpu().numpy() - ref_lp)) < 2e-4 and abs(float(loss.cpu()[0]) - ref_loss) < 1e-4 * max(1.0, abs(ref_loss))
+    gmax = max(float(np.max(np.abs(x))) for x in ref_g)
+    for g, b in zip(read_all(sapo, tr, 1), ref_g):
+        assert float(np.max(np.abs(g - b))) <= 2e-4 * max(float(np.max(np.abs(b))), 1e-3 * gmax) + 1e-7
+    tr.close()
