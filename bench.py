@@ -124,6 +124,7 @@ def bench_update(args, wl):
     torch.cuda.synchronize()
     gw.close()
     tr = sapo.sapo_trainer_create(shape, weights)
+    sapo.sapo_trainer_set_matmul_pieces(tr, args.pieces)
     nbytes = sapo.sapo_trainer_workspace_bytes(tr, S, T)
     ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
     setup_s = time.time() - t0
@@ -157,7 +158,8 @@ def bench_update(args, wl):
             roofline = {"kernel": "k_gemm_x3 + k_sgemm_mfma (all GEMMs of the update)", "bound": "mfma", "achieved": k["achieved"],
                         "peak": MFMA_16BIT_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": k["frac"], "traffic": None,
                         "avg_us": k["avg_us"], "launches": k["launches"], "work_per_launch": k["work_per_launch"],
-                        "executed_TFLOPs": round(6 * ach, 1), "executed_frac": round(6 * ach / MFMA_16BIT_PEAK_TFLOPS, 4),
+                        "executed_TFLOPs": round((6 if args.pieces == 3 else 1) * ach, 1),
+                        "executed_frac": round((6 if args.pieces == 3 else 1) * ach / MFMA_16BIT_PEAK_TFLOPS, 4),
                         "vs_fp32_mfma_peak": round(ach / FP32_MFMA_PEAK_TFLOPS, 4)}
     cpu = None
     if not args.no_cpu_baseline:
@@ -176,8 +178,10 @@ def bench_update(args, wl):
     out = {"metric": "trained tokens/s of one policy update (forward + clipped surrogate + backward + Adam)",
            "value": round(S * T / dt, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(dt * 1e3, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-           "dtype": "f32", "data": "synthetic",
-           "config": {"workload": wl.name, "arithmetic": "fp32 (GEMM products as 6 bf16 x bf16 partial products, fp32 accumulation)",
+           "dtype": "f32" if args.pieces == 3 else "bf16", "data": "synthetic",
+           "config": {"workload": wl.name,
+                      "arithmetic": "fp32 (GEMM products as 6 bf16 x bf16 partial products, fp32 accumulation)" if args.pieces == 3
+                      else "fp32 with bf16 GEMM operands (1 piece), fp32 accumulation",
                       "layers": shape.n_layers, "d_model": shape.d_model, "vocab": shape.vocab,
                       "seqs": S, "seq_len": T, "masked": Tm, "optimizer": "Adam lr 1e-3 (defaults)",
                       "weights": "fp32 masters of the bf16 model"},
@@ -202,6 +206,8 @@ def main():
                     help="counter runs only: same kernels and shapes with this many layers (fewer launches); "
                          "the printed line is then not a benchmark result")
     ap.add_argument("--new-tokens", type=int, default=0, help="counter runs only: generate this many tokens")
+    ap.add_argument("--pieces", type=int, default=3,
+                    help="halfb_update only: 3 = fp32-accurate matrix products (default), 1 = bf16 operands")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this library runs on ONE GPU (no sharding, no collectives); --gpus %d is not "

@@ -298,6 +298,16 @@ int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const uint8_t* c
  * to nearest even), gains as fp32.
  */
 int sapo_trainer_export(const sapo_trainer* tr, void* const* tensors_out, int n_tensors, void* stream);
+/*
+ * Arithmetic of the update's large matrix products (projections and LM head; forward and backward).
+ *   pieces = 3 (default): every fp32 operand is the exact sum of three bf16 values and a product is the
+ *                sum of the six largest of the nine partial products: the accuracy of an fp32 product.
+ *   pieces = 1: operands rounded to bf16 (nearest even), fp32 accumulation: plain mixed precision,
+ *                several times faster; gradients then carry the relative error of bf16 operands
+ *                (about 2^-8 of a contraction's sum of absolute terms).
+ * Masters, gradients, Adam and every other step stay fp32 either way.
+ */
+int sapo_trainer_set_matmul_pieces(sapo_trainer* tr, int pieces);
 /* Number of Adam steps taken (-1 for NULL). */
 int sapo_trainer_steps(const sapo_trainer* tr);
 /*

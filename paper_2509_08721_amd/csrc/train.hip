@@ -275,6 +275,13 @@ __device__ __forceinline__ void x3_store(uint4* __restrict__ dst, int NP, int KB
   uint32_t p[3][8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) split3(x[j], p[0][j], p[1][j], p[2][j]);
+  if (NP == 1) {   // a single piece is the value rounded to bf16 (nearest even), not its leading 8 bits
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const uint32_t u = __float_as_uint(x[j]);
+      p[0][j] = (u + 0x7FFFu + ((u >> 16) & 1u)) & 0xFFFF0000u;
+    }
+  }
   for (int pc = 0; pc < NP; ++pc)
     dst[x3_entry(NP, KB, pc, row, k8)] = make_uint4(pack_hi(p[pc][0], p[pc][1]), pack_hi(p[pc][2], p[pc][3]),
                                                     pack_hi(p[pc][4], p[pc][5]), pack_hi(p[pc][6], p[pc][7]));
@@ -743,6 +750,7 @@ struct sapo_trainer {
   sapo_model_config cfg;
   sapo_adam_config opt;
   int t = 0;                      // Adam steps taken
+  int pieces = 3;                 // bf16 pieces per value in the large GEMMs: 3 (fp32 accuracy) or 1 (bf16 operands)
   int device = 0;
   size_t n_params = 0;
   float* theta = nullptr;         // [n_params] masters, tensors back to back in tensor-list order
@@ -799,7 +807,7 @@ struct Arena {
 // Weight-gradient GEMMs with few output tiles (dW of the attention projections: 49 - 63 tiles of 128 x 128 on 256
 // compute units) are split over the token dimension into up to 8 parts that are added in part order.
 constexpr size_t kSplitParts = (size_t)8 * 192 * 128 * 128;
-constexpr int kPieces = 3;   // bf16 pieces per fp32 value in the packed GEMMs (3: fp32 accuracy)
+constexpr int kPieces = 3;   // most bf16 pieces per fp32 value in the packed GEMMs (3: fp32 accuracy; buffers are sized for it)
 
 struct LayerActs {
   float *h, *r1, *xn, *qkv, *lse, *ao, *h2, *r2, *xn2, *gu, *act;
@@ -972,6 +980,13 @@ extern "C" size_t sapo_trainer_workspace_bytes(const sapo_trainer* tr, int S, in
 
 extern "C" int sapo_trainer_steps(const sapo_trainer* tr) { return tr ? tr->t : -1; }
 
+extern "C" int sapo_trainer_set_matmul_pieces(sapo_trainer* tr, int pieces) {
+  if (!tr) return set_error(SAPO_EINVAL, "trainer is NULL");
+  if (pieces != 1 && pieces != 3) return set_error(SAPO_EINVAL, "pieces must be 3 (fp32 accuracy) or 1 (bf16 operands)");
+  tr->pieces = pieces;
+  return SAPO_OK;
+}
+
 extern "C" int sapo_trainer_read(const sapo_trainer* tr, int what, int tensor, float* out, size_t n, void* stream) {
   if (!tr || !out) return set_error(SAPO_EINVAL, "NULL argument");
   if (tensor < 0 || tensor >= (int)tr->len.size()) return set_error(SAPO_EINVAL, "tensor index %d out of range", tensor);
@@ -1043,7 +1058,8 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
   b_scores.causal = 1; b_dp.causal = 1; b_pv.causal = 2; b_dq.causal = 2; b_dk.causal = 3; b_dv.causal = 3;
 
   // The projections and the LM head run on the packed bf16-piece GEMM; forms as in sgemm<TA, TB>.
-  const X3Bufs xb{p.packa, p.packb, p.packa_cap, p.packb_cap, kPieces, p.kparts, kSplitParts};
+  const int pieces = tr->pieces;
+  const X3Bufs xb{p.packa, p.packb, p.packa_cap, p.packb_cap, pieces, p.kparts, kSplitParts};
   auto mm_nt = [&](const float* X, int ldx, const float* W, int ldw, float* C, int ldc, int M_, int N_, int K_, float beta,
                    const void* w_packed = nullptr) {   // C = beta C + X W^T
     return gemm_x3(X3Op{X, ldx, M_, K_, false}, X3Op{W, ldw, N_, K_, false}, C, ldc, beta, xb, st, false, nullptr, w_packed);
@@ -1091,8 +1107,8 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
   T_CK(g_fill_f32(tr->grad, 0.f, tr->n_params, st));
   T_CK(g_fill_f32(p.logp_new, 0.f, M, st));
   T_CK(launch(KID_MISC, k_count_mask, dim3(1), dim3(256), 0, st, completion_mask, M, p.n_masked));
-  T_CK(x3_pack(X3Op{TH(t_head), d, V, d, false}, p.head_nt, p.head_cap, kPieces, st));   // rows = vocabulary, k = d
-  T_CK(x3_pack(X3Op{TH(t_head), d, d, V, true}, p.head_t, p.head_t_cap, kPieces, st));    // rows = d, k = vocabulary
+  T_CK(x3_pack(X3Op{TH(t_head), d, V, d, false}, p.head_nt, p.head_cap, pieces, st));   // rows = vocabulary, k = d
+  T_CK(x3_pack(X3Op{TH(t_head), d, d, V, true}, p.head_t, p.head_t_cap, pieces, st));    // rows = d, k = vocabulary
   for (size_t r0 = 0; r0 < M; r0 += p.chunk) {
     const int R = (int)((M - r0 < p.chunk) ? M - r0 : p.chunk);
     T_CK(mm_nt(p.xf + r0 * D.d, d, TH(t_head), d, p.logits, V, R, V, d, 0.f, p.head_nt));

@@ -94,6 +94,8 @@ def load_library() -> C.CDLL:
     lib.sapo_policy_update.restype = i32
     lib.sapo_trainer_export.argtypes = [vp, C.POINTER(vp), i32, vp]
     lib.sapo_trainer_export.restype = i32
+    lib.sapo_trainer_set_matmul_pieces.argtypes = [vp, i32]
+    lib.sapo_trainer_set_matmul_pieces.restype = i32
     lib.sapo_trainer_steps.argtypes = [vp]
     lib.sapo_trainer_steps.restype = i32
     lib.sapo_trainer_read.argtypes = [vp, i32, i32, vp, sz, vp]
@@ -123,7 +125,7 @@ EXPORTED = ["sapo_weights_create", "sapo_weights_destroy", "sapo_weights_uses_mf
             "sapo_surrogate_workspace_bytes", "sapo_clipped_surrogate",
             "sapo_assemble_workspace_bytes", "sapo_assemble_training_set",
             "sapo_trainer_create", "sapo_trainer_destroy", "sapo_trainer_workspace_bytes", "sapo_policy_update",
-            "sapo_trainer_export", "sapo_trainer_steps", "sapo_trainer_read",
+            "sapo_trainer_export", "sapo_trainer_steps", "sapo_trainer_read", "sapo_trainer_set_matmul_pieces",
             "sapo_debug_logits", "sapo_debug_gumbel", "sapo_last_error", "sapo_profile_kernel_count",
             "sapo_profile_kernel_name", "sapo_profile_start", "sapo_profile_stop"]
 
@@ -471,6 +473,11 @@ def sapo_trainer_create(shape, weights: dict, lr: float = 1e-3, beta1: float = 0
 
 def sapo_trainer_destroy(tr: Trainer):
     tr.close()
+
+
+def sapo_trainer_set_matmul_pieces(tr: Trainer, pieces: int):
+    """3: fp32-accurate matrix products (default); 1: bf16 operands."""
+    _check(load_library().sapo_trainer_set_matmul_pieces(tr.handle, pieces))
 
 
 def sapo_trainer_steps(tr: Trainer) -> int:

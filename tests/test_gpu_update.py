@@ -292,3 +292,49 @@ def test_update_degenerate_batches(sapo):
     for g, b in zip(read_all(sapo, tr, 1), ref_g):
         assert float(np.max(np.abs(g - b))) <= 2e-4 * max(float(np.max(np.abs(b))), 1e-3 * gmax) + 1e-7
     tr.close()
+
+
+@pytest.mark.parametrize("which", ["mini", "halfb_4_layers"])
+def test_update_with_bf16_operands(sapo, which):
+    """sapo_trainer_set_matmul_pieces(tr, 1): the large GEMMs take their operands rounded to bf16 (fp32 accumulation).
+    An operand then carries a relative error of up to 2^-9, a product 2^-8, so a contraction is off by a small
+    multiple of 2^-8 of its typical term: the tolerances are those of the bf16 scoring path (log-probs 2e-2) and
+    5e-2 of a tensor's largest gradient entry, on models with the weight scale of the workloads (the stress cases of
+    the fp32-accurate tests have logits in the tens, where bf16 log-probs are off by 0.1 and clip branches flip)."""
+    import torch
+    from dataclasses import replace
+    from oracle import sapo_update_oracle as U
+    shape, seed, S, T, masked = ((W.MINI_BF16, 909, 4, 64, 40) if which == "mini"
+                                 else (replace(W.HALF_B, n_layers=4), 201, 2, 128, 64))
+    w = W.make_weights(shape, seed)
+    rng = np.random.default_rng(77)
+    tokens = rng.integers(0, shape.vocab, size=(S, T)).astype(np.int32)
+    mask = W.make_completion_mask(S, T, masked)
+    adv = rng.standard_normal(S).astype(np.float32)
+    params = U.parameter_list(shape, w)
+    _, lp0, _ = U.loss_and_gradients(shape, params, tokens, mask, np.zeros((S, T), np.float32), adv)
+    u = rng.uniform(-0.4, 0.4, size=lp0.shape)
+    u[(np.abs(np.exp(-u) - 1.28) < 0.05) | (np.abs(np.exp(-u) - 0.8) < 0.05)] = 0.0   # clear of the clip bounds by 2 x 2e-2
+    logp_old = (lp0 + u * (mask != 0)).astype(np.float32)
+    ref_loss, ref_lp, ref_g = U.loss_and_gradients(shape, params, tokens, mask, logp_old, adv)
+    tr = sapo.sapo_trainer_create(shape, w)
+    with pytest.raises(sapo.SapoError):
+        sapo.sapo_trainer_set_matmul_pieces(tr, 2)
+    sapo.sapo_trainer_set_matmul_pieces(tr, 1)
+    loss, lp = sapo.sapo_policy_update(tr, dev(tokens), dev(mask), dev(logp_old), dev(adv))
+    torch.cuda.synchronize()
+    lp_err = float(np.max(np.abs(lp.cpu().numpy() - ref_lp)))
+    assert 1e-5 < lp_err < 2e-2          # bf16 operands are really in use, and within the bf16 path's tolerance
+    assert abs(float(loss.cpu()[0]) - ref_loss) < 5e-3
+    gmax = max(float(np.max(np.abs(x))) for x in ref_g)
+    for i, b in enumerate(ref_g):
+        g = sapo.sapo_trainer_read(tr, 1, i).cpu().numpy().astype(np.float64)
+        assert float(np.max(np.abs(g - b))) <= 5e-2 * max(float(np.max(np.abs(b))), 1e-3 * gmax) + 1e-7, i
+    # back to three pieces: fp32 accuracy again
+    tr2 = sapo.sapo_trainer_create(shape, w)
+    sapo.sapo_trainer_set_matmul_pieces(tr2, 1)
+    sapo.sapo_trainer_set_matmul_pieces(tr2, 3)
+    _, lp3 = sapo.sapo_policy_update(tr2, dev(tokens), dev(mask), dev(logp_old), dev(adv))
+    torch.cuda.synchronize()
+    assert np.max(np.abs(lp3.cpu().numpy() - ref_lp)) < 2e-4
+    tr.close(); tr2.close()
