@@ -715,14 +715,28 @@ __global__ void k_dscores(const float* __restrict__ prob, float* __restrict__ dp
   dp[idx] = pr == 0.f ? 0.f : scale * pr * (dp[idx] - delta[idx / T]);
 }
 
-// Embedding rows: dE[tokens[m]] += dh[m], rows taken in order m = 0, 1, ... by the thread that owns the column.
+// Embedding rows: dE[tokens[m]] += dh[m].  Workgroup b owns the token ids congruent to b modulo the grid size
+// and walks the rows in order m = 0, 1, ..., 256 at a time: one id, one owner, one order of additions.
 __global__ void __launch_bounds__(256) k_embed_bwd(const int32_t* __restrict__ tokens, const float* __restrict__ dh, int M, int d,
                                                    int V, float* __restrict__ dE) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= d) return;
-  for (int m = 0; m < M; ++m) {
-    float* p = dE + (size_t)clamp_token(tokens[m], V) * d + i;
-    *p += dh[(size_t)m * d + i];
+  __shared__ int s_tok[256];
+  for (int m0 = 0; m0 < M; m0 += 256) {
+    const int m = m0 + threadIdx.x;
+    int tok = -1;
+    if (m < M) {
+      tok = clamp_token(tokens[m], V);
+      if (tok % (int)gridDim.x != (int)blockIdx.x) tok = -1;
+    }
+    __syncthreads();   // the previous round's list has been read
+    s_tok[threadIdx.x] = tok;
+    __syncthreads();
+    for (int j = 0; j < 256; ++j) {
+      const int t = s_tok[j];   // the same for every thread
+      if (t < 0) continue;
+      const float* src = dh + (size_t)(m0 + j) * d;
+      float* dst = dE + (size_t)t * d;
+      for (int i = threadIdx.x; i < d; i += 256) dst[i] += src[i];
+    }
   }
 }
 
@@ -1178,7 +1192,7 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
     T_CK(mm_tn(p.dqkv, nqkv, a.xn, d, GR(t0 + 1), nqkv, d, Mi, 0.f));
     T_CK(norm_bwd(p.dx, a.h, a.r1, t0, 1));
   }
-  T_CK(launch(KID_EMBED, k_embed_bwd, dim3((d + 255) / 256), dim3(256), 0, st, tokens, (const float*)p.dh, Mi, d, V, GR(0)));
+  T_CK(launch(KID_EMBED, k_embed_bwd, dim3(512), dim3(256), 0, st, tokens, (const float*)p.dh, Mi, d, V, GR(0)));
 
   // ---- Adam
   tr->t += 1;
