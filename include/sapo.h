@@ -266,8 +266,10 @@ void sapo_trainer_destroy(sapo_trainer* tr);
 /* Workspace of one update over S sequences of T tokens (every layer's activations are kept for the
  * backward pass: about 4 (4 d + 2 Hq hd + 2 Hkv hd + 3 F) bytes per token and layer, plus score
  * matrices, a chunk of logits and packed GEMM operands); 0 on invalid arguments (T < 2 or
- * T > max_seq).  At most 8192 tokens per sequence and 65535 (sequence, query head) pairs per call. */
+ * T > max_seq).  At most 8192 tokens per sequence. */
 size_t sapo_trainer_workspace_bytes(const sapo_trainer* tr, int S, int T);
+/* The same when the update is to run S_micro <= S sequences at a time (see sapo_policy_update). */
+size_t sapo_trainer_workspace_bytes_for(const sapo_trainer* tr, int S, int T, int S_micro);
 /*
  * One update on the training set: teacher-forced forward pass under the masters, loss =
  * sapo_clipped_surrogate(logp_new, logp_old, mask, advantages), backward pass, one Adam step on
@@ -281,7 +283,12 @@ size_t sapo_trainer_workspace_bytes(const sapo_trainer* tr, int S, int T);
  *   out_loss         dev fp32 [1]       the loss before the step
  *   out_logp_new     dev fp32 [S, T] or NULL: the log-probs under the masters before the step (0 where
  *                                       the mask is clear)
- *   workspace        dev, >= sapo_trainer_workspace_bytes(tr, S, T), 256-byte aligned
+ *   workspace        dev, 256-byte aligned.  With sapo_trainer_workspace_bytes(tr, S, T) bytes the whole set
+ *                    goes through forward and backward at once; with less, the call works through it in
+ *                    micro-batches of the largest number of sequences whose activations fit
+ *                    (sapo_trainer_workspace_bytes_for gives the size for a chosen number), adding their
+ *                    gradients up before the one Adam step: the same update up to the order of fp32
+ *                    additions.  SAPO_EWORKSPACE if not even one sequence fits.
  * fp32 values throughout (the large matrix products are formed from bf16 pieces on the matrix cores
  * with the accuracy of fp32 products), every sum in a fixed order (no atomics): the same call on the
  * same state gives the same bits.  Asynchronous on `stream`; the trainer's state is updated in place, so

@@ -438,7 +438,7 @@ hipError_t gemm_x3(const X3Op& A, const X3Op& B, float* C, int ldc, float beta, 
   // are split into parts, each part writes its own product and k_sum_parts adds them in part order
   const long tiles = (long)gnx * gny;
   int splits = 1;
-  if (split_ok && beta == 0.f && ldc == B.rows) {
+  if (split_ok && ldc == B.rows) {
     while (splits < 8 && tiles * splits < 192 && KB / (splits * 2) >= 16) splits *= 2;
     if ((size_t)splits * A.rows * B.rows > bufs.parts_cap) splits = 1;
   }
@@ -448,14 +448,14 @@ hipError_t gemm_x3(const X3Op& A, const X3Op& B, float* C, int ldc, float beta, 
   float* out = splits > 1 ? bufs.parts : C;
   const size_t c_split = splits > 1 ? (size_t)A.rows * B.rows : 0;
   if (bufs.NP == 3)
-    e = launch(KID_GEMM_GENERIC, k_gemm_x3<3>, grid, dim3(256), 0, st, pa_, pb_, out, ldc, A.rows, B.rows, KB, beta, kbs,
-               c_split);
+    e = launch(KID_GEMM_GENERIC, k_gemm_x3<3>, grid, dim3(256), 0, st, pa_, pb_, out, ldc, A.rows, B.rows, KB,
+               splits > 1 ? 0.f : beta, kbs, c_split);
   else
-    e = launch(KID_GEMM_GENERIC, k_gemm_x3<1>, grid, dim3(256), 0, st, pa_, pb_, out, ldc, A.rows, B.rows, KB, beta, kbs,
-               c_split);
+    e = launch(KID_GEMM_GENERIC, k_gemm_x3<1>, grid, dim3(256), 0, st, pa_, pb_, out, ldc, A.rows, B.rows, KB,
+               splits > 1 ? 0.f : beta, kbs, c_split);
   if (e != hipSuccess || splits == 1) return e;
   const size_t n = (size_t)A.rows * B.rows;
-  return launch(KID_MISC, k_sum_parts, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const float*)bufs.parts, splits, n, 0.f,
+  return launch(KID_MISC, k_sum_parts, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const float*)bufs.parts, splits, n, beta,
                 C);
 }
 
@@ -676,7 +676,7 @@ __global__ void __launch_bounds__(256) k_gain_grad_finish(const float* __restric
   if (i >= d) return;
   float s = 0.f;
   for (int p = 0; p < n_part; ++p) s += part[(size_t)p * d + i];
-  dgain[i] = s;
+  dgain[i] += s;   // the gradient buffer starts at zero; micro-batches add up
 }
 
 // dgu from dact: d gate = dact * up * sig(g) (1 + g (1 - sig(g))), d up = dact * silu(g)
@@ -830,7 +830,7 @@ struct TrainPlan {
   std::vector<LayerActs> layer;
   float *h_last, *rf, *xf;                      // final residual rows, their rstd, final-normed rows
   float *dh, *dx, *dact, *dgu, *dao, *dqkv;     // backward temporaries
-  float *delta, *prob, *dsc, *gpart, *logits, *logp_new, *loss;
+  float *delta, *prob, *dsc, *gpart, *logits, *logp_all, *loss;
   void* sur_ws;
   long long* n_masked;
   float* kparts;                                // partial products of the split weight-gradient GEMMs
@@ -840,7 +840,7 @@ struct TrainPlan {
   size_t bytes;
 };
 
-void make_plan(const sapo_model_config& c, size_t S, size_t T, char* base, TrainPlan& p) {
+void make_plan(const sapo_model_config& c, size_t S, size_t T, size_t S_total, char* base, TrainPlan& p) {
   const Dims D(c);
   const size_t M = S * T;
   Arena A{base, 0};
@@ -874,7 +874,7 @@ void make_plan(const sapo_model_config& c, size_t S, size_t T, char* base, Train
   p.gpart = A.take<float>(((M + 255) / 256) * D.d);
   p.chunk = lm_chunk_rows(D, M);
   p.logits = A.take<float>(p.chunk * D.V);
-  p.logp_new = A.take<float>(M);
+  p.logp_all = A.take<float>(S_total * T);   // log-probs of the whole training set (micro-batches fill their rows)
   p.loss = A.take<float>(4);
   p.n_masked = A.take<long long>(1);
   p.kparts = A.take<float>(kSplitParts);
@@ -988,7 +988,14 @@ extern "C" int sapo_trainer_create(const sapo_model_config* cfg, const void* con
 extern "C" size_t sapo_trainer_workspace_bytes(const sapo_trainer* tr, int S, int T) {
   if (!tr || S <= 0 || T < 2 || T > tr->cfg.max_seq) return 0;
   TrainPlan p;
-  make_plan(tr->cfg, (size_t)S, (size_t)T, nullptr, p);
+  make_plan(tr->cfg, (size_t)S, (size_t)T, (size_t)S, nullptr, p);
+  return p.bytes;
+}
+
+extern "C" size_t sapo_trainer_workspace_bytes_for(const sapo_trainer* tr, int S, int T, int S_micro) {
+  if (!tr || S <= 0 || T < 2 || T > tr->cfg.max_seq || S_micro <= 0 || S_micro > S) return 0;
+  TrainPlan p;
+  make_plan(tr->cfg, (size_t)S_micro, (size_t)T, (size_t)S, nullptr, p);
   return p.bytes;
 }
 
@@ -1026,25 +1033,15 @@ extern "C" int sapo_trainer_export(const sapo_trainer* tr, void* const* tensors_
   return SAPO_OK;
 }
 
-extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const uint8_t* completion_mask,
-                                  const float* logp_old, const float* advantages, int S_, int T_, float eps_low,
-                                  float eps_high, float* out_loss, float* out_logp_new, void* workspace,
-                                  size_t workspace_bytes, void* stream) {
-  if (!tr || !tokens || !completion_mask || !logp_old || !advantages || !out_loss || !workspace)
-    return set_error(SAPO_EINVAL, "NULL argument");
-  if (S_ <= 0 || T_ < 2) return set_error(SAPO_EINVAL, "S must be positive and T at least 2");
-  if (T_ > tr->cfg.max_seq) return set_error(SAPO_EINVAL, "T = %d exceeds max_seq = %d", T_, tr->cfg.max_seq);
-  if (T_ > 8192 || (long)S_ * tr->cfg.n_q_heads > 65535)
-    return set_error(SAPO_EINVAL, "at most 8192 tokens per sequence and 65535 (sequence, query head) pairs");
-  if (!(eps_low >= 0.f && eps_low < 1.f) || !(eps_high >= 0.f)) return set_error(SAPO_EINVAL, "eps_low in [0, 1), eps_high >= 0");
+// Forward, LM head and backward over one micro-batch of S_ sequences: gradients are added to tr->grad, the
+// log-probs go to logp_new [S_, T_].  p.n_masked holds the count of masked tokens of the whole training set and
+// the LM head is packed (p.head_nt, p.head_t).
+static int update_rows(sapo_trainer* tr, const TrainPlan& p, const int32_t* tokens, const uint8_t* completion_mask,
+                       const float* logp_old, const float* advantages, int S_, int T_, float eps_low, float eps_high,
+                       float* logp_new, hipStream_t st) {
   const sapo_model_config& c = tr->cfg;
   const Dims D(c);
   const size_t S = S_, T = T_, M = S * T;
-  if (M * D.V >= ((size_t)1 << 40) || M >= ((size_t)1 << 30)) return set_error(SAPO_EINVAL, "batch too large");
-  TrainPlan p;
-  make_plan(c, S, T, (char*)workspace, p);
-  if (workspace_bytes < p.bytes) return set_error(SAPO_EWORKSPACE, "workspace is %zu bytes, %zu needed", workspace_bytes, p.bytes);
-  hipStream_t st = (hipStream_t)stream;
   const int d = (int)D.d, q = (int)D.q, kv = (int)D.kv, nqkv = (int)D.nqkv, F = (int)D.F, V = (int)D.V;
   const int hq = c.n_q_heads, hkv = c.n_kv_heads, hd = c.head_dim;
   const int Mi = (int)M;
@@ -1118,25 +1115,15 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
               c.rms_eps, d, p.xf, p.rf));
 
   // ---- LM head, one pass over chunks of rows: logits, log-probs, d logits, then d xf (into p.dx) and d head
-  T_CK(g_fill_f32(tr->grad, 0.f, tr->n_params, st));
-  T_CK(g_fill_f32(p.logp_new, 0.f, M, st));
-  T_CK(launch(KID_MISC, k_count_mask, dim3(1), dim3(256), 0, st, completion_mask, M, p.n_masked));
-  T_CK(x3_pack(X3Op{TH(t_head), d, V, d, false}, p.head_nt, p.head_cap, pieces, st));   // rows = vocabulary, k = d
-  T_CK(x3_pack(X3Op{TH(t_head), d, d, V, true}, p.head_t, p.head_t_cap, pieces, st));    // rows = d, k = vocabulary
+  T_CK(g_fill_f32(logp_new, 0.f, M, st));
   for (size_t r0 = 0; r0 < M; r0 += p.chunk) {
     const int R = (int)((M - r0 < p.chunk) ? M - r0 : p.chunk);
     T_CK(mm_nt(p.xf + r0 * D.d, d, TH(t_head), d, p.logits, V, R, V, d, 0.f, p.head_nt));
     T_CK(launch(KID_SCORE_ROWS, k_logp_dlogits, dim3(R), dim3(256), 0, st, p.logits, V, (int)r0, (int)T, tokens, completion_mask,
-                logp_old, advantages, eps_low, eps_high, (const long long*)p.n_masked, p.logp_new));
+                logp_old, advantages, eps_low, eps_high, (const long long*)p.n_masked, logp_new));
     T_CK(mm_nn(p.logits, V, TH(t_head), d, p.dx + r0 * D.d, d, R, d, V, 0.f, p.head_t));
     T_CK(mm_tn(p.logits, V, p.xf + r0 * D.d, d, GR(t_head), V, d, R, 1.f));
   }
-  // ---- the loss (the surrogate of sapo_clipped_surrogate on the log-probs just computed)
-  T_CK(g_surrogate_loss(p.logp_new, logp_old, completion_mask, advantages, S_, T_, eps_low, eps_high, p.loss, nullptr, p.sur_ws,
-                        st));
-  T_CK(hipMemcpyAsync(out_loss, p.loss, sizeof(float), hipMemcpyDeviceToDevice, st));
-  if (out_logp_new) T_CK(hipMemcpyAsync(out_logp_new, p.logp_new, M * sizeof(float), hipMemcpyDeviceToDevice, st));
-
   // ---- backward through the layers
   const int n_gpart = (Mi + 255) / 256;
   auto norm_bwd = [&](const float* dxn, const float* hin, const float* rstd, int gain_tensor_idx, int accumulate) -> hipError_t {
@@ -1155,16 +1142,16 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
     const int t0 = 1 + 9 * l;
     // down projection
     T_CK(mm_nn(p.dh, d, TH(t0 + 8), F, p.dact, F, Mi, F, d, 0.f));
-    T_CK(mm_tn(p.dh, d, a.act, F, GR(t0 + 8), d, F, Mi, 0.f));
+    T_CK(mm_tn(p.dh, d, a.act, F, GR(t0 + 8), d, F, Mi, 1.f));
     T_CK(launch(KID_SWIGLU, k_swiglu_bwd, dim3(blocks256(M * D.F)), dim3(256), 0, st, (const float*)p.dact, (const float*)a.gu,
                 p.dgu, F, M * D.F));
     // gate / up projections
     T_CK(mm_nn(p.dgu, 2 * F, TH(t0 + 6), d, p.dx, d, Mi, d, 2 * F, 0.f));
-    T_CK(mm_tn(p.dgu, 2 * F, a.xn2, d, GR(t0 + 6), 2 * F, d, Mi, 0.f));
+    T_CK(mm_tn(p.dgu, 2 * F, a.xn2, d, GR(t0 + 6), 2 * F, d, Mi, 1.f));
     T_CK(norm_bwd(p.dx, a.h2, a.r2, t0 + 5, 1));
     // output projection
     T_CK(mm_nn(p.dh, d, TH(t0 + 4), q, p.dao, q, Mi, q, d, 0.f));
-    T_CK(mm_tn(p.dh, d, a.ao, q, GR(t0 + 4), d, q, Mi, 0.f));
+    T_CK(mm_tn(p.dh, d, a.ao, q, GR(t0 + 4), d, q, Mi, 1.f));
     // attention and the rotary embedding
     T_CK((sgemm<0, 1>(a.qkv, nqkv, a.qkv + q, nqkv, p.prob, (int)T, (int)T, (int)T, hd, 0.f, st, b_scores)));
     T_CK(launch(KID_ATTN_GENERIC, k_probs_from_lse, dim3(blocks256(n_sc)), dim3(256), 0, st, p.prob, (const float*)a.lse, (int)T,
@@ -1189,10 +1176,68 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
     }
     // query / key / value projections
     T_CK(mm_nn(p.dqkv, nqkv, TH(t0 + 1), d, p.dx, d, Mi, d, nqkv, 0.f));
-    T_CK(mm_tn(p.dqkv, nqkv, a.xn, d, GR(t0 + 1), nqkv, d, Mi, 0.f));
+    T_CK(mm_tn(p.dqkv, nqkv, a.xn, d, GR(t0 + 1), nqkv, d, Mi, 1.f));
     T_CK(norm_bwd(p.dx, a.h, a.r1, t0, 1));
   }
   T_CK(launch(KID_EMBED, k_embed_bwd, dim3(512), dim3(256), 0, st, tokens, (const float*)p.dh, Mi, d, V, GR(0)));
+
+  return SAPO_OK;
+}
+
+extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const uint8_t* completion_mask,
+                                  const float* logp_old, const float* advantages, int S_, int T_, float eps_low,
+                                  float eps_high, float* out_loss, float* out_logp_new, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+  if (!tr || !tokens || !completion_mask || !logp_old || !advantages || !out_loss || !workspace)
+    return set_error(SAPO_EINVAL, "NULL argument");
+  if (S_ <= 0 || T_ < 2) return set_error(SAPO_EINVAL, "S must be positive and T at least 2");
+  if (T_ > tr->cfg.max_seq) return set_error(SAPO_EINVAL, "T = %d exceeds max_seq = %d", T_, tr->cfg.max_seq);
+  if (T_ > 8192) return set_error(SAPO_EINVAL, "at most 8192 tokens per sequence");
+  if (!(eps_low >= 0.f && eps_low < 1.f) || !(eps_high >= 0.f)) return set_error(SAPO_EINVAL, "eps_low in [0, 1), eps_high >= 0");
+  const sapo_model_config& c = tr->cfg;
+  const Dims D(c);
+  const size_t S = S_, T = T_, M = S * T;
+  if (M >= ((size_t)1 << 30)) return set_error(SAPO_EINVAL, "batch too large");
+  // Micro-batches: the largest number of sequences whose activations fit the workspace is pushed through forward
+  // and backward at a time, the gradients adding up; the whole set at once when the workspace allows it.
+  TrainPlan p;
+  size_t S_mb = S;
+  const size_t most = (size_t)65535 / c.n_q_heads;   // (sequence, query head) pairs of one batched attention GEMM
+  if (S_mb > most) S_mb = most;
+  make_plan(c, S_mb, T, S, nullptr, p);
+  if (workspace_bytes < p.bytes) {
+    size_t lo = 0, hi = S_mb;   // plan(lo) fits (lo = 0: nothing known to fit), plan(hi) does not
+    while (hi - lo > 1) {
+      const size_t mid = (lo + hi) / 2;
+      make_plan(c, mid, T, S, nullptr, p);
+      if (p.bytes <= workspace_bytes) lo = mid; else hi = mid;
+    }
+    if (lo == 0) {
+      make_plan(c, 1, T, S, nullptr, p);
+      return set_error(SAPO_EWORKSPACE, "workspace is %zu bytes, at least %zu needed (one sequence at a time)", workspace_bytes,
+                       p.bytes);
+    }
+    S_mb = lo;
+  }
+  make_plan(c, S_mb, T, S, (char*)workspace, p);
+  hipStream_t st = (hipStream_t)stream;
+  const int t_head = c.tied_embeddings ? 0 : 1 + 9 * c.n_layers + 1;
+  const int d = (int)D.d, V = (int)D.V;
+  T_CK(g_fill_f32(tr->grad, 0.f, tr->n_params, st));
+  T_CK(launch(KID_MISC, k_count_mask, dim3(1), dim3(256), 0, st, completion_mask, M, p.n_masked));
+  T_CK(x3_pack(X3Op{tr->theta + tr->off[t_head], d, V, d, false}, p.head_nt, p.head_cap, tr->pieces, st));   // rows = vocabulary
+  T_CK(x3_pack(X3Op{tr->theta + tr->off[t_head], d, d, V, true}, p.head_t, p.head_t_cap, tr->pieces, st));    // rows = d
+  for (size_t s0 = 0; s0 < S; s0 += S_mb) {
+    const int n = (int)(S - s0 < S_mb ? S - s0 : S_mb);
+    const int rc = update_rows(tr, p, tokens + s0 * T, completion_mask + s0 * T, logp_old + s0 * T, advantages + s0, n, T_,
+                               eps_low, eps_high, p.logp_all + s0 * T, st);
+    if (rc != SAPO_OK) return rc;
+  }
+  // ---- the loss (the surrogate of sapo_clipped_surrogate on the log-probs just computed)
+  T_CK(g_surrogate_loss(p.logp_all, logp_old, completion_mask, advantages, S_, T_, eps_low, eps_high, p.loss, nullptr, p.sur_ws,
+                        st));
+  T_CK(hipMemcpyAsync(out_loss, p.loss, sizeof(float), hipMemcpyDeviceToDevice, st));
+  if (out_logp_new) T_CK(hipMemcpyAsync(out_logp_new, p.logp_all, M * sizeof(float), hipMemcpyDeviceToDevice, st));
 
   // ---- Adam
   tr->t += 1;

@@ -90,6 +90,8 @@ def load_library() -> C.CDLL:
     lib.sapo_trainer_destroy.restype = None
     lib.sapo_trainer_workspace_bytes.argtypes = [vp, i32, i32]
     lib.sapo_trainer_workspace_bytes.restype = sz
+    lib.sapo_trainer_workspace_bytes_for.argtypes = [vp, i32, i32, i32]
+    lib.sapo_trainer_workspace_bytes_for.restype = sz
     lib.sapo_policy_update.argtypes = [vp, vp, vp, vp, vp, i32, i32, f32, f32, vp, vp, vp, sz, vp]
     lib.sapo_policy_update.restype = i32
     lib.sapo_trainer_export.argtypes = [vp, C.POINTER(vp), i32, vp]
@@ -124,7 +126,8 @@ EXPORTED = ["sapo_weights_create", "sapo_weights_destroy", "sapo_weights_uses_mf
             "sapo_score_logprobs", "sapo_score_logprobs_at",
             "sapo_surrogate_workspace_bytes", "sapo_clipped_surrogate",
             "sapo_assemble_workspace_bytes", "sapo_assemble_training_set",
-            "sapo_trainer_create", "sapo_trainer_destroy", "sapo_trainer_workspace_bytes", "sapo_policy_update",
+            "sapo_trainer_create", "sapo_trainer_destroy", "sapo_trainer_workspace_bytes", "sapo_trainer_workspace_bytes_for",
+            "sapo_policy_update",
             "sapo_trainer_export", "sapo_trainer_steps", "sapo_trainer_read", "sapo_trainer_set_matmul_pieces",
             "sapo_debug_logits", "sapo_debug_gumbel", "sapo_last_error", "sapo_profile_kernel_count",
             "sapo_profile_kernel_name", "sapo_profile_start", "sapo_profile_stop"]
@@ -486,6 +489,10 @@ def sapo_trainer_steps(tr: Trainer) -> int:
 
 def sapo_trainer_workspace_bytes(tr: Trainer, S: int, T: int) -> int:
     return int(load_library().sapo_trainer_workspace_bytes(tr.handle, S, T))
+
+
+def sapo_trainer_workspace_bytes_for(tr: Trainer, S: int, T: int, S_micro: int) -> int:
+    return int(load_library().sapo_trainer_workspace_bytes_for(tr.handle, S, T, S_micro))
 
 
 def sapo_policy_update(tr: Trainer, tokens, completion_mask, logp_old, advantages, eps_low: float = 0.2,

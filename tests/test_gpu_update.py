@@ -338,3 +338,41 @@ def test_update_with_bf16_operands(sapo, which):
     torch.cuda.synchronize()
     assert np.max(np.abs(lp3.cpu().numpy() - ref_lp)) < 2e-4
     tr.close(); tr2.close()
+
+
+def test_update_in_micro_batches(sapo):
+    """A workspace too small for the whole training set: the call works through it a few sequences at a time and
+    adds the gradients up; same loss and log-probs, same gradient up to the order of fp32 additions, same parity bar."""
+    import torch
+    from oracle import sapo_update_oracle as U
+    shape = SHAPES["tiny"]
+    S, T = 8, 32
+    w, params, tokens, mask, logp_old, adv = make_case(shape, 4711, S, T, 16)
+    ref_loss, ref_lp, ref_g = U.loss_and_gradients(shape, params, tokens, mask, logp_old, adv)
+    gmax = max(float(np.max(np.abs(x))) for x in ref_g)
+    results = []
+    for s_micro in (8, 3, 1):
+        tr = sapo.sapo_trainer_create(shape, w)
+        nbytes = sapo.sapo_trainer_workspace_bytes_for(tr, S, T, s_micro)
+        assert nbytes > 0 and (s_micro == 8) == (nbytes == sapo.sapo_trainer_workspace_bytes(tr, S, T))
+        ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+        loss, lp = sapo.sapo_policy_update(tr, dev(tokens), dev(mask), dev(logp_old), dev(adv), workspace=ws)
+        torch.cuda.synchronize()
+        g = read_all(sapo, tr, 1)
+        results.append((float(loss.cpu()[0]), lp.cpu().numpy(), g, read_all(sapo, tr, 0)))
+        assert np.max(np.abs(results[-1][1] - ref_lp)) < 2e-4 and abs(results[-1][0] - ref_loss) < 1e-4 * max(1.0, abs(ref_loss))
+        for a, b in zip(g, ref_g):
+            assert float(np.max(np.abs(a - b))) <= 2e-4 * max(float(np.max(np.abs(b))), 1e-3 * gmax) + 1e-7
+        assert tr.steps == 1
+        tr.close()
+    for other in results[1:]:
+        assert np.allclose(other[1], results[0][1], rtol=0, atol=1e-5)     # per-row work: the batch size does not enter
+        for a, b in zip(other[2], results[0][2]):
+            assert float(np.max(np.abs(a - b))) <= 1e-5 * max(float(np.max(np.abs(b))), 1e-3 * gmax)
+    # not even one sequence fits
+    tr = sapo.sapo_trainer_create(shape, w)
+    small = torch.empty(sapo.sapo_trainer_workspace_bytes_for(tr, S, T, 1) // 2, dtype=torch.uint8, device="cuda")
+    with pytest.raises(sapo.SapoError) as e:
+        sapo.sapo_policy_update(tr, dev(tokens), dev(mask), dev(logp_old), dev(adv), workspace=small)
+    assert e.value.code == sapo.SAPO_EWORKSPACE and tr.steps == 0
+    tr.close()
