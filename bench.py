@@ -10,8 +10,8 @@ completions, Sec. 4.1 / Sec. 5) on the 0.5B-class decoder with synthetic weights
 Other workloads (--workload): halfb_long (rollout only, long generation), halfb_score_mixed
 (scoring only, half local / half external rollouts; the batch is prepared untimed), onehalfb
 (1.5B-class decoder, rollout + scoring), tiny, halfb_pass1 (one sequence: the latency of a
-decode step at batch 1), halfb_update (the local policy update on configuration 2's training set:
-trained tokens/s).
+decode step at batch 1), halfb_update / onehalfb_update (the local policy update on configuration 2's / 5's training set:
+trained tokens/s; --pieces 1 for bf16 GEMM operands).
 
 Prints ONE JSON line.
 """
@@ -125,7 +125,12 @@ def bench_update(args, wl):
     gw.close()
     tr = sapo.sapo_trainer_create(shape, weights)
     sapo.sapo_trainer_set_matmul_pieces(tr, args.pieces)
-    nbytes = sapo.sapo_trainer_workspace_bytes(tr, S, T)
+    # the whole set at once if its activations fit the free memory, else the largest micro-batch (halving) that does
+    s_micro = S
+    free_b = torch.cuda.mem_get_info()[0]
+    while s_micro > 1 and sapo.sapo_trainer_workspace_bytes_for(tr, S, T, s_micro) > 0.9 * free_b:
+        s_micro = (s_micro + 1) // 2
+    nbytes = sapo.sapo_trainer_workspace_bytes_for(tr, S, T, s_micro)
     ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
     setup_s = time.time() - t0
     losses = []
@@ -183,7 +188,8 @@ def bench_update(args, wl):
                       "arithmetic": "fp32 (GEMM products as 6 bf16 x bf16 partial products, fp32 accumulation)" if args.pieces == 3
                       else "fp32 with bf16 GEMM operands (1 piece), fp32 accumulation",
                       "layers": shape.n_layers, "d_model": shape.d_model, "vocab": shape.vocab,
-                      "seqs": S, "seq_len": T, "masked": Tm, "optimizer": "Adam lr 1e-3 (defaults)",
+                      "seqs": S, "seq_len": T, "masked": Tm, "sequences_per_micro_batch": s_micro,
+                      "optimizer": "Adam lr 1e-3 (defaults)",
                       "weights": "fp32 masters of the bf16 model"},
            "update_flops": flops, "achieved_TFLOPs": round(flops / dt / 1e12, 2),
            "workspace_GB": round(nbytes / 2 ** 30, 2), "loss_first": round(float(losses[0].cpu()[0]), 6),

@@ -161,6 +161,11 @@ WORKLOADS: Dict[str, Workload] = {
     "halfb_update": Workload("halfb_update", HALF_B, weight_seed=201, n_prompts=8, group=8, prompt_len=128,
                              n_new=0, prompt_seed=202, score_seqs=64, score_len=384, score_masked=256,
                              reward_p=0.3, reward_seed=204),
+    # the same for configuration 5 (1.5B-class decoder, 256 sequences of 256 + 512 tokens): the activations of the
+    # whole set would not fit one GPU, the update runs in micro-batches
+    "onehalfb_update": Workload("onehalfb_update", ONE_HALF_B, weight_seed=501, n_prompts=32, group=8, prompt_len=256,
+                                n_new=0, prompt_seed=502, score_seqs=256, score_len=768, score_masked=512,
+                                reward_p=0.3, reward_seed=504),
     "halfb_pass1": Workload("halfb_pass1", HALF_B, weight_seed=201, n_prompts=1, group=1,
                             prompt_len=128, n_new=256, temperature=1.0, prompt_seed=602,
                             rollout_seed=603),
