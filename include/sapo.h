@@ -253,8 +253,8 @@ int sapo_clipped_surrogate(const float* logp_new, const float* logp_old, const u
  * times the model in fp32, allocated by sapo_trainer_create and released by sapo_trainer_destroy.
  *   cfg, tensors, n_tensors   as for sapo_weights_create (device pointers, element type per
  *                             cfg->dtype, gains fp32); bf16 values become the fp32 masters unchanged.
- *                             head_dim at most 128.  A model with projection biases is not
- *                             supported (the biases would stay untrained).
+ *                             head_dim at most 128.  The trainer's model has no projection biases
+ *                             (sapo_weights_set_qkv_bias has no counterpart here).
  *   opt                       Adam's constants, or NULL for the defaults named above
  * Complete once `stream` has been synchronised.
  */

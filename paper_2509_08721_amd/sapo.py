@@ -464,6 +464,8 @@ def sapo_trainer_create(shape, weights: dict, lr: float = 1e-3, beta1: float = 0
     torch = _torch()
     lib = load_library()
     cfg = make_config(shape)
+    if any("bq" in lw for lw in weights["layers"]):
+        raise ValueError("the trainer's model has no projection biases: these weights carry them")
     order = _tensor_order(weights)
     dev = [_to_device(a) for a in order]
     ptrs = (C.c_void_p * len(dev))(*[t.data_ptr() for t in dev])
