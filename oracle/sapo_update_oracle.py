@@ -44,14 +44,22 @@ LAYER_MATS = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up",
 def parameter_list(shape, weights: dict) -> List[np.ndarray]:
     """The trainable tensors as float64 arrays in the order of the library's tensor list:
     embed, per layer (attn_norm, wq, wk, wv, wo, ffn_norm, w_gate, w_up, w_down), final_norm,
-    lm_head (only when the head is untied)."""
+    lm_head (only when the head is untied), then, if the model has projection biases, one vector
+    [bq | bk | bv] per layer."""
     out = [O._stored_to_f64(weights["embed"])]
     for lw in weights["layers"][: shape.n_layers]:
-        assert "bq" not in lw, "projection biases are not trained here"
         out += [O._stored_to_f64(lw[k]) for k in LAYER_MATS]
     out.append(O._stored_to_f64(weights["final_norm"]))
     if weights.get("lm_head") is not None:
         out.append(O._stored_to_f64(weights["lm_head"]))
+    if any("bq" in lw for lw in weights["layers"][: shape.n_layers]):
+        # optional biases of the query / key / value projections: one vector [bq | bk | bv] per layer, after
+        # everything else (a layer without them gets zeros, which are then trained like the others)
+        for lw in weights["layers"][: shape.n_layers]:
+            if "bq" in lw:
+                out.append(np.concatenate([lw["bq"], lw["bk"], lw["bv"]]).astype(np.float64))
+            else:
+                out.append(np.zeros(shape.q_dim + 2 * shape.kv_dim))
     return out
 
 
@@ -63,7 +71,13 @@ def weights_from_parameters(shape, params: Sequence[np.ndarray]) -> dict:
         w["layers"].append({k: np.asarray(next(it)) for k in LAYER_MATS})
     w["final_norm"] = np.asarray(next(it))
     rest = list(it)
-    w["lm_head"] = np.asarray(rest[0]) if rest else None
+    w["lm_head"] = np.asarray(rest.pop(0)) if (not shape.tied_embeddings) else None
+    if rest:
+        assert len(rest) == shape.n_layers
+        q, kv = shape.q_dim, shape.kv_dim
+        for lw, b in zip(w["layers"], rest):
+            b = np.asarray(b)
+            lw["bq"], lw["bk"], lw["bv"] = b[:q], b[q:q + kv], b[q + kv:]
     return w
 
 
@@ -93,14 +107,21 @@ def _sequence_logprobs(shape, p: Sequence[torch.Tensor], tokens: np.ndarray) -> 
     tok = torch.as_tensor(np.asarray(tokens, dtype=np.int64))
     h = p[0][tok]
     causal = torch.tril(torch.ones(T, T, dtype=torch.bool))
+    n_plain = 1 + 9 * shape.n_layers + 1 + (0 if shape.tied_embeddings else 1)
+    biases = p[n_plain:] if len(p) > n_plain else None      # per layer [bq | bk | bv], added before the rotary embedding
+    qd, kvd = hq * hd, hkv * hd
     i = 1
-    for _ in range(shape.n_layers):
+    for layer in range(shape.n_layers):
         g1, wq, wk, wv, wo, g2, wg, wu, wd = p[i:i + 9]
         i += 9
         a = _rmsnorm(h, g1, shape.rms_eps)
-        q = _rope((a @ wq.T).reshape(T, hq, hd), shape.rope_theta)
-        k = _rope((a @ wk.T).reshape(T, hkv, hd), shape.rope_theta)
-        v = (a @ wv.T).reshape(T, hkv, hd)
+        q, k, v = a @ wq.T, a @ wk.T, a @ wv.T
+        if biases is not None:
+            b = biases[layer]
+            q, k, v = q + b[:qd], k + b[qd:qd + kvd], v + b[qd + kvd:]
+        q = _rope(q.reshape(T, hq, hd), shape.rope_theta)
+        k = _rope(k.reshape(T, hkv, hd), shape.rope_theta)
+        v = v.reshape(T, hkv, hd)
         heads = []
         for hh in range(hq):
             s = (q[:, hh, :] @ k[:, hh // rep, :].T) / math.sqrt(hd)
@@ -110,7 +131,7 @@ def _sequence_logprobs(shape, p: Sequence[torch.Tensor], tokens: np.ndarray) -> 
         b = _rmsnorm(h, g2, shape.rms_eps)
         h = h + (torch.nn.functional.silu(b @ wg.T) * (b @ wu.T)) @ wd.T
     x = _rmsnorm(h, p[i], shape.rms_eps)
-    head = p[i + 1] if len(p) > i + 1 else p[0]
+    head = p[0] if shape.tied_embeddings else p[i + 1]
     lp = torch.log_softmax(x[:-1] @ head.T, dim=-1)
     picked = lp[torch.arange(T - 1), tok[1:]]
     return torch.cat([torch.zeros(1, dtype=torch.float64), picked])

@@ -16,10 +16,12 @@ SMALL_UNTIED = W.ModelShape(n_layers=1, d_model=32, n_q_heads=2, n_kv_heads=1, h
                             rms_eps=1e-5, rope_theta=1e6, tied_embeddings=False, dtype="f32", max_seq=64)
 
 
-def make_case(shape, seed, S=4, T=12, masked=7, std=0.3):
+def make_case(shape, seed, S=4, T=12, masked=7, std=0.3, biases=False):
     """Weights large enough for the logits to differ visibly between tokens, gains off 1, a batch with
     advantages of both signs and old log-probs off the new ones by up to +-0.4 (both clip bounds are hit)."""
     w = W.perturb_norm_gains(W.make_weights(shape, seed, std=std), seed)
+    if biases:
+        w = W.add_qkv_bias(w, shape, seed, std=0.3)
     rng = np.random.default_rng([seed, 1])
     tokens = rng.integers(0, shape.vocab - 3, size=(S, T)).astype(np.int32)   # the last 3 ids never occur
     mask = np.zeros((S, T), dtype=np.uint8)
@@ -49,9 +51,9 @@ def numpy_loss(shape, params, tokens, mask, logp_old, adv):
     return O.clipped_surrogate_loss(numpy_logprobs(shape, params, tokens, mask), logp_old, mask, adv)[0]
 
 
-@pytest.mark.parametrize("shape", [SMALL, SMALL_UNTIED])
-def test_forward_and_loss_equal_numpy_oracle(shape):
-    params, tokens, mask, logp_old, adv = make_case(shape, 11)
+@pytest.mark.parametrize("shape,biases", [(SMALL, False), (SMALL_UNTIED, False), (SMALL, True), (SMALL_UNTIED, True)])
+def test_forward_and_loss_equal_numpy_oracle(shape, biases):
+    params, tokens, mask, logp_old, adv = make_case(shape, 11, biases=biases)
     loss, lp, _ = U.loss_and_gradients(shape, params, tokens, mask, logp_old, adv)
     ref = numpy_logprobs(shape, params, tokens, mask)
     assert np.max(np.abs(lp - ref)) < 1e-11
@@ -64,11 +66,12 @@ def test_forward_and_loss_equal_numpy_oracle(shape):
     assert (rho > 1.28).any() and (rho < 0.8).any() and ((rho > 0.8) & (rho < 1.28)).any()
 
 
-@pytest.mark.parametrize("shape", [SMALL, SMALL_UNTIED])
-def test_gradient_equals_finite_differences_of_numpy_loss(shape):
-    params, tokens, mask, logp_old, adv = make_case(shape, 23)
+@pytest.mark.parametrize("shape,biases", [(SMALL, False), (SMALL_UNTIED, False), (SMALL, True), (SMALL_UNTIED, True)])
+def test_gradient_equals_finite_differences_of_numpy_loss(shape, biases):
+    params, tokens, mask, logp_old, adv = make_case(shape, 23, biases=biases)
     _, _, grads = U.loss_and_gradients(shape, params, tokens, mask, logp_old, adv)
-    assert len(grads) == len(params) == 1 + 9 * shape.n_layers + 1 + (0 if shape.tied_embeddings else 1)
+    assert len(grads) == len(params) == (1 + 9 * shape.n_layers + 1 + (0 if shape.tied_embeddings else 1)
+                                         + (shape.n_layers if biases else 0))
     rng = np.random.default_rng(5)
     h = 1e-6
     gmax = max(float(np.max(np.abs(g))) for g in grads)
