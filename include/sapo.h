@@ -253,8 +253,7 @@ int sapo_clipped_surrogate(const float* logp_new, const float* logp_old, const u
  * times the model in fp32, allocated by sapo_trainer_create and released by sapo_trainer_destroy.
  *   cfg, tensors, n_tensors   as for sapo_weights_create (device pointers, element type per
  *                             cfg->dtype, gains fp32); bf16 values become the fp32 masters unchanged.
- *                             head_dim at most 128.  The trainer's model has no projection biases
- *                             (sapo_weights_set_qkv_bias has no counterpart here).
+ *                             head_dim at most 128.  Projection biases: sapo_trainer_set_qkv_bias.
  *   opt                       Adam's constants, or NULL for the defaults named above
  * Complete once `stream` has been synchronised.
  */
@@ -306,6 +305,15 @@ int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const uint8_t* c
  */
 int sapo_trainer_export(const sapo_trainer* tr, void* const* tensors_out, int n_tensors, void* stream);
 /*
+ * Biases on the query / key / value projections of the trainer's model (the counterpart of
+ * sapo_weights_set_qkv_bias): set copies bq dev fp32 [Hq*hd], bk, bv dev fp32 [Hkv*hd] into the masters
+ * of `layer`; once any layer has been set, every layer's biases (zero where not set) are trained with
+ * the rest.  get copies the masters out (dev fp32, same sizes) for the next sapo_weights_set_qkv_bias.
+ */
+int sapo_trainer_set_qkv_bias(sapo_trainer* tr, int layer, const float* bq, const float* bk, const float* bv,
+                              void* stream);
+int sapo_trainer_get_qkv_bias(const sapo_trainer* tr, int layer, float* bq, float* bk, float* bv, void* stream);
+/*
  * Arithmetic of the update's large matrix products (projections and LM head; forward and backward).
  *   pieces = 3 (default): every fp32 operand is the exact sum of three bf16 values and a product is the
  *                sum of the six largest of the nine partial products: the accuracy of an fp32 product.
@@ -319,7 +327,8 @@ int sapo_trainer_set_matmul_pieces(sapo_trainer* tr, int pieces);
 int sapo_trainer_steps(const sapo_trainer* tr);
 /*
  * Test hook: copies one tensor of the trainer's state to out (dev fp32 [n], n = the tensor's element
- * count).  what: 0 masters, 1 the last update's gradient, 2 / 3 Adam's first / second moment.
+ * count).  what: 0 masters, 1 the last update's gradient, 2 / 3 Adam's first / second moment.  Tensor
+ * n_tensors + l is layer l's bias vector [bq | bk | bv].
  */
 int sapo_trainer_read(const sapo_trainer* tr, int what, int tensor, float* out, size_t n, void* stream);
 

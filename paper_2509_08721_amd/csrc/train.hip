@@ -670,6 +670,15 @@ __global__ void __launch_bounds__(256) k_gain_grad_partial(const float* __restri
   for (int m = m0; m < m1; ++m) s = fmaf(dxn[(size_t)m * d + i] * h[(size_t)m * d + i], rstd[m], s);
   part[(size_t)blockIdx.y * d + i] = s;
 }
+// column sums of x[M, N] over blocks of 256 rows (bias gradients); k_gain_grad_finish adds the blocks up in order
+__global__ void __launch_bounds__(256) k_colsum_partial(const float* __restrict__ x, int M, int N, float* __restrict__ part) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= N) return;
+  const int m0 = blockIdx.y * 256, m1 = min(M, m0 + 256);
+  float s = 0.f;
+  for (int m = m0; m < m1; ++m) s += x[(size_t)m * N + i];
+  part[(size_t)blockIdx.y * N + i] = s;
+}
 __global__ void __launch_bounds__(256) k_gain_grad_finish(const float* __restrict__ part, int n_part, int d,
                                                           float* __restrict__ dgain) {
   const int i = blockIdx.x * 256 + threadIdx.x;
@@ -765,6 +774,8 @@ struct sapo_trainer {
   sapo_adam_config opt;
   int t = 0;                      // Adam steps taken
   int pieces = 3;                 // bf16 pieces per value in the large GEMMs: 3 (fp32 accuracy) or 1 (bf16 operands)
+  bool use_bias = false;          // the model has biases on its query / key / value projections (set_qkv_bias)
+  int n_in = 0;                   // tensors of the input list; tensor n_in + l is layer l's bias vector
   int device = 0;
   size_t n_params = 0;
   float* theta = nullptr;         // [n_params] masters, tensors back to back in tensor-list order
@@ -797,6 +808,7 @@ void tensor_sizes(const sapo_model_config& c, std::vector<size_t>& len) {
   }
   len.push_back(D.d);
   if (!c.tied_embeddings) len.push_back(D.V * D.d);
+  for (int l = 0; l < D.L; ++l) len.push_back(D.nqkv);   // optional projection biases [bq | bk | bv] (zero and idle unless set)
 }
 
 // rows of logits held at once: about 2.5 GB (enough rows for the d-input GEMM of the head, whose output is only
@@ -871,7 +883,7 @@ void make_plan(const sapo_model_config& c, size_t S, size_t T, size_t S_total, c
   p.delta = A.take<float>(S * c.n_q_heads * T);
   p.prob = A.take<float>(S * c.n_q_heads * T * T);
   p.dsc = A.take<float>(S * c.n_q_heads * T * T);
-  p.gpart = A.take<float>(((M + 255) / 256) * D.d);
+  p.gpart = A.take<float>(((M + 255) / 256) * std::max(D.d, D.nqkv));
   p.chunk = lm_chunk_rows(D, M);
   p.logits = A.take<float>(p.chunk * D.V);
   p.logp_all = A.take<float>(S_total * T);   // log-probs of the whole training set (micro-batches fill their rows)
@@ -953,6 +965,7 @@ extern "C" int sapo_trainer_create(const sapo_model_config* cfg, const void* con
   size_t n = 0;
   for (size_t i = 0; i < tr->len.size(); ++i) { tr->off[i] = n; n += tr->len[i]; }
   tr->n_params = n;
+  tr->n_in = n_tensors;
   auto bail = [&](int code) { sapo_trainer_destroy(tr); return code; };
   for (float** p : {&tr->theta, &tr->grad, &tr->m, &tr->v}) {
     hipError_t e = hipMalloc((void**)p, n * sizeof(float));
@@ -969,6 +982,11 @@ extern "C" int sapo_trainer_create(const sapo_model_config* cfg, const void* con
   }
   for (float* p : {tr->grad, tr->m, tr->v}) {
     hipError_t e = g_fill_f32(p, 0.f, n, st);
+    if (e != hipSuccess) return bail(set_error(SAPO_EHIP, "fill failed: %s", hipGetErrorString(e)));
+  }
+  {
+    const size_t b0 = tr->off[n_tensors];   // the bias vectors start at zero
+    hipError_t e = g_fill_f32(tr->theta + b0, 0.f, n - b0, st);
     if (e != hipSuccess) return bail(set_error(SAPO_EHIP, "fill failed: %s", hipGetErrorString(e)));
   }
   const int half = cfg->head_dim / 2;
@@ -999,6 +1017,32 @@ extern "C" size_t sapo_trainer_workspace_bytes_for(const sapo_trainer* tr, int S
   return p.bytes;
 }
 
+extern "C" int sapo_trainer_set_qkv_bias(sapo_trainer* tr, int layer, const float* bq, const float* bk, const float* bv,
+                                         void* stream) {
+  if (!tr || !bq || !bk || !bv) return set_error(SAPO_EINVAL, "NULL argument");
+  if (layer < 0 || layer >= tr->cfg.n_layers) return set_error(SAPO_EINVAL, "layer %d out of range", layer);
+  const Dims D(tr->cfg);
+  float* dst = tr->theta + tr->off[tr->n_in + layer];
+  hipStream_t st = (hipStream_t)stream;
+  T_CK(hipMemcpyAsync(dst, bq, D.q * sizeof(float), hipMemcpyDeviceToDevice, st));
+  T_CK(hipMemcpyAsync(dst + D.q, bk, D.kv * sizeof(float), hipMemcpyDeviceToDevice, st));
+  T_CK(hipMemcpyAsync(dst + D.q + D.kv, bv, D.kv * sizeof(float), hipMemcpyDeviceToDevice, st));
+  tr->use_bias = true;
+  return SAPO_OK;
+}
+
+extern "C" int sapo_trainer_get_qkv_bias(const sapo_trainer* tr, int layer, float* bq, float* bk, float* bv, void* stream) {
+  if (!tr || !bq || !bk || !bv) return set_error(SAPO_EINVAL, "NULL argument");
+  if (layer < 0 || layer >= tr->cfg.n_layers) return set_error(SAPO_EINVAL, "layer %d out of range", layer);
+  const Dims D(tr->cfg);
+  const float* src = tr->theta + tr->off[tr->n_in + layer];
+  hipStream_t st = (hipStream_t)stream;
+  T_CK(hipMemcpyAsync(bq, src, D.q * sizeof(float), hipMemcpyDeviceToDevice, st));
+  T_CK(hipMemcpyAsync(bk, src + D.q, D.kv * sizeof(float), hipMemcpyDeviceToDevice, st));
+  T_CK(hipMemcpyAsync(bv, src + D.q + D.kv, D.kv * sizeof(float), hipMemcpyDeviceToDevice, st));
+  return SAPO_OK;
+}
+
 extern "C" int sapo_trainer_steps(const sapo_trainer* tr) { return tr ? tr->t : -1; }
 
 extern "C" int sapo_trainer_set_matmul_pieces(sapo_trainer* tr, int pieces) {
@@ -1020,7 +1064,7 @@ extern "C" int sapo_trainer_read(const sapo_trainer* tr, int what, int tensor, f
 
 extern "C" int sapo_trainer_export(const sapo_trainer* tr, void* const* tensors_out, int n_tensors, void* stream) {
   if (!tr || !tensors_out) return set_error(SAPO_EINVAL, "NULL argument");
-  if (n_tensors != (int)tr->len.size()) return set_error(SAPO_EINVAL, "n_tensors is %d, expected %zu", n_tensors, tr->len.size());
+  if (n_tensors != tr->n_in) return set_error(SAPO_EINVAL, "n_tensors is %d, expected %d", n_tensors, tr->n_in);
   hipStream_t st = (hipStream_t)stream;
   for (int i = 0; i < n_tensors; ++i) {
     if (!tensors_out[i]) return set_error(SAPO_EINVAL, "tensor %d is NULL", i);
@@ -1092,6 +1136,7 @@ static int update_rows(sapo_trainer* tr, const TrainPlan& p, const int32_t* toke
     T_CK(launch(KID_RMSNORM, k_rmsnorm_fwd, dim3(Mi), dim3(256), 0, st, (const float*)a.h, (const float*)TH(t0), c.rms_eps, d,
                 a.xn, a.r1));
     T_CK(mm_nt(a.xn, d, TH(t0 + 1), d, a.qkv, nqkv, Mi, nqkv, d, 0.f));   // wq, wk, wv are adjacent
+    if (tr->use_bias) T_CK(g_add_row_bias(a.qkv, TH(tr->n_in + l), Mi, nqkv, st));
     {
       const size_t total = M * (size_t)(hq + hkv) * (hd / 2);
       T_CK(launch(KID_ROPE_APPEND, k_rope, dim3(blocks256(total)), dim3(256), 0, st, a.qkv, (const float2*)tr->rope, (int)T,
@@ -1173,6 +1218,12 @@ static int update_rows(sapo_trainer* tr, const TrainPlan& p, const int32_t* toke
       const size_t total = M * (size_t)(hq + hkv) * (hd / 2);
       T_CK(launch(KID_ROPE_APPEND, k_rope, dim3(blocks256(total)), dim3(256), 0, st, p.dqkv, (const float2*)tr->rope, (int)T,
                   hq + hkv, hd, nqkv, -1.0f, total));
+    }
+    if (tr->use_bias) {   // the biases enter before the rotary embedding: their gradient is the column sum of dqkv here
+      T_CK(launch(KID_MISC, k_colsum_partial, dim3((nqkv + 255) / 256, n_gpart), dim3(256), 0, st, (const float*)p.dqkv, Mi, nqkv,
+                  p.gpart));
+      T_CK(launch(KID_MISC, k_gain_grad_finish, dim3((nqkv + 255) / 256), dim3(256), 0, st, (const float*)p.gpart, n_gpart, nqkv,
+                  GR(tr->n_in + l)));
     }
     // query / key / value projections
     T_CK(mm_nn(p.dqkv, nqkv, TH(t0 + 1), d, p.dx, d, Mi, d, nqkv, 0.f));

@@ -98,6 +98,10 @@ def load_library() -> C.CDLL:
     lib.sapo_trainer_export.restype = i32
     lib.sapo_trainer_set_matmul_pieces.argtypes = [vp, i32]
     lib.sapo_trainer_set_matmul_pieces.restype = i32
+    lib.sapo_trainer_set_qkv_bias.argtypes = [vp, i32, vp, vp, vp, vp]
+    lib.sapo_trainer_set_qkv_bias.restype = i32
+    lib.sapo_trainer_get_qkv_bias.argtypes = [vp, i32, vp, vp, vp, vp]
+    lib.sapo_trainer_get_qkv_bias.restype = i32
     lib.sapo_trainer_steps.argtypes = [vp]
     lib.sapo_trainer_steps.restype = i32
     lib.sapo_trainer_read.argtypes = [vp, i32, i32, vp, sz, vp]
@@ -129,6 +133,7 @@ EXPORTED = ["sapo_weights_create", "sapo_weights_destroy", "sapo_weights_uses_mf
             "sapo_trainer_create", "sapo_trainer_destroy", "sapo_trainer_workspace_bytes", "sapo_trainer_workspace_bytes_for",
             "sapo_policy_update",
             "sapo_trainer_export", "sapo_trainer_steps", "sapo_trainer_read", "sapo_trainer_set_matmul_pieces",
+            "sapo_trainer_set_qkv_bias", "sapo_trainer_get_qkv_bias",
             "sapo_debug_logits", "sapo_debug_gumbel", "sapo_last_error", "sapo_profile_kernel_count",
             "sapo_profile_kernel_name", "sapo_profile_start", "sapo_profile_stop"]
 
@@ -440,7 +445,9 @@ class Trainer:
         self.handle = handle
         self.cfg = cfg
         self.shape = shape
-        self.tensor_shapes = tensor_shapes     # per tensor of the list: (shape tuple, is fp32 gain)
+        self.tensor_shapes = tensor_shapes     # per tensor of the list: (shape tuple, is fp32 gain), then the bias vectors
+        self.n_in = len(tensor_shapes)
+        self.has_bias = False
 
     @property
     def steps(self) -> int:
@@ -464,16 +471,45 @@ def sapo_trainer_create(shape, weights: dict, lr: float = 1e-3, beta1: float = 0
     torch = _torch()
     lib = load_library()
     cfg = make_config(shape)
-    if any("bq" in lw for lw in weights["layers"]):
-        raise ValueError("the trainer's model has no projection biases: these weights carry them")
     order = _tensor_order(weights)
     dev = [_to_device(a) for a in order]
     ptrs = (C.c_void_p * len(dev))(*[t.data_ptr() for t in dev])
     opt = sapo_adam_config(lr, beta1, beta2, eps)
     out = C.c_void_p()
     _check(lib.sapo_trainer_create(C.byref(cfg), ptrs, len(dev), C.byref(opt), _stream_ptr(stream), C.byref(out)))
+    shapes = [(tuple(a.shape), a.ndim == 1) for a in order]
+    nqkv = shape.q_dim + 2 * shape.kv_dim
+    shapes += [((nqkv,), True)] * shape.n_layers        # the bias vectors [bq | bk | bv] (sapo_trainer_read)
+    tr = Trainer(out.value, cfg, shape, shapes)
+    tr.n_in = len(order)
+    for l, lw in enumerate(weights["layers"]):
+        if "bq" in lw:
+            sapo_trainer_set_qkv_bias(tr, l, _to_device(lw["bq"]), _to_device(lw["bk"]), _to_device(lw["bv"]), stream)
     torch.cuda.synchronize()          # the originals in `dev` may be freed after this
-    return Trainer(out.value, cfg, shape, [(tuple(a.shape), a.ndim == 1) for a in order])
+    return tr
+
+
+def sapo_trainer_set_qkv_bias(tr: Trainer, layer: int, bq, bk, bv, stream=None):
+    """bq float32 [Hq*hd], bk / bv float32 [Hkv*hd] device tensors."""
+    torch = _torch()
+    for t in (bq, bk, bv):
+        assert t.dtype == torch.float32 and t.is_cuda and t.is_contiguous()
+    _check(load_library().sapo_trainer_set_qkv_bias(tr.handle, layer, bq.data_ptr(), bk.data_ptr(), bv.data_ptr(),
+                                                    _stream_ptr(stream)))
+    tr.has_bias = True
+    torch.cuda.synchronize()
+
+
+def sapo_trainer_get_qkv_bias(tr: Trainer, layer: int, stream=None):
+    """(bq, bk, bv) float32 device tensors: the masters of one layer's projection biases."""
+    torch = _torch()
+    q, kv = tr.shape.q_dim, tr.shape.kv_dim
+    bq = torch.empty((q,), dtype=torch.float32, device="cuda")
+    bk = torch.empty((kv,), dtype=torch.float32, device="cuda")
+    bv = torch.empty((kv,), dtype=torch.float32, device="cuda")
+    _check(load_library().sapo_trainer_get_qkv_bias(tr.handle, layer, bq.data_ptr(), bk.data_ptr(), bv.data_ptr(),
+                                                    _stream_ptr(stream)))
+    return bq, bk, bv
 
 
 def sapo_trainer_destroy(tr: Trainer):
@@ -536,7 +572,7 @@ def sapo_trainer_export(tr: Trainer, stream=None) -> dict:
     torch = _torch()
     bf16 = tr.cfg.dtype == SAPO_DTYPE_BF16
     dev = [torch.empty(shp, dtype=torch.float32 if (gain or not bf16) else torch.bfloat16, device="cuda")
-           for shp, gain in tr.tensor_shapes]
+           for shp, gain in tr.tensor_shapes[:tr.n_in]]
     ptrs = (C.c_void_p * len(dev))(*[t.data_ptr() for t in dev])
     _check(load_library().sapo_trainer_export(tr.handle, ptrs, len(dev), _stream_ptr(stream)))
     torch.cuda.synchronize()
@@ -547,6 +583,9 @@ def sapo_trainer_export(tr: Trainer, stream=None) -> dict:
         w["layers"].append({k: next(it) for k in LAYER_TENSORS})
     w["final_norm"] = next(it)
     w["lm_head"] = None if tr.cfg.tied_embeddings else next(it)
+    if tr.has_bias:
+        for l, lw in enumerate(w["layers"]):
+            lw["bq"], lw["bk"], lw["bv"] = (t.cpu().numpy() for t in sapo_trainer_get_qkv_bias(tr, l, stream))
     return w
 
 

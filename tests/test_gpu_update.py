@@ -67,7 +67,9 @@ ADAM = dict(lr=float(np.float32(1e-3)), beta1=float(np.float32(0.9)), beta2=floa
 
 
 def read_all(sapo, tr, what):
-    return [sapo.sapo_trainer_read(tr, what, i).cpu().numpy().astype(np.float64) for i in range(len(tr.tensor_shapes))]
+    """The tensors of the input list, then (for a model with projection biases) the per-layer bias vectors."""
+    n = tr.n_in + (tr.shape.n_layers if tr.has_bias else 0)
+    return [sapo.sapo_trainer_read(tr, what, i).cpu().numpy().astype(np.float64) for i in range(n)]
 
 
 @pytest.mark.parametrize("name,S,T,masked", [("tiny", 8, 32, 16), ("ragged_untied", 3, 13, 9), ("hd128", 4, 70, 33),
@@ -137,7 +139,7 @@ def test_update_is_reproducible_and_lowers_the_loss(sapo):
             loss, _ = sapo.sapo_policy_update(tr, dev(tokens), dev(mask), dev(logp_old), dev(adv), want_logp=False)
             losses.append(float(loss.cpu()[0]))
         torch.cuda.synchronize()
-        outs.append((losses, [sapo.sapo_trainer_read(tr, 0, i).cpu().numpy() for i in range(len(tr.tensor_shapes))]))
+        outs.append((losses, [sapo.sapo_trainer_read(tr, 0, i).cpu().numpy() for i in range(tr.n_in)]))
         tr.close()
     assert outs[0][0] == outs[1][0]
     for a, b in zip(outs[0][1], outs[1][1]):
@@ -376,3 +378,48 @@ def test_update_in_micro_batches(sapo):
         sapo.sapo_policy_update(tr, dev(tokens), dev(mask), dev(logp_old), dev(adv), workspace=small)
     assert e.value.code == sapo.SAPO_EWORKSPACE and tr.steps == 0
     tr.close()
+
+
+def test_update_with_projection_biases(sapo):
+    """A model with biases on its query / key / value projections: they are trained with everything else; their
+    gradient is checked like every tensor's, and the exported policy (biases included) scores as the oracle does."""
+    import torch
+    from oracle import sapo_update_oracle as U
+    from oracle import sapo_oracle as O
+    shape = SHAPES["tiny"]
+    S, T = 6, 24
+    w, _, tokens, mask, _, adv = make_case(shape, 321, S, T, 12)
+    w = W.add_qkv_bias(w, shape, 321, std=0.3)
+    params = U.parameter_list(shape, w)
+    assert len(params) == 1 + 9 * shape.n_layers + 1 + shape.n_layers
+    _, lp0, _ = U.loss_and_gradients(shape, params, tokens, mask, np.zeros((S, T), np.float32), adv)
+    rng = np.random.default_rng(5)
+    u = rng.uniform(-0.4, 0.4, size=lp0.shape)
+    u[(np.abs(np.exp(-u) - 1.28) < 0.02) | (np.abs(np.exp(-u) - 0.8) < 0.02)] = 0.0
+    logp_old = (lp0 + u * (mask != 0)).astype(np.float32)
+    ref_loss, ref_lp, ref_g = U.loss_and_gradients(shape, params, tokens, mask, logp_old, adv)
+    tr = sapo.sapo_trainer_create(shape, w)
+    assert tr.has_bias
+    loss, lp = sapo.sapo_policy_update(tr, dev(tokens), dev(mask), dev(logp_old), dev(adv))
+    torch.cuda.synchronize()
+    assert np.max(np.abs(lp.cpu().numpy() - ref_lp)) < 2e-4 and abs(float(loss.cpu()[0]) - ref_loss) < 1e-4 * max(1.0, abs(ref_loss))
+    g = read_all(sapo, tr, 1)
+    assert len(g) == len(ref_g)
+    gmax = max(float(np.max(np.abs(x))) for x in ref_g)
+    for i, (a, b) in enumerate(zip(g, ref_g)):
+        assert float(np.max(np.abs(a - b))) <= 2e-4 * max(float(np.max(np.abs(b))), 1e-3 * gmax) + 1e-7, i
+    assert all(np.max(np.abs(b)) > 0 for b in ref_g[-shape.n_layers:])        # the bias gradients are not trivially zero
+    # Adam moved the biases; the exported policy carries them
+    new = sapo.sapo_trainer_export(tr)
+    for l, lw in enumerate(new["layers"]):
+        old_b = np.concatenate([w["layers"][l]["bq"], w["layers"][l]["bk"], w["layers"][l]["bv"]])
+        new_b = np.concatenate([lw["bq"], lw["bk"], lw["bv"]])
+        step = np.abs(new_b - old_b)
+        assert step.max() <= 1.001e-3 and step.max() > 0.9e-3               # first Adam step: lr * g / (|g| + eps)
+    gw = sapo.sapo_weights_create(shape, new)
+    rew = np.zeros(S, dtype=np.float32)
+    lp_gpu, _ = sapo.sapo_score_logprobs(gw, dev(tokens), dev(mask), dev(rew), 2)
+    torch.cuda.synchronize()
+    ref = O.score_logprobs(O.Model(shape, new), tokens, mask)
+    assert np.max(np.abs(lp_gpu.cpu().numpy() - ref)) < 1e-4
+    gw.close(); tr.close()
