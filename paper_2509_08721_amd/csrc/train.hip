@@ -328,22 +328,30 @@ __global__ void __launch_bounds__(256) k_pack_x3_t(const float* __restrict__ src
   }
 }
 
-template <int NP>
-__global__ void __launch_bounds__(256) k_gemm_x3(const u32x4_t* __restrict__ Ap, const u32x4_t* __restrict__ Bp, float* __restrict__ C,
-                                                 int ldc, int M, int N, int KB, float beta, int kb_split, size_t c_split) {
-  constexpr int E = NP * 256;                 // 16-byte entries per operand and k step
-  __shared__ u32x4_t As[2][E];
+// RB = row blocks of 128 per tile: 1 (128 x 128, three workgroups per CU) or 2 (256 x 128 for outputs with many
+// tiles: each wave 128 x 64, two workgroups per CU, a quarter less traffic per flop on both the L2 and the LDS side)
+template <int NP, int RB>
+__global__ void __launch_bounds__(256, RB == 2 ? 2 : 3) k_gemm_x3(const u32x4_t* __restrict__ Ap, const u32x4_t* __restrict__ Bp,
+                                                                  float* __restrict__ C, int ldc, int M, int N, int KB, float beta,
+                                                                  int kb_split, size_t c_split) {
+  constexpr int E = NP * 256;                 // 16-byte entries per row block, operand and k step
+  constexpr int MI = 2 * RB;                  // 32-row MFMA tiles per wave
+  __shared__ u32x4_t As[2][RB * E];
   __shared__ u32x4_t Bs[2][E];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   int tx, ty;
-  if (!raster_tile((N + kGM - 1) / kGM, (M + kGM - 1) / kGM, tx, ty)) return;
-  const int m0 = ty * kGM, n0 = tx * kGM;
-  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
-  const u32x4_t* ap = Ap + (size_t)ty * KB * E + threadIdx.x;
-  const u32x4_t* bp = Bp + (size_t)tx * KB * E + threadIdx.x;
-  f32x16_t acc[2][2];
+  const int n_rb = (M + kGM - 1) / kGM;       // row blocks of the packed operand
+  if (!raster_tile((N + kGM - 1) / kGM, (n_rb + RB - 1) / RB, tx, ty)) return;
+  const int m0 = ty * kGM * RB, n0 = tx * kGM;
+  const int wm = (wave >> 1) * 64 * RB, wn = (wave & 1) * 64;
+  const u32x4_t* ap[RB];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int r = 0; r < RB; ++r)   // a tile's last row block may not exist: it repeats the previous one and is not stored
+    ap[r] = Ap + (size_t)min(ty * RB + r, n_rb - 1) * KB * E + threadIdx.x;
+  const u32x4_t* bp = Bp + (size_t)tx * KB * E + threadIdx.x;
+  f32x16_t acc[MI][2];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -351,45 +359,63 @@ __global__ void __launch_bounds__(256) k_gemm_x3(const u32x4_t* __restrict__ Ap,
   // blockIdx.z takes the k steps [z kb_split, (z + 1) kb_split) and writes its own copy of C (split weight gradients)
   const int t0 = blockIdx.z * kb_split, t1 = min(KB, t0 + kb_split);
   C += (size_t)blockIdx.z * c_split;
-  u32x4_t ra[NP], rb[NP];
+  u32x4_t ra[RB][NP], rb[NP];
 #pragma unroll
-  for (int pc = 0; pc < NP; ++pc) { ra[pc] = ap[(size_t)t0 * E + pc * 256]; rb[pc] = bp[(size_t)t0 * E + pc * 256]; }
+  for (int pc = 0; pc < NP; ++pc) {
 #pragma unroll
-  for (int pc = 0; pc < NP; ++pc) { As[0][pc * 256 + threadIdx.x] = ra[pc]; Bs[0][pc * 256 + threadIdx.x] = rb[pc]; }
+    for (int r = 0; r < RB; ++r) ra[r][pc] = ap[r][(size_t)t0 * E + pc * 256];
+    rb[pc] = bp[(size_t)t0 * E + pc * 256];
+  }
+#pragma unroll
+  for (int pc = 0; pc < NP; ++pc) {
+#pragma unroll
+    for (int r = 0; r < RB; ++r) As[0][r * E + pc * 256 + threadIdx.x] = ra[r][pc];
+    Bs[0][pc * 256 + threadIdx.x] = rb[pc];
+  }
   __syncthreads();
   const int kh = lane >> 5, c = lane & 31;
   for (int t = t0; t < t1; ++t) {
     const int cur = (t - t0) & 1;
     if (t + 1 < t1) {
 #pragma unroll
-      for (int pc = 0; pc < NP; ++pc) { ra[pc] = ap[(size_t)(t + 1) * E + pc * 256]; rb[pc] = bp[(size_t)(t + 1) * E + pc * 256]; }
-    }
-    Frag8 a[2][NP], b[2][NP];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
       for (int pc = 0; pc < NP; ++pc) {
-        a[i][pc].u = As[cur][(pc * 2 + kh) * 128 + wm + i * 32 + c];
-        b[i][pc].u = Bs[cur][(pc * 2 + kh) * 128 + wn + i * 32 + c];
+#pragma unroll
+        for (int r = 0; r < RB; ++r) ra[r][pc] = ap[r][(size_t)(t + 1) * E + pc * 256];
+        rb[pc] = bp[(size_t)(t + 1) * E + pc * 256];
       }
+    }
+    Frag8 b[2][NP];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int pc = 0; pc < NP; ++pc) b[j][pc].u = Bs[cur][(pc * 2 + kh) * 128 + wn + j * 32 + c];
     // smallest partial products first: (hi lo), (lo hi), (mid mid), (hi mid), (mid hi), (hi hi)
     constexpr int n_terms = NP == 3 ? 6 : 1;
     constexpr int pa[6] = {0, 2, 1, 0, 1, 0}, pb[6] = {2, 0, 1, 1, 0, 0};
 #pragma unroll
-    for (int term = 6 - n_terms; term < 6; ++term)
+    for (int i = 0; i < MI; ++i) {
+      Frag8 a[NP];
+      const int row = wm + i * 32 + c;        // within the tile: row block row >> 7
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int pc = 0; pc < NP; ++pc) a[pc].u = As[cur][(row >> 7) * E + (pc * 2 + kh) * 128 + (row & 127)];
+#pragma unroll
+      for (int term = 6 - n_terms; term < 6; ++term)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][pa[term]].v, b[j][pb[term]].v, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[pa[term]].v, b[j][pb[term]].v, acc[i][j], 0, 0, 0);
+    }
     if (t + 1 < t1) {
 #pragma unroll
-      for (int pc = 0; pc < NP; ++pc) { As[cur ^ 1][pc * 256 + threadIdx.x] = ra[pc]; Bs[cur ^ 1][pc * 256 + threadIdx.x] = rb[pc]; }
+      for (int pc = 0; pc < NP; ++pc) {
+#pragma unroll
+        for (int r = 0; r < RB; ++r) As[cur ^ 1][r * E + pc * 256 + threadIdx.x] = ra[r][pc];
+        Bs[cur ^ 1][pc * 256 + threadIdx.x] = rb[pc];
+      }
     }
     __syncthreads();
   }
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int n = n0 + wn + j * 32 + (lane & 31);
@@ -433,13 +459,16 @@ hipError_t gemm_x3(const X3Op& A, const X3Op& B, float* C, int ldc, float beta, 
   const u32x4_t* pb_ = (const u32x4_t*)(b_packed ? b_packed : bufs.b);
   const int KB = (A.K + 15) / 16;
   const int gnx = (B.rows + kGM - 1) / kGM, gny = (A.rows + kGM - 1) / kGM;
-  dim3 grid(raster_grid(gnx, gny), 1);
+  // 256-row tiles when the output still has plenty of them
+  const int RB = (gnx >= 32 && (long)gnx * ((gny + 1) / 2) >= 512) ? 2 : 1;
+  const int gty = (gny + RB - 1) / RB;
+  dim3 grid(raster_grid(gnx, gty), 1);
   // an output with few tiles and a long contraction (weight gradients of the narrow projections): the k steps
   // are split into parts, each part writes its own product and k_sum_parts adds them in part order
-  const long tiles = (long)gnx * gny;
+  const long tiles = (long)gnx * gty;
   int splits = 1;
   if (split_ok && ldc == B.rows) {
-    while (splits < 8 && tiles * splits < 192 && KB / (splits * 2) >= 16) splits *= 2;
+    while (splits < 8 && tiles * splits * 2 <= 768 && KB / (splits * 2) >= 16) splits *= 2;   // 768 = workgroups in flight
     if ((size_t)splits * A.rows * B.rows > bufs.parts_cap) splits = 1;
   }
   const int kbs = (KB + splits - 1) / splits;
@@ -447,12 +476,12 @@ hipError_t gemm_x3(const X3Op& A, const X3Op& B, float* C, int ldc, float beta, 
   grid.z = splits;
   float* out = splits > 1 ? bufs.parts : C;
   const size_t c_split = splits > 1 ? (size_t)A.rows * B.rows : 0;
-  if (bufs.NP == 3)
-    e = launch(KID_GEMM_GENERIC, k_gemm_x3<3>, grid, dim3(256), 0, st, pa_, pb_, out, ldc, A.rows, B.rows, KB,
-               splits > 1 ? 0.f : beta, kbs, c_split);
-  else
-    e = launch(KID_GEMM_GENERIC, k_gemm_x3<1>, grid, dim3(256), 0, st, pa_, pb_, out, ldc, A.rows, B.rows, KB,
-               splits > 1 ? 0.f : beta, kbs, c_split);
+  const float b_ = splits > 1 ? 0.f : beta;
+  auto go = [&](auto kernel) {
+    return launch(KID_GEMM_GENERIC, kernel, grid, dim3(256), 0, st, pa_, pb_, out, ldc, A.rows, B.rows, KB, b_, kbs, c_split);
+  };
+  if (bufs.NP == 3) e = RB == 2 ? go(k_gemm_x3<3, 2>) : go(k_gemm_x3<3, 1>);
+  else e = RB == 2 ? go(k_gemm_x3<1, 2>) : go(k_gemm_x3<1, 1>);
   if (e != hipSuccess || splits == 1) return e;
   const size_t n = (size_t)A.rows * B.rows;
   return launch(KID_MISC, k_sum_parts, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const float*)bufs.parts, splits, n, beta,
@@ -830,8 +859,9 @@ struct Arena {
   }
 };
 
-// Weight-gradient GEMMs with few output tiles (dW of the attention projections: 49 - 63 tiles of 128 x 128 on 256
-// compute units) are split over the token dimension into up to 8 parts that are added in part order.
+// GEMMs with few output tiles and a long contraction (dW of the attention projections: 49 - 63 tiles of 128 x 128 on
+// 256 compute units; the head's d-input product: 238 tiles, contraction over the vocabulary) are split over the
+// contraction into up to 8 parts that are added in part order.
 constexpr size_t kSplitParts = (size_t)8 * 192 * 128 * 128;
 constexpr int kPieces = 3;   // most bf16 pieces per fp32 value in the packed GEMMs (3: fp32 accuracy; buffers are sized for it)
 
@@ -1121,7 +1151,7 @@ static int update_rows(sapo_trainer* tr, const TrainPlan& p, const int32_t* toke
   };
   auto mm_nn = [&](const float* A_, int lda, const float* B_, int ldb, float* C, int ldc, int M_, int N_, int K_, float beta,
                    const void* b_packed = nullptr) {   // C = beta C + A B
-    return gemm_x3(X3Op{A_, lda, M_, K_, false}, X3Op{B_, ldb, N_, K_, true}, C, ldc, beta, xb, st, false, nullptr, b_packed);
+    return gemm_x3(X3Op{A_, lda, M_, K_, false}, X3Op{B_, ldb, N_, K_, true}, C, ldc, beta, xb, st, true, nullptr, b_packed);
   };
   auto mm_tn = [&](const float* A_, int lda, const float* B_, int ldb, float* C, int Mg, int Ng, int Kg, float beta) {
     return gemm_x3(X3Op{A_, lda, Mg, Kg, true}, X3Op{B_, ldb, Ng, Kg, true}, C, Ng, beta, xb, st, true);   // C = beta C + A^T B
