@@ -1,0 +1,59 @@
+"""One SAPO node's round (Algorithm 1) as calls into libsapo: generate rollouts, assemble the training
+set from own and swarm rollouts, score it, update the policy, continue with the updated policy.
+
+Glue only: every step runs in the library's kernels; rewards come from the caller (the node's reward
+model, Sec. 3.1) and the exchange of rollouts with the swarm is the caller's business (Sec. 3.2)."""
+from __future__ import annotations
+
+from typing import Optional
+
+from . import sapo
+
+
+class Node:
+    """A node n of the swarm: its policy pi^n (a weights handle for generation and scoring) and the
+    trainer that improves it."""
+
+    def __init__(self, shape, weights: dict, group: int, lr: float = 1e-3, eps_low: float = 0.2, eps_high: float = 0.28,
+                 matmul_pieces: int = 3):
+        self.shape, self.group = shape, group
+        self.eps_low, self.eps_high = eps_low, eps_high
+        self.policy = sapo.sapo_weights_create(shape, weights)
+        self.trainer = sapo.sapo_trainer_create(shape, weights, lr=lr)
+        sapo.sapo_trainer_set_matmul_pieces(self.trainer, matmul_pieces)
+        self.rounds = 0
+
+    def rollouts(self, prompts, max_new: int, temperature: float, seed: int):
+        """prompts int32 [P, Lp] (device).  Returns (sequences int32 [P * G, Lp + max_new]: each prompt followed by
+        one of its G completions, log-probs of the completion tokens float32 [P * G, max_new])."""
+        torch = sapo._torch()
+        comp, lps = sapo.sapo_rollout_generate(self.policy, prompts, self.group, max_new, temperature, seed)
+        return torch.cat([prompts.repeat_interleave(self.group, dim=0), comp], dim=1).contiguous(), lps
+
+    def training_set(self, own_sequences, own_rewards, swarm_sequences, swarm_rewards, n_own: int, n_swarm: int, seed: int):
+        """I^n datapoints of the node's own and J^n sampled from the swarm's, those with zero advantage discarded
+        (a datapoint is a question's G sequences).  Returns (sequences, rewards) of the datapoints actually taken."""
+        tok, rew, _, cnt = sapo.sapo_assemble_training_set(own_sequences, own_rewards, swarm_sequences, swarm_rewards,
+                                                           self.group, n_own, n_swarm, seed)
+        n = int(cnt.sum().item()) * self.group
+        return tok[:n].contiguous(), rew[:n].contiguous()
+
+    def update(self, sequences, rewards, n_completion: int, workspace=None):
+        """One PolicyGradient step on the training set: score it under the current policy (old log-probs, group-relative
+        advantages), take the step, continue with the updated policy.  Returns the loss before the step (float32 [1])."""
+        torch = sapo._torch()
+        S, T = int(sequences.shape[0]), int(sequences.shape[1])
+        mask = torch.zeros((S, T), dtype=torch.uint8, device="cuda")
+        mask[:, T - n_completion:] = 1
+        logp_old, adv = sapo.sapo_score_logprobs(self.policy, sequences, mask, rewards, self.group)
+        loss, _ = sapo.sapo_policy_update(self.trainer, sequences, mask, logp_old, adv, self.eps_low, self.eps_high,
+                                          want_logp=False, workspace=workspace)
+        new_policy = sapo.sapo_trainer_export_weights(self.trainer)
+        self.policy.close()
+        self.policy = new_policy
+        self.rounds += 1
+        return loss
+
+    def close(self):
+        self.policy.close()
+        self.trainer.close()

@@ -589,6 +589,30 @@ def sapo_trainer_export(tr: Trainer, stream=None) -> dict:
     return w
 
 
+def sapo_trainer_export_weights(tr: Trainer, stream=None) -> Weights:
+    """The trainer's masters as a new policy handle (sapo_trainer_export into device buffers, then
+    sapo_weights_create and, for a model with projection biases, sapo_weights_set_qkv_bias), without a
+    trip through host memory."""
+    torch = _torch()
+    lib = load_library()
+    bf16 = tr.cfg.dtype == SAPO_DTYPE_BF16
+    dev = [torch.empty(shp, dtype=torch.float32 if (gain or not bf16) else torch.bfloat16, device="cuda")
+           for shp, gain in tr.tensor_shapes[:tr.n_in]]
+    ptrs = (C.c_void_p * len(dev))(*[t.data_ptr() for t in dev])
+    _check(lib.sapo_trainer_export(tr.handle, ptrs, len(dev), _stream_ptr(stream)))
+    full = list(dev) + ([None] if tr.cfg.tied_embeddings else [])     # sapo_weights_create's list has a head slot
+    wptrs = (C.c_void_p * len(full))(*[None if t is None else t.data_ptr() for t in full])
+    out = C.c_void_p()
+    _check(lib.sapo_weights_create(C.byref(tr.cfg), wptrs, len(full), _stream_ptr(stream), C.byref(out)))
+    w = Weights(out.value, tr.cfg)
+    if tr.has_bias:
+        for l in range(tr.cfg.n_layers):
+            bq, bk, bv = sapo_trainer_get_qkv_bias(tr, l, stream)
+            sapo_weights_set_qkv_bias(w, l, bq, bk, bv, stream)
+    torch.cuda.synchronize()          # `dev` may be freed after this
+    return w
+
+
 def sapo_debug_logits(w: Weights, tokens, positions: Sequence[Sequence[int]], stream=None):
     """Teacher-forced logits after consuming tokens[s, 0..t] for each (s, t) in positions.
     Returns float32 [n, vocab] device tensor."""

@@ -100,3 +100,35 @@ def test_one_round_of_algorithm_1(sapo):
     assert toks2.shape == (P * G, N) and np.all(np.isfinite(lps2.cpu().numpy()))
     assert tr.steps == 4
     gw.close(); gw2.close(); tr.close()
+
+
+def test_node_rounds(sapo):
+    """Two rounds through paper_2509_08721_amd.node.Node (the same calls, packaged): the policy handle is replaced by
+    the trainer's export each round, and what it scores is what the oracle scores for the exported masters."""
+    import torch
+    from oracle import sapo_oracle as O
+    from paper_2509_08721_amd.node import Node
+    shape = W.TINY
+    P, G, Lp, N = 4, 4, 8, 10
+    rng = np.random.default_rng(91)
+    prompts = dev(rng.integers(0, shape.vocab, size=(P, Lp)).astype(np.int32))
+    node = Node(shape, W.add_qkv_bias(W.make_weights(shape, 41, std=0.2), shape, 41, std=0.1), G)
+    other = Node(shape, W.make_weights(shape, 42, std=0.2), G)
+    losses = []
+    for rnd in range(2):
+        own, _ = node.rollouts(prompts, N, 1.0, 100 + rnd)
+        ext, _ = other.rollouts(prompts, N, 1.0, 200 + rnd)
+        own_r = dev(verifier(own[:, Lp:].cpu().numpy()))
+        ext_r = dev(verifier(ext[:, Lp:].cpu().numpy()))
+        seqs, rew = node.training_set(own, own_r, ext, ext_r, 2, 2, 7 + rnd)
+        assert seqs.shape[0] % G == 0 and seqs.shape[0] >= 2 * G and seqs.shape[1] == Lp + N
+        losses.append(float(node.update(seqs, rew, N).cpu()[0]))
+    torch.cuda.synchronize()
+    assert node.rounds == 2 and node.trainer.steps == 2 and all(np.isfinite(losses))
+    # the policy in use is the trainer's export (biases included)
+    exported = sapo.sapo_trainer_export(node.trainer)
+    mask = W.make_completion_mask(int(seqs.shape[0]), Lp + N, N)
+    lp, _ = sapo.sapo_score_logprobs(node.policy, seqs, dev(mask), rew, G)
+    ref = O.score_logprobs(O.Model(shape, exported), seqs.cpu().numpy(), mask)
+    assert np.max(np.abs(lp.cpu().numpy() - ref)) < 1e-4
+    node.close(); other.close()
