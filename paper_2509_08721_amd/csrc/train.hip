@@ -46,6 +46,11 @@ struct Batch {
   // column <= row are needed (scores, dP); 2 = op(A)[i][k] is zero for k > i, the k loop ends at the tile's last
   // row (P V, dS K); 3 = op(A)[j][k] is zero for k < j, the k loop starts at the tile's first row (dS^T Q, P^T dO)
   int causal = 0;
+  // Segmented contraction (MFMA kernel only): K consists of K / kseg segments of kseg (a multiple of 16); segment g
+  // reads op(A) from A + g sega and op(B) from B + g segb, indexed by k - g kseg.  With causal = 3 the skipped start
+  // applies to every segment.  Used to add the query heads of a group up inside one GEMM, in head order.
+  int kseg = 0;
+  long sega = 0, segb = 0;
 };
 // Tile of a 1-D launch of nx * ny workgroups.  Workgroup ids are dealt round-robin to the 8 XCDs (each with its
 // own L2), so XCD x = id % 8 takes the contiguous tile range [x per, (x + 1) per) and walks it in panels of 8
@@ -192,19 +197,34 @@ __global__ void __launch_bounds__(256) k_sgemm_mfma(const float* __restrict__ A,
   int t_begin = 0, nk = (K + kGK - 1) / kGK;
   if (bt.causal == 2) nk = min(nk, (m0 + kGM + kGK - 1) / kGK);
   if (bt.causal == 3) t_begin = min(m0 / kGK, nk - 1);
+  // segmented contraction: step u is step seg_skip + u % per of segment u / per
+  const int seg_steps = bt.kseg > 0 ? bt.kseg / kGK : 0;
+  const int seg_skip = (seg_steps && bt.causal == 3) ? min(m0 / kGK, seg_steps - 1) : 0;
+  const int per = seg_steps - seg_skip;
+  if (seg_steps) { t_begin = 0; nk = (K / bt.kseg) * per; }
   float4 ra[2], rb[2];
   // op(A) rows are m: A is "k contiguous" unless TA; op(B) rows are n: B is "k contiguous" when TB
-  gemm_fetch<TA>(A, lda, m0, M, t_begin * kGK, K, ra);
-  gemm_fetch<TB ? 0 : 1>(B, ldb, n0, N, t_begin * kGK, K, rb);
+  auto fetch = [&](int u) {
+    const float* Ag = A;
+    const float* Bg = B;
+    int k0 = u * kGK, Kb = K;
+    if (seg_steps) {
+      const int g = u / per;
+      k0 = (seg_skip + u - g * per) * kGK;
+      Ag += g * bt.sega;
+      Bg += g * bt.segb;
+      Kb = bt.kseg;
+    }
+    gemm_fetch<TA>(Ag, lda, m0, M, k0, Kb, ra);
+    gemm_fetch<TB ? 0 : 1>(Bg, ldb, n0, N, k0, Kb, rb);
+  };
+  fetch(t_begin);
   gemm_stage<TA>(As[t_begin & 1], ra);
   gemm_stage<TB ? 0 : 1>(Bs[t_begin & 1], rb);
   __syncthreads();
   for (int t = t_begin; t < nk; ++t) {
     const int cur = t & 1;
-    if (t + 1 < nk) {
-      gemm_fetch<TA>(A, lda, m0, M, (t + 1) * kGK, K, ra);
-      gemm_fetch<TB ? 0 : 1>(B, ldb, n0, N, (t + 1) * kGK, K, rb);
-    }
+    if (t + 1 < nk) fetch(t + 1);
 #pragma unroll
     for (int kk = 0; kk < kGK; kk += 2) {
       const int kr = kk + (lane >> 5), c = lane & 31;
@@ -492,7 +512,8 @@ template <int TA, int TB>
 hipError_t sgemm(const float* A, int lda, const float* B, int ldb, float* C, int ldc, int M, int N, int K, float beta,
                  hipStream_t st, const Batch& bt = Batch()) {
   if (M <= 0 || N <= 0 || K <= 0 || bt.count <= 0 || bt.count > 65535) return hipErrorInvalidValue;
-  const long strides = bt.a1 | bt.a2 | bt.b1 | bt.b2;
+  if (bt.kseg > 0 && (bt.kseg % kGK != 0 || K % bt.kseg != 0)) return hipErrorInvalidValue;
+  const long strides = bt.a1 | bt.a2 | bt.b1 | bt.b2 | bt.sega | bt.segb;
   const bool aligned = ((M | N | K | lda | ldb) & 3) == 0 && (strides & 3) == 0 && (((uintptr_t)A | (uintptr_t)B) & 15) == 0;
   if (aligned && (long)M * N * bt.count >= 128 * 128) {
     const dim3 grid(raster_grid((N + kGM - 1) / kGM, (M + kGM - 1) / kGM), 1, bt.count);
@@ -500,6 +521,7 @@ hipError_t sgemm(const float* A, int lda, const float* B, int ldb, float* C, int
       return launch(KID_GEMM_GENERIC, k_sgemm_mfma<TA, TB, 1>, grid, dim3(256), 0, st, A, lda, B, ldb, C, ldc, M, N, K, beta, bt);
     return launch(KID_GEMM_GENERIC, k_sgemm_mfma<TA, TB, 0>, grid, dim3(256), 0, st, A, lda, B, ldb, C, ldc, M, N, K, beta, bt);
   }
+  if (bt.kseg > 0) return hipErrorInvalidValue;   // the vector-ALU kernel has no segmented contraction
   return launch(KID_GEMM_GENERIC, k_sgemm<TA, TB>, dim3((N + kTN - 1) / kTN, (M + kTM - 1) / kTM, bt.count), dim3(256), 0, st, A,
                 lda, B, ldb, C, ldc, M, N, K, beta, bt);
 }
@@ -1237,7 +1259,16 @@ static int update_rows(sapo_trainer* tr, const TrainPlan& p, const int32_t* toke
     T_CK(launch(KID_ATTN_GENERIC, k_dscores, dim3(blocks256(n_sc)), dim3(256), 0, st, (const float*)p.prob, p.dsc,
                 (const float*)p.delta, (int)T, att_scale, n_sc));
     T_CK((sgemm<0, 0>(p.dsc, (int)T, a.qkv + q, nqkv, p.dqkv, nqkv, (int)T, hd, (int)T, 0.f, st, b_dq)));       // dQ = dS K
-    for (int hh = 0; hh < rep; ++hh) {   // the query heads of a group add up in a fixed order
+    const bool one_launch = T % 16 == 0 && hd % 4 == 0 && nqkv % 4 == 0 && q % 4 == 0 && (long)T * hd * S_ * hkv >= 128 * 128;
+    if (one_launch) {   // the query heads of a group are segments of one contraction (added in head order)
+      Batch kd = b_dk, vd = b_dv;
+      kd.kseg = vd.kseg = (int)T;
+      kd.sega = vd.sega = TT;
+      kd.segb = vd.segb = hd;
+      T_CK((sgemm<1, 0>(p.dsc, (int)T, a.qkv, nqkv, p.dqkv + q, nqkv, (int)T, hd, rep * (int)T, 0.f, st, kd)));        // dK = sum_h dS_h^T Q_h
+      T_CK((sgemm<1, 0>(p.prob, (int)T, p.dao, q, p.dqkv + q + kv, nqkv, (int)T, hd, rep * (int)T, 0.f, st, vd)));     // dV = sum_h P_h^T dO_h
+    }
+    for (int hh = 0; hh < (one_launch ? 0 : rep); ++hh) {   // otherwise one launch per head of the group, in order
       const float beta = hh > 0 ? 1.f : 0.f;
       T_CK((sgemm<1, 0>(p.dsc + (size_t)hh * T * T, (int)T, a.qkv + (size_t)hh * hd, nqkv, p.dqkv + q, nqkv, (int)T, hd, (int)T,
                         beta, st, b_dk)));                                                                       // dK += dS^T Q
