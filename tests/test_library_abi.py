@@ -60,3 +60,18 @@ def test_host_side_argument_validation_needs_no_gpu():
     assert rc == sapo.SAPO_EINVAL and b"tensor 0" in lib.sapo_last_error()
     cfg.kv_page_tokens = 32
     assert lib.sapo_weights_create(ctypes.byref(cfg), ptrs, 21, None, ctypes.byref(out)) == sapo.SAPO_ESHAPE
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: bench.py --gpus N > 1 exits with a message that says so (before anything touches a device)."""
+    import subprocess
+    import sys
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_node_glue_imports_without_a_gpu():
+    from paper_2509_08721_amd import node
+    assert hasattr(node, "Node")
