@@ -752,6 +752,112 @@ __global__ void k_swiglu_bwd(const float* __restrict__ dact, const float* __rest
   dgu[m * 2 * F + F + f] = da * g * sg;
 }
 
+// ---------------------------------------------------------------------------------------
+// Fused causal attention in fp32 on the matrix cores (v_mfma_f32_16x16x4_f32), for head dims 16, 32, 64, 128.
+// A wave owns 16 positions of one (sequence, head) and walks the other side in tiles of 16; nothing of size
+// T x T is stored.  Layouts of one 16x16x4 MFMA: A[m = lane % 16][k = lane / 16], B[k = lane / 16][n = lane % 16],
+// D rows 4 (lane / 16) + v (v = 0..3), column lane % 16.  Two kinds of products:
+//  * rows x rows over the head dim (scores, dP): both operands are read as float4 per lane - lane (r, g) takes
+//    dims 16 w + 4 g + c of row r - and MFMA (w, c) contracts the dims {16 w + 4 g + c : g}: any assignment of dims
+//    to k slots is fine as long as both operands use the same one;
+//  * (head dim x positions) products over the 16 positions of the tile (P V, dS K, ...): the B operand of MFMA u
+//    is the lane's own accumulator entry u of the tile just computed (position 4 g + u), the A operand is the
+//    matching row of V / K / Q / dO, read as scalars (lanes along the head dim).
+// qkv[M, q + 2 kv] holds rotated q, k and v; out[M, q]; lse[(s Hq + h) T + i].
+// ---------------------------------------------------------------------------------------
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+template <int HD>
+__device__ __forceinline__ void load_rows4(const float* __restrict__ base, size_t row_stride, int row, int g, float4 (&dst)[HD / 16]) {
+#pragma unroll
+  for (int w = 0; w < HD / 16; ++w) dst[w] = *(const float4*)(base + (size_t)row * row_stride + 16 * w + 4 * g);
+}
+__device__ __forceinline__ float f4c(const float4& v, int c) { return c == 0 ? v.x : c == 1 ? v.y : c == 2 ? v.z : v.w; }
+
+// acc (rows = positions of `a`, 4 g + v; column = position of `b`, lane % 16) += a b^T over the head dim
+template <int HD>
+__device__ __forceinline__ f32x4_t dot_rows(const float4 (&a)[HD / 16], const float4 (&b)[HD / 16]) {
+  f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int w = 0; w < HD / 16; ++w)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(f4c(a[w], c), f4c(b[w], c), acc, 0, 0, 0);
+  return acc;
+}
+// o[dt] (rows = head dims 16 dt + 4 g + v; column = lane % 16) += sum over the tile's positions 4 g + u of
+// src[position][dim] * p[u]; src rows start at `tile_base` (pointer to position 0 of the tile, this head's dims)
+template <int HD>
+__device__ __forceinline__ void accumulate_tile(const float* __restrict__ tile_base, size_t row_stride, int n_valid, int g, int r,
+                                                const f32x4_t& p, f32x4_t (&o)[HD / 16]) {
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int pos = min(4 * g + u, n_valid - 1);   // rows past the end repeat the last one (their p is zero)
+    const float* row = tile_base + (size_t)pos * row_stride;
+#pragma unroll
+    for (int dt = 0; dt < HD / 16; ++dt) o[dt] = __builtin_amdgcn_mfma_f32_16x16x4f32(row[16 * dt + r], p[u], o[dt], 0, 0, 0);
+  }
+}
+
+template <int HD>
+__global__ void __launch_bounds__(256) k_tattn_fwd(const float* __restrict__ qkv, int T, int hq, int hkv, float scale,
+                                                   float* __restrict__ out, float* __restrict__ lse) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+  const int h = blockIdx.y, s = blockIdx.z, kvh = h / (hq / hkv);
+  const int q0 = (blockIdx.x * 4 + wave) * 16;
+  if (q0 >= T) return;
+  const int qd = hq * HD, kvd = hkv * HD;
+  const size_t rl = (size_t)qd + 2 * kvd;
+  const float* base = qkv + (size_t)s * T * rl;
+  const float* qb = base + (size_t)h * HD;
+  const float* kb = base + qd + (size_t)kvh * HD;
+  const float* vb = kb + kvd;
+  const int qi = min(q0 + r, T - 1);   // this lane's query (columns past T repeat the last one and are not stored)
+  float4 qf[HD / 16];
+  load_rows4<HD>(qb, rl, qi, g, qf);
+  f32x4_t o[HD / 16];
+#pragma unroll
+  for (int dt = 0; dt < HD / 16; ++dt) o[dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY, l_run = 0.f;
+  const int last = min(q0 + 15, T - 1);
+  for (int k0 = 0; k0 <= last; k0 += 16) {
+    const int n_valid = min(16, T - k0);
+    float4 kf[HD / 16];
+    load_rows4<HD>(kb, rl, min(k0 + r, T - 1), g, kf);
+    f32x4_t sc = dot_rows<HD>(kf, qf);   // rows: keys k0 + 4 g + v; column: query qi
+    float mx = -INFINITY;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int key = k0 + 4 * g + v;
+      sc[v] = (key <= qi && key < T) ? sc[v] * scale : -INFINITY;
+      mx = fmaxf(mx, sc[v]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);        // finite: key 0 is visible to every query
+    const float alpha = expf(m_run - m_new);
+    f32x4_t p;
+    float ps = 0.f;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) { p[v] = expf(sc[v] - m_new); ps += p[v]; }
+    l_run = l_run * alpha + ps;
+    m_run = m_new;
+#pragma unroll
+    for (int dt = 0; dt < HD / 16; ++dt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) o[dt][v] *= alpha;
+    accumulate_tile<HD>(vb + (size_t)k0 * rl, rl, n_valid, g, r, p, o);
+  }
+  l_run += __shfl_xor(l_run, 16, 64);
+  l_run += __shfl_xor(l_run, 32, 64);
+  if (q0 + r >= T) return;
+  const float inv = 1.0f / l_run;
+  float* orow = out + ((size_t)s * T + qi) * qd + (size_t)h * HD;
+#pragma unroll
+  for (int dt = 0; dt < HD / 16; ++dt)
+    *(float4*)(orow + 16 * dt + 4 * g) = make_float4(o[dt][0] * inv, o[dt][1] * inv, o[dt][2] * inv, o[dt][3] * inv);
+  if (g == 0) lse[((size_t)s * hq + h) * T + qi] = m_run + logf(l_run);
+}
+
 // Attention backward pieces (the contractions are batched GEMMs):
 // delta[(s Hq + h) T + i] = dO_i . O_i over the head's dims; one wave per (s, i, h)
 __global__ void __launch_bounds__(64) k_attn_delta(const float* __restrict__ dout, const float* __restrict__ out, int T, int hq,
@@ -1146,6 +1252,8 @@ static int update_rows(sapo_trainer* tr, const TrainPlan& p, const int32_t* toke
   const int t_final = 1 + 9 * D.L, t_head = c.tied_embeddings ? 0 : t_final + 1;
   const int rep = hq / hkv;
   const float att_scale = 1.0f / sqrtf((float)hd);
+  // the fused attention kernels need float4 rows: head dim 16 / 32 / 64 / 128 and a row length that is a multiple of 4
+  const bool fused_attn = (hd == 16 || hd == 32 || hd == 64 || hd == 128) && nqkv % 4 == 0 && q % 4 == 0;
   const size_t n_sc = S * hq * T * T;
   const long TT = (long)(T * T), Trow = (long)(T * D.nqkv), Tq = (long)(T * D.q);
   Batch b_scores, b_pv, b_dp, b_dq, b_dk, b_dv;
@@ -1194,10 +1302,20 @@ static int update_rows(sapo_trainer* tr, const TrainPlan& p, const int32_t* toke
       T_CK(launch(KID_ROPE_APPEND, k_rope, dim3(blocks256(total)), dim3(256), 0, st, a.qkv, (const float2*)tr->rope, (int)T,
                   hq + hkv, hd, nqkv, 1.0f, total));
     }
-    T_CK((sgemm<0, 1>(a.qkv, nqkv, a.qkv + q, nqkv, p.prob, (int)T, (int)T, (int)T, hd, 0.f, st, b_scores)));
-    T_CK(launch(KID_ATTN_GENERIC, k_softmax_causal, dim3((unsigned)(S * hq * T)), dim3(64), 0, st, p.prob, a.lse, (int)T,
-                att_scale));
-    T_CK((sgemm<0, 0>(p.prob, (int)T, a.qkv + q + kv, nqkv, a.ao, q, (int)T, hd, (int)T, 0.f, st, b_pv)));
+    if (fused_attn) {
+      const dim3 ag((unsigned)((T + 63) / 64), hq, (unsigned)S);
+      hipError_t e = hipErrorInvalidValue;
+      if (hd == 16) e = launch(KID_ATTN_GENERIC, k_tattn_fwd<16>, ag, dim3(256), 0, st, (const float*)a.qkv, (int)T, hq, hkv, att_scale, a.ao, a.lse);
+      if (hd == 32) e = launch(KID_ATTN_GENERIC, k_tattn_fwd<32>, ag, dim3(256), 0, st, (const float*)a.qkv, (int)T, hq, hkv, att_scale, a.ao, a.lse);
+      if (hd == 64) e = launch(KID_ATTN_GENERIC, k_tattn_fwd<64>, ag, dim3(256), 0, st, (const float*)a.qkv, (int)T, hq, hkv, att_scale, a.ao, a.lse);
+      if (hd == 128) e = launch(KID_ATTN_GENERIC, k_tattn_fwd<128>, ag, dim3(256), 0, st, (const float*)a.qkv, (int)T, hq, hkv, att_scale, a.ao, a.lse);
+      T_CK(e);
+    } else {
+      T_CK((sgemm<0, 1>(a.qkv, nqkv, a.qkv + q, nqkv, p.prob, (int)T, (int)T, (int)T, hd, 0.f, st, b_scores)));
+      T_CK(launch(KID_ATTN_GENERIC, k_softmax_causal, dim3((unsigned)(S * hq * T)), dim3(64), 0, st, p.prob, a.lse, (int)T,
+                  att_scale));
+      T_CK((sgemm<0, 0>(p.prob, (int)T, a.qkv + q + kv, nqkv, a.ao, q, (int)T, hd, (int)T, 0.f, st, b_pv)));
+    }
     T_CK(hipMemcpyAsync(a.h2, a.h, M * D.d * sizeof(float), hipMemcpyDeviceToDevice, st));
     T_CK(mm_nt(a.ao, q, TH(t0 + 4), q, a.h2, d, Mi, d, q, 1.f));
     T_CK(launch(KID_RMSNORM, k_rmsnorm_fwd, dim3(Mi), dim3(256), 0, st, (const float*)a.h2, (const float*)TH(t0 + 5), c.rms_eps,
