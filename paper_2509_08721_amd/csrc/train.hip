@@ -858,6 +858,133 @@ __global__ void __launch_bounds__(256) k_tattn_fwd(const float* __restrict__ qkv
   if (g == 0) lse[((size_t)s * hq + h) * T + qi] = m_run + logf(l_run);
 }
 
+// Backward, queries: a wave owns 16 queries of one (sequence, head).  delta = dO . O; per key tile
+//   p = exp(scale s - lse), dP = V dO^T, dS = scale p (dP - delta), dQ^T += K^T dS.
+// Writes dq into dqkv's query columns and delta[(s Hq + h) T + i].
+template <int HD>
+__global__ void __launch_bounds__(256) k_tattn_bwd_q(const float* __restrict__ qkv, const float* __restrict__ out,
+                                                     const float* __restrict__ dout, const float* __restrict__ lse, int T, int hq,
+                                                     int hkv, float scale, float* __restrict__ dqkv, float* __restrict__ delta) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+  const int h = blockIdx.y, s = blockIdx.z, kvh = h / (hq / hkv);
+  const int q0 = (blockIdx.x * 4 + wave) * 16;
+  if (q0 >= T) return;
+  const int qd = hq * HD, kvd = hkv * HD;
+  const size_t rl = (size_t)qd + 2 * kvd;
+  const float* base = qkv + (size_t)s * T * rl;
+  const float* qb = base + (size_t)h * HD;
+  const float* kb = base + qd + (size_t)kvh * HD;
+  const float* vb = kb + kvd;
+  const int qi = min(q0 + r, T - 1);
+  float4 qf[HD / 16], dof[HD / 16], of[HD / 16];
+  load_rows4<HD>(qb, rl, qi, g, qf);
+  load_rows4<HD>(dout + (size_t)s * T * qd + (size_t)h * HD, qd, qi, g, dof);
+  load_rows4<HD>(out + (size_t)s * T * qd + (size_t)h * HD, qd, qi, g, of);
+  float dl = 0.f;
+#pragma unroll
+  for (int w = 0; w < HD / 16; ++w)
+    dl += dof[w].x * of[w].x + dof[w].y * of[w].y + dof[w].z * of[w].z + dof[w].w * of[w].w;
+  dl += __shfl_xor(dl, 16, 64);
+  dl += __shfl_xor(dl, 32, 64);
+  const size_t stat = ((size_t)s * hq + h) * T + qi;
+  const float l = lse[stat];
+  f32x4_t dq[HD / 16];
+#pragma unroll
+  for (int dt = 0; dt < HD / 16; ++dt) dq[dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  const int last = min(q0 + 15, T - 1);
+  for (int k0 = 0; k0 <= last; k0 += 16) {
+    const int n_valid = min(16, T - k0);
+    float4 kf[HD / 16], vf[HD / 16];
+    load_rows4<HD>(kb, rl, min(k0 + r, T - 1), g, kf);
+    load_rows4<HD>(vb, rl, min(k0 + r, T - 1), g, vf);
+    const f32x4_t sc = dot_rows<HD>(kf, qf);    // rows: keys k0 + 4 g + v; column: query qi
+    const f32x4_t dp = dot_rows<HD>(vf, dof);   // dP[key][query] = v_key . dO_query
+    f32x4_t ds;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int key = k0 + 4 * g + v;
+      const float pv = (key <= qi && key < T) ? expf(sc[v] * scale - l) : 0.f;
+      ds[v] = scale * pv * (dp[v] - dl);
+    }
+    accumulate_tile<HD>(kb + (size_t)k0 * rl, rl, n_valid, g, r, ds, dq);
+  }
+  if (q0 + r >= T) return;
+  float* drow = dqkv + ((size_t)s * T + qi) * rl + (size_t)h * HD;
+#pragma unroll
+  for (int dt = 0; dt < HD / 16; ++dt) *(float4*)(drow + 16 * dt + 4 * g) = make_float4(dq[dt][0], dq[dt][1], dq[dt][2], dq[dt][3]);
+  if (g == 0) delta[stat] = dl;
+}
+
+// Backward, keys and values: a wave owns 16 keys of one (sequence, KV head) and walks the query heads of the
+// group and the query tiles from its own on, in that fixed order:
+//   p = exp(scale s - lse_q), dV^T += dO^T p, dP = dO V^T, dS = scale p (dP - delta_q), dK^T += Q^T dS.
+template <int HD>
+__global__ void __launch_bounds__(256) k_tattn_bwd_kv(const float* __restrict__ qkv, const float* __restrict__ dout,
+                                                      const float* __restrict__ lse, const float* __restrict__ delta, int T, int hq,
+                                                      int hkv, float scale, float* __restrict__ dqkv) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+  const int kvh = blockIdx.y, s = blockIdx.z, rep = hq / hkv;
+  const int k0 = (blockIdx.x * 4 + wave) * 16;
+  if (k0 >= T) return;
+  const int qd = hq * HD, kvd = hkv * HD;
+  const size_t rl = (size_t)qd + 2 * kvd;
+  const float* base = qkv + (size_t)s * T * rl;
+  const float* kb = base + qd + (size_t)kvh * HD;
+  const float* vb = kb + kvd;
+  const int kj = min(k0 + r, T - 1);
+  const bool key_ok = k0 + r < T;
+  float4 kf[HD / 16], vf[HD / 16];
+  load_rows4<HD>(kb, rl, kj, g, kf);
+  load_rows4<HD>(vb, rl, kj, g, vf);
+  f32x4_t dk[HD / 16], dv[HD / 16];
+#pragma unroll
+  for (int dt = 0; dt < HD / 16; ++dt) { dk[dt] = f32x4_t{0.f, 0.f, 0.f, 0.f}; dv[dt] = dk[dt]; }
+  for (int hh = 0; hh < rep; ++hh) {
+    const int h = kvh * rep + hh;
+    const float* qb = base + (size_t)h * HD;
+    const float* dob = dout + (size_t)s * T * qd + (size_t)h * HD;
+    const float* lse_h = lse + ((size_t)s * hq + h) * T;
+    const float* del_h = delta + ((size_t)s * hq + h) * T;
+    for (int q0 = k0; q0 < T; q0 += 16) {
+      const int n_valid = min(16, T - q0);
+      float4 qf[HD / 16], dof[HD / 16];
+      load_rows4<HD>(qb, rl, min(q0 + r, T - 1), g, qf);
+      load_rows4<HD>(dob, qd, min(q0 + r, T - 1), g, dof);
+      const f32x4_t sc = dot_rows<HD>(qf, kf);    // rows: queries q0 + 4 g + v; column: key kj
+      const f32x4_t dp = dot_rows<HD>(dof, vf);   // dP[query][key]
+      f32x4_t pv, ds;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int qi = q0 + 4 * g + v;
+        const int qc = min(qi, T - 1);
+        const float pr = (key_ok && qi < T && kj <= qi) ? expf(sc[v] * scale - lse_h[qc]) : 0.f;
+        pv[v] = pr;
+        ds[v] = scale * pr * (dp[v] - del_h[qc]);
+      }
+      accumulate_tile<HD>(dob + (size_t)q0 * qd, qd, n_valid, g, r, pv, dv);
+      accumulate_tile<HD>(qb + (size_t)q0 * rl, rl, n_valid, g, r, ds, dk);
+    }
+  }
+  if (!key_ok) return;
+  float* krow = dqkv + ((size_t)s * T + kj) * rl + qd + (size_t)kvh * HD;
+#pragma unroll
+  for (int dt = 0; dt < HD / 16; ++dt) {
+    *(float4*)(krow + 16 * dt + 4 * g) = make_float4(dk[dt][0], dk[dt][1], dk[dt][2], dk[dt][3]);
+    *(float4*)(krow + kvd + 16 * dt + 4 * g) = make_float4(dv[dt][0], dv[dt][1], dv[dt][2], dv[dt][3]);
+  }
+}
+
+template <int HD>
+hipError_t tattn_bwd(const float* qkv, const float* out, const float* dout, const float* lse, int S, int T, int hq, int hkv,
+                     float scale, float* dqkv, float* delta, hipStream_t st) {
+  const unsigned tiles = (unsigned)((T + 63) / 64);
+  hipError_t e = launch(KID_ATTN_GENERIC, k_tattn_bwd_q<HD>, dim3(tiles, hq, S), dim3(256), 0, st, qkv, out, dout, lse, T, hq, hkv,
+                        scale, dqkv, delta);
+  if (e != hipSuccess) return e;
+  return launch(KID_ATTN_GENERIC, k_tattn_bwd_kv<HD>, dim3(tiles, hkv, S), dim3(256), 0, st, qkv, dout, lse, (const float*)delta, T,
+                hq, hkv, scale, dqkv);
+}
+
 // Attention backward pieces (the contractions are batched GEMMs):
 // delta[(s Hq + h) T + i] = dO_i . O_i over the head's dims; one wave per (s, i, h)
 __global__ void __launch_bounds__(64) k_attn_delta(const float* __restrict__ dout, const float* __restrict__ out, int T, int hq,
@@ -993,6 +1120,12 @@ struct Arena {
 constexpr size_t kSplitParts = (size_t)8 * 192 * 128 * 128;
 constexpr int kPieces = 3;   // most bf16 pieces per fp32 value in the packed GEMMs (3: fp32 accuracy; buffers are sized for it)
 
+// the fused attention kernels need float4 rows: head dim 16 / 32 / 64 / 128 and row lengths that are multiples of 4
+inline bool fused_attention(const sapo_model_config& c) {
+  const int hd = c.head_dim;
+  return (hd == 16 || hd == 32 || hd == 64 || hd == 128) && (c.n_q_heads * hd) % 4 == 0 && (c.n_kv_heads * hd) % 4 == 0;
+}
+
 struct LayerActs {
   float *h, *r1, *xn, *qkv, *lse, *ao, *h2, *r2, *xn2, *gu, *act;
 };
@@ -1039,8 +1172,10 @@ void make_plan(const sapo_model_config& c, size_t S, size_t T, size_t S_total, c
   p.dao = A.take<float>(M * D.q);
   p.dqkv = A.take<float>(M * D.nqkv);
   p.delta = A.take<float>(S * c.n_q_heads * T);
-  p.prob = A.take<float>(S * c.n_q_heads * T * T);
-  p.dsc = A.take<float>(S * c.n_q_heads * T * T);
+  // T x T score matrices: only for head dims the fused attention kernels do not take
+  const size_t n_tt = fused_attention(c) ? 0 : S * c.n_q_heads * T * T;
+  p.prob = A.take<float>(n_tt);
+  p.dsc = A.take<float>(n_tt);
   p.gpart = A.take<float>(((M + 255) / 256) * std::max(D.d, D.nqkv));
   p.chunk = lm_chunk_rows(D, M);
   p.logits = A.take<float>(p.chunk * D.V);
@@ -1252,8 +1387,7 @@ static int update_rows(sapo_trainer* tr, const TrainPlan& p, const int32_t* toke
   const int t_final = 1 + 9 * D.L, t_head = c.tied_embeddings ? 0 : t_final + 1;
   const int rep = hq / hkv;
   const float att_scale = 1.0f / sqrtf((float)hd);
-  // the fused attention kernels need float4 rows: head dim 16 / 32 / 64 / 128 and a row length that is a multiple of 4
-  const bool fused_attn = (hd == 16 || hd == 32 || hd == 64 || hd == 128) && nqkv % 4 == 0 && q % 4 == 0;
+  const bool fused_attn = fused_attention(c);
   const size_t n_sc = S * hq * T * T;
   const long TT = (long)(T * T), Trow = (long)(T * D.nqkv), Tq = (long)(T * D.q);
   Batch b_scores, b_pv, b_dp, b_dq, b_dk, b_dv;
@@ -1368,30 +1502,39 @@ static int update_rows(sapo_trainer* tr, const TrainPlan& p, const int32_t* toke
     T_CK(mm_nn(p.dh, d, TH(t0 + 4), q, p.dao, q, Mi, q, d, 0.f));
     T_CK(mm_tn(p.dh, d, a.ao, q, GR(t0 + 4), d, q, Mi, 1.f));
     // attention and the rotary embedding
-    T_CK((sgemm<0, 1>(a.qkv, nqkv, a.qkv + q, nqkv, p.prob, (int)T, (int)T, (int)T, hd, 0.f, st, b_scores)));
-    T_CK(launch(KID_ATTN_GENERIC, k_probs_from_lse, dim3(blocks256(n_sc)), dim3(256), 0, st, p.prob, (const float*)a.lse, (int)T,
-                att_scale, n_sc));
-    T_CK((sgemm<0, 1>(p.dao, q, a.qkv + q + kv, nqkv, p.dsc, (int)T, (int)T, (int)T, hd, 0.f, st, b_dp)));     // dP = dO V^T
-    T_CK(launch(KID_ATTN_GENERIC, k_attn_delta, dim3((unsigned)(M * hq)), dim3(64), 0, st, (const float*)p.dao, (const float*)a.ao,
-                (int)T, hq, hd, p.delta));
-    T_CK(launch(KID_ATTN_GENERIC, k_dscores, dim3(blocks256(n_sc)), dim3(256), 0, st, (const float*)p.prob, p.dsc,
-                (const float*)p.delta, (int)T, att_scale, n_sc));
-    T_CK((sgemm<0, 0>(p.dsc, (int)T, a.qkv + q, nqkv, p.dqkv, nqkv, (int)T, hd, (int)T, 0.f, st, b_dq)));       // dQ = dS K
-    const bool one_launch = T % 16 == 0 && hd % 4 == 0 && nqkv % 4 == 0 && q % 4 == 0 && (long)T * hd * S_ * hkv >= 128 * 128;
-    if (one_launch) {   // the query heads of a group are segments of one contraction (added in head order)
-      Batch kd = b_dk, vd = b_dv;
-      kd.kseg = vd.kseg = (int)T;
-      kd.sega = vd.sega = TT;
-      kd.segb = vd.segb = hd;
-      T_CK((sgemm<1, 0>(p.dsc, (int)T, a.qkv, nqkv, p.dqkv + q, nqkv, (int)T, hd, rep * (int)T, 0.f, st, kd)));        // dK = sum_h dS_h^T Q_h
-      T_CK((sgemm<1, 0>(p.prob, (int)T, p.dao, q, p.dqkv + q + kv, nqkv, (int)T, hd, rep * (int)T, 0.f, st, vd)));     // dV = sum_h P_h^T dO_h
-    }
-    for (int hh = 0; hh < (one_launch ? 0 : rep); ++hh) {   // otherwise one launch per head of the group, in order
-      const float beta = hh > 0 ? 1.f : 0.f;
-      T_CK((sgemm<1, 0>(p.dsc + (size_t)hh * T * T, (int)T, a.qkv + (size_t)hh * hd, nqkv, p.dqkv + q, nqkv, (int)T, hd, (int)T,
-                        beta, st, b_dk)));                                                                       // dK += dS^T Q
-      T_CK((sgemm<1, 0>(p.prob + (size_t)hh * T * T, (int)T, p.dao + (size_t)hh * hd, q, p.dqkv + q + kv, nqkv, (int)T, hd,
-                        (int)T, beta, st, b_dv)));                                                               // dV += P^T dO
+    if (fused_attn) {
+      hipError_t e = hipErrorInvalidValue;
+      if (hd == 16) e = tattn_bwd<16>(a.qkv, a.ao, p.dao, a.lse, S_, T_, hq, hkv, att_scale, p.dqkv, p.delta, st);
+      if (hd == 32) e = tattn_bwd<32>(a.qkv, a.ao, p.dao, a.lse, S_, T_, hq, hkv, att_scale, p.dqkv, p.delta, st);
+      if (hd == 64) e = tattn_bwd<64>(a.qkv, a.ao, p.dao, a.lse, S_, T_, hq, hkv, att_scale, p.dqkv, p.delta, st);
+      if (hd == 128) e = tattn_bwd<128>(a.qkv, a.ao, p.dao, a.lse, S_, T_, hq, hkv, att_scale, p.dqkv, p.delta, st);
+      T_CK(e);
+    } else {
+      T_CK((sgemm<0, 1>(a.qkv, nqkv, a.qkv + q, nqkv, p.prob, (int)T, (int)T, (int)T, hd, 0.f, st, b_scores)));
+      T_CK(launch(KID_ATTN_GENERIC, k_probs_from_lse, dim3(blocks256(n_sc)), dim3(256), 0, st, p.prob, (const float*)a.lse, (int)T,
+                  att_scale, n_sc));
+      T_CK((sgemm<0, 1>(p.dao, q, a.qkv + q + kv, nqkv, p.dsc, (int)T, (int)T, (int)T, hd, 0.f, st, b_dp)));     // dP = dO V^T
+      T_CK(launch(KID_ATTN_GENERIC, k_attn_delta, dim3((unsigned)(M * hq)), dim3(64), 0, st, (const float*)p.dao, (const float*)a.ao,
+                  (int)T, hq, hd, p.delta));
+      T_CK(launch(KID_ATTN_GENERIC, k_dscores, dim3(blocks256(n_sc)), dim3(256), 0, st, (const float*)p.prob, p.dsc,
+                  (const float*)p.delta, (int)T, att_scale, n_sc));
+      T_CK((sgemm<0, 0>(p.dsc, (int)T, a.qkv + q, nqkv, p.dqkv, nqkv, (int)T, hd, (int)T, 0.f, st, b_dq)));       // dQ = dS K
+      const bool one_launch = T % 16 == 0 && hd % 4 == 0 && nqkv % 4 == 0 && q % 4 == 0 && (long)T * hd * S_ * hkv >= 128 * 128;
+      if (one_launch) {   // the query heads of a group are segments of one contraction (added in head order)
+        Batch kd = b_dk, vd = b_dv;
+        kd.kseg = vd.kseg = (int)T;
+        kd.sega = vd.sega = TT;
+        kd.segb = vd.segb = hd;
+        T_CK((sgemm<1, 0>(p.dsc, (int)T, a.qkv, nqkv, p.dqkv + q, nqkv, (int)T, hd, rep * (int)T, 0.f, st, kd)));        // dK = sum_h dS_h^T Q_h
+        T_CK((sgemm<1, 0>(p.prob, (int)T, p.dao, q, p.dqkv + q + kv, nqkv, (int)T, hd, rep * (int)T, 0.f, st, vd)));     // dV = sum_h P_h^T dO_h
+      }
+      for (int hh = 0; hh < (one_launch ? 0 : rep); ++hh) {   // otherwise one launch per head of the group, in order
+        const float beta = hh > 0 ? 1.f : 0.f;
+        T_CK((sgemm<1, 0>(p.dsc + (size_t)hh * T * T, (int)T, a.qkv + (size_t)hh * hd, nqkv, p.dqkv + q, nqkv, (int)T, hd, (int)T,
+                          beta, st, b_dk)));                                                                       // dK += dS^T Q
+        T_CK((sgemm<1, 0>(p.prob + (size_t)hh * T * T, (int)T, p.dao + (size_t)hh * hd, q, p.dqkv + q + kv, nqkv, (int)T, hd,
+                          (int)T, beta, st, b_dv)));                                                               // dV += P^T dO
+      }
     }
     {
       const size_t total = M * (size_t)(hq + hkv) * (hd / 2);
@@ -1432,7 +1575,8 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
   // and backward at a time, the gradients adding up; the whole set at once when the workspace allows it.
   TrainPlan p;
   size_t S_mb = S;
-  const size_t most = (size_t)65535 / c.n_q_heads;   // (sequence, query head) pairs of one batched attention GEMM
+  // grid limits: sequences per launch of the fused attention kernels, (sequence, query head) pairs of a batched GEMM
+  const size_t most = fused_attention(c) ? (size_t)65535 : (size_t)65535 / c.n_q_heads;
   if (S_mb > most) S_mb = most;
   make_plan(c, S_mb, T, S, nullptr, p);
   if (workspace_bytes < p.bytes) {

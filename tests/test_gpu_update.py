@@ -17,7 +17,10 @@ SHAPES = {
     # sizes that are not multiples of the GEMM tile, untied head, one KV head
     "ragged_untied": W.ModelShape(n_layers=1, d_model=96, n_q_heads=3, n_kv_heads=1, head_dim=32, d_ff=80, vocab=300,
                                   rms_eps=1e-5, rope_theta=1e6, tied_embeddings=False, dtype="f32", max_seq=64),
-    # head_dim 128 (two head dims per lane in the attention kernels)
+    # a head dim the fused attention kernels do not take: attention as batched GEMMs over T x T score matrices
+    "hd24": W.ModelShape(n_layers=2, d_model=48, n_q_heads=4, n_kv_heads=2, head_dim=24, d_ff=64, vocab=96,
+                         rms_eps=1e-6, rope_theta=1e4, tied_embeddings=True, dtype="f32", max_seq=512),
+    # head_dim 128
     "hd128": W.ModelShape(n_layers=2, d_model=64, n_q_heads=2, n_kv_heads=1, head_dim=128, d_ff=72, vocab=130,
                           rms_eps=1e-6, rope_theta=1e4, tied_embeddings=True, dtype="f32", max_seq=128),
 }
@@ -74,7 +77,8 @@ def read_all(sapo, tr, what):
 
 @pytest.mark.parametrize("name,S,T,masked", [("tiny", 8, 32, 16), ("ragged_untied", 3, 13, 9), ("hd128", 4, 70, 33),
                                              ("tiny", 16, 64, 30),    # 1024 tokens: split weight-gradient GEMMs
-                                             ("tiny_long", 2, 300, 140)])
+                                             ("tiny_long", 2, 300, 140),
+                                             ("hd24", 3, 40, 20), ("hd24", 2, 272, 100)])
 def test_update_matches_oracle(sapo, name, S, T, masked):
     import torch
     from oracle import sapo_update_oracle as U
