@@ -157,14 +157,15 @@ def bench_update(args, wl):
             # MFMA multiply-adds.  `achieved` counts the algorithmic flops (what an fp32 GEMM would count) against
             # the bf16 MFMA peak, the contraction's own type; `executed_*` counts what the matrix cores ran.
             k = kernels["k_gemm"]
+            n_products = {3: 6, 2: 3, 1: 1}[args.pieces]
             ach = flops / (k["total_ms"] * 1e-3) / 1e12
             k.update(bound="mfma", work_per_launch=flops / k["launches"], achieved=round(ach, 2), unit="TFLOP/s",
                      frac=round(ach / MFMA_16BIT_PEAK_TFLOPS, 4))
             roofline = {"kernel": "k_gemm_x3 (the projection and LM-head GEMMs of the update)", "bound": "mfma", "achieved": k["achieved"],
                         "peak": MFMA_16BIT_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": k["frac"], "traffic": None,
                         "avg_us": k["avg_us"], "launches": k["launches"], "work_per_launch": k["work_per_launch"],
-                        "executed_TFLOPs": round((6 if args.pieces == 3 else 1) * ach, 1),
-                        "executed_frac": round((6 if args.pieces == 3 else 1) * ach / MFMA_16BIT_PEAK_TFLOPS, 4),
+                        "executed_TFLOPs": round(n_products * ach, 1),
+                        "executed_frac": round(n_products * ach / MFMA_16BIT_PEAK_TFLOPS, 4),
                         "vs_fp32_mfma_peak": round(ach / FP32_MFMA_PEAK_TFLOPS, 4)}
     cpu = None
     if not args.no_cpu_baseline:
@@ -183,10 +184,12 @@ def bench_update(args, wl):
     out = {"metric": "trained tokens/s of one policy update (forward + clipped surrogate + backward + Adam)",
            "value": round(S * T / dt, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(dt * 1e3, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-           "dtype": "f32" if args.pieces == 3 else "bf16", "data": "synthetic",
+           "dtype": {3: "f32", 2: "bf16x2", 1: "bf16"}[args.pieces], "data": "synthetic",
            "config": {"workload": wl.name,
-                      "arithmetic": "fp32 (GEMM products as 6 bf16 x bf16 partial products, fp32 accumulation)" if args.pieces == 3
-                      else "fp32 with bf16 GEMM operands (1 piece), fp32 accumulation",
+                      "arithmetic": {3: "fp32 (GEMM products as 6 bf16 x bf16 partial products, fp32 accumulation)",
+                                     2: "fp32 with GEMM operands of 16 significant bits (2 bf16 pieces, 3 partial products), "
+                                        "fp32 accumulation",
+                                     1: "fp32 with bf16 GEMM operands (1 piece), fp32 accumulation"}[args.pieces],
                       "layers": shape.n_layers, "d_model": shape.d_model, "vocab": shape.vocab,
                       "seqs": S, "seq_len": T, "masked": Tm, "sequences_per_micro_batch": s_micro,
                       "optimizer": "Adam lr 1e-3 (defaults)",
@@ -212,8 +215,9 @@ def main():
                     help="counter runs only: same kernels and shapes with this many layers (fewer launches); "
                          "the printed line is then not a benchmark result")
     ap.add_argument("--new-tokens", type=int, default=0, help="counter runs only: generate this many tokens")
-    ap.add_argument("--pieces", type=int, default=3,
-                    help="halfb_update only: 3 = fp32-accurate matrix products (default), 1 = bf16 operands")
+    ap.add_argument("--pieces", type=int, default=3, choices=(1, 2, 3),
+                    help="*_update workloads only: 3 = fp32-accurate matrix products (default), 2 = operands of 16 "
+                         "significant bits, 1 = bf16 operands")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this library runs on ONE GPU (no sharding, no collectives); --gpus %d is not "

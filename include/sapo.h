@@ -317,6 +317,9 @@ int sapo_trainer_get_qkv_bias(const sapo_trainer* tr, int layer, float* bq, floa
  * Arithmetic of the update's large matrix products (projections and LM head; forward and backward).
  *   pieces = 3 (default): every fp32 operand is the exact sum of three bf16 values and a product is the
  *                sum of the six largest of the nine partial products: the accuracy of an fp32 product.
+ *   pieces = 2: every operand is rounded to 16 significant bits (two bf16 values) and a product is the
+ *                sum of three partial products: relative error below 2^-16 per product, of either sign,
+ *                at half the matrix-core work.
  *   pieces = 1: operands rounded to bf16 (nearest even), fp32 accumulation: plain mixed precision,
  *                several times faster; gradients then carry the relative error of bf16 operands
  *                (about 2^-8 of a contraction's sum of absolute terms).

@@ -265,7 +265,10 @@ __global__ void __launch_bounds__(256) k_sgemm_mfma(const float* __restrict__ A,
 // partial products of weight >= 2^-16 (hi hi, hi mid, mid hi, hi lo, lo hi, mid mid), each exact in fp32,
 // the three dropped ones being below 2^-23 of the product: the rounding of an fp32 multiply.  Six
 // v_mfma_f32_32x32x16_bf16 (32 cycles each) do the work of sixteen v_mfma_f32_32x32x2_f32 (64 cycles each).
-// With one piece (hi only) the same kernels are a plain bf16 GEMM with fp32 accumulation.
+// With one piece the same kernels are a plain bf16 GEMM with fp32 accumulation (the value rounded to nearest).
+// With two pieces (the value rounded to bf16, then the exact remainder rounded to bf16: 16 significant bits) the
+// three products hi hi, hi mid, mid hi are taken: what is dropped is below 2^-16 of a product and of either sign,
+// at half the matrix-core work of the six-product form.
 //
 // Operands are cut once per GEMM by k_pack_x3 into the order a workgroup stages them in: for every block of
 // 128 rows and every 16-k step, [piece][k half][row] entries of 8 bf16 (16 bytes): one contiguous 2 KB x
@@ -295,11 +298,12 @@ __device__ __forceinline__ void x3_store(uint4* __restrict__ dst, int NP, int KB
   uint32_t p[3][8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) split3(x[j], p[0][j], p[1][j], p[2][j]);
-  if (NP == 1) {   // a single piece is the value rounded to bf16 (nearest even), not its leading 8 bits
+  if (NP < 3) {   // one or two pieces are roundings to nearest even (of the value, then of what is left), not bit fields
+    auto rne = [](float f) { const uint32_t u = __float_as_uint(f); return (u + 0x7FFFu + ((u >> 16) & 1u)) & 0xFFFF0000u; };
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const uint32_t u = __float_as_uint(x[j]);
-      p[0][j] = (u + 0x7FFFu + ((u >> 16) & 1u)) & 0xFFFF0000u;
+      p[0][j] = rne(x[j]);
+      p[1][j] = rne(x[j] - __uint_as_float(p[0][j]));
     }
   }
   for (int pc = 0; pc < NP; ++pc)
@@ -409,8 +413,9 @@ __global__ void __launch_bounds__(256, RB == 2 ? 2 : 3) k_gemm_x3(const u32x4_t*
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int pc = 0; pc < NP; ++pc) b[j][pc].u = Bs[cur][(pc * 2 + kh) * 128 + wn + j * 32 + c];
-    // smallest partial products first: (hi lo), (lo hi), (mid mid), (hi mid), (mid hi), (hi hi)
-    constexpr int n_terms = NP == 3 ? 6 : 1;
+    // smallest partial products first: (hi lo), (lo hi), (mid mid), (hi mid), (mid hi), (hi hi); two pieces take the
+    // last three, one piece the last
+    constexpr int n_terms = NP == 3 ? 6 : NP == 2 ? 3 : 1;
     constexpr int pa[6] = {0, 2, 1, 0, 1, 0}, pb[6] = {2, 0, 1, 1, 0, 0};
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
@@ -501,6 +506,7 @@ hipError_t gemm_x3(const X3Op& A, const X3Op& B, float* C, int ldc, float beta, 
     return launch(KID_GEMM_GENERIC, kernel, grid, dim3(256), 0, st, pa_, pb_, out, ldc, A.rows, B.rows, KB, b_, kbs, c_split);
   };
   if (bufs.NP == 3) e = RB == 2 ? go(k_gemm_x3<3, 2>) : go(k_gemm_x3<3, 1>);
+  else if (bufs.NP == 2) e = RB == 2 ? go(k_gemm_x3<2, 2>) : go(k_gemm_x3<2, 1>);
   else e = RB == 2 ? go(k_gemm_x3<1, 2>) : go(k_gemm_x3<1, 1>);
   if (e != hipSuccess || splits == 1) return e;
   const size_t n = (size_t)A.rows * B.rows;
@@ -1057,7 +1063,7 @@ struct sapo_trainer {
   sapo_model_config cfg;
   sapo_adam_config opt;
   int t = 0;                      // Adam steps taken
-  int pieces = 3;                 // bf16 pieces per value in the large GEMMs: 3 (fp32 accuracy) or 1 (bf16 operands)
+  int pieces = 3;                 // bf16 pieces per value in the large GEMMs: 3 (fp32 accuracy), 2 or 1 (bf16 operands)
   bool use_bias = false;          // the model has biases on its query / key / value projections (set_qkv_bias)
   int n_in = 0;                   // tensors of the input list; tensor n_in + l is layer l's bias vector
   int device = 0;
@@ -1340,7 +1346,8 @@ extern "C" int sapo_trainer_steps(const sapo_trainer* tr) { return tr ? tr->t : 
 
 extern "C" int sapo_trainer_set_matmul_pieces(sapo_trainer* tr, int pieces) {
   if (!tr) return set_error(SAPO_EINVAL, "trainer is NULL");
-  if (pieces != 1 && pieces != 3) return set_error(SAPO_EINVAL, "pieces must be 3 (fp32 accuracy) or 1 (bf16 operands)");
+  if (pieces < 1 || pieces > 3)
+    return set_error(SAPO_EINVAL, "pieces must be 3 (fp32 accuracy), 2 (16 significant bits) or 1 (bf16 operands)");
   tr->pieces = pieces;
   return SAPO_OK;
 }

@@ -324,8 +324,9 @@ def test_update_with_bf16_operands(sapo, which):
     logp_old = (lp0 + u * (mask != 0)).astype(np.float32)
     ref_loss, ref_lp, ref_g = U.loss_and_gradients(shape, params, tokens, mask, logp_old, adv)
     tr = sapo.sapo_trainer_create(shape, w)
-    with pytest.raises(sapo.SapoError):
-        sapo.sapo_trainer_set_matmul_pieces(tr, 2)
+    for bad in (0, 4):
+        with pytest.raises(sapo.SapoError):
+            sapo.sapo_trainer_set_matmul_pieces(tr, bad)
     sapo.sapo_trainer_set_matmul_pieces(tr, 1)
     loss, lp = sapo.sapo_policy_update(tr, dev(tokens), dev(mask), dev(logp_old), dev(adv))
     torch.cuda.synchronize()
@@ -336,6 +337,26 @@ def test_update_with_bf16_operands(sapo, which):
     for i, b in enumerate(ref_g):
         g = sapo.sapo_trainer_read(tr, 1, i).cpu().numpy().astype(np.float64)
         assert float(np.max(np.abs(g - b))) <= 5e-2 * max(float(np.max(np.abs(b))), 1e-3 * gmax) + 1e-7, i
+    g_err1 = max(float(np.max(np.abs(sapo.sapo_trainer_read(tr, 1, i).cpu().numpy() - b))) / max(float(np.max(np.abs(b))), 1e-3 * gmax)
+                 for i, b in enumerate(ref_g))
+    # two pieces (operands of 16 significant bits, three partial products): errors of 2^-16 of a product, of either
+    # sign.  Log-probs to 5e-4, gradients to 1e-3 of a tensor's largest entry, and far closer than one piece.
+    tr1 = sapo.sapo_trainer_create(shape, w)
+    sapo.sapo_trainer_set_matmul_pieces(tr1, 2)
+    loss2, lp2 = sapo.sapo_policy_update(tr1, dev(tokens), dev(mask), dev(logp_old), dev(adv))
+    torch.cuda.synchronize()
+    lp_err2 = float(np.max(np.abs(lp2.cpu().numpy() - ref_lp)))
+    assert lp_err2 < 5e-4 and lp_err2 < lp_err / 8
+    assert abs(float(loss2.cpu()[0]) - ref_loss) < 2e-4
+    g_err2 = 0.0
+    for i, b in enumerate(ref_g):
+        g = sapo.sapo_trainer_read(tr1, 1, i).cpu().numpy().astype(np.float64)
+        rel = float(np.max(np.abs(g - b))) / max(float(np.max(np.abs(b))), 1e-3 * gmax)
+        assert rel <= 1e-3, i
+        g_err2 = max(g_err2, rel)
+    assert g_err2 < g_err1 / 8
+    print("pieces 1: logp %.2e grad %.2e; pieces 2: logp %.2e grad %.2e" % (lp_err, g_err1, lp_err2, g_err2))
+    tr1.close()
     # back to three pieces: fp32 accuracy again
     tr2 = sapo.sapo_trainer_create(shape, w)
     sapo.sapo_trainer_set_matmul_pieces(tr2, 1)
