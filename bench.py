@@ -101,6 +101,90 @@ def update_flops(shape, S, T, n_chunks_rows):
     return proj + head, attn
 
 
+def bench_stop(args, wl):
+    """Rollouts with a stop token (answers of different lengths): generated tokens/s with ended sequences leaving
+    the decode batch, and the same call with every sequence kept in the batch to the end."""
+    import torch
+    from paper_2509_08721_amd import sapo, workloads as W
+    shape = wl.shape
+    torch.cuda.set_device(0)
+    t0 = time.time()
+    weights = W.boost_token(W.make_weights(shape, wl.weight_seed), shape, wl.stop_token, wl.stop_boost)
+    gw = sapo.sapo_weights_create(shape, weights)
+    P, G, Lp, N = wl.n_prompts, wl.group, wl.prompt_len, wl.n_new
+    S = P * G
+    prompts_np = W.make_prompts(wl)
+    prompts = torch.from_numpy(prompts_np).cuda()
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    torch.cuda.set_stream(side)
+    ws = torch.empty(sapo.sapo_rollout_workspace_bytes(gw, P, Lp, G, N) + 256, dtype=torch.uint8, device="cuda")
+    bufs = (torch.empty((S, N), dtype=torch.int32, device="cuda"), torch.empty((S, N), dtype=torch.float32, device="cuda"),
+            torch.empty((S,), dtype=torch.int32, device="cuda"))
+    setup_s = time.time() - t0
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+
+    def timed(compact):
+        if not compact:
+            os.environ["SAPO_NO_COMPACT"] = "1"
+        try:
+            ms, last = [], None
+            for i in range(args.warmup + args.steps):
+                ev[0].record()
+                last = sapo.sapo_rollout_generate_stop(gw, prompts, G, N, wl.temperature, wl.rollout_seed + i, wl.stop_token,
+                                                       workspace=ws, out=bufs)
+                ev[1].record()
+                torch.cuda.synchronize()
+                if i >= args.warmup:
+                    ms.append((ev[0].elapsed_time(ev[1]), int(last[2].sum().item())))
+            return ms, last, sapo.sapo_rollout_last_stats(gw)
+        finally:
+            os.environ.pop("SAPO_NO_COMPACT", None)
+
+    ms_c, last_c, stats_c = timed(True)
+    ms_n, last_n, stats_n = timed(False)
+    rate = lambda runs: float(np.median([tok / (m * 1e-3) for m, tok in runs]))
+    lens = last_c[2].cpu().numpy().astype(np.int64)
+    # algorithmic bytes of the last timed call: one pass over the weights per decode step that some sequence still
+    # needs, K/V of every running sequence's own tokens, a prompt's K/V once per group with a running sibling
+    Wb, kvb = shape.weight_bytes_per_decode_step(), shape.kv_bytes_per_token()
+    steps_needed = int(lens.max()) - 1
+    t_idx = np.arange(1, steps_needed + 1)
+    running = lens[None, :] > t_idx[:, None]                              # [steps, S]
+    groups_running = running.reshape(len(t_idx), P, G).any(axis=2).sum(axis=1)
+    kv_read = kvb * float((running * t_idx[:, None]).sum() + (groups_running * Lp).sum())
+    kv_write = kvb * float(P * Lp + running.sum())
+    alg_bytes = steps_needed * Wb + kv_read + kv_write
+    ms_last = ms_c[-1][0]
+    gbs = alg_bytes / (ms_last * 1e-3) / 1e9
+    out = {"metric": "generated tokens/s of rollouts with a stop token (%s, 1 GPU)" % wl.name,
+           "value": round(rate(ms_c), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(float(np.median([m for m, _ in ms_c])), 3), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+           "config": {"workload": wl.name, "layers": shape.n_layers, "d_model": shape.d_model, "vocab": shape.vocab,
+                      "prompts": P, "completions_per_prompt": G, "prompt_len": Lp, "max_new": N,
+                      "stop_token": wl.stop_token, "stop_row_scale": 2 ** wl.stop_boost,
+                      "lengths": {"mean": round(float(lens.mean()), 1), "min": int(lens.min()), "max": int(lens.max()),
+                                  "quartiles": [int(x) for x in np.percentile(lens, [25, 50, 75])],
+                                  "at_max_new": int((lens == N).sum())}},
+           "generated_tokens": int(lens.sum()),
+           "batch_compacted": {"tokens_per_s": round(rate(ms_c), 1), "ms": round(float(np.median([m for m, _ in ms_c])), 3), **stats_c},
+           "batch_kept_whole": {"tokens_per_s": round(rate(ms_n), 1), "ms": round(float(np.median([m for m, _ in ms_n])), 3), **stats_n},
+           "roofline": {"kernel": "the decode steps of the call (all kernels)", "bound": "hbm", "achieved": round(gbs, 1),
+                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                        "algorithmic_bytes": alg_bytes},
+           "cpu_baseline": None, "setup_s": round(setup_s, 1)}
+    if not args.no_cpu_baseline:
+        from oracle import sapo_oracle as O
+        m = O.Model(shape, weights)
+        t1 = time.perf_counter()
+        O.rollout_generate_stop(m, prompts_np[:1, :32], 1, 4, wl.temperature, wl.rollout_seed, wl.stop_token)
+        dtc = time.perf_counter() - t1
+        out["cpu_baseline"] = {"value": round(4 / dtc, 3), "unit": "tokens/s", "cores": len(os.sched_getaffinity(0)),
+                               "kind": "oracle", "sample": "numpy fp64 oracle: 1 sequence, 32-token prompt, 4 new tokens in %.1f s" % dtc}
+    print(json.dumps(out))
+
+
 def bench_update(args, wl):
     """The local policy update on one training set: trained tokens/s of sapo_policy_update."""
     import torch
@@ -231,6 +315,8 @@ def main():
     wl = W.WORKLOADS[args.workload]
     if args.workload.endswith("_update"):
         return bench_update(args, wl)
+    if wl.stop_token >= 0:
+        return bench_stop(args, wl)
     if args.layers > 0:
         wl = replace(wl, shape=replace(wl.shape, n_layers=args.layers))
     if args.new_tokens > 0:

@@ -127,7 +127,11 @@ int sapo_rollout_generate(const sapo_weights* w, const int32_t* prompts, int P, 
  * sequence samples ends it (the token and its log-prob are kept); the rest of its row is stop_token
  * with log-prob 0.  The noise is keyed on (seed, sequence, step), so a row equals the row of the
  * plain call up to and including its stop.  Every 32 steps the host reads a counter (this call then
- * synchronises the stream) and returns early once every sequence has ended.
+ * synchronises the stream) and returns early once every sequence has ended.  On the matrix-core
+ * path with more than 64 sequences, ended sequences also leave the batch: once the running ones fit 256
+ * (then 64) rows, the decode step goes on with that many rows.  A row of the result is then still the
+ * sample the definition above describes for its sequence (same noise, same cache), computed by the
+ * kernels of the smaller batch, whose logits differ from the larger batch's by fp32 summation order.
  *   stop_token   a vocabulary id
  *   out_lengths  dev int32 [P*G]   tokens generated including the stop token; max_new if none
  */
@@ -135,6 +139,15 @@ int sapo_rollout_generate_stop(const sapo_weights* w, const int32_t* prompts, in
                                int max_new, float temperature, uint64_t seed, int32_t stop_token,
                                int32_t* out_tokens, float* out_logprobs, int32_t* out_lengths,
                                void* workspace, size_t workspace_bytes, void* stream);
+/*
+ * Figures of the last rollout call made on this handle (host ints, for logs and tests):
+ *   out4[0] decode steps enqueued (max_new - 1 unless every sequence ended early)
+ *   out4[1] times the batch was compacted
+ *   out4[2] rows per decode step at the end of the call
+ *   out4[3] ended sequences at the last look (0 without a stop token)
+ */
+int sapo_rollout_last_stats(const sapo_weights* w, int32_t* out4);
+
 
 /*
  * Rollout generation for prompts of different lengths (questions are presented directly as prompts,

@@ -141,15 +141,24 @@ struct sapo_weights {
     hipGraph_t graph = nullptr;
     hipGraphExec_t exec = nullptr;
   };
-  mutable DecodeGraph dgraph;
+  // [0]: every sequence has its row; [1], [2]: the smaller batches a call with a stop token falls back to once
+  // enough sequences have ended (kCompactSlots)
+  mutable DecodeGraph dgraph[3];
+  // the last rollout call on this handle: decode steps enqueued, compactions, rows per step at the end,
+  // ended sequences at the last look
+  mutable int last_stats[4] = {0, 0, 0, 0};
 };
 
 static void drop_decode_graph(const sapo_weights* w) {
-  if (!w->dgraph.valid) return;
-  (void)hipDeviceSynchronize();           // replays of the old graph may still be in flight
-  if (w->dgraph.exec) (void)hipGraphExecDestroy(w->dgraph.exec);
-  if (w->dgraph.graph) (void)hipGraphDestroy(w->dgraph.graph);
-  w->dgraph = sapo_weights::DecodeGraph();
+  bool any = false;
+  for (const auto& g : w->dgraph) any = any || g.valid;
+  if (!any) return;
+  (void)hipDeviceSynchronize();           // replays of the old graphs may still be in flight
+  for (auto& g : w->dgraph) {
+    if (g.exec) (void)hipGraphExecDestroy(g.exec);
+    if (g.graph) (void)hipGraphDestroy(g.graph);
+    g = sapo_weights::DecodeGraph();
+  }
 }
 
 static int validate_config(const sapo_model_config* c) {
@@ -590,8 +599,22 @@ struct RolloutPlan {
   DecodeBufs dec;   // MFMA decode path
   bool fused_lm;    // LM head + sampler fused, 64-token kernel
   bool big_lm;      // LM head + sampler fused, token-parallel kernel (more sequences or a wider model)
+  // MFMA decode with a stop token: once the running sequences fit a smaller batch, the step goes on with that
+  // many rows (a row's sequence is slot_seq[row]); level 0 is the full batch
+  struct Level {
+    int slots = 0;
+    DecodeBufs dec;
+    bool fused_lm = false, big_lm = false;
+    float* partials = nullptr;
+    int* slot_seq = nullptr;
+  };
+  Level level[3];
+  int n_levels;
   size_t bytes;
 };
+// Rows per step a batch is compacted to: at 64 rows and below the weight-streaming kernels run, up to 256 the
+// token-parallel FFN with one token tile (see run_layers_decode16)
+static const int kCompactSlots[2] = {256, 64};
 
 static void plan_rollout(const sapo_weights* w, int P, int Lp, int G, int N, char* base, RolloutPlan& pl) {
   const sapo_model_config& c = w->cfg;
@@ -619,6 +642,22 @@ static void plan_rollout(const sapo_weights* w, int P, int Lp, int G, int N, cha
   pl.partials = pl.fused_lm ? A.take<float>(d_lmhead_sample_partial_floats())
                 : pl.big_lm ? A.take<float>((size_t)m_lmhead_sample_big_groups(c.vocab) * pl.S * 5) : nullptr;
   if (w->mfma) carve_decode(A, w, pl.S, pl.dec);
+  pl.n_levels = 1;
+  pl.level[0].slots = pl.S; pl.level[0].dec = pl.dec; pl.level[0].fused_lm = pl.fused_lm; pl.level[0].big_lm = pl.big_lm;
+  pl.level[0].partials = pl.partials; pl.level[0].slot_seq = nullptr;
+  if (w->mfma) {
+    for (int slots : kCompactSlots) {
+      if (slots >= pl.S) continue;
+      RolloutPlan::Level& lv = pl.level[pl.n_levels++];
+      lv.slots = slots;
+      carve_decode(A, w, slots, lv.dec);
+      lv.fused_lm = d_lmhead_sample_supported(c.d_model, slots);
+      lv.big_lm = !lv.fused_lm;
+      lv.partials = lv.fused_lm ? A.take<float>(d_lmhead_sample_partial_floats())
+                                : A.take<float>((size_t)m_lmhead_sample_big_groups(c.vocab) * slots * 5);
+      lv.slot_seq = A.take<int>(256);
+    }
+  }
   pl.bytes = (A.off + 255) & ~(size_t)255;
 }
 
@@ -642,22 +681,23 @@ extern "C" size_t sapo_rollout_workspace_bytes(const sapo_weights* w, int P, int
 //   fused path : the final norm's operand is in pl.dec.xa / pl.dec.ssq_a (ssq_parts parts); the merge
 //                also gathers the sampled tokens' embedding rows for the next step.
 //   otherwise  : from the residual rows in `h` (row s = sequence s) through materialised logits.
-static int sample_step(const sapo_weights* w, const RolloutPlan& pl, const float* h, int ssq_parts, SampleParams sp,
-                       hipStream_t st) {
+//   lv         : the batch of the step (rows, decode buffers, which sampler); sp.slot_seq = lv.slot_seq
+static int sample_step(const sapo_weights* w, const RolloutPlan& pl, const RolloutPlan::Level& lv, const float* h,
+                       int ssq_parts, SampleParams sp, hipStream_t st) {
   const sapo_model_config& c = w->cfg;
-  const int S = pl.S, d = c.d_model, V = c.vocab;
-  if (pl.fused_lm) {
+  const int S = lv.slots, d = c.d_model, V = c.vocab;
+  if (lv.fused_lm) {
     const float* gain_first = c.n_layers > 0 ? w->layers[0].attn_norm : w->final_norm;
-    HIP_CK(d_lmhead_sample(w->lm_head16, pl.dec.xa, d, V, pl.dec.ssq_a, ssq_parts, pl.dec.s_pad, c.rms_eps, S, sp,
-                           pl.partials, w->embed, gain_first, pl.fwd.h, pl.dec.xa, pl.dec.ssq_a, st));
+    HIP_CK(d_lmhead_sample(w->lm_head16, lv.dec.xa, d, V, lv.dec.ssq_a, ssq_parts, lv.dec.s_pad, c.rms_eps, S, sp,
+                           lv.partials, w->embed, gain_first, pl.fwd.h, lv.dec.xa, lv.dec.ssq_a, st));
     return SAPO_OK;
   }
-  if (pl.big_lm) {
+  if (lv.big_lm) {
     const float* gain_first = c.n_layers > 0 ? w->layers[0].attn_norm : w->final_norm;
     HIP_CK(m_rmsnorm_x32(h, w->final_norm, c.rms_eps, pl.x_last, S, d, nullptr, st));
-    HIP_CK(m_lmhead_sample_big(pl.x_last, w->lm_head, S, V, d, sp, pl.partials, st));
-    HIP_CK(d_lmhead_merge_embed(pl.partials, m_lmhead_sample_big_groups(V), S, S, sp, w->embed, d, gain_first, pl.fwd.h,
-                                pl.dec.xa, pl.dec.ssq_a, st));
+    HIP_CK(m_lmhead_sample_big(pl.x_last, w->lm_head, S, V, d, sp, lv.partials, st));
+    HIP_CK(d_lmhead_merge_embed(lv.partials, m_lmhead_sample_big_groups(V), S, S, sp, w->embed, d, gain_first, pl.fwd.h,
+                                lv.dec.xa, lv.dec.ssq_a, st));
     return SAPO_OK;
   } else {
     HIP_CK(g_rmsnorm(c.dtype, h, w->final_norm, c.rms_eps, pl.x_last, S, d, nullptr, st));
@@ -683,7 +723,9 @@ static int rollout_impl(const sapo_weights* w, const int32_t* prompts, const int
   const sapo_model_config& c = w->cfg;
   const int dt = c.dtype, d = c.d_model, S = pl.S;
   const float* gain_first = c.n_layers > 0 ? w->layers[0].attn_norm : w->final_norm;
-  const int parts_after_layers = c.n_layers == 0 ? 1 : (w->mfma && pl.dec.down_splits > 0) ? (d + 1023) / 1024 : d / 16;
+  auto parts_after_layers = [&](const RolloutPlan::Level& lv) {
+    return c.n_layers == 0 ? 1 : (w->mfma && lv.dec.down_splits > 0) ? (d + 1023) / 1024 : d / 16;
+  };
 
   SampleParams sp;
   sp.temperature = temperature;
@@ -712,15 +754,8 @@ static int rollout_impl(const sapo_weights* w, const int32_t* prompts, const int
     if (out_lengths) HIP_CK(g_lengths_out(pl.stop + 2, S, max_new, out_lengths, st));
     return SAPO_OK;
   };
-  // with a stop token the host looks, every kStopPoll steps, whether every sequence has ended
+  // with a stop token the host looks, every kStopPoll steps, how many sequences have ended
   const int kStopPoll = 32;
-  auto all_stopped = [&](bool& yes) -> int {
-    int n = 0;
-    HIP_CK(hipMemcpyAsync(&n, pl.stop + 1, sizeof(int), hipMemcpyDeviceToHost, st));
-    HIP_CK(hipStreamSynchronize(st));
-    yes = (n >= S);
-    return SAPO_OK;
-  };
 
   HIP_CK(g_fill_i32(pl.step, 0, 1, st));
   {
@@ -762,72 +797,114 @@ static int rollout_impl(const sapo_weights* w, const int32_t* prompts, const int
       HIP_CK(g_gather_last_rows(pl.fwd.h, pl.h_last, S, G, Lp, d, st));
     }
     if (pl.fused_lm) HIP_CK(d_pack_rows_x16(pl.h_last, w->final_norm, S, d, pl.dec.xa, pl.dec.ssq_a, st));
-    if ((rc = sample_step(w, pl, pl.h_last, 1, sp, st))) return rc;
+    if ((rc = sample_step(w, pl, pl.level[0], pl.h_last, 1, sp, st))) return rc;
   }
   // decode: token t-1 of every sequence goes through the layers, token t is sampled.  Everything
   // that changes from step to step is read from device memory (*step), so one step is captured
   // into a graph and replayed.
-  RowMap rm{1, 0, 1, Lp, pl.step, ragged ? pl.lens : nullptr, G};
-  auto enqueue_step = [&]() -> int {
+  auto enqueue_step = [&](const RolloutPlan::Level& lv) -> int {
     int rc2;
+    RowMap rm{1, 0, 1, Lp, pl.step, ragged ? pl.lens : nullptr, G};
+    rm.slot_seq = lv.slot_seq;
+    SampleParams spl = sp;
+    spl.slot_seq = lv.slot_seq;
     if (!merge_steps) HIP_CK(g_incr(pl.step, st));
     if (w->mfma) {
       // (the sampler's merge has already gathered the embedding rows of the previous step's tokens)
-      if ((rc2 = run_layers_decode16(w, pl.fwd, pl.dec, S, rm, pl.cache, st))) return rc2;
-      if ((rc2 = sample_step(w, pl, pl.fwd.h, parts_after_layers, sp, st))) return rc2;
+      if ((rc2 = run_layers_decode16(w, pl.fwd, lv.dec, lv.slots, rm, pl.cache, st))) return rc2;
+      if ((rc2 = sample_step(w, pl, lv, pl.fwd.h, parts_after_layers(lv), spl, st))) return rc2;
     } else {
       HIP_CK(g_embed(dt, out_tokens, max_new, pl.step, w->embed, pl.fwd.h, S, d, st));
       if ((rc2 = run_layers(w, pl.fwd, S, rm, pl.cache, Lp + max_new, st))) return rc2;
-      if ((rc2 = sample_step(w, pl, pl.fwd.h, 0, sp, st))) return rc2;
+      if ((rc2 = sample_step(w, pl, lv, pl.fwd.h, 0, spl, st))) return rc2;
     }
     return SAPO_OK;
   };
   const char* no_graph = getenv("SAPO_NO_GRAPH");
   const bool use_graph = st != nullptr && !g_prof_on && max_new > 2 && !(no_graph && no_graph[0] == '1');
-  if (!use_graph) {
-    for (int t = 1; t < max_new; ++t) {
-      if (stopping && t % kStopPoll == 0) {
-        bool done = false;
-        if ((rc = all_stopped(done))) return rc;
-        if (done) break;
+  // One captured step per level, kept with the weights and rebuilt when a call uses other buffers or sizes.
+  auto step_graph = [&](int li, hipGraphExec_t& exec) -> int {
+    sapo_weights::DecodeGraph& dg = w->dgraph[li];
+    if (!(dg.valid && dg.out_tokens == out_tokens && dg.out_logprobs == out_logprobs && dg.workspace == workspace &&
+          dg.P == P && dg.Lp == Lp && dg.G == G && dg.N == max_new && dg.ragged == ragged)) {
+      if (li == 0) {
+        drop_decode_graph(w);   // the smaller batches' graphs belong to the same call shape
+      } else if (dg.valid) {
+        (void)hipDeviceSynchronize();
+        if (dg.exec) (void)hipGraphExecDestroy(dg.exec);
+        if (dg.graph) (void)hipGraphDestroy(dg.graph);
+        dg = sapo_weights::DecodeGraph();
       }
-      if ((rc = enqueue_step())) return rc;
+      HIP_CK(hipStreamBeginCapture(st, hipStreamCaptureModeRelaxed));
+      const int rc2 = enqueue_step(pl.level[li]);
+      hipGraph_t graph = nullptr;
+      const hipError_t e = hipStreamEndCapture(st, &graph);
+      if (rc2) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return rc2;
+      }
+      if (e != hipSuccess) return fail(SAPO_EHIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
+      hipGraphExec_t ex = nullptr;
+      const hipError_t e2 = hipGraphInstantiate(&ex, graph, nullptr, nullptr, 0);
+      if (e2 != hipSuccess) {
+        (void)hipGraphDestroy(graph);
+        return fail(SAPO_EHIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e2));
+      }
+      dg.valid = true;
+      dg.out_tokens = out_tokens; dg.out_logprobs = out_logprobs; dg.workspace = workspace;
+      dg.P = P; dg.Lp = Lp; dg.G = G; dg.N = max_new; dg.ragged = ragged;
+      dg.graph = graph; dg.exec = ex;
     }
-    return finish();
-  }
-  sapo_weights::DecodeGraph& dg = w->dgraph;
-  if (!(dg.valid && dg.out_tokens == out_tokens && dg.out_logprobs == out_logprobs && dg.workspace == workspace &&
-        dg.P == P && dg.Lp == Lp && dg.G == G && dg.N == max_new && dg.ragged == ragged)) {
-    drop_decode_graph(w);
-    HIP_CK(hipStreamBeginCapture(st, hipStreamCaptureModeRelaxed));
-    rc = enqueue_step();
-    hipGraph_t graph = nullptr;
-    const hipError_t e = hipStreamEndCapture(st, &graph);
-    if (rc) {
-      if (graph) (void)hipGraphDestroy(graph);
-      return rc;
-    }
-    if (e != hipSuccess) return fail(SAPO_EHIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
-    hipGraphExec_t exec = nullptr;
-    const hipError_t e2 = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
-    if (e2 != hipSuccess) {
-      (void)hipGraphDestroy(graph);
-      return fail(SAPO_EHIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e2));
-    }
-    dg.valid = true;
-    dg.out_tokens = out_tokens; dg.out_logprobs = out_logprobs; dg.workspace = workspace;
-    dg.P = P; dg.Lp = Lp; dg.G = G; dg.N = max_new; dg.ragged = ragged;
-    dg.graph = graph; dg.exec = exec;
-  }
+    exec = dg.exec;
+    return SAPO_OK;
+  };
+  // Ended sequences leave the batch (MFMA path): when the running ones fit a smaller level, its rows are dealt
+  // to them (ended sequences fill what is left and keep emitting padding) and the rows' inputs, the embeddings
+  // of the tokens just emitted, are gathered again in the new order.  K/V stay where they are: the page table
+  // is indexed by sequence.
+  const char* no_compact = getenv("SAPO_NO_COMPACT");
+  const bool compacting = stopping && w->mfma && pl.n_levels > 1 && !(no_compact && no_compact[0] == '1');
+  int li = 0, n_compactions = 0, n_steps = 0, n_ended = 0;
+  auto look = [&](bool& all_done) -> int {   // every kStopPoll steps
+    HIP_CK(hipMemcpyAsync(&n_ended, pl.stop + 1, sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_CK(hipStreamSynchronize(st));
+    all_done = n_ended >= S;
+    if (all_done || !compacting) return SAPO_OK;
+    int target = li;
+    for (int k = li + 1; k < pl.n_levels; ++k)
+      if (S - n_ended <= pl.level[k].slots) target = k;
+    if (target == li) return SAPO_OK;
+    const RolloutPlan::Level& lv = pl.level[target];
+    HIP_CK(g_compact_slots(pl.stop + 2, S, lv.slots, lv.slot_seq, st));
+    HIP_CK(d_embed_x16(out_tokens, max_new, pl.step, w->embed, lv.slots, d, gain_first, pl.fwd.h, lv.dec.xa, lv.dec.ssq_a,
+                       lv.slot_seq, st));
+    li = target;
+    ++n_compactions;
+    return SAPO_OK;
+  };
   for (int t = 1; t < max_new; ++t) {
     if (stopping && t % kStopPoll == 0) {
-      bool done = false;
-      if ((rc = all_stopped(done))) return rc;
-      if (done) break;
+      bool all_done = false;
+      if ((rc = look(all_done))) return rc;
+      if (all_done) break;
     }
-    HIP_CK(hipGraphLaunch(dg.exec, st));
+    if (use_graph) {
+      hipGraphExec_t exec = nullptr;
+      if ((rc = step_graph(li, exec))) return rc;
+      HIP_CK(hipGraphLaunch(exec, st));
+    } else if ((rc = enqueue_step(pl.level[li]))) {
+      return rc;
+    }
+    ++n_steps;
   }
+  w->last_stats[0] = n_steps; w->last_stats[1] = n_compactions; w->last_stats[2] = pl.level[li].slots; w->last_stats[3] = n_ended;
   return finish();
+}
+
+extern "C" int sapo_rollout_last_stats(const sapo_weights* w, int32_t* out4) {
+  if (!w || !out4) return fail(SAPO_EINVAL, "NULL argument");
+  for (int i = 0; i < 4; ++i) out4[i] = w->last_stats[i];
+  return SAPO_OK;
 }
 
 extern "C" int sapo_rollout_generate(const sapo_weights* w, const int32_t* prompts, int P, int Lp, int G, int max_new,

@@ -36,10 +36,13 @@ struct RowMap {
   const int* step;  // decode mode: device pointer to the current step index (>= 1)
   const int* lens;  // optional, device: prompt lengths
   int G;            // sequences per prompt (with lens)
+  // decode mode, optional, device: the sequence behind each row once ended sequences have been taken out of
+  // the batch (row m of the step's activations belongs to sequence slot_seq[m]); NULL: row m is sequence m
+  const int* slot_seq = nullptr;
   __device__ __forceinline__ void get(int m, int& seq, int& pos) const {
     if (decode) {
-      seq = m;
-      pos = (lens ? lens[m / G] : Lp) + *step - 1;
+      seq = slot_seq ? slot_seq[m] : m;
+      pos = (lens ? lens[seq / G] : Lp) + *step - 1;
     } else {
       seq = (m / T) * seq_stride;
       pos = m % T;
@@ -155,6 +158,9 @@ struct SampleParams {
   // Optional: arrival counter of the sampler's merge kernel.  When set, the last workgroup of the merge to
   // have read *step advances it (the step counter then needs no kernel of its own).
   int* arrivals = nullptr;
+  // Optional, device: the sequence behind each row of the step (see RowMap::slot_seq).  The noise is keyed on
+  // the sequence, and tokens, log-probs and lengths are written at the sequence's own rows.
+  const int* slot_seq = nullptr;
 };
 
 // Optional per-kernel timing: when switched on, every launch carries two HIP events that take
@@ -240,6 +246,9 @@ hipError_t g_scale_f32(const float* x, float a, float* y, size_t n, hipStream_t 
 hipError_t g_add_row_bias(float* x, const float* bias, int M, int N, hipStream_t st);
 // out[s] = len[s] if the sequence has stopped (len > 0), else max_new
 hipError_t g_lengths_out(const int* len, int S, int max_new, int32_t* out, hipStream_t st);
+// slot_seq[0 .. n_slots): the running sequences (len[s] == 0) in ascending order, then ended ones in ascending
+// order as fill (n_slots <= S; the caller makes sure that at most n_slots sequences are running).
+hipError_t g_compact_slots(const int* len, int S, int n_slots, int* slot_seq, hipStream_t st);
 hipError_t g_assemble(const int32_t* local_tokens, const float* local_rewards, int n_local_pool, const int32_t* ext_tokens,
                       const float* ext_rewards, int n_ext_pool, int G, int T, int n_local, int n_ext, uint32_t seed_lo,
                       uint32_t seed_hi, int32_t* out_tokens, float* out_rewards, int* out_source, int* out_counts,
@@ -360,8 +369,9 @@ hipError_t d_pack_rows_x16(const float* h, const float* gain, int M, int d, void
 // h += sum_z partial[z] (z < splits, each [M, d], split_stride floats apart), then xp and ssq[(d + 1023) / 1024][s_pad]
 hipError_t d_resid_finish_x16(const float* partial, int splits, size_t split_stride, float* h, const float* gain, int M, int d,
                               int s_pad, void* xp, float* ssq, hipStream_t st);
+// Row m <- the embedding of the token that sequence m (slot_seq[m] when slot_seq is given) emitted at step *step - 1
 hipError_t d_embed_x16(const int32_t* tokens, int tok_stride, const int* step, const void* embed, int M, int d,
-                       const float* gain, float* h, void* xp, float* ssq, hipStream_t st);
+                       const float* gain, float* h, void* xp, float* ssq, const int* slot_seq, hipStream_t st);
 bool d_lmhead_sample_supported(int K, int n_rows);
 size_t d_lmhead_sample_partial_floats();
 // Fused LM head + sampler for at most 64 sequences, followed by the merge that writes token and

@@ -415,15 +415,18 @@ __device__ __forceinline__ void embed_row_x16(const bf16* __restrict__ embed, in
 // Decode-side embedding gather of the token sampled at the previous step.
 __global__ void __launch_bounds__(128) k_embed_x16(const int32_t* __restrict__ tokens, int tok_stride, const int* step,
                                                    const bf16* __restrict__ embed, int d, const float* __restrict__ gain,
-                                                   float* __restrict__ h, uint4* __restrict__ xp, float* __restrict__ ssq) {
+                                                   float* __restrict__ h, uint4* __restrict__ xp, float* __restrict__ ssq,
+                                                   const int* __restrict__ slot_seq) {
   __shared__ float red[2];
   const int row = blockIdx.x;
-  const int tok = tokens[(size_t)row * tok_stride + (*step - 1)];
+  const int seq = slot_seq ? slot_seq[row] : row;
+  const int tok = tokens[(size_t)seq * tok_stride + (*step - 1)];
   embed_row_x16(embed, tok, row, d, gain, h, xp, ssq, red);
 }
 hipError_t d_embed_x16(const int32_t* tokens, int tok_stride, const int* step, const void* embed, int M, int d,
-                       const float* gain, float* h, void* xp, float* ssq, hipStream_t st) {
-  return launch(KID_EMBED, k_embed_x16, dim3(M), dim3(128), 0, st, tokens, tok_stride, step, (const bf16*)embed, d, gain, h, (uint4*)xp, ssq);
+                       const float* gain, float* h, void* xp, float* ssq, const int* slot_seq, hipStream_t st) {
+  return launch(KID_EMBED, k_embed_x16, dim3(M), dim3(128), 0, st, tokens, tok_stride, step, (const bf16*)embed, d, gain, h,
+                (uint4*)xp, ssq, slot_seq);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -462,8 +465,13 @@ __global__ void __launch_bounds__(512) k_lmhead_sample16(const uint4* __restrict
   const float inv_t = noisy ? 1.0f / sp.temperature : 1.0f;
   const int fq = lane >> 4, tl = lane & 15;
   float scale[4];
+  uint32_t seq_id[4];   // the noise is keyed on the sequence, which need not be the row
 #pragma unroll
-  for (int g = 0; g < 4; ++g) scale[g] = s_scale[g * 16 + tl];
+  for (int g = 0; g < 4; ++g) {
+    scale[g] = s_scale[g * 16 + tl];
+    const int row = g * 16 + tl;
+    seq_id[g] = (uint32_t)((sp.slot_seq && row < n_rows) ? sp.slot_seq[row] : seq0 + row);
+  }
   LaneState stt;
 #pragma unroll
   for (int g = 0; g < 4; ++g) { stt.m[g] = -INFINITY; stt.l[g] = 0.f; stt.by[g] = -INFINITY; stt.bz[g] = 0.f; stt.bid[g] = 0x7fffffff; }
@@ -511,7 +519,7 @@ __global__ void __launch_bounds__(512) k_lmhead_sample16(const uint4* __restrict
         stt.l[g] = stt.l[g] * __expf(stt.m[g] - mn) + ((__expf(z[0] - mn) + __expf(z[1] - mn)) + (__expf(z[2] - mn) + __expf(z[3] - mn)));
         stt.m[g] = mn;
         float gn[4] = {0.f, 0.f, 0.f, 0.f};
-        if (noisy) gumbel4(sp.seed_lo, sp.seed_hi, (uint32_t)(seq0 + g * 16 + tl), (uint32_t)step, (uint32_t)(v0 >> 2), gn);
+        if (noisy) gumbel4(sp.seed_lo, sp.seed_hi, seq_id[g], (uint32_t)step, (uint32_t)(v0 >> 2), gn);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const float y = noisy ? z[j] * inv_t + gn[j] : z[j];
@@ -580,7 +588,7 @@ __global__ void __launch_bounds__(128) k_lmhead_merge_embed(const float* __restr
     }
     if (lane == 0) {
       const int step = *sp.step;
-      s_tok = emit_token(sp, seq0 + r, step, b.id, b.z - (a.m + logf(a.l)));
+      s_tok = emit_token(sp, sp.slot_seq ? sp.slot_seq[r] : seq0 + r, step, b.id, b.z - (a.m + logf(a.l)));
       // every workgroup has used the step index before it arrives here: the last one to arrive moves it on
       if (sp.arrivals && atomicAdd(sp.arrivals, 1) == (int)gridDim.x - 1) {
         *sp.arrivals = 0;

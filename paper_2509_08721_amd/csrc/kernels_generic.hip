@@ -459,6 +459,32 @@ __global__ void k_lengths_out(const int* __restrict__ len, int S, int max_new, i
 hipError_t g_lengths_out(const int* len, int S, int max_new, int32_t* out, hipStream_t st) {
   return launch(KID_MISC, k_lengths_out, dim3((S + 255) / 256), dim3(256), 0, st, len, S, max_new, out);
 }
+// One workgroup: thread i owns the sequences [i c, (i + 1) c), c = ceil(S / 256); an exclusive scan of the
+// per-thread counts of running and of ended sequences gives every sequence its place.
+__global__ void __launch_bounds__(256) k_compact_slots(const int* __restrict__ len, int S, int n_slots, int* __restrict__ slot_seq) {
+  __shared__ int run_before[257], end_before[257];
+  const int c = (S + 255) / 256, s0 = min(S, (int)threadIdx.x * c), s1 = min(S, s0 + c);
+  int n_run = 0;
+  for (int s = s0; s < s1; ++s) n_run += (len[s] == 0);
+  run_before[threadIdx.x + 1] = n_run;
+  end_before[threadIdx.x + 1] = (s1 - s0) - n_run;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    run_before[0] = end_before[0] = 0;
+    for (int i = 1; i <= 256; ++i) { run_before[i] += run_before[i - 1]; end_before[i] += end_before[i - 1]; }
+  }
+  __syncthreads();
+  const int total_run = run_before[256];
+  int r = run_before[threadIdx.x], e = total_run + end_before[threadIdx.x];
+  for (int s = s0; s < s1; ++s) {
+    const int slot = (len[s] == 0) ? r++ : e++;
+    if (slot < n_slots) slot_seq[slot] = s;
+  }
+}
+hipError_t g_compact_slots(const int* len, int S, int n_slots, int* slot_seq, hipStream_t st) {
+  if (n_slots > S) return hipErrorInvalidValue;
+  return launch(KID_MISC, k_compact_slots, dim3(1), dim3(256), 0, st, len, S, n_slots, slot_seq);
+}
 hipError_t g_advantages(const float* rewards, int S, int G, float* out, hipStream_t st) {
   const int ng = S / G;
   return launch(KID_MISC, k_advantages, dim3((ng + 63) / 64), dim3(64), 0, st, rewards, ng, G, out);

@@ -697,7 +697,8 @@ __global__ void __launch_bounds__(256, 2) k_lmhead_sample_big(const uint4* __res
   float* red = (float*)smem;   // [2][256][5]
 #pragma unroll
   for (int tj = 0; tj < 4; ++tj) {
-    const int seq = tok0 + wt * 128 + tj * 32 + (lane & 31);
+    const int row_ = tok0 + wt * 128 + tj * 32 + (lane & 31);
+    const int seq = (sp.slot_seq && row_ < n_rows) ? sp.slot_seq[row_] : row_;   // the noise is keyed on the sequence
     LseAcc lse;
     BestAcc best;
     lse.init();

@@ -69,6 +69,8 @@ def load_library() -> C.CDLL:
     lib.sapo_rollout_generate.restype = i32
     lib.sapo_rollout_generate_stop.argtypes = [vp, vp, i32, i32, i32, i32, f32, u64, i32, vp, vp, vp, vp, sz, vp]
     lib.sapo_rollout_generate_stop.restype = i32
+    lib.sapo_rollout_last_stats.argtypes = [vp, vp]
+    lib.sapo_rollout_last_stats.restype = i32
     lib.sapo_rollout_generate_ragged.argtypes = [vp, vp, vp, i32, i32, i32, i32, f32, u64, i32, vp, vp, vp, vp, sz, vp]
     lib.sapo_rollout_generate_ragged.restype = i32
     lib.sapo_score_logprobs.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
@@ -126,7 +128,8 @@ def load_library() -> C.CDLL:
 
 EXPORTED = ["sapo_weights_create", "sapo_weights_destroy", "sapo_weights_uses_mfma", "sapo_weights_set_qkv_bias",
             "sapo_rollout_workspace_bytes", "sapo_score_workspace_bytes",
-            "sapo_debug_logits_workspace_bytes", "sapo_rollout_generate", "sapo_rollout_generate_stop", "sapo_rollout_generate_ragged",
+            "sapo_debug_logits_workspace_bytes", "sapo_rollout_generate", "sapo_rollout_generate_stop", "sapo_rollout_last_stats",
+            "sapo_rollout_generate_ragged",
             "sapo_score_logprobs", "sapo_score_logprobs_at",
             "sapo_surrogate_workspace_bytes", "sapo_clipped_surrogate",
             "sapo_assemble_workspace_bytes", "sapo_assemble_training_set",
@@ -279,15 +282,23 @@ def sapo_rollout_generate(w: Weights, prompts, G: int, max_new: int, temperature
 
 
 def sapo_rollout_generate_stop(w: Weights, prompts, G: int, max_new: int, temperature: float, seed: int,
-                               stop_token: int, workspace=None, stream=None):
-    """As sapo_rollout_generate with a stop token.  Returns (tokens, logprobs, lengths int32 [P*G])."""
+                               stop_token: int, workspace=None, stream=None, out=None):
+    """As sapo_rollout_generate with a stop token.  Returns (tokens, logprobs, lengths int32 [P*G]); `out`, if
+    given, is such a triple of device tensors to write into (the captured decode step is reused between calls
+    that pass the same buffers)."""
     torch = _torch()
     lib = load_library()
     P, Lp = int(prompts.shape[0]), int(prompts.shape[1])
     assert prompts.dtype == torch.int32 and prompts.is_cuda and prompts.is_contiguous()
-    out_tokens = torch.empty((P * G, max_new), dtype=torch.int32, device="cuda")
-    out_logprobs = torch.empty((P * G, max_new), dtype=torch.float32, device="cuda")
-    out_lengths = torch.empty((P * G,), dtype=torch.int32, device="cuda")
+    if out is not None:
+        out_tokens, out_logprobs, out_lengths = out
+        assert out_tokens.shape == (P * G, max_new) and out_tokens.dtype == torch.int32 and out_tokens.is_contiguous()
+        assert out_logprobs.shape == (P * G, max_new) and out_logprobs.dtype == torch.float32 and out_logprobs.is_contiguous()
+        assert out_lengths.shape == (P * G,) and out_lengths.dtype == torch.int32
+    else:
+        out_tokens = torch.empty((P * G, max_new), dtype=torch.int32, device="cuda")
+        out_logprobs = torch.empty((P * G, max_new), dtype=torch.float32, device="cuda")
+        out_lengths = torch.empty((P * G,), dtype=torch.int32, device="cuda")
     nbytes = sapo_rollout_workspace_bytes(w, P, Lp, G, max_new)
     if workspace is None:
         workspace = _workspace(nbytes)
@@ -295,6 +306,14 @@ def sapo_rollout_generate_stop(w: Weights, prompts, G: int, max_new: int, temper
                                           int(seed), int(stop_token), out_tokens.data_ptr(), out_logprobs.data_ptr(),
                                           out_lengths.data_ptr(), *_ws_args(workspace), _stream_ptr(stream)))
     return out_tokens, out_logprobs, out_lengths
+
+
+def sapo_rollout_last_stats(w: Weights) -> dict:
+    """Figures of the last rollout call on this handle: decode steps enqueued, compactions of the batch, rows per
+    step at the end, ended sequences at the last look."""
+    out = (C.c_int32 * 4)()
+    _check(load_library().sapo_rollout_last_stats(w.handle, out))
+    return {"steps": out[0], "compactions": out[1], "rows": out[2], "ended": out[3]}
 
 
 def sapo_rollout_generate_ragged(w: Weights, prompts, prompt_lens, G: int, max_new: int, temperature: float, seed: int,

@@ -123,6 +123,10 @@ class Workload:
     reward_p: float = 0.5
     reward_seed: int = 0
     external_weight_seed: Optional[int] = None   # weights of the "other node" (config 4)
+    # answers of different lengths: rollouts end at stop_token, whose LM-head row is scaled by 2^stop_boost
+    # (boost_token) so that lengths spread between a few tokens and n_new
+    stop_token: int = -1
+    stop_boost: int = 0
 
     @property
     def n_seqs(self) -> int:
@@ -166,6 +170,11 @@ WORKLOADS: Dict[str, Workload] = {
     "onehalfb_update": Workload("onehalfb_update", ONE_HALF_B, weight_seed=501, n_prompts=32, group=8, prompt_len=256,
                                 n_new=0, prompt_seed=502, score_seqs=256, score_len=768, score_masked=512,
                                 reward_p=0.3, reward_seed=504),
+    # not one of the five: configuration 5's rollouts with answers of different lengths (a stop token), where
+    # ended sequences leave the decode batch
+    "onehalfb_stop": Workload("onehalfb_stop", ONE_HALF_B, weight_seed=501, n_prompts=32, group=8, prompt_len=256,
+                              n_new=512, temperature=1.0, prompt_seed=502, rollout_seed=503, stop_token=1000,
+                              stop_boost=4),
     "halfb_pass1": Workload("halfb_pass1", HALF_B, weight_seed=201, n_prompts=1, group=1,
                             prompt_len=128, n_new=256, temperature=1.0, prompt_seed=602,
                             rollout_seed=603),
@@ -187,6 +196,25 @@ def layer_tensor_shapes(s: ModelShape) -> Dict[str, tuple]:
     d, q, kv, f = s.d_model, s.q_dim, s.kv_dim, s.d_ff
     return {"attn_norm": (d,), "wq": (q, d), "wk": (kv, d), "wv": (kv, d), "wo": (d, q),
             "ffn_norm": (d,), "w_gate": (f, d), "w_up": (f, d), "w_down": (d, f)}
+
+
+def boost_token(weights: dict, shape: ModelShape, token: int, log2_scale: int) -> dict:
+    """A copy of `weights` whose LM-head row of `token` (the embedding row when the head is tied) is multiplied by
+    2^log2_scale, exactly in either storage type: the token's logit then swings that much more from position to
+    position, so a stop token placed there ends sequences after a spread of lengths (random heads of the
+    workloads' scale would emit any given token about once in `vocab` steps)."""
+    out = dict(weights)
+    key = "embed" if weights.get("lm_head") is None else "lm_head"
+    m = np.array(weights[key], copy=True)
+    if m.dtype == np.uint16:     # bf16 bit patterns: the exponent field starts at bit 7
+        row = m[token].astype(np.int32)
+        expo = (row >> 7) & 0xFF
+        assert np.all((expo == 0) | ((expo + log2_scale > 0) & (expo + log2_scale < 255)))
+        m[token] = np.where(expo == 0, row, row + (log2_scale << 7)).astype(np.uint16)
+    else:
+        m[token] = m[token] * np.float32(2.0 ** log2_scale)
+    out[key] = m
+    return out
 
 
 def make_weights(shape: ModelShape, seed: int, std: float = 0.02) -> dict:
