@@ -790,8 +790,13 @@ __device__ __forceinline__ f32x4_t dot_rows(const float4 (&a)[HD / 16], const fl
     for (int c = 0; c < 4; ++c) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(f4c(a[w], c), f4c(b[w], c), acc, 0, 0, 0);
   return acc;
 }
-// o[dt] (rows = head dims 16 dt + 4 g + v; column = lane % 16) += sum over the tile's positions 4 g + u of
-// src[position][dim] * p[u]; src rows start at `tile_base` (pointer to position 0 of the tile, this head's dims)
+// o (head dims x the 16 columns of lane % 16) += sum over the tile's positions 4 g + u of src[position][dim] * p[u];
+// src rows start at `tile_base` (pointer to position 0 of the tile, this head's dims).  Which head dim an
+// accumulator entry holds is free to choose (the rows of an MFMA are whatever its A operand's lanes supply):
+//   head dims in multiples of 64: lane r supplies the dims 64 j + 4 r + c of a position as float4 loads, so
+//     o[4 j + c][v] is dim 64 j + 16 g + 4 v + c;
+//   otherwise lane r supplies dim 16 dt + r as scalars: o[dt][v] is dim 16 dt + 4 g + v.
+// store_acc writes either arrangement out as float4 runs.
 template <int HD>
 __device__ __forceinline__ void accumulate_tile(const float* __restrict__ tile_base, size_t row_stride, int n_valid, int g, int r,
                                                 const f32x4_t& p, f32x4_t (&o)[HD / 16]) {
@@ -799,13 +804,37 @@ __device__ __forceinline__ void accumulate_tile(const float* __restrict__ tile_b
   for (int u = 0; u < 4; ++u) {
     const int pos = min(4 * g + u, n_valid - 1);   // rows past the end repeat the last one (their p is zero)
     const float* row = tile_base + (size_t)pos * row_stride;
+    if constexpr (HD % 64 == 0) {
 #pragma unroll
-    for (int dt = 0; dt < HD / 16; ++dt) o[dt] = __builtin_amdgcn_mfma_f32_16x16x4f32(row[16 * dt + r], p[u], o[dt], 0, 0, 0);
+      for (int j = 0; j < HD / 64; ++j) {
+        const float4 a = *(const float4*)(row + 64 * j + 4 * r);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) o[4 * j + c] = __builtin_amdgcn_mfma_f32_16x16x4f32(f4c(a, c), p[u], o[4 * j + c], 0, 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int dt = 0; dt < HD / 16; ++dt) o[dt] = __builtin_amdgcn_mfma_f32_16x16x4f32(row[16 * dt + r], p[u], o[dt], 0, 0, 0);
+    }
+  }
+}
+template <int HD>
+__device__ __forceinline__ void store_acc(float* __restrict__ row, const f32x4_t (&o)[HD / 16], int g, float mul) {
+  if constexpr (HD % 64 == 0) {
+#pragma unroll
+    for (int j = 0; j < HD / 64; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        *(float4*)(row + 64 * j + 16 * g + 4 * v) =
+            make_float4(o[4 * j][v] * mul, o[4 * j + 1][v] * mul, o[4 * j + 2][v] * mul, o[4 * j + 3][v] * mul);
+  } else {
+#pragma unroll
+    for (int dt = 0; dt < HD / 16; ++dt)
+      *(float4*)(row + 16 * dt + 4 * g) = make_float4(o[dt][0] * mul, o[dt][1] * mul, o[dt][2] * mul, o[dt][3] * mul);
   }
 }
 
 template <int HD>
-__global__ void __launch_bounds__(256) k_tattn_fwd(const float* __restrict__ qkv, int T, int hq, int hkv, float scale,
+__global__ void __launch_bounds__(256, HD == 128 ? 3 : 1) k_tattn_fwd(const float* __restrict__ qkv, int T, int hq, int hkv, float scale,
                                                    float* __restrict__ out, float* __restrict__ lse) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
   const int h = blockIdx.y, s = blockIdx.z, kvh = h / (hq / hkv);
@@ -857,10 +886,7 @@ __global__ void __launch_bounds__(256) k_tattn_fwd(const float* __restrict__ qkv
   l_run += __shfl_xor(l_run, 32, 64);
   if (q0 + r >= T) return;
   const float inv = 1.0f / l_run;
-  float* orow = out + ((size_t)s * T + qi) * qd + (size_t)h * HD;
-#pragma unroll
-  for (int dt = 0; dt < HD / 16; ++dt)
-    *(float4*)(orow + 16 * dt + 4 * g) = make_float4(o[dt][0] * inv, o[dt][1] * inv, o[dt][2] * inv, o[dt][3] * inv);
+  store_acc<HD>(out + ((size_t)s * T + qi) * qd + (size_t)h * HD, o, g, inv);
   if (g == 0) lse[((size_t)s * hq + h) * T + qi] = m_run + logf(l_run);
 }
 
@@ -868,7 +894,7 @@ __global__ void __launch_bounds__(256) k_tattn_fwd(const float* __restrict__ qkv
 //   p = exp(scale s - lse), dP = V dO^T, dS = scale p (dP - delta), dQ^T += K^T dS.
 // Writes dq into dqkv's query columns and delta[(s Hq + h) T + i].
 template <int HD>
-__global__ void __launch_bounds__(256) k_tattn_bwd_q(const float* __restrict__ qkv, const float* __restrict__ out,
+__global__ void __launch_bounds__(256, HD == 128 ? 3 : 1) k_tattn_bwd_q(const float* __restrict__ qkv, const float* __restrict__ out,
                                                      const float* __restrict__ dout, const float* __restrict__ lse, int T, int hq,
                                                      int hkv, float scale, float* __restrict__ dqkv, float* __restrict__ delta) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
@@ -915,9 +941,7 @@ __global__ void __launch_bounds__(256) k_tattn_bwd_q(const float* __restrict__ q
     accumulate_tile<HD>(kb + (size_t)k0 * rl, rl, n_valid, g, r, ds, dq);
   }
   if (q0 + r >= T) return;
-  float* drow = dqkv + ((size_t)s * T + qi) * rl + (size_t)h * HD;
-#pragma unroll
-  for (int dt = 0; dt < HD / 16; ++dt) *(float4*)(drow + 16 * dt + 4 * g) = make_float4(dq[dt][0], dq[dt][1], dq[dt][2], dq[dt][3]);
+  store_acc<HD>(dqkv + ((size_t)s * T + qi) * rl + (size_t)h * HD, dq, g, 1.0f);
   if (g == 0) delta[stat] = dl;
 }
 
@@ -925,7 +949,7 @@ __global__ void __launch_bounds__(256) k_tattn_bwd_q(const float* __restrict__ q
 // group and the query tiles from its own on, in that fixed order:
 //   p = exp(scale s - lse_q), dV^T += dO^T p, dP = dO V^T, dS = scale p (dP - delta_q), dK^T += Q^T dS.
 template <int HD>
-__global__ void __launch_bounds__(256) k_tattn_bwd_kv(const float* __restrict__ qkv, const float* __restrict__ dout,
+__global__ void __launch_bounds__(256, HD == 64 ? 4 : 1) k_tattn_bwd_kv(const float* __restrict__ qkv, const float* __restrict__ dout,
                                                       const float* __restrict__ lse, const float* __restrict__ delta, int T, int hq,
                                                       int hkv, float scale, float* __restrict__ dqkv) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
@@ -973,11 +997,8 @@ __global__ void __launch_bounds__(256) k_tattn_bwd_kv(const float* __restrict__ 
   }
   if (!key_ok) return;
   float* krow = dqkv + ((size_t)s * T + kj) * rl + qd + (size_t)kvh * HD;
-#pragma unroll
-  for (int dt = 0; dt < HD / 16; ++dt) {
-    *(float4*)(krow + 16 * dt + 4 * g) = make_float4(dk[dt][0], dk[dt][1], dk[dt][2], dk[dt][3]);
-    *(float4*)(krow + kvd + 16 * dt + 4 * g) = make_float4(dv[dt][0], dv[dt][1], dv[dt][2], dv[dt][3]);
-  }
+  store_acc<HD>(krow, dk, g, 1.0f);
+  store_acc<HD>(krow + kvd, dv, g, 1.0f);
 }
 
 template <int HD>
