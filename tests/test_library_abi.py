@@ -75,3 +75,25 @@ def test_bench_refuses_more_than_one_gpu():
 def test_node_glue_imports_without_a_gpu():
     from paper_2509_08721_amd import node
     assert hasattr(node, "Node")
+
+
+def test_boost_token_scales_one_head_row_exactly():
+    """workloads.boost_token (input generation for the stop-token workloads): one LM-head row times 2^k, exactly,
+    in both storage types, tied or not; everything else untouched, the original left alone."""
+    import numpy as np
+    from paper_2509_08721_amd import workloads as W
+    for shape, key in ((W.MINI_BF16, "embed"), (W.MINI_BF16_HD128, "lm_head"), (W.TINY, "embed" if W.TINY.tied_embeddings else "lm_head")):
+        w = W.make_weights(shape, 3, std=0.05)
+        before = np.array(w[key], copy=True)
+        b = W.boost_token(w, shape, 77, 3)
+        assert np.array_equal(w[key], before)                      # a copy, not in place
+        to_f = (lambda a: W.bf16_bits_to_f32(a)) if before.dtype == np.uint16 else (lambda a: a.astype(np.float32))
+        assert np.array_equal(to_f(b[key][77]), to_f(before[77]) * np.float32(8.0))
+        rest = np.ones(before.shape[0], dtype=bool)
+        rest[77] = False
+        assert np.array_equal(b[key][rest], before[rest])
+        for other in ("embed", "lm_head", "final_norm"):
+            if other != key and w.get(other) is not None:
+                assert b[other] is w[other]
+    wl = W.WORKLOADS["onehalfb_stop"]
+    assert 0 <= wl.stop_token < wl.shape.vocab and wl.stop_boost > 0 and wl.n_seqs == 256
