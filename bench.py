@@ -7,7 +7,7 @@ completions) followed by the scoring pass over the generated batch (sapo_score_l
 teacher-forced log-probs on the completion positions + group-relative advantages).
 The default workload is one node-round of the paper's experiment (8 questions x 8
 completions, Sec. 4.1 / Sec. 5) on the 0.5B-class decoder with synthetic weights and prompts.
-Other workloads (--workload): halfb_long (rollout only, long generation), halfb_score_mixed
+Other workloads (--workload): halfb_round (one whole round of Algorithm 1 for one node), halfb_long (rollout only, long generation), halfb_score_mixed
 (scoring only, half local / half external rollouts; the batch is prepared untimed), onehalfb
 (1.5B-class decoder, rollout + scoring), tiny, halfb_pass1 (one sequence: the latency of a
 decode step at batch 1), halfb_update / onehalfb_update (the local policy update on configuration 2's / 5's training set:
@@ -185,6 +185,70 @@ def bench_stop(args, wl):
     print(json.dumps(out))
 
 
+def bench_round(args, wl):
+    """One node's round of Algorithm 1, every step in the library: rollouts -> (rewards: an input) -> training set of
+    own and swarm datapoints -> scoring -> policy update -> updated policy in place.  The swarm's rollouts are
+    generated beforehand by a second set of weights (they arrive over the network in the paper's setting)."""
+    import torch
+    from paper_2509_08721_amd import sapo, workloads as W
+    from paper_2509_08721_amd.node import Node
+    shape = wl.shape
+    torch.cuda.set_device(0)
+    t0 = time.time()
+    P, G, Lp, N = wl.n_prompts, wl.group, wl.prompt_len, wl.n_new
+    S, T = P * G, Lp + N
+    n_own, n_swarm = P // 2, P // 2
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    torch.cuda.set_stream(side)
+    node = Node(shape, W.make_weights(shape, wl.weight_seed), G, matmul_pieces=args.pieces)
+    other = Node(shape, W.make_weights(shape, wl.external_weight_seed), G)
+    prompts = torch.from_numpy(W.make_prompts(wl)).cuda()
+    ext_prompts = torch.from_numpy(W.make_prompts(replace(wl, prompt_seed=wl.prompt_seed + 1))).cuda()
+    ext_seq, _ = other.rollouts(ext_prompts, N, wl.temperature, wl.rollout_seed + 1000)
+    ext_rew = torch.from_numpy(W.make_rewards(S, wl.reward_p, wl.reward_seed + 1)).cuda()
+    torch.cuda.synchronize()
+    other.close()
+    ws = torch.empty(sapo.sapo_trainer_workspace_bytes(node.trainer, (n_own + n_swarm) * G, T) + 256, dtype=torch.uint8,
+                     device="cuda")
+    setup_s = time.time() - t0
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    rows = []
+    for i in range(args.warmup + args.steps):
+        own_rew = torch.from_numpy(W.make_rewards(S, wl.reward_p, wl.reward_seed + 10 * i)).cuda()   # the reward model's verdicts
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ev[0].record()
+        own_seq, _ = node.rollouts(prompts, N, wl.temperature, wl.rollout_seed + i)
+        ev[1].record()
+        seqs, rew = node.training_set(own_seq, own_rew, ext_seq, ext_rew, n_own, n_swarm, 77 + i)
+        ev[2].record()
+        loss = node.update(seqs, rew, N, workspace=ws)
+        ev[3].record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t1) * 1e3
+        if i >= args.warmup:
+            rows.append((wall, ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2]), ev[2].elapsed_time(ev[3]),
+                         int(seqs.shape[0]), float(loss.cpu()[0])))
+    med = lambda k: float(np.median([r[k] for r in rows]))
+    n_train = int(np.median([r[4] for r in rows]))
+    tokens = S * N + n_train * T
+    out = {"metric": "tokens/s (generated + trained) of one node-round of Algorithm 1 (%s, 1 GPU)" % wl.name,
+           "value": round(tokens / (med(0) * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(med(0), 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": {3: "f32", 2: "bf16x2", 1: "bf16"}[args.pieces] + " update, f16 rollouts and scoring", "data": "synthetic",
+           "config": {"workload": wl.name, "layers": shape.n_layers, "d_model": shape.d_model, "vocab": shape.vocab,
+                      "prompts": P, "completions_per_prompt": G, "prompt_len": Lp, "new_tokens": N,
+                      "own_datapoints": n_own, "swarm_datapoints": n_swarm, "training_sequences": n_train,
+                      "update_matmul_pieces": args.pieces, "rewards": "Bernoulli(%.1f) stand-in for the verifier" % wl.reward_p},
+           "phases_ms": {"rollouts": round(med(1), 3), "training_set": round(med(2), 3),
+                         "scoring + update + new policy in place": round(med(3), 3)},
+           "rounds_per_s": round(1e3 / med(0), 3), "losses": [round(r[5], 6) for r in rows],
+           "roofline": None, "cpu_baseline": None, "setup_s": round(setup_s, 1)}
+    node.close()
+    print(json.dumps(out))
+
+
 def bench_update(args, wl):
     """The local policy update on one training set: trained tokens/s of sapo_policy_update."""
     import torch
@@ -317,6 +381,8 @@ def main():
         return bench_update(args, wl)
     if wl.stop_token >= 0:
         return bench_stop(args, wl)
+    if args.workload.endswith("_round"):
+        return bench_round(args, wl)
     if args.layers > 0:
         wl = replace(wl, shape=replace(wl.shape, n_layers=args.layers))
     if args.new_tokens > 0:

@@ -175,6 +175,12 @@ WORKLOADS: Dict[str, Workload] = {
     "onehalfb_stop": Workload("onehalfb_stop", ONE_HALF_B, weight_seed=501, n_prompts=32, group=8, prompt_len=256,
                               n_new=512, temperature=1.0, prompt_seed=502, rollout_seed=503, stop_token=1000,
                               stop_boost=4),
+    # not one of the five: one whole round of Algorithm 1 for one node on configuration 2's shapes - rollouts for 8
+    # questions, a training set of 4 own + 4 swarm datapoints (the best mix of Sec. 5), scoring, the policy update,
+    # the updated policy in place for the next round
+    "halfb_round": Workload("halfb_round", HALF_B, weight_seed=201, n_prompts=8, group=8, prompt_len=128, n_new=256,
+                            temperature=1.0, prompt_seed=202, rollout_seed=203, score_seqs=64, score_len=384,
+                            score_masked=256, reward_p=0.3, reward_seed=204, external_weight_seed=211),
     "halfb_pass1": Workload("halfb_pass1", HALF_B, weight_seed=201, n_prompts=1, group=1,
                             prompt_len=128, n_new=256, temperature=1.0, prompt_seed=602,
                             rollout_seed=603),
