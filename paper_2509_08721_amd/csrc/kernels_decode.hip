@@ -875,7 +875,12 @@ static hipError_t launch_decode_attention(const float* qkv, const float2* rope, 
 hipError_t d_decode_attention(const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* out, int S, int n_q_heads,
                               hipStream_t st) {
   if (kv.head_dim == 64) return launch_decode_attention<64, 8, 3>(qkv, rope, rm, kv, out, S, n_q_heads, st);
-  if (kv.head_dim == 128) return launch_decode_attention<128, 8, 2>(qkv, rope, rm, kv, out, S, n_q_heads, st);
+  if (kv.head_dim == 128) {
+    // more workgroups than compute units: 4-wave workgroups with one page pair in flight per wave leave room for
+    // two per compute unit, so the whole grid is resident at once (1.5B, 256 sequences: 24.7 us against 29.8)
+    if (S * kv.n_kv_heads > 256) return launch_decode_attention<128, 4, 1>(qkv, rope, rm, kv, out, S, n_q_heads, st);
+    return launch_decode_attention<128, 8, 2>(qkv, rope, rm, kv, out, S, n_q_heads, st);
+  }
   return hipErrorInvalidValue;
 }
 

@@ -62,6 +62,7 @@ def check_rollout(sapo, shape, w, gw, P, G, Lp, N, temp, seed, max_flip_frac=0.0
     ("MINI_BF16_HD128", 2, 3, 17, 30, 1.0),  # head_dim 128, 6 query heads on one KV head, untied LM head
     ("MINI_BF16", 9, 8, 16, 6, 1.0),         # 72 sequences: many-row decode path
     ("MINI_BF16", 2, 2, 5, 9, 0.0),          # greedy
+    ("MINI_BF16_HD128", 33, 8, 17, 20, 1.0), # 264 sequences on one KV head: more attention workgroups than compute units
     ("MINI_BF16", 1, 1, 24, 40, 1.0),        # one question, one completion (the pass@1 judge's shape)
 ])
 def test_mfma_rollout(sapo, shape_name, P, G, Lp, N, temp):
