@@ -309,11 +309,16 @@ hipError_t d_gemm_skinny(const SkinnyArgs& a, int mode, hipStream_t st) {
     if (per_wave <= 4) return launch_skinny<4, 4, 4, SKM_SWIGLU>(a, st);
     return launch_skinny<2, 4, 6, SKM_SWIGLU>(a, st);
   }
+  // several token blocks and a narrow output: 4 x 4 blocking would leave compute units idle (1.5B QKV at 256 rows:
+  // 128 workgroups of 393 KB); two tiles per workgroup double the workgroups at 295 KB each
+  const bool few = multi && tiles % 4 == 0 && (tiles / 4) * ((a.n_rows + 63) / 64) < 192;
   if (mode == SKM_STORE) {
+    if (few) return launch_skinny<2, 4, 3, SKM_STORE>(a, st);
     if (multi && tiles % 4 == 0) return launch_skinny<4, 4, 3, SKM_STORE>(a, st);
     if (per_wave <= 4) return launch_skinny<1, 1, 4, SKM_STORE>(a, st);
     return launch_skinny<1, 1, 8, SKM_STORE>(a, st);
   }
+  if (few && per_wave <= 8) return launch_skinny<2, 4, 3, SKM_RESID>(a, st);
   if (multi && per_wave <= 8 && tiles % 4 == 0) return launch_skinny<4, 4, 3, SKM_RESID>(a, st);
   if (multi && tiles % 2 == 0) return launch_skinny<2, 2, 9, SKM_RESID>(a, st);
   if (per_wave <= 4) return launch_skinny<1, 1, 4, SKM_RESID>(a, st);
