@@ -36,6 +36,11 @@
  *     threads after that.
  *   - A rollout call on a non-default stream replays one captured decode step (HIP graph);
  *     the calls with a stop token additionally synchronise the stream every 32 steps.
+ *   - Environment (read when a handle is created / at every rollout call; for measurements and tests):
+ *       SAPO_FORCE_GENERIC=1  a new sapo_weights handle uses the shape-generic kernels even for shapes the
+ *                             matrix-core kernels accept
+ *       SAPO_NO_GRAPH=1       rollout calls launch every decode step eagerly instead of replaying a graph
+ *       SAPO_NO_COMPACT=1     rollout calls with a stop token keep ended sequences in the decode batch
  */
 #ifndef SAPO_H
 #define SAPO_H
