@@ -177,3 +177,39 @@ def test_config5_1p5b_rollout_and_scoring(sapo):
     err = float(np.max(np.abs(lp[[130]] - o_lp)))
     print("config 5 scoring: 512 log-probs checked, max |dlogp| %.4f" % err)
     assert err <= LOGPROB_TOL
+
+
+def test_config5_stop_token_ended_sequences_leave_the_batch(sapo):
+    """Configuration 5's 256 sequences with a stop token (the `onehalfb_stop` workload: lengths from 1 to 512): once
+    the running sequences fit 64 rows the decode step goes on with 64 rows.  A sequence that runs to the end has
+    then been through both batch sizes; its tokens and log-probs are checked against the oracle before and after
+    the switch, as are those of a sequence that stopped early."""
+    import torch
+    wl = W.WORKLOADS["onehalfb_stop"]
+    w = W.boost_token(W.make_weights(wl.shape, wl.weight_seed), wl.shape, wl.stop_token, wl.stop_boost)
+    gw = sapo.sapo_weights_create(wl.shape, w)
+    assert gw.uses_mfma
+    prompts = W.make_prompts(wl)
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        toks, lps, lens = sapo.sapo_rollout_generate_stop(gw, dev(prompts), wl.group, wl.n_new, wl.temperature, wl.rollout_seed,
+                                                          wl.stop_token, stream=side)
+        side.synchronize()
+    stats = sapo.sapo_rollout_last_stats(gw)
+    toks, lps, lens = toks.cpu().numpy(), lps.cpu().numpy(), lens.cpu().numpy()
+    assert stats["compactions"] >= 1 and stats["rows"] == 64, stats
+    assert (lens == wl.n_new).sum() >= 4 and (lens < 32).sum() >= 32
+    for s in range(256):
+        k = int(lens[s])
+        assert (toks[s, k:] == wl.stop_token).all() and not lps[s, k:].any() and not (toks[s, :k - 1] == wl.stop_token).any()
+    s_long = int(np.nonzero(lens == wl.n_new)[0][0])
+    mid = np.nonzero((lens > 40) & (lens < 200))[0]
+    s_mid = int(mid[0]) if mid.size else int(np.argsort(lens)[128])
+    seq_steps = {s_long: [0, 20, 150, 400, wl.n_new - 1], s_mid: [0, int(lens[s_mid]) // 2, int(lens[s_mid]) - 1]}
+    res = check_rollout_steps(O.Model(wl.shape, w), prompts, wl.group, toks, lps, wl.temperature, wl.rollout_seed, seq_steps,
+                              band(wl.temperature))
+    print("config 5 with a stop token: %s; %d steps checked, %d exact, %d near-ties, max |dlogp| %.4f"
+          % (stats, res["n"], res["exact"], len(res["near"]), res["max_lp_err"]))
+    assert_rollout(res, toks.size)
+    gw.close()
