@@ -92,6 +92,14 @@ typedef struct sapo_weights sapo_weights; /* opaque, library-owned */
 int sapo_weights_create(const sapo_model_config* cfg, const void* const* tensors, int n_tensors,
                         void* stream, sapo_weights** out);
 void sapo_weights_destroy(sapo_weights* w);
+/*
+ * New values for an existing handle (Algorithm 1: the updated policy replaces pi^n for the next round).
+ * `tensors` as for sapo_weights_create with the handle's own configuration.  The handle's buffers are
+ * refilled in place on `stream` - nothing is allocated, and the decode step captured by an earlier
+ * rollout call stays valid - so no call that uses the handle may overlap with this one.  Biases set
+ * with sapo_weights_set_qkv_bias keep their values until set again.
+ */
+int sapo_weights_update(sapo_weights* w, const void* const* tensors, int n_tensors, void* stream);
 
 /*
  * Optional biases on the query / key / value projections of one layer (the decoder family the

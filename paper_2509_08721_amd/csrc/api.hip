@@ -106,29 +106,29 @@ extern "C" int sapo_profile_stop(double* total_ms, int64_t* launches, int n) {
 // ---------------------------------------------------------------------------------------
 // Row-major (shape-generic kernels) or fragment order (MFMA kernels); see common.h.
 struct LayerWeights {
-  float* attn_norm;
-  float* ffn_norm;
-  void* wqkv;   // [q + 2 kv, d]
+  float* attn_norm = nullptr;
+  float* ffn_norm = nullptr;
+  void* wqkv = nullptr;    // [q + 2 kv, d]
   float* bqkv = nullptr;   // [q + 2 kv] optional biases of the three projections (fp32)
-  void* wo;     // [d, q]
-  void* wgu;    // [2 F, d]: generic: gate rows then up rows; MFMA: 32-row gate/up tiles interleaved
-  void* wdown;  // [d, F]
+  void* wo = nullptr;      // [d, q]
+  void* wgu = nullptr;     // [2 F, d]: generic: gate rows then up rows; MFMA: 32-row gate/up tiles interleaved
+  void* wdown = nullptr;   // [d, F]
   // decode copies in W16 fragment order (MFMA path only)
-  void* wqkv16;
-  void* wo16;
-  void* wgu16;  // 16-row gate / up tiles interleaved
-  void* wdown16;
+  void* wqkv16 = nullptr;
+  void* wo16 = nullptr;
+  void* wgu16 = nullptr;   // 16-row gate / up tiles interleaved
+  void* wdown16 = nullptr;
 };
 
 struct sapo_weights {
   sapo_model_config cfg;
   int elt;                       // bytes per weight element
   bool mfma;
-  void* embed;                   // row-major [V, d]
-  void* lm_head;                 // generic: row-major [V, d] (== embed when tied); MFMA: fragment order
-  void* lm_head16;               // MFMA: W16 fragment order (decode)
-  float* final_norm;
-  float2* rope;                  // [max_seq][hd / 2] (cos, sin)
+  void* embed = nullptr;         // row-major [V, d]
+  void* lm_head = nullptr;       // generic: row-major [V, d] (== embed when tied); MFMA: fragment order
+  void* lm_head16 = nullptr;     // MFMA: W16 fragment order (decode)
+  float* final_norm = nullptr;
+  float2* rope = nullptr;        // [max_seq][hd / 2] (cos, sin)
   std::vector<LayerWeights> layers;
   std::vector<void*> allocs;
   // one captured decode step, replayed max_new - 1 times per rollout call; rebuilt when a call
@@ -206,16 +206,19 @@ extern "C" int sapo_weights_set_qkv_bias(sapo_weights* w, int layer, const float
   const size_t q = (size_t)w->cfg.n_q_heads * w->cfg.head_dim, kv = (size_t)w->cfg.n_kv_heads * w->cfg.head_dim;
   LayerWeights& lw = w->layers[layer];
   int rc;
-  if (!lw.bqkv && (rc = dev_alloc(w, (q + 2 * kv) * sizeof(float), (void**)&lw.bqkv))) return rc;
+  const bool fresh = lw.bqkv == nullptr;
+  if ((rc = dev_alloc(w, (q + 2 * kv) * sizeof(float), (void**)&lw.bqkv))) return rc;
   hipStream_t st = (hipStream_t)stream;
   HIP_CK(hipMemcpyAsync(lw.bqkv, bq, q * sizeof(float), hipMemcpyDeviceToDevice, st));
   HIP_CK(hipMemcpyAsync(lw.bqkv + q, bk, kv * sizeof(float), hipMemcpyDeviceToDevice, st));
   HIP_CK(hipMemcpyAsync(lw.bqkv + q + kv, bv, kv * sizeof(float), hipMemcpyDeviceToDevice, st));
-  drop_decode_graph(w);   // a captured decode step holds the old kernel arguments
+  if (fresh) drop_decode_graph(w);   // a captured decode step holds the old kernel arguments (no bias pointer)
   return SAPO_OK;
 }
 
+// A buffer of the handle: allocated on first use, kept when the handle is filled again (sapo_weights_update)
 static int dev_alloc(sapo_weights* w, size_t bytes, void** out) {
+  if (*out) return SAPO_OK;
   void* p = nullptr;
   hipError_t e = hipMalloc(&p, bytes ? bytes : 256);
   if (e != hipSuccess) return fail(SAPO_EHIP, "hipMalloc(%zu) failed: %s", bytes, hipGetErrorString(e));
@@ -290,6 +293,7 @@ static int create_impl(sapo_weights* w, const void* const* t, hipStream_t st) {
     if ((rc = dev_alloc(w, V * d * e, &w->lm_head))) return rc;
     HIP_CK(copy(w->lm_head, tail[1], V * d * e));
   }
+  if (w->rope) return SAPO_OK;   // a refill: the table depends on the configuration only
   // rotary table in double on the host: angle(pos, i) = pos * theta^(-2 i / hd)
   const int half = c.head_dim / 2;
   std::vector<float2> tab((size_t)c.max_seq * half);
@@ -325,6 +329,17 @@ extern "C" int sapo_weights_create(const sapo_model_config* cfg, const void* con
   }
   *out = w;
   return SAPO_OK;
+}
+
+extern "C" int sapo_weights_update(sapo_weights* w, const void* const* tensors, int n_tensors, void* stream) {
+  if (!w || !tensors) return fail(SAPO_EINVAL, "weights/tensors is NULL");
+  const int expect = 1 + 9 * w->cfg.n_layers + 2;
+  if (n_tensors != expect) return fail(SAPO_EINVAL, "n_tensors = %d, expected %d", n_tensors, expect);
+  for (int i = 0; i < expect; ++i)
+    if (!tensors[i] && !(i == expect - 1 && w->cfg.tied_embeddings)) return fail(SAPO_EINVAL, "tensor %d is NULL", i);
+  // every buffer of the handle exists already: the same walk as at creation only copies and packs, on `stream`,
+  // into the same addresses, so the captured decode steps stay valid and read the new values
+  return create_impl(w, tensors, (hipStream_t)stream);
 }
 
 // ---------------------------------------------------------------------------------------

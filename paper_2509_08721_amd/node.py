@@ -22,13 +22,26 @@ class Node:
         self.trainer = sapo.sapo_trainer_create(shape, weights, lr=lr)
         sapo.sapo_trainer_set_matmul_pieces(self.trainer, matmul_pieces)
         self.rounds = 0
+        self._export_buffers = None
+        self._rollout_buffers = {}
 
     def rollouts(self, prompts, max_new: int, temperature: float, seed: int):
         """prompts int32 [P, Lp] (device).  Returns (sequences int32 [P * G, Lp + max_new]: each prompt followed by
         one of its G completions, log-probs of the completion tokens float32 [P * G, max_new])."""
         torch = sapo._torch()
-        comp, lps = sapo.sapo_rollout_generate(self.policy, prompts, self.group, max_new, temperature, seed)
-        return torch.cat([prompts.repeat_interleave(self.group, dim=0), comp], dim=1).contiguous(), lps
+        # the same workspace and output buffers for every call of a shape: the policy handle then replays the decode
+        # step it captured the first time (sapo_weights_update leaves that capture valid)
+        P, Lp = int(prompts.shape[0]), int(prompts.shape[1])
+        key = (P, Lp, max_new)
+        if key not in self._rollout_buffers:
+            nbytes = sapo.sapo_rollout_workspace_bytes(self.policy, P, Lp, self.group, max_new)
+            self._rollout_buffers[key] = (torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda"),
+                                          torch.empty((P * self.group, max_new), dtype=torch.int32, device="cuda"),
+                                          torch.empty((P * self.group, max_new), dtype=torch.float32, device="cuda"))
+        ws, out_tok, out_lp = self._rollout_buffers[key]
+        comp, lps = sapo.sapo_rollout_generate(self.policy, prompts, self.group, max_new, temperature, seed, workspace=ws,
+                                               out_tokens=out_tok, out_logprobs=out_lp)
+        return torch.cat([prompts.repeat_interleave(self.group, dim=0), comp], dim=1).contiguous(), lps.clone()
 
     def training_set(self, own_sequences, own_rewards, swarm_sequences, swarm_rewards, n_own: int, n_swarm: int, seed: int):
         """I^n datapoints of the node's own and J^n sampled from the swarm's, those with zero advantage discarded
@@ -48,9 +61,9 @@ class Node:
         logp_old, adv = sapo.sapo_score_logprobs(self.policy, sequences, mask, rewards, self.group)
         loss, _ = sapo.sapo_policy_update(self.trainer, sequences, mask, logp_old, adv, self.eps_low, self.eps_high,
                                           want_logp=False, workspace=workspace)
-        new_policy = sapo.sapo_trainer_export_weights(self.trainer)
-        self.policy.close()
-        self.policy = new_policy
+        # the updated masters go into the policy handle in place: no allocation, and the decode step the handle
+        # captured for its rollout calls stays valid
+        self._export_buffers = sapo.sapo_trainer_export_into(self.trainer, self.policy, self._export_buffers)
         self.rounds += 1
         return loss
 

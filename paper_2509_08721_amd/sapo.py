@@ -69,6 +69,8 @@ def load_library() -> C.CDLL:
     lib.sapo_rollout_generate.restype = i32
     lib.sapo_rollout_generate_stop.argtypes = [vp, vp, i32, i32, i32, i32, f32, u64, i32, vp, vp, vp, vp, sz, vp]
     lib.sapo_rollout_generate_stop.restype = i32
+    lib.sapo_weights_update.argtypes = [vp, C.POINTER(vp), i32, vp]
+    lib.sapo_weights_update.restype = i32
     lib.sapo_rollout_last_stats.argtypes = [vp, vp]
     lib.sapo_rollout_last_stats.restype = i32
     lib.sapo_rollout_generate_ragged.argtypes = [vp, vp, vp, i32, i32, i32, i32, f32, u64, i32, vp, vp, vp, vp, sz, vp]
@@ -126,7 +128,7 @@ def load_library() -> C.CDLL:
     return lib
 
 
-EXPORTED = ["sapo_weights_create", "sapo_weights_destroy", "sapo_weights_uses_mfma", "sapo_weights_set_qkv_bias",
+EXPORTED = ["sapo_weights_create", "sapo_weights_update", "sapo_weights_destroy", "sapo_weights_uses_mfma", "sapo_weights_set_qkv_bias",
             "sapo_rollout_workspace_bytes", "sapo_score_workspace_bytes",
             "sapo_debug_logits_workspace_bytes", "sapo_rollout_generate", "sapo_rollout_generate_stop", "sapo_rollout_last_stats",
             "sapo_rollout_generate_ragged",
@@ -219,6 +221,22 @@ def sapo_weights_create(shape, weights: dict, stream=None) -> Weights:
             sapo_weights_set_qkv_bias(wts, l, _to_device(lw["bq"]), _to_device(lw["bk"]), _to_device(lw["bv"]), stream)
     torch.cuda.synchronize()          # the originals in `dev` may be freed after this
     return wts
+
+
+def sapo_weights_update(w: Weights, weights: dict, stream=None):
+    """New values (a dict as for sapo_weights_create, same shapes) into an existing handle, in place."""
+    torch = _torch()
+    order: List[Optional[np.ndarray]] = [weights["embed"]]
+    for lw in weights["layers"]:
+        order += [lw[k] for k in ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")]
+    order += [weights["final_norm"], weights.get("lm_head")]
+    dev = [None if a is None else _to_device(a) for a in order]
+    ptrs = (C.c_void_p * len(dev))(*[None if t is None else t.data_ptr() for t in dev])
+    _check(load_library().sapo_weights_update(w.handle, ptrs, len(dev), _stream_ptr(stream)))
+    for l, lw in enumerate(weights["layers"]):
+        if "bq" in lw:
+            sapo_weights_set_qkv_bias(w, l, _to_device(lw["bq"]), _to_device(lw["bk"]), _to_device(lw["bv"]), stream)
+    torch.cuda.synchronize()          # the originals in `dev` may be freed after this
 
 
 def sapo_weights_set_qkv_bias(w: Weights, layer: int, bq, bk, bv, stream=None):
@@ -630,6 +648,29 @@ def sapo_trainer_export_weights(tr: Trainer, stream=None) -> Weights:
             sapo_weights_set_qkv_bias(w, l, bq, bk, bv, stream)
     torch.cuda.synchronize()          # `dev` may be freed after this
     return w
+
+
+def sapo_trainer_export_into(tr: Trainer, w: Weights, buffers=None, stream=None):
+    """The trainer's masters into an existing policy handle of the same configuration, in place
+    (sapo_trainer_export into device buffers, then sapo_weights_update; biases through
+    sapo_weights_set_qkv_bias).  `buffers`: the list this call returned earlier, to reuse its device tensors.
+    Returns the buffers."""
+    torch = _torch()
+    lib = load_library()
+    bf16 = tr.cfg.dtype == SAPO_DTYPE_BF16
+    if buffers is None:
+        buffers = [torch.empty(shp, dtype=torch.float32 if (gain or not bf16) else torch.bfloat16, device="cuda")
+                   for shp, gain in tr.tensor_shapes[:tr.n_in]]
+    ptrs = (C.c_void_p * len(buffers))(*[t.data_ptr() for t in buffers])
+    _check(lib.sapo_trainer_export(tr.handle, ptrs, len(buffers), _stream_ptr(stream)))
+    full = list(buffers) + ([None] if tr.cfg.tied_embeddings else [])
+    wptrs = (C.c_void_p * len(full))(*[None if t is None else t.data_ptr() for t in full])
+    _check(lib.sapo_weights_update(w.handle, wptrs, len(full), _stream_ptr(stream)))
+    if tr.has_bias:
+        for l in range(tr.cfg.n_layers):
+            bq, bk, bv = sapo_trainer_get_qkv_bias(tr, l, stream)
+            sapo_weights_set_qkv_bias(w, l, bq, bk, bv, stream)
+    return buffers
 
 
 def sapo_debug_logits(w: Weights, tokens, positions: Sequence[Sequence[int]], stream=None):

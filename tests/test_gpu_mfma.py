@@ -184,3 +184,46 @@ def test_graph_replay_matches_eager_launches(sapo, shape_name, P, G):
         t2, l2 = sapo.sapo_rollout_generate(gw, prompts, G, N, 1.0, 1, stream=side)
         side.synchronize()
         assert np.array_equal(t2.cpu().numpy(), eager[(1, 1.0)][0])
+
+
+def test_weights_update_in_place_keeps_the_captured_step(sapo):
+    """sapo_weights_update: new values into the handle's own buffers.  A rollout call with the same workspace and
+    output buffers as before then replays the decode step captured under the old values and must return what a
+    handle created from the new values returns, byte for byte; scoring likewise."""
+    import torch
+    shape = W.MINI_BF16
+    wa, gw = make(sapo, shape, 61)
+    wb = W.perturb_norm_gains(W.make_weights(shape, 62, std=0.05), 62)
+    P, G, Lp, N = 3, 4, 21, 40
+    prompts = dev(np.random.default_rng(5).integers(0, shape.vocab, size=(P, Lp)).astype(np.int32))
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        ws = torch.empty(sapo.sapo_rollout_workspace_bytes(gw, P, Lp, G, N) + 256, dtype=torch.uint8, device="cuda")
+        ot = torch.empty((P * G, N), dtype=torch.int32, device="cuda")
+        ol = torch.empty((P * G, N), dtype=torch.float32, device="cuda")
+        sapo.sapo_rollout_generate(gw, prompts, G, N, 1.0, 7, workspace=ws, out_tokens=ot, out_logprobs=ol, stream=side)
+        side.synchronize()
+        ta = ot.cpu().numpy().copy()
+        sapo.sapo_weights_update(gw, wb, stream=side)
+        sapo.sapo_rollout_generate(gw, prompts, G, N, 1.0, 7, workspace=ws, out_tokens=ot, out_logprobs=ol, stream=side)
+        side.synchronize()
+        tb, lb = ot.cpu().numpy().copy(), ol.cpu().numpy().copy()
+        fresh = sapo.sapo_weights_create(shape, wb)
+        tf, lf = sapo.sapo_rollout_generate(fresh, prompts, G, N, 1.0, 7, stream=side)
+        side.synchronize()
+    assert not np.array_equal(ta, tb)
+    assert np.array_equal(tb, tf.cpu().numpy()) and np.array_equal(lb.view(np.uint32), lf.cpu().numpy().view(np.uint32))
+    seqs = dev(np.concatenate([np.repeat(prompts.cpu().numpy(), G, axis=0), tb], axis=1).astype(np.int32))
+    mask, rew = dev(W.make_completion_mask(P * G, Lp + N, N)), dev(W.make_rewards(P * G, 0.5, 3))
+    l1, _ = sapo.sapo_score_logprobs(gw, seqs, mask, rew, G)
+    l2, _ = sapo.sapo_score_logprobs(fresh, seqs, mask, rew, G)
+    assert np.array_equal(l1.cpu().numpy().view(np.uint32), l2.cpu().numpy().view(np.uint32))
+    # a list of the wrong length is refused and changes nothing
+    lib = sapo.load_library()
+    import ctypes as C
+    bad = (C.c_void_p * 3)()
+    assert lib.sapo_weights_update(gw.handle, bad, 3, None) == sapo.SAPO_EINVAL
+    l3, _ = sapo.sapo_score_logprobs(gw, seqs, mask, rew, G)
+    assert np.array_equal(l1.cpu().numpy().view(np.uint32), l3.cpu().numpy().view(np.uint32))
+    gw.close(); fresh.close()

@@ -102,18 +102,32 @@ def test_one_round_of_algorithm_1(sapo):
     gw.close(); gw2.close(); tr.close()
 
 
-def test_node_rounds(sapo):
-    """Two rounds through paper_2509_08721_amd.node.Node (the same calls, packaged): the policy handle is replaced by
-    the trainer's export each round, and what it scores is what the oracle scores for the exported masters."""
+@pytest.mark.parametrize("shape_name,tol,std", [("TINY", 1e-4, 0.2), ("MINI_BF16", 2e-2, 0.05)])
+def test_node_rounds(sapo, shape_name, tol, std):
+    """Two rounds through paper_2509_08721_amd.node.Node (the same calls, packaged), on a stream of its own so that
+    the decode step is replayed from a capture: the policy handle is refilled in place with the trainer's export each
+    round, what it scores is what the oracle scores for the exported masters, and its next rollouts (replaying the
+    step captured before the update) are those of a fresh handle."""
+    import torch
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    torch.cuda.set_stream(side)
+    try:
+        node_rounds(sapo, getattr(W, shape_name), tol, std)
+    finally:
+        torch.cuda.synchronize()
+        torch.cuda.set_stream(torch.cuda.default_stream())
+
+
+def node_rounds(sapo, shape, tol, std):
     import torch
     from oracle import sapo_oracle as O
     from paper_2509_08721_amd.node import Node
-    shape = W.TINY
     P, G, Lp, N = 4, 4, 8, 10
     rng = np.random.default_rng(91)
     prompts = dev(rng.integers(0, shape.vocab, size=(P, Lp)).astype(np.int32))
-    node = Node(shape, W.add_qkv_bias(W.make_weights(shape, 41, std=0.2), shape, 41, std=0.1), G)
-    other = Node(shape, W.make_weights(shape, 42, std=0.2), G)
+    node = Node(shape, W.add_qkv_bias(W.make_weights(shape, 41, std=std), shape, 41, std=0.1), G)
+    other = Node(shape, W.make_weights(shape, 42, std=std), G)
     losses = []
     for rnd in range(2):
         own, _ = node.rollouts(prompts, N, 1.0, 100 + rnd)
@@ -130,5 +144,14 @@ def test_node_rounds(sapo):
     mask = W.make_completion_mask(int(seqs.shape[0]), Lp + N, N)
     lp, _ = sapo.sapo_score_logprobs(node.policy, seqs, dev(mask), rew, G)
     ref = O.score_logprobs(O.Model(shape, exported), seqs.cpu().numpy(), mask)
-    assert np.max(np.abs(lp.cpu().numpy() - ref)) < 1e-4
+    assert np.max(np.abs(lp.cpu().numpy() - ref)) < tol
+    # the handle was refilled in place: its next rollouts (same buffers as the rounds before) are those of a handle
+    # made from the exported masters
+    fresh = sapo.sapo_weights_create(shape, exported)
+    t_new, l_new = sapo.sapo_rollout_generate(fresh, prompts, G, N, 1.0, 300)
+    own, l_own = node.rollouts(prompts, N, 1.0, 300)
+    torch.cuda.synchronize()
+    assert np.array_equal(own[:, Lp:].cpu().numpy(), t_new.cpu().numpy())
+    assert np.array_equal(l_own.cpu().numpy().view(np.uint32), l_new.cpu().numpy().view(np.uint32))
+    fresh.close()
     node.close(); other.close()
