@@ -461,6 +461,7 @@ inline size_t x3_pack_bytes(int NP, size_t rows, size_t K) {
   return ((rows + 127) / 128 * 128) * ((K + 15) / 16 * 16) * 2 * NP;
 }
 struct X3Bufs { void* a; void* b; size_t a_cap, b_cap; int NP; float* parts; size_t parts_cap; };
+constexpr int kMaxSplits = 16;
 __global__ void k_sum_parts(const float* __restrict__ part, int n_part, size_t n, float beta, float* __restrict__ out);
 
 hipError_t x3_pack(const X3Op& op, void* dst, size_t cap, int NP, hipStream_t st) {
@@ -488,13 +489,21 @@ hipError_t gemm_x3(const X3Op& A, const X3Op& B, float* C, int ldc, float beta, 
   const int RB = (gnx >= 32 && (long)gnx * ((gny + 1) / 2) >= 512) ? 2 : 1;
   const int gty = (gny + RB - 1) / RB;
   dim3 grid(raster_grid(gnx, gty), 1);
-  // an output with few tiles and a long contraction (weight gradients of the narrow projections): the k steps
-  // are split into parts, each part writes its own product and k_sum_parts adds them in part order
+  // A long contraction whose output tiles do not fill the workgroups in flight (weight gradients: 49 .. 532 tiles
+  // against 768 resident workgroups, or a last round that is mostly empty): the k steps are split into parts, each
+  // part writes its own product and k_sum_parts adds them in part order.  The number of parts is the one whose
+  // rounds of resident workgroups are fullest; more parts must buy at least 4 % (they cost a pass over the output).
   const long tiles = (long)gnx * gty;
   int splits = 1;
   if (split_ok && ldc == B.rows) {
-    while (splits < 8 && tiles * splits * 2 <= 768 && KB / (splits * 2) >= 16) splits *= 2;   // 768 = workgroups in flight
-    if ((size_t)splits * A.rows * B.rows > bufs.parts_cap) splits = 1;
+    const long slots = RB == 2 ? 512 : 768;
+    double best = 0.0;
+    for (int s_ = 1; s_ <= kMaxSplits; ++s_) {
+      if (s_ > 1 && (KB / s_ < 16 || (size_t)s_ * A.rows * B.rows > bufs.parts_cap)) break;
+      const long units = tiles * s_;
+      const double fill = (double)units / (double)((units + slots - 1) / slots * slots);
+      if (fill > best + 0.04) { best = fill; splits = s_; }
+    }
   }
   const int kbs = (KB + splits - 1) / splits;
   splits = (KB + kbs - 1) / kbs;
@@ -1141,10 +1150,10 @@ struct Arena {
   }
 };
 
-// GEMMs with few output tiles and a long contraction (dW of the attention projections: 49 - 63 tiles of 128 x 128 on
-// 256 compute units; the head's d-input product: 238 tiles, contraction over the vocabulary) are split over the
-// contraction into up to 8 parts that are added in part order.
-constexpr size_t kSplitParts = (size_t)8 * 192 * 128 * 128;
+// GEMMs with a long contraction whose output tiles do not fill the resident workgroups (the weight gradients; the
+// head's d-input product: 238 tiles, contraction over the vocabulary) are split over the contraction into up to
+// kMaxSplits parts that are added in part order; the buffer holds 8 parts of the largest layer matrix.
+inline size_t split_parts_floats(const Dims& D) { return (size_t)8 * std::max((size_t)2 * D.F * D.d, (size_t)192 * 128 * 128); }
 constexpr int kPieces = 3;   // most bf16 pieces per fp32 value in the packed GEMMs (3: fp32 accuracy; buffers are sized for it)
 
 // the fused attention kernels need float4 rows: head dim 16 / 32 / 64 / 128 and row lengths that are multiples of 4
@@ -1209,7 +1218,7 @@ void make_plan(const sapo_model_config& c, size_t S, size_t T, size_t S_total, c
   p.logp_all = A.take<float>(S_total * T);   // log-probs of the whole training set (micro-batches fill their rows)
   p.loss = A.take<float>(4);
   p.n_masked = A.take<long long>(1);
-  p.kparts = A.take<float>(kSplitParts);
+  p.kparts = A.take<float>(split_parts_floats(D));
   // packed GEMM operands: the largest row-side (A) and column-side (B) operand of any GEMM of the update
   {
     const size_t R = p.chunk, twoF = 2 * D.F;
@@ -1436,7 +1445,7 @@ static int update_rows(sapo_trainer* tr, const TrainPlan& p, const int32_t* toke
 
   // The projections and the LM head run on the packed bf16-piece GEMM; forms as in sgemm<TA, TB>.
   const int pieces = tr->pieces;
-  const X3Bufs xb{p.packa, p.packb, p.packa_cap, p.packb_cap, pieces, p.kparts, kSplitParts};
+  const X3Bufs xb{p.packa, p.packb, p.packa_cap, p.packb_cap, pieces, p.kparts, split_parts_floats(D)};
   auto mm_nt = [&](const float* X, int ldx, const float* W, int ldw, float* C, int ldc, int M_, int N_, int K_, float beta,
                    const void* w_packed = nullptr) {   // C = beta C + X W^T
     return gemm_x3(X3Op{X, ldx, M_, K_, false}, X3Op{W, ldw, N_, K_, false}, C, ldc, beta, xb, st, false, nullptr, w_packed);
