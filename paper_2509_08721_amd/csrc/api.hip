@@ -991,14 +991,42 @@ static void plan_score(const sapo_weights* w, int S, int T, int chunk_seqs, size
   pl.bytes = (A.off + 255) & ~(size_t)255;
 }
 
-// Sequences per forward pass of the scoring call: about 32768 tokens (enough tiles to fill the chip even
-// for the narrow projections), the passes balanced so that the last one is not a sliver.
-static int score_chunk_seqs(int S, int T) {
-  int cs = 32768 / T;
-  if (cs < 1) cs = 1;
-  if (cs > S) cs = S;
-  const int n_chunks = (S + cs - 1) / cs;
-  return (S + n_chunks - 1) / n_chunks;
+// Sequences per forward pass of the scoring call.
+// Shape-generic kernels: about 32768 tokens, the passes balanced so that the last one is not a sliver.
+// Token-parallel MFMA kernels: a GEMM runs in rounds of 512 resident workgroups (256 x 128 tiles, two per compute
+// unit), and a round costs the same whether it is full or not; the narrow projections (N = d: 7 feature tiles at
+// 0.5B) have few tiles per token tile, so the pass size decides how full their rounds are.  The size is the one
+// that minimises the summed rounds x contraction length of a layer's four GEMMs over the whole call (for 64 x 768
+// tokens at 0.5B: one pass of 192 token tiles, 3 rounds for the narrow GEMMs, instead of two passes of 2 rounds
+// each), among passes of at most 131072 tokens.
+static int score_chunk_seqs(const sapo_weights* w, int S, int T) {
+  if (!w->mfma) {
+    int cs = 32768 / T;
+    if (cs < 1) cs = 1;
+    if (cs > S) cs = S;
+    const int n_chunks = (S + cs - 1) / cs;
+    return (S + n_chunks - 1) / n_chunks;
+  }
+  const sapo_model_config& c = w->cfg;
+  const long q = (long)c.n_q_heads * c.head_dim, kv = (long)c.n_kv_heads * c.head_dim;
+  const long n_tiles[4] = {(q + 2 * kv) / 128, c.d_model / 128, 2L * c.d_ff / 128, c.d_model / 128};   // QKV, O, gate/up, down
+  const long k_len[4] = {c.d_model, q, c.d_model, c.d_ff};
+  auto pass_cost = [&](long n_seq) {
+    const long r = (n_seq * T + 255) / 256;
+    double cost = 0.0;
+    for (int g = 0; g < 4; ++g) cost += (double)k_len[g] * (double)((r * n_tiles[g] + 511) / 512);
+    return cost;
+  };
+  int cs_max = 131072 / T;
+  if (cs_max < 1) cs_max = 1;
+  if (cs_max > S) cs_max = S;
+  int best_cs = cs_max;
+  double best = -1.0;
+  for (int cs = cs_max; cs >= 1; --cs) {   // from the largest: ties go to fewer passes
+    const double total = (double)(S / cs) * pass_cost(cs) + ((S % cs) ? pass_cost(S % cs) : 0.0);
+    if (best < 0.0 || total < best * (1.0 - 1e-9)) { best = total; best_cs = cs; }
+  }
+  return best_cs;
 }
 
 static int check_score_args(const sapo_weights* w, int S, int T) {
@@ -1012,7 +1040,7 @@ static int check_score_args(const sapo_weights* w, int S, int T) {
 extern "C" size_t sapo_score_workspace_bytes(const sapo_weights* w, int S, int T) {
   if (check_score_args(w, S, T)) return 0;
   ScorePlan pl;
-  plan_score(w, S, T, score_chunk_seqs(S, T), 0, nullptr, pl);
+  plan_score(w, S, T, score_chunk_seqs(w, S, T), 0, nullptr, pl);
   return pl.bytes;
 }
 
@@ -1036,7 +1064,7 @@ static int score_impl(const sapo_weights* w, const int32_t* tokens, const uint8_
     return fail(SAPO_EINVAL, "NULL buffer");
   if (((uintptr_t)workspace & 255) != 0) return fail(SAPO_EINVAL, "workspace must be 256-byte aligned");
   ScorePlan pl;
-  plan_score(w, S, T, score_chunk_seqs(S, T), 0, (char*)workspace, pl);
+  plan_score(w, S, T, score_chunk_seqs(w, S, T), 0, (char*)workspace, pl);
   if (workspace_bytes < pl.bytes) return fail(SAPO_EWORKSPACE, "workspace %zu < required %zu", workspace_bytes, pl.bytes);
   hipStream_t st = (hipStream_t)stream;
   const sapo_model_config& c = w->cfg;
