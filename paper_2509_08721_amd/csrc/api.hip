@@ -451,10 +451,8 @@ static int run_layers_generic(const sapo_weights* w, const FwdBufs& b, int M, Ro
 }
 
 // MFMA, many rows (prefill and scoring)
-static int run_layers_big(const sapo_weights* w, const FwdBufs& b, int M, RowMap rm, const CacheBufs& cb, int max_ctx,
-                          hipStream_t st) {
+static int run_layers_big(const sapo_weights* w, const FwdBufs& b, int M, RowMap rm, const CacheBufs& cb, hipStream_t st) {
   const sapo_model_config& c = w->cfg;
-  const int dt = c.dtype;
   const int d = c.d_model, q = c.n_q_heads * c.head_dim, kv = c.n_kv_heads * c.head_dim, F = c.d_ff;
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerWeights& lw = w->layers[l];
@@ -590,7 +588,7 @@ static int run_layers_decode16(const sapo_weights* w, const FwdBufs& b, const De
 static int run_layers(const sapo_weights* w, const FwdBufs& b, int M, RowMap rm, const CacheBufs& cb, int max_ctx,
                       hipStream_t st) {
   if (!w->mfma) return run_layers_generic(w, b, M, rm, cb, max_ctx, st);
-  return run_layers_big(w, b, M, rm, cb, max_ctx, st);
+  return run_layers_big(w, b, M, rm, cb, st);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1048,7 +1046,7 @@ extern "C" size_t sapo_score_workspace_bytes(const sapo_weights* w, int S, int T
 static int forward_chunk(const sapo_weights* w, const ScorePlan& pl, const int32_t* tokens, int s0, int ns, hipStream_t st) {
   const sapo_model_config& c = w->cfg;
   const int M = ns * pl.T;
-  RowMap rm{0, pl.T, 1, 0, nullptr};
+  RowMap rm{0, pl.T, 1, 0, nullptr, nullptr, 1};
   HIP_CK(g_embed(c.dtype, tokens + (size_t)s0 * pl.T, 1, nullptr, w->embed, pl.fwd.h, M, c.d_model, st));
   return run_layers(w, pl.fwd, M, rm, pl.cache, pl.T, st);
 }

@@ -312,7 +312,7 @@ __device__ __forceinline__ void x3_store(uint4* __restrict__ dst, int NP, int KB
 }
 // src[row * ld + k]: one workgroup per (block of 128 rows, 8 k steps); thread (row, k half) reads 8 consecutive
 // k per step, so a row is read in 64-byte runs and every piece of a step goes out as two 2 KB runs
-__global__ void __launch_bounds__(256) k_pack_x3(const float* __restrict__ src, int ld, int rows, int K, int rows_pad, int KB,
+__global__ void __launch_bounds__(256) k_pack_x3(const float* __restrict__ src, int ld, int rows, int K, int /*rows_pad*/, int KB,
                                                  int NP, uint4* __restrict__ dst) {
   const int row = blockIdx.x * 128 + (threadIdx.x >> 1), kh = threadIdx.x & 1;
   const float* rp = src + (size_t)row * ld;
