@@ -312,15 +312,21 @@ hipError_t d_gemm_skinny(const SkinnyArgs& a, int mode, hipStream_t st) {
   // several token blocks and a narrow output: 4 x 4 blocking would leave compute units idle (1.5B QKV at 256 rows:
   // 128 workgroups of 393 KB); two tiles per workgroup double the workgroups at 295 KB each
   const bool few = multi && tiles % 4 == 0 && (tiles / 4) * ((a.n_rows + 63) / 64) < 192;
+  // one token block, more 16-token workgroups than compute units (0.5B QKV: 72 tiles x 4 = 288): some compute
+  // units would get two workgroups and ingest twice; 32-token workgroups (144 of them, 86 KB each) keep it one each
+  const bool tg2 = !multi && tiles * 4 > 256;
   if (mode == SKM_STORE) {
     if (few) return launch_skinny<2, 4, 3, SKM_STORE>(a, st);
     if (multi && tiles % 4 == 0) return launch_skinny<4, 4, 3, SKM_STORE>(a, st);
+    if (tg2) return per_wave <= 4 ? launch_skinny<1, 2, 4, SKM_STORE>(a, st) : launch_skinny<1, 2, 8, SKM_STORE>(a, st);
     if (per_wave <= 4) return launch_skinny<1, 1, 4, SKM_STORE>(a, st);
     return launch_skinny<1, 1, 8, SKM_STORE>(a, st);
   }
   if (few && per_wave <= 8) return launch_skinny<2, 4, 3, SKM_RESID>(a, st);
   if (multi && per_wave <= 8 && tiles % 4 == 0) return launch_skinny<4, 4, 3, SKM_RESID>(a, st);
   if (multi && tiles % 2 == 0) return launch_skinny<2, 2, 9, SKM_RESID>(a, st);
+  if (tg2 && per_wave <= 4) return launch_skinny<1, 2, 4, SKM_RESID>(a, st);
+  if (tg2 && per_wave <= 8) return launch_skinny<1, 2, 8, SKM_RESID>(a, st);
   if (per_wave <= 4) return launch_skinny<1, 1, 4, SKM_RESID>(a, st);
   if (per_wave <= 8) return launch_skinny<1, 1, 8, SKM_RESID>(a, st);
   return launch_skinny<1, 1, 20, SKM_RESID>(a, st);
