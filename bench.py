@@ -89,14 +89,14 @@ def per_launch_work(shape, plan, kernel, launches):
 FP32_MFMA_PEAK_TFLOPS = 157.3
 
 
-def update_flops(shape, S, T, n_chunks_rows):
-    """(GEMM flops, attention flops) of one policy update: every projection and the LM head three times
-    (forward, d input, d weight); attention's seven products (scores twice, P V, dP, dQ, dK, dV) over the causal
-    half of T x T."""
+def update_flops(shape, S, T, Tm):
+    """(GEMM flops, attention flops) of one policy update: every projection three times (forward, d input, d weight),
+    the LM head three times on the rows that predict a masked token (Tm per sequence); attention's seven products
+    (scores twice, P V, dP, dQ, dK, dV) over the causal half of T x T."""
     M = S * T
     per_layer = shape.matmul_params_per_layer()
     proj = 2 * M * 3 * per_layer * shape.n_layers
-    head = 2 * M * 3 * shape.vocab * shape.d_model
+    head = 2 * S * Tm * 3 * shape.vocab * shape.d_model
     attn = 2 * 7 * S * shape.n_q_heads * (T * (T + 1) // 2) * shape.head_dim * shape.n_layers
     return proj + head, attn
 
@@ -292,7 +292,7 @@ def bench_update(args, wl):
         losses.append(loss)
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t1) / args.steps
-    flops, attn_flops = update_flops(shape, S, T, 0)
+    flops, attn_flops = update_flops(shape, S, T, Tm)
     kernels, roofline = {}, None
     if not args.no_kernel_profile:
         sapo.sapo_profile_start()

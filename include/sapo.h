@@ -316,8 +316,10 @@ size_t sapo_trainer_workspace_bytes_for(const sapo_trainer* tr, int S, int T, in
  *                    additions.  SAPO_EWORKSPACE if not even one sequence fits.
  * fp32 values throughout (the large matrix products are formed from bf16 pieces on the matrix cores
  * with the accuracy of fp32 products), every sum in a fixed order (no atomics): the same call on the
- * same state gives the same bits.  Asynchronous on `stream`; the trainer's state is updated in place, so
- * calls on one trainer must not overlap.  Errors: SAPO_EINVAL (NULL, sizes, eps), SAPO_EWORKSPACE.
+ * same state gives the same bits.  The LM head runs only on the rows that predict a masked token; the host
+ * sizes its products from their number, so the call waits once, at its start, for a small kernel that lists
+ * them (and for whatever `stream` held before); everything else is enqueued and the call returns before the
+ * update has finished.  The trainer's state is updated in place, so calls on one trainer must not overlap.  Errors: SAPO_EINVAL (NULL, sizes, eps), SAPO_EWORKSPACE.
  */
 int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const uint8_t* completion_mask,
                        const float* logp_old, const float* advantages, int S, int T, float eps_low,

@@ -666,16 +666,18 @@ __global__ void __launch_bounds__(256) k_count_mask(const uint8_t* __restrict__ 
     *out = t;
   }
 }
-__global__ void __launch_bounds__(256) k_logp_dlogits(float* __restrict__ logits, int V, int r0, int T,
+// Row k of `logits` belongs to row r = rows[k] of the batch (position r % T of sequence r / T), which predicts the
+// masked token at r + 1 (the list holds exactly those rows).  In place: logits -> d loss / d logits.
+__global__ void __launch_bounds__(256) k_logp_dlogits(float* __restrict__ logits, int V, const int* __restrict__ rows, int T,
                                                       const int32_t* __restrict__ tokens, const uint8_t* __restrict__ mask,
                                                       const float* __restrict__ logp_old, const float* __restrict__ adv,
                                                       float eps_low, float eps_high, const long long* __restrict__ n_masked,
                                                       float* __restrict__ logp_new) {
   __shared__ float red[4];
-  const int r = r0 + blockIdx.x;
+  const int r = rows[blockIdx.x];
   const int t = r % T;
   float* z = logits + (size_t)blockIdx.x * V;
-  if (t == T - 1 || !mask[r + 1]) {   // uniform over the workgroup
+  if (t == T - 1 || !mask[r + 1]) {   // not in a well-formed list; uniform over the workgroup
     for (int v = threadIdx.x; v < V; v += 256) z[v] = 0.f;
     return;
   }
@@ -697,6 +699,14 @@ __global__ void __launch_bounds__(256) k_logp_dlogits(float* __restrict__ logits
   for (int v = threadIdx.x; v < V; v += 256) z[v] = (w == 0.f) ? 0.f : w * ((v == target ? 1.f : 0.f) - expf(z[v] - l));
 }
 
+// dst[k] = src[rows[k]] (gather) or dst[rows[k]] = src[k] (scatter): rows of d floats, one workgroup per listed row
+__global__ void __launch_bounds__(256) k_move_rows(const float* __restrict__ src, const int* __restrict__ rows, int d, int scatter,
+                                                   float* __restrict__ dst) {
+  const size_t k = blockIdx.x, r = (size_t)rows[blockIdx.x];
+  const float* a = src + (scatter ? k : r) * d;
+  float* b = dst + (scatter ? r : k) * d;
+  for (int i = threadIdx.x; i < d; i += 256) b[i] = a[i];
+}
 // out = (beta ? out : 0) + sum over the parts, in part order
 __global__ void k_sum_parts(const float* __restrict__ part, int n_part, size_t n, float beta, float* __restrict__ out) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -1168,6 +1178,8 @@ struct LayerActs {
 struct TrainPlan {
   std::vector<LayerActs> layer;
   float *h_last, *rf, *xf;                      // final residual rows, their rstd, final-normed rows
+  float* xfc;                                   // the final-normed rows that predict a masked token, gathered
+  int *mrows, *mpos, *mcount;                   // per micro-batch: those rows' indices (mpos: their (s, t)), their number
   float *dh, *dx, *dact, *dgu, *dao, *dqkv;     // backward temporaries
   float *delta, *prob, *dsc, *gpart, *logits, *logp_all, *loss;
   void* sur_ws;
@@ -1201,6 +1213,10 @@ void make_plan(const sapo_model_config& c, size_t S, size_t T, size_t S_total, c
   p.h_last = A.take<float>(M * D.d);
   p.rf = A.take<float>(M);
   p.xf = A.take<float>(M * D.d);
+  p.xfc = A.take<float>(M * D.d);
+  p.mrows = A.take<int>(S_total * T);
+  p.mpos = A.take<int>(2 * M);
+  p.mcount = A.take<int>((S_total + S - 1) / S);
   p.dh = A.take<float>(M * D.d);
   p.dx = A.take<float>(M * D.d);
   p.dact = A.take<float>(M * D.F);
@@ -1412,7 +1428,7 @@ extern "C" int sapo_trainer_export(const sapo_trainer* tr, void* const* tensors_
 // the LM head is packed (p.head_nt, p.head_t).
 static int update_rows(sapo_trainer* tr, const TrainPlan& p, const int32_t* tokens, const uint8_t* completion_mask,
                        const float* logp_old, const float* advantages, int S_, int T_, float eps_low, float eps_high,
-                       float* logp_new, hipStream_t st) {
+                       float* logp_new, const int* rows, int n_rows, hipStream_t st) {
   const sapo_model_config& c = tr->cfg;
   const Dims D(c);
   const size_t S = S_, T = T_, M = S * T;
@@ -1500,15 +1516,22 @@ static int update_rows(sapo_trainer* tr, const TrainPlan& p, const int32_t* toke
   T_CK(launch(KID_RMSNORM, k_rmsnorm_fwd, dim3(Mi), dim3(256), 0, st, (const float*)p.h_last, (const float*)TH(t_final),
               c.rms_eps, d, p.xf, p.rf));
 
-  // ---- LM head, one pass over chunks of rows: logits, log-probs, d logits, then d xf (into p.dx) and d head
+  // ---- LM head, over the rows that predict a masked token only (the others have no log-prob to report and a zero
+  // d logits row): their final-normed rows gathered, then chunks of them: logits, log-probs, d logits, d rows (into
+  // p.dh, scattered to p.dx afterwards) and d head
   T_CK(g_fill_f32(logp_new, 0.f, M, st));
-  for (size_t r0 = 0; r0 < M; r0 += p.chunk) {
-    const int R = (int)((M - r0 < p.chunk) ? M - r0 : p.chunk);
-    T_CK(mm_nt(p.xf + r0 * D.d, d, TH(t_head), d, p.logits, V, R, V, d, 0.f, p.head_nt));
-    T_CK(launch(KID_SCORE_ROWS, k_logp_dlogits, dim3(R), dim3(256), 0, st, p.logits, V, (int)r0, (int)T, tokens, completion_mask,
-                logp_old, advantages, eps_low, eps_high, (const long long*)p.n_masked, logp_new));
-    T_CK(mm_nn(p.logits, V, TH(t_head), d, p.dx + r0 * D.d, d, R, d, V, 0.f, p.head_t));
-    T_CK(mm_tn(p.logits, V, p.xf + r0 * D.d, d, GR(t_head), V, d, R, 1.f));
+  T_CK(g_fill_f32(p.dx, 0.f, M * D.d, st));
+  if (n_rows > 0) {
+    T_CK(launch(KID_MISC, k_move_rows, dim3(n_rows), dim3(256), 0, st, (const float*)p.xf, rows, d, 0, p.xfc));
+    for (size_t r0 = 0; r0 < (size_t)n_rows; r0 += p.chunk) {
+      const int R = (int)(((size_t)n_rows - r0 < p.chunk) ? (size_t)n_rows - r0 : p.chunk);
+      T_CK(mm_nt(p.xfc + r0 * D.d, d, TH(t_head), d, p.logits, V, R, V, d, 0.f, p.head_nt));
+      T_CK(launch(KID_SCORE_ROWS, k_logp_dlogits, dim3(R), dim3(256), 0, st, p.logits, V, rows + r0, (int)T, tokens, completion_mask,
+                  logp_old, advantages, eps_low, eps_high, (const long long*)p.n_masked, logp_new));
+      T_CK(mm_nn(p.logits, V, TH(t_head), d, p.dh + r0 * D.d, d, R, d, V, 0.f, p.head_t));
+      T_CK(mm_tn(p.logits, V, p.xfc + r0 * D.d, d, GR(t_head), V, d, R, 1.f));
+    }
+    T_CK(launch(KID_MISC, k_move_rows, dim3(n_rows), dim3(256), 0, st, (const float*)p.dh, rows, d, 1, p.dx));
   }
   // ---- backward through the layers
   const int n_gpart = (Mi + 255) / 256;
@@ -1638,10 +1661,24 @@ extern "C" int sapo_policy_update(sapo_trainer* tr, const int32_t* tokens, const
   T_CK(launch(KID_MISC, k_count_mask, dim3(1), dim3(256), 0, st, completion_mask, M, p.n_masked));
   T_CK(x3_pack(X3Op{tr->theta + tr->off[t_head], d, V, d, false}, p.head_nt, p.head_cap, tr->pieces, st));   // rows = vocabulary
   T_CK(x3_pack(X3Op{tr->theta + tr->off[t_head], d, d, V, true}, p.head_t, p.head_t_cap, tr->pieces, st));    // rows = d
-  for (size_t s0 = 0; s0 < S; s0 += S_mb) {
+  // The rows that predict a masked token, per micro-batch (indices within it, ascending), and how many there are:
+  // the host needs the numbers to size the LM head's GEMMs, so the call waits here once, before the forward passes
+  // are enqueued, for these small kernels (and for whatever the stream held before).
+  const size_t n_mb = (S + S_mb - 1) / S_mb;
+  std::vector<int> n_rows(n_mb, 0);
+  for (size_t i = 0; i < n_mb; ++i) {
+    const size_t s0 = i * S_mb;
     const int n = (int)(S - s0 < S_mb ? S - s0 : S_mb);
+    T_CK(g_masked_rows(completion_mask + s0 * T, T_, 0, n, p.mpos, p.mrows + s0 * T, p.mcount + i, st));
+  }
+  T_CK(hipMemcpyAsync(n_rows.data(), p.mcount, n_mb * sizeof(int), hipMemcpyDeviceToHost, st));
+  T_CK(hipStreamSynchronize(st));
+  for (size_t i = 0; i < n_mb; ++i) {
+    const size_t s0 = i * S_mb;
+    const int n = (int)(S - s0 < S_mb ? S - s0 : S_mb);
+    if (n_rows[i] < 0 || (size_t)n_rows[i] > (size_t)n * T) return set_error(SAPO_EHIP, "row count read back from the device is out of range");
     const int rc = update_rows(tr, p, tokens + s0 * T, completion_mask + s0 * T, logp_old + s0 * T, advantages + s0, n, T_,
-                               eps_low, eps_high, p.logp_all + s0 * T, st);
+                               eps_low, eps_high, p.logp_all + s0 * T, p.mrows + s0 * T, n_rows[i], st);
     if (rc != SAPO_OK) return rc;
   }
   // ---- the loss (the surrogate of sapo_clipped_surrogate on the log-probs just computed)
