@@ -624,8 +624,13 @@ def main():
                "sample": "numpy fp64 oracle: " + ", ".join(parts) + "; whole-step rate extrapolated from the slice rates"}
         cpu.update(res)
 
+    # context for the HBM fractions: what a kernel that only reads reaches on this machine (not a denominator)
+    read_probe = None
+    if not (args.layers or args.new_tokens):
+        read_probe = {"GBs": round(sapo.sapo_debug_read_probe(), 1), "bytes": 1 << 31,
+                      "note": "streaming read of 2 GiB, 16-byte non-temporal loads; the roofline fractions use the published 8000 GB/s"}
     out.update({"roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "surrogate_loss": surrogate,
-                "setup_s": round(setup_s, 1)})
+                "hbm_read_probe": read_probe, "setup_s": round(setup_s, 1)})
     print(json.dumps(out))
 
 

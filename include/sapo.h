@@ -364,6 +364,13 @@ int sapo_trainer_steps(const sapo_trainer* tr);
 int sapo_trainer_read(const sapo_trainer* tr, int what, int tensor, float* out, size_t n, void* stream);
 
 /*
+ * Measurement hook: one launch of a kernel that only reads `bytes` bytes at `buf` (dev, 16-byte aligned; 2048
+ * workgroups, 16-byte non-temporal loads): timed by the caller, it gives the streaming read bandwidth a kernel
+ * can reach on the machine, as context for the HBM roofline figures.  sink: dev, 4 bytes (normally left alone).
+ */
+int sapo_debug_read_probe(const void* buf, size_t bytes, void* sink, void* stream);
+
+/*
  * Test hook: the sampler's noise.  out[i] = g for (seed, seq, step, v = v0 + i), i < n.
  * out dev fp32 [n].
  */

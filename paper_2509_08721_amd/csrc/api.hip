@@ -1196,6 +1196,25 @@ extern "C" int sapo_clipped_surrogate(const float* logp_new, const float* logp_o
   return SAPO_OK;
 }
 
+// Measurement hook: a plain streaming read (what a kernel that only reads can reach on this machine).
+namespace {
+typedef unsigned int probe_u32x4 __attribute__((ext_vector_type(4)));
+__global__ void __launch_bounds__(256) k_read_probe(const probe_u32x4* __restrict__ src, size_t n16, unsigned* __restrict__ sink) {
+  unsigned acc = 0;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) {
+    const probe_u32x4 v = __builtin_nontemporal_load(src + i);
+    acc ^= v.x ^ v.y ^ v.z ^ v.w;
+  }
+  if (acc == 0x9e3779b9u) sink[0] = acc;   // keeps the loads alive; practically never taken
+}
+}  // namespace
+extern "C" int sapo_debug_read_probe(const void* buf, size_t bytes, void* sink, void* stream) {
+  if (!buf || !sink || bytes < 16 || ((uintptr_t)buf & 15) != 0) return fail(SAPO_EINVAL, "bad arguments");
+  HIP_CK(sapo::launch(sapo::KID_MISC, k_read_probe, dim3(2048), dim3(256), 0, (hipStream_t)stream, (const probe_u32x4*)buf,
+                      bytes / 16, (unsigned*)sink));
+  return SAPO_OK;
+}
+
 extern "C" int sapo_debug_gumbel(uint64_t seed, uint32_t seq, uint32_t step, uint32_t v0, int n, float* out,
                                  void* stream) {
   if (n < 0 || !out) return fail(SAPO_EINVAL, "bad arguments");

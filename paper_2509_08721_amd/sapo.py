@@ -69,6 +69,8 @@ def load_library() -> C.CDLL:
     lib.sapo_rollout_generate.restype = i32
     lib.sapo_rollout_generate_stop.argtypes = [vp, vp, i32, i32, i32, i32, f32, u64, i32, vp, vp, vp, vp, sz, vp]
     lib.sapo_rollout_generate_stop.restype = i32
+    lib.sapo_debug_read_probe.argtypes = [vp, sz, vp, vp]
+    lib.sapo_debug_read_probe.restype = i32
     lib.sapo_weights_update.argtypes = [vp, C.POINTER(vp), i32, vp]
     lib.sapo_weights_update.restype = i32
     lib.sapo_rollout_last_stats.argtypes = [vp, vp]
@@ -139,7 +141,7 @@ EXPORTED = ["sapo_weights_create", "sapo_weights_update", "sapo_weights_destroy"
             "sapo_policy_update",
             "sapo_trainer_export", "sapo_trainer_steps", "sapo_trainer_read", "sapo_trainer_set_matmul_pieces",
             "sapo_trainer_set_qkv_bias", "sapo_trainer_get_qkv_bias",
-            "sapo_debug_logits", "sapo_debug_gumbel", "sapo_last_error", "sapo_profile_kernel_count",
+            "sapo_debug_logits", "sapo_debug_gumbel", "sapo_debug_read_probe", "sapo_last_error", "sapo_profile_kernel_count",
             "sapo_profile_kernel_name", "sapo_profile_start", "sapo_profile_stop"]
 
 
@@ -671,6 +673,25 @@ def sapo_trainer_export_into(tr: Trainer, w: Weights, buffers=None, stream=None)
             bq, bk, bv = sapo_trainer_get_qkv_bias(tr, l, stream)
             sapo_weights_set_qkv_bias(w, l, bq, bk, bv, stream)
     return buffers
+
+
+def sapo_debug_read_probe(nbytes: int = 1 << 31, repeats: int = 5) -> float:
+    """Streaming read bandwidth in GB/s of a kernel that only reads: median of `repeats` timed launches over a
+    buffer of `nbytes` (larger than the memory-side cache)."""
+    torch = _torch()
+    lib = load_library()
+    buf = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ms = []
+    for i in range(repeats + 1):
+        ev[0].record()
+        _check(lib.sapo_debug_read_probe(buf.data_ptr(), nbytes, sink.data_ptr(), _stream_ptr(None)))
+        ev[1].record()
+        torch.cuda.synchronize()
+        if i > 0:
+            ms.append(ev[0].elapsed_time(ev[1]))
+    return nbytes / (float(np.median(ms)) * 1e-3) / 1e9
 
 
 def sapo_debug_logits(w: Weights, tokens, positions: Sequence[Sequence[int]], stream=None):
