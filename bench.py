@@ -629,8 +629,10 @@ def main():
     if not (args.layers or args.new_tokens):
         read_probe = {"GBs": round(sapo.sapo_debug_read_probe(), 1), "bytes": 1 << 31,
                       "note": "streaming read of 2 GiB, 16-byte non-temporal loads; the roofline fractions use the published 8000 GB/s"}
+    props = torch.cuda.get_device_properties(0)
+    device = {"name": props.name, "memory_GB": round(props.total_memory / 2 ** 30), **sapo.sapo_device_info()}
     out.update({"roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "surrogate_loss": surrogate,
-                "hbm_read_probe": read_probe, "setup_s": round(setup_s, 1)})
+                "hbm_read_probe": read_probe, "device": device, "setup_s": round(setup_s, 1)})
     print(json.dumps(out))
 
 

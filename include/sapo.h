@@ -364,6 +364,12 @@ int sapo_trainer_steps(const sapo_trainer* tr);
 int sapo_trainer_read(const sapo_trainer* tr, int what, int tensor, float* out, size_t n, void* stream);
 
 /*
+ * The current device as the runtime reports it (host ints, for the measurement's record):
+ * out4 = {compute units, peak shader clock MHz, memory clock MHz, memory bus width in bits}.
+ */
+int sapo_device_info(int32_t* out4);
+
+/*
  * Measurement hook: one launch of a kernel that only reads `bytes` bytes at `buf` (dev, 16-byte aligned; 2048
  * workgroups, 16-byte non-temporal loads): timed by the caller, it gives the streaming read bandwidth a kernel
  * can reach on the machine, as context for the HBM roofline figures.  sink: dev, 4 bytes (normally left alone).

@@ -1196,6 +1196,19 @@ extern "C" int sapo_clipped_surrogate(const float* logp_new, const float* logp_o
   return SAPO_OK;
 }
 
+extern "C" int sapo_device_info(int32_t* out4) {
+  if (!out4) return fail(SAPO_EINVAL, "NULL argument");
+  int dev = 0;
+  HIP_CK(hipGetDevice(&dev));
+  hipDeviceProp_t pr;
+  HIP_CK(hipGetDeviceProperties(&pr, dev));
+  out4[0] = pr.multiProcessorCount;
+  out4[1] = pr.clockRate / 1000;         // MHz
+  out4[2] = pr.memoryClockRate / 1000;   // MHz
+  out4[3] = pr.memoryBusWidth;           // bits
+  return SAPO_OK;
+}
+
 // Measurement hook: a plain streaming read (what a kernel that only reads can reach on this machine).
 namespace {
 typedef unsigned int probe_u32x4 __attribute__((ext_vector_type(4)));

@@ -69,6 +69,8 @@ def load_library() -> C.CDLL:
     lib.sapo_rollout_generate.restype = i32
     lib.sapo_rollout_generate_stop.argtypes = [vp, vp, i32, i32, i32, i32, f32, u64, i32, vp, vp, vp, vp, sz, vp]
     lib.sapo_rollout_generate_stop.restype = i32
+    lib.sapo_device_info.argtypes = [vp]
+    lib.sapo_device_info.restype = i32
     lib.sapo_debug_read_probe.argtypes = [vp, sz, vp, vp]
     lib.sapo_debug_read_probe.restype = i32
     lib.sapo_weights_update.argtypes = [vp, C.POINTER(vp), i32, vp]
@@ -141,7 +143,7 @@ EXPORTED = ["sapo_weights_create", "sapo_weights_update", "sapo_weights_destroy"
             "sapo_policy_update",
             "sapo_trainer_export", "sapo_trainer_steps", "sapo_trainer_read", "sapo_trainer_set_matmul_pieces",
             "sapo_trainer_set_qkv_bias", "sapo_trainer_get_qkv_bias",
-            "sapo_debug_logits", "sapo_debug_gumbel", "sapo_debug_read_probe", "sapo_last_error", "sapo_profile_kernel_count",
+            "sapo_debug_logits", "sapo_debug_gumbel", "sapo_debug_read_probe", "sapo_device_info", "sapo_last_error", "sapo_profile_kernel_count",
             "sapo_profile_kernel_name", "sapo_profile_start", "sapo_profile_stop"]
 
 
@@ -673,6 +675,12 @@ def sapo_trainer_export_into(tr: Trainer, w: Weights, buffers=None, stream=None)
             bq, bk, bv = sapo_trainer_get_qkv_bias(tr, l, stream)
             sapo_weights_set_qkv_bias(w, l, bq, bk, bv, stream)
     return buffers
+
+
+def sapo_device_info() -> dict:
+    out = (C.c_int32 * 4)()
+    _check(load_library().sapo_device_info(out))
+    return {"compute_units": out[0], "max_clock_MHz": out[1], "memory_clock_MHz": out[2], "memory_bus_bits": out[3]}
 
 
 def sapo_debug_read_probe(nbytes: int = 1 << 31, repeats: int = 5) -> float:
