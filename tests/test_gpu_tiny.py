@@ -199,3 +199,16 @@ def test_error_codes(sapo):
     with pytest.raises(sapo.SapoError) as e:
         sapo.sapo_score_logprobs(gw, toks, mask, rew, 3)                # S % G != 0
     assert e.value.code == sapo.SAPO_EINVAL
+
+
+def test_measurement_hooks(sapo):
+    """The two hooks bench.py records as context: what the runtime reports for the device, and the bandwidth of a
+    kernel that only reads (a sanity range, not a performance assertion: above 1 TB/s, not above the 8 TB/s peak)."""
+    info = sapo.sapo_device_info()
+    assert info["compute_units"] > 0 and info["max_clock_MHz"] > 0 and info["memory_bus_bits"] > 0
+    gbs = sapo.sapo_debug_read_probe(nbytes=1 << 28, repeats=3)
+    assert 1000.0 < gbs < 16000.0, gbs      # 256 MiB sits partly in the memory-side cache, hence the loose upper end
+    import ctypes as C
+    lib = sapo.load_library()
+    assert lib.sapo_debug_read_probe(None, 1 << 20, None, None) == sapo.SAPO_EINVAL
+    assert lib.sapo_device_info(None) == sapo.SAPO_EINVAL
