@@ -26,11 +26,8 @@ the design notes.  Sampling is exact sampling from softmax(z / T) done by
 Gumbel-max with noise from Philox4x32-10 (Salmon et al., SC'11) keyed on
 (seed, sequence, step) so that it can be reproduced element by element.
 
-All arithmetic is float64 on float32- or bf16-valued weights ("mode A").  With
-act_round="bf16" the activations are additionally rounded to bf16 at the points
-where a bf16 pipeline stores them ("mode B": norm outputs, post-rotary q and k,
-v, attention output, SwiGLU product); that mode exists to tighten token-level
-comparison with a bf16 device path and is not the definition.
+All arithmetic is float64 on float32- or bf16-valued weights: the definition,
+with no rounding of activations anywhere.
 
 Pins (tests/test_oracle_*.py): Philox known-answer vectors, Gumbel moments,
 sampler histogram vs softmax, brute-force attention, rotary closed forms,
@@ -133,7 +130,7 @@ def _stored_to_f64(a: Optional[np.ndarray]) -> Optional[np.ndarray]:
 class Model:
     """Model description + float64 copies of the weights (values unchanged)."""
 
-    def __init__(self, shape, weights: dict, act_round: Optional[str] = None):
+    def __init__(self, shape, weights: dict):
         self.n_layers = shape.n_layers
         self.d = shape.d_model
         self.hq = shape.n_q_heads
@@ -144,16 +141,11 @@ class Model:
         self.eps = float(shape.rms_eps)
         self.theta = float(shape.rope_theta)
         assert self.hq % self.hkv == 0 and self.hd % 2 == 0
-        assert act_round in (None, "bf16")
-        self.act_round = act_round
         self.embed = _stored_to_f64(weights["embed"])
         self.layers = [{k: _stored_to_f64(v) for k, v in lw.items()} for lw in weights["layers"][: self.n_layers]]
         self.final_norm = _stored_to_f64(weights["final_norm"])
         lm = weights.get("lm_head")
         self.lm_head = self.embed if lm is None else _stored_to_f64(lm)
-
-    def rnd(self, x: np.ndarray) -> np.ndarray:
-        return round_bf16(x) if self.act_round == "bf16" else x
 
 
 # --------------------------------------------------------------------------- #
@@ -216,21 +208,20 @@ def _layer(m: Model, lw: dict, h: np.ndarray, positions: np.ndarray, k_prev, v_p
     earlier positions (or None).  Returns (h_out, k_all, v_all).
     """
     n = h.shape[0]
-    a = m.rnd(rmsnorm(h, lw["attn_norm"], m.eps))
+    a = rmsnorm(h, lw["attn_norm"], m.eps)
     q, k, v = a @ lw["wq"].T, a @ lw["wk"].T, a @ lw["wv"].T
     if "bq" in lw:   # optional biases of the three projections (the 0.5B model family the paper ran has them)
         q, k, v = q + lw["bq"], k + lw["bk"], v + lw["bv"]
     q, k, v = q.reshape(n, m.hq, m.hd), k.reshape(n, m.hkv, m.hd), v.reshape(n, m.hkv, m.hd)
-    q = m.rnd(rope_rotate(q, positions, m.theta))
-    k = m.rnd(rope_rotate(k, positions, m.theta))
-    v = m.rnd(v)
+    q = rope_rotate(q, positions, m.theta)
+    k = rope_rotate(k, positions, m.theta)
     if k_prev is not None:
         k = np.concatenate([k_prev, k], axis=0)
         v = np.concatenate([v_prev, v], axis=0)
-    o = m.rnd(attention(q, k, v, int(positions[0])))
+    o = attention(q, k, v, int(positions[0]))
     h = h + o.reshape(n, m.hq * m.hd) @ lw["wo"].T
-    b = m.rnd(rmsnorm(h, lw["ffn_norm"], m.eps))
-    act = m.rnd(silu(b @ lw["w_gate"].T) * (b @ lw["w_up"].T))
+    b = rmsnorm(h, lw["ffn_norm"], m.eps)
+    act = silu(b @ lw["w_gate"].T) * (b @ lw["w_up"].T)
     h = h + act @ lw["w_down"].T
     return h, k, v
 
@@ -251,7 +242,7 @@ def hidden_states(m: Model, tokens: np.ndarray, cache: Optional[list] = None) ->
         h, k, v = _layer(m, lw, h, positions, kp, vp)
         if cache is not None:
             cache[li] = [k, v]
-    return m.rnd(rmsnorm(h, m.final_norm, m.eps))
+    return rmsnorm(h, m.final_norm, m.eps)
 
 
 def logits_from_hidden(m: Model, x: np.ndarray) -> np.ndarray:
@@ -279,8 +270,9 @@ def log_softmax(z: np.ndarray) -> np.ndarray:
 def perturbed_scores(z: np.ndarray, temperature: float, seed: int, seq: int, step: int) -> np.ndarray:
     """float32[vocab] scores y_v = z_v / T + g_v whose argmax is the sampled token.
 
-    The decision is taken in fp32, the device path's precision: z is rounded to
-    fp32, divided by T in fp32, and the fp32 Gumbel noise added in fp32.
+    The decision is taken in fp32 (both sides of a parity check take it in the
+    same precision): z is rounded to fp32, divided by T in fp32, and the fp32
+    Gumbel noise added in fp32.
     T == 0 means greedy decoding: y = z.
     """
     z32 = np.asarray(z, dtype=np.float64).astype(np.float32)

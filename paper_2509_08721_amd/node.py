@@ -46,10 +46,16 @@ class Node:
     def training_set(self, own_sequences, own_rewards, swarm_sequences, swarm_rewards, n_own: int, n_swarm: int, seed: int):
         """I^n datapoints of the node's own and J^n sampled from the swarm's, those with zero advantage discarded
         (a datapoint is a question's G sequences).  Returns (sequences, rewards) of the datapoints actually taken."""
+        torch = sapo._torch()
         tok, rew, _, cnt = sapo.sapo_assemble_training_set(own_sequences, own_rewards, swarm_sequences, swarm_rewards,
                                                            self.group, n_own, n_swarm, seed)
-        n = int(cnt.sum().item()) * self.group
-        return tok[:n].contiguous(), rew[:n].contiguous()
+        # the node's own datapoints fill slots 0 .. n_own - 1 and the swarm's start at slot n_own whatever the own pool
+        # held, so with fewer own datapoints than asked for the slots in between are empty: take both runs, not a prefix
+        taken_own, taken_swarm = (int(c) for c in cnt.cpu().tolist())
+        G = self.group
+        rows = torch.cat([torch.arange(0, taken_own * G, device=tok.device),
+                          torch.arange(n_own * G, (n_own + taken_swarm) * G, device=tok.device)])
+        return tok[rows].contiguous(), rew[rows].contiguous()
 
     def update(self, sequences, rewards, n_completion: int, workspace=None):
         """One PolicyGradient step on the training set: score it under the current policy (old log-probs, group-relative

@@ -1,28 +1,45 @@
 """GPU parity at the full sizes of the five configurations, in the launch configuration the
-benchmark times (bf16 MFMA kernels, captured decode graph on a side stream).
+benchmark times (half-precision MFMA kernels, captured decode graph on a side stream).
 
-The oracle costs about 1 GFLOP (fp64) per token and billion parameters, so it checks samples:
-whole sequences where that takes seconds, otherwise chosen (sequence, step) pairs whose prefix the
-oracle re-runs from scratch.  Every check is teacher-forced on the GPU's own tokens, so a flip
-cannot cascade.  Token rule: the GPU's token is the oracle's argmax of the perturbed scores, or a
-stated near-tie (gap <= 1e-3 + 2 * 5e-2 / T: the literal band widened by the bf16 logit tolerance);
-log-probs within 2e-2 of the definition (oracle mode A)."""
+The three bars (all against the oracle's definition, fp64 on the bf16-valued weights):
+  * token ids: the device's token is the oracle's argmax of the perturbed scores z / T + g on the device's own
+    prefix (teacher-forced per step, so a flip cannot cascade), or a stated near-tie.  The literal near-tie band is
+    1e-3; a device whose logits are off by eps at that position can legitimately flip a step whose top two scores
+    are within 2 eps / T, so a flip must lie within 1e-3 + 2 eps / T with eps the error MEASURED at that position
+    (not the 5e-2 ceiling), and the number of flips beyond the literal band is held to a stated count;
+  * teacher-forced logits (sapo_debug_logits at the sampled positions): max-abs error <= 5e-2;
+  * log-probs, rollout's and scoring pass's: <= 2e-2 abs.
+
+The oracle costs about 1 GFLOP (fp64) per token and billion parameters, so it checks a stated sample, drawn
+with SAMPLE_SEED: for each configuration one whole sequence per group (every step of it), plus every other
+sequence at 8 random steps (configurations 2 - 4) or 32 random (sequence, step) pairs (configuration 5).  The
+oracle re-runs a sequence up to its deepest checked step; for the long sequences the random steps of a
+sequence are drawn below a horizon that cycles over the sequences (stated per configuration below), so that
+a quarter of them reach into the deepest part and the rest stay affordable.  Whole sequences go through the
+oracle's full recompute, the others through its incremental path on the prompt's K/V (pinned equal)."""
+import math
+import time
+
 import numpy as np
 import pytest
 
 from oracle import sapo_oracle as O
 from paper_2509_08721_amd import workloads as W
-from tests.parity import check_rollout_steps
+from tests.parity import SampleStats, check_sequence, prompt_cache
 
 pytestmark = pytest.mark.gpu
 
-LOGIT_TOL_BF16 = 5e-2
+LOGIT_TOL_HALF = 5e-2
 LOGPROB_TOL = 2e-2
 NEAR_TIE = 1e-3
+SAMPLE_SEED = 250908721
 
 
-def band(temp):
-    return NEAR_TIE + 2 * LOGIT_TOL_BF16 / (temp if temp > 0 else 1.0)
+def flips_allowed_beyond_literal_band(n_steps):
+    """A step flips when the top two perturbed scores are closer than the difference of the two logit errors.  With
+    Gumbel noise P(gap < x) <= x, and the measured errors are a few 1e-3, so about 0.5 % of steps can flip
+    and most of those lie beyond the literal 1e-3 band.  Stated ceiling: 1 % of the sample (at least 2)."""
+    return max(2, int(math.ceil(0.01 * n_steps)))
 
 
 @pytest.fixture(scope="module")
@@ -56,11 +73,6 @@ class Loaded:
         return self._oracle
 
 
-@pytest.fixture(scope="module")
-def halfb(sapo):
-    return Loaded(sapo, W.WORKLOADS["halfb_rollout"])
-
-
 def rollout_on_side_stream(sapo, gw, prompts, G, N, temp, seed):
     import torch
     side = torch.cuda.Stream()
@@ -71,64 +83,173 @@ def rollout_on_side_stream(sapo, gw, prompts, G, N, temp, seed):
     return toks.cpu().numpy(), lps.cpu().numpy()
 
 
-def assert_rollout(res, n_tokens_total):
-    assert not res["bad"], res["bad"][:10]
-    assert res["n"] - res["exact"] <= max(2, 0.05 * res["n"]), (res["n"], res["exact"], res["near"][:10])
-    assert res["max_lp_err"] <= LOGPROB_TOL, res["max_lp_err"]
+class Case:
+    """One configuration on the device: the rollout (when it has one), the batch of whole sequences, the scoring
+    pass over it (when it has one), and what the sample showed so far."""
+
+    def __init__(self, name, model, prompts, group, Lp, N, temperature, seed, seqs, toks=None, lps=None, score_lp=None,
+                 logits_rows=None):
+        self.name, self.model, self.prompts, self.group = name, model, prompts, group
+        self.Lp, self.N, self.temperature, self.seed = Lp, N, temperature, seed
+        self.seqs, self.toks, self.lps, self.score_lp = seqs, toks, lps, score_lp
+        self.logits_rows = logits_rows       # rows per sapo_debug_logits call around the sequence (None: whole batch)
+        self.caches = {}
+        self.total = SampleStats()
+        self.seconds = 0.0
+        self._dev_seqs = None
+
+    def device_logits(self, sapo, s):
+        import torch
+        if self.logits_rows is None:
+            if self._dev_seqs is None:
+                self._dev_seqs = dev(self.seqs)
+            batch, row = self._dev_seqs, s
+        else:   # the sequence's own group of rows: a sequence's result does not depend on its batch
+            r0 = s // self.logits_rows * self.logits_rows
+            batch, row = dev(self.seqs[r0:r0 + self.logits_rows]), s - r0
+        return lambda positions: sapo.sapo_debug_logits(self.model.gw, batch, [(row, p) for p in positions]).cpu().numpy()
+
+    def check(self, sapo, seq_steps, whole):
+        """seq_steps: {sequence: steps}.  Asserts the three bars on this part of the sample and adds it to the total."""
+        t0 = time.time()
+        part = SampleStats()
+        for s, steps in seq_steps.items():
+            cache = None
+            if not whole:
+                p = s // self.group
+                if p not in self.caches:
+                    self.caches[p] = prompt_cache(self.model.oracle, self.prompts[p])
+                cache = self.caches[p]
+            lp_rows = []
+            if self.lps is not None:
+                lp_rows.append(self.lps[s])
+            if self.score_lp is not None:
+                lp_rows.append(self.score_lp[s, self.Lp:])
+            part.merge(check_sequence(self.model.oracle, self.seqs[s], self.Lp, steps, s, device_logits=self.device_logits(sapo, s),
+                                      gpu_tokens=self.toks[s] if self.toks is not None else None, gpu_logprobs=lp_rows,
+                                      temperature=self.temperature, seed=self.seed, cache=cache))
+        self.seconds += time.time() - t0
+        self.total.merge(part)
+        print("%s %s: %s  [%.0f s]" % (self.name, "whole sequences" if whole else "sampled steps", part.summary(), time.time() - t0))
+        assert part.max_eps <= LOGIT_TOL_HALF, part.max_eps
+        assert part.max_lp_err <= LOGPROB_TOL, part.max_lp_err
+        temp = self.temperature if self.temperature > 0 else 1.0
+        outside = [f for f in part.flips if f[4] > NEAR_TIE + 2 * f[5] / temp]
+        assert not outside, outside[:10]
+        return part
+
+    def assert_totals(self):
+        print("%s TOTAL: %s  [oracle + device logits %.0f s]" % (self.name, self.total.summary(), self.seconds))
+        if self.toks is not None:
+            beyond = self.total.above(NEAR_TIE)
+            assert len(beyond) <= flips_allowed_beyond_literal_band(self.total.n), (len(beyond), self.total.n, beyond[:10])
 
 
-def test_config2_rollout_0p5b(sapo, halfb):
-    """8 prompts x 8 completions, prompt 128, 256 new tokens, temperature 1."""
+def draw_sample(config, n_seqs, group, N, horizons, n_steps=8):
+    """(whole, sampled): one whole sequence per group, and every other sequence at n_steps random steps below its
+    horizon (horizons cycle over the sequences)."""
+    rng = np.random.default_rng([SAMPLE_SEED, config])
+    whole = {p * group + int(rng.integers(group)): list(range(N)) for p in range(n_seqs // group)}
+    sampled = {}
+    for s in range(n_seqs):
+        h = horizons[s % len(horizons)]
+        steps = sorted(rng.choice(h, size=min(n_steps, h), replace=False).tolist())
+        if s not in whole:
+            sampled[s] = steps
+    return whole, sampled
+
+
+def part_of(d, i, n):
+    keys = sorted(d)
+    return {k: d[k] for k in keys[i::n]}
+
+
+# ------------------------------------------------------------------------------------------------
+# configuration 2: 0.5B-class decoder, 8 prompts x 8 completions, prompt 128, 256 new tokens, temperature 1
+# ------------------------------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def halfb(sapo):
+    return Loaded(sapo, W.WORKLOADS["halfb_rollout"])
+
+
+@pytest.fixture(scope="module")
+def config2(sapo, halfb):
     wl = W.WORKLOADS["halfb_rollout"]
     prompts = W.make_prompts(wl)
     toks, lps = rollout_on_side_stream(sapo, halfb.gw, prompts, wl.group, wl.n_new, wl.temperature, wl.rollout_seed)
     assert toks.shape == (64, 256) and toks.min() >= 0 and toks.max() < wl.shape.vocab and np.isfinite(lps).all()
     # siblings of a prompt draw from the same step-0 logits with different noise: not all equal
     assert len(set(toks[:8, 0].tolist())) > 1
-    rng = np.random.default_rng(2)
-    seq_steps = {0: None, 63: None}                                   # two whole sequences
-    for s in (9, 22, 37, 50):                                         # one more per few groups, sampled steps
-        seq_steps[s] = sorted(rng.choice(wl.n_new, size=6, replace=False).tolist())
-    res = check_rollout_steps(halfb.oracle, prompts, wl.group, toks, lps, wl.temperature, wl.rollout_seed, seq_steps,
-                              band(wl.temperature))
-    print("config 2: %d steps checked, %d exact, %d near-ties (max gap %.4f), max |dlogp| %.4f"
-          % (res["n"], res["exact"], len(res["near"]), res["max_gap"], res["max_lp_err"]))
-    assert_rollout(res, toks.size)
-    # the scoring pass reproduces the rollout's log-probs (decode with the cache == teacher-forced recompute)
     seqs = np.concatenate([np.repeat(prompts, wl.group, axis=0), toks], axis=1).astype(np.int32)
     mask = W.make_completion_mask(64, 384, 256)
     rew = W.make_rewards(64, wl.reward_p, wl.reward_seed)
     lp, adv = sapo.sapo_score_logprobs(halfb.gw, dev(seqs), dev(mask), dev(rew), wl.group)
     lp, adv = lp.cpu().numpy(), adv.cpu().numpy()
-    assert np.max(np.abs(lp[:, 128:] - lps)) <= 2 * LOGPROB_TOL      # two device paths, each within tolerance of the definition
+    # decode with the cache == teacher-forced recompute: two device paths, each within tolerance of the definition
+    assert np.max(np.abs(lp[:, 128:] - lps)) <= 2 * LOGPROB_TOL
     assert np.max(np.abs(adv - O.group_advantages(rew, wl.group))) <= 1e-5
+    c = Case("config 2", halfb, prompts, wl.group, 128, 256, wl.temperature, wl.rollout_seed, seqs, toks, lps, lp)
+    c.sample = draw_sample(2, 64, wl.group, 256, [256])
+    return c
 
 
-def test_config3_long_generation_0p5b(sapo, halfb):
-    """Prompt 512, 1024 new tokens, temperature 0.7: contexts up to 1535 over 96 pages per sequence."""
+def test_config2_whole_sequences(sapo, config2):
+    config2.check(sapo, config2.sample[0], whole=True)
+
+
+@pytest.mark.parametrize("part", range(2))
+def test_config2_every_sequence_at_8_steps(sapo, config2, part):
+    config2.check(sapo, part_of(config2.sample[1], part, 2), whole=False)
+
+
+def test_config2_totals(config2):
+    assert config2.total.n == 8 * 256 + 56 * 8
+    config2.assert_totals()
+
+
+# ------------------------------------------------------------------------------------------------
+# configuration 3: same decoder, prompt 512, 1024 new tokens, temperature 0.7 (contexts up to 1535, 96 pages)
+# ------------------------------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def config3(sapo, halfb):
     wl = W.WORKLOADS["halfb_long"]
     prompts = W.make_prompts(wl)
     toks, lps = rollout_on_side_stream(sapo, halfb.gw, prompts, wl.group, wl.n_new, wl.temperature, wl.rollout_seed)
     assert toks.shape == (64, 1024) and toks.min() >= 0 and toks.max() < wl.shape.vocab and np.isfinite(lps).all()
-    seq_steps = {3: list(range(0, 48)),            # the first steps of one sequence, contiguous
-                 40: [0, 15, 16, 17, 500, 1023],   # page boundary (512 + 16) and the deepest context
-                 63: [255, 777]}
-    res = check_rollout_steps(halfb.oracle, prompts, wl.group, toks, lps, wl.temperature, wl.rollout_seed, seq_steps,
-                              band(wl.temperature))
-    print("config 3: %d steps checked, %d exact, %d near-ties (max gap %.4f), max |dlogp| %.4f"
-          % (res["n"], res["exact"], len(res["near"]), res["max_gap"], res["max_lp_err"]))
-    assert_rollout(res, toks.size)
+    seqs = np.concatenate([np.repeat(prompts, wl.group, axis=0), toks], axis=1).astype(np.int32)
+    c = Case("config 3", halfb, prompts, wl.group, 512, 1024, wl.temperature, wl.rollout_seed, seqs, toks, lps)
+    # horizons: a quarter of the sequences draw their 8 steps from all 1024, the others below 512 / 256 / 128
+    c.sample = draw_sample(3, 64, wl.group, 1024, [1024, 512, 256, 128])
+    return c
 
 
-def test_config4_mixed_scoring_0p5b(sapo, halfb):
-    """64 sequences of 768 tokens: groups 0-3 rolled out by the local weights, groups 4-7 by an
-    independently seeded copy ("external" rollouts of another node); all scored under the local
-    policy; mask = last 512 positions; rewards Bernoulli(0.3) in groups of 8."""
+@pytest.mark.parametrize("part", range(2))
+def test_config3_whole_sequences(sapo, config3, part):
+    config3.check(sapo, part_of(config3.sample[0], part, 2), whole=True)
+
+
+@pytest.mark.parametrize("part", range(4))
+def test_config3_every_sequence_at_8_steps(sapo, config3, part):
+    config3.check(sapo, part_of(config3.sample[1], part, 4), whole=False)
+
+
+def test_config3_totals(config3):
+    assert config3.total.n == 8 * 1024 + 56 * 8
+    config3.assert_totals()
+
+
+# ------------------------------------------------------------------------------------------------
+# configuration 4: scoring of a swarm-mixed batch, 64 x 768 (groups 0-3 rolled out by the local weights, groups
+# 4-7 by an independently seeded copy), mask = last 512 positions, rewards Bernoulli(0.3) in groups of 8
+# ------------------------------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def config4(sapo, halfb):
     wl = W.WORKLOADS["halfb_score_mixed"]
     other = Loaded(sapo, wl, seed=wl.external_weight_seed)
     prompts = W.make_prompts(W.scaled(wl, n_prompts=8))
     t_loc, _ = rollout_on_side_stream(sapo, halfb.gw, prompts[:4], 8, 512, 1.0, wl.rollout_seed)
     t_ext, _ = rollout_on_side_stream(sapo, other.gw, prompts[4:], 8, 512, 1.0, wl.rollout_seed + 1)
+    other.gw.close()
     del other
     seqs = np.concatenate([np.repeat(prompts, 8, axis=0), np.concatenate([t_loc, t_ext], axis=0)], axis=1).astype(np.int32)
     assert seqs.shape == (64, 768)
@@ -142,30 +263,38 @@ def test_config4_mixed_scoring_0p5b(sapo, halfb):
     # external rollouts are less likely under the local policy than its own (random weights are
     # close to uniform over the vocabulary, so the margin is small), and finite
     assert lp[32:, 256:].mean() < lp[:32, 256:].mean() - 0.2
-    check = [5, 44]                                              # one local, one external sequence
-    o_lp = O.score_logprobs(halfb.oracle, seqs[check], mask[check])
-    err = float(np.max(np.abs(lp[check] - o_lp)))
-    print("config 4: 2 x 512 log-probs checked, max |dlogp| %.4f (local mean %.2f, external mean %.2f)"
-          % (err, lp[:32, 256:].mean(), lp[32:, 256:].mean()))
-    assert err <= LOGPROB_TOL
     # batch-composition invariance: the local half alone gives the same bytes as inside the mixed batch
     lp_half, _ = sapo.sapo_score_logprobs(halfb.gw, dev(seqs[:32]), dev(mask[:32]), dev(rew[:32]), 8)
     assert np.array_equal(lp_half.cpu().numpy(), lp[:32])
+    c = Case("config 4", halfb, prompts, 8, 256, 512, 1.0, 0, seqs, None, None, lp)
+    c.sample = draw_sample(4, 64, 8, 512, [512, 384, 256, 128])
+    return c
 
 
-def test_config5_1p5b_rollout_and_scoring(sapo):
-    """1.5B-class decoder, 32 prompts x 8 completions, prompt 256, 512 new tokens, then scoring of all 256."""
+def test_config4_whole_sequences(sapo, config4):
+    config4.check(sapo, config4.sample[0], whole=True)
+
+
+@pytest.mark.parametrize("part", range(2))
+def test_config4_every_sequence_at_8_positions(sapo, config4, part):
+    config4.check(sapo, part_of(config4.sample[1], part, 2), whole=False)
+
+
+def test_config4_totals(config4):
+    assert config4.total.n == 8 * 512 + 56 * 8
+    config4.assert_totals()
+
+
+# ------------------------------------------------------------------------------------------------
+# configuration 5: 1.5B-class decoder, 32 prompts x 8 completions, prompt 256, 512 new tokens, then scoring of all 256
+# ------------------------------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def config5(sapo):
     wl = W.WORKLOADS["onehalfb"]
     m = Loaded(sapo, wl)
     prompts = W.make_prompts(wl)
     toks, lps = rollout_on_side_stream(sapo, m.gw, prompts, wl.group, wl.n_new, wl.temperature, wl.rollout_seed)
     assert toks.shape == (256, 512) and toks.min() >= 0 and toks.max() < wl.shape.vocab and np.isfinite(lps).all()
-    seq_steps = {17: list(range(0, 24)), 200: [0, 100, 511], 255: [300]}
-    res = check_rollout_steps(m.oracle, prompts, wl.group, toks, lps, wl.temperature, wl.rollout_seed, seq_steps,
-                              band(wl.temperature))
-    print("config 5 rollout: %d steps checked, %d exact, %d near-ties (max gap %.4f), max |dlogp| %.4f"
-          % (res["n"], res["exact"], len(res["near"]), res["max_gap"], res["max_lp_err"]))
-    assert_rollout(res, toks.size)
     seqs = np.concatenate([np.repeat(prompts, wl.group, axis=0), toks], axis=1).astype(np.int32)
     mask = W.make_completion_mask(256, 768, 512)
     rew = W.make_rewards(256, wl.reward_p, wl.reward_seed)
@@ -173,10 +302,33 @@ def test_config5_1p5b_rollout_and_scoring(sapo):
     lp, adv = lp.cpu().numpy(), adv.cpu().numpy()
     assert np.isfinite(lp).all()
     assert np.max(np.abs(adv - O.group_advantages(rew, wl.group))) <= 1e-5
-    o_lp = O.score_logprobs(m.oracle, seqs[[130]], mask[[130]])
-    err = float(np.max(np.abs(lp[[130]] - o_lp)))
-    print("config 5 scoring: 512 log-probs checked, max |dlogp| %.4f" % err)
-    assert err <= LOGPROB_TOL
+    c = Case("config 5", m, prompts, wl.group, 256, 512, wl.temperature, wl.rollout_seed, seqs, toks, lps, lp, logits_rows=8)
+    rng = np.random.default_rng([SAMPLE_SEED, 5])
+    groups = sorted(rng.choice(32, size=8, replace=False).tolist())
+    whole = {g * 8 + int(rng.integers(8)): list(range(512)) for g in groups}            # 8 whole sequences
+    pairs = {}
+    while len(pairs) < 32:                                                               # 32 random (sequence, step)
+        s, t = int(rng.integers(256)), int(rng.integers(512))
+        if s not in whole and s not in pairs:
+            pairs[s] = [t]
+    c.sample = (whole, pairs)
+    return c
+
+
+@pytest.mark.parametrize("part", range(2))
+def test_config5_whole_sequences(sapo, config5, part):
+    config5.check(sapo, part_of(config5.sample[0], part, 2), whole=True)
+
+
+@pytest.mark.parametrize("part", range(4))
+def test_config5_random_sequence_step_pairs(sapo, config5, part):
+    config5.check(sapo, part_of(config5.sample[1], part, 4), whole=False)
+
+
+def test_config5_totals(config5):
+    assert config5.total.n == 8 * 512 + 32
+    config5.assert_totals()
+    config5.model.gw.close()
 
 
 def test_config5_stop_token_ended_sequences_leave_the_batch(sapo):
@@ -185,6 +337,7 @@ def test_config5_stop_token_ended_sequences_leave_the_batch(sapo):
     then been through both batch sizes; its tokens and log-probs are checked against the oracle before and after
     the switch, as are those of a sequence that stopped early."""
     import torch
+    from tests.parity import check_rollout_steps
     wl = W.WORKLOADS["onehalfb_stop"]
     w = W.boost_token(W.make_weights(wl.shape, wl.weight_seed), wl.shape, wl.stop_token, wl.stop_boost)
     gw = sapo.sapo_weights_create(wl.shape, w)
@@ -207,9 +360,12 @@ def test_config5_stop_token_ended_sequences_leave_the_batch(sapo):
     mid = np.nonzero((lens > 40) & (lens < 200))[0]
     s_mid = int(mid[0]) if mid.size else int(np.argsort(lens)[128])
     seq_steps = {s_long: [0, 20, 150, 400, wl.n_new - 1], s_mid: [0, int(lens[s_mid]) // 2, int(lens[s_mid]) - 1]}
+    # no teacher-forced logits of the boosted model are taken here: the band is the literal one widened by the
+    # largest logit error the configuration-5 sample above measured on this decoder class (1e-2 is its ceiling)
     res = check_rollout_steps(O.Model(wl.shape, w), prompts, wl.group, toks, lps, wl.temperature, wl.rollout_seed, seq_steps,
-                              band(wl.temperature))
+                              NEAR_TIE + 2 * 1e-2 / wl.temperature)
     print("config 5 with a stop token: %s; %d steps checked, %d exact, %d near-ties, max |dlogp| %.4f"
           % (stats, res["n"], res["exact"], len(res["near"]), res["max_lp_err"]))
-    assert_rollout(res, toks.size)
+    assert not res["bad"], res["bad"]
+    assert res["max_lp_err"] <= LOGPROB_TOL, res["max_lp_err"]
     gw.close()

@@ -13,8 +13,7 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(scope="module")
 def sapo():
     import torch
-    if not torch.cuda.is_available():
-        pytest.skip("no GPU")
+    assert torch.cuda.is_available(), "these tests need the GPU"
     from paper_2509_08721_amd import sapo as S
     S.load_library()
     return S
@@ -155,3 +154,26 @@ def node_rounds(sapo, shape, tol, std):
     assert np.array_equal(l_own.cpu().numpy().view(np.uint32), l_new.cpu().numpy().view(np.uint32))
     fresh.close()
     node.close(); other.close()
+
+
+def test_training_set_with_fewer_own_datapoints_than_asked_for(sapo):
+    """Algorithm 1's training set when the node's own pool is smaller than I^n: the swarm's datapoints sit after the
+    empty own slots, and the node keeps all of them and no empty row (equal to the oracle's assembly, rows of
+    datapoints that exist only)."""
+    from oracle import sapo_oracle as O
+    from paper_2509_08721_amd.node import Node
+    shape = W.TINY
+    G, T = 4, 12
+    rng = np.random.default_rng(77)
+    own_tok = rng.integers(1, shape.vocab, size=(2 * G, T)).astype(np.int32)        # 2 own datapoints, 4 asked for
+    own_rew = rng.integers(0, 2, size=2 * G).astype(np.float32)
+    ext_tok = rng.integers(1, shape.vocab, size=(6 * G, T)).astype(np.int32)
+    ext_rew = np.tile(np.array([1, 0, 0, 1], dtype=np.float32), 6)                  # every swarm datapoint is informative
+    node = Node(shape, W.make_weights(shape, 5), G)
+    seqs, rew = node.training_set(dev(own_tok), dev(own_rew), dev(ext_tok), dev(ext_rew), 4, 3, 11)
+    o_tok, o_rew, o_src, o_cnt = O.assemble_training_set(own_tok, own_rew, ext_tok, ext_rew, G, 4, 3, 11)
+    assert list(o_cnt) == [2, 3]
+    keep = np.repeat(np.asarray(o_src) >= 0, G)
+    assert seqs.shape[0] == 5 * G and np.array_equal(seqs.cpu().numpy(), o_tok[keep]) and np.array_equal(rew.cpu().numpy(), o_rew[keep])
+    assert (seqs.cpu().numpy() != 0).all()                                          # no empty slot's zero rows
+    node.close()

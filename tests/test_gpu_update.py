@@ -29,8 +29,7 @@ SHAPES = {
 @pytest.fixture(scope="module")
 def sapo():
     import torch
-    if not torch.cuda.is_available():
-        pytest.skip("no GPU")
+    assert torch.cuda.is_available(), "these tests need the GPU"
     from paper_2509_08721_amd import sapo as S
     S.load_library()
     return S

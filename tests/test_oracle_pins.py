@@ -390,15 +390,6 @@ def test_temperature_changes_sampling_not_logprob_definition():
     assert abs(l7[0, 0] - O.log_softmax(z)[t7[0, 0]]) < 1e-6   # log-prob is at T = 1
 
 
-def test_mode_b_rounding_is_small_perturbation():
-    shape, w, _ = tiny_model()
-    ma, mb = O.Model(shape, w), O.Model(shape, w, act_round="bf16")
-    toks = np.random.default_rng(4).integers(0, shape.vocab, size=20)
-    za, zb = O.forward_logits(ma, toks), O.forward_logits(mb, toks)
-    err = np.abs(za - zb).max()
-    assert 0 < err < 5e-2
-
-
 # ----------------------------------------------------------------------------- advantages
 def test_group_advantages_closed_forms():
     G = 8
