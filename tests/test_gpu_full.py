@@ -5,8 +5,9 @@ The three bars (all against the oracle's definition, fp64 on the bf16-valued wei
   * token ids: the device's token is the oracle's argmax of the perturbed scores z / T + g on the device's own
     prefix (teacher-forced per step, so a flip cannot cascade), or a stated near-tie.  The literal near-tie band is
     1e-3; a device whose logits are off by eps at that position can legitimately flip a step whose top two scores
-    are within 2 eps / T, so a flip must lie within 1e-3 + 2 eps / T with eps the error MEASURED at that position
-    (not the 5e-2 ceiling), and the number of flips beyond the literal band is held to a stated count;
+    are within 2 eps / T, so a flip must lie within 1e-3 + 2 eps / T with eps the largest logit error MEASURED on
+    that part of the sample (teacher-forced device logits against the oracle's: about 1e-2, not the 5e-2 ceiling),
+    and the number of flips beyond the literal band is held to a stated count;
   * teacher-forced logits (sapo_debug_logits at the sampled positions): max-abs error <= 5e-2;
   * log-probs, rollout's and scoring pass's: <= 2e-2 abs.
 
@@ -37,9 +38,10 @@ SAMPLE_SEED = 250908721
 
 def flips_allowed_beyond_literal_band(n_steps):
     """A step flips when the top two perturbed scores are closer than the difference of the two logit errors.  With
-    Gumbel noise P(gap < x) <= x, and the measured errors are a few 1e-3, so about 0.5 % of steps can flip
-    and most of those lie beyond the literal 1e-3 band.  Stated ceiling: 1 % of the sample (at least 2)."""
-    return max(2, int(math.ceil(0.01 * n_steps)))
+    Gumbel noise P(gap < x) <= x; the measured logit errors (4e-3 on the 0.5B-class decoder, 9e-3 on the 1.5B-class
+    one) bound x by 2 eps / T, about 1 % of steps, and what was seen is 0 of 2496, 3 of 8640 (T = 0.7), 0 of 4128.
+    Stated ceiling: 0.2 % of the sample (at least 2)."""
+    return max(2, int(math.ceil(0.002 * n_steps)))
 
 
 @pytest.fixture(scope="module")
@@ -134,7 +136,7 @@ class Case:
         assert part.max_eps <= LOGIT_TOL_HALF, part.max_eps
         assert part.max_lp_err <= LOGPROB_TOL, part.max_lp_err
         temp = self.temperature if self.temperature > 0 else 1.0
-        outside = [f for f in part.flips if f[4] > NEAR_TIE + 2 * f[5] / temp]
+        outside = [f for f in part.flips if f[4] > NEAR_TIE + 2 * part.max_eps / temp]
         assert not outside, outside[:10]
         return part
 
