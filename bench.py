@@ -13,6 +13,9 @@ Other workloads (--workload): halfb_round (one whole round of Algorithm 1 for on
 decode step at batch 1), halfb_update / onehalfb_update (the local policy update on configuration 2's / 5's training set:
 trained tokens/s; --pieces 1 for bf16 GEMM operands).
 
+The default invocation also times, a few steps each, the other full-size configurations (halfb_long, halfb_score_mixed,
+onehalfb) and reports them under "other_configs" of the same line; the headline fields stay those of the default workload.
+
 Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -349,40 +352,12 @@ def bench_update(args, wl):
     print(json.dumps(out))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="halfb_rollout")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-kernel-profile", action="store_true")
-    ap.add_argument("--copy-probe", action="store_true",
-                    help="also run one 1 GiB device copy (a kernel of known traffic, for scaling profiler byte counters)")
-    ap.add_argument("--layers", type=int, default=0,
-                    help="counter runs only: same kernels and shapes with this many layers (fewer launches); "
-                         "the printed line is then not a benchmark result")
-    ap.add_argument("--new-tokens", type=int, default=0, help="counter runs only: generate this many tokens")
-    ap.add_argument("--pieces", type=int, default=3, choices=(1, 2, 3),
-                    help="*_update workloads only: 3 = fp32-accurate matrix products (default), 2 = operands of 16 "
-                         "significant bits, 1 = bf16 operands")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this library runs on ONE GPU (no sharding, no collectives); --gpus %d is not "
-              "supported. Sequences are independent, so N GPUs would each take P/N prompts." % args.gpus,
-              file=sys.stderr)
-        sys.exit(2)
-
+def run_workload(args, workload, n_steps, n_warmup, cpu_baseline, probes):
+    """Time one workload (rollout and / or scoring) and return its record."""
     import torch
     from paper_2509_08721_amd import sapo, workloads as W
 
-    wl = W.WORKLOADS[args.workload]
-    if args.workload.endswith("_update"):
-        return bench_update(args, wl)
-    if wl.stop_token >= 0:
-        return bench_stop(args, wl)
-    if args.workload.endswith("_round"):
-        return bench_round(args, wl)
+    wl = W.WORKLOADS[workload]
     if args.layers > 0:
         wl = replace(wl, shape=replace(wl.shape, n_layers=args.layers))
     if args.new_tokens > 0:
@@ -393,7 +368,7 @@ def main():
     weights = W.make_weights(shape, wl.weight_seed)
     gw = sapo.sapo_weights_create(shape, weights)
     G = wl.group
-    do_rollout = wl.n_new > 0 and args.workload != "halfb_score_mixed"
+    do_rollout = wl.n_new > 0 and workload != "halfb_score_mixed"
     do_score = wl.score_seqs > 0
     side = torch.cuda.Stream()      # a non-default stream: the library replays a captured decode step on it
     torch.cuda.synchronize()
@@ -443,7 +418,7 @@ def main():
         sc_adv = torch.empty((S_score,), dtype=torch.float32, device="cuda")
     setup_s = time.time() - t0
 
-    if args.copy_probe:
+    if args.copy_probe and probes:
         a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         b = torch.empty_like(a)
         b.copy_(a)
@@ -464,18 +439,18 @@ def main():
                                      out_advantages=sc_adv)
         ev[2].record()
 
-    for i in range(args.warmup):
+    for i in range(n_warmup):
         step(i)
     torch.cuda.synchronize()
     roll_ms, score_ms = [], []
     t_start = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(n_steps):
         step(100 + i)
         torch.cuda.synchronize()
         roll_ms.append(ev[0].elapsed_time(ev[1]))
         score_ms.append(ev[1].elapsed_time(ev[2]))
     torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t_start) * 1e3 / max(1, args.steps)
+    wall_ms = (time.perf_counter() - t_start) * 1e3 / max(1, n_steps)
     r_ms, s_ms = float(np.median(roll_ms)), float(np.median(score_ms))
     step_ms = r_ms + s_ms
 
@@ -504,7 +479,7 @@ def main():
 
     # the update's clipped surrogate on this batch (Sec. 4.2), outside the timed step: a few small kernels
     surrogate = None
-    if do_score:
+    if do_score and probes:
         lp_old = sc_lp + 0.05 * torch.randn_like(sc_lp)
         ws_l = torch.empty(sapo.sapo_surrogate_workspace_bytes() + 256, dtype=torch.uint8, device="cuda")
         lm = []
@@ -526,7 +501,7 @@ def main():
                   "rollout tokens/s + scored tokens/s (%s, 1 GPU)" % wl.name,
         "value": round((gen_tokens + scored_tokens) / (step_ms * 1e-3), 1),
         "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "n_gpus": 1, "steps": n_steps, "warmup": n_warmup,
         "ms_per_step": round(step_ms, 3), "wall_ms_per_step": round(wall_ms, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if shape.dtype == "f32" else "f16", "data": "synthetic",
@@ -594,24 +569,40 @@ def main():
 
     # CPU baseline: the oracle as it stands, on a bounded slice of the same workload
     cpu = None
-    if not args.no_cpu_baseline:
+    if cpu_baseline:
         from oracle import sapo_oracle as O
         ncores = len(os.sched_getaffinity(0))
         m = O.Model(shape, weights)
         big = shape.d_model >= 512
         parts, cpu_step_s = [], 0.0
         res = {}
-        if do_rollout:
-            p_n, g_n, n_n = (1, 2, 6) if big else (P, G, N)
+        if do_rollout and big:
+            # one group of G sequences, 16 decode steps each at the starting context, timed apart from the prompt's
+            # forward: the call is timed whole, the prompt's forward alone is timed again and taken off
+            n_n = 16
             t1 = time.perf_counter()
-            O.rollout_generate(m, prompts_np[:p_n], g_n, n_n, wl.temperature, wl.rollout_seed)
+            O.rollout_generate(m, prompts_np[:1], G, n_n + 1, wl.temperature, wl.rollout_seed)
+            dt_all = time.perf_counter() - t1
+            t1 = time.perf_counter()
+            O.hidden_states(m, prompts_np[0], [[None, None] for _ in range(m.n_layers)])
+            dt_prompt = time.perf_counter() - t1
+            dec_rate = G * n_n / max(dt_all - dt_prompt, 1e-9)
+            res["decode_tokens_per_s"] = round(dec_rate, 3)
+            res["prompt_forward_s"] = round(dt_prompt, 3)
+            cpu_roll_s = P * dt_prompt + gen_tokens / dec_rate          # every prompt once, every token one decode step
+            res["rollout_tokens_per_s"] = round(gen_tokens / cpu_roll_s, 3)
+            cpu_step_s += cpu_roll_s
+            parts.append("decode of one group of %d sequences x %d steps after a %d-token prompt in %.1f s "
+                         "(+ %.1f s for the prompt's forward, timed apart)" % (G, n_n, Lp, dt_all - dt_prompt, dt_prompt))
+        elif do_rollout:
+            t1 = time.perf_counter()
+            O.rollout_generate(m, prompts_np, G, N, wl.temperature, wl.rollout_seed)
             dt = time.perf_counter() - t1
-            res["rollout_tokens_per_s"] = round(p_n * g_n * n_n / dt, 3)
-            cpu_step_s += gen_tokens / (p_n * g_n * n_n / dt)
-            parts.append("rollout of %d prompt(s) x %d completions x %d new tokens (prompt %d) in %.1f s"
-                         % (p_n, g_n, n_n, Lp, dt))
+            res["rollout_tokens_per_s"] = round(gen_tokens / dt, 3)
+            cpu_step_s += dt
+            parts.append("the whole rollout call in %.1f s" % dt)
         if do_score:
-            s_n = 1 if big else S_score
+            s_n = 2 if big else S_score
             seq_np = (seq_src if seq_src is not None else torch.cat([prompt_rep, out_tok], dim=1))[:s_n].cpu().numpy()
             t1 = time.perf_counter()
             O.score_logprobs(m, seq_np, W.make_completion_mask(s_n, T, Tm))
@@ -626,14 +617,75 @@ def main():
 
     # context for the HBM fractions: what a kernel that only reads reaches on this machine (not a denominator)
     read_probe = None
-    if not (args.layers or args.new_tokens):
+    if probes and not (args.layers or args.new_tokens):
         read_probe = {"GBs": round(sapo.sapo_debug_read_probe(), 1), "bytes": 1 << 31,
                       "note": "streaming read of 2 GiB, 16-byte non-temporal loads; the roofline fractions use the published 8000 GB/s"}
     props = torch.cuda.get_device_properties(0)
     device = {"name": props.name, "memory_GB": round(props.total_memory / 2 ** 30), **sapo.sapo_device_info()}
     out.update({"roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "surrogate_loss": surrogate,
                 "hbm_read_probe": read_probe, "device": device, "setup_s": round(setup_s, 1)})
+    gw.close()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="halfb_rollout")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-profile", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="default workload only: do not also time the long-generation, mixed-scoring and 1.5B-class workloads")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one 1 GiB device copy (a kernel of known traffic, for scaling profiler byte counters)")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="counter runs only: same kernels and shapes with this many layers (fewer launches); "
+                         "the printed line is then not a benchmark result")
+    ap.add_argument("--new-tokens", type=int, default=0, help="counter runs only: generate this many tokens")
+    ap.add_argument("--pieces", type=int, default=3, choices=(1, 2, 3),
+                    help="*_update workloads only: 3 = fp32-accurate matrix products (default), 2 = operands of 16 "
+                         "significant bits, 1 = bf16 operands")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this library runs on ONE GPU (no sharding, no collectives); --gpus %d is not "
+              "supported. Sequences are independent, so N GPUs would each take P/N prompts." % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2509_08721_amd import sapo, workloads as W
+
+    wl = W.WORKLOADS[args.workload]
+    if args.workload.endswith("_update"):
+        return bench_update(args, wl)
+    if wl.stop_token >= 0:
+        return bench_stop(args, wl)
+    if args.workload.endswith("_round"):
+        return bench_round(args, wl)
+    out = run_workload(args, args.workload, args.steps, args.warmup, cpu_baseline=not args.no_cpu_baseline,
+                       probes=True)
+    default_run = args.workload == "halfb_rollout" and not (args.layers or args.new_tokens or args.no_other_configs)
+    if default_run:
+        # the other full-size configurations, a few steps each, in the same line: the long-generation rollout, the
+        # swarm-mixed scoring batch the scoring target is stated on, and the 1.5B-class decoder
+        other = {}
+        for name in ("halfb_long", "halfb_score_mixed", "onehalfb"):
+            r = run_workload(args, name, 3, 1, cpu_baseline=False, probes=False)
+            keep = {k: r[k] for k in ("value", "ms_per_step", "rollout_tokens_per_s", "rollout_ms", "decode_only_tokens_per_s",
+                                      "rollout_hbm", "scored_tokens_per_s", "score_ms", "score_mfma", "roofline",
+                                      "rollout_vs_score_logprob_max_abs") if k in r}
+            keep["steps"], keep["warmup"] = 3, 1
+            keep["config"] = {k: r["config"][k] for k in ("workload", "prompts", "completions_per_prompt", "prompt_len",
+                                                          "new_tokens", "temperature", "timed", "score_seqs", "score_len",
+                                                          "score_masked")}
+            keep["kernels"] = {k: {f: v[f] for f in ("launches", "avg_us", "frac") if f in v} for k, v in r["kernels"].items()
+                               if "frac" in v}
+            other[name] = keep
+        out["other_configs"] = other
     print(json.dumps(out))
+
 
 
 if __name__ == "__main__":
