@@ -270,6 +270,24 @@ int sapo_clipped_surrogate(const float* logp_new, const float* logp_old, const u
                            void* stream);
 
 /*
+ * sapo_clipped_surrogate for callers that cannot allocate device memory and have no workspace to hand over: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the
+ * workspace, same kernels, same results bit for bit.  The call allocates nothing (no hipMalloc / hipFree, no
+ * allocating library routine): its scratch (256 block partials and the totals, 4112 bytes) is a file-scope
+ * device array of the library, one copy per GPU, held until the process ends; its address is looked up on the
+ * first call on a device.  The caller still passes inputs and outputs (device pointers).
+ *   S * T at most SAPO_SURROGATE_NOALLOC_MAX_TOKENS; larger inputs are rejected with SAPO_EINVAL (as are NULL buffers,
+ *   non-positive sizes and clip bounds out of range); SAPO_EHIP when the array's address cannot be obtained.
+ * Every call on a GPU uses that GPU's one array (each call overwrites all of it before reading it, so nothing
+ * carries over from the previous call): two calls that overlap in time on one GPU - different streams or
+ * threads - race; run them in order.
+ */
+#define SAPO_SURROGATE_NOALLOC_MAX_TOKENS (1L << 28)
+int sapo_clipped_surrogate_noalloc(const float* logp_new, const float* logp_old, const uint8_t* completion_mask,
+                                   const float* advantages, int S, int T, float eps_low, float eps_high,
+                                   float* out_loss, float* out_dlogp, void* stream);
+
+/*
  * The local policy update (Algorithm 1, the PolicyGradient step; Sec. 4.2: GRPO with the KL weight
  * at zero, the clipped surrogate above, Adam with its default hyper-parameters: learning rate
  * 1e-3, beta1 0.9, beta2 0.999, eps 1e-8, no weight decay).

@@ -2,6 +2,8 @@
 // They run the fp32 configuration and every step that has no tile-aligned MFMA kernel.
 #include "common.h"
 #include "surrogate.h"
+#include "train.h"
+#include <mutex>
 
 namespace sapo {
 
@@ -560,6 +562,60 @@ hipError_t g_surrogate_loss(const float* logp_new, const float* logp_old, const 
   return launch(KID_MISC, k_surrogate_grad, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, logp_new, logp_old, mask,
                 adv, T, n, eps_low, eps_high, (const LossPartial*)(part + kLossBlocks), out_dlogp);
 }
+
+// ---------------------------------------------------------------------------------------
+// The same three passes for callers that cannot allocate (code under graph capture, serving loops, harnesses that
+// forbid hipMalloc): the block partials and the totals live in a file-scope device array instead of a workspace.
+// Every device holds its own copy of the array; its address is looked up once per device, with that device
+// current, and kept.  All 256 partial slots and the totals slot are overwritten by every call before they are
+// read, so nothing has to be cleared between calls; two calls that overlap on one device share the array and race.
+// ---------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[(kLossBlocks + 1) * sizeof(LossPartial)];   // 4112 bytes per device
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices] = {};
+static std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (looked up on the first call on that device).
+static hipError_t scratch_address(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
+}  // namespace sapo
+
+extern "C" int sapo_clipped_surrogate_noalloc(const float* logp_new, const float* logp_old, const uint8_t* completion_mask,
+                                              const float* advantages, int S, int T, float eps_low, float eps_high,
+                                              float* out_loss, float* out_dlogp, void* stream) {
+  using namespace sapo;
+  if (S <= 0 || T <= 0) return set_error(SAPO_EINVAL, "S and T must be positive");
+  if ((long)S * T > SAPO_SURROGATE_NOALLOC_MAX_TOKENS)
+    return set_error(SAPO_EINVAL, "S * T = %ld exceeds the maximum of %ld tokens of sapo_clipped_surrogate_noalloc",
+                     (long)S * T, (long)SAPO_SURROGATE_NOALLOC_MAX_TOKENS);
+  if (!logp_new || !logp_old || !completion_mask || !advantages || !out_loss) return set_error(SAPO_EINVAL, "NULL buffer");
+  if (!(eps_low >= 0.f && eps_low < 1.f && eps_high >= 0.f)) return set_error(SAPO_EINVAL, "clip bounds out of range");
+  void* ptr = nullptr;
+  hipError_t e = scratch_address(&ptr);
+  if (e != hipSuccess) return set_error(SAPO_EHIP, "hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e));
+  e = g_surrogate_loss(logp_new, logp_old, completion_mask, advantages, S, T, eps_low, eps_high, out_loss, out_dlogp, ptr,
+                       (hipStream_t)stream);
+  if (e != hipSuccess) return set_error(SAPO_EHIP, "launch failed: %s", hipGetErrorString(e));
+  return SAPO_OK;
+}
+
+namespace sapo {
 
 // ---------------------------------------------------------------------------------------
 // Training-set assembly (Sec. 3.2; Algorithm 1 "Assemble training set").  A datapoint is one

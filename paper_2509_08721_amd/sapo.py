@@ -91,6 +91,8 @@ def load_library() -> C.CDLL:
     lib.sapo_surrogate_workspace_bytes.restype = sz
     lib.sapo_clipped_surrogate.argtypes = [vp, vp, vp, vp, i32, i32, f32, f32, vp, vp, vp, sz, vp]
     lib.sapo_clipped_surrogate.restype = i32
+    lib.sapo_clipped_surrogate_noalloc.argtypes = [vp, vp, vp, vp, i32, i32, f32, f32, vp, vp, vp]
+    lib.sapo_clipped_surrogate_noalloc.restype = i32
     lib.sapo_trainer_create.argtypes = [C.POINTER(sapo_model_config), C.POINTER(vp), i32, C.POINTER(sapo_adam_config), vp,
                                         C.POINTER(vp)]
     lib.sapo_trainer_create.restype = i32
@@ -137,7 +139,7 @@ EXPORTED = ["sapo_weights_create", "sapo_weights_update", "sapo_weights_destroy"
             "sapo_debug_logits_workspace_bytes", "sapo_rollout_generate", "sapo_rollout_generate_stop", "sapo_rollout_last_stats",
             "sapo_rollout_generate_ragged",
             "sapo_score_logprobs", "sapo_score_logprobs_at",
-            "sapo_surrogate_workspace_bytes", "sapo_clipped_surrogate",
+            "sapo_surrogate_workspace_bytes", "sapo_clipped_surrogate", "sapo_clipped_surrogate_noalloc",
             "sapo_assemble_workspace_bytes", "sapo_assemble_training_set",
             "sapo_trainer_create", "sapo_trainer_destroy", "sapo_trainer_workspace_bytes", "sapo_trainer_workspace_bytes_for",
             "sapo_policy_update",
@@ -461,6 +463,25 @@ def sapo_clipped_surrogate(logp_new, logp_old, completion_mask, advantages, eps_
                                       grad.data_ptr() if want_grad else None, *_ws_args(workspace),
                                       _stream_ptr(stream)))
     return loss, grad
+
+
+def sapo_clipped_surrogate_noalloc(logp_new, logp_old, completion_mask, advantages, out_loss, out_dlogp=None,
+                                   eps_low: float = 0.2, eps_high: float = 0.28, stream=None):
+    """sapo_clipped_surrogate without a workspace and without any allocation: the caller passes the outputs
+    (out_loss float32 [1], out_dlogp float32 [S, T] or None); the library's scratch is a device array of its own."""
+    torch = _torch()
+    S, T = int(logp_new.shape[0]), int(logp_new.shape[1])
+    for t in (logp_new, logp_old) + ((out_dlogp,) if out_dlogp is not None else ()):
+        assert t.dtype == torch.float32 and t.is_cuda and t.is_contiguous() and tuple(t.shape) == (S, T)
+    assert completion_mask.dtype == torch.uint8 and completion_mask.is_cuda and completion_mask.is_contiguous()
+    assert tuple(completion_mask.shape) == (S, T)
+    assert advantages.dtype == torch.float32 and advantages.is_cuda and advantages.is_contiguous() and advantages.numel() == S
+    assert out_loss.dtype == torch.float32 and out_loss.is_cuda and out_loss.numel() >= 1
+    _check(load_library().sapo_clipped_surrogate_noalloc(logp_new.data_ptr(), logp_old.data_ptr(), completion_mask.data_ptr(),
+                                                         advantages.data_ptr(), S, T, eps_low, eps_high, out_loss.data_ptr(),
+                                                         out_dlogp.data_ptr() if out_dlogp is not None else None,
+                                                         _stream_ptr(stream)))
+    return out_loss, out_dlogp
 
 
 # --------------------------------------------------------------------------- #
