@@ -17,7 +17,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsapo.so")
 
-SOURCES = ["api.hip", "kernels_generic.hip", "kernels_mfma.hip", "kernels_decode.hip", "train.hip"]
+SOURCES = ["api.hip", "kernels_generic.hip", "kernels_mfma.hip", "kernels_decode.hip", "decode_persist.hip", "train.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-unused-variable"]

@@ -75,7 +75,7 @@ void prof_events(int kid, hipEvent_t* e0, hipEvent_t* e1) {
 static const char* const kKernelNames[KID_COUNT] = {
     "k_embed", "k_rmsnorm", "k_gemm", "k_rope_append", "k_attention", "k_swiglu", "k_sample_rows", "k_score_rows",
     "misc", "k_gemm_big", "k_lmhead_score", "k_lmhead_score_merge", "k_gemm_skinny", "k_lmhead_sample",
-    "k_lmhead_sample_merge", "k_decode_attention", "k_flash_attention", "k_gemm_big_decode"};
+    "k_lmhead_sample_merge", "k_decode_attention", "k_flash_attention", "k_gemm_big_decode", "k_decode_layers"};
 
 extern "C" int sapo_profile_kernel_count(void) { return KID_COUNT; }
 extern "C" const char* sapo_profile_kernel_name(int i) { return (i >= 0 && i < KID_COUNT) ? kKernelNames[i] : ""; }
@@ -129,6 +129,7 @@ struct sapo_weights {
   void* lm_head16 = nullptr;     // MFMA: W16 fragment order (decode)
   float* final_norm = nullptr;
   float2* rope = nullptr;        // [max_seq][hd / 2] (cos, sin)
+  PersistLayer* persist_tbl = nullptr;   // MFMA path: per-layer pointers for the persistent decode kernel (device)
   std::vector<LayerWeights> layers;
   std::vector<void*> allocs;
   // one captured decode step, replayed max_new - 1 times per rollout call; rebuilt when a call
@@ -197,6 +198,7 @@ extern "C" int sapo_weights_uses_mfma(const sapo_weights* w) { return (w && w->m
 
 static int dev_alloc(sapo_weights* w, size_t bytes, void** out);
 static void drop_decode_graph(const sapo_weights* w);
+static int upload_persist_table(sapo_weights* w);
 
 extern "C" int sapo_weights_set_qkv_bias(sapo_weights* w, int layer, const float* bq, const float* bk, const float* bv,
                                          void* stream) {
@@ -212,7 +214,10 @@ extern "C" int sapo_weights_set_qkv_bias(sapo_weights* w, int layer, const float
   HIP_CK(hipMemcpyAsync(lw.bqkv, bq, q * sizeof(float), hipMemcpyDeviceToDevice, st));
   HIP_CK(hipMemcpyAsync(lw.bqkv + q, bk, kv * sizeof(float), hipMemcpyDeviceToDevice, st));
   HIP_CK(hipMemcpyAsync(lw.bqkv + q + kv, bv, kv * sizeof(float), hipMemcpyDeviceToDevice, st));
-  if (fresh) drop_decode_graph(w);   // a captured decode step holds the old kernel arguments (no bias pointer)
+  if (fresh) {
+    drop_decode_graph(w);   // a captured decode step holds the old kernel arguments (no bias pointer)
+    if (w->persist_tbl && (rc = upload_persist_table(w))) return rc;
+  }
   return SAPO_OK;
 }
 
@@ -224,6 +229,29 @@ static int dev_alloc(sapo_weights* w, size_t bytes, void** out) {
   if (e != hipSuccess) return fail(SAPO_EHIP, "hipMalloc(%zu) failed: %s", bytes, hipGetErrorString(e));
   w->allocs.push_back(p);
   *out = p;
+  return SAPO_OK;
+}
+
+// The per-layer pointer table of the persistent decode kernel.  The handle's buffers keep their addresses when it is
+// filled again, so the table is written when the handle is created and when a layer gets biases.
+static int upload_persist_table(sapo_weights* w) {
+  if (!w->mfma || w->cfg.n_layers == 0) return SAPO_OK;
+  if (d_decode_layers_prepare() != hipSuccess) {   // the step then runs as one kernel per phase
+    (void)hipGetLastError();
+    return SAPO_OK;
+  }
+  const int L = w->cfg.n_layers;
+  std::vector<PersistLayer> tbl(L);
+  for (int l = 0; l < L; ++l) {
+    const LayerWeights& lw = w->layers[l];
+    tbl[l].wqkv = (const uint4*)lw.wqkv16; tbl[l].wo = (const uint4*)lw.wo16;
+    tbl[l].wgu = (const uint4*)lw.wgu16; tbl[l].wdown = (const uint4*)lw.wdown16;
+    tbl[l].bqkv = lw.bqkv; tbl[l].ffn_norm = lw.ffn_norm;
+    tbl[l].gain_after = (l + 1 < L) ? w->layers[l + 1].attn_norm : w->final_norm;
+  }
+  int rc;
+  if ((rc = dev_alloc(w, (size_t)L * sizeof(PersistLayer), (void**)&w->persist_tbl))) return rc;
+  HIP_CK(hipMemcpy(w->persist_tbl, tbl.data(), (size_t)L * sizeof(PersistLayer), hipMemcpyHostToDevice));
   return SAPO_OK;
 }
 
@@ -293,6 +321,7 @@ static int create_impl(sapo_weights* w, const void* const* t, hipStream_t st) {
     if ((rc = dev_alloc(w, V * d * e, &w->lm_head))) return rc;
     HIP_CK(copy(w->lm_head, tail[1], V * d * e));
   }
+  if (!w->persist_tbl && (rc = upload_persist_table(w))) return rc;
   if (w->rope) return SAPO_OK;   // a refill: the table depends on the configuration only
   // rotary table in double on the host: angle(pos, i) = pos * theta^(-2 i / hd)
   const int half = c.head_dim / 2;
@@ -500,6 +529,8 @@ struct DecodeBufs {
   // more than 64 sequences: the FFN runs on the token-parallel GEMM, the down projection split over K
   int down_splits;  // 0: not used
   float* partial;   // [down_splits][S, d]
+  // up to 64 sequences: the layers of a step run as one persistent kernel (decode_persist.hip)
+  bool persistent;
 };
 
 // Splits of the down projection's K: a multiple of 8 (one residue class per XCD) that brings the grid to about
@@ -520,6 +551,10 @@ static void carve_decode(Arena& A, const sapo_weights* w, int S, DecodeBufs& db)
   db.ssq_b = A.take<float>((d / 16) * db.s_pad);
   db.down_splits = 0;
   db.partial = nullptr;
+  const char* no_persist = getenv("SAPO_NO_PERSIST");
+  db.persistent = !(no_persist && no_persist[0] == '1') && w->persist_tbl != nullptr &&
+                  d_decode_layers_supported(S, (int)d, w->cfg.n_q_heads * w->cfg.head_dim, w->cfg.n_kv_heads * w->cfg.head_dim,
+                                            w->cfg.d_ff, w->cfg.head_dim, w->cfg.n_kv_heads);
   if (S > 64 && S <= 256 && d % 128 == 0 && (2 * w->cfg.d_ff) % 128 == 0 && w->cfg.d_ff % 32 == 0) {
     db.down_splits = pick_down_splits((int)d, w->cfg.d_ff);
     if (db.down_splits > 0) db.partial = A.take<float>((size_t)db.down_splits * S * d);
@@ -530,10 +565,24 @@ static void carve_decode(Arena& A, const sapo_weights* w, int S, DecodeBufs& db)
 // db.ssq_a their sums of squares in ONE part.  On exit db.xa / db.ssq_a (d/16 parts) feed the
 // final norm, and b.h holds the final residual rows.
 static int run_layers_decode16(const sapo_weights* w, const FwdBufs& b, const DecodeBufs& db, int S, RowMap rm,
-                               const CacheBufs& cb, hipStream_t st) {
+                               const CacheBufs& cb, PersistCtl* pctl, hipStream_t st) {
   const sapo_model_config& c = w->cfg;
   const int d = c.d_model, q = c.n_q_heads * c.head_dim, kv = c.n_kv_heads * c.head_dim, F = c.d_ff;
   const int nqkv = q + 2 * kv;
+  if (db.persistent && pctl && c.n_layers > 0) {
+    PersistArgs pa{};
+    pa.n_layers = c.n_layers; pa.S = S; pa.s_pad = db.s_pad; pa.d = d; pa.q_dim = q; pa.kv_dim = kv; pa.F = F;
+    pa.n_q_heads = c.n_q_heads; pa.eps = c.rms_eps;
+    pa.layers = w->persist_tbl;
+    pa.h = b.h; pa.qkv = b.qkv; pa.attn = (uint4*)b.attn; pa.xa = (uint4*)db.xa; pa.xb = (uint4*)db.xb; pa.act = (uint4*)b.act;
+    pa.ssq_a = db.ssq_a; pa.ssq_b = db.ssq_b;
+    pa.rope = w->rope; pa.rm = rm;
+    pa.kv0 = layer_cache(w, cb, 0);
+    pa.kv_layer_stride = cb.pool_bytes * 2;
+    pa.ctl = pctl;
+    HIP_CK(d_decode_layers(pa, c.head_dim, st));
+    return SAPO_OK;
+  }
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerWeights& lw = w->layers[l];
     const KVCache kvc = layer_cache(w, cb, l);
@@ -605,6 +654,7 @@ struct RolloutPlan {
   int* lens;        // device [P]: prompt lengths (calls with prompts of different lengths)
   int own_pages;    // pages of its own per sequence
   int* last_rows;   // [P]
+  PersistCtl* pctl; // exchange counters of the persistent decode kernel (MFMA path)
   float* h_last;    // [S, d] residual of each sequence's last prompt position
   void* x_last;     // [max(P, S), d] final-norm output (T)
   float* logits;    // [max(P, S), V] (paths that materialise logits)
@@ -644,6 +694,7 @@ static void plan_rollout(const sapo_weights* w, int P, int Lp, int G, int N, cha
   pl.stop = A.take<int>((size_t)pl.S + 2);
   pl.lens = A.take<int>(P);
   pl.last_rows = A.take<int>(P);
+  pl.pctl = w->mfma ? (PersistCtl*)A.take_bytes(d_decode_layers_ctl_bytes()) : nullptr;
   carve_cache(A, w, pl.S, pl.pages_per_seq, pl.n_pages, pl.cache);
   carve_fwd(A, w, pl.M_max, pl.fwd);
   const size_t R = (size_t)(P > pl.S ? P : pl.S);
@@ -745,6 +796,7 @@ static int rollout_impl(const sapo_weights* w, const int32_t* prompts, const int
   sp.seed_lo = (uint32_t)(seed & 0xffffffffu);
   sp.seed_hi = (uint32_t)(seed >> 32);
   sp.max_new = max_new;
+  sp.vocab = c.vocab;
   sp.step = pl.step;
   sp.dyn = (const uint32_t*)(pl.step + 1);
   sp.out_tokens = out_tokens;
@@ -754,6 +806,8 @@ static int rollout_impl(const sapo_weights* w, const int32_t* prompts, const int
   if (merge_steps) {
     sp.arrivals = pl.step + 8;
     HIP_CK(g_fill_i32(pl.step + 8, 0, 1, st));
+    HIP_CK(g_fill_i32((int*)pl.pctl, 0, d_decode_layers_ctl_bytes() / 4, st));
+    sp.fault = &pl.pctl->fault;
   }
   const bool stopping = stop_token >= 0;
   HIP_CK(g_fill_i32(pl.stop, stop_token, 1, st));
@@ -824,7 +878,7 @@ static int rollout_impl(const sapo_weights* w, const int32_t* prompts, const int
     if (!merge_steps) HIP_CK(g_incr(pl.step, st));
     if (w->mfma) {
       // (the sampler's merge has already gathered the embedding rows of the previous step's tokens)
-      if ((rc2 = run_layers_decode16(w, pl.fwd, lv.dec, lv.slots, rm, pl.cache, st))) return rc2;
+      if ((rc2 = run_layers_decode16(w, pl.fwd, lv.dec, lv.slots, rm, pl.cache, pl.pctl, st))) return rc2;
       if ((rc2 = sample_step(w, pl, lv, pl.fwd.h, parts_after_layers(lv), spl, st))) return rc2;
     } else {
       HIP_CK(g_embed(dt, out_tokens, max_new, pl.step, w->embed, pl.fwd.h, S, d, st));

@@ -73,6 +73,13 @@ template <typename T> __device__ __forceinline__ float to_f32(T x) { return stat
 template <typename T> __device__ __forceinline__ T from_f32(float x) { return static_cast<T>(x); }
 template <> __device__ __forceinline__ f16 from_f32<f16>(float x) { return (f16)fminf(fmaxf(x, -65504.f), 65504.f); }
 
+// The wave's index inside its workgroup as a scalar (the same for every lane, and known to the compiler as such).
+// Kernels guard matrix-core instructions with conditions on it ("has this wave another k step"); with the index in
+// a vector register such a guard is a lane mask, the compiler may drop the branch around a short masked block, and a
+// matrix-core instruction - which ignores the lane mask - then runs on registers that hold nothing.  A scalar index
+// makes the guard a real branch.
+__device__ __forceinline__ int wave_index(int thread_index) { return __builtin_amdgcn_readfirstlane(thread_index >> 6); }
+
 __device__ __forceinline__ float wave_reduce_max(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
@@ -161,6 +168,12 @@ struct SampleParams {
   // Optional, device: the sequence behind each row of the step (see RowMap::slot_seq).  The noise is keyed on
   // the sequence, and tokens, log-probs and lengths are written at the sequence's own rows.
   const int* slot_seq = nullptr;
+  // Optional, device: a word that is non-zero once a decode step could not complete (see PersistCtl::fault).  From
+  // then on the sampler emits token -1 with log-prob 0, so the failure is visible in the call's output.
+  const unsigned* fault = nullptr;
+  // Vocabulary size (0: unknown).  A sampled id outside [0, vocab) - what a row of NaN logits leaves behind, since no
+  // score ever beats the initial one - is emitted as -1 and never used as an index.
+  int vocab = 0;
 };
 
 // Optional per-kernel timing: when switched on, every launch carries two HIP events that take
@@ -169,7 +182,8 @@ struct SampleParams {
 enum KernelId {
   KID_EMBED = 0, KID_RMSNORM, KID_GEMM_GENERIC, KID_ROPE_APPEND, KID_ATTN_GENERIC, KID_SWIGLU, KID_SAMPLE_ROWS,
   KID_SCORE_ROWS, KID_MISC, KID_GEMM_BIG, KID_LMHEAD_SCORE, KID_LMHEAD_SCORE_MERGE, KID_GEMM_SKINNY,
-  KID_LMHEAD_SAMPLE, KID_LMHEAD_SAMPLE_MERGE, KID_DECODE_ATTN, KID_FLASH_ATTN, KID_GEMM_BIG_DECODE, KID_COUNT
+  KID_LMHEAD_SAMPLE, KID_LMHEAD_SAMPLE_MERGE, KID_DECODE_ATTN, KID_FLASH_ATTN, KID_GEMM_BIG_DECODE, KID_DECODE_LAYERS,
+  KID_COUNT
 };
 extern bool g_prof_on;
 // A pair of events for one profiled launch of kernel `kid` (recorded for sapo_profile_stop).
@@ -196,6 +210,12 @@ inline hipError_t launch(int kid, void (*kernel)(KArgs...), dim3 grid, dim3 bloc
 // The one place a sampled token is written.  A sequence that has emitted the stop token keeps
 // emitting it with log-prob 0 (padding); the token returned is the one the next step embeds.
 __device__ __forceinline__ int emit_token(const SampleParams& sp, int seq, int step, int token, float logprob) {
+  if ((sp.fault && *sp.fault != 0u) || (sp.vocab > 0 && (unsigned)token >= (unsigned)sp.vocab)) {
+    const size_t o = (size_t)seq * sp.max_new + step;
+    sp.out_tokens[o] = -1;
+    sp.out_logprobs[o] = 0.f;
+    return 0;   // a valid id for the next step's embedding gather
+  }
   if (sp.stop && sp.stop[0] >= 0) {
     int* len = sp.stop + 2 + seq;
     if (*len > 0) {
@@ -387,6 +407,49 @@ hipError_t d_lmhead_merge_embed(const float* partials, int n_parts, int row_stri
                                 float* ssq_first, hipStream_t st);
 hipError_t d_decode_attention(const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* out_x16, int S,
                               int n_q_heads, hipStream_t st);
+
+// One decode step's layers as one persistent kernel (decode_persist.hip), up to 64 rows ----------------------
+// Exchange counters between the resident workgroups; zeroed once at the start of a rollout call, then only growing
+// (launch n since then starts from n x the arrivals of one launch).
+struct PersistCtl {
+  unsigned global;         // arrival groups that have completed a phase, summed over phases and launches
+  unsigned pad0[63];
+  unsigned group[8][64];   // one counter per arrival group, each in a 256-byte line of its own
+  unsigned fault;          // set when a wait ran into its time limit: the step's results are not valid
+  unsigned pad1[63];
+  unsigned launches;       // launches of the persistent kernel since the counters were zeroed (moved on by the last
+  unsigned pad2[63];       // workgroup to report the last phase of a launch)
+};
+struct PersistLayer {      // device table, one entry per layer (weights in W16 fragment order)
+  const uint4 *wqkv, *wo, *wgu, *wdown;
+  const float *bqkv, *ffn_norm, *gain_after;   // gain_after: the next layer's attention norm, or the final norm
+};
+struct PersistArgs {
+  int n_layers, S, s_pad, d, q_dim, kv_dim, F, n_q_heads;
+  float eps;
+  const PersistLayer* layers;
+  float* h;                // [S, d] residual stream
+  float* qkv;              // [S, q + 2 kv]
+  uint4* attn;             // X16 [s_pad, q]
+  uint4* xa;               // X16 [s_pad, d]: QKV projection's operand (in: from the sampler's merge; out: for the LM head)
+  uint4* xb;               // X16 [s_pad, d]: gate / up projection's operand
+  uint4* act;              // X16 [s_pad, F]
+  float* ssq_a;            // [d / 16][s_pad]; one part on entry
+  float* ssq_b;            // [d / 16][s_pad]
+  const float2* rope;
+  RowMap rm;               // decode mode
+  KVCache kv0;             // layer 0's cache
+  size_t kv_layer_stride;  // bytes from a layer's K (V) pool to the next layer's
+  PersistCtl* ctl;
+  int v_qkv, v_o, v_gu, v_down;   // blocking of each GEMM phase (set by the launcher)
+  unsigned spin_ticks;            // limit of one wait in ticks of the 100 MHz wall clock (set by the launcher)
+};
+size_t d_decode_layers_ctl_bytes();
+bool d_decode_layers_supported(int S, int d, int q_dim, int kv_dim, int F, int head_dim, int n_kv_heads);
+// kernel attributes and the residency check, once per process and outside any stream capture; the launch needs it
+hipError_t d_decode_layers_prepare();
+hipError_t d_decode_layers(PersistArgs args, int head_dim, hipStream_t st);
+
 hipError_t g_gather_last_rows(const float* h, float* out, int S, int G, int Lp, int d, hipStream_t st);
 // with per-prompt lengths (device): row p * Lp + lens[p] - 1
 hipError_t g_gather_last_rows_ragged(const float* h, float* out, int S, int G, int Lp, const int* lens, int d,

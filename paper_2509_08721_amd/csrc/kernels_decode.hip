@@ -124,7 +124,7 @@ __global__ void __launch_bounds__(512) k_skinny16(SkinnyArgs a, int n_units) {
   extern __shared__ float4 red[];
   __shared__ float s_part[512];
   constexpr int TS = 4 / TG;        // workgroups per (tile unit, token block)
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63;
   const int KS = a.K >> 5;
   // block id -> (unit, token block, token split).  Ids are dealt round-robin to the 8 XCDs; the workgroups
   // that read the same weight tiles (all token blocks and splits of a unit) sit 8 ids apart, so they run on
@@ -431,7 +431,8 @@ __global__ void __launch_bounds__(128) k_embed_x16(const int32_t* __restrict__ t
   __shared__ float red[2];
   const int row = blockIdx.x;
   const int seq = slot_seq ? slot_seq[row] : row;
-  const int tok = tokens[(size_t)seq * tok_stride + (*step - 1)];
+  int tok = tokens[(size_t)seq * tok_stride + (*step - 1)];
+  if (tok < 0) tok = 0;   // a step that reported a fault left -1 behind: never an index
   embed_row_x16(embed, tok, row, d, gain, h, xp, ssq, red);
 }
 hipError_t d_embed_x16(const int32_t* tokens, int tok_stride, const int* step, const void* embed, int M, int d,
@@ -462,7 +463,7 @@ __global__ void __launch_bounds__(512) k_lmhead_sample16(const uint4* __restrict
   extern __shared__ uint4 xs[];   // [KS][4][64]
   __shared__ float s_part[512];
   __shared__ float s_scale[64];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63;
   float sq[kSsqPerThread];
   ssq_issue(ssq, ssq_parts, s_pad, 0, sq);
   for (int i = tid; i < KS * 256; i += 512) xs[i] = Xp[i];
@@ -682,7 +683,7 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
   __shared__ __attribute__((aligned(16))) f16 knew[HD];
   __shared__ __attribute__((aligned(16))) f16 vnew[HD];
   __shared__ float sm_m[NW][16], sm_l[NW][16];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63;
   const int qcol = lane & 15, grp = lane >> 4;
   const int hkv = kv.n_kv_heads, rep = n_q_heads / hkv;
   const int s = blockIdx.x / hkv, kvh = blockIdx.x % hkv;

@@ -132,7 +132,7 @@ template <int NS = kStages, class Prologue = NoPrologue>
 __device__ __forceinline__ void big_mainloop(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int n_tblk,
                                              int KS, int tblk0, int fblk0, uint4* smem, f32x16 (&acc)[2][4],
                                              Prologue prologue = Prologue(), int st0 = 0, int n_stages = -1) {
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63;
   const int wf = wave & 1, wt = wave >> 1;
   const int nst = n_stages < 0 ? (KS >> 1) : n_stages;   // stages of 32 k; a split-K workgroup runs st0 .. st0 + nst - 1
   const uint4* src[6];
@@ -209,7 +209,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ X
     return;
   }
   f32x16 acc[2][4];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = wave_index(threadIdx.x), lane = threadIdx.x & 63;
   const int wf = wave & 1, wt = wave >> 1;
   float row_scale[4] = {1.f, 1.f, 1.f, 1.f};
   big_mainloop(Xp, Wp, (M + 31) >> 5, K >> 4, by * 8, bx * 4, smem, acc, [&]() {
@@ -321,7 +321,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_qkv_rope(const uint4* __restric
   int bx, by;
   if (!big_raster(N >> 7, (M + 255) >> 8, bx, by)) return;
   f32x16 acc[2][4];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = wave_index(threadIdx.x), lane = threadIdx.x & 63;
   const int wf = wave & 1, wt = wave >> 1;
   float row_scale[4] = {1.f, 1.f, 1.f, 1.f};
   big_mainloop(Xp, Wp, (M + 31) >> 5, K >> 4, by * 8, bx * 4, smem, acc, [&]() {
@@ -576,7 +576,7 @@ __global__ void __launch_bounds__(256, 2) k_lmhead_score(const uint4* __restrict
   const int tok0 = by * 256;
   if (tok0 >= n_rows) return;
   const int ft_begin = bx * kScoreGroup, ft_end = min(n_ft, ft_begin + kScoreGroup);
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = wave_index(threadIdx.x), lane = threadIdx.x & 63;
   const int wf = wave & 1, wt = wave >> 1;
   LseAcc lse[4];
   int target[4];
@@ -685,7 +685,7 @@ __global__ void __launch_bounds__(256, 2) k_lmhead_sample_big(const uint4* __res
   int ft, by;
   if (!big_raster(V >> 7, (n_rows + 255) >> 8, ft, by)) return;
   const int tok0 = by * 256;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = wave_index(threadIdx.x), lane = threadIdx.x & 63;
   const int wf = wave & 1, wt = wave >> 1;
   f32x16 acc[2][4];
   big_mainloop(Xp, Wp, (n_rows + 31) >> 5, K >> 4, by * 8, ft * 4, smem, acc);
@@ -780,7 +780,7 @@ template <int HD, int HPW>
 __global__ void __launch_bounds__(256, 2) k_flash_attention(const f16* __restrict__ q, RowMap rm, KVCache kv,
                                                          f16* __restrict__ out, int n_q_heads) {
   constexpr int KK = HD / 32, DT = HD / 16;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = wave_index(threadIdx.x), lane = threadIdx.x & 63;
   const int qcol = lane & 15, grp = lane >> 4;
   const int T = rm.T;
   const int qb = gridDim.x - 1 - blockIdx.x;

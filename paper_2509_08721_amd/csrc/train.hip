@@ -180,7 +180,7 @@ __global__ void __launch_bounds__(256) k_sgemm_mfma(const float* __restrict__ A,
   __shared__ __align__(16) float As[2][kGK][kGP];
   __shared__ __align__(16) float Bs[2][kGK][kGP];
   batch_offsets(bt, A, B, C);
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = wave_index(threadIdx.x), lane = threadIdx.x & 63;
   int tx, ty;
   if (!raster_tile((N + kGM - 1) / kGM, (M + kGM - 1) / kGM, tx, ty)) return;
   const int m0 = ty * kGM, n0 = tx * kGM;
@@ -362,7 +362,7 @@ __global__ void __launch_bounds__(256, RB == 2 ? 2 : 3) k_gemm_x3(const u32x4_t*
   constexpr int MI = 2 * RB;                  // 32-row MFMA tiles per wave
   __shared__ u32x4_t As[2][RB * E];
   __shared__ u32x4_t Bs[2][E];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = wave_index(threadIdx.x), lane = threadIdx.x & 63;
   int tx, ty;
   const int n_rb = (M + kGM - 1) / kGM;       // row blocks of the packed operand
   if (!raster_tile((N + kGM - 1) / kGM, (n_rb + RB - 1) / RB, tx, ty)) return;
@@ -855,7 +855,7 @@ __device__ __forceinline__ void store_acc(float* __restrict__ row, const f32x4_t
 template <int HD>
 __global__ void __launch_bounds__(256, HD == 128 ? 3 : 1) k_tattn_fwd(const float* __restrict__ qkv, int T, int hq, int hkv, float scale,
                                                    float* __restrict__ out, float* __restrict__ lse) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+  const int wave = wave_index(threadIdx.x), lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
   const int h = blockIdx.y, s = blockIdx.z, kvh = h / (hq / hkv);
   const int q0 = (blockIdx.x * 4 + wave) * 16;
   if (q0 >= T) return;
@@ -916,7 +916,7 @@ template <int HD>
 __global__ void __launch_bounds__(256, HD == 128 ? 3 : 1) k_tattn_bwd_q(const float* __restrict__ qkv, const float* __restrict__ out,
                                                      const float* __restrict__ dout, const float* __restrict__ lse, int T, int hq,
                                                      int hkv, float scale, float* __restrict__ dqkv, float* __restrict__ delta) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+  const int wave = wave_index(threadIdx.x), lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
   const int h = blockIdx.y, s = blockIdx.z, kvh = h / (hq / hkv);
   const int q0 = (blockIdx.x * 4 + wave) * 16;
   if (q0 >= T) return;
@@ -971,7 +971,7 @@ template <int HD>
 __global__ void __launch_bounds__(256, HD == 64 ? 4 : 1) k_tattn_bwd_kv(const float* __restrict__ qkv, const float* __restrict__ dout,
                                                       const float* __restrict__ lse, const float* __restrict__ delta, int T, int hq,
                                                       int hkv, float scale, float* __restrict__ dqkv) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+  const int wave = wave_index(threadIdx.x), lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
   const int kvh = blockIdx.y, s = blockIdx.z, rep = hq / hkv;
   const int k0 = (blockIdx.x * 4 + wave) * 16;
   if (k0 >= T) return;
