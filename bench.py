@@ -68,6 +68,9 @@ def per_launch_work(shape, plan, kernel, launches):
     if kernel == "k_gemm_skinny":       # the projection GEMMs of a decode layer that run on the register-direct kernel
         params = shape.matmul_params_per_layer() - (ffn_params if plan["ffn_big"] else 0.0)
         return "hbm", 2.0 * params * L * dec_steps / launches
+    if kernel == "k_decode_layers":     # every layer of a decode step in one launch: the layers' matrices + the cached K/V
+        kv = 2 * shape.kv_dim * 2 * L * S * sum(Lp + t for t in range(1, N))
+        return "hbm", (2.0 * shape.matmul_params_per_layer() * L * dec_steps + kv) / launches
     if kernel == "k_gemm_big_decode":   # gate/up and down projections of a decode layer on the token-parallel kernel
         return "hbm", 2.0 * ffn_params * L * dec_steps / launches
     if kernel == "k_lmhead_sample":     # LM head of one decode step: the whole [V, d] matrix

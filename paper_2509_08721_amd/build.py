@@ -18,7 +18,8 @@ BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsapo.so")
 
 SOURCES = ["api.hip", "kernels_generic.hip", "kernels_mfma.hip", "kernels_decode.hip", "decode_persist.hip", "train.hip"]
-FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
+# SAPO_PERSIST_TRACE=1 in the environment: diagnostic build of the persistent decode kernel (per-phase tick counters)
+FLAGS = (["-DSAPO_PERSIST_TRACE"] if os.environ.get("SAPO_PERSIST_TRACE") == "1" else []) + ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-unused-variable"]
 

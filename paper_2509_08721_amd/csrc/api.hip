@@ -551,8 +551,9 @@ static void carve_decode(Arena& A, const sapo_weights* w, int S, DecodeBufs& db)
   db.ssq_b = A.take<float>((d / 16) * db.s_pad);
   db.down_splits = 0;
   db.partial = nullptr;
-  const char* no_persist = getenv("SAPO_NO_PERSIST");
-  db.persistent = !(no_persist && no_persist[0] == '1') && w->persist_tbl != nullptr &&
+  // opt-in: measured slower than one kernel per phase on the 0.5B-class decoder
+  const char* persist = getenv("SAPO_PERSIST");
+  db.persistent = (persist && persist[0] == '1') && w->persist_tbl != nullptr &&
                   d_decode_layers_supported(S, (int)d, w->cfg.n_q_heads * w->cfg.head_dim, w->cfg.n_kv_heads * w->cfg.head_dim,
                                             w->cfg.d_ff, w->cfg.head_dim, w->cfg.n_kv_heads);
   if (S > 64 && S <= 256 && d % 128 == 0 && (2 * w->cfg.d_ff) % 128 == 0 && w->cfg.d_ff % 32 == 0) {

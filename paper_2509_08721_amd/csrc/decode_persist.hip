@@ -18,6 +18,8 @@
 // Every wait is bounded by a wall-clock limit: a workgroup that waits longer (its peers cannot all be resident,
 // e.g. because other work holds compute units) sets the fault word, stops waiting for the rest of the launch and
 // runs to the end; the sampler then emits -1 tokens, so the failure is visible and no wave is left spinning.
+// Measured on the 0.5B-class decoder the kernel does NOT beat one kernel per phase (see the design notes): it is kept
+// as an option (SAPO_PERSIST=1 in the environment), off by default.
 // The arithmetic is that of the per-phase kernels (same device functions, same summation orders): a step through
 // this kernel returns the same bytes.
 #include "decode_units.h"
@@ -30,7 +32,17 @@ constexpr int kGroups = 8;
 constexpr size_t kRedBytes = 131072;                 // the largest cross-wave reduction buffer of a GEMM unit
 constexpr size_t kPersistSmem = kRedBytes + 512 * sizeof(float);
 
+#ifdef SAPO_PERSIST_TRACE
+// Diagnostic build (-DSAPO_PERSIST_TRACE): per workgroup and phase type, summed over a run, the ticks of the 100 MHz
+// wall clock from one report to the next, those spent waiting for the previous phase, those spent in the report
+// (draining the stores, the barrier, the counters), and the number of phases.  Read with sapo_debug_persist_trace.
+__device__ unsigned long long g_trace[256][5][4];
+#endif
+
 struct Exchange {
+#ifdef SAPO_PERSIST_TRACE
+  mutable unsigned long long t_prev = 0, t_wait = 0;
+#endif
   PersistCtl* ctl;
   unsigned base_global, base_group;   // counter values when this launch began
   unsigned group_size;                // workgroups per arrival group
@@ -41,6 +53,9 @@ struct Exchange {
 
   // all workgroups have reported `phases` phases (every thread of the workgroup calls this)
   __device__ __forceinline__ void wait_for(unsigned phases) const {
+#ifdef SAPO_PERSIST_TRACE
+    const unsigned long long tw0 = wall_clock64();
+#endif
     if (threadIdx.x == 0 && *s_dead == 0) {
       const unsigned target = base_global + (unsigned)kGroups * phases;
       const unsigned long long t0 = wall_clock64();
@@ -54,9 +69,15 @@ struct Exchange {
       }
     }
     __syncthreads();
+#ifdef SAPO_PERSIST_TRACE
+    t_wait += wall_clock64() - tw0;
+#endif
   }
   // this workgroup's part of phase number `phase` (0-based) is written (every thread calls this)
   __device__ __forceinline__ void arrive(unsigned phase) const {
+#ifdef SAPO_PERSIST_TRACE
+    const unsigned long long ta0 = wall_clock64();
+#endif
     coh_drain();
     __syncthreads();
     const unsigned done = phase + 1u;
@@ -69,6 +90,14 @@ struct Exchange {
         if (og + 1u == base_global + (unsigned)kGroups * n_phases) ctl->launches = launch + 1u;
       }
     }
+#ifdef SAPO_PERSIST_TRACE
+    if (threadIdx.x == 0 && blockIdx.x < 256) {
+      const unsigned long long now = wall_clock64();
+      unsigned long long* t = g_trace[blockIdx.x][phase % 5];
+      t[0] += now - t_prev; t[1] += t_wait; t[2] += now - ta0; t[3] += 1;
+      t_prev = now; t_wait = 0;
+    }
+#endif
   }
 };
 
@@ -129,6 +158,9 @@ __global__ void __launch_bounds__(512) k_decode_layers(PersistArgs A) {
   ex.base_group = launch * ex.group_size * n_phases;
   ex.spin_ticks = A.spin_ticks;
   ex.s_dead = &s_dead;
+#ifdef SAPO_PERSIST_TRACE
+  ex.t_prev = wall_clock64();
+#endif
   const int d = A.d, F = A.F, hkv = A.kv0.n_kv_heads;
   const int nqkv = A.q_dim + 2 * A.kv_dim;
   unsigned ph = 0;   // phases before the current one
@@ -196,6 +228,20 @@ int pick_variant(int N, int K, int n_wg) {
 }
 
 }  // namespace
+
+#ifdef SAPO_PERSIST_TRACE
+}  // namespace sapo
+// out: 256 x 5 x 4 counters (see g_trace); reset != 0 clears them afterwards.  Diagnostic builds only.
+extern "C" int sapo_debug_persist_trace(unsigned long long* out, int reset) {
+  if (out && hipMemcpyFromSymbol(out, HIP_SYMBOL(sapo::g_trace), sizeof(sapo::g_trace)) != hipSuccess) return -1;
+  if (reset) {
+    static unsigned long long zeros[256 * 5 * 4];
+    if (hipMemcpyToSymbol(HIP_SYMBOL(sapo::g_trace), zeros, sizeof(zeros)) != hipSuccess) return -1;
+  }
+  return 0;
+}
+namespace sapo {
+#endif
 
 size_t d_decode_layers_ctl_bytes() { return sizeof(PersistCtl); }
 

@@ -1,4 +1,4 @@
-"""The decode step's layers as one persistent kernel (up to 64 rows) against the same step as one kernel per phase:
+"""The decode step's layers as one persistent kernel (up to 64 rows; opt-in, SAPO_PERSIST=1) against the same step as one kernel per phase:
 the two run the same arithmetic in the same order, so tokens and log-probs must be identical bit for bit; and a call
 must leave no fault mark (a wait that ran into its limit would show as -1 tokens)."""
 import contextlib
@@ -22,12 +22,12 @@ def sapo():
 
 
 @contextlib.contextmanager
-def one_kernel_per_phase():
-    os.environ["SAPO_NO_PERSIST"] = "1"
+def persistent_kernel():
+    os.environ["SAPO_PERSIST"] = "1"
     try:
         yield
     finally:
-        os.environ.pop("SAPO_NO_PERSIST", None)
+        os.environ.pop("SAPO_PERSIST", None)
 
 
 def dev(a):
@@ -50,11 +50,12 @@ def test_persistent_step_equals_one_kernel_per_phase(sapo, shape_name, P, G, Lp,
     assert gw.uses_mfma
     prompts = dev(np.random.default_rng(7).integers(0, shape.vocab, size=(P, Lp)).astype(np.int32))
     print("persistent step: %s P %d G %d Lp %d N %d" % (shape_name, P, G, Lp, N), flush=True)
-    t_p, l_p = sapo.sapo_rollout_generate(gw, prompts, G, N, temp, 99)           # eager launches, persistent kernel
-    torch.cuda.synchronize()
-    with one_kernel_per_phase():
-        t_k, l_k = sapo.sapo_rollout_generate(gw, prompts, G, N, temp, 99)
+    with persistent_kernel():
+        t_p, l_p = sapo.sapo_rollout_generate(gw, prompts, G, N, temp, 99)       # eager launches, persistent kernel
         torch.cuda.synchronize()
+        assert sapo.sapo_rollout_last_stats(gw)["steps"] == N - 1
+    t_k, l_k = sapo.sapo_rollout_generate(gw, prompts, G, N, temp, 99)
+    torch.cuda.synchronize()
     t_p, l_p, t_k, l_k = t_p.cpu().numpy(), l_p.cpu().numpy(), t_k.cpu().numpy(), l_k.cpu().numpy()
     print("   -1 tokens: persistent %d, per-phase %d; first differing step %s" % (
         int((t_p < 0).sum()), int((t_k < 0).sum()),
@@ -64,7 +65,7 @@ def test_persistent_step_equals_one_kernel_per_phase(sapo, shape_name, P, G, Lp,
     assert np.array_equal(l_p.view(np.uint32), l_k.view(np.uint32))
     # the captured step replays the same kernel
     st = torch.cuda.Stream()
-    with torch.cuda.stream(st):
+    with persistent_kernel(), torch.cuda.stream(st):
         t_g, l_g = sapo.sapo_rollout_generate(gw, prompts, G, N, temp, 99, stream=st)
         st.synchronize()
     assert np.array_equal(t_g.cpu().numpy(), t_p) and np.array_equal(l_g.cpu().numpy().view(np.uint32), l_p.view(np.uint32))
