@@ -88,6 +88,19 @@ typedef struct sapo_weights sapo_weights; /* opaque, library-owned */
  * the originals.  Allocates device memory: bf16 models whose shapes fit the MFMA tiles keep two
  * fragment-ordered copies of every matrix (one per MFMA shape, for decode and for prefill/scoring)
  * besides the embedding table, about three times the model size; other models about once.
+ *
+ * Number format of the matrix-core path (bf16 models whose shapes fit the MFMA tiles;
+ * sapo_weights_uses_mfma() tells): the packed matrices hold the bf16 weights' values as IEEE half,
+ * and activations and the KV cache are rounded to half.  Half represents a bf16 value exactly for
+ * 2^-14 <= |w| <= 65504; smaller non-zero weights keep an absolute error below 3e-8
+ * (sapo_weights_half_stats counts them).  A weight beyond +-65504, infinite or NaN cannot be held:
+ * the call then fails with SAPO_EINVAL (so does sapo_weights_update, which leaves the handle's
+ * matrices unusable until it is filled again with valid weights), and because the answer needs the
+ * packing kernels' counters the call waits for `stream` on this path.  An activation beyond
+ * +-65504 is clamped to +-65504 (never infinite): the results stay finite but no longer follow the
+ * definition; sapo_debug_half_clamped counts such values for a given batch.  The operand of a
+ * projection after an RMSNorm is (residual row x gain), normalised after the product, so the clamp
+ * is reached when |residual x gain| exceeds 65504, whatever the row's norm.
  */
 int sapo_weights_create(const sapo_model_config* cfg, const void* const* tensors, int n_tensors,
                         void* stream, sapo_weights** out);
@@ -100,6 +113,11 @@ void sapo_weights_destroy(sapo_weights* w);
  * with sapo_weights_set_qkv_bias keep their values until set again.
  */
 int sapo_weights_update(sapo_weights* w, const void* const* tensors, int n_tensors, void* stream);
+/*
+ * out2[0] = 1 when the handle runs on the 16-bit matrix-core path, else 0; out2[1] = the number of
+ * non-zero weight values below half's normal range (2^-14) at the last create / update (host ints).
+ */
+int sapo_weights_half_stats(const sapo_weights* w, int64_t* out2);
 
 /*
  * Optional biases on the query / key / value projections of one layer (the decoder family the
@@ -128,6 +146,9 @@ size_t sapo_debug_logits_workspace_bytes(const sapo_weights* w, int S, int T, in
  *   out_logprobs  dev fp32  [P*G, max_new]   log softmax(z)[token] at temperature 1
  *   workspace     dev, >= sapo_rollout_workspace_bytes(w, P, Lp, G, max_new), 256-byte aligned
  * Requires Lp >= 1, Lp + max_new <= cfg.max_seq.
+ * A step whose logits are not numbers (NaN from non-finite weights set behind the library's back, or
+ * a decode step that gave up its bounded wait) yields token -1 with log-prob 0 for that row instead
+ * of an id; the row's later steps continue from id 0.  A caller that sees -1 discards the row.
  */
 int sapo_rollout_generate(const sapo_weights* w, const int32_t* prompts, int P, int Lp, int G,
                           int max_new, float temperature, uint64_t seed, int32_t* out_tokens,
@@ -217,6 +238,19 @@ int sapo_score_logprobs_at(const sapo_weights* w, const int32_t* tokens,
 int sapo_debug_logits(const sapo_weights* w, const int32_t* tokens, int S, int T,
                       const int32_t* positions, int n, float* out_logits, void* workspace,
                       size_t workspace_bytes, void* stream);
+
+/*
+ * Test hook for the number format stated at sapo_weights_create: runs the teacher-forced forward
+ * pass of Sec. 3.2 over tokens[S, T] and counts, over every layer, the half-precision activation
+ * values that sit at the clamp +-65504 (projection operands, rotated queries, attention outputs,
+ * SwiGLU outputs, the LM head's operand).  0 means no activation of this batch was clamped (a
+ * value that is exactly 65504 by itself also counts).  Always 0 for models on the shape-generic
+ * kernels, which keep activations in the weights' own type.  Synchronises `stream`.
+ *   tokens dev int32 [S, T]; out_count host; workspace dev, >= sapo_debug_logits_workspace_bytes(w, S, T, 1)
+ */
+int sapo_debug_half_clamped(const sapo_weights* w, const int32_t* tokens, int S, int T,
+                            int64_t* out_count, void* workspace, size_t workspace_bytes,
+                            void* stream);
 
 /*
  * Training-set assembly (Sec. 3.2; Algorithm 1 "Assemble training set": SampleSelf and

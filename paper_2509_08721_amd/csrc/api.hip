@@ -130,6 +130,9 @@ struct sapo_weights {
   float* final_norm = nullptr;
   float2* rope = nullptr;        // [max_seq][hd / 2] (cos, sin)
   PersistLayer* persist_tbl = nullptr;   // MFMA path: per-layer pointers for the persistent decode kernel (device)
+  unsigned* pack_range = nullptr;        // MFMA path, device: [0] values outside half's range, [1] below its normal range
+  long long half_tiny = 0;               // [1] of the last packing
+  mutable unsigned long long* clamp_counter = nullptr;   // device; non-null while a debug forward counts clamped activations
   std::vector<LayerWeights> layers;
   std::vector<void*> allocs;
   // one captured decode step, replayed max_new - 1 times per rollout call; rebuilt when a call
@@ -266,6 +269,10 @@ static int create_impl(sapo_weights* w, const void* const* t, hipStream_t st) {
   };
   if ((rc = dev_alloc(w, V * d * e, &w->embed))) return rc;
   HIP_CK(copy(w->embed, t[0], V * d * e));
+  if (w->mfma) {
+    if ((rc = dev_alloc(w, 2 * sizeof(unsigned), (void**)&w->pack_range))) return rc;
+    HIP_CK(g_fill_i32((int*)w->pack_range, 0, 2, st));
+  }
   w->layers.resize(c.n_layers);
   for (int l = 0; l < c.n_layers; ++l) {
     const void* const* lt = t + 1 + 9 * l;
@@ -279,13 +286,13 @@ static int create_impl(sapo_weights* w, const void* const* t, hipStream_t st) {
     HIP_CK(copy(lw.attn_norm, lt[0], d * 4));
     HIP_CK(copy(lw.ffn_norm, lt[5], d * 4));
     if (w->mfma) {
-      HIP_CK(m_pack_weight(lt[1], (int)q, (int)d, lw.wqkv, 0, 1, st));
-      HIP_CK(m_pack_weight(lt[2], (int)kv, (int)d, lw.wqkv, (int)(q / 32), 1, st));
-      HIP_CK(m_pack_weight(lt[3], (int)kv, (int)d, lw.wqkv, (int)((q + kv) / 32), 1, st));
-      HIP_CK(m_pack_weight(lt[4], (int)d, (int)q, lw.wo, 0, 1, st));
-      HIP_CK(m_pack_weight(lt[6], (int)F, (int)d, lw.wgu, 0, 2, st));
-      HIP_CK(m_pack_weight(lt[7], (int)F, (int)d, lw.wgu, 1, 2, st));
-      HIP_CK(m_pack_weight(lt[8], (int)d, (int)F, lw.wdown, 0, 1, st));
+      HIP_CK(m_pack_weight(lt[1], (int)q, (int)d, lw.wqkv, 0, 1, w->pack_range, st));
+      HIP_CK(m_pack_weight(lt[2], (int)kv, (int)d, lw.wqkv, (int)(q / 32), 1, w->pack_range, st));
+      HIP_CK(m_pack_weight(lt[3], (int)kv, (int)d, lw.wqkv, (int)((q + kv) / 32), 1, w->pack_range, st));
+      HIP_CK(m_pack_weight(lt[4], (int)d, (int)q, lw.wo, 0, 1, w->pack_range, st));
+      HIP_CK(m_pack_weight(lt[6], (int)F, (int)d, lw.wgu, 0, 2, w->pack_range, st));
+      HIP_CK(m_pack_weight(lt[7], (int)F, (int)d, lw.wgu, 1, 2, w->pack_range, st));
+      HIP_CK(m_pack_weight(lt[8], (int)d, (int)F, lw.wdown, 0, 1, w->pack_range, st));
       if ((rc = dev_alloc(w, (q + 2 * kv) * d * e, &lw.wqkv16))) return rc;
       if ((rc = dev_alloc(w, d * q * e, &lw.wo16))) return rc;
       if ((rc = dev_alloc(w, 2 * F * d * e, &lw.wgu16))) return rc;
@@ -312,7 +319,7 @@ static int create_impl(sapo_weights* w, const void* const* t, hipStream_t st) {
   HIP_CK(copy(w->final_norm, tail[0], d * 4));
   if (w->mfma) {
     if ((rc = dev_alloc(w, V * d * e, &w->lm_head))) return rc;
-    HIP_CK(m_pack_weight(c.tied_embeddings ? t[0] : tail[1], (int)V, (int)d, w->lm_head, 0, 1, st));
+    HIP_CK(m_pack_weight(c.tied_embeddings ? t[0] : tail[1], (int)V, (int)d, w->lm_head, 0, 1, w->pack_range, st));
     if ((rc = dev_alloc(w, V * d * e, &w->lm_head16))) return rc;
     HIP_CK(d_pack_weight16(c.tied_embeddings ? t[0] : tail[1], (int)V, (int)d, w->lm_head16, 0, 1, st));
   } else if (c.tied_embeddings) {
@@ -320,6 +327,17 @@ static int create_impl(sapo_weights* w, const void* const* t, hipStream_t st) {
   } else {
     if ((rc = dev_alloc(w, V * d * e, &w->lm_head))) return rc;
     HIP_CK(copy(w->lm_head, tail[1], V * d * e));
+  }
+  if (w->mfma) {
+    // The matrix-core kernels hold the weights as IEEE half.  A value half cannot hold would be clamped (or carried
+    // as NaN) with no trace in the results: refuse it here.  Costs one wait for the packing kernels.
+    unsigned range[2] = {0, 0};
+    HIP_CK(hipMemcpyAsync(range, w->pack_range, sizeof(range), hipMemcpyDeviceToHost, st));
+    HIP_CK(hipStreamSynchronize(st));
+    w->half_tiny = range[1];
+    if (range[0])
+      return fail(SAPO_EINVAL, "%u weight values are outside the range of IEEE half (|w| > 65504, infinite or NaN): "
+                  "the 16-bit matrix-core path cannot hold them", range[0]);
   }
   if (!w->persist_tbl && (rc = upload_persist_table(w))) return rc;
   if (w->rope) return SAPO_OK;   // a refill: the table depends on the configuration only
@@ -498,8 +516,12 @@ static int run_layers_big(const sapo_weights* w, const FwdBufs& b, int M, RowMap
     } else {
       qkv_ep.ssq_in = b.ssq; qkv_ep.ssq_parts = parts; qkv_ep.norm_dim = (float)d; qkv_ep.eps = c.rms_eps;
     }
+    unsigned long long* const clamped = w->clamp_counter;   // debug forward only: count the half values at the clamp
+    if (clamped) HIP_CK(g_count_half_at_limit(b.a, M, d, 1, clamped, st));
     HIP_CK(m_gemm_qkv_rope(b.a, lw.wqkv, M, q + 2 * kv, d, qkv_ep, st));
+    if (clamped) HIP_CK(g_count_half_at_limit(b.q, M, q, 0, clamped, st));
     HIP_CK(m_flash_attention(b.q, rm, kvc, b.attn, M / rm.T, c.n_q_heads, st));
+    if (clamped) HIP_CK(g_count_half_at_limit(b.attn, M, q, 1, clamped, st));
     BigEpi o_ep{BIG_ADD_F32, b.h, d, nullptr};
     BigEpi gu_ep{BIG_SWIGLU, nullptr, 0, (f16*)b.act};
     if (fold) {
@@ -508,7 +530,9 @@ static int run_layers_big(const sapo_weights* w, const FwdBufs& b, int M, RowMap
     }
     HIP_CK(m_gemm_big(b.attn, lw.wo, M, d, q, o_ep, st));
     if (!fold) HIP_CK(m_rmsnorm_x32(b.h, lw.ffn_norm, c.rms_eps, b.a, M, d, nullptr, st));
+    if (clamped) HIP_CK(g_count_half_at_limit(b.a, M, d, 1, clamped, st));
     HIP_CK(m_gemm_big(b.a, lw.wgu, M, 2 * F, d, gu_ep, st));
+    if (clamped) HIP_CK(g_count_half_at_limit(b.act, M, F, 1, clamped, st));
     BigEpi down_ep{BIG_ADD_F32, b.h, d, nullptr};
     if (fold && l + 1 < c.n_layers) {
       down_ep.gain_next = w->layers[l + 1].attn_norm; down_ep.xn_out = (f16*)b.a; down_ep.ssq_out = b.ssq;
@@ -1201,6 +1225,46 @@ extern "C" int sapo_debug_logits(const sapo_weights* w, const int32_t* tokens, i
     HIP_CK(g_rmsnorm(c.dtype, pl.fwd.h, w->final_norm, c.rms_eps, pl.x, n, c.d_model, pl.src_rows, st));
     HIP_CK(g_gemm(c.dtype, pl.x, w->lm_head, out_logits, n, c.vocab, c.d_model, c.vocab, EPI_STORE_F32, st));
   }
+  return SAPO_OK;
+}
+
+extern "C" int sapo_weights_half_stats(const sapo_weights* w, int64_t* out2) {
+  if (!w || !out2) return fail(SAPO_EINVAL, "NULL argument");
+  out2[0] = w->mfma ? 1 : 0;
+  out2[1] = w->half_tiny;
+  return SAPO_OK;
+}
+
+extern "C" int sapo_debug_half_clamped(const sapo_weights* w, const int32_t* tokens, int S, int T, int64_t* out_count,
+                                       void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_score_args(w, S, T);
+  if (rc) return rc;
+  if (!tokens || !out_count || !workspace) return fail(SAPO_EINVAL, "NULL buffer");
+  if (((uintptr_t)workspace & 255) != 0) return fail(SAPO_EINVAL, "workspace must be 256-byte aligned");
+  if (!w->mfma) {          // the shape-generic kernels keep activations in the weights' own type: nothing is clamped
+    *out_count = 0;
+    return SAPO_OK;
+  }
+  ScorePlan pl;
+  plan_score(w, S, T, S, 1, (char*)workspace, pl);
+  if (workspace_bytes < pl.bytes) return fail(SAPO_EWORKSPACE, "workspace %zu < required %zu", workspace_bytes, pl.bytes);
+  hipStream_t st = (hipStream_t)stream;
+  const sapo_model_config& c = w->cfg;
+  unsigned long long* counter = (unsigned long long*)(pl.count + 2);   // pl.count is 256-byte aligned, 64 ints long
+  HIP_CK(g_fill_i32(pl.count + 2, 0, 2, st));
+  HIP_CK(g_page_table(pl.cache.page_table, S, pl.pages_per_seq, 1, 0, S, st));
+  if ((rc = clear_cache(pl.cache, c.n_layers, st))) return rc;
+  w->clamp_counter = counter;
+  rc = forward_chunk(w, pl, tokens, 0, S, st);
+  w->clamp_counter = nullptr;
+  if (rc) return rc;
+  // the operand of the LM head: every row's final norm
+  HIP_CK(m_rmsnorm_x32(pl.fwd.h, w->final_norm, c.rms_eps, pl.x, S * T, c.d_model, nullptr, st));
+  HIP_CK(g_count_half_at_limit(pl.x, S * T, c.d_model, 1, counter, st));
+  unsigned long long n = 0;
+  HIP_CK(hipMemcpyAsync(&n, counter, sizeof(n), hipMemcpyDeviceToHost, st));
+  HIP_CK(hipStreamSynchronize(st));
+  *out_count = (int64_t)n;
   return SAPO_OK;
 }
 

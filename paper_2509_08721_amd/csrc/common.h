@@ -286,6 +286,10 @@ hipError_t g_copy_partial_page_ragged(int dtype, KVCache kv, int n_prompts, int 
 hipError_t g_page_table_ragged(int* pt, int n_seq, int pages_per_seq, int G, int fp_max, int own, int n_prompts,
                                const int* lens, hipStream_t st);
 hipError_t g_fill_i32(int* p, int v, size_t n, hipStream_t st);
+// counter += number of IEEE-half elements equal to +-65504 (the value the float -> half conversion clamps to) among the
+// rows < rows_valid of buf; x32 != 0: buf is in 32-row fragment order (blocks of 32 rows x 16 k), else row-major
+hipError_t g_count_half_at_limit(const void* buf, int rows_valid, int row_len, int x32, unsigned long long* counter,
+                                 hipStream_t st);
 hipError_t g_fill_f32(float* p, float v, size_t n, hipStream_t st);
 hipError_t g_incr(int* p, hipStream_t st);
 hipError_t g_masked_rows(const uint8_t* mask, int T, int s0, int ns, int* rows /*[ns*T,2]*/, int* src_rows /*[ns*T]*/,
@@ -343,7 +347,7 @@ struct QkvEpi {
 };
 hipError_t m_gemm_qkv_rope(const void* Xp, const void* Wp, int M, int N, int K, const QkvEpi& epi, hipStream_t st);
 
-hipError_t m_pack_weight(const void* src, int n_rows, int K, void* dst, int dst_tile0, int dst_tile_stride,
+hipError_t m_pack_weight(const void* src, int n_rows, int K, void* dst, int dst_tile0, int dst_tile_stride, unsigned* range,
                          hipStream_t st);
 // Xp: tokens in X32 fragment order (rows padded to a multiple of 32); Wp: weights in W32 order
 hipError_t m_gemm_big(const void* Xp, const void* Wp, int M, int N, int K, BigEpi epi, hipStream_t st);

@@ -26,6 +26,37 @@ __global__ void k_fill_f32(float* p, float v, size_t n) {
 }
 __global__ void k_incr(int* p) { if (threadIdx.x == 0) *p += 1; }
 
+// 8 halfs per thread; a wave adds its count with one atomic
+__global__ void k_count_half_at_limit(const uint4* __restrict__ buf, size_t n_chunks, int rows_valid, int row_len, int x32,
+                                      unsigned long long* __restrict__ counter) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  unsigned hits = 0;
+  if (i < n_chunks) {
+    // row of chunk i: row-major rows hold row_len / 8 chunks; fragment order holds 64 chunks per (32 rows x 16 k) block
+    const size_t row = x32 ? (i / ((size_t)64 * (row_len >> 4))) * 32 + (i & 31) : i / (size_t)(row_len >> 3);
+    if (row < (size_t)rows_valid) {
+      const uint4 v = buf[i];
+      const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        hits += ((w[e] & 0x7fffu) == 0x7bffu);
+        hits += (((w[e] >> 16) & 0x7fffu) == 0x7bffu);
+      }
+    }
+  }
+  for (int off = 32; off > 0; off >>= 1) hits += __shfl_xor(hits, off, 64);
+  if ((threadIdx.x & 63) == 0 && hits) atomicAdd(counter, (unsigned long long)hits);
+}
+hipError_t g_count_half_at_limit(const void* buf, int rows_valid, int row_len, int x32, unsigned long long* counter,
+                                 hipStream_t st) {
+  if (rows_valid <= 0 || row_len <= 0) return hipSuccess;
+  if (row_len % 16 != 0) return hipErrorInvalidValue;
+  const size_t rows = x32 ? ((size_t)rows_valid + 31) / 32 * 32 : (size_t)rows_valid;
+  const size_t n_chunks = rows * (size_t)row_len / 8;
+  return launch(KID_MISC, k_count_half_at_limit, dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, st, (const uint4*)buf,
+                n_chunks, rows_valid, row_len, x32, counter);
+}
+
 hipError_t g_fill_i32(int* p, int v, size_t n, hipStream_t st) {
   if (n == 0) return hipSuccess;
   return launch(KID_MISC, k_fill_i32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, v, n);

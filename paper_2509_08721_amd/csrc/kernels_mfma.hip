@@ -38,8 +38,10 @@ __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)
 // weight packing: row-major bf16 [n_rows, K] -> half, fragment order, 32-row tiles placed at
 // dst_tile0 + t * dst_tile_stride (stride 2 interleaves gate and up tiles).
 // ---------------------------------------------------------------------------------------
+// range[0] counts values half cannot hold (|w| > 65504, infinities, NaN: they would be clamped or carried as NaN),
+// range[1] non-zero values below half's smallest normal number 2^-14 (kept with an absolute error below 3e-8).
 __global__ void k_pack_weight(const bf16* __restrict__ src, int n_rows, int K, uint4* __restrict__ dst, int tile0,
-                              int tile_stride) {
+                              int tile_stride, unsigned* __restrict__ range) {
   const int KS = K >> 4;
   const size_t total = (size_t)(n_rows >> 5) * KS * 64;
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -53,13 +55,24 @@ __global__ void k_pack_weight(const bf16* __restrict__ src, int n_rows, int K, u
 #pragma unroll
   for (int e = 0; e < 8; ++e) o.h[e] = from_f32<f16>((float)v.v[e]);   // bf16 value -> half
   dst[((size_t)(tile0 + t * tile_stride) * KS + ks) * 64 + lane] = o.u;
+  if (range) {
+    unsigned too_large = 0, tiny = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float a = fabsf((float)v.v[e]);
+      too_large += !(a <= 65504.f);
+      tiny += (a > 0.f && a < 6.103515625e-05f);
+    }
+    if (too_large) atomicAdd(range, too_large);
+    if (tiny) atomicAdd(range + 1, tiny);
+  }
 }
 hipError_t m_pack_weight(const void* src, int n_rows, int K, void* dst, int dst_tile0, int dst_tile_stride,
-                         hipStream_t st) {
+                         unsigned* range, hipStream_t st) {
   const size_t total = (size_t)(n_rows / 32) * (K / 16) * 64;
   if (total == 0) return hipSuccess;
   return launch(KID_MISC, k_pack_weight, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16*)src, n_rows, K, (uint4*)dst, dst_tile0,
-                                                                  dst_tile_stride);
+                                                                  dst_tile_stride, range);
 }
 
 // =======================================================================================

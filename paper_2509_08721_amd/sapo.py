@@ -118,6 +118,10 @@ def load_library() -> C.CDLL:
     lib.sapo_trainer_read.restype = i32
     lib.sapo_debug_logits.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, sz, vp]
     lib.sapo_debug_logits.restype = i32
+    lib.sapo_debug_half_clamped.argtypes = [vp, vp, i32, i32, vp, vp, sz, vp]
+    lib.sapo_debug_half_clamped.restype = i32
+    lib.sapo_weights_half_stats.argtypes = [vp, vp]
+    lib.sapo_weights_half_stats.restype = i32
     lib.sapo_debug_gumbel.argtypes = [u64, u32, u32, u32, i32, vp, vp]
     lib.sapo_debug_gumbel.restype = i32
     lib.sapo_profile_kernel_count.argtypes = []
@@ -145,7 +149,7 @@ EXPORTED = ["sapo_weights_create", "sapo_weights_update", "sapo_weights_destroy"
             "sapo_policy_update",
             "sapo_trainer_export", "sapo_trainer_steps", "sapo_trainer_read", "sapo_trainer_set_matmul_pieces",
             "sapo_trainer_set_qkv_bias", "sapo_trainer_get_qkv_bias",
-            "sapo_debug_logits", "sapo_debug_gumbel", "sapo_debug_read_probe", "sapo_device_info", "sapo_last_error", "sapo_profile_kernel_count",
+            "sapo_debug_logits", "sapo_debug_half_clamped", "sapo_weights_half_stats", "sapo_debug_gumbel", "sapo_debug_read_probe", "sapo_device_info", "sapo_last_error", "sapo_profile_kernel_count",
             "sapo_profile_kernel_name", "sapo_profile_start", "sapo_profile_stop"]
 
 
@@ -739,6 +743,26 @@ def sapo_debug_logits(w: Weights, tokens, positions: Sequence[Sequence[int]], st
                                  _aligned_ptr(ws), nbytes, _stream_ptr(stream)))
     torch.cuda.synchronize()
     return out
+
+
+def sapo_debug_half_clamped(w: Weights, tokens, stream=None) -> int:
+    """Half-precision activation values at the clamp (+-65504) in a teacher-forced forward pass over tokens [S, T]."""
+    lib = load_library()
+    S, T = int(tokens.shape[0]), int(tokens.shape[1])
+    nbytes = int(lib.sapo_debug_logits_workspace_bytes(w.handle, S, T, 1))
+    ws = _workspace(nbytes)
+    out = C.c_int64(0)
+    _check(lib.sapo_debug_half_clamped(w.handle, tokens.data_ptr(), S, T, C.byref(out), _aligned_ptr(ws), nbytes,
+                                       _stream_ptr(stream)))
+    return int(out.value)
+
+
+def sapo_weights_half_stats(w: Weights) -> dict:
+    """{"half_path": the handle runs on the 16-bit matrix-core path, "below_normal_range": non-zero weight values
+    under 2^-14 at the last create / update}."""
+    out = (C.c_int64 * 2)()
+    _check(load_library().sapo_weights_half_stats(w.handle, out))
+    return {"half_path": bool(out[0]), "below_normal_range": int(out[1])}
 
 
 def sapo_debug_gumbel(seed: int, seq: int, step: int, v0: int, n: int, stream=None):
