@@ -623,10 +623,17 @@ def run_workload(args, workload, n_steps, n_warmup, cpu_baseline, probes):
     if probes and not (args.layers or args.new_tokens):
         read_probe = {"GBs": round(sapo.sapo_debug_read_probe(), 1), "bytes": 1 << 31,
                       "note": "streaming read of 2 GiB, 16-byte non-temporal loads; the roofline fractions use the published 8000 GB/s"}
+    # context for the MFMA fractions: what a kernel that only issues MFMAs on registers sustains (not a denominator)
+    mfma_probe = None
+    if probes and not (args.layers or args.new_tokens):
+        tf = sapo.sapo_debug_mfma_probe()
+        mfma_probe = {"TFLOPs": round(tf, 1), "frac_of_peak": round(tf / MFMA_16BIT_PEAK_TFLOPS, 3),
+                      "note": "32x32x16 half MFMAs on registers only, two waves per SIMD, N(0,1) operands; the roofline "
+                              "fractions use the published 2500 TFLOP/s"}
     props = torch.cuda.get_device_properties(0)
     device = {"name": props.name, "memory_GB": round(props.total_memory / 2 ** 30), **sapo.sapo_device_info()}
     out.update({"roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "surrogate_loss": surrogate,
-                "hbm_read_probe": read_probe, "device": device, "setup_s": round(setup_s, 1)})
+                "hbm_read_probe": read_probe, "mfma_probe": mfma_probe, "device": device, "setup_s": round(setup_s, 1)})
     gw.close()
     return out
 

@@ -427,6 +427,15 @@ int sapo_device_info(int32_t* out4);
  * can reach on the machine, as context for the HBM roofline figures.  sink: dev, 4 bytes (normally left alone).
  */
 int sapo_debug_read_probe(const void* buf, size_t bytes, void* sink, void* stream);
+/*
+ * Measurement hook: one launch of a kernel that only issues matrix-core instructions on registers (n_workgroups
+ * workgroups of 4 waves, two resident per compute unit; per wave `iters` rounds of 8 independent 32x32x16 half
+ * MFMAs on the 6 KiB at `operands`: dev, 16-byte aligned, half values, read once).  *out_flops (host) = the
+ * flops the launch executes; timed by the caller, it gives the rate the matrix cores sustain on the machine with
+ * these operand values, as context for the MFMA roofline figures.  sink: dev, 4 bytes (normally left alone).
+ */
+int sapo_debug_mfma_probe(const void* operands, int n_workgroups, int iters, double* out_flops, void* sink,
+                          void* stream);
 
 /*
  * Test hook: the sampler's noise.  out[i] = g for (seed, seq, step, v = v0 + i), i < n.

@@ -1347,6 +1347,51 @@ extern "C" int sapo_debug_read_probe(const void* buf, size_t bytes, void* sink, 
   return SAPO_OK;
 }
 
+// Measurement hook: matrix-core instructions on registers only (what the matrix cores sustain on this machine when
+// nothing else is asked of the compute unit).  Every workgroup of 4 waves runs `iters` rounds of 8 independent
+// 32x32x16 half MFMAs per wave on operands read once from `operands`.
+namespace {
+typedef _Float16 probe_f16x8 __attribute__((ext_vector_type(8)));
+typedef float probe_f32x16 __attribute__((ext_vector_type(16)));
+__global__ void __launch_bounds__(256, 2) k_mfma_probe(const probe_f16x8* __restrict__ operands, int iters,
+                                                       float* __restrict__ sink) {
+  const int lane = threadIdx.x & 63;
+  probe_f16x8 a[4], b[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) a[i] = operands[i * 64 + lane];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) b[i] = operands[(4 + i) * 64 + lane];
+  probe_f32x16 acc[2][4];
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int y = 0; y < 4; ++y)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[x][y][v] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+      for (int y = 0; y < 4; ++y) acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_f16(b[x], a[y], acc[x][y], 0, 0, 0);
+  }
+  float chk = 0.f;
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int y = 0; y < 4; ++y) chk += acc[x][y][0];
+  if (chk == 1.2345e-30f) sink[0] = chk;   // keeps the MFMAs alive; practically never taken
+}
+}  // namespace
+extern "C" int sapo_debug_mfma_probe(const void* operands, int n_workgroups, int iters, double* out_flops, void* sink,
+                                     void* stream) {
+  if (!operands || !sink || !out_flops || n_workgroups <= 0 || iters <= 0 || ((uintptr_t)operands & 15) != 0)
+    return fail(SAPO_EINVAL, "bad arguments");
+  HIP_CK(sapo::launch(sapo::KID_MISC, k_mfma_probe, dim3(n_workgroups), dim3(256), 0, (hipStream_t)stream,
+                      (const probe_f16x8*)operands, iters, (float*)sink));
+  *out_flops = (double)n_workgroups * 4.0 * iters * 8.0 * (2.0 * 32 * 32 * 16);
+  return SAPO_OK;
+}
+
 extern "C" int sapo_debug_gumbel(uint64_t seed, uint32_t seq, uint32_t step, uint32_t v0, int n, float* out,
                                  void* stream) {
   if (n < 0 || !out) return fail(SAPO_EINVAL, "bad arguments");

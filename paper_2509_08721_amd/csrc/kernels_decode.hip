@@ -658,6 +658,18 @@ hipError_t d_lmhead_merge_embed(const float* partials, int n_parts, int row_stri
                 0, sp, (const bf16*)embed, d, gain_first, h, (uint4*)xp_first, ssq_first);
 }
 
+// global -> LDS copy of one wave-wide 1 KiB block (lane l's 16 bytes land at lds + 16 l); completion is awaited with
+// wait_vmcnt_d (requests complete in order)
+__device__ __forceinline__ unsigned lds_addr16(const void* p) {
+  return (unsigned)(size_t)(const __attribute__((address_space(3))) void*)p;
+}
+__device__ __forceinline__ void dma16_lds(const void* g, unsigned lds) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds), "v"(g) : "memory");
+}
+template <int N> __device__ __forceinline__ void wait_vmcnt_d() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
 // =======================================================================================
 // Decode attention over the paged KV cache, fused with rotary + KV append of the new token.
 // One workgroup (NW waves) per (sequence, KV head); all query heads of the group ride together as
@@ -672,13 +684,19 @@ hipError_t d_lmhead_merge_embed(const float* partials, int n_parts, int row_stri
 // Queries, keys, values and probabilities are IEEE half (the cache's type on this path); the
 // output goes out as half in X16 order (the O projection's operand).
 // ---------------------------------------------------------------------------------------
-template <int HD, int NW, int PD>
+// LDS = true is the measured alternative to the register-direct K/V reads: the same requests go global -> LDS
+// (one 1 KiB block per fragment, lane l's 16 bytes at 16 l, so the read back is conflict-free) into PD slots per
+// wave and are read into registers pair by pair; the requests in flight and the order of the arithmetic are the
+// same, the results bit-identical.
+template <int HD, int NW, int PD, bool LDS>
 __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __restrict__ qkv,
                                                                const float2* __restrict__ rope, RowMap rm, KVCache kv,
                                                                uint4* __restrict__ out, int n_q_heads) {
   constexpr int KK = HD / 32;   // k steps of S^T = K Q^T
   constexpr int DT = HD / 16;   // 16-row tiles of O^T
-  extern __shared__ float sm_o[];   // [NW][HD][16]
+  constexpr int NFRAG = 2 * KK + DT;                        // 1 KiB fragments of one page pair
+  constexpr size_t kOStride = LDS ? (size_t)PD * NFRAG * 256 : (size_t)HD * 16;   // floats between two waves' outputs
+  extern __shared__ float sm_o[];   // [NW][HD][16]; LDS: [NW][PD][NFRAG] KiB of staged pairs, a wave's output over its slot 0
   __shared__ __attribute__((aligned(16))) f16 qs[16 * HD];
   __shared__ __attribute__((aligned(16))) f16 knew[HD];
   __shared__ __attribute__((aligned(16))) f16 vnew[HD];
@@ -714,10 +732,41 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) vf[dt].u = *(const uint4*)(vp + (size_t)(dt * 16 + (lane & 15)) * kPageTokens);
   };
-  Frag16 kf[PD][2][KK], vf[PD][DT];
+  // the same requests into slot j of this wave's staging area
+  const unsigned stage0 = LDS ? __builtin_amdgcn_readfirstlane(lds_addr16(sm_o) + (unsigned)wave * PD * NFRAG * 1024u) : 0u;
+  auto stage_pair = [&](int pp, int j) {
+    const int pa = pt[2 * pp];
+    const int pb = pt[min(2 * pp + 1, last_page)];
+    const unsigned dst = stage0 + (unsigned)j * NFRAG * 1024u;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int r = lane & 15;
+      const int ptok = 8 * (r >> 2) + 4 * t + (r & 3);
+      const f16* kp = kpool + (size_t)(ptok < 16 ? pa : pb) * page_elems + ((size_t)kvh * kPageTokens + (ptok & 15)) * HD;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) dma16_lds(kp + kk * 32 + grp * 8, dst + (unsigned)(t * KK + kk) * 1024u);
+    }
+    const f16* vp = vpool + (size_t)(grp < 2 ? pa : pb) * page_elems + (size_t)kvh * HD * kPageTokens + (grp & 1) * 8;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) dma16_lds(vp + (size_t)(dt * 16 + (lane & 15)) * kPageTokens, dst + (unsigned)(2 * KK + dt) * 1024u);
+  };
+  auto read_pair = [&](int j, Frag16 (&kf)[2][KK], Frag16 (&vf)[DT]) {
+    const uint4* src = (const uint4*)sm_o + ((size_t)(wave * PD + j) * NFRAG) * 64 + lane;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) kf[t][kk].u = src[(t * KK + kk) * 64];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) vf[dt].u = src[(2 * KK + dt) * 64];
+  };
+  constexpr int PR = LDS ? 1 : PD;   // register sets of fragments
+  Frag16 kf[PR][2][KK], vf[PR][DT];
 #pragma unroll
   for (int j = 0; j < PD; ++j)
-    if (wave + NW * j < npairs) load_pair(wave + NW * j, kf[j], vf[j]);
+    if (wave + NW * j < npairs) {
+      if constexpr (LDS) stage_pair(wave + NW * j, j);
+      else load_pair(wave + NW * j, kf[j], vf[j]);
+    }
 
   // ---- rotary on the group's queries and the new key; append key / value -------------------
   {
@@ -765,12 +814,29 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
     if (c0 > 0) {
 #pragma unroll
       for (int j = 0; j < PD; ++j)
-        if (wave + NW * (c0 + j) < npairs) load_pair(wave + NW * (c0 + j), kf[j], vf[j]);
+        if (wave + NW * (c0 + j) < npairs) {
+          if constexpr (LDS) stage_pair(wave + NW * (c0 + j), j);   // every slot has been read into registers and used
+          else load_pair(wave + NW * (c0 + j), kf[j], vf[j]);
+        }
     }
+    // pairs of this chunk that exist for this wave (LDS: requests issued above, in slot order)
+    const int n_chunk = min(PD, (npairs - (wave + NW * c0) + NW - 1) / NW);
 #pragma unroll
-    for (int j = 0; j < PD; ++j) {
-      const int pp = wave + NW * (c0 + j);
+    for (int jj = 0; jj < PD; ++jj) {
+      const int pp = wave + NW * (c0 + jj);
       if (pp >= npairs) break;
+      constexpr int kSetStride = LDS ? 0 : 1;
+      const int j = jj * kSetStride;          // register set: the pair's own, or the single one of the LDS variant
+      if constexpr (LDS) {
+        // slot jj has landed once at most the later slots' requests are outstanding (requests complete in order)
+        const int newer = n_chunk - 1 - jj;
+        if (newer >= 3) wait_vmcnt_d<3 * NFRAG>();
+        else if (newer == 2) wait_vmcnt_d<2 * NFRAG>();
+        else if (newer == 1) wait_vmcnt_d<NFRAG>();
+        else wait_vmcnt_d<0>();
+        asm volatile("" ::: "memory");
+        read_pair(jj, kf[0], vf[0]);
+      }
       // the token appended by this workgroup comes from LDS, not from the global copy written above
       if (pp == pos / 32) {
 #pragma unroll
@@ -843,7 +909,7 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) sm_o[((size_t)wave * HD + dt * 16 + grp * 4 + i) * 16 + qcol] = o[dt][i];
+    for (int i = 0; i < 4; ++i) sm_o[(size_t)wave * kOStride + (size_t)(dt * 16 + grp * 4 + i) * 16 + qcol] = o[dt][i];
   __syncthreads();
   // thread -> (query q, 8 consecutive head dims): one 16-byte chunk of the X16 output.  Waves that
   // had no page pair carry (m = -inf, l = 0, o = 0) and drop out of the merge.
@@ -862,31 +928,40 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
     for (int e = 0; e < 8; ++e) {
       float num = 0.f;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) num += wgt[w] * sm_o[((size_t)w * HD + d0 + e) * 16 + q];
+      for (int w = 0; w < NW; ++w) num += wgt[w] * sm_o[(size_t)w * kOStride + (size_t)(d0 + e) * 16 + q];
       ov.h[e] = from_f32<f16>(num * inv);
     }
     out[x16_chunk(s, (kvh * rep + q) * HD + d0, KSo)] = ov.u;
   }
 }
 
-template <int HD, int NW, int PD>
+template <int HD, int NW, int PD, bool LDS = false>
 static hipError_t launch_decode_attention(const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* out, int S,
                                           int n_q_heads, hipStream_t st) {
   static bool attr_done = false;
-  const size_t smem = (size_t)NW * HD * 16 * sizeof(float);
+  static_assert(PD <= 4, "the LDS variant's waits cover up to 4 slots");
+  const size_t smem = LDS ? (size_t)NW * PD * (HD / 8) * 1024 : (size_t)NW * HD * 16 * sizeof(float);
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_decode_attention16<HD, NW, PD>,
+    hipError_t e = hipFuncSetAttribute((const void*)k_decode_attention16<HD, NW, PD, LDS>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  return launch(KID_DECODE_ATTN, k_decode_attention16<HD, NW, PD>, dim3(S * kv.n_kv_heads), dim3(NW * 64), smem, st, qkv, rope,
+  return launch(KID_DECODE_ATTN, k_decode_attention16<HD, NW, PD, LDS>, dim3(S * kv.n_kv_heads), dim3(NW * 64), smem, st, qkv, rope,
                 rm, kv, (uint4*)out, n_q_heads);
 }
 
 hipError_t d_decode_attention(const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* out, int S, int n_q_heads,
                               hipStream_t st) {
-  if (kv.head_dim == 64) return launch_decode_attention<64, 8, 3>(qkv, rope, rm, kv, out, S, n_q_heads, st);
+  // SAPO_ATTN_LDS=1 in the environment: the LDS-staged variant, kept as the measured alternative (0.5B-class decoder,
+  // 64 sequences, same waves and pairs in flight: 6.6 against 5.8 us per launch at contexts 128..383, 12.5 against
+  // 11.4 us at 512..1535).  Two slots of 8 KiB per wave are what 8 waves fit into the 160 KiB.  Read per call, so
+  // that a test can switch it; a captured decode step keeps the variant it was captured with.
+  const char* lds_env = getenv("SAPO_ATTN_LDS");
+  if (kv.head_dim == 64) {
+    if (lds_env && lds_env[0] == '1') return launch_decode_attention<64, 8, 2, true>(qkv, rope, rm, kv, out, S, n_q_heads, st);
+    return launch_decode_attention<64, 8, 3>(qkv, rope, rm, kv, out, S, n_q_heads, st);
+  }
   if (kv.head_dim == 128) {
     // more workgroups than compute units: 4-wave workgroups with one page pair in flight per wave leave room for
     // two per compute unit, so the whole grid is resident at once (1.5B, 256 sequences: 24.7 us against 29.8)

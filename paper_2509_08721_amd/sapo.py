@@ -73,6 +73,8 @@ def load_library() -> C.CDLL:
     lib.sapo_device_info.restype = i32
     lib.sapo_debug_read_probe.argtypes = [vp, sz, vp, vp]
     lib.sapo_debug_read_probe.restype = i32
+    lib.sapo_debug_mfma_probe.argtypes = [vp, i32, i32, vp, vp, vp]
+    lib.sapo_debug_mfma_probe.restype = i32
     lib.sapo_weights_update.argtypes = [vp, C.POINTER(vp), i32, vp]
     lib.sapo_weights_update.restype = i32
     lib.sapo_rollout_last_stats.argtypes = [vp, vp]
@@ -149,7 +151,7 @@ EXPORTED = ["sapo_weights_create", "sapo_weights_update", "sapo_weights_destroy"
             "sapo_policy_update",
             "sapo_trainer_export", "sapo_trainer_steps", "sapo_trainer_read", "sapo_trainer_set_matmul_pieces",
             "sapo_trainer_set_qkv_bias", "sapo_trainer_get_qkv_bias",
-            "sapo_debug_logits", "sapo_debug_half_clamped", "sapo_weights_half_stats", "sapo_debug_gumbel", "sapo_debug_read_probe", "sapo_device_info", "sapo_last_error", "sapo_profile_kernel_count",
+            "sapo_debug_logits", "sapo_debug_half_clamped", "sapo_weights_half_stats", "sapo_debug_gumbel", "sapo_debug_read_probe", "sapo_debug_mfma_probe", "sapo_device_info", "sapo_last_error", "sapo_profile_kernel_count",
             "sapo_profile_kernel_name", "sapo_profile_start", "sapo_profile_stop"]
 
 
@@ -725,6 +727,26 @@ def sapo_debug_read_probe(nbytes: int = 1 << 31, repeats: int = 5) -> float:
         if i > 0:
             ms.append(ev[0].elapsed_time(ev[1]))
     return nbytes / (float(np.median(ms)) * 1e-3) / 1e9
+
+
+def sapo_debug_mfma_probe(std: float = 1.0, iters: int = 4096, repeats: int = 5, seed: int = 7) -> float:
+    """TFLOP/s of a kernel that only issues half-precision MFMAs on registers (operands N(0, std^2)): median of
+    `repeats` timed launches of 4096 workgroups."""
+    torch = _torch()
+    lib = load_library()
+    ops = torch.from_numpy((np.random.default_rng(seed).standard_normal(6 * 64 * 8) * std).astype(np.float16)).cuda()
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    flops = C.c_double(0.0)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ms = []
+    for i in range(repeats + 1):
+        ev[0].record()
+        _check(lib.sapo_debug_mfma_probe(ops.data_ptr(), 4096, iters, C.byref(flops), sink.data_ptr(), _stream_ptr(None)))
+        ev[1].record()
+        torch.cuda.synchronize()
+        if i > 0:
+            ms.append(ev[0].elapsed_time(ev[1]))
+    return flops.value / (float(np.median(ms)) * 1e-3) / 1e12
 
 
 def sapo_debug_logits(w: Weights, tokens, positions: Sequence[Sequence[int]], stream=None):
