@@ -130,7 +130,7 @@ struct sapo_weights {
   float* final_norm = nullptr;
   float2* rope = nullptr;        // [max_seq][hd / 2] (cos, sin)
   PersistLayer* persist_tbl = nullptr;   // MFMA path: per-layer pointers for the persistent decode kernel (device)
-  unsigned* pack_range = nullptr;        // MFMA path, device: [0] values outside half's range, [1] below its normal range
+  unsigned* pack_range = nullptr;        // MFMA path, device: kPackRangeSlots pairs (outside half's range, below its normal range)
   long long half_tiny = 0;               // [1] of the last packing
   mutable unsigned long long* clamp_counter = nullptr;   // device; non-null while a debug forward counts clamped activations
   std::vector<LayerWeights> layers;
@@ -270,8 +270,8 @@ static int create_impl(sapo_weights* w, const void* const* t, hipStream_t st) {
   if ((rc = dev_alloc(w, V * d * e, &w->embed))) return rc;
   HIP_CK(copy(w->embed, t[0], V * d * e));
   if (w->mfma) {
-    if ((rc = dev_alloc(w, 2 * sizeof(unsigned), (void**)&w->pack_range))) return rc;
-    HIP_CK(g_fill_i32((int*)w->pack_range, 0, 2, st));
+    if ((rc = dev_alloc(w, 2 * kPackRangeSlots * sizeof(unsigned), (void**)&w->pack_range))) return rc;
+    HIP_CK(g_fill_i32((int*)w->pack_range, 0, 2 * kPackRangeSlots, st));
   }
   w->layers.resize(c.n_layers);
   for (int l = 0; l < c.n_layers; ++l) {
@@ -331,13 +331,15 @@ static int create_impl(sapo_weights* w, const void* const* t, hipStream_t st) {
   if (w->mfma) {
     // The matrix-core kernels hold the weights as IEEE half.  A value half cannot hold would be clamped (or carried
     // as NaN) with no trace in the results: refuse it here.  Costs one wait for the packing kernels.
-    unsigned range[2] = {0, 0};
-    HIP_CK(hipMemcpyAsync(range, w->pack_range, sizeof(range), hipMemcpyDeviceToHost, st));
+    std::vector<unsigned> slots(2 * kPackRangeSlots);
+    HIP_CK(hipMemcpyAsync(slots.data(), w->pack_range, slots.size() * sizeof(unsigned), hipMemcpyDeviceToHost, st));
     HIP_CK(hipStreamSynchronize(st));
-    w->half_tiny = range[1];
-    if (range[0])
-      return fail(SAPO_EINVAL, "%u weight values are outside the range of IEEE half (|w| > 65504, infinite or NaN): "
-                  "the 16-bit matrix-core path cannot hold them", range[0]);
+    unsigned long long too_large = 0, tiny = 0;
+    for (int i = 0; i < kPackRangeSlots; ++i) { too_large += slots[2 * i]; tiny += slots[2 * i + 1]; }
+    w->half_tiny = (long long)tiny;
+    if (too_large)
+      return fail(SAPO_EINVAL, "%llu weight values are outside the range of IEEE half (|w| > 65504, infinite or NaN): "
+                  "the 16-bit matrix-core path cannot hold them", too_large);
   }
   if (!w->persist_tbl && (rc = upload_persist_table(w))) return rc;
   if (w->rope) return SAPO_OK;   // a refill: the table depends on the configuration only

@@ -347,6 +347,7 @@ struct QkvEpi {
 };
 hipError_t m_gemm_qkv_rope(const void* Xp, const void* Wp, int M, int N, int K, const QkvEpi& epi, hipStream_t st);
 
+constexpr int kPackRangeSlots = 512;   // pairs of range counters behind m_pack_weight's `range`
 hipError_t m_pack_weight(const void* src, int n_rows, int K, void* dst, int dst_tile0, int dst_tile_stride, unsigned* range,
                          hipStream_t st);
 // Xp: tokens in X32 fragment order (rows padded to a multiple of 32); Wp: weights in W32 order

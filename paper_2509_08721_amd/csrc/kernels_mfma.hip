@@ -38,14 +38,15 @@ __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)
 // weight packing: row-major bf16 [n_rows, K] -> half, fragment order, 32-row tiles placed at
 // dst_tile0 + t * dst_tile_stride (stride 2 interleaves gate and up tiles).
 // ---------------------------------------------------------------------------------------
-// range[0] counts values half cannot hold (|w| > 65504, infinities, NaN: they would be clamped or carried as NaN),
-// range[1] non-zero values below half's smallest normal number 2^-14 (kept with an absolute error below 3e-8).
+// range: kPackRangeSlots (512) pairs of counters, to be summed by the reader.  The first of a pair counts values half
+// cannot hold (|w| > 65504, infinities, NaN: they would be clamped or carried as NaN), the second non-zero values
+// below half's smallest normal number 2^-14 (kept with an absolute error below 3e-8).
 __global__ void k_pack_weight(const bf16* __restrict__ src, int n_rows, int K, uint4* __restrict__ dst, int tile0,
                               int tile_stride, unsigned* __restrict__ range) {
   const int KS = K >> 4;
   const size_t total = (size_t)(n_rows >> 5) * KS * 64;
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= total) return;
+  if (idx >= total) return;   // total is a multiple of 64: a wave leaves or stays as a whole
   const int lane = (int)(idx & 63);
   const int ks = (int)((idx >> 6) % KS);
   const int t = (int)((idx >> 6) / KS);
@@ -63,8 +64,15 @@ __global__ void k_pack_weight(const bf16* __restrict__ src, int n_rows, int K, u
       too_large += !(a <= 65504.f);
       tiny += (a > 0.f && a < 6.103515625e-05f);
     }
-    if (too_large) atomicAdd(range, too_large);
-    if (tiny) atomicAdd(range + 1, tiny);
+    // one atomic per wave and counter, only when there is something to add, spread over kPackRangeSlots pairs of
+    // counters (small weights are common: with one pair every wave of a 0.5B model queues on the same address)
+    unsigned packed = (too_large << 16) | tiny;          // at most 8 each per lane
+    for (int off = 32; off > 0; off >>= 1) packed += __shfl_xor(packed, off, 64);   // at most 512 each per wave
+    if (lane == 0) {
+      unsigned* slot = range + 2 * (((unsigned)(idx >> 6) * 2654435761u) >> (32 - 9));
+      if (packed >> 16) atomicAdd(slot, packed >> 16);
+      if (packed & 0xffffu) atomicAdd(slot + 1, packed & 0xffffu);
+    }
   }
 }
 hipError_t m_pack_weight(const void* src, int n_rows, int K, void* dst, int dst_tile0, int dst_tile_stride,
