@@ -79,6 +79,11 @@ def per_launch_work(shape, plan, kernel, launches):
         kv_layer = 2 * shape.kv_dim * 2
         tot = kv_layer * S * sum(Lp + t for t in range(1, N)) * L
         return "hbm", tot / launches
+    if kernel == "k_decode_attention_shared":   # the same with a prompt's full page pairs read once per group of siblings
+        kv_layer = 2 * shape.kv_dim * 2
+        shared_tokens = (Lp // 32) * 32
+        tot = kv_layer * L * sum(P * shared_tokens + S * (Lp + t - shared_tokens) for t in range(1, N))
+        return "hbm", tot / launches
     if kernel == "k_gemm_big":          # projection GEMMs of prefill + scoring (+ LM head where logits are materialised)
         fl = 2.0 * L * shape.matmul_params_per_layer() * big_tokens
         if plan["rollout"] and not plan["fused_lm"]:

@@ -75,7 +75,7 @@ void prof_events(int kid, hipEvent_t* e0, hipEvent_t* e1) {
 static const char* const kKernelNames[KID_COUNT] = {
     "k_embed", "k_rmsnorm", "k_gemm", "k_rope_append", "k_attention", "k_swiglu", "k_sample_rows", "k_score_rows",
     "misc", "k_gemm_big", "k_lmhead_score", "k_lmhead_score_merge", "k_gemm_skinny", "k_lmhead_sample",
-    "k_lmhead_sample_merge", "k_decode_attention", "k_flash_attention", "k_gemm_big_decode", "k_decode_layers"};
+    "k_lmhead_sample_merge", "k_decode_attention", "k_flash_attention", "k_gemm_big_decode", "k_decode_layers", "k_decode_attention_shared"};
 
 extern "C" int sapo_profile_kernel_count(void) { return KID_COUNT; }
 extern "C" const char* sapo_profile_kernel_name(int i) { return (i >= 0 && i < KID_COUNT) ? kKernelNames[i] : ""; }
@@ -142,6 +142,7 @@ struct sapo_weights {
     const void* out_tokens = nullptr; const void* out_logprobs = nullptr; const void* workspace = nullptr;
     int P = 0, Lp = 0, G = 0, N = 0;
     bool ragged = false;
+    int share_pairs = 0;           // page pairs of the prompt read once per group of siblings (0: the plain attention)
     hipGraph_t graph = nullptr;
     hipGraphExec_t exec = nullptr;
   };
@@ -592,7 +593,7 @@ static void carve_decode(Arena& A, const sapo_weights* w, int S, DecodeBufs& db)
 // db.ssq_a their sums of squares in ONE part.  On exit db.xa / db.ssq_a (d/16 parts) feed the
 // final norm, and b.h holds the final residual rows.
 static int run_layers_decode16(const sapo_weights* w, const FwdBufs& b, const DecodeBufs& db, int S, RowMap rm,
-                               const CacheBufs& cb, PersistCtl* pctl, hipStream_t st) {
+                               const CacheBufs& cb, PersistCtl* pctl, const ShareArgs* share, hipStream_t st) {
   const sapo_model_config& c = w->cfg;
   const int d = c.d_model, q = c.n_q_heads * c.head_dim, kv = c.n_kv_heads * c.head_dim, F = c.d_ff;
   const int nqkv = q + 2 * kv;
@@ -620,7 +621,9 @@ static int run_layers_decode16(const sapo_weights* w, const FwdBufs& b, const De
     a.ssq_in = db.ssq_a; a.ssq_parts = (l == 0) ? 1 : db.down_splits > 0 ? (d + 1023) / 1024 : d / 16;
     a.out_f32 = b.qkv; a.ldc = nqkv; a.bias = lw.bqkv;
     HIP_CK(d_gemm_skinny(a, SKM_STORE, st));
-    HIP_CK(d_decode_attention(b.qkv, w->rope, rm, kvc, b.attn, S, c.n_q_heads, st));
+    ShareArgs sh_l;
+    if (share && share->prefix_pairs > 0) { sh_l = *share; sh_l.layer = l; sh_l.n_layers = c.n_layers; }
+    HIP_CK(d_decode_attention(b.qkv, w->rope, rm, kvc, b.attn, S, c.n_q_heads, &sh_l, st));
     // output projection + residual; emits the FFN norm's operand
     SkinnyArgs o{};
     o.n_rows = S; o.s_pad = db.s_pad;
@@ -682,6 +685,8 @@ struct RolloutPlan {
   int own_pages;    // pages of its own per sequence
   int* last_rows;   // [P]
   PersistCtl* pctl; // exchange counters of the persistent decode kernel (MFMA path)
+  float* attn_pre;       // [S][Hq][hd + 4]: the prompt's part of the decode attention (shared-prompt variant)
+  unsigned* attn_flags;  // [P x Hkv]: launch number whose prompt part is complete
   float* h_last;    // [S, d] residual of each sequence's last prompt position
   void* x_last;     // [max(P, S), d] final-norm output (T)
   float* logits;    // [max(P, S), V] (paths that materialise logits)
@@ -722,6 +727,8 @@ static void plan_rollout(const sapo_weights* w, int P, int Lp, int G, int N, cha
   pl.lens = A.take<int>(P);
   pl.last_rows = A.take<int>(P);
   pl.pctl = w->mfma ? (PersistCtl*)A.take_bytes(d_decode_layers_ctl_bytes()) : nullptr;
+  pl.attn_pre = w->mfma ? A.take<float>((size_t)pl.S * c.n_q_heads * (c.head_dim + 4)) : nullptr;
+  pl.attn_flags = w->mfma ? A.take<unsigned>((size_t)P * c.n_kv_heads) : nullptr;
   carve_cache(A, w, pl.S, pl.pages_per_seq, pl.n_pages, pl.cache);
   carve_fwd(A, w, pl.M_max, pl.fwd);
   const size_t R = (size_t)(P > pl.S ? P : pl.S);
@@ -836,6 +843,23 @@ static int rollout_impl(const sapo_weights* w, const int32_t* prompts, const int
     HIP_CK(g_fill_i32((int*)pl.pctl, 0, d_decode_layers_ctl_bytes() / 4, st));
     sp.fault = &pl.pctl->fault;
   }
+  // Decode attention that reads the prompt's full pages once per group of siblings (a second kind of workgroup in the
+  // same launch): measured slower than the plain kernel on this hardware (the hand-over between workgroups of one
+  // launch costs more than the shared bytes save: 17.8 against 11.6 us per launch at contexts 512..1535), so it is
+  // off unless SAPO_SHARE_PREFIX_MIN_PAIRS names the number of shared page pairs from which to use it.  Needs prompts
+  // of one length, head dim 64, all siblings' query heads within the prefix workgroup's columns, the per-phase step.
+  ShareArgs share;
+  if (w->mfma && !lens_host && G >= 2 && c.head_dim == 64 && c.n_layers > 0 &&
+      G * (c.n_q_heads / c.n_kv_heads) <= kSharePrefixMaxColumns && !pl.dec.persistent) {
+    const char* e = getenv("SAPO_SHARE_PREFIX_MIN_PAIRS");
+    const int min_pairs = e ? atoi(e) : 0;
+    const int pairs = pl.full_prompt_pages / 2;
+    if (min_pairs > 0 && pairs >= min_pairs) {
+      share.G = G; share.prefix_pairs = pairs; share.n_prefix = P * c.n_kv_heads;
+      share.pre = pl.attn_pre; share.flags = pl.attn_flags; share.fault = &pl.pctl->fault;
+      HIP_CK(g_fill_i32((int*)pl.attn_flags, 0, (size_t)share.n_prefix, st));
+    }
+  }
   const bool stopping = stop_token >= 0;
   HIP_CK(g_fill_i32(pl.stop, stop_token, 1, st));
   HIP_CK(g_fill_i32(pl.stop + 1, 0, (size_t)S + 1, st));
@@ -905,7 +929,9 @@ static int rollout_impl(const sapo_weights* w, const int32_t* prompts, const int
     if (!merge_steps) HIP_CK(g_incr(pl.step, st));
     if (w->mfma) {
       // (the sampler's merge has already gathered the embedding rows of the previous step's tokens)
-      if ((rc2 = run_layers_decode16(w, pl.fwd, lv.dec, lv.slots, rm, pl.cache, pl.pctl, st))) return rc2;
+      // the prompt's pages once per group of siblings: the full batch only (rows = sequences)
+      const ShareArgs* sh = (share.prefix_pairs > 0 && lv.slot_seq == nullptr && lv.slots == S) ? &share : nullptr;
+      if ((rc2 = run_layers_decode16(w, pl.fwd, lv.dec, lv.slots, rm, pl.cache, pl.pctl, sh, st))) return rc2;
       if ((rc2 = sample_step(w, pl, lv, pl.fwd.h, parts_after_layers(lv), spl, st))) return rc2;
     } else {
       HIP_CK(g_embed(dt, out_tokens, max_new, pl.step, w->embed, pl.fwd.h, S, d, st));
@@ -920,7 +946,8 @@ static int rollout_impl(const sapo_weights* w, const int32_t* prompts, const int
   auto step_graph = [&](int li, hipGraphExec_t& exec) -> int {
     sapo_weights::DecodeGraph& dg = w->dgraph[li];
     if (!(dg.valid && dg.out_tokens == out_tokens && dg.out_logprobs == out_logprobs && dg.workspace == workspace &&
-          dg.P == P && dg.Lp == Lp && dg.G == G && dg.N == max_new && dg.ragged == ragged)) {
+          dg.P == P && dg.Lp == Lp && dg.G == G && dg.N == max_new && dg.ragged == ragged &&
+          dg.share_pairs == share.prefix_pairs)) {
       if (li == 0) {
         drop_decode_graph(w);   // the smaller batches' graphs belong to the same call shape
       } else if (dg.valid) {
@@ -946,7 +973,7 @@ static int rollout_impl(const sapo_weights* w, const int32_t* prompts, const int
       }
       dg.valid = true;
       dg.out_tokens = out_tokens; dg.out_logprobs = out_logprobs; dg.workspace = workspace;
-      dg.P = P; dg.Lp = Lp; dg.G = G; dg.N = max_new; dg.ragged = ragged;
+      dg.P = P; dg.Lp = Lp; dg.G = G; dg.N = max_new; dg.ragged = ragged; dg.share_pairs = share.prefix_pairs;
       dg.graph = graph; dg.exec = ex;
     }
     exec = dg.exec;

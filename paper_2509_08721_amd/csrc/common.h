@@ -183,7 +183,7 @@ enum KernelId {
   KID_EMBED = 0, KID_RMSNORM, KID_GEMM_GENERIC, KID_ROPE_APPEND, KID_ATTN_GENERIC, KID_SWIGLU, KID_SAMPLE_ROWS,
   KID_SCORE_ROWS, KID_MISC, KID_GEMM_BIG, KID_LMHEAD_SCORE, KID_LMHEAD_SCORE_MERGE, KID_GEMM_SKINNY,
   KID_LMHEAD_SAMPLE, KID_LMHEAD_SAMPLE_MERGE, KID_DECODE_ATTN, KID_FLASH_ATTN, KID_GEMM_BIG_DECODE, KID_DECODE_LAYERS,
-  KID_COUNT
+  KID_DECODE_ATTN_SHARED, KID_COUNT
 };
 extern bool g_prof_on;
 // A pair of events for one profiled launch of kernel `kid` (recorded for sapo_profile_stop).
@@ -410,8 +410,25 @@ hipError_t d_lmhead_sample(const void* Wp, const void* Xp, int K, int V, const f
 hipError_t d_lmhead_merge_embed(const float* partials, int n_parts, int row_stride, int n_rows, SampleParams sp,
                                 const void* embed, int d, const float* gain_first, float* h, void* xp_first,
                                 float* ssq_first, hipStream_t st);
+// Decode attention with the prompt's pages read once per group of siblings (rows = P prompts x G siblings in order,
+// every sequence at the same position, the siblings' page tables pointing at the same pages for the first
+// 2 * prefix_pairs pages).  The launch then holds two kinds of workgroups: block ids 0 .. n_prefix - 1, one per
+// (prompt, KV head), cover those pages for all siblings' query heads at once and leave per (row, query head) the
+// unnormalised partial result (running max, sum, weighted values) in `pre`; the others, one per (row, KV head), cover
+// the row's remaining tokens and fold the partial result in once the prefix workgroup's flag shows this launch's number.
+struct ShareArgs {
+  int G = 0;                  // siblings per prompt
+  int prefix_pairs = 0;       // shared page pairs (32 tokens each); 0: no sharing
+  int n_prefix = 0;           // P x KV heads
+  float* pre = nullptr;       // [rows][n_q_heads][head_dim + 4]: m, l, -, -, o[head_dim]
+  unsigned* flags = nullptr;  // [n_prefix], zero when the call begins; launch number = step * n_layers + layer + 1
+  unsigned* fault = nullptr;  // set when a wait gave up
+  int layer = 0, n_layers = 1;
+  unsigned spin_ticks = 20000000u;   // bound of the wait in ticks of the 100 MHz wall clock
+};
+constexpr int kSharePrefixMaxColumns = 64;   // G x (query heads per KV head) the prefix workgroups can take
 hipError_t d_decode_attention(const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* out_x16, int S,
-                              int n_q_heads, hipStream_t st);
+                              int n_q_heads, const ShareArgs* share, hipStream_t st);
 
 // One decode step's layers as one persistent kernel (decode_persist.hip), up to 64 rows ----------------------
 // Exchange counters between the resident workgroups; zeroed once at the start of a rollout call, then only growing

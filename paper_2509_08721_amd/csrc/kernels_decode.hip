@@ -17,6 +17,7 @@
 // multiplies its accumulators by rsqrt(mean(h^2) + eps) (the scale is per token, so it commutes
 // with the contraction).
 #include "common.h"
+#include "coherent.h"
 
 namespace sapo {
 
@@ -684,14 +685,182 @@ template <int N> __device__ __forceinline__ void wait_vmcnt_d() {
 // Queries, keys, values and probabilities are IEEE half (the cache's type on this path); the
 // output goes out as half in X16 order (the O projection's operand).
 // ---------------------------------------------------------------------------------------
+// The prefix workgroup of the shared-prompt variant (see ShareArgs): block (prompt p, KV head kvh) walks the page
+// pairs 0 .. prefix_pairs - 1 of the prompt once, with the query heads of all G siblings as columns of up to four
+// 16-column MFMA tiles (column c = sibling c / rep, head c % rep), and leaves per column the merged, unnormalised
+// (max, sum, weighted values) of its waves in sh.pre, stored write-through; then it publishes the launch number.
+template <int HD, int NW>
+__device__ __forceinline__ void attention_prefix_role(const float* __restrict__ qkv, const float2* __restrict__ rope,
+                                                      const RowMap& rm, const KVCache& kv, int n_q_heads,
+                                                      const ShareArgs& sh, float* sm_o, f16* qs64, float (*sm_m)[16],
+                                                      float (*sm_l)[16]) {
+  constexpr int KK = HD / 32, DT = HD / 16, NT = kSharePrefixMaxColumns / 16;
+  const int tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63;
+  const int qcol = lane & 15, grp = lane >> 4;
+  const int hkv = kv.n_kv_heads, rep = n_q_heads / hkv;
+  const int p = blockIdx.x / hkv, kvh = blockIdx.x % hkv;
+  const int row0 = p * sh.G;
+  const int ncols = sh.G * rep;
+  int seq, pos;
+  rm.get(row0, seq, pos);             // every sibling is at this position; the shared pages are the same for all
+  const int* pt = kv.page_table + (size_t)seq * kv.pages_per_seq;
+  const f16* kpool = (const f16*)kv.k;
+  const f16* vpool = (const f16*)kv.v;
+  const size_t page_elems = (size_t)hkv * kPageTokens * HD;
+  auto load_pair = [&](int pp, Frag16 (&kf)[2][KK], Frag16 (&vf)[DT]) {
+    const int pa = pt[2 * pp], pb = pt[2 * pp + 1];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int r = lane & 15;
+      const int ptok = 8 * (r >> 2) + 4 * t + (r & 3);
+      const f16* kp = kpool + (size_t)(ptok < 16 ? pa : pb) * page_elems + ((size_t)kvh * kPageTokens + (ptok & 15)) * HD;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) kf[t][kk].u = *(const uint4*)(kp + kk * 32 + grp * 8);
+    }
+    const f16* vp = vpool + (size_t)(grp < 2 ? pa : pb) * page_elems + (size_t)kvh * HD * kPageTokens + (grp & 1) * 8;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) vf[dt].u = *(const uint4*)(vp + (size_t)(dt * 16 + (lane & 15)) * kPageTokens);
+  };
+  Frag16 kf[2][2][KK], vf[2][DT];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+    if (wave + NW * j < sh.prefix_pairs) load_pair(wave + NW * j, kf[j], vf[j]);
+  // rotated queries of every column (zero rows for the columns past G x rep)
+  {
+    const int half = HD / 2;
+    const size_t row_floats = (size_t)(n_q_heads + 2 * hkv) * HD;
+    for (int idx = tid; idx < NT * 16 * half; idx += NW * 64) {
+      const int cc = idx / half, i = idx % half;
+      float r1 = 0.f, r2 = 0.f;
+      if (cc < ncols) {
+        const float* x = qkv + (size_t)(row0 + cc / rep) * row_floats + (size_t)(kvh * rep + cc % rep) * HD;
+        const float2 cs = rope[(size_t)pos * half + i];
+        r1 = x[i] * cs.x - x[i + half] * cs.y;
+        r2 = x[i + half] * cs.x + x[i] * cs.y;
+      }
+      qs64[cc * HD + i] = from_f32<f16>(r1);
+      qs64[cc * HD + i + half] = from_f32<f16>(r2);
+    }
+  }
+  __syncthreads();
+  const float scale = 1.0f / sqrtf((float)HD);
+  float m_run[NT], l_run[NT];
+  f32x4 o[NT][DT];
+#pragma unroll
+  for (int jt = 0; jt < NT; ++jt) {
+    m_run[jt] = -INFINITY; l_run[jt] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) o[jt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  for (int c0 = 0; wave + NW * c0 < sh.prefix_pairs; c0 += 2) {
+    if (c0 > 0) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        if (wave + NW * (c0 + j) < sh.prefix_pairs) load_pair(wave + NW * (c0 + j), kf[j], vf[j]);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      if (wave + NW * (c0 + j) >= sh.prefix_pairs) break;
+#pragma unroll
+      for (int jt = 0; jt < NT; ++jt) {
+        Frag16 qf[KK];
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) qf[kk].u = *(const uint4*)(qs64 + (jt * 16 + qcol) * HD + kk * 32 + grp * 8);
+        f32x4 sc[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          sc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int kk = 0; kk < KK; ++kk) sc[t] = mfma16(kf[j][t][kk], qf[kk], sc[t]);
+        }
+        // every token of a shared pair lies inside every sibling's context: nothing to mask
+        float pv[8];
+        float m_loc = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          pv[e] = sc[e >> 2][e & 3] * scale;
+          m_loc = fmaxf(m_loc, pv[e]);
+        }
+        m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 16, 64));
+        m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, 64));
+        const float m_new = fmaxf(m_run[jt], m_loc);
+        const float alpha = __expf(m_run[jt] - m_new);
+        float psum = 0.f;
+        Frag16 pf;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float pe = __expf(pv[e] - m_new);
+          psum += pe;
+          pf.h[e] = (f16)pe;
+        }
+        l_run[jt] = l_run[jt] * alpha + psum;
+        m_run[jt] = m_new;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) o[jt][dt][i] *= alpha;
+          o[jt][dt] = mfma16(vf[j][dt], pf, o[jt][dt]);
+        }
+      }
+    }
+  }
+  // merge the waves tile by tile; a wave without a pair carries (-inf, 0, 0) and drops out (wave 0 always has pair 0)
+#pragma unroll
+  for (int jt = 0; jt < NT; ++jt) {
+    float l = l_run[jt];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    if (jt > 0) __syncthreads();   // the previous tile's sums have been read
+    if (grp == 0) { sm_m[wave][qcol] = m_run[jt]; sm_l[wave][qcol] = l; }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sm_o[((size_t)wave * HD + dt * 16 + grp * 4 + i) * 16 + qcol] = o[jt][dt][i];
+    __syncthreads();
+    for (int idx = tid; idx < 16 * (HD / 8); idx += NW * 64) {
+      const int q = idx / (HD / 8), d0 = (idx % (HD / 8)) * 8;
+      const int cc = jt * 16 + q;
+      if (cc >= ncols) continue;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) mx = fmaxf(mx, sm_m[w][q]);
+      float den = 0.f, wgt[NW];
+#pragma unroll
+      for (int w = 0; w < NW; ++w) { wgt[w] = __expf(sm_m[w][q] - mx); den += wgt[w] * sm_l[w][q]; }
+      float num[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        num[e] = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) num[e] += wgt[w] * sm_o[((size_t)w * HD + d0 + e) * 16 + q];
+      }
+      const size_t base = ((size_t)(row0 + cc / rep) * n_q_heads + kvh * rep + cc % rep) * (HD + 4);
+      st_f4<true>(sh.pre, (base + 4 + d0) * sizeof(float), make_float4(num[0], num[1], num[2], num[3]));
+      st_f4<true>(sh.pre, (base + 8 + d0) * sizeof(float), make_float4(num[4], num[5], num[6], num[7]));
+      if (d0 == 0) {
+        st_f32<true>(sh.pre, base * sizeof(float), mx);
+        st_f32<true>(sh.pre, (base + 1) * sizeof(float), den);
+      }
+    }
+  }
+  coh_drain();        // this thread's write-through stores have completed ...
+  __syncthreads();    // ... and everybody's
+  if (tid == 0) {
+    const unsigned launch_no = (unsigned)(*rm.step) * (unsigned)sh.n_layers + (unsigned)sh.layer + 1u;
+    (void)__hip_atomic_exchange(&sh.flags[blockIdx.x], launch_no, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
 // LDS = true is the measured alternative to the register-direct K/V reads: the same requests go global -> LDS
 // (one 1 KiB block per fragment, lane l's 16 bytes at 16 l, so the read back is conflict-free) into PD slots per
 // wave and are read into registers pair by pair; the requests in flight and the order of the arithmetic are the
 // same, the results bit-identical.
-template <int HD, int NW, int PD, bool LDS>
+// SHARE = true: the shared-prompt variant (ShareArgs): the first sh.n_prefix blocks are prefix workgroups, the others
+// cover page pairs sh.prefix_pairs .. of their row and fold the prefix workgroup's partial result into the merge.
+template <int HD, int NW, int PD, bool LDS, bool SHARE>
 __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __restrict__ qkv,
                                                                const float2* __restrict__ rope, RowMap rm, KVCache kv,
-                                                               uint4* __restrict__ out, int n_q_heads) {
+                                                               uint4* __restrict__ out, int n_q_heads, ShareArgs sh) {
   constexpr int KK = HD / 32;   // k steps of S^T = K Q^T
   constexpr int DT = HD / 16;   // 16-row tiles of O^T
   constexpr int NFRAG = 2 * KK + DT;                        // 1 KiB fragments of one page pair
@@ -701,10 +870,19 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
   __shared__ __attribute__((aligned(16))) f16 knew[HD];
   __shared__ __attribute__((aligned(16))) f16 vnew[HD];
   __shared__ float sm_m[NW][16], sm_l[NW][16];
+  if constexpr (SHARE) {
+    static_assert(!LDS, "the shared-prompt variant reads K/V register-direct");
+    if ((int)blockIdx.x < sh.n_prefix) {   // uniform over the workgroup
+      attention_prefix_role<HD, NW>(qkv, rope, rm, kv, n_q_heads, sh, sm_o, (f16*)(sm_o + (size_t)NW * HD * 16), sm_m, sm_l);
+      return;
+    }
+  }
   const int tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63;
   const int qcol = lane & 15, grp = lane >> 4;
   const int hkv = kv.n_kv_heads, rep = n_q_heads / hkv;
-  const int s = blockIdx.x / hkv, kvh = blockIdx.x % hkv;
+  const int bid = SHARE ? (int)blockIdx.x - sh.n_prefix : (int)blockIdx.x;
+  const int s = bid / hkv, kvh = bid % hkv;
+  const int pp0 = SHARE ? sh.prefix_pairs : 0;   // first page pair this workgroup covers
   int seq, pos;
   rm.get(s, seq, pos);
   const int ctx = pos + 1;
@@ -763,9 +941,9 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
   Frag16 kf[PR][2][KK], vf[PR][DT];
 #pragma unroll
   for (int j = 0; j < PD; ++j)
-    if (wave + NW * j < npairs) {
-      if constexpr (LDS) stage_pair(wave + NW * j, j);
-      else load_pair(wave + NW * j, kf[j], vf[j]);
+    if (pp0 + wave + NW * j < npairs) {
+      if constexpr (LDS) stage_pair(pp0 + wave + NW * j, j);
+      else load_pair(pp0 + wave + NW * j, kf[j], vf[j]);
     }
 
   // ---- rotary on the group's queries and the new key; append key / value -------------------
@@ -810,20 +988,20 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  for (int c0 = 0; wave + NW * c0 < npairs; c0 += PD) {
+  for (int c0 = 0; pp0 + wave + NW * c0 < npairs; c0 += PD) {
     if (c0 > 0) {
 #pragma unroll
       for (int j = 0; j < PD; ++j)
-        if (wave + NW * (c0 + j) < npairs) {
-          if constexpr (LDS) stage_pair(wave + NW * (c0 + j), j);   // every slot has been read into registers and used
-          else load_pair(wave + NW * (c0 + j), kf[j], vf[j]);
+        if (pp0 + wave + NW * (c0 + j) < npairs) {
+          if constexpr (LDS) stage_pair(pp0 + wave + NW * (c0 + j), j);   // every slot has been read into registers and used
+          else load_pair(pp0 + wave + NW * (c0 + j), kf[j], vf[j]);
         }
     }
     // pairs of this chunk that exist for this wave (LDS: requests issued above, in slot order)
-    const int n_chunk = min(PD, (npairs - (wave + NW * c0) + NW - 1) / NW);
+    const int n_chunk = min(PD, (npairs - (pp0 + wave + NW * c0) + NW - 1) / NW);
 #pragma unroll
     for (int jj = 0; jj < PD; ++jj) {
-      const int pp = wave + NW * (c0 + jj);
+      const int pp = pp0 + wave + NW * (c0 + jj);
       if (pp >= npairs) break;
       constexpr int kSetStride = LDS ? 0 : 1;
       const int j = jj * kSetStride;          // register set: the pair's own, or the single one of the LDS variant
@@ -910,6 +1088,23 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
     for (int i = 0; i < 4; ++i) sm_o[(size_t)wave * kOStride + (size_t)(dt * 16 + grp * 4 + i) * 16 + qcol] = o[dt][i];
+  if constexpr (SHARE) {
+    // the prompt's part of this row comes from the prefix workgroup (prompt s / G, this KV head): wait, bounded by the
+    // wall clock, until its flag shows this launch's number; a wait that gives up sets the fault word, which makes the
+    // sampler emit -1 for the step
+    if (tid == 0) {
+      const unsigned launch_no = (unsigned)(*rm.step) * (unsigned)sh.n_layers + (unsigned)sh.layer + 1u;
+      const unsigned* flag = sh.flags + (size_t)(s / sh.G) * hkv + kvh;
+      const unsigned long long t0 = wall_clock64();
+      while ((int)(__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - launch_no) < 0) {
+        if (wall_clock64() - t0 > sh.spin_ticks) {
+          atomicOr(sh.fault, 2u);
+          break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+      }
+    }
+  }
   __syncthreads();
   // thread -> (query q, 8 consecutive head dims): one 16-byte chunk of the X16 output.  Waves that
   // had no page pair carry (m = -inf, l = 0, o = 0) and drop out of the merge.
@@ -919,14 +1114,26 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
     float mx = -INFINITY;
 #pragma unroll
     for (int w = 0; w < NW; ++w) mx = fmaxf(mx, sm_m[w][q]);
-    float den = 0.f, wgt[NW];
+    // the prefix part (shared-prompt variant): read past the L2, it was written by another workgroup of this launch
+    float m_p = -INFINITY, l_p = 0.f, o_p[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if constexpr (SHARE) {
+      const size_t base = ((size_t)s * n_q_heads + kvh * rep + q) * (HD + 4);
+      m_p = ld_f32<true>(sh.pre, base * sizeof(float));
+      l_p = ld_f32<true>(sh.pre, (base + 1) * sizeof(float));
+      const float4 a = as_f4(ld_u4<true>(sh.pre, (base + 4 + d0) * sizeof(float)));
+      const float4 b = as_f4(ld_u4<true>(sh.pre, (base + 8 + d0) * sizeof(float)));
+      o_p[0] = a.x; o_p[1] = a.y; o_p[2] = a.z; o_p[3] = a.w; o_p[4] = b.x; o_p[5] = b.y; o_p[6] = b.z; o_p[7] = b.w;
+      mx = fmaxf(mx, m_p);
+    }
+    const float w_p = SHARE ? __expf(m_p - mx) : 0.f;
+    float den = w_p * l_p, wgt[NW];
 #pragma unroll
     for (int w = 0; w < NW; ++w) { wgt[w] = __expf(sm_m[w][q] - mx); den += wgt[w] * sm_l[w][q]; }
     const float inv = 1.0f / den;
     Frag16 ov;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      float num = 0.f;
+      float num = w_p * o_p[e];
 #pragma unroll
       for (int w = 0; w < NW; ++w) num += wgt[w] * sm_o[(size_t)w * kOStride + (size_t)(d0 + e) * 16 + q];
       ov.h[e] = from_f32<f16>(num * inv);
@@ -935,24 +1142,36 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
   }
 }
 
-template <int HD, int NW, int PD, bool LDS = false>
+template <int HD, int NW, int PD, bool LDS = false, bool SHARE = false>
 static hipError_t launch_decode_attention(const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* out, int S,
-                                          int n_q_heads, hipStream_t st) {
+                                          int n_q_heads, hipStream_t st, const ShareArgs& sh = ShareArgs()) {
   static bool attr_done = false;
   static_assert(PD <= 4, "the LDS variant's waits cover up to 4 slots");
-  const size_t smem = LDS ? (size_t)NW * PD * (HD / 8) * 1024 : (size_t)NW * HD * 16 * sizeof(float);
+  const size_t smem = LDS ? (size_t)NW * PD * (HD / 8) * 1024
+                          : (size_t)NW * HD * 16 * sizeof(float) + (SHARE ? (size_t)kSharePrefixMaxColumns * HD * sizeof(f16) : 0);
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_decode_attention16<HD, NW, PD, LDS>,
+    hipError_t e = hipFuncSetAttribute((const void*)k_decode_attention16<HD, NW, PD, LDS, SHARE>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  return launch(KID_DECODE_ATTN, k_decode_attention16<HD, NW, PD, LDS>, dim3(S * kv.n_kv_heads), dim3(NW * 64), smem, st, qkv, rope,
-                rm, kv, (uint4*)out, n_q_heads);
+  return launch(SHARE ? KID_DECODE_ATTN_SHARED : KID_DECODE_ATTN, k_decode_attention16<HD, NW, PD, LDS, SHARE>,
+                dim3((SHARE ? sh.n_prefix : 0) + S * kv.n_kv_heads), dim3(NW * 64), smem, st, qkv, rope, rm, kv, (uint4*)out,
+                n_q_heads, sh);
 }
 
 hipError_t d_decode_attention(const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* out, int S, int n_q_heads,
-                              hipStream_t st) {
+                              const ShareArgs* share, hipStream_t st) {
+  if (share && share->prefix_pairs > 0) {
+    // what the two-role launch assumes: rows are P x G sequences in order, all at one position, with their own
+    // page-table rows; the columns of all siblings fit the prefix workgroup's four MFMA tiles
+    const int rep = n_q_heads / kv.n_kv_heads;
+    if (kv.head_dim != 64 || !rm.decode || rm.lens || rm.slot_seq || share->G < 1 || S % share->G != 0 ||
+        share->G * rep > kSharePrefixMaxColumns || share->n_prefix != (S / share->G) * kv.n_kv_heads || !share->pre ||
+        !share->flags || !share->fault || share->prefix_pairs * 32 > rm.Lp)
+      return hipErrorInvalidValue;
+    return launch_decode_attention<64, 8, 3, false, true>(qkv, rope, rm, kv, out, S, n_q_heads, st, *share);
+  }
   // SAPO_ATTN_LDS=1 in the environment: the LDS-staged variant, kept as the measured alternative (0.5B-class decoder,
   // 64 sequences, same waves and pairs in flight: 6.6 against 5.8 us per launch at contexts 128..383, 12.5 against
   // 11.4 us at 512..1535).  Two slots of 8 KiB per wave are what 8 waves fit into the 160 KiB.  Read per call, so
