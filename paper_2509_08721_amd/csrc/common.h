@@ -80,6 +80,27 @@ template <> __device__ __forceinline__ f16 from_f32<f16>(float x) { return (f16)
 // makes the guard a real branch.
 __device__ __forceinline__ int wave_index(int thread_index) { return __builtin_amdgcn_readfirstlane(thread_index >> 6); }
 
+// The values of lanes l and l ^ 16 (l ^ 32) combined in every lane, through gfx950's lane-swap instructions
+// (v_permlane16_swap / v_permlane32_swap: one vector-ALU instruction, no trip through LDS as the generic shuffle
+// takes).  Both lanes of a pair combine (lower lane's value, upper lane's value) in that order.
+typedef unsigned int lane_u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float max_xor16(float x) {
+  const lane_u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float max_xor32(float x) {
+  const lane_u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_xor16(float x) {
+  const lane_u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float sum_xor32(float x) {
+  const lane_u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 __device__ __forceinline__ float wave_reduce_max(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));

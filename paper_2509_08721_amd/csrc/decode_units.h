@@ -260,8 +260,8 @@ __device__ __forceinline__ void skinny_unit(const SkinnyArgs& a, int unit, int t
           o[0] = o[1] = o[2] = o[3] = (f16)0.f;
         }
         st_h4<COH>(a.xp_out, (x16_chunk(tok, f0, a.N >> 5) * 8 + (f0 & 4)) * sizeof(f16), o);
-        q += __shfl_xor(q, 16, 64);
-        q += __shfl_xor(q, 32, 64);
+        q = sum_xor16(q);
+        q = sum_xor32(q);
         if (l < 16) st_f32<COH>(a.ssq_out, ((size_t)(tile0 + c0 + t) * a.s_pad + tok) * sizeof(float), q);
       }
     }
@@ -423,8 +423,8 @@ __device__ __forceinline__ void attention_unit(const float* __restrict__ qkv, co
         p[e] = (n < ctx) ? sv : -INFINITY;
         m_loc = fmaxf(m_loc, p[e]);
       }
-      m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 16, 64));
-      m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, 64));
+      m_loc = max_xor16(m_loc);
+      m_loc = max_xor32(m_loc);
       const float m_new = fmaxf(m_run, m_loc);
       const float alpha = __expf(m_run - m_new);
       float psum = 0.f;
@@ -456,8 +456,8 @@ __device__ __forceinline__ void attention_unit(const float* __restrict__ qkv, co
       }
     }
   }
-  l_run += __shfl_xor(l_run, 16, 64);
-  l_run += __shfl_xor(l_run, 32, 64);
+  l_run = sum_xor16(l_run);
+  l_run = sum_xor32(l_run);
   if (grp == 0) { sm_m[wave][qcol] = m_run; sm_l[wave][qcol] = l_run; }
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)

@@ -268,8 +268,8 @@ __global__ void __launch_bounds__(512) k_skinny16(SkinnyArgs a, int n_units) {
           o[0] = o[1] = o[2] = o[3] = (f16)0.f;
         }
         *(f16x4*)((f16*)a.xp_out + x16_chunk(tok, f0, a.N >> 5) * 8 + (f0 & 4)) = o;
-        q += __shfl_xor(q, 16, 64);
-        q += __shfl_xor(q, 32, 64);
+        q = sum_xor16(q);
+        q = sum_xor32(q);
         if (l < 16) a.ssq_out[(size_t)(tile0 + c0 + t) * a.s_pad + tok] = q;
       }
     }
@@ -781,8 +781,8 @@ __device__ __forceinline__ void attention_prefix_role(const float* __restrict__ 
           pv[e] = sc[e >> 2][e & 3] * scale;
           m_loc = fmaxf(m_loc, pv[e]);
         }
-        m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 16, 64));
-        m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, 64));
+        m_loc = max_xor16(m_loc);
+        m_loc = max_xor32(m_loc);
         const float m_new = fmaxf(m_run[jt], m_loc);
         const float alpha = __expf(m_run[jt] - m_new);
         float psum = 0.f;
@@ -808,8 +808,8 @@ __device__ __forceinline__ void attention_prefix_role(const float* __restrict__ 
 #pragma unroll
   for (int jt = 0; jt < NT; ++jt) {
     float l = l_run[jt];
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
+    l = sum_xor16(l);
+    l = sum_xor32(l);
     if (jt > 0) __syncthreads();   // the previous tile's sums have been read
     if (grp == 0) { sm_m[wave][qcol] = m_run[jt]; sm_l[wave][qcol] = l; }
 #pragma unroll
@@ -1048,8 +1048,8 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
         p[e] = (n < ctx) ? sv : -INFINITY;
         m_loc = fmaxf(m_loc, p[e]);
       }
-      m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 16, 64));
-      m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, 64));
+      m_loc = max_xor16(m_loc);
+      m_loc = max_xor32(m_loc);
       const float m_new = fmaxf(m_run, m_loc);
       const float alpha = __expf(m_run - m_new);
       float psum = 0.f;
@@ -1081,8 +1081,8 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
       }
     }
   }
-  l_run += __shfl_xor(l_run, 16, 64);
-  l_run += __shfl_xor(l_run, 32, 64);
+  l_run = sum_xor16(l_run);
+  l_run = sum_xor32(l_run);
   if (grp == 0) { sm_m[wave][qcol] = m_run; sm_l[wave][qcol] = l_run; }
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)

@@ -838,7 +838,8 @@ __global__ void __launch_bounds__(256, 2) k_flash_attention(const f16* __restric
   const f16* kpool = (const f16*)kv.k;
   const f16* vpool = (const f16*)kv.v;
   const size_t page_elems = (size_t)hkv * kPageTokens * HD;
-  // K / V fragments of a page pair; the next pair's are requested before the current one is multiplied
+  // K / V fragments of a page pair; the next pair's are requested before the current one is multiplied (a third
+  // register set, two pairs ahead, was measured at head dim 64: 238 against 223 us per launch at 64 x 768)
   Frag kf[2][KK], vf[DT], kn[2][KK], vn[DT];
   auto fetch = [&](int pp, Frag (&kd)[2][KK], Frag (&vd)[DT]) {
     const int pa = pt[2 * pp];
@@ -885,8 +886,8 @@ __global__ void __launch_bounds__(256, 2) k_flash_attention(const f16* __restric
           if (pp * 32 + 8 * grp + e > qpos) p[e] = -INFINITY;
       }
       float m_loc = fmaxf(fmaxf(fmaxf(p[0], p[1]), fmaxf(p[2], p[3])), fmaxf(fmaxf(p[4], p[5]), fmaxf(p[6], p[7])));
-      m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 16, 64));
-      m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, 64));
+      m_loc = max_xor16(m_loc);
+      m_loc = max_xor32(m_loc);
       const float m_new = fmaxf(m_run[h], m_loc * scale2);   // finite: key 0 is visible to every query
       const float alpha = __builtin_amdgcn_exp2f(m_run[h] - m_new);   // exp2(-inf) = 0 on the first pair
       float psum = 0.f;
@@ -899,15 +900,17 @@ __global__ void __launch_bounds__(256, 2) k_flash_attention(const f16* __restric
       }
       l_run[h] = l_run[h] * alpha + psum;
       m_run[h] = m_new;
-      const bool rescale = __builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0;   // the running max moved in some lane
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {   // the running max moved in some lane
+        // the empty statement keeps this a branch: turned into selects, the 16 multiplies (and 16 selects) would run
+        // for every pair, a quarter of the loop's vector-ALU work
+        asm volatile("");
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        if (rescale) {
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
           for (int j = 0; j < 4; ++j) o[h][dt][j] *= alpha;
-        }
-        o[h][dt] = mfma16h(vf[dt], pf, o[h][dt]);
       }
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) o[h][dt] = mfma16h(vf[dt], pf, o[h][dt]);
     }
   }
   if (q0 + qcol >= T) return;
@@ -915,8 +918,8 @@ __global__ void __launch_bounds__(256, 2) k_flash_attention(const f16* __restric
   for (int h = 0; h < HPW; ++h) {
     if (h >= nh) continue;
     float l = l_run[h];
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
+    l = sum_xor16(l);
+    l = sum_xor32(l);
     const float inv = 1.0f / l;
     const int col0 = (kvh * rep + h0 + h) * HD + grp * 4;   // lane's 4 consecutive head dims, per 16-row tile
 #pragma unroll
