@@ -18,8 +18,9 @@
 // Every wait is bounded by a wall-clock limit: a workgroup that waits longer (its peers cannot all be resident,
 // e.g. because other work holds compute units) sets the fault word, stops waiting for the rest of the launch and
 // runs to the end; the sampler then emits -1 tokens, so the failure is visible and no wave is left spinning.
-// Measured on the 0.5B-class decoder the kernel does NOT beat one kernel per phase (see the design notes): it is kept
-// as an option (SAPO_PERSIST=1 in the environment), off by default.
+// Measured on the 0.5B-class decoder (64 rows) the kernel does NOT beat one kernel per phase: 815 us per launch against
+// about 750 us for the same 120 phases as kernels (the hand-over between workgroups costs 3-4 us per phase, a kernel
+// boundary in a replayed graph 2.3 us).  It is kept as an option (SAPO_PERSIST=1 in the environment), off by default.
 // The arithmetic is that of the per-phase kernels (same device functions, same summation orders): a step through
 // this kernel returns the same bytes.
 #include "decode_units.h"
