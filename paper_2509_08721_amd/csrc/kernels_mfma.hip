@@ -274,9 +274,18 @@ __global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ X
     }
   }, st0, n_st);
   float ssq_mine[4] = {0.f, 0.f, 0.f, 0.f};
+  const int tok0 = by * 256 + wt * 128 + (lane & 31);
+  const int fcol = bx * 128 + wf * 64 + (lane >> 5) * 4;   // + fi * 32 + 8 r: this lane's four features of block (fi, r)
+  float4 bb[2][4];
+  if (ep.mode == BIG_STORE_F32 && ep.bias) {
+#pragma unroll
+    for (int fi = 0; fi < 2; ++fi)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) bb[fi][r] = *(const float4*)(ep.bias + fcol + fi * 32 + 8 * r);
+  }
 #pragma unroll
   for (int tj = 0; tj < 4; ++tj) {
-    const int tok = by * 256 + wt * 128 + tj * 32 + (lane & 31);
+    const int tok = tok0 + tj * 32;
     if (tok >= M) continue;   // lanes l and l + 32 hold the same token: they leave together
     if (ep.ssq_in) {
       const float sc = row_scale[tj];
@@ -296,34 +305,76 @@ __global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ X
         for (int j = 0; j < 4; ++j) o[j] = from_f32<f16>(silu_f(acc[0][tj][4 * r + j]) * acc[1][tj][4 * r + j]);
         *(f16x4*)(ep.out_act + x32_chunk(tok, f0 + 8 * r, F >> 4) * 8 + ((lane >> 5) << 2)) = o;
       }
-    } else {
-      float ssq = 0.f;
+    } else if (ep.mode == BIG_STORE_F32) {
 #pragma unroll
-      for (int fi = 0; fi < 2; ++fi) {
-        const int f0 = bx * 128 + wf * 64 + fi * 32 + (lane >> 5) * 4;
+      for (int fi = 0; fi < 2; ++fi)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          float4* p = (float4*)(ep.out_f32 + (size_t)tok * ep.ldc + f0 + 8 * r);
           float4 v = make_float4(acc[fi][tj][4 * r], acc[fi][tj][4 * r + 1], acc[fi][tj][4 * r + 2], acc[fi][tj][4 * r + 3]);
-          if (ep.mode == BIG_ADD_F32) {
-            const float4 o = *p;
-            v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
-          } else if (ep.bias) {
-            const float4 bb = *(const float4*)(ep.bias + f0 + 8 * r);
-            v.x += bb.x; v.y += bb.y; v.z += bb.z; v.w += bb.w;
-          }
-          *p = v;
-          if (ep.gain_next) {
-            const float4 g = *(const float4*)(ep.gain_next + f0 + 8 * r);
-            ssq += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-            f16x4 o;
-            o[0] = from_f32<f16>(v.x * g.x); o[1] = from_f32<f16>(v.y * g.y);
-            o[2] = from_f32<f16>(v.z * g.z); o[3] = from_f32<f16>(v.w * g.w);
-            *(f16x4*)(ep.xn_out + x32_chunk(tok, f0 + 8 * r, N >> 4) * 8 + ((lane >> 5) << 2)) = o;
-          }
+          if (ep.bias) { v.x += bb[fi][r].x; v.y += bb[fi][r].y; v.z += bb[fi][r].z; v.w += bb[fi][r].w; }
+          *(float4*)(ep.out_f32 + (size_t)tok * ep.ldc + fcol + fi * 32 + 8 * r) = v;
         }
+    }
+  }
+  if (ep.mode == BIG_ADD_F32) {
+    // Residual update.  A thread's pieces of the residual rows are requested one token block ahead of the block being
+    // written, before that block's stores: written as load, add, store per piece, every load waited for the
+    // acknowledgement of the stores in front of it, 64 dependent round trips per thread.  Rows past the end read row
+    // M - 1 (in bounds) and store nothing.  A tile without such rows and the producer side are compile-time cases, so
+    // that the common one is straight-line code whose waits the compiler can count exactly.
+    auto update = [&](auto full_c, auto prod_c) {
+      constexpr bool full = decltype(full_c)::value, prod = decltype(prod_c)::value;
+      float4 g[2][4];
+      if (prod) {
+#pragma unroll
+        for (int fi = 0; fi < 2; ++fi)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) g[fi][r] = *(const float4*)(ep.gain_next + fcol + fi * 32 + 8 * r);
       }
-      ssq_mine[tj] = ssq + __shfl_xor(ssq, 32, 64);
+      float4 o[2][2][4];
+      auto request = [&](int tj, float4 (&dst)[2][4]) {
+        const int row = full ? tok0 + tj * 32 : min(tok0 + tj * 32, M - 1);
+        const float* p = ep.out_f32 + (size_t)row * ep.ldc + fcol;
+#pragma unroll
+        for (int fi = 0; fi < 2; ++fi)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) dst[fi][r] = *(const float4*)(p + fi * 32 + 8 * r);
+      };
+      request(0, o[0]);
+#pragma unroll
+      for (int tj = 0; tj < 4; ++tj) {
+        if (tj < 3) request(tj + 1, o[(tj + 1) & 1]);
+        const int tok = tok0 + tj * 32;
+        float ssq = 0.f;
+        if (full || tok < M) {
+          float* p = ep.out_f32 + (size_t)tok * ep.ldc + fcol;
+#pragma unroll
+          for (int fi = 0; fi < 2; ++fi)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const float4 w = o[tj & 1][fi][r];
+              const float4 v = make_float4(acc[fi][tj][4 * r] + w.x, acc[fi][tj][4 * r + 1] + w.y,
+                                           acc[fi][tj][4 * r + 2] + w.z, acc[fi][tj][4 * r + 3] + w.w);
+              *(float4*)(p + fi * 32 + 8 * r) = v;
+              if (prod) {
+                ssq += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+                f16x4 h;
+                h[0] = from_f32<f16>(v.x * g[fi][r].x); h[1] = from_f32<f16>(v.y * g[fi][r].y);
+                h[2] = from_f32<f16>(v.z * g[fi][r].z); h[3] = from_f32<f16>(v.w * g[fi][r].w);
+                *(f16x4*)(ep.xn_out + x32_chunk(tok, fcol + fi * 32 + 8 * r, N >> 4) * 8 + ((lane >> 5) << 2)) = h;
+              }
+            }
+        }
+        ssq_mine[tj] = ssq + __shfl_xor(ssq, 32, 64);
+      }
+    };
+    const bool full = by * 256 + 256 <= M;
+    if (ep.gain_next) {
+      if (full) update(std::true_type(), std::true_type());
+      else update(std::false_type(), std::true_type());
+    } else {
+      if (full) update(std::true_type(), std::false_type());
+      else update(std::false_type(), std::false_type());
     }
   }
   if (ep.gain_next) {   // uniform: the two feature waves of a token half meet in LDS, summed in wave order
@@ -390,100 +441,113 @@ __global__ void __launch_bounds__(256, 2) k_gemm_qkv_rope(const uint4* __restric
   const bool is_v = head >= hq + hkv;
   const int half_sel = lane >> 5;
   // row scale and bias first: what is rotated is the finished projection
+  {
+    float4 bb[2][4];
 #pragma unroll
-  for (int tj = 0; tj < 4; ++tj)
+    for (int fi = 0; fi < 2; ++fi)
 #pragma unroll
-    for (int fi = 0; fi < 2; ++fi) {
-      const int f0 = bx * 128 + wf * 64 + fi * 32 + half_sel * 4;
+      for (int r = 0; r < 4; ++r)
+        bb[fi][r] = ep.bias ? *(const float4*)(ep.bias + bx * 128 + wf * 64 + fi * 32 + half_sel * 4 + 8 * r)
+                            : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        float4 bb = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (ep.bias) bb = *(const float4*)(ep.bias + f0 + 8 * r);
-        acc[fi][tj][4 * r + 0] = acc[fi][tj][4 * r + 0] * row_scale[tj] + bb.x;
-        acc[fi][tj][4 * r + 1] = acc[fi][tj][4 * r + 1] * row_scale[tj] + bb.y;
-        acc[fi][tj][4 * r + 2] = acc[fi][tj][4 * r + 2] * row_scale[tj] + bb.z;
-        acc[fi][tj][4 * r + 3] = acc[fi][tj][4 * r + 3] * row_scale[tj] + bb.w;
-      }
-    }
+    for (int tj = 0; tj < 4; ++tj)
+#pragma unroll
+      for (int fi = 0; fi < 2; ++fi)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          acc[fi][tj][4 * r + 0] = acc[fi][tj][4 * r + 0] * row_scale[tj] + bb[fi][r].x;
+          acc[fi][tj][4 * r + 1] = acc[fi][tj][4 * r + 1] * row_scale[tj] + bb[fi][r].y;
+          acc[fi][tj][4 * r + 2] = acc[fi][tj][4 * r + 2] * row_scale[tj] + bb[fi][r].z;
+          acc[fi][tj][4 * r + 3] = acc[fi][tj][4 * r + 3] * row_scale[tj] + bb[fi][r].w;
+        }
+  }
   f16* kpool = (f16*)ep.kv.k;
   f16* vpool = (f16*)ep.kv.v;
-  // one token block (tj) of this wave: `other` holds the rotation partners (HD = 128) or is unused
-  auto finish = [&](const f32x16& mine0, const f32x16& mine1, int tj, const f32x16 (&other)[2]) {
-    const f32x16* const mine_p[2] = {&mine0, &mine1};
-#define mine(fi) (*mine_p[fi])
-    const int tok = by * 256 + wt * 128 + tj * 32 + (lane & 31);
-    if (tok >= M) return;
-    int seq, pos;
-    ep.rm.get(tok, seq, pos);
-    const bool keep = ep.rm.keeps_kv(tok);
-    const int page = ep.kv.page_table[(size_t)seq * ep.kv.pages_per_seq + pos / kPageTokens];
-    const int slot = pos % kPageTokens;
-    if (is_v) {
-      if (!keep) return;
-      const int vh = head - hq - hkv;
-      f16* vp = vpool + ((size_t)page * hkv + vh) * HD * kPageTokens + slot;
+  // Where the four token blocks of this lane go: position, cache page, and whether anything is stored.  All four
+  // page-table lookups are in flight together (rows past the end look up row M - 1 and store nothing).
+  int pos_of[4], page_of[4];
+  bool stores[4];
+#pragma unroll
+  for (int tj = 0; tj < 4; ++tj) {
+    const int tok = by * 256 + wt * 128 + tj * 32 + (lane & 31), tokc = min(tok, M - 1);
+    int seq;
+    ep.rm.get(tokc, seq, pos_of[tj]);
+    stores[tj] = tok < M && (head < hq || ep.rm.keeps_kv(tokc));
+    page_of[tj] = ep.kv.page_table[(size_t)seq * ep.kv.pages_per_seq + pos_of[tj] / kPageTokens];
+  }
+  if (is_v) {
+    const int vh = head - hq - hkv;
+#pragma unroll
+    for (int tj = 0; tj < 4; ++tj) {
+      if (!stores[tj]) continue;
+      f16* vp = vpool + ((size_t)page_of[tj] * hkv + vh) * HD * kPageTokens + pos_of[tj] % kPageTokens;
 #pragma unroll
       for (int fi = 0; fi < 2; ++fi)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int f = (HD == 64 ? 0 : wf * 64) + fi * 32 + 8 * (v >> 2) + (v & 3) + half_sel * 4;
-          vp[(size_t)f * kPageTokens] = from_f32<f16>(mine(fi)[v]);
+          vp[(size_t)f * kPageTokens] = from_f32<f16>(acc[fi][tj][v]);
         }
-      return;
     }
-    f16* dst;   // start of this row's head: q row-major, k in its page slot
-    if (head < hq) dst = ep.q_out + ((size_t)tok * hq + head) * HD;
-    else dst = kpool + (((size_t)page * hkv + (head - hq)) * kPageTokens + slot) * HD;
-    if (head >= hq && !keep) return;
-    const float2* cs_row = ep.rope + (size_t)pos * (HD / 2);
-    if (HD == 64) {
-      // pair (i, i + 32): x1 = block fi = 0, x2 = block fi = 1, i = 8 r + j + 4 half_sel
+    return;
+  }
+  // start of a row's head: q row-major, k in its page slot
+  auto head_row = [&](int tj) -> f16* {
+    const int tok = by * 256 + wt * 128 + tj * 32 + (lane & 31);
+    if (head < hq) return ep.q_out + ((size_t)tok * hq + head) * HD;
+    return kpool + (((size_t)page_of[tj] * hkv + (head - hq)) * kPageTokens + pos_of[tj] % kPageTokens) * HD;
+  };
+  // The (cos, sin) pairs of a token block are requested one block ahead of the block being written, before that
+  // block's stores: a load issued behind a store waits for the store's acknowledgement as well.
+  if (HD == 64) {
+    // pair (i, i + 32): x1 = block fi = 0, x2 = block fi = 1, i = 8 r + j + 4 half_sel
+    float4 cs[2][4][2];
+    auto request = [&](int tj, float4 (&dst)[4][2]) {
+      const float2* cs_row = ep.rope + (size_t)pos_of[tj] * (HD / 2) + half_sel * 4;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        dst[r][0] = *(const float4*)(cs_row + 8 * r);
+        dst[r][1] = *(const float4*)(cs_row + 8 * r + 2);
+      }
+    };
+    request(0, cs[0]);
+#pragma unroll
+    for (int tj = 0; tj < 4; ++tj) {
+      if (tj < 3) request(tj + 1, cs[(tj + 1) & 1]);
+      if (!stores[tj]) continue;
+      f16* dst = head_row(tj);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int i0 = 8 * r + half_sel * 4;
-        const float4 c01 = *(const float4*)(cs_row + i0), c23 = *(const float4*)(cs_row + i0 + 2);
-        const float cs[8] = {c01.x, c01.y, c01.z, c01.w, c23.x, c23.y, c23.z, c23.w};
+        const float4 c01 = cs[tj & 1][r][0], c23 = cs[tj & 1][r][1];
+        const float c[8] = {c01.x, c01.y, c01.z, c01.w, c23.x, c23.y, c23.z, c23.w};
         f16x4 o1, o2;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          const float x1 = mine0[4 * r + j], x2 = mine1[4 * r + j], c = cs[2 * j], sn = cs[2 * j + 1];
-          o1[j] = from_f32<f16>(x1 * c - x2 * sn);
-          o2[j] = from_f32<f16>(x2 * c + x1 * sn);
+          const float x1 = acc[0][tj][4 * r + j], x2 = acc[1][tj][4 * r + j], co = c[2 * j], sn = c[2 * j + 1];
+          o1[j] = from_f32<f16>(x1 * co - x2 * sn);
+          o2[j] = from_f32<f16>(x2 * co + x1 * sn);
         }
         *(f16x4*)(dst + i0) = o1;
         *(f16x4*)(dst + i0 + 32) = o2;
       }
-    } else {
-      // pair (i, i + 64): this wave holds x1 (wf = 0) or x2 (wf = 1) at i = fi 32 + 8 r + j + 4 half_sel
-#pragma unroll
-      for (int fi = 0; fi < 2; ++fi)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int i0 = fi * 32 + 8 * r + half_sel * 4;
-          const float4 c01 = *(const float4*)(cs_row + i0), c23 = *(const float4*)(cs_row + i0 + 2);
-          const float cs[8] = {c01.x, c01.y, c01.z, c01.w, c23.x, c23.y, c23.z, c23.w};
-          f16x4 o;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const float a = mine(fi)[4 * r + j], b = other[fi][4 * r + j], c = cs[2 * j], sn = cs[2 * j + 1];
-            o[j] = from_f32<f16>(wf == 0 ? a * c - b * sn : a * c + b * sn);
-          }
-          *(f16x4*)(dst + wf * 64 + i0) = o;
-        }
-    }
-#undef mine
-  };
-  if (HD == 64 || is_v) {
-#pragma unroll
-    for (int tj = 0; tj < 4; ++tj) {
-      const f32x16 none[2] = {};
-      finish(acc[0][tj], acc[1][tj], tj, none);
-      __builtin_amdgcn_sched_barrier(0);   // one token block at a time: hoisted loads of all four spill
     }
     return;
   }
-  // HD = 128, q or k head: swap accumulators with the other feature wave through LDS, two token blocks at a time
+  // HD = 128, q or k head: pair (i, i + 64); this wave holds x1 (wf = 0) or x2 (wf = 1) at i = fi 32 + 8 r + j + 4 half_sel
+  // and swaps accumulators with the other feature wave through LDS, two token blocks at a time
   float* ex = (float*)smem;   // [wt][wf][tj2][fi][v][lane]: 2 x 2 x 2 x 2 x 16 x 64 floats = 64 KiB
+  float4 cs[2][4][2];
+  auto request = [&](int tj, float4 (&dst)[2][4][2]) {
+    const float2* cs_row = ep.rope + (size_t)pos_of[tj] * (HD / 2) + half_sel * 4;
+#pragma unroll
+    for (int fi = 0; fi < 2; ++fi)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        dst[fi][r][0] = *(const float4*)(cs_row + fi * 32 + 8 * r);
+        dst[fi][r][1] = *(const float4*)(cs_row + fi * 32 + 8 * r + 2);
+      }
+  };
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     wg_barrier();   // the ring (first round) or the previous round's partners have been read
@@ -497,13 +561,30 @@ __global__ void __launch_bounds__(256, 2) k_gemm_qkv_rope(const uint4* __restric
     __syncthreads();
 #pragma unroll
     for (int t2 = 0; t2 < 2; ++t2) {
-      f32x16 other[2];
+      const int tj = 2 * h + t2;
+      request(tj, cs);   // all of the block's pairs before its first store (a full block ahead would not fit the registers)
+      if (stores[tj]) {
+        f16* dst = head_row(tj);
 #pragma unroll
-      for (int fi = 0; fi < 2; ++fi)
+        for (int fi = 0; fi < 2; ++fi) {
+          f32x16 other;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) other[fi][v] = ex[((((wt * 2 + (wf ^ 1)) * 2 + t2) * 2 + fi) * 16 + v) * 64 + lane];
-      finish(acc[0][2 * h + t2], acc[1][2 * h + t2], 2 * h + t2, other);
-      __builtin_amdgcn_sched_barrier(0);
+          for (int v = 0; v < 16; ++v) other[v] = ex[((((wt * 2 + (wf ^ 1)) * 2 + t2) * 2 + fi) * 16 + v) * 64 + lane];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int i0 = fi * 32 + 8 * r + half_sel * 4;
+            const float4 c01 = cs[fi][r][0], c23 = cs[fi][r][1];
+            const float c[8] = {c01.x, c01.y, c01.z, c01.w, c23.x, c23.y, c23.z, c23.w};
+            f16x4 o;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const float a = acc[fi][tj][4 * r + j], b2 = other[4 * r + j], co = c[2 * j], sn = c[2 * j + 1];
+              o[j] = from_f32<f16>(wf == 0 ? a * co - b2 * sn : a * co + b2 * sn);
+            }
+            *(f16x4*)(dst + wf * 64 + i0) = o;
+          }
+        }
+      }
     }
   }
 }
@@ -541,6 +622,7 @@ hipError_t m_gemm_big(const void* Xp, const void* Wp, int M, int N, int K, BigEp
   if (epi.splits < 1 || (epi.splits > 1 && (epi.splits % 8 != 0 || K / 32 < epi.splits || M > 256 ||
                                             epi.mode != BIG_STORE_F32 || epi.ssq_in || epi.bias)))
     return hipErrorInvalidValue;
+  if (epi.gain_next && epi.mode != BIG_ADD_F32) return hipErrorInvalidValue;
   const int g = epi.splits > 1 ? epi.splits * (N / 128) : big_grid(N / 128, (M + 255) / 256);
   return launch(epi.decode ? KID_GEMM_BIG_DECODE : KID_GEMM_BIG, k_gemm_big, dim3(g), dim3(256), kBigLds, st, (const uint4*)Xp,
                 (const uint4*)Wp, M, N, K, epi);
