@@ -317,55 +317,85 @@ __global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ X
     }
   }
   if (ep.mode == BIG_ADD_F32) {
-    // Residual update.  A thread's pieces of the residual rows are requested one token block ahead of the block being
-    // written, before that block's stores: written as load, add, store per piece, every load waited for the
-    // acknowledgement of the stores in front of it, 64 dependent round trips per thread.  Rows past the end read row
-    // M - 1 (in bounds) and store nothing.  A tile without such rows and the producer side are compile-time cases, so
-    // that the common one is straight-line code whose waits the compiler can count exactly.
+    // Residual update.  In the accumulator layout a lane holds one token, so a load or store instruction on the
+    // row-major fp32 residual touches 32 cache lines for 1 KiB.  The residual therefore moves in row layout (16 lanes
+    // cover 256 contiguous bytes of a row: 8 full lines per instruction) and changes layout through LDS, once on the
+    // way in and once on the way out, a wave's 64 tokens x 64 features at a time in the wave's own part of the ring
+    // (rows padded to 68 floats).  The sums, the next operand and the sums of squares are taken in the accumulator
+    // layout as before: same results bit for bit.  The second half's rows are requested before the first half's
+    // stores, since a load issued behind a store also waits for the store's acknowledgement.  A tile without rows
+    // past the end and the producer side are compile-time cases, so that the common one is straight-line code
+    // whose waits the compiler can count exactly.
+    constexpr int RS = 68;
+    wg_barrier();   // every wave has read its last stage: the ring is free
+    float* R = (float*)smem + wave * (64 * RS);
+    const int rt = lane >> 4, rc = (lane & 15) * 4;   // row layout: token 4 i + rt of the half, features rc .. rc + 3
+    const int row0 = by * 256 + wt * 128, gcol = bx * 128 + wf * 64;
+    auto wave_sync = [] {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
     auto update = [&](auto full_c, auto prod_c) {
       constexpr bool full = decltype(full_c)::value, prod = decltype(prod_c)::value;
-      float4 g[2][4];
-      if (prod) {
+      // the wave's 64 gains wait in LDS behind the four row areas (held in registers they would not fit next to the
+      // rows in flight)
+      float* G = (float*)smem + 4 * 64 * RS + wave * 64;
+      if (prod && lane < 16) *(float4*)(G + 4 * lane) = *(const float4*)(ep.gain_next + gcol + 4 * lane);
+      float4 in[16];
+      auto request = [&](int h, int i0) {   // rows 4 i + rt, i = i0 .. i0 + 7, of half h
 #pragma unroll
-        for (int fi = 0; fi < 2; ++fi)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) g[fi][r] = *(const float4*)(ep.gain_next + fcol + fi * 32 + 8 * r);
-      }
-      float4 o[2][2][4];
-      auto request = [&](int tj, float4 (&dst)[2][4]) {
-        const int row = full ? tok0 + tj * 32 : min(tok0 + tj * 32, M - 1);
-        const float* p = ep.out_f32 + (size_t)row * ep.ldc + fcol;
-#pragma unroll
-        for (int fi = 0; fi < 2; ++fi)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) dst[fi][r] = *(const float4*)(p + fi * 32 + 8 * r);
+        for (int i = i0; i < i0 + 8; ++i) {
+          const int tok = row0 + h * 64 + 4 * i + rt;
+          in[i] = (full || tok < M) ? *(const float4*)(ep.out_f32 + (size_t)tok * ep.ldc + gcol + rc)
+                                    : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
       };
-      request(0, o[0]);
+      request(0, 0);
+      request(0, 8);
 #pragma unroll
-      for (int tj = 0; tj < 4; ++tj) {
-        if (tj < 3) request(tj + 1, o[(tj + 1) & 1]);
-        const int tok = tok0 + tj * 32;
-        float ssq = 0.f;
-        if (full || tok < M) {
-          float* p = ep.out_f32 + (size_t)tok * ep.ldc + fcol;
+      for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) *(float4*)(R + (4 * i + rt) * RS + rc) = in[i];
+        wave_sync();
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2) {
+          const int tj = 2 * h + t2, tok = tok0 + tj * 32;
+          float ssq = 0.f;
 #pragma unroll
           for (int fi = 0; fi < 2; ++fi)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-              const float4 w = o[tj & 1][fi][r];
+              float4* q = (float4*)(R + (t2 * 32 + (lane & 31)) * RS + fi * 32 + 8 * r + (lane >> 5) * 4);
+              const float4 w = *q;
               const float4 v = make_float4(acc[fi][tj][4 * r] + w.x, acc[fi][tj][4 * r + 1] + w.y,
                                            acc[fi][tj][4 * r + 2] + w.z, acc[fi][tj][4 * r + 3] + w.w);
-              *(float4*)(p + fi * 32 + 8 * r) = v;
-              if (prod) {
+              *q = v;
+              if (prod && (full || tok < M)) {
                 ssq += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-                f16x4 h;
-                h[0] = from_f32<f16>(v.x * g[fi][r].x); h[1] = from_f32<f16>(v.y * g[fi][r].y);
-                h[2] = from_f32<f16>(v.z * g[fi][r].z); h[3] = from_f32<f16>(v.w * g[fi][r].w);
-                *(f16x4*)(ep.xn_out + x32_chunk(tok, fcol + fi * 32 + 8 * r, N >> 4) * 8 + ((lane >> 5) << 2)) = h;
+                const float4 gn = *(const float4*)(G + fi * 32 + 8 * r + (lane >> 5) * 4);
+                f16x4 hv;
+                hv[0] = from_f32<f16>(v.x * gn.x); hv[1] = from_f32<f16>(v.y * gn.y);
+                hv[2] = from_f32<f16>(v.z * gn.z); hv[3] = from_f32<f16>(v.w * gn.w);
+                *(f16x4*)(ep.xn_out + x32_chunk(tok, fcol + fi * 32 + 8 * r, N >> 4) * 8 + ((lane >> 5) << 2)) = hv;
               }
             }
+          ssq_mine[tj] = ssq + __shfl_xor(ssq, 32, 64);
         }
-        ssq_mine[tj] = ssq + __shfl_xor(ssq, 32, 64);
+        wave_sync();
+#pragma unroll
+        for (int i0 = 0; i0 < 16; i0 += 8) {   // eight rows at a time: sixteen out and sixteen in would not fit the registers
+          float4 out[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) out[i] = *(const float4*)(R + (4 * (i0 + i) + rt) * RS + rc);
+          if (h == 0) request(1, i0);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const int tok = row0 + h * 64 + 4 * (i0 + i) + rt;
+            if (full || tok < M) *(float4*)(ep.out_f32 + (size_t)tok * ep.ldc + gcol + rc) = out[i];
+          }
+        }
+        wave_sync();   // the rows are in registers before the next half overwrites them
       }
     };
     const bool full = by * 256 + 256 <= M;
