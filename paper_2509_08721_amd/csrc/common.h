@@ -69,6 +69,11 @@ struct KVCache {
 // ---------------------------------------------------------------------------------------
 // Device helpers
 // ---------------------------------------------------------------------------------------
+// A pair (a, b) rotated by (cos, sin), the rounding written out - one product rounded, then one fused multiply-add -
+// so that every decode kernel that rotates gives the same bits whatever the code around the expression looks like
+// (left to the compiler, which product is fused depends on the instruction order it happens to pick).
+__device__ __forceinline__ float rot_first(float a, float b, float c, float s) { return __builtin_fmaf(a, c, -(b * s)); }
+__device__ __forceinline__ float rot_second(float a, float b, float c, float s) { return __builtin_fmaf(b, c, a * s); }
 template <typename T> __device__ __forceinline__ float to_f32(T x) { return static_cast<float>(x); }
 template <typename T> __device__ __forceinline__ T from_f32(float x) { return static_cast<T>(x); }
 template <> __device__ __forceinline__ f16 from_f32<f16>(float x) { return (f16)fminf(fmaxf(x, -65504.f), 65504.f); }

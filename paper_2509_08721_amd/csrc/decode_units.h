@@ -349,8 +349,8 @@ __device__ __forceinline__ void attention_unit(const float* __restrict__ qkv, co
         const size_t x = (size_t)(kvh * rep + r) * HD;
         const float2 cs = rope[(size_t)pos * half + i];
         const float a = x_at(x + i), b = x_at(x + i + half);
-        r1 = a * cs.x - b * cs.y;
-        r2 = b * cs.x + a * cs.y;
+        r1 = rot_first(a, b, cs.x, cs.y);
+        r2 = rot_second(a, b, cs.x, cs.y);
       }
       qs[r * HD + i] = from_f32<f16>(r1);
       qs[r * HD + i + half] = from_f32<f16>(r2);
@@ -360,7 +360,7 @@ __device__ __forceinline__ void attention_unit(const float* __restrict__ qkv, co
       const float2 cs = rope[(size_t)pos * half + i];
       f16* kp = kpool + (size_t)new_page * page_elems + ((size_t)kvh * kPageTokens + new_slot) * HD;
       const float a = x_at(x + i), b = x_at(x + i + half);
-      const f16 k1 = from_f32<f16>(a * cs.x - b * cs.y), k2 = from_f32<f16>(b * cs.x + a * cs.y);
+      const f16 k1 = from_f32<f16>(rot_first(a, b, cs.x, cs.y)), k2 = from_f32<f16>(rot_second(a, b, cs.x, cs.y));
       kp[i] = k1; kp[i + half] = k2;
       knew[i] = k1; knew[i + half] = k2;
     }

@@ -78,20 +78,21 @@ hipError_t d_pack_weight16(const void* src, int n_rows, int K, void* dst, int ds
 // ---------------------------------------------------------------------------------------
 constexpr int kSsqPerThread = 12;   // up to 96 parts
 
+// ssq is not null and parts >= 1.  Every thread asks for all kSsqPerThread values, a part past the end being the last
+// part again (dropped in ssq_publish): with a request under a branch each, the compiler waited for the first one on
+// the spot - a memory round trip in front of the kernel's weight requests.
 __device__ __forceinline__ void ssq_issue(const float* __restrict__ ssq, int parts, int stride, int tok0,
                                           float (&sq)[kSsqPerThread]) {
   const int tok = threadIdx.x & 63, grp = threadIdx.x >> 6;
 #pragma unroll
-  for (int i = 0; i < kSsqPerThread; ++i) {
-    const int p = grp + 8 * i;
-    sq[i] = (ssq != nullptr && p < parts) ? ssq[(size_t)p * stride + tok0 + tok] : 0.f;
-  }
+  for (int i = 0; i < kSsqPerThread; ++i) sq[i] = ssq[(size_t)min(grp + 8 * i, parts - 1) * stride + tok0 + tok];
 }
 // s_part: LDS [8][64].  Call before a __syncthreads(); ssq_scale() after it.
-__device__ __forceinline__ void ssq_publish(const float (&sq)[kSsqPerThread], float* s_part) {
+__device__ __forceinline__ void ssq_publish(const float (&sq)[kSsqPerThread], int parts, float* s_part) {
+  const int grp = threadIdx.x >> 6;
   float s = 0.f;
 #pragma unroll
-  for (int i = 0; i < kSsqPerThread; ++i) s += sq[i];
+  for (int i = 0; i < kSsqPerThread; ++i) s += (grp + 8 * i < parts) ? sq[i] : 0.f;
   s_part[threadIdx.x] = s;
 }
 __device__ __forceinline__ float ssq_scale(const float* s_part, int tok_local, int norm_dim, float eps) {
@@ -190,7 +191,7 @@ __global__ void __launch_bounds__(512) k_skinny16(SkinnyArgs a, int n_units) {
       }
     }
   }
-  if (MODE != SKM_RESID) ssq_publish(sq, s_part);
+  if (MODE != SKM_RESID) ssq_publish(sq, a.ssq_parts, s_part);
   auto sum8 = [&](int tg, int l) -> float4 {   // tg = (t - chunk start) * TG + g
     float4 s = red[(size_t)tg * 64 + l];
 #pragma unroll
@@ -245,6 +246,16 @@ __global__ void __launch_bounds__(512) k_skinny16(SkinnyArgs a, int n_units) {
         }
       }
     } else {
+      if (CH == NT) {
+        // The operands requested up front are taken here, outside the branch on the row bound: otherwise the
+        // compiler, which cannot see that they landed rounds ago, waits for every outstanding memory operation where
+        // the branch rejoins - and that includes the residual store just issued, a full round trip in front of the
+        // second store.
+#pragma unroll
+        for (int i = 0; i < RS; ++i)
+          asm volatile("" ::"v"(h_old[i].x), "v"(h_old[i].y), "v"(h_old[i].z), "v"(h_old[i].w), "v"(g_next[i].x),
+                       "v"(g_next[i].y), "v"(g_next[i].z), "v"(g_next[i].w));
+      }
 #pragma unroll
       for (int i = 0; i < RS; ++i) {
         const int slot = tid + 512 * i;
@@ -300,7 +311,7 @@ static hipError_t launch_skinny(const SkinnyArgs& a, hipStream_t st) {
 // the re-reads of the token operand dominate and the blocking goes towards square.
 hipError_t d_gemm_skinny(const SkinnyArgs& a, int mode, hipStream_t st) {
   if (a.K % 32 != 0 || a.N % 16 != 0 || a.n_rows <= 0) return hipErrorInvalidValue;
-  if (mode != SKM_RESID && a.ssq_parts > 8 * kSsqPerThread) return hipErrorInvalidValue;
+  if (mode != SKM_RESID && (a.ssq_in == nullptr || a.ssq_parts < 1 || a.ssq_parts > 8 * kSsqPerThread)) return hipErrorInvalidValue;
   const int per_wave = ((a.K >> 5) + 7) / 8;   // k steps per wave
   const int tiles = a.N / 16;
   const bool multi = a.n_rows > 64;
@@ -456,6 +467,18 @@ struct LaneState {
   int bid[4];
 };
 
+// global -> LDS copy of one wave-wide 1 KiB block (lane l's 16 bytes land at lds + 16 l); completion is awaited with
+// wait_vmcnt_d (requests complete in order)
+__device__ __forceinline__ unsigned lds_addr16(const void* p) {
+  return (unsigned)(size_t)(const __attribute__((address_space(3))) void*)p;
+}
+__device__ __forceinline__ void dma16_lds(const void* g, unsigned lds) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds), "v"(g) : "memory");
+}
+template <int N> __device__ __forceinline__ void wait_vmcnt_d() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
 template <int U>
 __global__ void __launch_bounds__(512) k_lmhead_sample16(const uint4* __restrict__ Wp, const uint4* __restrict__ Xp, int KS,
                                                          int n_tiles, const float* __restrict__ ssq, int ssq_parts,
@@ -465,32 +488,9 @@ __global__ void __launch_bounds__(512) k_lmhead_sample16(const uint4* __restrict
   __shared__ float s_part[512];
   __shared__ float s_scale[64];
   const int tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63;
-  float sq[kSsqPerThread];
-  ssq_issue(ssq, ssq_parts, s_pad, 0, sq);
-  for (int i = tid; i < KS * 256; i += 512) xs[i] = Xp[i];
-  ssq_publish(sq, s_part);
-  __syncthreads();
-  if (tid < 64) s_scale[tid] = ssq_scale(s_part, tid, norm_dim, eps);
-  __syncthreads();
-  resolve_sample_params(sp);
-  const int step = *sp.step;
-  const bool noisy = sp.temperature != 0.f;
-  const float inv_t = noisy ? 1.0f / sp.temperature : 1.0f;
-  const int fq = lane >> 4, tl = lane & 15;
-  float scale[4];
-  uint32_t seq_id[4];   // the noise is keyed on the sequence, which need not be the row
-#pragma unroll
-  for (int g = 0; g < 4; ++g) {
-    scale[g] = s_scale[g * 16 + tl];
-    const int row = g * 16 + tl;
-    seq_id[g] = (uint32_t)((sp.slot_seq && row < n_rows) ? sp.slot_seq[row] : seq0 + row);
-  }
-  LaneState stt;
-#pragma unroll
-  for (int g = 0; g < 4; ++g) { stt.m[g] = -INFINITY; stt.l[g] = 0.f; stt.by[g] = -INFINITY; stt.bz[g] = 0.f; stt.bid[g] = 0x7fffffff; }
-
-  const int n_waves = gridDim.x * 8;
-  const int groups_per_tile = KS / U;
+  // The wave's first weight group is requested before anything else, and the token operand goes to LDS without
+  // passing through registers (copied through registers, every 16 bytes were one load, wait, LDS store - a
+  // dependent round trip per loop pass, KS / 2 of them in front of the first weight request).
   int tile = blockIdx.x * 8 + wave;
   Frag16 cur[U], nxt[U];
   if (tile < n_tiles) {
@@ -498,6 +498,38 @@ __global__ void __launch_bounds__(512) k_lmhead_sample16(const uint4* __restrict
 #pragma unroll
     for (int i = 0; i < U; ++i) cur[i].n = __builtin_nontemporal_load((const u32x4*)(wb + (size_t)i * 64));
   }
+  float sq[kSsqPerThread];
+  ssq_issue(ssq, ssq_parts, s_pad, 0, sq);
+  // the sampling parameters too (behind the copy below they would be read through the vector path, one more round trip)
+  resolve_sample_params(sp);
+  const int step = *sp.step;
+  const bool noisy = sp.temperature != 0.f;
+  const float inv_t = noisy ? 1.0f / sp.temperature : 1.0f;
+  const int fq = lane >> 4, tl = lane & 15;
+  uint32_t seq_id[4];   // the noise is keyed on the sequence, which need not be the row
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    const int row = g * 16 + tl;
+    seq_id[g] = (uint32_t)((sp.slot_seq && row < n_rows) ? sp.slot_seq[row] : seq0 + row);
+  }
+  {
+    const unsigned xs0 = __builtin_amdgcn_readfirstlane(lds_addr16(xs));
+    for (int b = wave * 64; b < KS * 256; b += 512) dma16_lds(Xp + b + lane, xs0 + (unsigned)b * 16u);
+  }
+  ssq_publish(sq, ssq_parts, s_part);
+  wait_vmcnt_d<0>();   // this wave's blocks of the operand have landed ...
+  __syncthreads();     // ... and everybody's
+  if (tid < 64) s_scale[tid] = ssq_scale(s_part, tid, norm_dim, eps);
+  __syncthreads();
+  float scale[4];
+#pragma unroll
+  for (int g = 0; g < 4; ++g) scale[g] = s_scale[g * 16 + tl];
+  LaneState stt;
+#pragma unroll
+  for (int g = 0; g < 4; ++g) { stt.m[g] = -INFINITY; stt.l[g] = 0.f; stt.by[g] = -INFINITY; stt.bz[g] = 0.f; stt.bid[g] = 0x7fffffff; }
+
+  const int n_waves = gridDim.x * 8;
+  const int groups_per_tile = KS / U;
   f32x4 acc[4];
 #pragma unroll
   for (int g = 0; g < 4; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -635,7 +667,8 @@ bool d_lmhead_sample_supported(int K, int n_rows) { return n_rows <= 64 && K % 3
 hipError_t d_lmhead_sample(const void* Wp, const void* Xp, int K, int V, const float* ssq, int ssq_parts, int s_pad,
                            float eps, int n_rows, SampleParams sp, float* partials, const void* embed,
                            const float* gain_first, float* h, void* xp_first, float* ssq_first, hipStream_t st) {
-  if (!d_lmhead_sample_supported(K, n_rows) || V % 16 != 0 || ssq_parts > 8 * kSsqPerThread) return hipErrorInvalidValue;
+  if (!d_lmhead_sample_supported(K, n_rows) || V % 16 != 0 || ssq == nullptr || ssq_parts < 1 || ssq_parts > 8 * kSsqPerThread)
+    return hipErrorInvalidValue;
   const int KS = K / 32, n_tiles = V / 16;
   int n_wg = 256;
   if (n_wg > (n_tiles + 7) / 8) n_wg = (n_tiles + 7) / 8;
@@ -657,18 +690,6 @@ hipError_t d_lmhead_merge_embed(const float* partials, int n_parts, int row_stri
                                 float* ssq_first, hipStream_t st) {
   return launch(KID_LMHEAD_SAMPLE_MERGE, k_lmhead_merge_embed, dim3(n_rows), dim3(128), 0, st, partials, n_parts, row_stride,
                 0, sp, (const bf16*)embed, d, gain_first, h, (uint4*)xp_first, ssq_first);
-}
-
-// global -> LDS copy of one wave-wide 1 KiB block (lane l's 16 bytes land at lds + 16 l); completion is awaited with
-// wait_vmcnt_d (requests complete in order)
-__device__ __forceinline__ unsigned lds_addr16(const void* p) {
-  return (unsigned)(size_t)(const __attribute__((address_space(3))) void*)p;
-}
-__device__ __forceinline__ void dma16_lds(const void* g, unsigned lds) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds), "v"(g) : "memory");
-}
-template <int N> __device__ __forceinline__ void wait_vmcnt_d() {
-  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
 // =======================================================================================
@@ -735,8 +756,8 @@ __device__ __forceinline__ void attention_prefix_role(const float* __restrict__ 
       if (cc < ncols) {
         const float* x = qkv + (size_t)(row0 + cc / rep) * row_floats + (size_t)(kvh * rep + cc % rep) * HD;
         const float2 cs = rope[(size_t)pos * half + i];
-        r1 = x[i] * cs.x - x[i + half] * cs.y;
-        r2 = x[i + half] * cs.x + x[i] * cs.y;
+        r1 = rot_first(x[i], x[i + half], cs.x, cs.y);
+        r2 = rot_second(x[i], x[i + half], cs.x, cs.y);
       }
       qs64[cc * HD + i] = from_f32<f16>(r1);
       qs64[cc * HD + i + half] = from_f32<f16>(r2);
@@ -895,9 +916,7 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
 
   // K rows of the two score tiles and the V tile of page pair pp: tile t row r is pair-token
   // 8 (r / 4) + 4 t + r % 4; the lane's V chunk holds pair-tokens 8 grp .. 8 grp + 7
-  auto load_pair = [&](int pp, Frag16 (&kf)[2][KK], Frag16 (&vf)[DT]) {
-    const int pa = pt[2 * pp];
-    const int pb = pt[min(2 * pp + 1, last_page)];
+  auto load_pages = [&](int pa, int pb, Frag16 (&kf)[2][KK], Frag16 (&vf)[DT]) {
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int r = lane & 15;
@@ -910,11 +929,12 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) vf[dt].u = *(const uint4*)(vp + (size_t)(dt * 16 + (lane & 15)) * kPageTokens);
   };
+  auto load_pair = [&](int pp, Frag16 (&kf)[2][KK], Frag16 (&vf)[DT]) {
+    load_pages(pt[2 * pp], pt[min(2 * pp + 1, last_page)], kf, vf);
+  };
   // the same requests into slot j of this wave's staging area
   const unsigned stage0 = LDS ? __builtin_amdgcn_readfirstlane(lds_addr16(sm_o) + (unsigned)wave * PD * NFRAG * 1024u) : 0u;
-  auto stage_pair = [&](int pp, int j) {
-    const int pa = pt[2 * pp];
-    const int pb = pt[min(2 * pp + 1, last_page)];
+  auto stage_pages = [&](int pa, int pb, int j) {
     const unsigned dst = stage0 + (unsigned)j * NFRAG * 1024u;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
@@ -928,6 +948,7 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) dma16_lds(vp + (size_t)(dt * 16 + (lane & 15)) * kPageTokens, dst + (unsigned)(2 * KK + dt) * 1024u);
   };
+  auto stage_pair = [&](int pp, int j) { stage_pages(pt[2 * pp], pt[min(2 * pp + 1, last_page)], j); };
   auto read_pair = [&](int j, Frag16 (&kf)[2][KK], Frag16 (&vf)[DT]) {
     const uint4* src = (const uint4*)sm_o + ((size_t)(wave * PD + j) * NFRAG) * 64 + lane;
 #pragma unroll
@@ -937,46 +958,85 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) vf[dt].u = src[(2 * KK + dt) * 64];
   };
+  // The row's own q / k / v values and rotary pairs are requested before the cached pages: loads complete in the
+  // order they were issued, so behind the pages they would be waited for together with every page in flight, and
+  // behind the appended key's stores together with those stores' acknowledgements.
+  constexpr int half = HD / 2;
+  constexpr int NQ = 16 * half / (NW * 64);   // query elements per thread
+  static_assert(NQ * NW * 64 == 16 * half && half <= NW * 64 && HD <= NW * 64, "whole passes over the 16 query rows");
+  const float* row = qkv + (size_t)s * (n_q_heads + 2 * hkv) * HD;
+  const int new_page = pt[pos / kPageTokens], new_slot = pos % kPageTokens;
+  // every thread asks (clamped to a valid row or element) so that nothing here sits under a branch
+  float qx1[NQ], qx2[NQ];
+  float2 qcs[NQ];
+#pragma unroll
+  for (int n = 0; n < NQ; ++n) {
+    const int idx = tid + n * NW * 64, r = min(idx / half, rep - 1), i = idx % half;
+    const float* x = row + (size_t)(kvh * rep + r) * HD;
+    qx1[n] = x[i];
+    qx2[n] = x[i + half];
+    qcs[n] = rope[(size_t)pos * half + i];
+  }
+  const int ki = min(tid, half - 1), vi = min(tid, HD - 1);
+  float kx1 = row[(size_t)(n_q_heads + kvh) * HD + ki], kx2 = row[(size_t)(n_q_heads + kvh) * HD + ki + half];
+  float2 kcs = rope[(size_t)pos * half + ki];
+  float vx = row[(size_t)(n_q_heads + hkv + kvh) * HD + vi];
+  __builtin_amdgcn_sched_barrier(0);   // ... and these requests stay in front of the pages'
+
   constexpr int PR = LDS ? 1 : PD;   // register sets of fragments
   Frag16 kf[PR][2][KK], vf[PR][DT];
+  // ---- the first page pairs are requested; rotary on the group's queries and the new key; append key / value ----
+  // The number of pairs a wave requests (0 .. PD, wave-uniform) selects one of PD + 1 copies of the code: within a
+  // copy the compiler knows how many requests stand behind the row's own values and waits for those alone, while
+  // the pages are still on their way.  (Requests under a branch each would leave it a wait for everything; asking
+  // for a page again in place of a missing pair costs more than it saves: a compute unit's ingest is the bound.)
+  int first_pa[PD], first_pb[PD];   // looked up here (a missing pair: the last one's entries, unused) rather than in the copies
 #pragma unroll
-  for (int j = 0; j < PD; ++j)
-    if (pp0 + wave + NW * j < npairs) {
-      if constexpr (LDS) stage_pair(pp0 + wave + NW * j, j);
-      else load_pair(pp0 + wave + NW * j, kf[j], vf[j]);
+  for (int j = 0; j < PD; ++j) {
+    const int pp = min(pp0 + wave + NW * j, npairs - 1);
+    first_pa[j] = pt[2 * pp];
+    first_pb[j] = pt[min(2 * pp + 1, last_page)];
+  }
+  auto first_pairs_and_rotary = [&](auto n_c) {
+    constexpr int n_req = decltype(n_c)::value;
+#pragma unroll
+    for (int j = 0; j < n_req; ++j) {
+      if constexpr (LDS) stage_pages(first_pa[j], first_pb[j], j);
+      else load_pages(first_pa[j], first_pb[j], kf[j], vf[j]);
     }
-
-  // ---- rotary on the group's queries and the new key; append key / value -------------------
-  {
-    const int half = HD / 2;
-    const int new_page = pt[pos / kPageTokens], new_slot = pos % kPageTokens;
-    const float* row = qkv + (size_t)s * (n_q_heads + 2 * hkv) * HD;
-    for (int idx = tid; idx < 16 * half; idx += NW * 64) {
-      const int r = idx / half, i = idx % half;
-      float r1 = 0.f, r2 = 0.f;
-      if (r < rep) {
-        const float* x = row + (size_t)(kvh * rep + r) * HD;
-        const float2 cs = rope[(size_t)pos * half + i];
-        r1 = x[i] * cs.x - x[i + half] * cs.y;
-        r2 = x[i + half] * cs.x + x[i] * cs.y;
-      }
-      qs[r * HD + i] = from_f32<f16>(r1);
-      qs[r * HD + i + half] = from_f32<f16>(r2);
+    __builtin_amdgcn_sched_barrier(0);
+    // nothing below may be moved above the requests (the compiler would otherwise convert the value element, and
+    // wait for it, in front of them)
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) asm volatile("" : "+v"(qx1[n]), "+v"(qx2[n]), "+v"(qcs[n].x), "+v"(qcs[n].y));
+    asm volatile("" : "+v"(kx1), "+v"(kx2), "+v"(kcs.x), "+v"(kcs.y), "+v"(vx));
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) {
+      const int idx = tid + n * NW * 64, r = idx / half, i = idx % half;
+      const bool live = r < rep;   // columns past the group's heads are zero
+      qs[r * HD + i] = from_f32<f16>(live ? rot_first(qx1[n], qx2[n], qcs[n].x, qcs[n].y) : 0.f);
+      qs[r * HD + i + half] = from_f32<f16>(live ? rot_second(qx1[n], qx2[n], qcs[n].x, qcs[n].y) : 0.f);
     }
-    for (int i = tid; i < half; i += NW * 64) {
-      const float* x = row + (size_t)(n_q_heads + kvh) * HD;
-      const float2 cs = rope[(size_t)pos * half + i];
+    if (tid < half) {
       f16* kp = kpool + (size_t)new_page * page_elems + ((size_t)kvh * kPageTokens + new_slot) * HD;
-      const f16 k1 = from_f32<f16>(x[i] * cs.x - x[i + half] * cs.y), k2 = from_f32<f16>(x[i + half] * cs.x + x[i] * cs.y);
-      kp[i] = k1; kp[i + half] = k2;
-      knew[i] = k1; knew[i + half] = k2;
+      const f16 k1 = from_f32<f16>(rot_first(kx1, kx2, kcs.x, kcs.y)), k2 = from_f32<f16>(rot_second(kx1, kx2, kcs.x, kcs.y));
+      kp[tid] = k1; kp[tid + half] = k2;
+      knew[tid] = k1; knew[tid + half] = k2;
     }
-    for (int i = tid; i < HD; i += NW * 64) {
-      const float* x = row + (size_t)(n_q_heads + hkv + kvh) * HD;
-      const f16 vv = from_f32<f16>(x[i]);
-      vpool[(size_t)new_page * page_elems + ((size_t)kvh * HD + i) * kPageTokens + new_slot] = vv;
-      vnew[i] = vv;
+    if (tid < HD) {
+      const f16 vv = from_f32<f16>(vx);
+      vpool[(size_t)new_page * page_elems + ((size_t)kvh * HD + tid) * kPageTokens + new_slot] = vv;
+      vnew[tid] = vv;
     }
+  };
+  {
+    static_assert(PD <= 3, "one copy per number of requested pairs");
+    const int mine = npairs - pp0 - wave;                                // pairs wave, wave + NW, ... below it
+    const int n_req = mine <= 0 ? 0 : min((mine + NW - 1) / NW, PD);
+    if (n_req == 0) first_pairs_and_rotary(std::integral_constant<int, 0>());
+    else if (n_req == 1 || PD == 1) first_pairs_and_rotary(std::integral_constant<int, 1>());
+    else if (n_req == 2 || PD == 2) first_pairs_and_rotary(std::integral_constant<int, (PD >= 2 ? 2 : 1)>());
+    else first_pairs_and_rotary(std::integral_constant<int, PD>());
   }
   __syncthreads();
   Frag16 qf[KK];
