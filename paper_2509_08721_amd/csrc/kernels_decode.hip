@@ -1005,11 +1005,6 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
       else load_pages(first_pa[j], first_pb[j], kf[j], vf[j]);
     }
     __builtin_amdgcn_sched_barrier(0);
-    // nothing below may be moved above the requests (the compiler would otherwise convert the value element, and
-    // wait for it, in front of them)
-#pragma unroll
-    for (int n = 0; n < NQ; ++n) asm volatile("" : "+v"(qx1[n]), "+v"(qx2[n]), "+v"(qcs[n].x), "+v"(qcs[n].y));
-    asm volatile("" : "+v"(kx1), "+v"(kx2), "+v"(kcs.x), "+v"(kcs.y), "+v"(vx));
 #pragma unroll
     for (int n = 0; n < NQ; ++n) {
       const int idx = tid + n * NW * 64, r = idx / half, i = idx % half;
