@@ -8,6 +8,14 @@ guards around MFMAs (the wave index is read as a scalar); this check makes sure 
 follows a `saveexec` inside the same masked region must have a branch on the mask in front of it.
 
     python -m paper_2509_08721_amd.isa_check        # compiles every source of the library to assembly and checks it
+
+A second scan is a report, not a pass/fail check (`--waits`): one counter covers a wave's loads and stores and they
+retire in issue order, so a wait for a loaded value that was requested behind a store also waits for that store's
+acknowledgement - a memory round trip in the middle of an epilogue.  `waits_behind_stores` lists the waits that
+allow fewer outstanding operations than there are stores issued before them in program order (a linear scan: it does
+not follow branches, so it over-reports where a store and the wait sit on different paths).
+
+    python -m paper_2509_08721_amd.isa_check --waits
 """
 from __future__ import annotations
 
@@ -50,6 +58,44 @@ def unguarded_mfmas(asm_text: str):
     return out
 
 
+def waits_behind_stores(asm_text: str):
+    """{function: [(line number, allowed outstanding, stores issued before in program order)]}."""
+    out = {}
+    fn, pending = None, 0
+    for i, raw in enumerate(asm_text.splitlines(), 1):
+        line = raw.split(";")[0].strip()
+        if not line:
+            continue
+        m = re.match(r"^(_Z\w+):$", line)
+        if m:
+            fn, pending = m.group(1), 0
+            continue
+        if fn is None or line.startswith("."):
+            continue
+        op = line.split()[0]
+        if op == "s_endpgm":
+            pending = 0
+        elif re.match(r"(global|buffer|scratch|flat)_(store|atomic)", op):
+            pending += 1
+        elif op == "s_waitcnt":
+            m = re.search(r"vmcnt\((\d+)\)", line)
+            if m:
+                n = int(m.group(1))
+                if pending > n:
+                    out.setdefault(fn, []).append((i, n, pending))
+                pending = min(pending, n)
+    return out
+
+
+def assemble(src: str, tmp: str) -> str:
+    """The gfx950 assembly of one source of the library."""
+    flags = [f for f in B.FLAGS if f not in ("-fPIC",)] + ["--cuda-device-only", "-S"]
+    out = os.path.join(tmp, src.replace(".hip", ".s"))
+    B._run([B._hipcc()] + flags + [os.path.join(B.CSRC, src), "-o", out])
+    with open(out) as f:
+        return f.read()
+
+
 def check_sources(verbose: bool = True):
     hipcc = B._hipcc()
     flags = [f for f in B.FLAGS if f not in ("-fPIC",)] + ["--cuda-device-only", "-S"]
@@ -69,6 +115,13 @@ def check_sources(verbose: bool = True):
 
 
 if __name__ == "__main__":
+    if "--waits" in sys.argv[1:]:
+        with tempfile.TemporaryDirectory() as tmp:
+            for src in B.SOURCES:
+                for fn, found in sorted(waits_behind_stores(assemble(src, tmp)).items()):
+                    print("%-22s %-70s %3d wait(s) behind stores, first at line %d (vmcnt(%d), %d stores before)" % (
+                        (src, fn[:70], len(found)) + found[0]))
+        sys.exit(0)
     problems = check_sources()
     for p in problems[:20]:
         print("  %s: %s line %d: %s" % p)

@@ -43,3 +43,40 @@ def test_accepts_a_branch_on_the_mask_and_code_after_the_restore():
 @pytest.mark.skipif(shutil.which("hipcc") is None and not shutil.os.path.exists("/opt/rocm/bin/hipcc"), reason="no hipcc")
 def test_every_source_of_the_library_is_clean():
     assert isa_check.check_sources(verbose=False) == []
+
+
+STORE_THEN_LOAD = """
+_Z6kernelPv:
+	global_load_dwordx4 v[0:3], v[4:5], off
+	s_waitcnt vmcnt(0)
+	global_store_dwordx4 v[4:5], v[0:3], off
+	global_load_dwordx4 v[8:11], v[6:7], off
+	s_waitcnt vmcnt(0)
+	global_store_dwordx4 v[6:7], v[8:11], off
+	s_endpgm
+"""
+
+LOADS_AHEAD = """
+_Z6kernelPv:
+	global_load_dwordx4 v[0:3], v[4:5], off
+	global_load_dwordx4 v[8:11], v[6:7], off
+	s_waitcnt vmcnt(1)
+	global_store_dwordx4 v[4:5], v[0:3], off
+	s_waitcnt vmcnt(1)
+	global_store_dwordx4 v[6:7], v[8:11], off
+	s_endpgm
+"""
+
+
+def test_reports_a_wait_that_covers_a_store():
+    found = isa_check.waits_behind_stores(STORE_THEN_LOAD)
+    assert list(found) == ["_Z6kernelPv"] and found["_Z6kernelPv"] == [(7, 0, 1)]
+    # the second load requested before the first store: the wait for it leaves the store outstanding
+    assert isa_check.waits_behind_stores(LOADS_AHEAD) == {}
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None and not shutil.os.path.exists("/opt/rocm/bin/hipcc"), reason="no hipcc")
+def test_residual_epilogues_of_the_decode_gemms_do_not_wait_behind_their_stores(tmp_path):
+    found = isa_check.waits_behind_stores(isa_check.assemble("kernels_decode.hip", str(tmp_path)))
+    resid = [fn for fn in found if "k_skinny16" in fn and fn.endswith("ELi1EEEvNS_10SkinnyArgsEi")]
+    assert resid == [], resid
