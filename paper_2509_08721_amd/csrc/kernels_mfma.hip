@@ -152,37 +152,43 @@ static int big_grid(int NX, int NY) {
 struct NoPrologue { __device__ __forceinline__ void operator()() const {} };
 // `prologue` runs once the first two stages are requested (loads it issues ride on the same latency).
 // NS: depth of the LDS ring (NS - 1 stages in flight).
-template <int NS = kStages, class Prologue = NoPrologue>
+// TJ: 32-token blocks per wave (4: a 256-token tile, the default; 2: a 128-token tile with a third workgroup per
+// compute unit, for launches whose 256-token tiles would leave the last round of workgroups mostly empty).
+template <int NS = kStages, class Prologue = NoPrologue, int TJ = 4>
 __device__ __forceinline__ void big_mainloop(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int n_tblk,
-                                             int KS, int tblk0, int fblk0, uint4* smem, f32x16 (&acc)[2][4],
+                                             int KS, int tblk0, int fblk0, uint4* smem, f32x16 (&acc)[2][TJ],
                                              Prologue prologue = Prologue(), int st0 = 0, int n_stages = -1) {
+  constexpr int TF = 4 * TJ;        // token fragments of a stage (2 TJ token blocks x 2 k halves)
+  constexpr int SF = TF + 8;        // fragments of a stage
+  constexpr int NF = SF / 4;        // requests per wave and stage
+  static_assert(TJ == 4 || TJ == 2, "tile of 256 or 128 tokens");
   const int tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63;
   const int wf = wave & 1, wt = wave >> 1;
   const int nst = n_stages < 0 ? (KS >> 1) : n_stages;   // stages of 32 k; a split-K workgroup runs st0 .. st0 + nst - 1
-  const uint4* src[6];
-  unsigned dst[6];
+  const uint4* src[NF];
+  unsigned dst[NF];
 #pragma unroll
-  for (int i = 0; i < 6; ++i) {
-    const int f = wave * 6 + i;
-    if (f < 16) {
+  for (int i = 0; i < NF; ++i) {
+    const int f = wave * NF + i;
+    if (f < TF) {
       int tb = tblk0 + (f >> 1);
       if (tb > n_tblk - 1) tb = n_tblk - 1;
       src[i] = Xp + ((size_t)tb * KS + 2 * st0 + (f & 1)) * 64 + lane;
     } else {
-      const int g = f - 16;
+      const int g = f - TF;
       src[i] = Wp + ((size_t)(fblk0 + (g >> 1)) * KS + 2 * st0 + (g & 1)) * 64 + lane;
     }
     dst[i] = __builtin_amdgcn_readfirstlane(lds_addr(smem + f * 64));
   }
   auto issue = [&](int st) {
-    const unsigned sbase = (unsigned)((st % NS) * kStageFrags * 1024);
+    const unsigned sbase = (unsigned)((st % NS) * SF * 1024);
 #pragma unroll
-    for (int i = 0; i < 6; ++i) dma16(src[i] + (size_t)st * 128, dst[i] + sbase);
+    for (int i = 0; i < NF; ++i) dma16(src[i] + (size_t)st * 128, dst[i] + sbase);
   };
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int b = 0; b < 4; ++b)
+    for (int b = 0; b < TJ; ++b)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
   wg_barrier();   // a previous pass over the ring (fused LM head) is over in every wave
@@ -193,33 +199,33 @@ __device__ __forceinline__ void big_mainloop(const uint4* __restrict__ Xp, const
   for (int st = 0; st < nst; ++st) {
     // this wave's part of stage st has landed once at most the newer stages' requests are outstanding
     const int newer = min(NS - 2, nst - 1 - st);
-    if (newer >= 4) wait_vmcnt<24>();
-    else if (newer == 3) wait_vmcnt<18>();
-    else if (newer == 2) wait_vmcnt<12>();
-    else if (newer == 1) wait_vmcnt<6>();
+    if (newer >= 4) wait_vmcnt<4 * NF>();
+    else if (newer == 3) wait_vmcnt<3 * NF>();
+    else if (newer == 2) wait_vmcnt<2 * NF>();
+    else if (newer == 1) wait_vmcnt<NF>();
     else wait_vmcnt<0>();
     wg_barrier();                                               // ... and everybody's; stage st-1 is consumed
-    // The six requests of stage st + NS - 1 go out one after each of the first six MFMAs instead of in a burst behind
+    // The requests of stage st + NS - 1 go out one after each of the first MFMAs instead of in a burst behind
     // the barrier: the burst held up the LDS reads and MFMAs queued behind it (same sums, 15 % faster on the scorer's
     // shape in a stand-alone copy of the loop).  The fences keep the compiler from regrouping them.
     const bool more = st + NS - 1 < nst;
-    const unsigned next_base = (unsigned)(((st + NS - 1) % NS) * kStageFrags * 1024);
+    const unsigned next_base = (unsigned)(((st + NS - 1) % NS) * SF * 1024);
     const size_t next_off = (size_t)(st + NS - 1) * 128;
-    const uint4* buf = smem + (st % NS) * kStageFrags * 64;
+    const uint4* buf = smem + (st % NS) * SF * 64;
 #pragma unroll
     for (int s2 = 0; s2 < 2; ++s2) {
-      Frag xf[4], wfr[2];
+      Frag xf[TJ], wfr[2];
 #pragma unroll
-      for (int tj = 0; tj < 4; ++tj) xf[tj].u = buf[((wt * 4 + tj) * 2 + s2) * 64 + lane];
+      for (int tj = 0; tj < TJ; ++tj) xf[tj].u = buf[((wt * TJ + tj) * 2 + s2) * 64 + lane];
 #pragma unroll
-      for (int fi = 0; fi < 2; ++fi) wfr[fi].u = buf[(16 + (wf * 2 + fi) * 2 + s2) * 64 + lane];
+      for (int fi = 0; fi < 2; ++fi) wfr[fi].u = buf[(TF + (wf * 2 + fi) * 2 + s2) * 64 + lane];
 #pragma unroll
       for (int fi = 0; fi < 2; ++fi)
 #pragma unroll
-        for (int tj = 0; tj < 4; ++tj) {
+        for (int tj = 0; tj < TJ; ++tj) {
           acc[fi][tj] = mfma32(wfr[fi], xf[tj], acc[fi][tj]);
-          const int m = s2 * 8 + fi * 4 + tj;
-          if (m < 6) {
+          const int m = (s2 * 2 + fi) * TJ + tj;
+          if (m < NF) {
             __builtin_amdgcn_sched_barrier(0);
             if (more) dma16(src[m] + next_off, dst[m] + next_base);
             __builtin_amdgcn_sched_barrier(0);
@@ -229,8 +235,10 @@ __device__ __forceinline__ void big_mainloop(const uint4* __restrict__ Xp, const
   }
 }
 
-__global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp, int M,
-                                                     int N, int K, BigEpi ep) {
+template <int TJ>
+__global__ void __launch_bounds__(256, TJ == 4 ? 2 : 3) k_gemm_big(const uint4* __restrict__ Xp, const uint4* __restrict__ Wp,
+                                                                  int M, int N, int K, BigEpi ep) {
+  constexpr int TM = 64 * TJ;   // tokens per tile
   extern __shared__ uint4 smem[];
   int bx, by, st0 = 0, n_st = K >> 5;
   if (ep.splits > 1) {
@@ -242,26 +250,28 @@ __global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ X
     st0 = (int)((long)z * n_st / ep.splits);
     n_st = (int)((long)(z + 1) * n_st / ep.splits) - st0;
     ep.out_f32 += (size_t)z * ep.split_stride;
-  } else if (!big_raster(N >> 7, (M + 255) >> 8, bx, by)) {
+  } else if (!big_raster(N >> 7, (M + TM - 1) / TM, bx, by)) {
     return;
   }
-  f32x16 acc[2][4];
+  f32x16 acc[2][TJ];
   const int wave = wave_index(threadIdx.x), lane = threadIdx.x & 63;
   const int wf = wave & 1, wt = wave >> 1;
-  float row_scale[4] = {1.f, 1.f, 1.f, 1.f};
-  big_mainloop(Xp, Wp, (M + 31) >> 5, K >> 4, by * 8, bx * 4, smem, acc, [&]() {
+  float row_scale[TJ];
+#pragma unroll
+  for (int tj = 0; tj < TJ; ++tj) row_scale[tj] = 1.f;
+  auto prologue = [&]() {
     if (!ep.ssq_in) return;
     const int ps = (ep.ssq_parts + 3) & ~3;   // row stride of the parts; at most 16 parts
-    float4 part[4][4];
+    float4 part[TJ][4];
 #pragma unroll
-    for (int tj = 0; tj < 4; ++tj) {
-      const int tok = min(by * 256 + wt * 128 + tj * 32 + (lane & 31), M - 1);
+    for (int tj = 0; tj < TJ; ++tj) {
+      const int tok = min(by * TM + wt * (32 * TJ) + tj * 32 + (lane & 31), M - 1);
 #pragma unroll
       for (int i = 0; i < 4; ++i)
         part[tj][i] = (4 * i < ps) ? *(const float4*)(ep.ssq_in + (size_t)tok * ps + 4 * i) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
 #pragma unroll
-    for (int tj = 0; tj < 4; ++tj) {
+    for (int tj = 0; tj < TJ; ++tj) {
       float ss = 0.f;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {   // padding slots are never written: select, do not add
@@ -272,9 +282,12 @@ __global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ X
       }
       row_scale[tj] = rsqrtf(ss / ep.norm_dim + ep.eps);
     }
-  }, st0, n_st);
-  float ssq_mine[4] = {0.f, 0.f, 0.f, 0.f};
-  const int tok0 = by * 256 + wt * 128 + (lane & 31);
+  };
+  big_mainloop<kStages, decltype(prologue), TJ>(Xp, Wp, (M + 31) >> 5, K >> 4, by * (2 * TJ), bx * 4, smem, acc, prologue, st0, n_st);
+  float ssq_mine[TJ];
+#pragma unroll
+  for (int tj = 0; tj < TJ; ++tj) ssq_mine[tj] = 0.f;
+  const int tok0 = by * TM + wt * (32 * TJ) + (lane & 31);
   const int fcol = bx * 128 + wf * 64 + (lane >> 5) * 4;   // + fi * 32 + 8 r: this lane's four features of block (fi, r)
   float4 bb[2][4];
   if (ep.mode == BIG_STORE_F32 && ep.bias) {
@@ -284,7 +297,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ X
       for (int r = 0; r < 4; ++r) bb[fi][r] = *(const float4*)(ep.bias + fcol + fi * 32 + 8 * r);
   }
 #pragma unroll
-  for (int tj = 0; tj < 4; ++tj) {
+  for (int tj = 0; tj < TJ; ++tj) {
     const int tok = tok0 + tj * 32;
     if (tok >= M) continue;   // lanes l and l + 32 hold the same token: they leave together
     if (ep.ssq_in) {
@@ -320,17 +333,17 @@ __global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ X
     // Residual update.  In the accumulator layout a lane holds one token, so a load or store instruction on the
     // row-major fp32 residual touches 32 cache lines for 1 KiB.  The residual therefore moves in row layout (16 lanes
     // cover 256 contiguous bytes of a row: 8 full lines per instruction) and changes layout through LDS, once on the
-    // way in and once on the way out, a wave's 64 tokens x 64 features at a time in the wave's own part of the ring
-    // (rows padded to 68 floats).  The sums, the next operand and the sums of squares are taken in the accumulator
+    // way in and once on the way out, a wave's 64 (128-token tiles: 32) tokens x 64 features at a time in the wave's own
+    // part of the ring (rows padded to 68 floats).  The sums, the next operand and the sums of squares are taken in the accumulator
     // layout as before: same results bit for bit.  The second half's rows are requested before the first half's
     // stores, since a load issued behind a store also waits for the store's acknowledgement.  A tile without rows
     // past the end and the producer side are compile-time cases, so that the common one is straight-line code
     // whose waits the compiler can count exactly.
-    constexpr int RS = 68;
+    constexpr int RS = 68, HB = TJ == 4 ? 64 : 32, T2 = HB / 32, NI = HB / 4;   // HB tokens per pass, two passes
     wg_barrier();   // every wave has read its last stage: the ring is free
-    float* R = (float*)smem + wave * (64 * RS);
+    float* R = (float*)smem + wave * (HB * RS);
     const int rt = lane >> 4, rc = (lane & 15) * 4;   // row layout: token 4 i + rt of the half, features rc .. rc + 3
-    const int row0 = by * 256 + wt * 128, gcol = bx * 128 + wf * 64;
+    const int row0 = by * TM + wt * (32 * TJ), gcol = bx * 128 + wf * 64;
     auto wave_sync = [] {
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
@@ -340,27 +353,27 @@ __global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ X
       constexpr bool full = decltype(full_c)::value, prod = decltype(prod_c)::value;
       // the wave's 64 gains wait in LDS behind the four row areas (held in registers they would not fit next to the
       // rows in flight)
-      float* G = (float*)smem + 4 * 64 * RS + wave * 64;
+      float* G = (float*)smem + 4 * HB * RS + wave * 64;
       if (prod && lane < 16) *(float4*)(G + 4 * lane) = *(const float4*)(ep.gain_next + gcol + 4 * lane);
-      float4 in[16];
+      float4 in[NI];
       auto request = [&](int h, int i0) {   // rows 4 i + rt, i = i0 .. i0 + 7, of half h
 #pragma unroll
         for (int i = i0; i < i0 + 8; ++i) {
-          const int tok = row0 + h * 64 + 4 * i + rt;
+          const int tok = row0 + h * HB + 4 * i + rt;
           in[i] = (full || tok < M) ? *(const float4*)(ep.out_f32 + (size_t)tok * ep.ldc + gcol + rc)
                                     : make_float4(0.f, 0.f, 0.f, 0.f);
         }
       };
-      request(0, 0);
-      request(0, 8);
+#pragma unroll
+      for (int i0 = 0; i0 < NI; i0 += 8) request(0, i0);
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) *(float4*)(R + (4 * i + rt) * RS + rc) = in[i];
+        for (int i = 0; i < NI; ++i) *(float4*)(R + (4 * i + rt) * RS + rc) = in[i];
         wave_sync();
 #pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2) {
-          const int tj = 2 * h + t2, tok = tok0 + tj * 32;
+        for (int t2 = 0; t2 < T2; ++t2) {
+          const int tj = T2 * h + t2, tok = tok0 + tj * 32;
           float ssq = 0.f;
 #pragma unroll
           for (int fi = 0; fi < 2; ++fi)
@@ -384,21 +397,21 @@ __global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ X
         }
         wave_sync();
 #pragma unroll
-        for (int i0 = 0; i0 < 16; i0 += 8) {   // eight rows at a time: sixteen out and sixteen in would not fit the registers
+        for (int i0 = 0; i0 < NI; i0 += 8) {   // eight rows at a time: sixteen out and sixteen in would not fit the registers
           float4 out[8];
 #pragma unroll
           for (int i = 0; i < 8; ++i) out[i] = *(const float4*)(R + (4 * (i0 + i) + rt) * RS + rc);
           if (h == 0) request(1, i0);
 #pragma unroll
           for (int i = 0; i < 8; ++i) {
-            const int tok = row0 + h * 64 + 4 * (i0 + i) + rt;
+            const int tok = row0 + h * HB + 4 * (i0 + i) + rt;
             if (full || tok < M) *(float4*)(ep.out_f32 + (size_t)tok * ep.ldc + gcol + rc) = out[i];
           }
         }
         wave_sync();   // the rows are in registers before the next half overwrites them
       }
     };
-    const bool full = by * 256 + 256 <= M;
+    const bool full = by * TM + TM <= M;
     if (ep.gain_next) {
       if (full) update(std::true_type(), std::true_type());
       else update(std::false_type(), std::true_type());
@@ -411,15 +424,15 @@ __global__ void __launch_bounds__(256, 2) k_gemm_big(const uint4* __restrict__ X
     __shared__ float red[256];
     if (wf == 1 && lane < 32) {
 #pragma unroll
-      for (int tj = 0; tj < 4; ++tj) red[wt * 128 + tj * 32 + lane] = ssq_mine[tj];
+      for (int tj = 0; tj < TJ; ++tj) red[wt * (32 * TJ) + tj * 32 + lane] = ssq_mine[tj];
     }
     __syncthreads();
     if (wf == 0 && lane < 32) {
       const int ps = ((N >> 7) + 3) & ~3;
 #pragma unroll
-      for (int tj = 0; tj < 4; ++tj) {
-        const int tok = by * 256 + wt * 128 + tj * 32 + lane;
-        if (tok < M) ep.ssq_out[(size_t)tok * ps + bx] = ssq_mine[tj] + red[wt * 128 + tj * 32 + lane];
+      for (int tj = 0; tj < TJ; ++tj) {
+        const int tok = by * TM + wt * (32 * TJ) + tj * 32 + lane;
+        if (tok < M) ep.ssq_out[(size_t)tok * ps + bx] = ssq_mine[tj] + red[wt * (32 * TJ) + tj * 32 + lane];
       }
     }
   }
@@ -640,12 +653,37 @@ hipError_t m_gemm_qkv_rope(const void* Xp, const void* Wp, int M, int N, int K, 
                 epi);
 }
 
+// 128-token tiles (three workgroups per compute unit) instead of 256-token tiles (two): for narrow outputs whose
+// 256-token tiles fill their last round of resident workgroups badly, when the half-size tiles need no more rounds
+// (64 x 384 tokens x 896 features: 672 tiles in 2 rounds of 512 become 1344 in 2 rounds of 768; O projection 86 ->
+// 70 us, the prompt's small launches 70 -> 58 us.  With one round more - 64 x 768: 4 against 3 - the down projection
+// lost 14 %, so that case keeps the large tile).  SAPO_BIG_TILE=128 / 256 in the environment forces one or the
+// other (measurement).
+static bool big_prefers_small_tiles(int NX, int M) {
+  static int forced = -1, n_cu = 0;
+  if (forced < 0) {
+    const char* e = getenv("SAPO_BIG_TILE");
+    forced = e ? atoi(e) : 0;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+      n_cu = 256;
+  }
+  if (forced == 128) return true;
+  if (forced == 256) return false;
+  if (NX > 16) return false;   // wide outputs have rounds enough: the smaller tile only adds operand traffic per flop
+  const long big = (long)NX * ((M + 255) / 256), small = (long)NX * ((M + 127) / 128);
+  const long rounds_big = (big + 2 * n_cu - 1) / (2 * n_cu), rounds_small = (small + 3 * n_cu - 1) / (3 * n_cu);
+  return rounds_small <= rounds_big;
+}
+
 hipError_t m_gemm_big(const void* Xp, const void* Wp, int M, int N, int K, BigEpi epi, hipStream_t st) {
   if (M == 0) return hipSuccess;
   if (N % 128 != 0 || K % 32 != 0) return hipErrorInvalidValue;
+  constexpr int kSmallLds = kStages * (8 + 8) * 1024;   // the ring of a 128-token tile: 8 token + 8 feature fragments per stage
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_gemm_big, hipFuncAttributeMaxDynamicSharedMemorySize, kBigLds);
+    hipError_t e = hipFuncSetAttribute((const void*)k_gemm_big<4>, hipFuncAttributeMaxDynamicSharedMemorySize, kBigLds);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_gemm_big<2>, hipFuncAttributeMaxDynamicSharedMemorySize, kSmallLds);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
@@ -653,8 +691,13 @@ hipError_t m_gemm_big(const void* Xp, const void* Wp, int M, int N, int K, BigEp
                                             epi.mode != BIG_STORE_F32 || epi.ssq_in || epi.bias)))
     return hipErrorInvalidValue;
   if (epi.gain_next && epi.mode != BIG_ADD_F32) return hipErrorInvalidValue;
+  if (epi.splits == 1 && big_prefers_small_tiles(N / 128, M)) {
+    const int g2 = big_grid(N / 128, (M + 127) / 128);
+    return launch(epi.decode ? KID_GEMM_BIG_DECODE : KID_GEMM_BIG, k_gemm_big<2>, dim3(g2), dim3(256), kSmallLds, st,
+                  (const uint4*)Xp, (const uint4*)Wp, M, N, K, epi);
+  }
   const int g = epi.splits > 1 ? epi.splits * (N / 128) : big_grid(N / 128, (M + 255) / 256);
-  return launch(epi.decode ? KID_GEMM_BIG_DECODE : KID_GEMM_BIG, k_gemm_big, dim3(g), dim3(256), kBigLds, st, (const uint4*)Xp,
+  return launch(epi.decode ? KID_GEMM_BIG_DECODE : KID_GEMM_BIG, k_gemm_big<4>, dim3(g), dim3(256), kBigLds, st, (const uint4*)Xp,
                 (const uint4*)Wp, M, N, K, epi);
 }
 
