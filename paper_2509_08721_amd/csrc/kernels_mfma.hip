@@ -660,14 +660,14 @@ hipError_t m_gemm_qkv_rope(const void* Xp, const void* Wp, int M, int N, int K, 
 // lost 14 %, so that case keeps the large tile).  SAPO_BIG_TILE=128 / 256 in the environment forces one or the
 // other (measurement).
 static bool big_prefers_small_tiles(int NX, int M) {
-  static int forced = -1, n_cu = 0;
-  if (forced < 0) {
-    const char* e = getenv("SAPO_BIG_TILE");
-    forced = e ? atoi(e) : 0;
+  static int n_cu = 0;
+  if (n_cu == 0) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
       n_cu = 256;
   }
+  const char* e = getenv("SAPO_BIG_TILE");   // read per call, so that a test can switch it
+  const int forced = e ? atoi(e) : 0;
   if (forced == 128) return true;
   if (forced == 256) return false;
   if (NX > 16) return false;   // wide outputs have rounds enough: the smaller tile only adds operand traffic per flop

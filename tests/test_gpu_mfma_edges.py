@@ -124,3 +124,27 @@ def test_scoring_smallest_and_largest_batches(sapo, model, S, T, G):
     with pytest.raises(sapo.SapoError):
         sapo.sapo_score_logprobs(gw, dev(np.zeros((1, shape.max_seq + 1), dtype=np.int32)),
                                  dev(np.ones((1, shape.max_seq + 1), dtype=np.uint8)), dev(np.zeros(1, dtype=np.float32)), 1)
+
+
+@pytest.mark.parametrize("S,T", [(3, 200),      # 600 rows: the last 128-token and 256-token tiles both end inside
+                                 (8, 128)])     # 1024 rows: whole tiles of either height
+def test_both_tile_heights_of_the_token_parallel_gemm_give_the_same_bits(sapo, model, S, T):
+    """The projections run on 256-token or 128-token tiles, chosen per launch from how full the rounds of resident
+    workgroups are; SAPO_BIG_TILE forces one.  Same products in the same order: the log-probs must agree bit for bit,
+    and with the oracle as everywhere."""
+    import os
+    shape, w, gw, ma = model
+    rng = np.random.default_rng(S * 7 + T)
+    toks = rng.integers(0, shape.vocab, size=(S, T)).astype(np.int32)
+    mask = np.ones((S, T), dtype=np.uint8)
+    rewards = rng.random(S).astype(np.float32)
+    out = {}
+    try:
+        for tile in ("128", "256"):
+            os.environ["SAPO_BIG_TILE"] = tile
+            lp, _ = sapo.sapo_score_logprobs(gw, dev(toks), dev(mask), dev(rewards), 1)
+            out[tile] = lp.cpu().numpy()
+    finally:
+        os.environ.pop("SAPO_BIG_TILE", None)
+    assert np.array_equal(out["128"].view(np.uint32), out["256"].view(np.uint32))
+    assert np.max(np.abs(out["256"] - O.score_logprobs(ma, toks, mask))) <= LOGPROB_TOL
