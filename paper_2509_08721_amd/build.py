@@ -21,6 +21,8 @@ SOURCES = ["api.hip", "kernels_generic.hip", "kernels_mfma.hip", "kernels_decode
 # SAPO_PERSIST_TRACE=1 in the environment: diagnostic build of the persistent decode kernel (per-phase tick counters)
 FLAGS = (["-DSAPO_PERSIST_TRACE"] if os.environ.get("SAPO_PERSIST_TRACE") == "1" else []) + ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # the first kernel arguments arrive in scalar registers with the wave instead of through a load
+         "-mllvm", "-amdgpu-kernarg-preload-count=16",
          "-Wall", "-Wno-unused-function", "-Wno-unused-variable"]
 
 
