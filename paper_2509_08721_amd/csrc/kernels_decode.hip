@@ -891,12 +891,12 @@ __device__ __forceinline__ void attention_prefix_role(const float* __restrict__ 
 template <int HD, int NW, int PD, bool LDS, bool SHARE>
 __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __restrict__ qkv,
                                                                const float2* __restrict__ rope, const int* step_,
-                                                               const int* page_table_, void* kpool_, void* vpool_, int Lp_,
-                                                               int pages_per_seq_, RowMap rm, KVCache kv,
-                                                               uint4* __restrict__ out, int n_q_heads, ShareArgs sh) {
-  // what leads from the start of the kernel to its first requests arrives preloaded (see k_skinny16)
+                                                               const int* page_table_, int Lp_, int pages_per_seq_,
+                                                               int n_kv_heads_, int n_q_heads, void* kpool_, RowMap rm,
+                                                               KVCache kv, uint4* __restrict__ out, ShareArgs sh) {
+  // what leads from the start of the kernel to its first requests arrives preloaded (see k_skinny16): 14 dwords
   rm.step = step_; rm.Lp = Lp_;
-  kv.page_table = page_table_; kv.k = kpool_; kv.v = vpool_; kv.pages_per_seq = pages_per_seq_;
+  kv.page_table = page_table_; kv.pages_per_seq = pages_per_seq_; kv.n_kv_heads = n_kv_heads_; kv.k = kpool_;
   constexpr int KK = HD / 32;   // k steps of S^T = K Q^T
   constexpr int DT = HD / 16;   // 16-row tiles of O^T
   constexpr int NFRAG = 2 * KK + DT;                        // 1 KiB fragments of one page pair
@@ -990,12 +990,14 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
     const float* x = row + (size_t)(kvh * rep + r) * HD;
     qx1[n] = x[i];
     qx2[n] = x[i + half];
-    qcs[n] = rope[(size_t)pos * half + i];
   }
   const int ki = min(tid, half - 1), vi = min(tid, HD - 1);
   float kx1 = row[(size_t)(n_q_heads + kvh) * HD + ki], kx2 = row[(size_t)(n_q_heads + kvh) * HD + ki + half];
-  float2 kcs = rope[(size_t)pos * half + ki];
   float vx = row[(size_t)(n_q_heads + hkv + kvh) * HD + vi];
+  // ... the rotary pairs behind them: they need the position, which is a load away (the step counter)
+#pragma unroll
+  for (int n = 0; n < NQ; ++n) qcs[n] = rope[(size_t)pos * half + (tid + n * NW * 64) % half];
+  float2 kcs = rope[(size_t)pos * half + ki];
   __builtin_amdgcn_sched_barrier(0);   // ... and these requests stay in front of the pages'
 
   constexpr int PR = LDS ? 1 : PD;   // register sets of fragments
@@ -1176,23 +1178,23 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
     }
   }
   __syncthreads();
-  // thread -> (query q, 8 consecutive head dims): one 16-byte chunk of the X16 output.  Waves that
-  // had no page pair carry (m = -inf, l = 0, o = 0) and drop out of the merge.
+  // thread -> (query head q, head dim d): one half of the X16 output (the query heads run fastest over the lanes: their
+  // LDS columns are adjacent).  With one thread per 16-byte chunk only rep x HD / 8 threads - one wave - did the
+  // whole merge, 80 dependent LDS reads each: 0.8 us at the end of a 4.5 us kernel.  Waves that had no page pair
+  // carry (m = -inf, l = 0, o = 0) and drop out of the merge.
   const int KSo = (n_q_heads * HD) >> 5;
-  for (int idx = tid; idx < rep * (HD / 8); idx += NW * 64) {
-    const int q = idx / (HD / 8), d0 = (idx % (HD / 8)) * 8;
+  for (int idx = tid; idx < rep * HD; idx += NW * 64) {
+    const int q = idx % rep, d = idx / rep;
     float mx = -INFINITY;
 #pragma unroll
     for (int w = 0; w < NW; ++w) mx = fmaxf(mx, sm_m[w][q]);
     // the prefix part (shared-prompt variant): read past the L2, it was written by another workgroup of this launch
-    float m_p = -INFINITY, l_p = 0.f, o_p[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float m_p = -INFINITY, l_p = 0.f, o_p = 0.f;
     if constexpr (SHARE) {
       const size_t base = ((size_t)s * n_q_heads + kvh * rep + q) * (HD + 4);
       m_p = ld_f32<true>(sh.pre, base * sizeof(float));
       l_p = ld_f32<true>(sh.pre, (base + 1) * sizeof(float));
-      const float4 a = as_f4(ld_u4<true>(sh.pre, (base + 4 + d0) * sizeof(float)));
-      const float4 b = as_f4(ld_u4<true>(sh.pre, (base + 8 + d0) * sizeof(float)));
-      o_p[0] = a.x; o_p[1] = a.y; o_p[2] = a.z; o_p[3] = a.w; o_p[4] = b.x; o_p[5] = b.y; o_p[6] = b.z; o_p[7] = b.w;
+      o_p = ld_f32<true>(sh.pre, (base + 4 + d) * sizeof(float));
       mx = fmaxf(mx, m_p);
     }
     const float w_p = SHARE ? __expf(m_p - mx) : 0.f;
@@ -1200,15 +1202,10 @@ __global__ void __launch_bounds__(NW * 64) k_decode_attention16(const float* __r
 #pragma unroll
     for (int w = 0; w < NW; ++w) { wgt[w] = __expf(sm_m[w][q] - mx); den += wgt[w] * sm_l[w][q]; }
     const float inv = 1.0f / den;
-    Frag16 ov;
+    float num = w_p * o_p;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float num = w_p * o_p[e];
-#pragma unroll
-      for (int w = 0; w < NW; ++w) num += wgt[w] * sm_o[(size_t)w * kOStride + (size_t)(d0 + e) * 16 + q];
-      ov.h[e] = from_f32<f16>(num * inv);
-    }
-    out[x16_chunk(s, (kvh * rep + q) * HD + d0, KSo)] = ov.u;
+    for (int w = 0; w < NW; ++w) num += wgt[w] * sm_o[(size_t)w * kOStride + (size_t)d * 16 + q];
+    ((f16*)out)[x16_chunk(s, (kvh * rep + q) * HD + (d & ~7), KSo) * 8 + (d & 7)] = from_f32<f16>(num * inv);
   }
 }
 
@@ -1227,7 +1224,7 @@ static hipError_t launch_decode_attention(const float* qkv, const float2* rope, 
   }
   return launch(SHARE ? KID_DECODE_ATTN_SHARED : KID_DECODE_ATTN, k_decode_attention16<HD, NW, PD, LDS, SHARE>,
                 dim3((SHARE ? sh.n_prefix : 0) + S * kv.n_kv_heads), dim3(NW * 64), smem, st, qkv, rope, rm.step,
-                kv.page_table, kv.k, kv.v, rm.Lp, kv.pages_per_seq, rm, kv, (uint4*)out, n_q_heads, sh);
+                kv.page_table, rm.Lp, kv.pages_per_seq, kv.n_kv_heads, n_q_heads, kv.k, rm, kv, (uint4*)out, sh);
 }
 
 hipError_t d_decode_attention(const float* qkv, const float2* rope, RowMap rm, KVCache kv, void* out, int S, int n_q_heads,
